@@ -1,0 +1,177 @@
+"""CPU oracle for the batched Cholesky operator family -- TEST INFRASTRUCTURE ONLY.
+
+Thin ctypes access to ``oracle.c`` (plain fp64 loops written from the paper's
+operator statements, sections 3.1, 4.1, 4.2 and the appendix).  It shares nothing
+with the HIP library and must never be imported by it.  Inputs are numpy arrays;
+fp32 inputs are widened to fp64 exactly, results are always fp64.
+"""
+import ctypes
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "oracle.c")
+_LIB = os.path.join(_HERE, "liboracle.so")
+
+
+def build(force=False):
+    """Compile oracle.c with gcc (OpenMP over the batch / independent right-hand sides)."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        subprocess.check_call(
+            ["gcc", "-O2", "-fopenmp", "-fPIC", "-shared", "-Wall", "-Wextra", "-o", _LIB, _SRC, "-lm"]
+        )
+    return _LIB
+
+
+_lib = None
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        lib = ctypes.CDLL(build())
+        dp = ctypes.POINTER(ctypes.c_double)
+        ip = ctypes.POINTER(ctypes.c_int32)
+        i64, i32, f64 = ctypes.c_int64, ctypes.c_int, ctypes.c_double
+        lib.orc_potrf.argtypes = [i32, i64, i32, dp, dp, ip]
+        lib.orc_potrf_backward.argtypes = [i32, i64, i32, dp, dp, dp]
+        lib.orc_potrf_backward_phi.argtypes = [i64, i32, dp, dp, dp]
+        lib.orc_trsm.argtypes = [i32, i32, i32, f64, i64, i32, i32, dp, dp, dp]
+        lib.orc_trmm.argtypes = [i32, i32, i32, f64, i64, i32, i32, dp, dp, dp]
+        lib.orc_syrk.argtypes = [i32, f64, i64, i32, i32, dp, dp]
+        lib.orc_sumlogdiag.argtypes = [i64, i32, dp, dp]
+        lib.orc_gp_glue.argtypes = [i64, i32, dp, dp, dp, dp, dp, dp]
+        lib.orc_llt_entry.argtypes = [i32, i32, dp, i32, i32]
+        lib.orc_llt_entry.restype = f64
+        lib.orc_ltxl_entry.argtypes = [i32, dp, dp, i32, i32]
+        lib.orc_ltxl_entry.restype = f64
+        lib.orc_ltlbar_entry.argtypes = [i32, dp, dp, i32, i32]
+        lib.orc_ltlbar_entry.restype = f64
+        _lib = lib
+    return _lib
+
+
+def _p(a):
+    return a.ctypes.data_as(ctypes.POINTER(ctypes.c_double))
+
+
+def _f64(a):
+    return np.ascontiguousarray(np.asarray(a), dtype=np.float64)
+
+
+def _check(rc, name):
+    if rc != 0:
+        raise ValueError(f"{name}: oracle rejected the arguments (status {rc})")
+
+
+def _batch_of(a, trailing):
+    """Flatten every leading axis into one batch count ("batch mode", section 4.1)."""
+    lead = a.shape[: a.ndim - trailing]
+    return int(np.prod(lead, dtype=np.int64)) if lead else 1
+
+
+def potrf(A, lower=True, return_info=False):
+    A = _f64(A)
+    n = A.shape[-1]
+    assert A.shape[-2] == n
+    b = _batch_of(A, 2)
+    L = np.empty_like(A)
+    info = np.zeros(b, dtype=np.int32)
+    _check(_load().orc_potrf(int(lower), b, n, _p(A), _p(L), info.ctypes.data_as(ctypes.POINTER(ctypes.c_int32))), "potrf")
+    return (L, info) if return_info else L
+
+
+def potrf_inplace(A, lower=True):
+    """Factor overwriting its (fp64, contiguous) input, as the paper allows."""
+    assert A.dtype == np.float64 and A.flags.c_contiguous
+    n = A.shape[-1]
+    _check(_load().orc_potrf(int(lower), _batch_of(A, 2), n, _p(A), _p(A), None), "potrf")
+    return A
+
+
+def potrf_backward(L, Lbar, lower=True, inplace=False):
+    L = _f64(L)
+    Lbar = _f64(Lbar)
+    n = L.shape[-1]
+    assert L.shape == Lbar.shape and L.shape[-2] == n
+    out = Lbar if inplace else np.empty_like(Lbar)
+    _check(_load().orc_potrf_backward(int(lower), _batch_of(L, 2), n, _p(L), _p(Lbar), _p(out)), "potrf_backward")
+    return out
+
+
+def potrf_backward_phi(L, Lbar):
+    L = _f64(L)
+    Lbar = _f64(Lbar)
+    n = L.shape[-1]
+    out = np.empty_like(Lbar)
+    _check(_load().orc_potrf_backward_phi(_batch_of(L, 2), n, _p(L), _p(Lbar), _p(out)), "potrf_backward_phi")
+    return out
+
+
+def _tri_op(fn, name, L, A, lower, trans, rightside, alpha, inplace):
+    L = _f64(L)
+    A = _f64(A)
+    n = L.shape[-1]
+    assert L.shape[-2] == n
+    m = A.shape[-2] if rightside else A.shape[-1]
+    assert (A.shape[-1] if rightside else A.shape[-2]) == n
+    b = _batch_of(L, 2)
+    assert _batch_of(A, 2) == b
+    out = A if inplace else np.empty_like(A)
+    _check(fn(int(lower), int(trans), int(rightside), float(alpha), b, n, m, _p(L), _p(A), _p(out)), name)
+    return out
+
+
+def trsm(L, A, lower=True, trans=False, rightside=False, alpha=1.0, inplace=False):
+    return _tri_op(_load().orc_trsm, "trsm", L, A, lower, trans, rightside, alpha, inplace)
+
+
+def trmm(L, A, lower=True, trans=False, rightside=False, alpha=1.0, inplace=False):
+    return _tri_op(_load().orc_trmm, "trmm", L, A, lower, trans, rightside, alpha, inplace)
+
+
+def syrk(A, trans=False, alpha=1.0):
+    A = _f64(A)
+    n, k = (A.shape[-1], A.shape[-2]) if trans else (A.shape[-2], A.shape[-1])
+    b = _batch_of(A, 2)
+    out = np.empty(A.shape[:-2] + (n, n), dtype=np.float64)
+    _check(_load().orc_syrk(int(trans), float(alpha), b, n, k, _p(A), _p(out)), "syrk")
+    return out
+
+
+def sumlogdiag(L):
+    L = _f64(L)
+    n = L.shape[-1]
+    out = np.empty(L.shape[:-2], dtype=np.float64)
+    outf = out.reshape(-1) if out.ndim else out.reshape(1)
+    _check(_load().orc_sumlogdiag(_batch_of(L, 2), n, _p(L), _p(outf)), "sumlogdiag")
+    return out
+
+
+def gp_glue(L, y, z, alpha):
+    """loss = 1/2 y^T alpha + sum log l_ii and Lbar = -tril(alpha z^T) + diag(1/l_ii)."""
+    L, y, z, alpha = _f64(L), _f64(y), _f64(z), _f64(alpha)
+    n = L.shape[-1]
+    b = _batch_of(L, 2)
+    loss = np.empty(L.shape[:-2], dtype=np.float64)
+    lossf = loss.reshape(-1) if loss.ndim else loss.reshape(1)
+    Lbar = np.empty_like(L)
+    _check(_load().orc_gp_glue(b, n, _p(L), _p(y), _p(z), _p(alpha), _p(lossf), _p(Lbar)), "gp_glue")
+    return loss, Lbar
+
+
+def llt_entry(L, i, j, lower=True):
+    L = _f64(L)
+    return _load().orc_llt_entry(int(lower), L.shape[-1], _p(L), int(i), int(j))
+
+
+def ltxl_entry(L, X, i, j):
+    L, X = _f64(L), _f64(X)
+    return _load().orc_ltxl_entry(L.shape[-1], _p(L), _p(X), int(i), int(j))
+
+
+def ltlbar_entry(L, Lbar, i, j):
+    L, Lbar = _f64(L), _f64(Lbar)
+    return _load().orc_ltlbar_entry(L.shape[-1], _p(L), _p(Lbar), int(i), int(j))

@@ -1,0 +1,564 @@
+/*
+ * oracle.c - TEST INFRASTRUCTURE, NOT PRODUCT CODE.
+ *
+ * A plain, slow, fp64 CPU statement of what the batched Cholesky operator family
+ * of "Auto-Differentiating Linear Algebra" (arXiv 1710.08717) computes.  It exists
+ * to check the HIP library; it shares no code with it.  Only tests, the smoke
+ * check and the benchmark's cpu_baseline leg may load it.
+ *
+ * Conventions (section 4, "BLAS and LAPACK" paragraph): every matrix is a full
+ * square / rectangle in ROW-MAJOR order; a batch is the same-shape matrices laid
+ * one after another ("batch mode").  All arithmetic is double precision.
+ *
+ * Every result here is exactly defined (the factor with positive diagonal is
+ * unique; the rest are closed-form matrix expressions), so each routine is the
+ * definition written as loops.  The only liberty taken is the order of the loop
+ * nest (so that inner loops walk along rows); there is no tiling, no fusion.
+ *
+ * Pins: every function below is pinned by tests/test_oracle_*.py against closed
+ * forms, brute-force determinants / inverses, finite differences and the adjoint
+ * identity.  Nothing here is "parity unpinned".
+ */
+#include <math.h>
+#include <stddef.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+
+#define ORC_OK 0
+#define ORC_ERR_INVALID_ARG 1
+
+/* Entry (i,k) of the triangular operand as the operator sees it.
+ * M is stored row-major n x n.  lower!=0: M is lower triangular, entries above
+ * the diagonal are taken to be zero whatever the memory holds.  lower==0: M is
+ * upper triangular.  trans!=0 gives the entry of the transpose, t(M) = M^T
+ * (operator table of section 4). */
+static inline double tri_at(const double *M, int n, int lower, int trans, int i, int k)
+{
+    int r = trans ? k : i;
+    int c = trans ? i : k;
+    if (lower ? (r < c) : (r > c))
+        return 0.0;
+    return M[(size_t)r * n + c];
+}
+
+/* ------------------------------------------------------------------------- */
+/* potrf forward: A = L L^T, l_ij = 0 for i < j, positive diagonal
+ * (operator table row "potrf"; section 4.2 first paragraph).
+ * lower == 0 gives the upper factor R with A = R^T R (appendix, potrf, last
+ * paragraph).  Only the named triangle of A is read.  info[b] = 0, or the
+ * 1-based index of the first pivot that is not > 0 (then that matrix's factor
+ * is unspecified from that column/row on).  L may be the same memory as A. */
+static void potrf_one_lower(int n, const double *A, double *L, int32_t *info)
+{
+    int fail = 0;
+    for (int j = 0; j < n; ++j) {
+        const double *Lj = L + (size_t)j * n;
+        double d = A[(size_t)j * n + j];
+        for (int k = 0; k < j; ++k)
+            d -= Lj[k] * Lj[k];
+        if (!(d > 0.0)) {
+            fail = j + 1;
+            break;
+        }
+        double ljj = sqrt(d);
+        L[(size_t)j * n + j] = ljj;
+#pragma omp parallel for schedule(static) if (n >= 1024)
+        for (int i = j + 1; i < n; ++i) {
+            const double *Li = L + (size_t)i * n;
+            double s = A[(size_t)i * n + j];
+            for (int k = 0; k < j; ++k)
+                s -= Li[k] * Lj[k];
+            L[(size_t)i * n + j] = s / ljj;
+        }
+    }
+    for (int i = 0; i < n; ++i)
+        for (int j = i + 1; j < n; ++j)
+            L[(size_t)i * n + j] = 0.0;
+    if (info)
+        *info = fail;
+}
+
+static void potrf_one_upper(int n, const double *A, double *R, int32_t *info)
+{
+    /* Row i of R needs rows 0..i-1 of R: r_ij = (a_ij - sum_{k<i} r_ki r_kj) / r_ii. */
+    int fail = 0;
+    for (int i = 0; i < n; ++i) {
+        double d = A[(size_t)i * n + i];
+        for (int k = 0; k < i; ++k)
+            d -= R[(size_t)k * n + i] * R[(size_t)k * n + i];
+        if (!(d > 0.0)) {
+            fail = i + 1;
+            break;
+        }
+        double rii = sqrt(d);
+        R[(size_t)i * n + i] = rii;
+#pragma omp parallel for schedule(static) if (n >= 1024)
+        for (int j = i + 1; j < n; ++j) {
+            double s = A[(size_t)i * n + j];
+            for (int k = 0; k < i; ++k)
+                s -= R[(size_t)k * n + i] * R[(size_t)k * n + j];
+            R[(size_t)i * n + j] = s / rii;
+        }
+    }
+    for (int i = 0; i < n; ++i)
+        for (int j = 0; j < i; ++j)
+            R[(size_t)i * n + j] = 0.0;
+    if (info)
+        *info = fail;
+}
+
+int orc_potrf(int lower, int64_t batch, int n, const double *A, double *L, int32_t *info)
+{
+    if (batch < 0 || n < 0)
+        return ORC_ERR_INVALID_ARG;
+    if (batch == 0 || n == 0)
+        return ORC_OK;
+    if (!A || !L)
+        return ORC_ERR_INVALID_ARG;
+    size_t nn = (size_t)n * n;
+#pragma omp parallel for schedule(dynamic) if (batch > 1)
+    for (int64_t b = 0; b < batch; ++b) {
+        int32_t *ib = info ? info + b : NULL;
+        if (lower)
+            potrf_one_lower(n, A + b * nn, L + b * nn, ib);
+        else
+            potrf_one_upper(n, A + b * nn, L + b * nn, ib);
+    }
+    return ORC_OK;
+}
+
+/* ------------------------------------------------------------------------- */
+/* trmm forward (section 4.2, "trmm"):
+ *   rightside == 0:  B = alpha * t(L) A,   A and B are n x m
+ *   rightside != 0:  B = alpha * A t(L),   A and B are m x n
+ * alpha is not in the paper's statement (alpha = 1 reproduces it); it scales the
+ * result the way it does for gemm2 and syrk.  B may be the same memory as A. */
+static void trmm_one(int lower, int trans, int rightside, double alpha, int n, int m,
+                     const double *L, const double *A, double *B, double *tmp)
+{
+    /* t(L) is effectively lower triangular when exactly one of (upper, trans) holds;
+     * entries on the other side of the diagonal are structural zeros and take no
+     * part in the sums (so nothing stored there, or paired with it, is touched). */
+    int eff_lower = (lower != 0) != (trans != 0);
+    if (!rightside) {
+        /* row i of the product = sum_k T(i,k) * row k of A */
+        for (int i = 0; i < n; ++i) {
+            double *ti = tmp + (size_t)i * m;
+            for (int c = 0; c < m; ++c)
+                ti[c] = 0.0;
+            int k0 = eff_lower ? 0 : i;
+            int k1 = eff_lower ? i + 1 : n;
+            for (int k = k0; k < k1; ++k) {
+                double t = tri_at(L, n, lower, trans, i, k);
+                const double *ak = A + (size_t)k * m;
+                for (int c = 0; c < m; ++c)
+                    ti[c] += t * ak[c];
+            }
+        }
+    } else {
+        /* entry (r,c) of the product = sum_k a_rk T(k,c) */
+        for (int r = 0; r < m; ++r) {
+            const double *ar = A + (size_t)r * n;
+            double *tr = tmp + (size_t)r * n;
+            for (int c = 0; c < n; ++c) {
+                double s = 0.0;
+                int k0 = eff_lower ? c : 0;
+                int k1 = eff_lower ? n : c + 1;
+                for (int k = k0; k < k1; ++k)
+                    s += ar[k] * tri_at(L, n, lower, trans, k, c);
+                tr[c] = s;
+            }
+        }
+    }
+    for (size_t e = 0; e < (size_t)n * m; ++e)
+        B[e] = alpha * tmp[e];
+}
+
+int orc_trmm(int lower, int trans, int rightside, double alpha, int64_t batch, int n, int m,
+             const double *L, const double *A, double *B)
+{
+    if (batch < 0 || n < 0 || m < 0)
+        return ORC_ERR_INVALID_ARG;
+    if (batch == 0 || n == 0 || m == 0)
+        return ORC_OK;
+    if (!L || !A || !B)
+        return ORC_ERR_INVALID_ARG;
+    size_t nn = (size_t)n * n, nm = (size_t)n * m;
+    int fail = 0;
+#pragma omp parallel for schedule(dynamic)
+    for (int64_t b = 0; b < batch; ++b) {
+        double *tmp = (double *)malloc(nm * sizeof(double));
+        if (!tmp) {
+            fail = 1;
+            continue;
+        }
+        trmm_one(lower, trans, rightside, alpha, n, m, L + b * nn, A + b * nm, B + b * nm, tmp);
+        free(tmp);
+    }
+    return fail ? ORC_ERR_INVALID_ARG : ORC_OK;
+}
+
+/* ------------------------------------------------------------------------- */
+/* trsm forward (section 4.2, "trsm"):
+ *   rightside == 0:  B = alpha * t(L)^{-1} A,   A and B are n x m
+ *   rightside != 0:  B = alpha * A t(L)^{-1},   A and B are m x n
+ * Plain substitution.  B may be the same memory as A. */
+static void trsm_left_cols(int lower, int trans, double alpha, int n, int m, const double *L,
+                           const double *A, double *B, int c0, int c1)
+{
+    /* t(L) X = alpha A on columns [c0, c1).  Row i of X =
+     * (alpha * row i of A - sum_k T(i,k) row k of X) / T(i,i), with k < i for a lower T
+     * (rows top to bottom) and k > i for an upper T (rows bottom to top). */
+    int eff_lower = (lower != 0) != (trans != 0);
+    for (int step = 0; step < n; ++step) {
+        int i = eff_lower ? step : n - 1 - step;
+        double *xi = B + (size_t)i * m;
+        const double *ai = A + (size_t)i * m;
+        for (int c = c0; c < c1; ++c)
+            xi[c] = alpha * ai[c];
+        int k0 = eff_lower ? 0 : i + 1;
+        int k1 = eff_lower ? i : n;
+        for (int k = k0; k < k1; ++k) {
+            double t = tri_at(L, n, lower, trans, i, k);
+            const double *xk = B + (size_t)k * m;
+            for (int c = c0; c < c1; ++c)
+                xi[c] -= t * xk[c];
+        }
+        double d = tri_at(L, n, lower, trans, i, i);
+        for (int c = c0; c < c1; ++c)
+            xi[c] /= d;
+    }
+}
+
+static void trsm_right_row(int lower, int trans, double alpha, int n, const double *L,
+                           const double *a, double *x)
+{
+    /* x t(L) = alpha a for one row: sum_k x_k T(k,c) = alpha a_c.  Lower T: T(k,c) != 0
+     * for k >= c, so c runs n-1 .. 0; upper T: c runs 0 .. n-1. */
+    int eff_lower = (lower != 0) != (trans != 0);
+    for (int step = 0; step < n; ++step) {
+        int c = eff_lower ? n - 1 - step : step;
+        double s = alpha * a[c];
+        int k0 = eff_lower ? c + 1 : 0;
+        int k1 = eff_lower ? n : c;
+        for (int k = k0; k < k1; ++k)
+            s -= x[k] * tri_at(L, n, lower, trans, k, c);
+        x[c] = s / tri_at(L, n, lower, trans, c, c);
+    }
+}
+
+/* The right-hand sides (columns for a left solve, rows for a right solve) are
+ * independent; for one big matrix they are shared out over threads, nothing else. */
+static void trsm_one(int lower, int trans, int rightside, double alpha, int n, int m,
+                     const double *L, const double *A, double *B)
+{
+    int big = ((double)n * n * m > 5e7);
+    if (!rightside) {
+        const int chunk = 64;
+        int nchunk = (m + chunk - 1) / chunk;
+#pragma omp parallel for schedule(dynamic) if (big)
+        for (int q = 0; q < nchunk; ++q) {
+            int c0 = q * chunk, c1 = c0 + chunk < m ? c0 + chunk : m;
+            trsm_left_cols(lower, trans, alpha, n, m, L, A, B, c0, c1);
+        }
+    } else {
+#pragma omp parallel for schedule(dynamic) if (big)
+        for (int r = 0; r < m; ++r)
+            trsm_right_row(lower, trans, alpha, n, L, A + (size_t)r * n, B + (size_t)r * n);
+    }
+}
+
+int orc_trsm(int lower, int trans, int rightside, double alpha, int64_t batch, int n, int m,
+             const double *L, const double *A, double *B)
+{
+    if (batch < 0 || n < 0 || m < 0)
+        return ORC_ERR_INVALID_ARG;
+    if (batch == 0 || n == 0 || m == 0)
+        return ORC_OK;
+    if (!L || !A || !B)
+        return ORC_ERR_INVALID_ARG;
+    size_t nn = (size_t)n * n, nm = (size_t)n * m;
+#pragma omp parallel for schedule(dynamic)
+    for (int64_t b = 0; b < batch; ++b)
+        trsm_one(lower, trans, rightside, alpha, n, m, L + b * nn, A + b * nm, B + b * nm);
+    return ORC_OK;
+}
+
+/* ------------------------------------------------------------------------- */
+/* syrk forward (section 4.2, "syrk"):
+ *   trans == 0:  B = alpha A A^T,  A is n x k, B is n x n
+ *   trans != 0:  B = alpha A^T A,  A is k x n, B is n x n
+ * Both triangles of B are written.  B must not overlap A. */
+int orc_syrk(int trans, double alpha, int64_t batch, int n, int k, const double *A, double *B)
+{
+    if (batch < 0 || n < 0 || k < 0)
+        return ORC_ERR_INVALID_ARG;
+    if (batch == 0 || n == 0)
+        return ORC_OK;
+    if (!B || (k > 0 && !A))
+        return ORC_ERR_INVALID_ARG;
+    size_t nn = (size_t)n * n, nk = (size_t)n * k;
+#pragma omp parallel for schedule(dynamic) collapse(2)
+    for (int64_t b = 0; b < batch; ++b) {
+        for (int i = 0; i < n; ++i) {
+            const double *Ab = A + b * nk;
+            double *Bb = B + b * nn;
+            for (int j = 0; j < n; ++j) {
+                double s = 0.0;
+                if (!trans)
+                    for (int p = 0; p < k; ++p)
+                        s += Ab[(size_t)i * k + p] * Ab[(size_t)j * k + p];
+                else
+                    for (int p = 0; p < k; ++p)
+                        s += Ab[(size_t)p * n + i] * Ab[(size_t)p * n + j];
+                Bb[(size_t)i * n + j] = alpha * s;
+            }
+        }
+    }
+    return ORC_OK;
+}
+
+/* ------------------------------------------------------------------------- */
+/* log|L| = sum_i log l_ii (section 3.1, the identity below the GP code).
+ * Plain log: a non-positive diagonal gives NaN / -inf as IEEE says. */
+int orc_sumlogdiag(int64_t batch, int n, const double *L, double *out)
+{
+    if (batch < 0 || n < 0)
+        return ORC_ERR_INVALID_ARG;
+    if (batch == 0)
+        return ORC_OK;
+    if (!out || (n > 0 && !L))
+        return ORC_ERR_INVALID_ARG;
+    size_t nn = (size_t)n * n;
+    for (int64_t b = 0; b < batch; ++b) {
+        double s = 0.0;
+        for (int i = 0; i < n; ++i)
+            s += log(L[b * nn + (size_t)i * n + i]);
+        out[b] = s;
+    }
+    return ORC_OK;
+}
+
+/* ------------------------------------------------------------------------- */
+/* copyltu / copyutl (section 4.1 "Simple Matrix Functions"; appendix potrf). */
+static void copyltu(int n, double *X)
+{
+    for (int i = 0; i < n; ++i)
+        for (int j = i + 1; j < n; ++j)
+            X[(size_t)i * n + j] = X[(size_t)j * n + i];
+}
+static void copyutl(int n, double *X)
+{
+    for (int i = 0; i < n; ++i)
+        for (int j = 0; j < i; ++j)
+            X[(size_t)i * n + j] = X[(size_t)j * n + i];
+}
+
+/* potrf backward in the order section 4.2 gives it:
+ *   Abar = 1/2 L^{-T} copyltu(L^T Lbar) L^{-1}
+ * carried out the way the paragraph after it describes: copy Lbar to Abar,
+ * multiply by L^T from the left (trmm), copyltu, back-substitute from the left
+ * with L^T and from the right with L (two trsm), halve.
+ * lower == 0: Abar = 1/2 R^{-1} copyutl(Rbar R^T) R^{-T} (appendix, potrf). */
+static void potrf_backward_one(int lower, int n, const double *L, const double *Lbar, double *Abar,
+                               double *tmp)
+{
+    size_t nn = (size_t)n * n;
+    if (Abar != Lbar)
+        memcpy(Abar, Lbar, nn * sizeof(double));
+    if (lower) {
+        trmm_one(1, 1, 0, 1.0, n, n, L, Abar, Abar, tmp); /* L^T Lbar */
+        copyltu(n, Abar);
+        trsm_one(1, 1, 0, 1.0, n, n, L, Abar, Abar); /* L^{-T} (.) */
+        trsm_one(1, 0, 1, 1.0, n, n, L, Abar, Abar); /* (.) L^{-1} */
+    } else {
+        trmm_one(0, 1, 1, 1.0, n, n, L, Abar, Abar, tmp); /* Rbar R^T */
+        copyutl(n, Abar);
+        trsm_one(0, 0, 0, 1.0, n, n, L, Abar, Abar); /* R^{-1} (.) */
+        trsm_one(0, 1, 1, 1.0, n, n, L, Abar, Abar); /* (.) R^{-T} */
+    }
+    for (size_t e = 0; e < nn; ++e)
+        Abar[e] *= 0.5;
+}
+
+int orc_potrf_backward(int lower, int64_t batch, int n, const double *L, const double *Lbar,
+                       double *Abar)
+{
+    if (batch < 0 || n < 0)
+        return ORC_ERR_INVALID_ARG;
+    if (batch == 0 || n == 0)
+        return ORC_OK;
+    if (!L || !Lbar || !Abar)
+        return ORC_ERR_INVALID_ARG;
+    size_t nn = (size_t)n * n;
+    int fail = 0;
+#pragma omp parallel for schedule(dynamic)
+    for (int64_t b = 0; b < batch; ++b) {
+        double *tmp = (double *)malloc(nn * sizeof(double));
+        if (!tmp) {
+            fail = 1;
+            continue;
+        }
+        potrf_backward_one(lower, n, L + b * nn, Lbar + b * nn, Abar + b * nn, tmp);
+        free(tmp);
+    }
+    return fail ? ORC_ERR_INVALID_ARG : ORC_OK;
+}
+
+/* The same quantity through the masking matrix E of the appendix (e_ij = 0, 1, 2
+ * for i <, =, > j): with Phi(X) = 1/2 (X o E) (lower triangle, halved diagonal),
+ * copyltu(X) = Phi(X) + Phi(X)^T, hence
+ *   Abar = sym( L^{-T} Phi(L^T Lbar) L^{-1} ).
+ * Written with its own loops (dense inverse of L by substitution, dense
+ * products) so that it cross-checks the routine above.  Lower factor only. */
+int orc_potrf_backward_phi(int64_t batch, int n, const double *L, const double *Lbar, double *Abar)
+{
+    if (batch < 0 || n < 0)
+        return ORC_ERR_INVALID_ARG;
+    if (batch == 0 || n == 0)
+        return ORC_OK;
+    if (!L || !Lbar || !Abar)
+        return ORC_ERR_INVALID_ARG;
+    size_t nn = (size_t)n * n;
+    double *Li = (double *)malloc(nn * sizeof(double));  /* L^{-1} */
+    double *Ph = (double *)malloc(nn * sizeof(double));  /* Phi(L^T Lbar) */
+    double *W = (double *)malloc(nn * sizeof(double));
+    if (!Li || !Ph || !W) {
+        free(Li);
+        free(Ph);
+        free(W);
+        return ORC_ERR_INVALID_ARG;
+    }
+    for (int64_t b = 0; b < batch; ++b) {
+        const double *Lb = L + b * nn, *Gb = Lbar + b * nn;
+        double *Ab = Abar + b * nn;
+        /* inverse of L, column c: solve L x = e_c */
+        for (int c = 0; c < n; ++c)
+            for (int i = 0; i < n; ++i) {
+                double s = (i == c) ? 1.0 : 0.0;
+                for (int k = c; k < i; ++k)
+                    s -= Lb[(size_t)i * n + k] * Li[(size_t)k * n + c];
+                Li[(size_t)i * n + c] = (i < c) ? 0.0 : s / Lb[(size_t)i * n + i];
+            }
+        for (int i = 0; i < n; ++i)
+            for (int j = 0; j < n; ++j) {
+                double s = 0.0;
+                if (i >= j) {
+                    for (int k = i; k < n; ++k) /* l_ki = 0 for k < i; lbar_kj needs k >= j */
+                        s += Lb[(size_t)k * n + i] * Gb[(size_t)k * n + j];
+                    if (i == j)
+                        s *= 0.5;
+                }
+                Ph[(size_t)i * n + j] = s;
+            }
+        /* W = L^{-T} Ph : w_ij = sum_k linv_ki ph_kj */
+        for (int i = 0; i < n; ++i)
+            for (int j = 0; j < n; ++j) {
+                double s = 0.0;
+                for (int k = 0; k < n; ++k)
+                    s += Li[(size_t)k * n + i] * Ph[(size_t)k * n + j];
+                W[(size_t)i * n + j] = s;
+            }
+        /* Ph <- W L^{-1} */
+        for (int i = 0; i < n; ++i)
+            for (int j = 0; j < n; ++j) {
+                double s = 0.0;
+                for (int k = 0; k < n; ++k)
+                    s += W[(size_t)i * n + k] * Li[(size_t)k * n + j];
+                Ph[(size_t)i * n + j] = s;
+            }
+        for (int i = 0; i < n; ++i)
+            for (int j = 0; j < n; ++j)
+                Ab[(size_t)i * n + j] = 0.5 * (Ph[(size_t)i * n + j] + Ph[(size_t)j * n + i]);
+    }
+    free(Li);
+    free(Ph);
+    free(W);
+    return ORC_OK;
+}
+
+/* ------------------------------------------------------------------------- */
+/* Gaussian-process criterion pieces (section 3.1) for one noisy kernel matrix
+ * A = L L^T and targets y:
+ *   z = L^{-1} y, alpha = L^{-T} z,
+ *   loss = 1/2 y^T alpha + sum_i log l_ii          (= phi - n/2 log 2 pi)
+ * and the gradient that reaches potrf's output: the trsm backward case
+ * B = L^{-1} A gives -tril(abar b^T) with bbar = z, abar = alpha, b = z
+ * (section 4.2 "trsm", first case), and d/dl_ii sum log l_ii = 1 / l_ii:
+ *   Lbar = -tril(alpha z^T) + diag(1 / l_ii).
+ * z and alpha are inputs here (they come from two trsm calls). */
+int orc_gp_glue(int64_t batch, int n, const double *L, const double *y, const double *z,
+                const double *alpha, double *loss, double *Lbar)
+{
+    if (batch < 0 || n < 0)
+        return ORC_ERR_INVALID_ARG;
+    if (batch == 0)
+        return ORC_OK;
+    if (!loss || (n > 0 && (!L || !y || !z || !alpha || !Lbar)))
+        return ORC_ERR_INVALID_ARG;
+    size_t nn = (size_t)n * n;
+    for (int64_t b = 0; b < batch; ++b) {
+        const double *Lb = L + b * nn, *yb = y + b * n, *zb = z + b * n, *ab = alpha + b * n;
+        double *Gb = Lbar + b * nn;
+        double q = 0.0, ld = 0.0;
+        for (int i = 0; i < n; ++i) {
+            q += yb[i] * ab[i];
+            ld += log(Lb[(size_t)i * n + i]);
+        }
+        loss[b] = 0.5 * q + ld;
+        for (int i = 0; i < n; ++i)
+            for (int j = 0; j < n; ++j) {
+                double g = 0.0;
+                if (i >= j)
+                    g = -ab[i] * zb[j];
+                if (i == j)
+                    g += 1.0 / Lb[(size_t)i * n + i];
+                Gb[(size_t)i * n + j] = g;
+            }
+    }
+    return ORC_OK;
+}
+
+/* One entry of L L^T (lower != 0) or R^T R (lower == 0): lets a test compare a
+ * huge factor against A on sampled positions without forming the product. */
+double orc_llt_entry(int lower, int n, const double *L, int i, int j)
+{
+    double s = 0.0;
+    int kmax = (i < j ? i : j);
+    if (lower)
+        for (int k = 0; k <= kmax; ++k)
+            s += L[(size_t)i * n + k] * L[(size_t)j * n + k];
+    else
+        for (int k = 0; k <= kmax; ++k)
+            s += L[(size_t)k * n + i] * L[(size_t)k * n + j];
+    return s;
+}
+
+/* One entry of L^T X L for a lower factor L and a dense X: the defining relation
+ * 2 L^T Abar L = copyltu(L^T Lbar) of the backward expression can be sampled with
+ * it at sizes where the full backward is too slow on the CPU.  O(n^2) per entry. */
+double orc_ltxl_entry(int n, const double *L, const double *X, int i, int j)
+{
+    double s = 0.0;
+#pragma omp parallel for reduction(+ : s) schedule(static)
+    for (int p = i; p < n; ++p) {
+        double lpi = L[(size_t)p * n + i];
+        const double *xp = X + (size_t)p * n;
+        double t = 0.0;
+        for (int q = j; q < n; ++q)
+            t += xp[q] * L[(size_t)q * n + j];
+        s += lpi * t;
+    }
+    return s;
+}
+
+/* One entry of L^T Lbar, lower triangles only (k >= max(i, j)). */
+double orc_ltlbar_entry(int n, const double *L, const double *Lbar, int i, int j)
+{
+    double s = 0.0;
+    int k0 = i > j ? i : j;
+    for (int k = k0; k < n; ++k)
+        s += L[(size_t)k * n + i] * Lbar[(size_t)k * n + j];
+    return s;
+}
