@@ -1,0 +1,114 @@
+/*
+ * la.h - C ABI of the MI355X (gfx950) batched Cholesky operator library.
+ *
+ * Operators follow "Auto-Differentiating Linear Algebra" (arXiv 1710.08717),
+ * section 4 (operator table) and section 4.2 ("Cholesky Decomposition. Related
+ * Operators"), with the backward expressions of the appendix.
+ *
+ * Common conventions
+ * ------------------
+ *  - Every pointer except where stated is a DEVICE pointer owned by the caller.
+ *  - Matrices are full rectangles in ROW-MAJOR order (section 4.1, "BLAS and
+ *    LAPACK": flat storage, no packed triangles).  A batched operand of shape
+ *    [batch, r, c] is contiguous: item i starts at base + i*r*c elements
+ *    ("batch mode", section 4.1; the caller flattens all leading axes into batch).
+ *  - dt selects the element type of every matrix argument (LA_F32 / LA_F64).
+ *  - lower != 0: the triangular factor is lower triangular L (A = L L^T).
+ *    lower == 0: it is upper triangular R (A = R^T R; appendix, last paragraph
+ *    of "potrf", and the R variants of trsm / trmm).  Entries on the other side
+ *    of the diagonal of a triangular INPUT are never read.
+ *  - trans != 0 applies t(L) = L^T, rightside != 0 multiplies / solves from the
+ *    right (operator table and section 4.2).
+ *  - stream is a hipStream_t passed as void* (NULL = the default stream).  Calls
+ *    only enqueue work on that stream and return; results are ready when the
+ *    stream reaches that point.
+ *  - batch == 0 or a zero matrix dimension is valid: LA_OK, nothing is launched.
+ *  - Return value: LA_OK, or LA_ERR_INVALID_ARG (null pointer with non-empty
+ *    work, negative size, bad enum, forbidden aliasing), LA_ERR_UNSUPPORTED,
+ *    LA_ERR_RUNTIME (a HIP call failed; see la_last_error()).
+ *  - Workspace: blocked paths (n > 64) keep small device scratch buffers that the
+ *    library allocates itself on first use (per device, grown on demand, kept
+ *    until process exit).  Calls that use it must not overlap on different
+ *    streams of one device.  Paths for n <= 64 use none.
+ */
+#ifndef LA_MI355X_H
+#define LA_MI355X_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum { LA_OK = 0, LA_ERR_INVALID_ARG = 1, LA_ERR_UNSUPPORTED = 2, LA_ERR_RUNTIME = 3 } la_status;
+typedef enum { LA_F32 = 0, LA_F64 = 1 } la_dtype;
+
+/* potrf forward (operator table row "potrf"; section 4.2): for each item,
+ * L lower triangular with positive diagonal and A = L L^T (lower != 0), or R upper
+ * with A = R^T R (lower == 0).  A, L: [batch, n, n].  Only the named triangle of A
+ * is read; the other triangle of the output is written as exact zeros.  L may be
+ * the same buffer as A (the paper's "L can overwrite A"); partial overlap is
+ * forbidden.  info: NULL, or int32 [batch] on the device: 0, or the 1-based index
+ * of the first pivot that is not > 0 (that item's factor is then unspecified from
+ * that column on; the call still returns LA_OK). */
+la_status la_potrf_batched(la_dtype dt, int lower, int64_t batch, int n, const void *A, void *L,
+                           int32_t *info, void *stream);
+
+/* potrf backward (section 4.2, backward of potrf; appendix "potrf"):
+ *   Abar = 1/2 L^{-T} copyltu(L^T Lbar) L^{-1}                      (lower != 0)
+ *   Abar = 1/2 R^{-1} copyutl(Rbar R^T) R^{-T}                      (lower == 0)
+ * evaluated as sym(L^{-T} Phi(L^T Lbar) L^{-1}) with Phi = lower triangle with
+ * halved diagonal, which is the same matrix (copyltu X = Phi X + (Phi X)^T).
+ * L, Lbar, Abar: [batch, n, n].  Only the named triangles of L and Lbar are read.
+ * Abar is written in full and is exactly symmetric.  Abar may be the same buffer
+ * as Lbar ("Abar can overwrite Lbar"); it must not overlap L. */
+la_status la_potrf_backward(la_dtype dt, int lower, int64_t batch, int n, const void *L,
+                            const void *Lbar, void *Abar, void *stream);
+
+/* trsm (section 4.2 "trsm"): B = alpha * t(L)^{-1} A   (rightside == 0, A,B: [batch, n, m])
+ *                            B = alpha * A t(L)^{-1}   (rightside != 0, A,B: [batch, m, n])
+ * L: [batch, n, n] triangular (see lower).  alpha = 1 is the paper's operator.
+ * B may be the same buffer as A; neither may overlap L. */
+la_status la_trsm_batched(la_dtype dt, int lower, int trans, int rightside, double alpha,
+                          int64_t batch, int n, int m, const void *L, const void *A, void *B,
+                          void *stream);
+
+/* trmm (section 4.2 "trmm"): B = alpha * t(L) A   (rightside == 0, A,B: [batch, n, m])
+ *                            B = alpha * A t(L)   (rightside != 0, A,B: [batch, m, n])
+ * Same shapes and aliasing rules as la_trsm_batched. */
+la_status la_trmm_batched(la_dtype dt, int lower, int trans, int rightside, double alpha,
+                          int64_t batch, int n, int m, const void *L, const void *A, void *B,
+                          void *stream);
+
+/* syrk (section 4.2 "syrk"): B = alpha * A A^T  (trans == 0, A: [batch, n, k])
+ *                            B = alpha * A^T A  (trans != 0, A: [batch, k, n])
+ * B: [batch, n, n], both triangles written, exactly symmetric.  B must not
+ * overlap A. */
+la_status la_syrk_batched(la_dtype dt, int trans, double alpha, int64_t batch, int n, int k,
+                          const void *A, void *B, void *stream);
+
+/* log|L| = sum_i log l_ii (section 3.1, identity below the GP criterion code).
+ * L: [batch, n, n]; out: [batch] of dt.  Plain log, no abs: a non-positive
+ * diagonal gives NaN / -inf. n == 0 gives 0. */
+la_status la_sumlogdiag(la_dtype dt, int64_t batch, int n, const void *L, void *out, void *stream);
+
+/* Gaussian-process criterion glue (section 3.1; trsm backward, first case, of
+ * section 4.2).  Given the factor L of the noisy kernel matrix, targets y,
+ * z = L^{-1} y and alpha = L^{-T} z (two la_trsm_batched calls):
+ *   loss[b] = 1/2 y^T alpha + sum_i log l_ii      (the criterion minus n/2 log 2 pi)
+ *   Lbar    = -tril(alpha z^T) + diag(1 / l_ii)   (gradient of loss w.r.t. L)
+ * L, Lbar: [batch, n, n]; y, z, alpha: [batch, n]; loss: [batch].  Lbar is written
+ * in full (zeros above the diagonal) and must not overlap L.  Lower factor only. */
+la_status la_gp_glue(la_dtype dt, int64_t batch, int n, const void *L, const void *y, const void *z,
+                     const void *alpha, void *loss, void *Lbar, void *stream);
+
+/* Text of the last HIP error seen by this thread's calls (host pointer, never NULL). */
+const char *la_last_error(void);
+
+/* Library version as major*10000 + minor*100 + patch. */
+int la_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* LA_MI355X_H */

@@ -1,0 +1,22 @@
+"""MI355X-native batched Cholesky operator family (potrf, trsm, trmm, syrk, sumlogdiag and
+the potrf backward expression) of arXiv 1710.08717, section 4.2.
+
+The work is done by hand-written HIP kernels behind the C ABI declared in ``include/la.h``;
+this package is only a thin ctypes binding that marshals ``torch`` device tensors
+(pointer + stream) into those calls.  There is no CPU or PyTorch fallback: if the shared
+library is missing, importing the binding raises.
+"""
+from .binding import (  # noqa: F401
+    LaError,
+    gp_glue,
+    lib_path,
+    load,
+    potrf,
+    potrf_backward,
+    sumlogdiag,
+    syrk,
+    trmm,
+    trsm,
+)
+
+__all__ = ["potrf", "potrf_backward", "trsm", "trmm", "syrk", "sumlogdiag", "gp_glue", "load", "lib_path", "LaError"]

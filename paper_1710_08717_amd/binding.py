@@ -1,0 +1,182 @@
+"""ctypes binding of ``libla_mi355x.so``: argument marshalling only.
+
+Each function mirrors one ``la_*`` entry point of ``include/la.h``.  Tensors must live on
+the GPU, be contiguous and be float32 or float64; all leading axes are flattened into the
+batch ("batch mode", section 4.1 of the paper).  Work is enqueued on torch's current
+stream.
+"""
+import ctypes
+import os
+
+import torch
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_PKG, "libla_mi355x.so")
+_lib = None
+
+SYMBOLS = [
+    "la_potrf_batched", "la_potrf_backward", "la_trsm_batched", "la_trmm_batched", "la_syrk_batched",
+    "la_sumlogdiag", "la_gp_glue", "la_last_error", "la_version",
+]
+
+
+class LaError(RuntimeError):
+    pass
+
+
+def lib_path():
+    return _LIB_PATH
+
+
+def load():
+    """Load the HIP library (built beforehand by ``paper_1710_08717_amd.build``); raises if absent."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_LIB_PATH):
+        raise LaError(
+            f"{_LIB_PATH} is missing: build it with `python -m paper_1710_08717_amd.build` "
+            "(there is no fallback path)"
+        )
+    lib = ctypes.CDLL(_LIB_PATH)
+    vp, i32, i64, f64 = ctypes.c_void_p, ctypes.c_int, ctypes.c_int64, ctypes.c_double
+    lib.la_potrf_batched.argtypes = [i32, i32, i64, i32, vp, vp, vp, vp]
+    lib.la_potrf_backward.argtypes = [i32, i32, i64, i32, vp, vp, vp, vp]
+    lib.la_trsm_batched.argtypes = [i32, i32, i32, i32, f64, i64, i32, i32, vp, vp, vp, vp]
+    lib.la_trmm_batched.argtypes = [i32, i32, i32, i32, f64, i64, i32, i32, vp, vp, vp, vp]
+    lib.la_syrk_batched.argtypes = [i32, i32, f64, i64, i32, i32, vp, vp, vp]
+    lib.la_sumlogdiag.argtypes = [i32, i64, i32, vp, vp, vp]
+    lib.la_gp_glue.argtypes = [i32, i64, i32, vp, vp, vp, vp, vp, vp, vp]
+    lib.la_last_error.restype = ctypes.c_char_p
+    lib.la_version.restype = i32
+    for name in SYMBOLS[:7]:
+        getattr(lib, name).restype = i32
+    _lib = lib
+    return lib
+
+
+_STATUS = {1: "LA_ERR_INVALID_ARG", 2: "LA_ERR_UNSUPPORTED", 3: "LA_ERR_RUNTIME"}
+
+
+def _check(rc, name):
+    if rc != 0:
+        msg = f"{name}: {_STATUS.get(rc, rc)}"
+        if rc == 3:
+            msg += f" ({load().la_last_error().decode()})"
+        raise LaError(msg)
+
+
+def _dt(t):
+    if t.dtype == torch.float32:
+        return 0
+    if t.dtype == torch.float64:
+        return 1
+    raise LaError(f"unsupported dtype {t.dtype}")
+
+
+def _chk(*ts):
+    d = ts[0]
+    for t in ts:
+        if not t.is_cuda:
+            raise LaError("tensors must be on the GPU")
+        if not t.is_contiguous():
+            raise LaError("tensors must be contiguous")
+        if t.dtype != d.dtype or t.device != d.device:
+            raise LaError("tensors must share dtype and device")
+
+
+def _stream(t):
+    return ctypes.c_void_p(torch.cuda.current_stream(t.device).cuda_stream)
+
+
+def _ptr(t):
+    return ctypes.c_void_p(t.data_ptr()) if t is not None else ctypes.c_void_p(0)
+
+
+def _batch(t, trailing=2):
+    b = 1
+    for s in t.shape[: t.dim() - trailing]:
+        b *= s
+    return b
+
+
+def potrf(A, lower=True, out=None, info=None):
+    """la_potrf_batched.  ``out`` may be ``A`` itself (in place).  ``info``: int32 [batch] or None."""
+    _chk(A)
+    n = A.shape[-1]
+    assert A.shape[-2] == n
+    L = torch.empty_like(A) if out is None else out
+    _chk(A, L)
+    if info is not None:
+        assert info.dtype == torch.int32 and info.is_cuda and info.numel() == _batch(A)
+    with torch.cuda.device(A.device):
+        _check(load().la_potrf_batched(_dt(A), int(lower), _batch(A), n, _ptr(A), _ptr(L), _ptr(info), _stream(A)),
+               "la_potrf_batched")
+    return L
+
+
+def potrf_backward(L, Lbar, lower=True, out=None):
+    """la_potrf_backward.  ``out`` may be ``Lbar`` itself."""
+    _chk(L, Lbar)
+    n = L.shape[-1]
+    assert L.shape == Lbar.shape and L.shape[-2] == n
+    Abar = torch.empty_like(Lbar) if out is None else out
+    _chk(L, Abar)
+    with torch.cuda.device(L.device):
+        _check(load().la_potrf_backward(_dt(L), int(lower), _batch(L), n, _ptr(L), _ptr(Lbar), _ptr(Abar), _stream(L)),
+               "la_potrf_backward")
+    return Abar
+
+
+def _tri(fn, name, L, A, lower, trans, rightside, alpha, out):
+    _chk(L, A)
+    n = L.shape[-1]
+    assert L.shape[-2] == n
+    m = A.shape[-2] if rightside else A.shape[-1]
+    assert (A.shape[-1] if rightside else A.shape[-2]) == n
+    assert _batch(L) == _batch(A)
+    B = torch.empty_like(A) if out is None else out
+    _chk(A, B)
+    with torch.cuda.device(L.device):
+        _check(fn(_dt(L), int(lower), int(trans), int(rightside), float(alpha), _batch(L), n, m, _ptr(L), _ptr(A),
+                  _ptr(B), _stream(L)), name)
+    return B
+
+
+def trsm(L, A, lower=True, trans=False, rightside=False, alpha=1.0, out=None):
+    return _tri(load().la_trsm_batched, "la_trsm_batched", L, A, lower, trans, rightside, alpha, out)
+
+
+def trmm(L, A, lower=True, trans=False, rightside=False, alpha=1.0, out=None):
+    return _tri(load().la_trmm_batched, "la_trmm_batched", L, A, lower, trans, rightside, alpha, out)
+
+
+def syrk(A, trans=False, alpha=1.0, out=None):
+    _chk(A)
+    n, k = (A.shape[-1], A.shape[-2]) if trans else (A.shape[-2], A.shape[-1])
+    B = torch.empty(A.shape[:-2] + (n, n), dtype=A.dtype, device=A.device) if out is None else out
+    _chk(A, B)
+    with torch.cuda.device(A.device):
+        _check(load().la_syrk_batched(_dt(A), int(trans), float(alpha), _batch(A), n, k, _ptr(A), _ptr(B), _stream(A)),
+               "la_syrk_batched")
+    return B
+
+
+def sumlogdiag(L, out=None):
+    _chk(L)
+    n = L.shape[-1]
+    o = torch.empty(L.shape[:-2], dtype=L.dtype, device=L.device) if out is None else out
+    with torch.cuda.device(L.device):
+        _check(load().la_sumlogdiag(_dt(L), _batch(L), n, _ptr(L), _ptr(o), _stream(L)), "la_sumlogdiag")
+    return o
+
+
+def gp_glue(L, y, z, alpha, loss=None, Lbar=None):
+    _chk(L, y, z, alpha)
+    n = L.shape[-1]
+    loss = torch.empty(L.shape[:-2], dtype=L.dtype, device=L.device) if loss is None else loss
+    Lbar = torch.empty_like(L) if Lbar is None else Lbar
+    with torch.cuda.device(L.device):
+        _check(load().la_gp_glue(_dt(L), _batch(L), n, _ptr(L), _ptr(y), _ptr(z), _ptr(alpha), _ptr(loss), _ptr(Lbar),
+                                 _stream(L)), "la_gp_glue")
+    return loss, Lbar

@@ -1,0 +1,191 @@
+// Shared declarations of the gfx950 batched Cholesky library: status codes, the
+// strided-view descriptors passed from the host dispatcher to the kernels, wavefront
+// broadcast helpers and launcher prototypes.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "la.h"
+
+namespace la {
+
+constexpr int WAVE = 64;
+constexpr int NB = 64;  // edge of the triangular base-case tile of the blocked algorithms
+
+// View of one matrix operand inside a batched buffer: element (i, j) of item b lives at
+// base + b*bs + i*rs + j*cs (element units).  Row-major storage has cs == 1; the
+// transposed view of the same memory swaps rs and cs, which is how an upper factor
+// R = L^T (appendix, potrf, last paragraph) is handled without copying.
+template <typename T>
+struct View {
+    T *p;
+    int64_t bs, rs, cs;
+    __host__ __device__ View<T> sub(int64_t i, int64_t j) const { return {p + i * rs + j * cs, bs, rs, cs}; }
+    __host__ __device__ View<T> t() const { return {p, bs, cs, rs}; }
+    __device__ T *item(int64_t b) const { return p + b * bs; }
+};
+
+void set_error(hipError_t e, const char *where);
+
+#define LA_HIP(call)                         \
+    do {                                     \
+        hipError_t e__ = (call);             \
+        if (e__ != hipSuccess) {             \
+            ::la::set_error(e__, #call);     \
+            return LA_ERR_RUNTIME;           \
+        }                                    \
+    } while (0)
+
+#define LA_TRY(call)                \
+    do {                            \
+        la_status s__ = (call);     \
+        if (s__ != LA_OK)           \
+            return s__;             \
+    } while (0)
+
+inline la_status launch_check(const char *where)
+{
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) {
+        set_error(e, where);
+        return LA_ERR_RUNTIME;
+    }
+    return LA_OK;
+}
+
+// ---------------------------------------------------------------------------------
+// Broadcast of one lane's value to the G lanes of its group (G = 16, 32 or 64).
+// G = 16: DPP row_newbcast, folded by the compiler into the consuming VALU op.
+// G = 32: ds_bpermute through the LDS crossbar.  G = 64: v_readlane into an SGPR.
+// ---------------------------------------------------------------------------------
+template <int K>
+__device__ __forceinline__ int dpp_row_bcast_i(int x)
+{
+    return __builtin_amdgcn_update_dpp(0, x, 0x150 + K, 0xf, 0xf, false);
+}
+
+__device__ __forceinline__ int row_bcast_i(int x, int k)
+{
+    switch (k & 15) {
+    case 0: return dpp_row_bcast_i<0>(x);
+    case 1: return dpp_row_bcast_i<1>(x);
+    case 2: return dpp_row_bcast_i<2>(x);
+    case 3: return dpp_row_bcast_i<3>(x);
+    case 4: return dpp_row_bcast_i<4>(x);
+    case 5: return dpp_row_bcast_i<5>(x);
+    case 6: return dpp_row_bcast_i<6>(x);
+    case 7: return dpp_row_bcast_i<7>(x);
+    case 8: return dpp_row_bcast_i<8>(x);
+    case 9: return dpp_row_bcast_i<9>(x);
+    case 10: return dpp_row_bcast_i<10>(x);
+    case 11: return dpp_row_bcast_i<11>(x);
+    case 12: return dpp_row_bcast_i<12>(x);
+    case 13: return dpp_row_bcast_i<13>(x);
+    case 14: return dpp_row_bcast_i<14>(x);
+    default: return dpp_row_bcast_i<15>(x);
+    }
+}
+
+template <int G>
+__device__ __forceinline__ int group_bcast_i(int x, int k)
+{
+    if constexpr (G == 16) {
+        return row_bcast_i(x, k);
+    } else if constexpr (G == 32) {
+        int lane = __lane_id();
+        return __builtin_amdgcn_ds_bpermute(((lane & 32) | k) << 2, x);
+    } else {
+        return __builtin_amdgcn_readlane(x, k);
+    }
+}
+
+template <int G>
+__device__ __forceinline__ float group_bcast(float x, int k)
+{
+    return __builtin_bit_cast(float, group_bcast_i<G>(__builtin_bit_cast(int, x), k));
+}
+
+template <int G>
+__device__ __forceinline__ double group_bcast(double x, int k)
+{
+    long long v = __builtin_bit_cast(long long, x);
+    int lo = group_bcast_i<G>((int)(v & 0xffffffffll), k);
+    int hi = group_bcast_i<G>((int)(v >> 32), k);
+    long long r = ((long long)hi << 32) | (unsigned int)lo;
+    return __builtin_bit_cast(double, r);
+}
+
+// Reciprocal square root and reciprocal accurate to a few ulp of T.
+__device__ __forceinline__ float rsqrt_acc(float x) { return __builtin_amdgcn_rsqf(x); }
+__device__ __forceinline__ double rsqrt_acc(double x)
+{
+    // hardware seed (about 2^-26 relative), two Newton steps r <- r (1.5 - 0.5 x r^2)
+    double r = __builtin_amdgcn_rsq(x);
+    double h = 0.5 * x;
+    r = r * fma(-h * r, r, 1.5);
+    r = r * fma(-h * r, r, 1.5);
+    return r;
+}
+__device__ __forceinline__ float rcp_acc(float x) { return 1.0f / x; }
+__device__ __forceinline__ double rcp_acc(double x) { return 1.0 / x; }
+
+// ---------------------------------------------------------------------------------
+// Launchers (defined one per .hip file).  All take element-unit strides.
+// ---------------------------------------------------------------------------------
+
+// Register-resident potrf of blocks of edge nb <= G (G lanes per matrix), reading the
+// lower triangle of A(i,j) and writing L(i,j) (zeros above the diagonal of the block).
+// info (may be null): set to info_off + failing column (1-based) where it is still 0.
+template <typename T>
+la_status launch_potrf_tiny(View<const T> A, View<T> L, int32_t *info, int info_off, int64_t batch, int nb,
+                            hipStream_t st);
+
+// Register-resident potrf backward for n <= 32: Abar = sym(L^-T Phi(L^T Lbar) L^-1).
+template <typename T>
+la_status launch_backward_tiny(View<const T> L, View<const T> G, View<T> Abar, int64_t batch, int n,
+                               hipStream_t st);
+
+// Triangular base-case tiles.  Lam is a lower-triangular nb x nb block (nb <= 64), X holds
+// nvec vectors of length nb: element e of vector v at X.p + b*bs + e*rs + v*cs.
+//   solve, fwd:  Lam x = b        solve, !fwd: Lam^T x = b
+//   mult,  fwd:  x <- Lam x       mult,  !fwd: x <- Lam^T x
+// phi (mult only): the vectors are the columns of a lower-triangular block (entries above
+// the block's diagonal are taken as zero) and the result keeps only its lower triangle with
+// the diagonal halved.
+template <typename T>
+la_status launch_tile_solve(View<const T> Lam, View<T> X, int64_t batch, int nb, int64_t nvec, bool fwd,
+                            hipStream_t st);
+template <typename T>
+la_status launch_tile_mult(View<const T> Lam, View<T> X, int64_t batch, int nb, int64_t nvec, bool fwd, bool phi,
+                           hipStream_t st);
+
+// C(i,j) = beta*C(i,j) + alpha * sum_k A(i,k) B(k,j), i < M, j < N, k < K, per batch item.
+struct GemmOpts {
+    int triA = 0;      // 1: A(i,k) is zero for i < k (lower), 2: zero for i > k (upper)
+    int triB = 0;      // same on (k,j)
+    int maskC = 0;     // 1: only entries with i >= j are written
+    int halfDiag = 0;  // 1: the update of entries with i == j is halved
+};
+template <typename T>
+la_status launch_gemm(View<const T> A, View<const T> B, View<T> C, int64_t batch, int M, int N, int K, T alpha,
+                      T beta, GemmOpts o, hipStream_t st);
+
+// Element-wise helpers.
+// dst(i,j) = alpha * src(i,j) on rows x cols; keep: 0 all, 1 only i >= j (rest written as 0).
+template <typename T>
+la_status launch_copy(View<const T> src, View<T> dst, int64_t batch, int rows, int cols, T alpha, int keep,
+                      hipStream_t st);
+// X <- scale * (X + X^T) on n x n (exactly symmetric result).
+template <typename T>
+la_status launch_symmetrize(View<T> X, int64_t batch, int n, T scale, hipStream_t st);
+// X(i,j) <- X(j,i) for i < j (copy the lower triangle over the upper).
+template <typename T>
+la_status launch_mirror_lower(View<T> X, int64_t batch, int n, hipStream_t st);
+template <typename T>
+la_status launch_sumlogdiag(const T *L, T *out, int64_t batch, int n, hipStream_t st);
+template <typename T>
+la_status launch_gp_glue(const T *L, const T *y, const T *z, const T *alpha, T *loss, T *Lbar, int64_t batch, int n,
+                         hipStream_t st);
+la_status launch_fill_i32(int32_t *p, int64_t count, int32_t v, hipStream_t st);
+
+}  // namespace la

@@ -1,0 +1,231 @@
+// Memory-bound helper kernels: masked / scaled copies, the symmetrisation that ends the
+// potrf backward expression (appendix "potrf": Abar must be symmetric), copyltu-style
+// mirroring for syrk's full symmetric output, log|L| = sum_i log l_ii (section 3.1) and
+// the Gaussian-process criterion glue (section 3.1 with the trsm backward rule of
+// section 4.2).
+#include "common.hpp"
+
+namespace la {
+
+constexpr int ET = 32;  // tile edge of the transposing helpers
+
+template <typename T>
+__global__ __launch_bounds__(256) void k_copy(View<const T> src, View<T> dst, int64_t batch, int rows, int cols,
+                                              T alpha, int keep, int tiles_r, int tiles_c)
+{
+    const int64_t per = (int64_t)tiles_r * tiles_c;
+    const int64_t b = blockIdx.x / per;
+    const int tile = (int)(blockIdx.x % per);
+    const int r0 = (tile / tiles_c) * ET, c0 = (tile % tiles_c) * ET;
+    const bool colfast = (dst.cs == 1) || (dst.rs != 1);
+    const T *sp = src.p + b * src.bs;
+    T *dp = dst.p + b * dst.bs;
+    for (int t = threadIdx.x; t < ET * ET; t += 256) {
+        const int u = t / ET, w = t % ET;
+        const int r = r0 + (colfast ? u : w), c = c0 + (colfast ? w : u);
+        if (r < rows && c < cols) {
+            T v = T(0);
+            if (!(keep == 1 && r < c))
+                v = alpha * sp[(int64_t)r * src.rs + (int64_t)c * src.cs];
+            dp[(int64_t)r * dst.rs + (int64_t)c * dst.cs] = v;
+        }
+    }
+}
+
+template <typename T>
+la_status launch_copy(View<const T> src, View<T> dst, int64_t batch, int rows, int cols, T alpha, int keep,
+                      hipStream_t st)
+{
+    if (batch <= 0 || rows <= 0 || cols <= 0)
+        return LA_OK;
+    const int tr = (rows + ET - 1) / ET, tc = (cols + ET - 1) / ET;
+    const int64_t blocks = (int64_t)tr * tc * batch;
+    if (blocks > 0x7fffffffll)
+        return LA_ERR_UNSUPPORTED;
+    hipLaunchKernelGGL((k_copy<T>), dim3((unsigned)blocks), dim3(256), 0, st, src, dst, batch, rows, cols, alpha, keep,
+                       tr, tc);
+    return launch_check("copy");
+}
+
+// mode 0: X <- scale * (X + X^T).   mode 1: X(i,j) <- X(j,i) for i < j (lower copied to upper).
+// One block per tile pair (ti >= tj); both tiles pass through LDS so every global access is
+// along the contiguous direction.
+template <typename T>
+__global__ __launch_bounds__(256) void k_sym(View<T> X, int64_t batch, int n, T scale, int mode, int nt)
+{
+    __shared__ T sa[ET][ET + 1];
+    __shared__ T sb[ET][ET + 1];
+    const int64_t per = (int64_t)nt * nt;
+    const int64_t b = blockIdx.x / per;
+    const int tile = (int)(blockIdx.x % per);
+    const int ti = tile / nt, tj = tile % nt;
+    if (tj > ti)
+        return;
+    T *xp = X.p + b * X.bs;
+    // treat the matrix in memory order: for a symmetric operation the orientation is immaterial
+    const bool tr = (X.cs != 1);
+    const int64_t ld = tr ? X.cs : X.rs;
+    const int r0 = ti * ET, c0 = tj * ET;
+    for (int t = threadIdx.x; t < ET * ET; t += 256) {
+        const int u = t / ET, w = t % ET;
+        sa[u][w] = (r0 + u < n && c0 + w < n) ? xp[(int64_t)(r0 + u) * ld + c0 + w] : T(0);  // tile (ti,tj)
+        sb[u][w] = (c0 + u < n && r0 + w < n) ? xp[(int64_t)(c0 + u) * ld + r0 + w] : T(0);  // tile (tj,ti)
+    }
+    __syncthreads();
+    // In memory order "lower" means row >= column; when the view is transposed the logical
+    // lower triangle is the memory upper triangle.
+    for (int t = threadIdx.x; t < ET * ET; t += 256) {
+        const int u = t / ET, w = t % ET;
+        // entry (r0+u, c0+w) of tile (ti,tj) pairs with entry (c0+w, r0+u) = sb[w][u]
+        if (mode == 0) {
+            const T v = scale * (sa[u][w] + sb[w][u]);
+            if (r0 + u < n && c0 + w < n)
+                xp[(int64_t)(r0 + u) * ld + c0 + w] = v;
+        } else {
+            const int r = r0 + u, c = c0 + w;
+            if (r < n && c < n) {
+                const bool src_is_here = tr ? (r < c) : (r > c);  // this entry lies in the logical lower triangle
+                if (!src_is_here && r != c)
+                    xp[(int64_t)r * ld + c] = sb[w][u];
+            }
+        }
+    }
+    if (ti != tj) {
+        for (int t = threadIdx.x; t < ET * ET; t += 256) {
+            const int u = t / ET, w = t % ET;
+            // entry (c0+u, r0+w) of tile (tj,ti) pairs with entry (r0+w, c0+u) = sa[w][u]
+            const int r = c0 + u, c = r0 + w;
+            if (r < n && c < n) {
+                if (mode == 0) {
+                    xp[(int64_t)r * ld + c] = scale * (sa[w][u] + sb[u][w]);
+                } else {
+                    const bool src_is_here = tr ? (r < c) : (r > c);
+                    if (!src_is_here)
+                        xp[(int64_t)r * ld + c] = sa[w][u];
+                }
+            }
+        }
+    }
+}
+
+template <typename T>
+static la_status launch_sym(View<T> X, int64_t batch, int n, T scale, int mode, hipStream_t st)
+{
+    if (batch <= 0 || n <= 0)
+        return LA_OK;
+    const int nt = (n + ET - 1) / ET;
+    const int64_t blocks = (int64_t)nt * nt * batch;
+    if (blocks > 0x7fffffffll)
+        return LA_ERR_UNSUPPORTED;
+    hipLaunchKernelGGL((k_sym<T>), dim3((unsigned)blocks), dim3(256), 0, st, X, batch, n, scale, mode, nt);
+    return launch_check("sym");
+}
+template <typename T>
+la_status launch_symmetrize(View<T> X, int64_t batch, int n, T scale, hipStream_t st)
+{
+    return launch_sym<T>(X, batch, n, scale, 0, st);
+}
+template <typename T>
+la_status launch_mirror_lower(View<T> X, int64_t batch, int n, hipStream_t st)
+{
+    return launch_sym<T>(X, batch, n, T(1), 1, st);
+}
+
+// One wavefront per matrix: out[b] = sum_i log L[b,i,i].
+template <typename T>
+__global__ __launch_bounds__(WAVE) void k_sumlogdiag(const T *L, T *out, int64_t batch, int n)
+{
+    const int64_t b = blockIdx.x;
+    const T *lp = L + b * (int64_t)n * n;
+    double s = 0.0;
+    for (int i = threadIdx.x; i < n; i += WAVE)
+        s += (double)log(lp[(int64_t)i * n + i]);
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1)
+        s += __shfl_xor(s, off, WAVE);
+    if (threadIdx.x == 0)
+        out[b] = (T)s;
+}
+
+template <typename T>
+la_status launch_sumlogdiag(const T *L, T *out, int64_t batch, int n, hipStream_t st)
+{
+    if (batch <= 0)
+        return LA_OK;
+    if (batch > 0x7fffffffll)
+        return LA_ERR_UNSUPPORTED;
+    hipLaunchKernelGGL((k_sumlogdiag<T>), dim3((unsigned)batch), dim3(WAVE), 0, st, L, out, batch, n);
+    return launch_check("sumlogdiag");
+}
+
+// One workgroup per matrix: loss = 1/2 y.alpha + sum log l_ii, Lbar = -tril(alpha z^T) + diag(1/l_ii).
+template <typename T>
+__global__ __launch_bounds__(256) void k_gp_glue(const T *L, const T *y, const T *z, const T *alpha, T *loss, T *Lbar,
+                                                 int64_t batch, int n)
+{
+    __shared__ double red[4];
+    const int64_t b = blockIdx.x;
+    const T *lp = L + b * (int64_t)n * n;
+    const T *yp = y + b * n, *zp = z + b * n, *ap = alpha + b * n;
+    T *gp = Lbar + b * (int64_t)n * n;
+    double s = 0.0;
+    for (int i = threadIdx.x; i < n; i += 256)
+        s += 0.5 * (double)yp[i] * (double)ap[i] + (double)log(lp[(int64_t)i * n + i]);
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1)
+        s += __shfl_xor(s, off, WAVE);
+    if ((threadIdx.x & 63) == 0)
+        red[threadIdx.x >> 6] = s;
+    __syncthreads();
+    if (threadIdx.x == 0)
+        loss[b] = (T)(red[0] + red[1] + red[2] + red[3]);
+    const int64_t nn = (int64_t)n * n;
+    for (int64_t e = threadIdx.x; e < nn; e += 256) {
+        const int i = (int)(e / n), j = (int)(e % n);
+        T g = T(0);
+        if (i >= j)
+            g = -ap[i] * zp[j];
+        if (i == j)
+            g += T(1) / lp[e];
+        gp[e] = g;
+    }
+}
+
+template <typename T>
+la_status launch_gp_glue(const T *L, const T *y, const T *z, const T *alpha, T *loss, T *Lbar, int64_t batch, int n,
+                         hipStream_t st)
+{
+    if (batch <= 0)
+        return LA_OK;
+    if (batch > 0x7fffffffll)
+        return LA_ERR_UNSUPPORTED;
+    hipLaunchKernelGGL((k_gp_glue<T>), dim3((unsigned)batch), dim3(256), 0, st, L, y, z, alpha, loss, Lbar, batch, n);
+    return launch_check("gp_glue");
+}
+
+__global__ void k_fill_i32(int32_t *p, int64_t count, int32_t v)
+{
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < count)
+        p[i] = v;
+}
+
+la_status launch_fill_i32(int32_t *p, int64_t count, int32_t v, hipStream_t st)
+{
+    if (count <= 0)
+        return LA_OK;
+    hipLaunchKernelGGL(k_fill_i32, dim3((unsigned)((count + 255) / 256)), dim3(256), 0, st, p, count, v);
+    return launch_check("fill");
+}
+
+#define LA_INST(T)                                                                                              \
+    template la_status launch_copy<T>(View<const T>, View<T>, int64_t, int, int, T, int, hipStream_t);          \
+    template la_status launch_symmetrize<T>(View<T>, int64_t, int, T, hipStream_t);                             \
+    template la_status launch_mirror_lower<T>(View<T>, int64_t, int, hipStream_t);                              \
+    template la_status launch_sumlogdiag<T>(const T *, T *, int64_t, int, hipStream_t);                         \
+    template la_status launch_gp_glue<T>(const T *, const T *, const T *, const T *, T *, T *, int64_t, int,    \
+                                         hipStream_t);
+LA_INST(float)
+LA_INST(double)
+
+}  // namespace la

@@ -1,0 +1,396 @@
+// Register-resident kernels for small matrices: G lanes of a wavefront own one matrix
+// (lane = row, registers = columns), so a wave64 works on 64/G matrices at once and the
+// column reductions of the factorisation are lane broadcasts (DPP row broadcast for
+// G = 16, LDS crossbar permute for G = 32, v_readlane for G = 64).
+//
+// potrf forward: section 4.2 of arXiv 1710.08717 (A = L L^T, positive diagonal).
+// potrf backward: section 4.2 / appendix "potrf":
+//   Abar = 1/2 L^-T copyltu(L^T Lbar) L^-1 = sym(L^-T Phi(L^T Lbar) L^-1),
+//   Phi = lower triangle with halved diagonal (copyltu X = Phi X + (Phi X)^T).
+//
+// Global memory is only touched through coalesced passes that stage whole matrices in
+// LDS; the lanes then pick rows or columns out of LDS, which is also how the transposed
+// (upper-factor) views are served.
+#include "common.hpp"
+
+namespace la {
+
+template <typename T>
+struct VecOf;
+template <>
+struct VecOf<float> {
+    using type = float4;
+    static constexpr int N = 4;
+};
+template <>
+struct VecOf<double> {
+    using type = double2;
+    static constexpr int N = 2;
+};
+
+// LDS staging area of one wave: MPW matrices of G x G, rows padded by 16 bytes and
+// matrices by 64 bytes so row reads, column reads and the flat fill are conflict-poor.
+template <typename T, int G>
+struct Stage {
+    static constexpr int MPW = WAVE / G;
+    static constexpr int PAD = 16 / sizeof(T);
+    static constexpr int LD = G + PAD;
+    static constexpr int MS = G * LD + 64 / sizeof(T);
+    static constexpr int ELEMS = MPW * MS;
+};
+
+// Memory-order description of a batched block operand: entry (r, c) of item b at
+// p + b*bs + r*ld + c.  tr says the LOGICAL matrix is the transpose of what memory holds.
+template <typename T>
+struct Mem {
+    T *p;
+    int64_t bs, ld;
+    bool tr;
+};
+template <typename T>
+__device__ __forceinline__ Mem<T> mem_of(View<T> V)
+{
+    const bool tr = (V.cs != 1);
+    return {V.p, V.bs, tr ? V.cs : V.rs, tr};
+}
+
+template <typename T, int G>
+__device__ __forceinline__ bool flat_ok(const T *p, int64_t bs, int64_t ld, int64_t b0, int64_t batch, int nb)
+{
+    return nb == G && ld == G && bs == G * G && b0 + Stage<T, G>::MPW <= batch &&
+           (reinterpret_cast<uintptr_t>(p) & 15) == 0;
+}
+
+// Fill the stage from global memory, in memory order.  Matrix q of the wave is item
+// (b0 + q); entries outside nb x nb, and whole matrices past the batch end, become identity.
+template <typename T, int G>
+__device__ __forceinline__ void stage_load(T *sm, Mem<const T> M, int64_t b0, int64_t batch, int nb)
+{
+    using S = Stage<T, G>;
+    const int lane = threadIdx.x;
+    // fast path: full G x G matrices stored back to back -> one flat vectorised copy
+    if (flat_ok<T, G>(M.p, M.bs, M.ld, b0, batch, nb)) {
+        using V4 = typename VecOf<T>::type;
+        constexpr int VN = VecOf<T>::N;
+        const V4 *src = reinterpret_cast<const V4 *>(M.p + b0 * M.bs);
+        constexpr int NV = S::MPW * G * G / VN;
+#pragma unroll
+        for (int t = 0; t < NV / WAVE; ++t) {
+            int e = (t * WAVE + lane) * VN;
+            int q = e / (G * G), r = (e / G) % G, c = e % G;
+            *reinterpret_cast<V4 *>(sm + q * S::MS + r * S::LD + c) = src[t * WAVE + lane];
+        }
+        return;
+    }
+#pragma unroll 4
+    for (int t = 0; t < S::MPW * G * G / WAVE; ++t) {
+        int e = t * WAVE + lane;
+        int q = e / (G * G);
+        int r = (e / G) % G, c = e % G;
+        T v = (r == c) ? T(1) : T(0);
+        if (b0 + q < batch && r < nb && c < nb)
+            v = M.p[(b0 + q) * M.bs + r * M.ld + c];
+        sm[q * S::MS + r * S::LD + c] = v;
+    }
+}
+
+template <typename T, int G>
+__device__ __forceinline__ void stage_store(const T *sm, Mem<T> M, int64_t b0, int64_t batch, int nb)
+{
+    using S = Stage<T, G>;
+    const int lane = threadIdx.x;
+    if (flat_ok<T, G>(M.p, M.bs, M.ld, b0, batch, nb)) {
+        using V4 = typename VecOf<T>::type;
+        constexpr int VN = VecOf<T>::N;
+        V4 *dst = reinterpret_cast<V4 *>(M.p + b0 * M.bs);
+        constexpr int NV = S::MPW * G * G / VN;
+#pragma unroll
+        for (int t = 0; t < NV / WAVE; ++t) {
+            int e = (t * WAVE + lane) * VN;
+            int q = e / (G * G), r = (e / G) % G, c = e % G;
+            dst[t * WAVE + lane] = *reinterpret_cast<const V4 *>(sm + q * S::MS + r * S::LD + c);
+        }
+        return;
+    }
+#pragma unroll 4
+    for (int t = 0; t < S::MPW * G * G / WAVE; ++t) {
+        int e = t * WAVE + lane;
+        int q = e / (G * G);
+        int r = (e / G) % G, c = e % G;
+        if (b0 + q < batch && r < nb && c < nb)
+            M.p[(b0 + q) * M.bs + r * M.ld + c] = sm[q * S::MS + r * S::LD + c];
+    }
+}
+
+// Row i of the staged matrix into registers (row read), or column i (column read).
+template <typename T, int G>
+__device__ __forceinline__ void read_row(const T *smq, int i, T (&a)[G])
+{
+    using S = Stage<T, G>;
+    using V4 = typename VecOf<T>::type;
+    constexpr int VN = VecOf<T>::N;
+#pragma unroll
+    for (int c = 0; c < G; c += VN) {
+        V4 v = *reinterpret_cast<const V4 *>(smq + i * S::LD + c);
+        if constexpr (VN == 4) {
+            a[c] = v.x; a[c + 1] = v.y; a[c + 2] = v.z; a[c + 3] = v.w;
+        } else {
+            a[c] = v.x; a[c + 1] = v.y;
+        }
+    }
+}
+template <typename T, int G>
+__device__ __forceinline__ void write_row(T *smq, int i, const T (&a)[G])
+{
+    using S = Stage<T, G>;
+    using V4 = typename VecOf<T>::type;
+    constexpr int VN = VecOf<T>::N;
+#pragma unroll
+    for (int c = 0; c < G; c += VN) {
+        V4 v;
+        if constexpr (VN == 4) {
+            v.x = a[c]; v.y = a[c + 1]; v.z = a[c + 2]; v.w = a[c + 3];
+        } else {
+            v.x = a[c]; v.y = a[c + 1];
+        }
+        *reinterpret_cast<V4 *>(smq + i * S::LD + c) = v;
+    }
+}
+template <typename T, int G>
+__device__ __forceinline__ void read_col(const T *smq, int i, T (&a)[G])
+{
+    using S = Stage<T, G>;
+#pragma unroll
+    for (int r = 0; r < G; ++r)
+        a[r] = smq[r * S::LD + i];
+}
+
+template <typename T, int G>
+__device__ __forceinline__ void write_col(T *smq, int i, const T (&a)[G])
+{
+    using S = Stage<T, G>;
+#pragma unroll
+    for (int r = 0; r < G; ++r)
+        smq[r * S::LD + i] = a[r];
+}
+// Logical row i of a staged matrix whose memory image may be the transpose.
+template <typename T, int G>
+__device__ __forceinline__ void read_lrow(const T *smq, int i, bool tr, T (&a)[G])
+{
+    if (tr)
+        read_col<T, G>(smq, i, a);
+    else
+        read_row<T, G>(smq, i, a);
+}
+template <typename T, int G>
+__device__ __forceinline__ void read_lcol(const T *smq, int i, bool tr, T (&a)[G])
+{
+    if (tr)
+        read_row<T, G>(smq, i, a);
+    else
+        read_col<T, G>(smq, i, a);
+}
+
+// ---------------------------------------------------------------------------------
+// potrf forward.  View A / L give the LOGICAL lower-triangular problem: A(i,j), i >= j,
+// is read; L(i,j) is written for the whole nb x nb block (zeros for i < j).
+// ---------------------------------------------------------------------------------
+template <typename T, int G>
+__global__ __launch_bounds__(WAVE) void k_potrf_tiny(View<const T> A, View<T> L, int32_t *info, int info_off,
+                                                      int64_t batch, int nb)
+{
+    using S = Stage<T, G>;
+    __shared__ __align__(16) T sm[S::ELEMS];
+    const int lane = threadIdx.x;
+    const int q = lane / G, i = lane % G;
+    const int64_t b0 = (int64_t)blockIdx.x * S::MPW;
+
+    const Mem<const T> Am = mem_of(A);
+    const Mem<T> Lm = mem_of(L);
+    stage_load<T, G>(sm, Am, b0, batch, nb);
+    __syncthreads();
+    T a[G];
+    read_lrow<T, G>(sm + q * S::MS, i, Am.tr, a);
+#pragma unroll
+    for (int k = 0; k < G; ++k)
+        if (k > i)
+            a[k] = T(0);  // the other triangle of A is never used
+
+    int fail = 0;
+#pragma unroll
+    for (int j = 0; j < G; ++j) {
+        T piv = group_bcast<G>(a[j], j);  // a_jj after the updates of columns < j
+        if (!(piv > T(0)) && fail == 0)
+            fail = j + 1;
+        T r = rsqrt_acc(piv);
+        a[j] = (i >= j) ? a[j] * r : T(0);  // column j of L (lane j gets sqrt(piv))
+#pragma unroll
+        for (int k = j + 1; k < G; ++k)
+            a[k] = fma(-a[j], group_bcast<G>(a[j], k), a[k]);  // a_ik -= l_ij l_kj
+    }
+#pragma unroll
+    for (int k = 0; k < G; ++k)
+        if (k > i)
+            a[k] = T(0);
+
+    __syncthreads();
+    if (Lm.tr)
+        write_col<T, G>(sm + q * S::MS, i, a);
+    else
+        write_row<T, G>(sm + q * S::MS, i, a);
+    __syncthreads();
+    stage_store<T, G>(sm, Lm, b0, batch, nb);
+    if (info != nullptr && i == 0 && b0 + q < batch && fail != 0 && fail <= nb) {
+        if (info[b0 + q] == 0)
+            info[b0 + q] = info_off + fail;
+    }
+}
+
+// ---------------------------------------------------------------------------------
+// potrf backward for n <= G.  Views give the logical lower-triangular L and Lbar.
+// ---------------------------------------------------------------------------------
+template <typename T, int G>
+__global__ __launch_bounds__(WAVE) void k_backward_tiny(View<const T> Lv, View<const T> Gv, View<T> Av,
+                                                         int64_t batch, int n)
+{
+    using S = Stage<T, G>;
+    __shared__ __align__(16) T sm[S::ELEMS];
+    const int lane = threadIdx.x;
+    const int q = lane / G, i = lane % G;
+    const int64_t b0 = (int64_t)blockIdx.x * S::MPW;
+    T *smq = sm + q * S::MS;
+
+    // lane i takes column i of L: lc[k] = l_ki (k >= i), and its reciprocal diagonal
+    T lc[G];
+    const Mem<const T> Lm = mem_of(Lv);
+    const Mem<const T> Gm = mem_of(Gv);
+    stage_load<T, G>(sm, Lm, b0, batch, n);
+    __syncthreads();
+    read_lcol<T, G>(smq, i, Lm.tr, lc);
+    T dii = T(1);
+#pragma unroll
+    for (int k = 0; k < G; ++k) {
+        if (k == i)
+            dii = lc[k];
+        if (k < i)
+            lc[k] = T(0);
+    }
+    const T rd = rcp_acc(dii);
+    __syncthreads();
+
+    // lane k takes row k of Lbar: g[j] = lbar_kj (j <= k)
+    T g[G];
+    stage_load<T, G>(sm, Gm, b0, batch, n);
+    __syncthreads();
+    read_lrow<T, G>(smq, i, Gm.tr, g);
+#pragma unroll
+    for (int j = 0; j < G; ++j)
+        if (j > i || i >= n)
+            g[j] = T(0);  // also drops the identity padding of the stage
+
+    // P = L^T Lbar, row i in lane i: p_ij = sum_k l_ki lbar_kj   (terms with j > k are zero)
+    T y[G];
+#pragma unroll
+    for (int j = 0; j < G; ++j)
+        y[j] = T(0);
+#pragma unroll
+    for (int k = 0; k < G; ++k) {
+#pragma unroll
+        for (int j = 0; j <= k; ++j)
+            y[j] = fma(lc[k], group_bcast<G>(g[j], k), y[j]);
+    }
+    // Phi, then the row scaling D^-1 of L = Lt D (Lt unit lower triangular)
+#pragma unroll
+    for (int j = 0; j < G; ++j) {
+        T v = (j < i) ? y[j] : ((j == i) ? T(0.5) * y[j] : T(0));
+        y[j] = v * rd;
+    }
+    // lt[k] = l_ki / l_ii for k > i, zero otherwise
+#pragma unroll
+    for (int k = 0; k < G; ++k)
+        lc[k] = (k > i) ? lc[k] * rd : T(0);
+
+    // Y = Lt^-T (D^-1 Phi): rows from the bottom; row k is final when it is broadcast
+#pragma unroll
+    for (int k = G - 1; k >= 1; --k) {
+#pragma unroll
+        for (int c = 0; c < G; ++c)
+            y[c] = fma(-lc[k], group_bcast<G>(y[c], k), y[c]);
+    }
+    // V = Y D^-1 (column c scaled by 1 / l_cc), then W = V Lt^-1 from the last column back
+#pragma unroll
+    for (int c = 0; c < G; ++c)
+        y[c] *= group_bcast<G>(rd, c);
+#pragma unroll
+    for (int c = G - 2; c >= 0; --c) {
+#pragma unroll
+        for (int k = c + 1; k < G; ++k)
+            y[c] = fma(-y[k], group_bcast<G>(lc[k], c), y[c]);
+    }
+
+    // Abar = 1/2 (W + W^T): rows out to LDS, columns back in
+    __syncthreads();
+    write_row<T, G>(smq, i, y);
+    __syncthreads();
+    T wt[G];
+    read_col<T, G>(smq, i, wt);
+#pragma unroll
+    for (int c = 0; c < G; ++c)
+        y[c] = T(0.5) * (y[c] + wt[c]);
+    __syncthreads();
+    write_row<T, G>(smq, i, y);
+    __syncthreads();
+    stage_store<T, G>(sm, mem_of(Av), b0, batch, n);  // symmetric: orientation is immaterial
+}
+
+template <typename T>
+la_status launch_potrf_tiny(View<const T> A, View<T> L, int32_t *info, int info_off, int64_t batch, int nb,
+                            hipStream_t st)
+{
+    if (batch <= 0 || nb <= 0)
+        return LA_OK;
+    if (nb > 64)
+        return LA_ERR_UNSUPPORTED;
+    if (nb <= 16) {
+        constexpr int MPW = Stage<T, 16>::MPW;
+        hipLaunchKernelGGL((k_potrf_tiny<T, 16>), dim3((unsigned)((batch + MPW - 1) / MPW)), dim3(WAVE), 0, st, A, L,
+                           info, info_off, batch, nb);
+    } else if (nb <= 32) {
+        constexpr int MPW = Stage<T, 32>::MPW;
+        hipLaunchKernelGGL((k_potrf_tiny<T, 32>), dim3((unsigned)((batch + MPW - 1) / MPW)), dim3(WAVE), 0, st, A, L,
+                           info, info_off, batch, nb);
+    } else {
+        hipLaunchKernelGGL((k_potrf_tiny<T, 64>), dim3((unsigned)batch), dim3(WAVE), 0, st, A, L, info, info_off,
+                           batch, nb);
+    }
+    return launch_check("potrf_tiny");
+}
+
+template <typename T>
+la_status launch_backward_tiny(View<const T> L, View<const T> G, View<T> Abar, int64_t batch, int n, hipStream_t st)
+{
+    if (batch <= 0 || n <= 0)
+        return LA_OK;
+    if (n > 32)
+        return LA_ERR_UNSUPPORTED;
+    if (n <= 16) {
+        constexpr int MPW = Stage<T, 16>::MPW;
+        hipLaunchKernelGGL((k_backward_tiny<T, 16>), dim3((unsigned)((batch + MPW - 1) / MPW)), dim3(WAVE), 0, st, L,
+                           G, Abar, batch, n);
+    } else {
+        constexpr int MPW = Stage<T, 32>::MPW;
+        hipLaunchKernelGGL((k_backward_tiny<T, 32>), dim3((unsigned)((batch + MPW - 1) / MPW)), dim3(WAVE), 0, st, L,
+                           G, Abar, batch, n);
+    }
+    return launch_check("backward_tiny");
+}
+
+template la_status launch_potrf_tiny<float>(View<const float>, View<float>, int32_t *, int, int64_t, int, hipStream_t);
+template la_status launch_potrf_tiny<double>(View<const double>, View<double>, int32_t *, int, int64_t, int,
+                                             hipStream_t);
+template la_status launch_backward_tiny<float>(View<const float>, View<const float>, View<float>, int64_t, int,
+                                               hipStream_t);
+template la_status launch_backward_tiny<double>(View<const double>, View<const double>, View<double>, int64_t, int,
+                                                hipStream_t);
+
+}  // namespace la

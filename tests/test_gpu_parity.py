@@ -1,0 +1,324 @@
+"""Parity of the HIP library (through the C ABI / ctypes binding) against the CPU oracle.
+
+Every test runs the same seeded inputs through both, element by element.
+Tolerances (the benchmark spec): relative Frobenius error per matrix
+<= 1e-10 in fp64 and <= 2e-4 in fp32 for matrices with condition number <= 1e3
+(the fp32 result is compared with the fp64 oracle evaluated on the same fp32 inputs).
+Integer outputs (info) and structural zeros are compared exactly.
+"""
+import itertools
+import sys
+
+import numpy as np
+import pytest
+
+import workloads
+
+pytestmark = pytest.mark.gpu
+
+TOL = {"f32": 2e-4, "f64": 1e-10}
+FLAGS = list(itertools.product([True, False], [False, True], [False, True]))  # lower, trans, rightside
+
+
+@pytest.fixture(scope="module")
+def la():
+    import torch
+
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    import paper_1710_08717_amd as la_mod
+
+    la_mod.load()  # raises if the HIP library is missing: there is no fallback
+    return la_mod
+
+
+@pytest.fixture(autouse=True)
+def _announce(request):
+    sys.stderr.write(f"\n[gpu-case] {request.node.nodeid}\n")
+    sys.stderr.flush()
+    yield
+
+
+def dev(a):
+    import torch
+
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+def host(t):
+    import torch
+
+    torch.cuda.synchronize()
+    return t.cpu().numpy()
+
+
+def npdt(dtype):
+    return workloads.np_dtype(dtype)
+
+
+def relerr(x, ref):
+    """max over the batch of ||x - ref||_F / ||ref||_F."""
+    x = np.asarray(x, dtype=np.float64)
+    ref = np.asarray(ref, dtype=np.float64)
+    if x.ndim < 3:
+        x, ref = x[None], ref[None]
+    x = x.reshape(x.shape[0], -1)
+    ref = ref.reshape(ref.shape[0], -1)
+    num = np.linalg.norm(x - ref, axis=1)
+    den = np.maximum(np.linalg.norm(ref, axis=1), 1e-300)
+    return float(np.max(num / den)) if len(num) else 0.0
+
+
+def spd(seed, batch, n, dtype):
+    rng = np.random.default_rng(seed)
+    X = rng.standard_normal((batch, n, 2 * n))
+    A = X @ X.transpose(0, 2, 1) / (2 * n) + np.eye(n)
+    return (0.5 * (A + A.transpose(0, 2, 1))).astype(npdt(dtype))
+
+
+def tri(seed, batch, n, lower, dtype):
+    rng = np.random.default_rng(seed)
+    T = rng.standard_normal((batch, n, n)) * (0.5 / np.sqrt(max(n, 1)))
+    T = np.tril(T) if lower else np.triu(T)
+    idx = np.arange(n)
+    T[:, idx, idx] = 1.0 + rng.uniform(0.0, 1.0, size=(batch, n))
+    return T.astype(npdt(dtype))
+
+
+SIZES = [1, 2, 5, 15, 16, 17, 31, 32, 33, 48, 64, 65, 100, 128, 129, 200, 256, 321]
+
+
+# ----------------------------------------------------------------------------
+# potrf forward
+# ----------------------------------------------------------------------------
+@pytest.mark.parametrize("dtype", ["f64", "f32"])
+@pytest.mark.parametrize("n", SIZES)
+@pytest.mark.parametrize("lower", [True, False])
+def test_potrf_parity(la, orc, dtype, n, lower):
+    import torch
+
+    batch = 7 if n <= 64 else 3
+    A = spd(n * 3 + lower, batch, n, dtype)
+    ref = orc.potrf(A, lower=lower)
+    info = torch.full((batch,), -1, dtype=torch.int32, device="cuda")
+    L = host(la.potrf(dev(A), lower=lower, info=info))
+    assert L.dtype == A.dtype
+    assert np.all(host(info) == 0)
+    other = np.triu_indices(n, 1) if lower else np.tril_indices(n, -1)
+    assert np.all(L[:, other[0], other[1]] == 0.0)  # exact zeros in the other triangle
+    assert relerr(L, ref) <= TOL[dtype]
+
+
+@pytest.mark.parametrize("dtype", ["f64", "f32"])
+@pytest.mark.parametrize("n", [8, 16, 32, 50, 150])
+@pytest.mark.parametrize("lower", [True, False])
+def test_potrf_in_place_and_other_triangle_ignored(la, orc, dtype, n, lower):
+    A = spd(n + 11, 5, n, dtype)
+    ref = orc.potrf(A, lower=lower)
+    junk = A.copy()
+    other = np.triu_indices(n, 1) if lower else np.tril_indices(n, -1)
+    junk[:, other[0], other[1]] = np.nan
+    t = dev(junk)
+    out = la.potrf(t, lower=lower, out=t)  # L overwrites A
+    L = host(out)
+    assert np.all(L[:, other[0], other[1]] == 0.0)
+    assert relerr(L, ref) <= TOL[dtype]
+
+
+@pytest.mark.parametrize("dtype", ["f64", "f32"])
+@pytest.mark.parametrize("n,bad", [(6, 3), (16, 15), (32, 0), (64, 40), (200, 130)])
+def test_potrf_info_first_bad_pivot(la, orc, dtype, n, bad):
+    import torch
+
+    A = spd(n, 3, n, dtype)
+    A[1, bad, bad] = -1.0  # leading minor of order bad+1 is not positive definite
+    _, ref_info = orc.potrf(A, return_info=True)
+    info = torch.zeros(3, dtype=torch.int32, device="cuda")
+    L = host(la.potrf(dev(A), info=info))
+    assert list(host(info)) == list(ref_info) == [0, bad + 1, 0]
+    ok = [0, 2]
+    assert relerr(L[ok], orc.potrf(A[ok])) <= TOL[dtype]
+
+
+def test_potrf_ragged_batch_and_large_batch(la, orc):
+    # batches that do not fill the last wavefront, and more items than one grid dimension holds
+    for n, batch, dtype in [(16, 5, "f32"), (16, 70001, "f32"), (9, 3, "f64"), (32, 3, "f64"), (20, 4097, "f32")]:
+        A = spd(n + batch, batch, n, dtype)
+        assert relerr(host(la.potrf(dev(A))), orc.potrf(A)) <= TOL[dtype]
+
+
+def test_empty_inputs(la):
+    import torch
+
+    for shape in [(0, 4, 4), (3, 0, 0)]:
+        A = torch.zeros(shape, dtype=torch.float64, device="cuda")
+        assert la.potrf(A).shape == shape
+        assert la.potrf_backward(A, A.clone()).shape == shape
+        assert la.syrk(A).shape == shape
+    L = torch.eye(4, dtype=torch.float32, device="cuda")[None]
+    B = torch.zeros((1, 4, 0), dtype=torch.float32, device="cuda")
+    assert la.trsm(L, B).shape == (1, 4, 0)
+    assert la.trmm(L, B).shape == (1, 4, 0)
+    assert la.sumlogdiag(torch.zeros((0, 3, 3), device="cuda")).shape == (0,)
+
+
+def test_argument_errors(la):
+    import torch
+
+    A = torch.eye(4, dtype=torch.float64, device="cuda")[None].contiguous()
+    flat = torch.zeros(64, dtype=torch.float64, device="cuda")
+    a = flat[:16].view(1, 4, 4)
+    b = flat[8:24].view(1, 4, 4)  # partial overlap
+    with pytest.raises(la.LaError):
+        la.potrf(a, out=b)
+    with pytest.raises(la.LaError):
+        la.potrf_backward(A, a, out=A)  # Abar must not overlap L
+    with pytest.raises(la.LaError):
+        la.syrk(A, out=A)
+    with pytest.raises(la.LaError):
+        la.potrf(A.to(torch.float16))
+    with pytest.raises(la.LaError):
+        la.potrf(A.cpu())
+
+
+# ----------------------------------------------------------------------------
+# potrf backward
+# ----------------------------------------------------------------------------
+@pytest.mark.parametrize("dtype", ["f64", "f32"])
+@pytest.mark.parametrize("n", SIZES)
+@pytest.mark.parametrize("lower", [True, False])
+def test_backward_parity(la, orc, dtype, n, lower):
+    batch = 6 if n <= 64 else 2
+    A = spd(n * 5 + lower, batch, n, dtype)
+    Lf = orc.potrf(A, lower=lower).astype(npdt(dtype))  # the factor both sides start from
+    rng = np.random.default_rng(n)
+    G = rng.standard_normal((batch, n, n))
+    G = (np.tril(G) if lower else np.triu(G)).astype(npdt(dtype))
+    ref = orc.potrf_backward(Lf, G, lower=lower)
+    out = host(la.potrf_backward(dev(Lf), dev(G), lower=lower))
+    assert np.array_equal(out, out.transpose(0, 2, 1))  # exactly symmetric
+    assert relerr(out, ref) <= TOL[dtype]
+
+
+@pytest.mark.parametrize("dtype", ["f64", "f32"])
+@pytest.mark.parametrize("n", [7, 16, 32, 40, 130])
+@pytest.mark.parametrize("lower", [True, False])
+def test_backward_aliasing_and_junk_triangles(la, orc, dtype, n, lower):
+    batch = 5
+    A = spd(n + 77, batch, n, dtype)
+    Lf = orc.potrf(A, lower=lower).astype(npdt(dtype))
+    rng = np.random.default_rng(n + 1)
+    G = rng.standard_normal((batch, n, n)).astype(npdt(dtype))  # full: the other triangle must be ignored
+    ref = orc.potrf_backward(Lf, (np.tril(G) if lower else np.triu(G)), lower=lower)
+    other = np.triu_indices(n, 1) if lower else np.tril_indices(n, -1)
+    Lj = Lf.copy()
+    Lj[:, other[0], other[1]] = np.nan
+    Gj = G.copy()
+    Gj[:, other[0], other[1]] = np.nan
+    g = dev(Gj)
+    out = host(la.potrf_backward(dev(Lj), g, lower=lower, out=g))  # Abar overwrites Lbar
+    assert np.all(np.isfinite(out))
+    assert relerr(out, ref) <= TOL[dtype]
+
+
+def test_backward_closed_forms(la, orc):
+    """Lbar = L gives Abar = I/2; Lbar = diag(1/l_ii) gives Abar = inv(A)/2 (both from phi's definition)."""
+    for n, dtype in [(16, "f64"), (32, "f64"), (96, "f64"), (16, "f32")]:
+        A = spd(n, 4, n, dtype)
+        L = la.potrf(dev(A))
+        half_eye = np.broadcast_to(0.5 * np.eye(n), A.shape)
+        got = host(la.potrf_backward(L, L.clone()))
+        assert np.max(np.abs(got - half_eye)) <= (1e-12 if dtype == "f64" else 1e-5)
+        Lh = host(L)
+        D = np.zeros_like(Lh)
+        idx = np.arange(n)
+        D[:, idx, idx] = 1.0 / Lh[:, idx, idx]
+        got = host(la.potrf_backward(L, dev(D)))
+        assert relerr(got, 0.5 * np.linalg.inv(A.astype(np.float64))) <= 10 * TOL[dtype]
+
+
+# ----------------------------------------------------------------------------
+# trsm / trmm
+# ----------------------------------------------------------------------------
+@pytest.mark.parametrize("dtype", ["f64", "f32"])
+@pytest.mark.parametrize("lower,trans,rightside", FLAGS)
+@pytest.mark.parametrize("n,m", [(1, 1), (5, 3), (32, 8), (64, 64), (65, 7), (100, 130), (200, 33), (257, 70)])
+def test_trsm_parity(la, orc, dtype, lower, trans, rightside, n, m):
+    batch = 3
+    T = tri(n + m, batch, n, lower, dtype)
+    other = np.triu_indices(n, 1) if lower else np.tril_indices(n, -1)
+    Tj = T.copy()
+    Tj[:, other[0], other[1]] = np.nan  # never read
+    rng = np.random.default_rng(n * m)
+    A = rng.standard_normal((batch, m, n) if rightside else (batch, n, m)).astype(npdt(dtype))
+    alpha = 0.5 if (n + m) % 2 else 1.0
+    ref = orc.trsm(T, A, lower=lower, trans=trans, rightside=rightside, alpha=alpha)
+    out = host(la.trsm(dev(Tj), dev(A), lower=lower, trans=trans, rightside=rightside, alpha=alpha))
+    assert relerr(out, ref) <= TOL[dtype]
+    a = dev(A)
+    out2 = host(la.trsm(dev(Tj), a, lower=lower, trans=trans, rightside=rightside, alpha=alpha, out=a))  # in place
+    assert np.array_equal(out, out2)
+
+
+@pytest.mark.parametrize("dtype", ["f64", "f32"])
+@pytest.mark.parametrize("lower,trans,rightside", FLAGS)
+@pytest.mark.parametrize("n,m", [(1, 2), (6, 3), (64, 5), (70, 64), (150, 150), (260, 9)])
+def test_trmm_parity(la, orc, dtype, lower, trans, rightside, n, m):
+    batch = 3
+    T = tri(n + 2 * m, batch, n, lower, dtype)
+    other = np.triu_indices(n, 1) if lower else np.tril_indices(n, -1)
+    Tj = T.copy()
+    Tj[:, other[0], other[1]] = np.nan
+    rng = np.random.default_rng(n * m + 1)
+    A = rng.standard_normal((batch, m, n) if rightside else (batch, n, m)).astype(npdt(dtype))
+    alpha = -2.0 if (n + m) % 2 else 1.0
+    ref = orc.trmm(T, A, lower=lower, trans=trans, rightside=rightside, alpha=alpha)
+    out = host(la.trmm(dev(Tj), dev(A), lower=lower, trans=trans, rightside=rightside, alpha=alpha))
+    assert relerr(out, ref) <= TOL[dtype]
+    a = dev(A)
+    out2 = host(la.trmm(dev(Tj), a, lower=lower, trans=trans, rightside=rightside, alpha=alpha, out=a))
+    assert np.array_equal(out, out2)
+
+
+# ----------------------------------------------------------------------------
+# syrk / sumlogdiag / GP glue
+# ----------------------------------------------------------------------------
+@pytest.mark.parametrize("dtype", ["f64", "f32"])
+@pytest.mark.parametrize("trans", [False, True])
+@pytest.mark.parametrize("n,k", [(1, 1), (4, 9), (16, 32), (32, 64), (65, 17), (130, 200), (64, 0)])
+def test_syrk_parity(la, orc, dtype, trans, n, k):
+    batch = 3
+    rng = np.random.default_rng(n + k)
+    A = rng.standard_normal((batch, k, n) if trans else (batch, n, k)).astype(npdt(dtype))
+    ref = orc.syrk(A, trans=trans, alpha=0.25)
+    out = host(la.syrk(dev(A), trans=trans, alpha=0.25))
+    assert np.array_equal(out, out.transpose(0, 2, 1))
+    if k == 0:
+        assert np.all(out == 0)
+    else:
+        assert relerr(out, ref) <= TOL[dtype]
+
+
+@pytest.mark.parametrize("dtype", ["f64", "f32"])
+@pytest.mark.parametrize("n", [1, 16, 32, 100, 1000])
+def test_sumlogdiag_parity(la, orc, dtype, n):
+    batch = 9
+    T = tri(n, batch, n, True, dtype)
+    ref = orc.sumlogdiag(T)
+    out = host(la.sumlogdiag(dev(T))).astype(np.float64)
+    assert np.max(np.abs(out - ref) / np.maximum(np.abs(ref), 1.0)) <= TOL[dtype]
+
+
+@pytest.mark.parametrize("dtype", ["f64", "f32"])
+@pytest.mark.parametrize("n", [3, 32, 128, 150])
+def test_gp_glue_parity(la, orc, dtype, n):
+    batch = 4
+    T = tri(n + 5, batch, n, True, dtype)
+    rng = np.random.default_rng(n)
+    y, z, a = (rng.standard_normal((batch, n)).astype(npdt(dtype)) for _ in range(3))
+    ref_loss, ref_G = orc.gp_glue(T, y, z, a)
+    loss, G = la.gp_glue(dev(T), dev(y), dev(z), dev(a))
+    loss, G = host(loss).astype(np.float64), host(G)
+    assert np.all(np.triu(G, 1) == 0.0)
+    assert relerr(G, ref_G) <= TOL[dtype]
+    assert np.max(np.abs(loss - ref_loss) / np.maximum(np.abs(ref_loss), 1.0)) <= TOL[dtype]
