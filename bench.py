@@ -1,0 +1,244 @@
+#!/usr/bin/env python3
+"""Throughput benchmark of the batched Cholesky hot path on one MI355X.
+
+Default workload (the one the headline metric is quoted on): 65536 SPD matrices of
+size 16 in fp32, potrf forward + potrf backward per step ("C2").  Other configurations
+can be timed with --config C1|C3|C4|C5 (C5 also with --dtype f32).
+
+One JSON line is printed on stdout; progress goes to stderr.
+
+Timed region 1 (headline): W warm-up steps, then exactly K steps between
+torch.cuda.synchronize() calls, wall clock.  Inputs are resident in HBM before it starts.
+Steps rotate over several distinct buffer sets so that the 256 MB Infinity Cache cannot
+serve repeats of the HBM-bound configurations.
+Timed region 2 (roofline): the same K steps again with a HIP event pair around every
+library call, on the stream the kernels run on, which gives the average duration of each
+entry point's launch(es).
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+PEAK_TFLOPS = {"f64": 78.6, "f32": 157.3}
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def flops_model(name, n, m):
+    """Useful flops per matrix: potrf n^3/3, backward 2 n^3, trsm/trmm n^2 m each."""
+    f = {"potrf": n ** 3 / 3.0, "backward": 2.0 * n ** 3}
+    if name == "C1":
+        f["trsm"] = float(n * n * m)
+        f["sumlogdiag"] = float(n)
+    elif name == "C3":
+        f["trsm"] = 2.0 * n * n
+        f["sumlogdiag"] = float(n)
+    elif name == "C4":
+        f["trsm"] = float(n * n * m)
+        f["trmm"] = float(n * n * m)
+    elif name == "C5":
+        f["trsm"] = float(n * n * m)
+    return f
+
+
+def bytes_model(n, s):
+    """Algorithmic HBM bytes per matrix: triangular inputs count n(n+1)/2, outputs are full squares."""
+    tri = n * (n + 1) // 2
+    return {"potrf": (tri + n * n) * s, "backward": (2 * tri + n * n) * s}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=None)
+    ap.add_argument("--warmup", type=int, default=None)
+    ap.add_argument("--config", default="C2", choices=["C1", "C2", "C3", "C4", "C5"])
+    ap.add_argument("--dtype", default=None, choices=["f32", "f64"])
+    ap.add_argument("--batch", type=int, default=None)
+    ap.add_argument("--n", type=int, default=None)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        log("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1")
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    import paper_1710_08717_amd as la
+    import workloads
+
+    la.load()  # raises if the HIP library is missing
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+
+    name = args.config
+    w = workloads.make(name, batch=args.batch, n=args.n, dtype=args.dtype)
+    batch, n, dtype, m = w["batch"], w["n"], w["dtype"], w["m"]
+    s = 4 if dtype == "f32" else 8
+    steps = args.steps if args.steps is not None else {"C1": 200, "C2": 200, "C3": 100, "C4": 20, "C5": 3}[name]
+    warmup = args.warmup if args.warmup is not None else {"C1": 20, "C2": 20, "C3": 10, "C4": 3, "C5": 1}[name]
+    log(f"[bench] {name}: batch={batch} n={n} dtype={dtype} m={m} steps={steps} warmup={warmup}")
+
+    # ---- resident inputs, several rotating buffer sets -----------------------------
+    set_bytes = 4 * batch * n * n * s
+    nsets = int(max(1, min(8, (1 << 31) // max(set_bytes, 1)))) if name != "C5" else 1
+    A0 = torch.from_numpy(w["A"]).cuda()
+    G0 = torch.from_numpy(w["Lbar"]).cuda()
+    sets = []
+    for i in range(nsets):
+        d = {"A": A0.clone() if i else A0, "G": G0.clone() if i else G0,
+             "L": torch.empty_like(A0), "Abar": torch.empty_like(A0)}
+        if "rhs" in w:
+            d["rhs"] = torch.from_numpy(w["rhs"]).cuda()
+            d["X"] = torch.empty_like(d["rhs"])
+            d["Y"] = torch.empty_like(d["rhs"])
+        if name == "C3":
+            d["y"] = torch.from_numpy(w["y"]).cuda().contiguous()
+            d["z"] = torch.empty_like(d["y"])
+            d["alpha"] = torch.empty_like(d["y"])
+            d["loss"] = torch.empty(batch, dtype=A0.dtype, device="cuda")
+        if name == "C1":
+            d["sld"] = torch.empty(batch, dtype=A0.dtype, device="cuda")
+        sets.append(d)
+    torch.cuda.synchronize()
+
+    timers = {}
+
+    def call(tag, fn, timed):
+        if not timed:
+            fn()
+            return
+        e0 = torch.cuda.Event(enable_timing=True)
+        e1 = torch.cuda.Event(enable_timing=True)
+        e0.record()
+        fn()
+        e1.record()
+        timers.setdefault(tag, []).append((e0, e1))
+
+    def step(i, timed=False):
+        d = sets[i % nsets]
+        call("potrf", lambda: la.potrf(d["A"], out=d["L"]), timed)
+        if name == "C1":
+            call("trsm", lambda: la.trsm(d["L"], d["rhs"], out=d["X"]), timed)
+            call("sumlogdiag", lambda: la.sumlogdiag(d["L"], out=d["sld"]), timed)
+        elif name == "C3":
+            yv, zv, av = d["y"].view(batch, n, 1), d["z"].view(batch, n, 1), d["alpha"].view(batch, n, 1)
+            call("trsm", lambda: (la.trsm(d["L"], yv, out=zv), la.trsm(d["L"], zv, trans=True, out=av)), timed)
+            call("gp_glue", lambda: la.gp_glue(d["L"], d["y"], d["z"], d["alpha"], loss=d["loss"], Lbar=d["G"]), timed)
+        elif name == "C4":
+            call("trsm", lambda: la.trsm(d["L"], d["rhs"], out=d["X"]), timed)
+            call("trmm", lambda: la.trmm(d["L"], d["X"], out=d["Y"]), timed)
+        elif name == "C5":
+            call("trsm", lambda: la.trsm(d["L"], d["rhs"], out=d["X"]), timed)
+        call("backward", lambda: la.potrf_backward(d["L"], d["G"], out=d["Abar"]), timed)
+
+    for i in range(warmup):
+        step(i)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(steps):
+        step(i)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    ms_per_step = wall * 1e3 / steps
+    log(f"[bench] region 1: {ms_per_step:.4f} ms/step")
+
+    for i in range(steps):
+        step(i, timed=True)
+    torch.cuda.synchronize()
+    kern_ms = {k: float(np.mean([a.elapsed_time(b) for a, b in v])) for k, v in timers.items()}
+    log(f"[bench] region 2 (per entry point, ms): {kern_ms}")
+
+    fm = flops_model(name, n, m)
+    total_flops = batch * sum(fm.values())
+    mats_per_s = batch / (ms_per_step * 1e-3)
+    gflops = total_flops / (ms_per_step * 1e-3) / 1e9
+
+    # ---- roofline of the dominant kernel -------------------------------------------
+    if name in ("C1", "C2", "C3"):
+        bm = bytes_model(n, s)
+        dom = "backward"
+        alg_bytes = bm[dom] * batch
+        achieved = alg_bytes / (kern_ms[dom] * 1e-3) / 1e9
+        roof = {"bound": "hbm", "kernel": "la_potrf_backward", "achieved": achieved, "peak": HBM_PEAK_GBS,
+                "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                "algorithmic_bytes_per_launch": alg_bytes, "avg_launch_ms": kern_ms[dom],
+                "potrf_forward": {"achieved": bm["potrf"] * batch / (kern_ms["potrf"] * 1e-3) / 1e9,
+                                  "avg_launch_ms": kern_ms["potrf"]}}
+        tf = os.path.join(ROOT, "profiles", f"traffic_{name.lower()}.json")
+        if os.path.exists(tf):
+            with open(tf) as f:
+                roof["traffic"] = json.load(f).get("backward_bytes_per_launch")
+    else:
+        dom = "backward"
+        fl = fm[dom] * batch
+        achieved = fl / (kern_ms[dom] * 1e-3) / 1e12
+        roof = {"bound": "mfma", "kernel": "la_potrf_backward (GEMM phases)", "achieved": achieved,
+                "peak": PEAK_TFLOPS[dtype], "unit": "TFLOP/s", "frac": achieved / PEAK_TFLOPS[dtype], "traffic": None,
+                "useful_flops_per_call": fl, "avg_call_ms": kern_ms[dom],
+                "whole_step_frac": gflops / 1e3 / PEAK_TFLOPS[dtype]}
+
+    # ---- CPU baseline: the oracle, as it stands, on this machine's host cores ------------
+    cpu = None
+    if not args.no_cpu_baseline:
+        import oracle
+
+        sb = batch
+        # bounded sample: shrink the batch until a pass is a few seconds of CPU work
+        est = sb * (n ** 3) * 2.0  # rough oracle flops (fwd + composite backward)
+        while sb > 1 and est > 6e10:
+            sb //= 2
+            est /= 2
+        if name == "C5":
+            cpu = {"value": None, "unit": "matrices/s", "cores": oracle.num_threads(), "kind": "oracle",
+                   "sample": "not timed for C5 in the default run (a single n=8192 pass takes minutes)"}
+        else:
+            As, Gs = w["A"][:sb], w["Lbar"][:sb]
+            t0 = time.perf_counter()
+            Lr = oracle.potrf(As)
+            oracle.potrf_backward(Lr, Gs)
+            if "rhs" in w:
+                X = oracle.trsm(Lr, w["rhs"][:sb])
+                if name == "C4":
+                    oracle.trmm(Lr, X)
+            dt_cpu = time.perf_counter() - t0
+            cpu = {"value": sb / dt_cpu, "unit": "matrices/s", "cores": oracle.num_threads(), "kind": "oracle",
+                   "sample": f"first {sb} of {batch} matrices of {name}, one pass of the same ops, {dt_cpu:.2f} s",
+                   "gflops": sb * sum(fm.values()) / dt_cpu / 1e9}
+        log(f"[bench] cpu baseline: {cpu}")
+
+    out = {
+        "metric": "batched potrf fwd+bwd matrices/s",
+        "value": mats_per_s,
+        "unit": "matrices/s",
+        "n_gpus": 1,
+        "steps": steps,
+        "warmup": warmup,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": dtype,
+        "data": "synthetic",
+        "config": {"workload": f"{name}: batch={batch} n={n} {dtype}" + (f" rhs={m}" if m else ""),
+                   "ops": list(fm.keys()) + (["gp_glue"] if name == "C3" else []), "buffer_sets": nsets},
+        "gflops": gflops,
+        "useful_flops_per_step": total_flops,
+        "kernel_ms": kern_ms,
+        "roofline": roof,
+        "cpu_baseline": cpu,
+    }
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

@@ -49,8 +49,14 @@ def _load():
         lib.orc_ltxl_entry.restype = f64
         lib.orc_ltlbar_entry.argtypes = [i32, dp, dp, i32, i32]
         lib.orc_ltlbar_entry.restype = f64
+        lib.orc_num_threads.restype = i32
         _lib = lib
     return _lib
+
+
+def num_threads():
+    """Threads the OpenMP loops of the oracle use (what a timing of it ran on)."""
+    return int(_load().orc_num_threads())
 
 
 def _p(a):

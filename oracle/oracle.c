@@ -25,6 +25,10 @@
 #include <stdlib.h>
 #include <string.h>
 
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
 #define ORC_OK 0
 #define ORC_ERR_INVALID_ARG 1
 
@@ -561,4 +565,14 @@ double orc_ltlbar_entry(int n, const double *L, const double *Lbar, int i, int j
     for (int k = k0; k < n; ++k)
         s += L[(size_t)k * n + i] * Lbar[(size_t)k * n + j];
     return s;
+}
+
+/* Number of threads the batch loops above will use. */
+int orc_num_threads(void)
+{
+#ifdef _OPENMP
+    return omp_get_max_threads();
+#else
+    return 1;
+#endif
 }

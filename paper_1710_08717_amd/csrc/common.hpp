@@ -5,6 +5,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <type_traits>
+
 #include "la.h"
 
 namespace la {
@@ -113,6 +115,75 @@ __device__ __forceinline__ double group_bcast(double x, int k)
     int hi = group_bcast_i<G>((int)(v >> 32), k);
     long long r = ((long long)hi << 32) | (unsigned int)lo;
     return __builtin_bit_cast(double, r);
+}
+
+// acc <- acc + other * (value of src in lane k of the group)   (neg: minus instead of plus)
+//
+// fp32 with 16-lane groups is the throughput-critical case: there the multiply-add and the
+// broadcast are ONE instruction, v_fmac_f32 with a DPP row_newbcast source operand.  The
+// compiler only forms that for plain multiplies, so it is written out.  The hardware needs
+// two wait states between a VALU write of a register and a DPP read of it and nothing
+// checks that inside inline asm: callers keep the broadcast source untouched for at least
+// two instructions before the call (see dpp_settle()).
+template <int K>
+__device__ __forceinline__ void fmac_dpp16(float &acc, float src, float other)
+{
+    asm volatile("v_fmac_f32_dpp %0, %1, %2 row_newbcast:%3 row_mask:0xf bank_mask:0xf"
+                 : "+v"(acc)
+                 : "v"(src), "v"(other), "n"(K));
+}
+template <int K>
+__device__ __forceinline__ void fnmac_dpp16(float &acc, float src, float other)
+{
+    asm volatile("v_fmac_f32_dpp %0, -%1, %2 row_newbcast:%3 row_mask:0xf bank_mask:0xf"
+                 : "+v"(acc)
+                 : "v"(src), "v"(other), "n"(K));
+}
+
+template <int G, int K, typename T>
+__device__ __forceinline__ void fma_bcast(T &acc, T src, T other, bool neg)
+{
+    if constexpr (G == 16 && sizeof(T) == 4) {
+        if (neg)
+            fnmac_dpp16<K>(acc, src, other);
+        else
+            fmac_dpp16<K>(acc, src, other);
+    } else {
+        const T b = group_bcast<G>(src, K);
+        acc = fma(neg ? -other : other, b, acc);
+    }
+}
+
+// Compile-time loop: f(std::integral_constant<int, I>) for I = B .. E-1, so that lane numbers
+// reach the DPP / readlane encodings as constants without relying on the unroller.
+template <int B, int E, class F>
+__device__ __forceinline__ void static_for(F &&f)
+{
+    if constexpr (B < E) {
+        f(std::integral_constant<int, B>{});
+        static_for<B + 1, E>(f);
+    }
+}
+
+// Makes every register of v[] "settled" for a following DPP read: two wait states, and the
+// values are routed through the statement so that nothing that computes them can be moved
+// after it.
+template <int G, typename T, int N>
+__device__ __forceinline__ void dpp_settle(T (&v)[N])
+{
+    if constexpr (G == 16 && sizeof(T) == 4) {
+#pragma unroll
+        for (int i = 0; i < N; ++i)
+            asm volatile("" : "+v"(v[i]));
+        asm volatile("s_nop 1");
+    }
+}
+template <int G, typename T>
+__device__ __forceinline__ void dpp_settle1(T &v)
+{
+    if constexpr (G == 16 && sizeof(T) == 4) {
+        asm volatile("s_nop 1" : "+v"(v));
+    }
 }
 
 // Reciprocal square root and reciprocal accurate to a few ulp of T.

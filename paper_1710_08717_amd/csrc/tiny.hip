@@ -217,17 +217,19 @@ __global__ __launch_bounds__(WAVE) void k_potrf_tiny(View<const T> A, View<T> L,
             a[k] = T(0);  // the other triangle of A is never used
 
     int fail = 0;
-#pragma unroll
-    for (int j = 0; j < G; ++j) {
+    static_for<0, G>([&](auto J) {
+        constexpr int j = decltype(J)::value;
         T piv = group_bcast<G>(a[j], j);  // a_jj after the updates of columns < j
         if (!(piv > T(0)) && fail == 0)
             fail = j + 1;
         T r = rsqrt_acc(piv);
         a[j] = (i >= j) ? a[j] * r : T(0);  // column j of L (lane j gets sqrt(piv))
-#pragma unroll
-        for (int k = j + 1; k < G; ++k)
-            a[k] = fma(-a[j], group_bcast<G>(a[j], k), a[k]);  // a_ik -= l_ij l_kj
-    }
+        dpp_settle1<G>(a[j]);
+        static_for<j + 1, G>([&](auto K) {
+            constexpr int k = decltype(K)::value;
+            fma_bcast<G, k>(a[k], a[j], a[j], true);  // a_ik -= l_ij l_kj
+        });
+    });
 #pragma unroll
     for (int k = 0; k < G; ++k)
         if (k > i)
@@ -293,12 +295,14 @@ __global__ __launch_bounds__(WAVE) void k_backward_tiny(View<const T> Lv, View<c
 #pragma unroll
     for (int j = 0; j < G; ++j)
         y[j] = T(0);
-#pragma unroll
-    for (int k = 0; k < G; ++k) {
-#pragma unroll
-        for (int j = 0; j <= k; ++j)
-            y[j] = fma(lc[k], group_bcast<G>(g[j], k), y[j]);
-    }
+    dpp_settle<G>(g);
+    static_for<0, G>([&](auto K) {
+        constexpr int k = decltype(K)::value;
+        static_for<0, k + 1>([&](auto J) {
+            constexpr int j = decltype(J)::value;
+            fma_bcast<G, k>(y[j], g[j], lc[k], false);
+        });
+    });
     // Phi, then the row scaling D^-1 of L = Lt D (Lt unit lower triangular)
 #pragma unroll
     for (int j = 0; j < G; ++j) {
@@ -311,22 +315,26 @@ __global__ __launch_bounds__(WAVE) void k_backward_tiny(View<const T> Lv, View<c
         lc[k] = (k > i) ? lc[k] * rd : T(0);
 
     // Y = Lt^-T (D^-1 Phi): rows from the bottom; row k is final when it is broadcast
-#pragma unroll
-    for (int k = G - 1; k >= 1; --k) {
-#pragma unroll
-        for (int c = 0; c < G; ++c)
-            y[c] = fma(-lc[k], group_bcast<G>(y[c], k), y[c]);
-    }
+    dpp_settle<G>(y);
+    static_for<0, G - 1>([&](auto Tt) {
+        constexpr int k = G - 1 - decltype(Tt)::value;
+        static_for<0, G>([&](auto C) {
+            constexpr int c = decltype(C)::value;
+            fma_bcast<G, k>(y[c], y[c], lc[k], true);  // G instructions lie between two touches of y[c]
+        });
+    });
     // V = Y D^-1 (column c scaled by 1 / l_cc), then W = V Lt^-1 from the last column back
 #pragma unroll
     for (int c = 0; c < G; ++c)
         y[c] *= group_bcast<G>(rd, c);
-#pragma unroll
-    for (int c = G - 2; c >= 0; --c) {
-#pragma unroll
-        for (int k = c + 1; k < G; ++k)
-            y[c] = fma(-y[k], group_bcast<G>(lc[k], c), y[c]);
-    }
+    dpp_settle<G>(lc);
+    static_for<0, G - 1>([&](auto Tt) {
+        constexpr int c = G - 2 - decltype(Tt)::value;
+        static_for<c + 1, G>([&](auto K) {
+            constexpr int k = decltype(K)::value;
+            fma_bcast<G, c>(y[c], lc[k], y[k], true);
+        });
+    });
 
     // Abar = 1/2 (W + W^T): rows out to LDS, columns back in
     __syncthreads();
