@@ -26,10 +26,9 @@
  *  - Return value: LA_OK, or LA_ERR_INVALID_ARG (null pointer with non-empty
  *    work, negative size, bad enum, forbidden aliasing), LA_ERR_UNSUPPORTED,
  *    LA_ERR_RUNTIME (a HIP call failed; see la_last_error()).
- *  - Workspace: blocked paths (n > 64) keep small device scratch buffers that the
- *    library allocates itself on first use (per device, grown on demand, kept
- *    until process exit).  Calls that use it must not overlap on different
- *    streams of one device.  Paths for n <= 64 use none.
+ *  - The library allocates no memory and keeps no state between calls (the paper's
+ *    "no extra memory" notes hold for every operator here); calls on different
+ *    streams are independent.
  */
 #ifndef LA_MI355X_H
 #define LA_MI355X_H
