@@ -9,9 +9,13 @@
 // upper/lower variants never copy.  Triangular operands are masked while they are staged
 // in LDS and their structurally-zero K range is skipped.
 //
-// Tiling: a 256-thread workgroup owns a BM x BN tile of C, four wavefronts in a 2 x 2
-// arrangement, each accumulating (BM/2) x (BN/2) with 16x16x4 MFMA tiles
-// (v_mfma_f64_16x16x4_f64 / v_mfma_f32_16x16x4_f32).  K advances in slabs of BK staged in LDS.
+// Two kernels:
+//  * k_gemm_fast: 16-byte vector loads, register prefetch of the next K slab while the
+//    current one is multiplied out of a double-buffered LDS stage (one barrier per slab),
+//    128x128 or 64x64 workgroup tiles, four wavefronts in a 2 x 2 arrangement, 16x16x4 MFMA
+//    (v_mfma_f64_16x16x4_f64 / v_mfma_f32_16x16x4_f32).  Needs 16-byte aligned operands and
+//    K a multiple of 16.
+//  * k_gemm: element-wise staged fallback for everything else (ragged / unaligned shapes).
 #include "common.hpp"
 
 namespace la {
@@ -24,6 +28,8 @@ struct Mfma;
 template <>
 struct Mfma<double> {
     using acc_t = d4_t;
+    using vec_t = double2;
+    static constexpr int VW = 2;
     static __device__ __forceinline__ acc_t run(double a, double b, acc_t c)
     {
         return __builtin_amdgcn_mfma_f64_16x16x4f64(a, b, c, 0, 0, 0);
@@ -34,6 +40,8 @@ struct Mfma<double> {
 template <>
 struct Mfma<float> {
     using acc_t = f4_t;
+    using vec_t = float4;
+    static constexpr int VW = 4;
     static __device__ __forceinline__ acc_t run(float a, float b, acc_t c)
     {
         return __builtin_amdgcn_mfma_f32_16x16x4f32(a, b, c, 0, 0, 0);
@@ -41,18 +49,37 @@ struct Mfma<float> {
     static __device__ __forceinline__ int row(int l, int v) { return 4 * (l >> 4) + v; }
 };
 
+__device__ __forceinline__ bool tri_keep(int tri, int o, int k)
+{
+    // tri 1 keeps o >= k, tri 2 keeps o <= k
+    return tri == 0 || (tri == 1 ? (o >= k) : (o <= k));
+}
+
+// ---------------------------------------------------------------------------------------
+// Workgroup -> (batch item, tile) mapping shared by both kernels.  Consecutive workgroups are
+// dealt round-robin to the 8 XCDs (each with its own L2), so the 8 workgroups of one "round"
+// are given the same batch item and neighbouring tiles only after a regrouping: workgroup w
+// works on logical slot (w % 8) * (total / 8) + w / 8, which keeps each XCD on a contiguous
+// range of tiles (shared A / B panels stay in that XCD's L2).
+// ---------------------------------------------------------------------------------------
+__device__ __forceinline__ int64_t xcd_slot(int64_t w, int64_t total)
+{
+    const int64_t per = total / 8;
+    if (per == 0 || w >= per * 8)
+        return w;  // tail (and tiny grids) keep their order
+    return (w % 8) * per + (w / 8);
+}
+
+// ---------------------------------------------------------------------------------------
+// Fallback kernel: element-wise staging, any strides / sizes.
+// ---------------------------------------------------------------------------------------
 template <int BM, int BN, int BK>
 struct GemmCfg {
-    static constexpr int THREADS = 256;
     static constexpr int PAD = 16;
-    // an operand slab is kept either "outer-fast" ([k][outer + PAD]) or "k-fast" ([outer][BK + 1]),
-    // whichever matches the contiguous direction of its global memory
     static constexpr int A_ELEMS = (BK * (BM + PAD) > BM * (BK + 1)) ? BK * (BM + PAD) : BM * (BK + 1);
     static constexpr int B_ELEMS = (BK * (BN + PAD) > BN * (BK + 1)) ? BK * (BN + PAD) : BN * (BK + 1);
 };
 
-// Stage a (OUT x BK) slab: element (o, k) of the operand is src[o*so + k*sk] for o < no, k in
-// [k0, k0+BK) & k < kmax; tri: 1 keeps o_glob >= k, 2 keeps o_glob <= k (o_glob = o0 + o), else zero.
 template <typename T, int OUT, int BK, int PAD>
 __device__ __forceinline__ void stage_slab(T *s, const T *src, int64_t so, int64_t sk, int o0, int no, int k0,
                                            int kmax, int tri, bool kfast)
@@ -72,14 +99,36 @@ __device__ __forceinline__ void stage_slab(T *s, const T *src, int64_t so, int64
         }
         const int og = o0 + o, kg = k0 + k;
         T v = T(0);
-        bool ok = (og < no) && (kg < kmax);
-        if (tri == 1)
-            ok = ok && (og >= kg);
-        else if (tri == 2)
-            ok = ok && (og <= kg);
-        if (ok)
+        if ((og < no) && (kg < kmax) && tri_keep(tri, og, kg))
             v = src[(int64_t)og * so + (int64_t)kg * sk];
         s[kfast ? (o * (BK + 1) + k) : (k * (OUT + PAD) + o)] = v;
+    }
+}
+
+__device__ __forceinline__ void k_range(const GemmOpts &o, int i0, int j0, int BM, int BN, int K, int &kbeg, int &kend)
+{
+    kbeg = 0;
+    kend = K;
+    if (o.triA == 1)
+        kend = min(kend, i0 + BM);
+    else if (o.triA == 2)
+        kbeg = max(kbeg, i0);
+    if (o.triB == 1)
+        kbeg = max(kbeg, j0);
+    else if (o.triB == 2)
+        kend = min(kend, j0 + BN);
+}
+
+template <typename T>
+__device__ __forceinline__ void store_c(T *Cp, int64_t rs, int64_t cs, int i, int j, int M, int N, T acc, T alpha,
+                                        T beta, const GemmOpts &o)
+{
+    if (i < M && j < N && !(o.maskC == 1 && i < j) && !(o.maskC == 2 && i > j)) {
+        T upd = alpha * acc;
+        if (o.halfDiag && i == j)
+            upd *= T(0.5);
+        T *c = Cp + (int64_t)i * rs + (int64_t)j * cs;
+        *c = (beta == T(0)) ? upd : fma(beta, *c, upd);
     }
 }
 
@@ -91,7 +140,7 @@ __global__ __launch_bounds__(256) void k_gemm(View<const T> A, View<const T> B, 
     using MF = Mfma<T>;
     using acc_t = typename MF::acc_t;
     constexpr int PAD = Cfg::PAD;
-    constexpr int WM = BM / 2, WN = BN / 2;  // wave tile
+    constexpr int WM = BM / 2, WN = BN / 2;
     constexpr int TM = WM / 16, TN = WN / 16;
     __shared__ T sA[Cfg::A_ELEMS];
     __shared__ T sB[Cfg::B_ELEMS];
@@ -102,25 +151,18 @@ __global__ __launch_bounds__(256) void k_gemm(View<const T> A, View<const T> B, 
     const int tile = (int)(bid % per);
     const int tm = tile / tiles_n, tn = tile % tiles_n;
     const int i0 = tm * BM, j0 = tn * BN;
-    if (o.maskC == 1 && j0 > i0 + BM - 1)
-        return;  // tile entirely above the diagonal
+    if ((o.maskC == 1 && j0 > i0 + BM - 1) || (o.maskC == 2 && i0 > j0 + BN - 1))
+        return;  // tile entirely on the masked side of the diagonal
 
-    int kbeg = 0, kend = K;
-    if (o.triA == 1)
-        kend = min(kend, i0 + BM);
-    else if (o.triA == 2)
-        kbeg = max(kbeg, i0);
-    if (o.triB == 1)
-        kbeg = max(kbeg, j0);
-    else if (o.triB == 2)
-        kend = min(kend, j0 + BN);
+    int kbeg, kend;
+    k_range(o, i0, j0, BM, BN, K, kbeg, kend);
     kbeg = (kbeg / BK) * BK;
 
     const T *Ap = A.p + b * A.bs;
     const T *Bp = B.p + b * B.bs;
     T *Cp = C.p + b * C.bs;
-    const bool a_kfast = (A.cs == 1);  // A(i,k): k contiguous
-    const bool b_kfast = (B.rs == 1);  // B(k,j): k contiguous
+    const bool a_kfast = (A.cs == 1);
+    const bool b_kfast = (B.rs == 1);
 
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
     const int wm = (w >> 1) * WM, wn = (w & 1) * WN;
@@ -135,12 +177,11 @@ __global__ __launch_bounds__(256) void k_gemm(View<const T> A, View<const T> B, 
 
     const int a_si = a_kfast ? (BK + 1) : 1, a_sk = a_kfast ? 1 : (BM + PAD);
     const int b_sj = b_kfast ? (BK + 1) : 1, b_sk = b_kfast ? 1 : (BN + PAD);
+    const int triB_o = o.triB == 1 ? 2 : (o.triB == 2 ? 1 : 0);  // in (j, k) order
 
     for (int k0 = kbeg; k0 < kend; k0 += BK) {
         stage_slab<T, BM, BK, PAD>(sA, Ap, A.rs, A.cs, i0, M, k0, kend, o.triA, a_kfast);
-        // B(k,j): "outer" index is j; its triangle test compares k against j, so swap the sense
-        stage_slab<T, BN, BK, PAD>(sB, Bp, B.cs, B.rs, j0, N, k0, kend, o.triB == 1 ? 2 : (o.triB == 2 ? 1 : 0),
-                                   b_kfast);
+        stage_slab<T, BN, BK, PAD>(sB, Bp, B.cs, B.rs, j0, N, k0, kend, triB_o, b_kfast);
         __syncthreads();
 #pragma unroll
         for (int kk = 0; kk < BK; kk += 4) {
@@ -165,18 +206,216 @@ __global__ __launch_bounds__(256) void k_gemm(View<const T> A, View<const T> B, 
 #pragma unroll
         for (int y = 0; y < TN; ++y)
 #pragma unroll
-            for (int v = 0; v < 4; ++v) {
-                const int i = i0 + wm + x * 16 + MF::row(lane, v);
-                const int j = j0 + wn + y * 16 + l16;
-                if (i < M && j < N && !(o.maskC == 1 && i < j)) {
-                    T upd = alpha * acc[x][y][v];
-                    if (o.halfDiag && i == j)
-                        upd *= T(0.5);
-                    T *c = Cp + (int64_t)i * C.rs + (int64_t)j * C.cs;
-                    *c = (beta == T(0)) ? upd : fma(beta, *c, upd);
-                }
-            }
+            for (int v = 0; v < 4; ++v)
+                store_c<T>(Cp, C.rs, C.cs, i0 + wm + x * 16 + MF::row(lane, v), j0 + wn + y * 16 + l16, M, N,
+                           acc[x][y][v], alpha, beta, o);
 }
+
+// ---------------------------------------------------------------------------------------
+// Fast kernel.  AKF: A(i,k) has k contiguous (A.cs == 1), else i contiguous (A.rs == 1).
+// BKF: B(k,j) has k contiguous (B.rs == 1), else j contiguous (B.cs == 1).
+// LDS slab layouts (chosen so that global->LDS stores are 16-byte vectors and the MFMA
+// fragment reads are bank-conflict free):
+//   k contiguous:     s[o][BK + VW]      (row stride 18 doubles / 20 floats)
+//   outer contiguous: s[k][OUT + 16]
+// ---------------------------------------------------------------------------------------
+template <typename T, int OUT, int BK, bool KF>
+struct Slab {
+    using MF = Mfma<T>;
+    static constexpr int VW = MF::VW;
+    static constexpr int LD = KF ? (BK + VW) : (OUT + 16);
+    static constexpr int ELEMS = KF ? OUT * LD : BK * LD;
+    static constexpr int NCH = OUT * BK / VW / 256;  // 16-byte chunks per thread
+    static_assert(NCH >= 1, "tile too small for 256 threads");
+    static constexpr int so = KF ? LD : 1;  // LDS stride of the outer index
+    static constexpr int sk = KF ? 1 : LD;  // LDS stride of k
+
+    // (outer, k) of chunk c of this thread
+    static __device__ __forceinline__ void coords(int c, int &o, int &k)
+    {
+        const int q = c * 256 + threadIdx.x;
+        if constexpr (KF) {
+            o = q / (BK / VW);
+            k = (q % (BK / VW)) * VW;
+        } else {
+            k = q / (OUT / VW);
+            o = (q % (OUT / VW)) * VW;
+        }
+    }
+};
+
+template <typename T, int OUT, int BK, bool KF, typename RV>
+__device__ __forceinline__ void slab_fetch(RV &r, const T *src, int64_t so, int64_t sk, int o0, int no, int k0)
+{
+    using S = Slab<T, OUT, BK, KF>;
+    using V = typename Mfma<T>::vec_t;
+#pragma unroll
+    for (int c = 0; c < S::NCH; ++c) {
+        int o, k;
+        S::coords(c, o, k);
+        V v;
+        if constexpr (S::VW == 2)
+            v = V{0, 0};
+        else
+            v = V{0, 0, 0, 0};
+        if (o0 + o < no)  // whole chunk in range: K is a multiple of BK, `no` a multiple of VW when !KF
+            v = *reinterpret_cast<const V *>(src + (int64_t)(o0 + o) * so + (int64_t)(k0 + k) * sk);
+        r[c] = v;
+    }
+}
+
+template <typename T, int OUT, int BK, bool KF, typename RV>
+__device__ __forceinline__ void slab_commit(T *s, RV &r, int o0, int k0, int tri)
+{
+    using S = Slab<T, OUT, BK, KF>;
+    using V = typename Mfma<T>::vec_t;
+    // does this slab touch the zero side of a triangular operand at all?
+    bool need_mask = false;
+    if (tri == 1)
+        need_mask = (o0 < k0 + BK - 1);  // keep o >= k: some (o, k) with o < k exists
+    else if (tri == 2)
+        need_mask = (o0 + OUT - 1 > k0);
+#pragma unroll
+    for (int c = 0; c < S::NCH; ++c) {
+        int o, k;
+        S::coords(c, o, k);
+        V v = r[c];
+        if (need_mask) {
+            T *e = reinterpret_cast<T *>(&v);
+#pragma unroll
+            for (int u = 0; u < S::VW; ++u) {
+                const int og = o0 + o + (KF ? 0 : u), kg = k0 + k + (KF ? u : 0);
+                if (!tri_keep(tri, og, kg))
+                    e[u] = T(0);
+            }
+        }
+        *reinterpret_cast<V *>(s + o * S::so + k * S::sk) = v;
+    }
+}
+
+template <typename T, int BM, int BN, bool AKF, bool BKF>
+__global__ __launch_bounds__(256) void k_gemm_fast(View<const T> A, View<const T> B, View<T> C, int64_t batch, int M,
+                                                   int N, int K, T alpha, T beta, GemmOpts o, int tiles_m, int tiles_n)
+{
+    constexpr int BK = 16;
+    using MF = Mfma<T>;
+    using acc_t = typename MF::acc_t;
+    using V = typename MF::vec_t;
+    using SA = Slab<T, BM, BK, AKF>;
+    using SB = Slab<T, BN, BK, BKF>;
+    constexpr int WM = BM / 2, WN = BN / 2;
+    constexpr int TM = WM / 16, TN = WN / 16;
+    __shared__ __align__(16) T sA[2][SA::ELEMS];
+    __shared__ __align__(16) T sB[2][SB::ELEMS];
+
+    const int64_t per = (int64_t)tiles_m * tiles_n;
+    const int64_t slot = xcd_slot(blockIdx.x, per * batch);
+    const int64_t b = slot / per;
+    const int tile = (int)(slot % per);
+    const int tm = tile / tiles_n, tn = tile % tiles_n;
+    const int i0 = tm * BM, j0 = tn * BN;
+    if ((o.maskC == 1 && j0 > i0 + BM - 1) || (o.maskC == 2 && i0 > j0 + BN - 1))
+        return;
+
+    int kbeg, kend;
+    k_range(o, i0, j0, BM, BN, K, kbeg, kend);
+    kbeg = (kbeg / BK) * BK;
+    kend = ((kend + BK - 1) / BK) * BK;  // K is a multiple of BK, so this stays <= K
+
+    const T *Ap = A.p + b * A.bs;
+    const T *Bp = B.p + b * B.bs;
+    T *Cp = C.p + b * C.bs;
+    const int triB_o = o.triB == 1 ? 2 : (o.triB == 2 ? 1 : 0);
+
+    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+    const int wm = (w >> 1) * WM, wn = (w & 1) * WN;
+    const int l16 = lane & 15, lk = lane >> 4;
+
+    acc_t acc[TM][TN];
+#pragma unroll
+    for (int x = 0; x < TM; ++x)
+#pragma unroll
+        for (int y = 0; y < TN; ++y)
+            acc[x][y] = acc_t{0, 0, 0, 0};
+
+    V ra[SA::NCH], rb[SB::NCH];
+    if (kbeg < kend) {
+        slab_fetch<T, BM, BK, AKF>(ra, Ap, A.rs, A.cs, i0, M, kbeg);
+        slab_fetch<T, BN, BK, BKF>(rb, Bp, B.cs, B.rs, j0, N, kbeg);
+        slab_commit<T, BM, BK, AKF>(sA[0], ra, i0, kbeg, o.triA);
+        slab_commit<T, BN, BK, BKF>(sB[0], rb, j0, kbeg, triB_o);
+    }
+    __syncthreads();
+
+    int buf = 0;
+    for (int k0 = kbeg; k0 < kend; k0 += BK) {
+        const bool more = (k0 + BK < kend);
+        if (more) {
+            slab_fetch<T, BM, BK, AKF>(ra, Ap, A.rs, A.cs, i0, M, k0 + BK);
+            slab_fetch<T, BN, BK, BKF>(rb, Bp, B.cs, B.rs, j0, N, k0 + BK);
+        }
+        const T *a_s = sA[buf], *b_s = sB[buf];
+#pragma unroll
+        for (int kk = 0; kk < BK; kk += 4) {
+            T af[TM], bf[TN];
+#pragma unroll
+            for (int x = 0; x < TM; ++x)
+                af[x] = a_s[(wm + x * 16 + l16) * SA::so + (kk + lk) * SA::sk];
+#pragma unroll
+            for (int y = 0; y < TN; ++y)
+                bf[y] = b_s[(wn + y * 16 + l16) * SB::so + (kk + lk) * SB::sk];
+#pragma unroll
+            for (int x = 0; x < TM; ++x)
+#pragma unroll
+                for (int y = 0; y < TN; ++y)
+                    acc[x][y] = MF::run(af[x], bf[y], acc[x][y]);
+        }
+        if (more) {
+            slab_commit<T, BM, BK, AKF>(sA[buf ^ 1], ra, i0, k0 + BK, o.triA);
+            slab_commit<T, BN, BK, BKF>(sB[buf ^ 1], rb, j0, k0 + BK, triB_o);
+        }
+        __syncthreads();
+        buf ^= 1;
+    }
+
+#pragma unroll
+    for (int x = 0; x < TM; ++x)
+#pragma unroll
+        for (int y = 0; y < TN; ++y)
+#pragma unroll
+            for (int v = 0; v < 4; ++v)
+                store_c<T>(Cp, C.rs, C.cs, i0 + wm + x * 16 + MF::row(lane, v), j0 + wn + y * 16 + l16, M, N,
+                           acc[x][y][v], alpha, beta, o);
+}
+
+template <typename T>
+static bool aligned16(const View<const T> &V, int64_t lead)
+{
+    constexpr int VW = Mfma<T>::VW;
+    return (reinterpret_cast<uintptr_t>(V.p) & 15) == 0 && (lead % VW) == 0 && (V.bs % VW) == 0;
+}
+
+template <typename T, int BM, int BN>
+static void launch_fast(bool akf, bool bkf, View<const T> A, View<const T> B, View<T> C, int64_t batch, int M, int N,
+                        int K, T alpha, T beta, GemmOpts o, hipStream_t st)
+{
+    const int tiles_m = (M + BM - 1) / BM, tiles_n = (N + BN - 1) / BN;
+    const dim3 grid((unsigned)((int64_t)tiles_m * tiles_n * batch)), block(256);
+#define LA_GO(AK, BKF_)                                                                                              \
+    hipLaunchKernelGGL((k_gemm_fast<T, BM, BN, AK, BKF_>), grid, block, 0, st, A, B, C, batch, M, N, K, alpha, beta, \
+                       o, tiles_m, tiles_n)
+    if (akf && bkf)
+        LA_GO(true, true);
+    else if (akf && !bkf)
+        LA_GO(true, false);
+    else if (!akf && bkf)
+        LA_GO(false, true);
+    else
+        LA_GO(false, false);
+#undef LA_GO
+}
+
+static inline int flip_tri(int t) { return t == 1 ? 2 : (t == 2 ? 1 : 0); }
 
 template <typename T>
 la_status launch_gemm(View<const T> A, View<const T> B, View<T> C, int64_t batch, int M, int N, int K, T alpha, T beta,
@@ -184,6 +423,31 @@ la_status launch_gemm(View<const T> A, View<const T> B, View<T> C, int64_t batch
 {
     if (batch <= 0 || M <= 0 || N <= 0)
         return LA_OK;
+    // Keep the stores of C along its contiguous direction: if C is stored with i contiguous,
+    // compute C^T = B^T A^T instead (a pure re-labelling of the views).
+    if (C.cs != 1 && C.rs == 1) {
+        GemmOpts t;
+        t.triA = flip_tri(o.triB);
+        t.triB = flip_tri(o.triA);
+        t.maskC = flip_tri(o.maskC);
+        t.halfDiag = o.halfDiag;
+        return launch_gemm<T>(B.t(), A.t(), C.t(), batch, N, M, K, alpha, beta, t, st);
+    }
+    constexpr int VW = Mfma<T>::VW;
+    const bool akf = (A.cs == 1), bkf = (B.rs == 1);
+    const bool a_ok = akf ? aligned16<T>(A, A.rs) : (A.rs == 1 && aligned16<T>(A, A.cs) && M % VW == 0);
+    const bool b_ok = bkf ? aligned16<T>(B, B.cs) : (B.cs == 1 && aligned16<T>(B, B.rs) && N % VW == 0);
+    if (K > 0 && K % 16 == 0 && a_ok && b_ok) {
+        const int64_t t128 = (int64_t)((M + 127) / 128) * ((N + 127) / 128) * batch;
+        const int64_t t64 = (int64_t)((M + 63) / 64) * ((N + 63) / 64) * batch;
+        if (t64 > 0x7fffffffll)
+            return LA_ERR_UNSUPPORTED;
+        if (t128 >= 192 && M >= 128 && N >= 128)
+            launch_fast<T, 128, 128>(akf, bkf, A, B, C, batch, M, N, K, alpha, beta, o, st);
+        else
+            launch_fast<T, 64, 64>(akf, bkf, A, B, C, batch, M, N, K, alpha, beta, o, st);
+        return launch_check("gemm_fast");
+    }
     constexpr int BM = 64, BN = 64, BK = 16;
     const int tiles_m = (M + BM - 1) / BM, tiles_n = (N + BN - 1) / BN;
     const int64_t blocks = (int64_t)tiles_m * tiles_n * batch;
