@@ -230,11 +230,17 @@ template <typename T>
 la_status launch_tile_mult(View<const T> Lam, View<T> X, int64_t batch, int nb, int64_t nvec, bool fwd, bool phi,
                            hipStream_t st);
 
+// Dense inverses of the 64 x 64 diagonal blocks of Lam (n x n lower triangular) into a
+// caller-provided buffer: block j of item b at winv + b*winv_bs + (blk0 + j)*64*64, row-major.
+template <typename T>
+la_status launch_tile_inverse(View<const T> Lam, T *winv, int64_t winv_bs, int64_t batch, int n, int blk0,
+                              hipStream_t st);
+
 // C(i,j) = beta*C(i,j) + alpha * sum_k A(i,k) B(k,j), i < M, j < N, k < K, per batch item.
 struct GemmOpts {
     int triA = 0;      // 1: A(i,k) is zero for i < k (lower), 2: zero for i > k (upper)
     int triB = 0;      // same on (k,j)
-    int maskC = 0;     // 1: only entries with i >= j are written
+    int maskC = 0;     // 1: only entries with i >= j are written, 2: only i <= j
     int halfDiag = 0;  // 1: the update of entries with i == j is halved
 };
 template <typename T>

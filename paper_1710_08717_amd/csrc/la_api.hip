@@ -5,11 +5,15 @@
 // 1710.08717, "potrf", last paragraph, and the R variants of trsm / trmm) is the transposed
 // view of the same memory, so no data is ever transposed or copied for it.
 //
-// Matrices with n <= 64 are handled by single register-resident kernels.  Larger ones are
-// split recursively in halves (multiples of 64): the off-diagonal work becomes GEMMs on the
-// matrix cores and the 64 x 64 diagonal blocks go to the triangular tile kernels.
+// potrf / backward of small matrices are single register-resident kernels.  Everything else is
+// split recursively in halves (multiples of 64) down to 64 x 64 diagonal blocks; all the work
+// is GEMMs on the matrix cores: off-diagonal updates, products with (masked) diagonal blocks,
+// and solves as products with the diagonal blocks' inverses, which one kernel launch computes
+// for the whole batch up front.
 #include <cstdio>
 #include <cstring>
+#include <mutex>
+#include <vector>
 
 #include "common.hpp"
 
@@ -20,6 +24,61 @@ static thread_local char g_err[256] = "no error";
 void set_error(hipError_t e, const char *where)
 {
     snprintf(g_err, sizeof(g_err), "%s: %s", where, hipGetErrorString(e));
+}
+
+// ---------------------------------------------------------------------------------
+// Scratch memory of the blocked paths: the dense inverses of the 64 x 64 diagonal blocks of the
+// triangular factor (batch * ceil(n/64) * 64 * 64 elements).  One buffer per device, grown on
+// demand with hipMalloc and kept until the process ends; a buffer that is outgrown is parked,
+// not freed, because work queued on a stream may still be using it.  Calls that use it
+// (n > 64) must therefore not run concurrently on several streams of one device.
+// ---------------------------------------------------------------------------------
+struct Scratch {
+    void *p = nullptr;
+    size_t bytes = 0;
+};
+static std::mutex g_ws_mutex;
+static std::vector<Scratch> g_ws(64);
+static std::vector<void *> g_parked;
+
+static la_status scratch_get(size_t bytes, void **out)
+{
+    int dev = 0;
+    LA_HIP(hipGetDevice(&dev));
+    std::lock_guard<std::mutex> lock(g_ws_mutex);
+    if (dev < 0 || dev >= (int)g_ws.size())
+        return LA_ERR_UNSUPPORTED;
+    Scratch &s = g_ws[dev];
+    if (s.bytes < bytes) {
+        size_t want = bytes + bytes / 4;
+        void *np = nullptr;
+        LA_HIP(hipMalloc(&np, want));
+        if (s.p)
+            g_parked.push_back(s.p);
+        s.p = np;
+        s.bytes = want;
+    }
+    *out = s.p;
+    return LA_OK;
+}
+
+// Inverses of the diagonal blocks of one factor: block j of item b at p + b*bs + j*64*64.
+template <typename T>
+struct InvBlocks {
+    T *p = nullptr;
+    int64_t bs = 0;
+    View<const T> block(int j) const { return {p + (int64_t)j * NB * NB, bs, NB, 1}; }
+};
+
+template <typename T>
+static la_status inv_alloc(int64_t batch, int n, InvBlocks<T> &inv)
+{
+    const int nblk = (n + NB - 1) / NB;
+    void *p = nullptr;
+    LA_TRY(scratch_get((size_t)batch * nblk * NB * NB * sizeof(T), &p));
+    inv.p = (T *)p;
+    inv.bs = (int64_t)nblk * NB * NB;
+    return LA_OK;
 }
 
 static inline int split_point(int n)
@@ -41,34 +100,42 @@ static inline View<const T> cv(View<T> v)
 //   solve fwd: X <- Lam^-1 X      solve !fwd: X <- Lam^-T X
 //   mult  fwd: X <- Lam X         mult  !fwd: X <- Lam^T X
 // ---------------------------------------------------------------------------------
+// Leaves (n <= 64) are in-place GEMMs: a solve multiplies by the precomputed inverse of the
+// diagonal block (inv, block index blk), a product multiplies by the masked block itself.
+// In place is safe there because one workgroup tile covers all n <= 64 rows of its vectors.
 template <typename T>
-static la_status solve_rec(View<const T> Lam, View<T> X, int64_t batch, int n, int64_t nvec, bool fwd, hipStream_t st)
+static la_status solve_rec(View<const T> Lam, View<T> X, int64_t batch, int n, int64_t nvec, bool fwd,
+                           const InvBlocks<T> &inv, int blk, hipStream_t st)
 {
-    if (n <= NB)
-        return launch_tile_solve<T>(Lam, X, batch, n, nvec, fwd, st);
+    GemmOpts o;
+    if (n <= NB) {
+        View<const T> Ib = inv.block(blk);
+        return launch_gemm<T>(fwd ? Ib : Ib.t(), cv(X), X, batch, n, (int)nvec, n, T(1), T(0), o, st);
+    }
     const int n1 = split_point(n), n2 = n - n1;
     View<const T> L11 = Lam, L21 = Lam.sub(n1, 0), L22 = Lam.sub(n1, n1);
     View<T> X1 = X, X2 = X.sub(n1, 0);
-    GemmOpts o;
     if (fwd) {
-        LA_TRY(solve_rec<T>(L11, X1, batch, n1, nvec, true, st));
+        LA_TRY(solve_rec<T>(L11, X1, batch, n1, nvec, true, inv, blk, st));
         LA_TRY(launch_gemm<T>(L21, cv(X1), X2, batch, n2, (int)nvec, n1, T(-1), T(1), o, st));
-        return solve_rec<T>(L22, X2, batch, n2, nvec, true, st);
+        return solve_rec<T>(L22, X2, batch, n2, nvec, true, inv, blk + n1 / NB, st);
     }
-    LA_TRY(solve_rec<T>(L22, X2, batch, n2, nvec, false, st));
+    LA_TRY(solve_rec<T>(L22, X2, batch, n2, nvec, false, inv, blk + n1 / NB, st));
     LA_TRY(launch_gemm<T>(L21.t(), cv(X2), X1, batch, n1, (int)nvec, n2, T(-1), T(1), o, st));
-    return solve_rec<T>(L11, X1, batch, n1, nvec, false, st);
+    return solve_rec<T>(L11, X1, batch, n1, nvec, false, inv, blk, st);
 }
 
 template <typename T>
 static la_status mult_rec(View<const T> Lam, View<T> X, int64_t batch, int n, int64_t nvec, bool fwd, hipStream_t st)
 {
-    if (n <= NB)
-        return launch_tile_mult<T>(Lam, X, batch, n, nvec, fwd, false, st);
+    GemmOpts o;
+    if (n <= NB) {
+        o.triA = fwd ? 1 : 2;  // Lam keeps i >= k, Lam^T keeps i <= k
+        return launch_gemm<T>(fwd ? Lam : Lam.t(), cv(X), X, batch, n, (int)nvec, n, T(1), T(0), o, st);
+    }
     const int n1 = split_point(n), n2 = n - n1;
     View<const T> L11 = Lam, L21 = Lam.sub(n1, 0), L22 = Lam.sub(n1, n1);
     View<T> X1 = X, X2 = X.sub(n1, 0);
-    GemmOpts o;
     if (fwd) {  // y2 = Lam21 x1 + Lam22 x2 first (needs the old x1), then y1 = Lam11 x1
         LA_TRY(mult_rec<T>(L22, X2, batch, n2, nvec, true, st));
         LA_TRY(launch_gemm<T>(L21, cv(X1), X2, batch, n2, (int)nvec, n1, T(1), T(1), o, st));
@@ -85,20 +152,24 @@ static la_status mult_rec(View<const T> Lam, View<T> X, int64_t batch, int n, in
 // A = L L^T).  W already holds tril(A).  off is the index of W's first row in the whole matrix.
 // ---------------------------------------------------------------------------------
 template <typename T>
-static la_status potrf_rec(View<T> W, int32_t *info, int off, int64_t batch, int n, hipStream_t st)
+static la_status potrf_rec(View<T> W, int32_t *info, int off, int64_t batch, int n, const InvBlocks<T> &inv,
+                           hipStream_t st)
 {
-    if (n <= NB)
-        return launch_potrf_tiny<T>(cv(W), W, info, off, batch, n, st);
+    if (n <= NB) {
+        LA_TRY(launch_potrf_tiny<T>(cv(W), W, info, off, batch, n, st));
+        // the inverse of the fresh diagonal block serves every later panel solve against it
+        return launch_tile_inverse<T>(cv(W), inv.p, inv.bs, batch, n, off / NB, st);
+    }
     const int n1 = split_point(n), n2 = n - n1;
     View<T> W21 = W.sub(n1, 0), W22 = W.sub(n1, n1);
-    LA_TRY(potrf_rec<T>(W, info, off, batch, n1, st));
+    LA_TRY(potrf_rec<T>(W, info, off, batch, n1, inv, st));
     // panel: L21 = A21 L11^-T, i.e. every row x of the panel solves L11 x^T = a^T
-    LA_TRY(solve_rec<T>(cv(W), W21.t(), batch, n1, n2, true, st));
+    LA_TRY(solve_rec<T>(cv(W), W21.t(), batch, n1, n2, true, inv, off / NB, st));
     // trailing update of the lower triangle: A22 -= L21 L21^T
     GemmOpts o;
     o.maskC = 1;
     LA_TRY(launch_gemm<T>(cv(W21), cv(W21).t(), W22, batch, n2, n2, n1, T(-1), T(1), o, st));
-    return potrf_rec<T>(W22, info, off + n1, batch, n2, st);
+    return potrf_rec<T>(W22, info, off + n1, batch, n2, inv, st);
 }
 
 // ---------------------------------------------------------------------------------
@@ -110,13 +181,19 @@ static la_status potrf_rec(View<T> W, int32_t *info, int off, int64_t batch, int
 template <typename T>
 static la_status phi_ltw_rec(View<const T> Lam, View<T> W, int64_t batch, int n, hipStream_t st)
 {
-    if (n <= NB)
-        return launch_tile_mult<T>(Lam, W, batch, n, n, false, true, st);
+    GemmOpts o;
+    if (n <= NB) {
+        // Lam^T (keeps i <= k) times the lower-triangular block (keeps k >= j); lower part kept, diagonal halved
+        o.triA = 2;
+        o.triB = 1;
+        o.maskC = 1;
+        o.halfDiag = 1;
+        return launch_gemm<T>(Lam.t(), cv(W), W, batch, n, n, n, T(1), T(0), o, st);
+    }
     const int n1 = split_point(n), n2 = n - n1;
     View<const T> L21 = Lam.sub(n1, 0), L22 = Lam.sub(n1, n1);
     View<T> W21 = W.sub(n1, 0), W22 = W.sub(n1, n1);
     LA_TRY(phi_ltw_rec<T>(Lam, W, batch, n1, st));
-    GemmOpts o;
     o.maskC = 1;
     o.halfDiag = 1;
     LA_TRY(launch_gemm<T>(L21.t(), cv(W21), W, batch, n1, n1, n2, T(1), T(1), o, st));
@@ -126,20 +203,21 @@ static la_status phi_ltw_rec(View<const T> Lam, View<T> W, int64_t batch, int n,
 
 // W (lower triangular) <- W Lam^-1, which stays lower triangular.
 template <typename T>
-static la_status rsolve_tri_rec(View<const T> Lam, View<T> W, int64_t batch, int n, hipStream_t st)
+static la_status rsolve_tri_rec(View<const T> Lam, View<T> W, int64_t batch, int n, const InvBlocks<T> &inv, int blk,
+                                hipStream_t st)
 {
     if (n <= NB)  // rows of W are the vectors: x Lam = b  <=>  Lam^T x^T = b^T
-        return launch_tile_solve<T>(Lam, W.t(), batch, n, n, false, st);
+        return solve_rec<T>(Lam, W.t(), batch, n, n, false, inv, blk, st);
     const int n1 = split_point(n), n2 = n - n1;
     View<const T> L21 = Lam.sub(n1, 0), L22 = Lam.sub(n1, n1);
     View<T> W21 = W.sub(n1, 0), W22 = W.sub(n1, n1);
-    LA_TRY(rsolve_tri_rec<T>(Lam, W, batch, n1, st));
-    LA_TRY(rsolve_tri_rec<T>(L22, W22, batch, n2, st));
+    LA_TRY(rsolve_tri_rec<T>(Lam, W, batch, n1, inv, blk, st));
+    LA_TRY(rsolve_tri_rec<T>(L22, W22, batch, n2, inv, blk + n1 / NB, st));
     // X21 = (W21 - X22 Lam21) Lam11^-1
     GemmOpts o;
     o.triA = 1;
     LA_TRY(launch_gemm<T>(cv(W22), L21, W21, batch, n2, n1, n2, T(-1), T(1), o, st));
-    return solve_rec<T>(Lam, W21.t(), batch, n1, n2, false, st);
+    return solve_rec<T>(Lam, W21.t(), batch, n1, n2, false, inv, blk, st);
 }
 
 template <typename T>
@@ -147,10 +225,13 @@ static la_status backward_impl(View<const T> Lam, View<const T> G, View<T> W, in
 {
     if (n <= 32)
         return launch_backward_tiny<T>(Lam, G, W, batch, n, st);
+    InvBlocks<T> inv;
+    LA_TRY(inv_alloc<T>(batch, n, inv));
+    LA_TRY(launch_tile_inverse<T>(Lam, inv.p, inv.bs, batch, n, 0, st));
     LA_TRY(launch_copy<T>(G, W, batch, n, n, T(1), 1, st));          // W = tril(Lbar)
     LA_TRY(phi_ltw_rec<T>(Lam, W, batch, n, st));                    // W = Phi(Lam^T Lbar)
-    LA_TRY(rsolve_tri_rec<T>(Lam, W, batch, n, st));                 // W = Phi(.) Lam^-1   (still lower)
-    LA_TRY(solve_rec<T>(Lam, W, batch, n, n, false, st));            // W = Lam^-T Phi(.) Lam^-1
+    LA_TRY(rsolve_tri_rec<T>(Lam, W, batch, n, inv, 0, st));         // W = Phi(.) Lam^-1   (still lower)
+    LA_TRY(solve_rec<T>(Lam, W, batch, n, n, false, inv, 0, st));    // W = Lam^-T Phi(.) Lam^-1
     return launch_symmetrize<T>(W, batch, n, T(0.5), st);            // Abar = 1/2 (W + W^T)
 }
 
@@ -182,8 +263,10 @@ static la_status potrf_t(int lower, int64_t batch, int n, const void *A, void *L
         LA_TRY(launch_fill_i32(info, batch, 0, st));
     if (n <= NB)
         return launch_potrf_tiny<T>(Av, Lv, info, 0, batch, n, st);
+    InvBlocks<T> inv;
+    LA_TRY(inv_alloc<T>(batch, n, inv));
     LA_TRY(launch_copy<T>(Av, Lv, batch, n, n, T(1), 1, st));  // L = tril(A), zeros above
-    return potrf_rec<T>(Lv, info, 0, batch, n, st);
+    return potrf_rec<T>(Lv, info, 0, batch, n, inv, st);
 }
 
 template <typename T>
@@ -201,7 +284,12 @@ static la_status tri_apply_t(bool solve, int lower, int trans, int rightside, do
     View<T> X = rightside ? View<T>{(T *)B, nm, 1, n} : View<T>{(T *)B, nm, m, 1};
     const bool use_lt = (trans != 0) != (lower == 0);  // t(L) equals Lam^T
     const bool fwd = (use_lt == (rightside != 0));
-    return solve ? solve_rec<T>(Lam, X, batch, n, m, fwd, st) : mult_rec<T>(Lam, X, batch, n, m, fwd, st);
+    if (!solve)
+        return mult_rec<T>(Lam, X, batch, n, m, fwd, st);
+    InvBlocks<T> inv;
+    LA_TRY(inv_alloc<T>(batch, n, inv));
+    LA_TRY(launch_tile_inverse<T>(Lam, inv.p, inv.bs, batch, n, 0, st));
+    return solve_rec<T>(Lam, X, batch, n, m, fwd, inv, 0, st);
 }
 
 template <typename T>

@@ -156,6 +156,57 @@ __global__ __launch_bounds__(WAVE) void k_tile(View<const T> Lam, View<T> X, int
     }
 }
 
+// Inverses of the 64 x 64 diagonal blocks of a lower-triangular Lam (n x n): block j of item b
+// goes to winv + b*winv_bs + (blk0 + j)*64*64 as a dense row-major 64 x 64 lower-triangular
+// matrix (zeros above the diagonal, identity padding when the last block is ragged).
+// Lane c solves Lam_jj x = e_c, i.e. owns column c of the inverse.
+template <typename T>
+__global__ __launch_bounds__(WAVE) void k_tile_inv(View<const T> Lam, T *winv, int64_t winv_bs, int64_t batch, int n,
+                                                   int nblk, int blk0)
+{
+    constexpr int LDM = TileCfg<T>::LDM;
+    __shared__ __align__(16) T sM[NB * LDM];
+    __shared__ T sD[NB];
+    const int lane = threadIdx.x;
+    const int64_t b = blockIdx.x / nblk;
+    const int j = (int)(blockIdx.x % nblk);
+    const int nb = min(NB, n - j * NB);
+    load_tri<T>(sM, Lam.sub((int64_t)j * NB, (int64_t)j * NB), b, nb, true);  // sM[k][i] = Lam_jj(i,k)
+    __syncthreads();
+    sD[lane] = rcp_acc(sM[lane * LDM + lane]);
+    __syncthreads();
+    T x[NB];
+#pragma unroll
+    for (int e = 0; e < NB; ++e)
+        x[e] = (e == lane) ? T(1) : T(0);
+#pragma unroll
+    for (int k = 0; k < NB; ++k) {
+        x[k] *= sD[k];
+#pragma unroll
+        for (int i = k + 1; i < NB; ++i)
+            x[i] = fma(-sM[k * LDM + i], x[k], x[i]);
+    }
+    T *out = winv + b * winv_bs + (int64_t)(blk0 + j) * NB * NB;
+#pragma unroll
+    for (int e = 0; e < NB; ++e)
+        out[e * NB + lane] = x[e];
+}
+
+template <typename T>
+la_status launch_tile_inverse(View<const T> Lam, T *winv, int64_t winv_bs, int64_t batch, int n, int blk0,
+                              hipStream_t st)
+{
+    if (batch <= 0 || n <= 0)
+        return LA_OK;
+    const int nblk = (n + NB - 1) / NB;
+    const int64_t blocks = (int64_t)nblk * batch;
+    if (blocks > 0x7fffffffll)
+        return LA_ERR_UNSUPPORTED;
+    hipLaunchKernelGGL((k_tile_inv<T>), dim3((unsigned)blocks), dim3(WAVE), 0, st, Lam, winv, winv_bs, batch, n, nblk,
+                       blk0);
+    return launch_check("tile_inverse");
+}
+
 template <typename T, int MODE>
 static la_status launch_tile(View<const T> Lam, View<T> X, int64_t batch, int nb, int64_t nvec, int tflag, int phi,
                              hipStream_t st)
@@ -195,6 +246,8 @@ la_status launch_tile_mult(View<const T> Lam, View<T> X, int64_t batch, int nb, 
     return launch_tile<T, 3>(Lam, X, batch, nb, nvec, 1, phi ? 1 : 0, st);
 }
 
+template la_status launch_tile_inverse<float>(View<const float>, float *, int64_t, int64_t, int, int, hipStream_t);
+template la_status launch_tile_inverse<double>(View<const double>, double *, int64_t, int64_t, int, int, hipStream_t);
 template la_status launch_tile_solve<float>(View<const float>, View<float>, int64_t, int, int64_t, bool, hipStream_t);
 template la_status launch_tile_solve<double>(View<const double>, View<double>, int64_t, int, int64_t, bool, hipStream_t);
 template la_status launch_tile_mult<float>(View<const float>, View<float>, int64_t, int, int64_t, bool, bool,
