@@ -22,9 +22,14 @@ template <typename T>
 struct View {
     T *p;
     int64_t bs, rs, cs;
-    __host__ __device__ View<T> sub(int64_t i, int64_t j) const { return {p + i * rs + j * cs, bs, rs, cs}; }
-    __host__ __device__ View<T> t() const { return {p, bs, cs, rs}; }
-    __device__ T *item(int64_t b) const { return p + b * bs; }
+    // optional second batch level: batch index q addresses item (q / nb2) and sub-item (q % nb2),
+    // the latter bs2 elements apart (e.g. the diagonal blocks of one matrix)
+    int64_t bs2 = 0;
+    int32_t nb2 = 1;
+    __host__ __device__ View<T> sub(int64_t i, int64_t j) const { return {p + i * rs + j * cs, bs, rs, cs, bs2, nb2}; }
+    __host__ __device__ View<T> t() const { return {p, bs, cs, rs, bs2, nb2}; }
+    __host__ __device__ View<T> level2(int64_t stride2, int32_t count2) const { return {p, bs, rs, cs, stride2, count2}; }
+    __device__ T *item(int64_t q) const { return nb2 == 1 ? p + q * bs : p + (q / nb2) * bs + (q % nb2) * bs2; }
 };
 
 void set_error(hipError_t e, const char *where);
@@ -230,11 +235,10 @@ template <typename T>
 la_status launch_tile_mult(View<const T> Lam, View<T> X, int64_t batch, int nb, int64_t nvec, bool fwd, bool phi,
                            hipStream_t st);
 
-// Dense inverses of the 64 x 64 diagonal blocks of Lam (n x n lower triangular) into a
-// caller-provided buffer: block j of item b at winv + b*winv_bs + (blk0 + j)*64*64, row-major.
+// Inverses of the 64 x 64 diagonal blocks of Lam (n x n lower triangular) written onto the
+// diagonal blocks of Inv (n x n, entries off those blocks are left alone).
 template <typename T>
-la_status launch_tile_inverse(View<const T> Lam, T *winv, int64_t winv_bs, int64_t batch, int n, int blk0,
-                              hipStream_t st);
+la_status launch_tile_inverse(View<const T> Lam, View<T> Inv, int64_t batch, int n, hipStream_t st);
 
 // C(i,j) = beta*C(i,j) + alpha * sum_k A(i,k) B(k,j), i < M, j < N, k < K, per batch item.
 struct GemmOpts {

@@ -11,10 +11,11 @@
 //
 // Two kernels:
 //  * k_gemm_fast: 16-byte vector loads, register prefetch of the next K slab while the
-//    current one is multiplied out of a double-buffered LDS stage (one barrier per slab),
-//    128x128 or 64x64 workgroup tiles, four wavefronts in a 2 x 2 arrangement, 16x16x4 MFMA
-//    (v_mfma_f64_16x16x4_f64 / v_mfma_f32_16x16x4_f32).  Needs 16-byte aligned operands and
-//    K a multiple of 16.
+//    current one is multiplied out of LDS, 128x128 (K slabs of 16, double-buffered LDS, one
+//    barrier per slab) or 64x64 workgroup tiles (K slabs of 64 for the small, latency-bound
+//    grids of the recursion's lower levels), four wavefronts in a 2 x 2 arrangement, 16x16x4
+//    MFMA (v_mfma_f64_16x16x4_f64 / v_mfma_f32_16x16x4_f32).  Needs 16-byte aligned operands
+//    and K a multiple of 16.
 //  * k_gemm: element-wise staged fallback for everything else (ragged / unaligned shapes).
 #include "common.hpp"
 
@@ -158,9 +159,9 @@ __global__ __launch_bounds__(256) void k_gemm(View<const T> A, View<const T> B, 
     k_range(o, i0, j0, BM, BN, K, kbeg, kend);
     kbeg = (kbeg / BK) * BK;
 
-    const T *Ap = A.p + b * A.bs;
-    const T *Bp = B.p + b * B.bs;
-    T *Cp = C.p + b * C.bs;
+    const T *Ap = A.item(b);
+    const T *Bp = B.item(b);
+    T *Cp = C.item(b);
     const bool a_kfast = (A.cs == 1);
     const bool b_kfast = (B.rs == 1);
 
@@ -293,11 +294,10 @@ __device__ __forceinline__ void slab_commit(T *s, RV &r, int o0, int k0, int tri
     }
 }
 
-template <typename T, int BM, int BN, bool AKF, bool BKF>
+template <typename T, int BM, int BN, int BK, int NBUF, bool AKF, bool BKF>
 __global__ __launch_bounds__(256) void k_gemm_fast(View<const T> A, View<const T> B, View<T> C, int64_t batch, int M,
                                                    int N, int K, T alpha, T beta, GemmOpts o, int tiles_m, int tiles_n)
 {
-    constexpr int BK = 16;
     using MF = Mfma<T>;
     using acc_t = typename MF::acc_t;
     using V = typename MF::vec_t;
@@ -305,8 +305,8 @@ __global__ __launch_bounds__(256) void k_gemm_fast(View<const T> A, View<const T
     using SB = Slab<T, BN, BK, BKF>;
     constexpr int WM = BM / 2, WN = BN / 2;
     constexpr int TM = WM / 16, TN = WN / 16;
-    __shared__ __align__(16) T sA[2][SA::ELEMS];
-    __shared__ __align__(16) T sB[2][SB::ELEMS];
+    __shared__ __align__(16) T sA[NBUF][SA::ELEMS];
+    __shared__ __align__(16) T sB[NBUF][SB::ELEMS];
 
     const int64_t per = (int64_t)tiles_m * tiles_n;
     const int64_t slot = xcd_slot(blockIdx.x, per * batch);
@@ -322,9 +322,9 @@ __global__ __launch_bounds__(256) void k_gemm_fast(View<const T> A, View<const T
     kbeg = (kbeg / BK) * BK;
     kend = ((kend + BK - 1) / BK) * BK;  // K is a multiple of BK, so this stays <= K
 
-    const T *Ap = A.p + b * A.bs;
-    const T *Bp = B.p + b * B.bs;
-    T *Cp = C.p + b * C.bs;
+    const T *Ap = A.item(b);
+    const T *Bp = B.item(b);
+    T *Cp = C.item(b);
     const int triB_o = o.triB == 1 ? 2 : (o.triB == 2 ? 1 : 0);
 
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
@@ -338,19 +338,20 @@ __global__ __launch_bounds__(256) void k_gemm_fast(View<const T> A, View<const T
         for (int y = 0; y < TN; ++y)
             acc[x][y] = acc_t{0, 0, 0, 0};
 
+    // Software pipeline: slab s+1 is fetched into registers while slab s is multiplied out of LDS.
+    // With two LDS buffers one barrier per slab is enough (the barrier of slab s+1 separates the
+    // reads of slab s from the overwrite by slab s+2); with one buffer a second barrier is needed.
     V ra[SA::NCH], rb[SB::NCH];
     if (kbeg < kend) {
         slab_fetch<T, BM, BK, AKF>(ra, Ap, A.rs, A.cs, i0, M, kbeg);
         slab_fetch<T, BN, BK, BKF>(rb, Bp, B.cs, B.rs, j0, N, kbeg);
-        slab_commit<T, BM, BK, AKF>(sA[0], ra, i0, kbeg, o.triA);
-        slab_commit<T, BN, BK, BKF>(sB[0], rb, j0, kbeg, triB_o);
     }
-    __syncthreads();
-
     int buf = 0;
     for (int k0 = kbeg; k0 < kend; k0 += BK) {
-        const bool more = (k0 + BK < kend);
-        if (more) {
+        slab_commit<T, BM, BK, AKF>(sA[buf], ra, i0, k0, o.triA);
+        slab_commit<T, BN, BK, BKF>(sB[buf], rb, j0, k0, triB_o);
+        __syncthreads();
+        if (k0 + BK < kend) {
             slab_fetch<T, BM, BK, AKF>(ra, Ap, A.rs, A.cs, i0, M, k0 + BK);
             slab_fetch<T, BN, BK, BKF>(rb, Bp, B.cs, B.rs, j0, N, k0 + BK);
         }
@@ -370,12 +371,10 @@ __global__ __launch_bounds__(256) void k_gemm_fast(View<const T> A, View<const T
                 for (int y = 0; y < TN; ++y)
                     acc[x][y] = MF::run(af[x], bf[y], acc[x][y]);
         }
-        if (more) {
-            slab_commit<T, BM, BK, AKF>(sA[buf ^ 1], ra, i0, k0 + BK, o.triA);
-            slab_commit<T, BN, BK, BKF>(sB[buf ^ 1], rb, j0, k0 + BK, triB_o);
-        }
-        __syncthreads();
-        buf ^= 1;
+        if constexpr (NBUF == 1)
+            __syncthreads();
+        else
+            buf ^= 1;
     }
 
 #pragma unroll
@@ -392,18 +391,18 @@ template <typename T>
 static bool aligned16(const View<const T> &V, int64_t lead)
 {
     constexpr int VW = Mfma<T>::VW;
-    return (reinterpret_cast<uintptr_t>(V.p) & 15) == 0 && (lead % VW) == 0 && (V.bs % VW) == 0;
+    return (reinterpret_cast<uintptr_t>(V.p) & 15) == 0 && (lead % VW) == 0 && (V.bs % VW) == 0 && (V.bs2 % VW) == 0;
 }
 
-template <typename T, int BM, int BN>
+template <typename T, int BM, int BN, int BK, int NBUF>
 static void launch_fast(bool akf, bool bkf, View<const T> A, View<const T> B, View<T> C, int64_t batch, int M, int N,
                         int K, T alpha, T beta, GemmOpts o, hipStream_t st)
 {
     const int tiles_m = (M + BM - 1) / BM, tiles_n = (N + BN - 1) / BN;
     const dim3 grid((unsigned)((int64_t)tiles_m * tiles_n * batch)), block(256);
 #define LA_GO(AK, BKF_)                                                                                              \
-    hipLaunchKernelGGL((k_gemm_fast<T, BM, BN, AK, BKF_>), grid, block, 0, st, A, B, C, batch, M, N, K, alpha, beta, \
-                       o, tiles_m, tiles_n)
+    hipLaunchKernelGGL((k_gemm_fast<T, BM, BN, BK, NBUF, AK, BKF_>), grid, block, 0, st, A, B, C, batch, M, N, K,    \
+                       alpha, beta, o, tiles_m, tiles_n)
     if (akf && bkf)
         LA_GO(true, true);
     else if (akf && !bkf)
@@ -443,9 +442,11 @@ la_status launch_gemm(View<const T> A, View<const T> B, View<T> C, int64_t batch
         if (t64 > 0x7fffffffll)
             return LA_ERR_UNSUPPORTED;
         if (t128 >= 192 && M >= 128 && N >= 128)
-            launch_fast<T, 128, 128>(akf, bkf, A, B, C, batch, M, N, K, alpha, beta, o, st);
+            launch_fast<T, 128, 128, 16, 2>(akf, bkf, A, B, C, batch, M, N, K, alpha, beta, o, st);
+        else if (K % 64 == 0)  // small grids are latency bound: fewer, fatter K slabs
+            launch_fast<T, 64, 64, 64, 1>(akf, bkf, A, B, C, batch, M, N, K, alpha, beta, o, st);
         else
-            launch_fast<T, 64, 64>(akf, bkf, A, B, C, batch, M, N, K, alpha, beta, o, st);
+            launch_fast<T, 64, 64, 16, 2>(akf, bkf, A, B, C, batch, M, N, K, alpha, beta, o, st);
         return launch_check("gemm_fast");
     }
     constexpr int BM = 64, BN = 64, BK = 16;

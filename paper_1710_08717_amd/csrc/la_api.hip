@@ -27,11 +27,12 @@ void set_error(hipError_t e, const char *where)
 }
 
 // ---------------------------------------------------------------------------------
-// Scratch memory of the blocked paths: the dense inverses of the 64 x 64 diagonal blocks of the
-// triangular factor (batch * ceil(n/64) * 64 * 64 elements).  One buffer per device, grown on
-// demand with hipMalloc and kept until the process ends; a buffer that is outgrown is parked,
-// not freed, because work queued on a stream may still be using it.  Calls that use it
-// (n > 64) must therefore not run concurrently on several streams of one device.
+// Scratch memory of the blocked paths (n > 64 for potrf / trsm, n > 32 for the backward pass):
+// inverses of (diagonal blocks of) the triangular factor and one work matrix, at most
+// 2 * batch * n * n elements.  One buffer per device, grown on demand with hipMalloc and kept
+// until the process ends; a buffer that is outgrown is parked, not freed, because work queued
+// on a stream may still be using it.  Calls that use it must therefore not run concurrently
+// on several streams of one device.
 // ---------------------------------------------------------------------------------
 struct Scratch {
     void *p = nullptr;
@@ -62,22 +63,15 @@ static la_status scratch_get(size_t bytes, void **out)
     return LA_OK;
 }
 
-// Inverses of the diagonal blocks of one factor: block j of item b at p + b*bs + j*64*64.
 template <typename T>
-struct InvBlocks {
-    T *p = nullptr;
-    int64_t bs = 0;
-    View<const T> block(int j) const { return {p + (int64_t)j * NB * NB, bs, NB, 1}; }
-};
-
-template <typename T>
-static la_status inv_alloc(int64_t batch, int n, InvBlocks<T> &inv)
+static la_status scratch_views(int64_t batch, int n, int count, View<T> *out)
 {
-    const int nblk = (n + NB - 1) / NB;
+    // `count` row-major n x n matrices per batch item, each batch-contiguous
+    const int64_t nn = (int64_t)n * n;
     void *p = nullptr;
-    LA_TRY(scratch_get((size_t)batch * nblk * NB * NB * sizeof(T), &p));
-    inv.p = (T *)p;
-    inv.bs = (int64_t)nblk * NB * NB;
+    LA_TRY(scratch_get((size_t)count * batch * nn * sizeof(T), &p));
+    for (int c = 0; c < count; ++c)
+        out[c] = View<T>{(T *)p + (int64_t)c * batch * nn, nn, n, 1};
     return LA_OK;
 }
 
@@ -91,7 +85,44 @@ static inline int split_point(int n)
 template <typename T>
 static inline View<const T> cv(View<T> v)
 {
-    return {v.p, v.bs, v.rs, v.cs};
+    return {v.p, v.bs, v.rs, v.cs, v.bs2, v.nb2};
+}
+
+// ---------------------------------------------------------------------------------
+// Explicit inverse of a lower-triangular Lam (n x n) into Inv (n x n, lower triangle; what lies
+// above the diagonal is never written and never read).  First the 64 x 64 diagonal blocks (one
+// launch for the whole batch), then level by level
+//     inv [A 0; C D] = [A^-1 0; -D^-1 C A^-1, D^-1]
+// with all pairs of one level in one batched GEMM pair.  Stops when blocks of `upto` are
+// inverted (upto >= n: the whole matrix).  Tmp: scratch of at least n*n/2 per item.
+// ---------------------------------------------------------------------------------
+template <typename T>
+static la_status inverse_build(View<const T> Lam, View<T> Inv, View<T> Tmp, int64_t batch, int n, int upto,
+                               hipStream_t st)
+{
+    LA_TRY(launch_tile_inverse<T>(Lam, Inv, batch, n, st));
+    for (int64_t h = NB; h < upto && h < n; h *= 2) {
+        const int nfull = (int)(n / (2 * h));                       // pairs whose right block is a full h
+        const int r = (int)(n - (int64_t)nfull * 2 * h - h);        // rows of a ragged right block (if > 0)
+        for (int pass = 0; pass < 2; ++pass) {
+            const int cnt = pass == 0 ? nfull : (r > 0 ? 1 : 0);
+            if (cnt == 0)
+                continue;
+            const int64_t o0 = pass == 0 ? 0 : (int64_t)nfull * 2 * h;  // first row of the first pair
+            const int mr = pass == 0 ? (int)h : r;
+            View<const T> A = cv(Inv).sub(o0, o0).level2(2 * h * (Inv.rs + Inv.cs), cnt);
+            View<const T> D = cv(Inv).sub(o0 + h, o0 + h).level2(2 * h * (Inv.rs + Inv.cs), cnt);
+            View<const T> C = Lam.sub(o0 + h, o0).level2(2 * h * (Lam.rs + Lam.cs), cnt);
+            View<T> O = Inv.sub(o0 + h, o0).level2(2 * h * (Inv.rs + Inv.cs), cnt);
+            View<T> Tv{Tmp.p + (pass == 0 ? 0 : (int64_t)nfull * h * h), Tmp.bs, h, 1, h * h, cnt};
+            GemmOpts o1, o2;
+            o1.triA = 1;  // D^-1 is lower triangular
+            o2.triB = 1;  // A^-1 is lower triangular
+            LA_TRY(launch_gemm<T>(D, C, Tv, batch * cnt, mr, (int)h, mr, T(1), T(0), o1, st));
+            LA_TRY(launch_gemm<T>(cv(Tv), A, O, batch * cnt, mr, (int)h, (int)h, T(-1), T(0), o2, st));
+        }
+    }
+    return LA_OK;
 }
 
 // ---------------------------------------------------------------------------------
@@ -101,28 +132,29 @@ static inline View<const T> cv(View<T> v)
 //   mult  fwd: X <- Lam X         mult  !fwd: X <- Lam^T X
 // ---------------------------------------------------------------------------------
 // Leaves (n <= 64) are in-place GEMMs: a solve multiplies by the precomputed inverse of the
-// diagonal block (inv, block index blk), a product multiplies by the masked block itself.
-// In place is safe there because one workgroup tile covers all n <= 64 rows of its vectors.
+// diagonal block (Inv, whose diagonal 64-blocks hold those inverses), a product multiplies by
+// the masked block itself.  In place is safe there because one workgroup tile covers all
+// n <= 64 rows of its vectors.
 template <typename T>
 static la_status solve_rec(View<const T> Lam, View<T> X, int64_t batch, int n, int64_t nvec, bool fwd,
-                           const InvBlocks<T> &inv, int blk, hipStream_t st)
+                           View<const T> Inv, hipStream_t st)
 {
     GemmOpts o;
     if (n <= NB) {
-        View<const T> Ib = inv.block(blk);
-        return launch_gemm<T>(fwd ? Ib : Ib.t(), cv(X), X, batch, n, (int)nvec, n, T(1), T(0), o, st);
+        o.triA = fwd ? 1 : 2;
+        return launch_gemm<T>(fwd ? Inv : Inv.t(), cv(X), X, batch, n, (int)nvec, n, T(1), T(0), o, st);
     }
     const int n1 = split_point(n), n2 = n - n1;
     View<const T> L11 = Lam, L21 = Lam.sub(n1, 0), L22 = Lam.sub(n1, n1);
     View<T> X1 = X, X2 = X.sub(n1, 0);
     if (fwd) {
-        LA_TRY(solve_rec<T>(L11, X1, batch, n1, nvec, true, inv, blk, st));
+        LA_TRY(solve_rec<T>(L11, X1, batch, n1, nvec, true, Inv, st));
         LA_TRY(launch_gemm<T>(L21, cv(X1), X2, batch, n2, (int)nvec, n1, T(-1), T(1), o, st));
-        return solve_rec<T>(L22, X2, batch, n2, nvec, true, inv, blk + n1 / NB, st);
+        return solve_rec<T>(L22, X2, batch, n2, nvec, true, Inv.sub(n1, n1), st);
     }
-    LA_TRY(solve_rec<T>(L22, X2, batch, n2, nvec, false, inv, blk + n1 / NB, st));
+    LA_TRY(solve_rec<T>(L22, X2, batch, n2, nvec, false, Inv.sub(n1, n1), st));
     LA_TRY(launch_gemm<T>(L21.t(), cv(X2), X1, batch, n1, (int)nvec, n2, T(-1), T(1), o, st));
-    return solve_rec<T>(L11, X1, batch, n1, nvec, false, inv, blk, st);
+    return solve_rec<T>(L11, X1, batch, n1, nvec, false, Inv, st);
 }
 
 template <typename T>
@@ -152,24 +184,23 @@ static la_status mult_rec(View<const T> Lam, View<T> X, int64_t batch, int n, in
 // A = L L^T).  W already holds tril(A).  off is the index of W's first row in the whole matrix.
 // ---------------------------------------------------------------------------------
 template <typename T>
-static la_status potrf_rec(View<T> W, int32_t *info, int off, int64_t batch, int n, const InvBlocks<T> &inv,
-                           hipStream_t st)
+static la_status potrf_rec(View<T> W, int32_t *info, int off, int64_t batch, int n, View<T> Inv, hipStream_t st)
 {
     if (n <= NB) {
         LA_TRY(launch_potrf_tiny<T>(cv(W), W, info, off, batch, n, st));
         // the inverse of the fresh diagonal block serves every later panel solve against it
-        return launch_tile_inverse<T>(cv(W), inv.p, inv.bs, batch, n, off / NB, st);
+        return launch_tile_inverse<T>(cv(W), Inv, batch, n, st);
     }
     const int n1 = split_point(n), n2 = n - n1;
     View<T> W21 = W.sub(n1, 0), W22 = W.sub(n1, n1);
-    LA_TRY(potrf_rec<T>(W, info, off, batch, n1, inv, st));
+    LA_TRY(potrf_rec<T>(W, info, off, batch, n1, Inv, st));
     // panel: L21 = A21 L11^-T, i.e. every row x of the panel solves L11 x^T = a^T
-    LA_TRY(solve_rec<T>(cv(W), W21.t(), batch, n1, n2, true, inv, off / NB, st));
+    LA_TRY(solve_rec<T>(cv(W), W21.t(), batch, n1, n2, true, cv(Inv), st));
     // trailing update of the lower triangle: A22 -= L21 L21^T
     GemmOpts o;
     o.maskC = 1;
     LA_TRY(launch_gemm<T>(cv(W21), cv(W21).t(), W22, batch, n2, n2, n1, T(-1), T(1), o, st));
-    return potrf_rec<T>(W22, info, off + n1, batch, n2, inv, st);
+    return potrf_rec<T>(W22, info, off + n1, batch, n2, Inv.sub(n1, n1), st);
 }
 
 // ---------------------------------------------------------------------------------
@@ -177,62 +208,43 @@ static la_status potrf_rec(View<T> W, int32_t *info, int off, int64_t batch, int
 //   Abar = sym( Lam^-T Phi(Lam^T Lbar) Lam^-1 ),  Phi = lower triangle, halved diagonal.
 // ---------------------------------------------------------------------------------
 
-// W (lower triangular, zeros above) <- Phi(tril(Lam^T W)), in place.
+// With the explicit inverse Li of the factor the whole expression is three masked GEMMs whose
+// K ranges skip every structural zero (5 n^3 / 3 flops in all, inverse included):
+//   P = Phi(tril(Lam^T Lbar))      lower x lower, lower part kept, diagonal halved
+//   Z = P Li                       lower x lower = lower
+//   W = Li^T Z                     upper x lower = full
+//   Abar = 1/2 (W + W^T)
 template <typename T>
-static la_status phi_ltw_rec(View<const T> Lam, View<T> W, int64_t batch, int n, hipStream_t st)
-{
-    GemmOpts o;
-    if (n <= NB) {
-        // Lam^T (keeps i <= k) times the lower-triangular block (keeps k >= j); lower part kept, diagonal halved
-        o.triA = 2;
-        o.triB = 1;
-        o.maskC = 1;
-        o.halfDiag = 1;
-        return launch_gemm<T>(Lam.t(), cv(W), W, batch, n, n, n, T(1), T(0), o, st);
-    }
-    const int n1 = split_point(n), n2 = n - n1;
-    View<const T> L21 = Lam.sub(n1, 0), L22 = Lam.sub(n1, n1);
-    View<T> W21 = W.sub(n1, 0), W22 = W.sub(n1, n1);
-    LA_TRY(phi_ltw_rec<T>(Lam, W, batch, n1, st));
-    o.maskC = 1;
-    o.halfDiag = 1;
-    LA_TRY(launch_gemm<T>(L21.t(), cv(W21), W, batch, n1, n1, n2, T(1), T(1), o, st));
-    LA_TRY(mult_rec<T>(L22, W21, batch, n2, n1, false, st));
-    return phi_ltw_rec<T>(L22, W22, batch, n2, st);
-}
-
-// W (lower triangular) <- W Lam^-1, which stays lower triangular.
-template <typename T>
-static la_status rsolve_tri_rec(View<const T> Lam, View<T> W, int64_t batch, int n, const InvBlocks<T> &inv, int blk,
-                                hipStream_t st)
-{
-    if (n <= NB)  // rows of W are the vectors: x Lam = b  <=>  Lam^T x^T = b^T
-        return solve_rec<T>(Lam, W.t(), batch, n, n, false, inv, blk, st);
-    const int n1 = split_point(n), n2 = n - n1;
-    View<const T> L21 = Lam.sub(n1, 0), L22 = Lam.sub(n1, n1);
-    View<T> W21 = W.sub(n1, 0), W22 = W.sub(n1, n1);
-    LA_TRY(rsolve_tri_rec<T>(Lam, W, batch, n1, inv, blk, st));
-    LA_TRY(rsolve_tri_rec<T>(L22, W22, batch, n2, inv, blk + n1 / NB, st));
-    // X21 = (W21 - X22 Lam21) Lam11^-1
-    GemmOpts o;
-    o.triA = 1;
-    LA_TRY(launch_gemm<T>(cv(W22), L21, W21, batch, n2, n1, n2, T(-1), T(1), o, st));
-    return solve_rec<T>(Lam, W21.t(), batch, n1, n2, false, inv, blk, st);
-}
-
-template <typename T>
-static la_status backward_impl(View<const T> Lam, View<const T> G, View<T> W, int64_t batch, int n, hipStream_t st)
+static la_status backward_impl(View<const T> Lam, View<const T> G, View<T> W, int64_t batch, int n, bool aliased,
+                               hipStream_t st)
 {
     if (n <= 32)
         return launch_backward_tiny<T>(Lam, G, W, batch, n, st);
-    InvBlocks<T> inv;
-    LA_TRY(inv_alloc<T>(batch, n, inv));
-    LA_TRY(launch_tile_inverse<T>(Lam, inv.p, inv.bs, batch, n, 0, st));
-    LA_TRY(launch_copy<T>(G, W, batch, n, n, T(1), 1, st));          // W = tril(Lbar)
-    LA_TRY(phi_ltw_rec<T>(Lam, W, batch, n, st));                    // W = Phi(Lam^T Lbar)
-    LA_TRY(rsolve_tri_rec<T>(Lam, W, batch, n, inv, 0, st));         // W = Phi(.) Lam^-1   (still lower)
-    LA_TRY(solve_rec<T>(Lam, W, batch, n, n, false, inv, 0, st));    // W = Lam^-T Phi(.) Lam^-1
-    return launch_symmetrize<T>(W, batch, n, T(0.5), st);            // Abar = 1/2 (W + W^T)
+    View<T> sc[2];
+    LA_TRY(scratch_views<T>(batch, n, 2, sc));
+    View<T> Li = sc[0], X = sc[1];
+    LA_TRY(inverse_build<T>(Lam, Li, X, batch, n, n, st));
+    View<const T> Gs = G;
+    if (aliased) {  // Abar overwrites Lbar: keep a copy of its lower triangle
+        LA_TRY(launch_copy<T>(G, X, batch, n, n, T(1), 1, st));
+        Gs = cv(X);
+    }
+    GemmOpts o;
+    o.triA = 2;  // Lam^T
+    o.triB = 1;
+    o.maskC = 1;
+    o.halfDiag = 1;
+    LA_TRY(launch_gemm<T>(Lam.t(), Gs, W, batch, n, n, n, T(1), T(0), o, st));
+    GemmOpts oz;
+    oz.triA = 1;
+    oz.triB = 1;
+    oz.maskC = 1;
+    LA_TRY(launch_gemm<T>(cv(W), cv(Li), X, batch, n, n, n, T(1), T(0), oz, st));
+    GemmOpts ow;
+    ow.triA = 2;
+    ow.triB = 1;
+    LA_TRY(launch_gemm<T>(cv(Li).t(), cv(X), W, batch, n, n, n, T(1), T(0), ow, st));
+    return launch_symmetrize<T>(W, batch, n, T(0.5), st);
 }
 
 // ---------------------------------------------------------------------------------
@@ -263,10 +275,10 @@ static la_status potrf_t(int lower, int64_t batch, int n, const void *A, void *L
         LA_TRY(launch_fill_i32(info, batch, 0, st));
     if (n <= NB)
         return launch_potrf_tiny<T>(Av, Lv, info, 0, batch, n, st);
-    InvBlocks<T> inv;
-    LA_TRY(inv_alloc<T>(batch, n, inv));
+    View<T> Inv;
+    LA_TRY(scratch_views<T>(batch, n, 1, &Inv));
     LA_TRY(launch_copy<T>(Av, Lv, batch, n, n, T(1), 1, st));  // L = tril(A), zeros above
-    return potrf_rec<T>(Lv, info, 0, batch, n, inv, st);
+    return potrf_rec<T>(Lv, info, 0, batch, n, Inv, st);
 }
 
 template <typename T>
@@ -286,10 +298,10 @@ static la_status tri_apply_t(bool solve, int lower, int trans, int rightside, do
     const bool fwd = (use_lt == (rightside != 0));
     if (!solve)
         return mult_rec<T>(Lam, X, batch, n, m, fwd, st);
-    InvBlocks<T> inv;
-    LA_TRY(inv_alloc<T>(batch, n, inv));
-    LA_TRY(launch_tile_inverse<T>(Lam, inv.p, inv.bs, batch, n, 0, st));
-    return solve_rec<T>(Lam, X, batch, n, m, fwd, inv, 0, st);
+    View<T> Inv;
+    LA_TRY(scratch_views<T>(batch, n, 1, &Inv));
+    LA_TRY(launch_tile_inverse<T>(Lam, Inv, batch, n, st));
+    return solve_rec<T>(Lam, X, batch, n, m, fwd, cv(Inv), st);
 }
 
 template <typename T>
@@ -345,10 +357,10 @@ la_status la_potrf_backward(la_dtype dt, int lower, int64_t batch, int n, const 
     if (dt == LA_F32)
         return backward_impl<float>(tri_view<const float>((const float *)L, n, lower),
                                     tri_view<const float>((const float *)Lbar, n, lower),
-                                    tri_view<float>((float *)Abar, n, lower), batch, n, st);
+                                    tri_view<float>((float *)Abar, n, lower), batch, n, Lbar == Abar, st);
     return backward_impl<double>(tri_view<const double>((const double *)L, n, lower),
                                  tri_view<const double>((const double *)Lbar, n, lower),
-                                 tri_view<double>((double *)Abar, n, lower), batch, n, st);
+                                 tri_view<double>((double *)Abar, n, lower), batch, n, Lbar == Abar, st);
 }
 
 static la_status tri_apply(bool solve, la_dtype dt, int lower, int trans, int rightside, double alpha, int64_t batch,

@@ -156,16 +156,16 @@ __global__ __launch_bounds__(WAVE) void k_tile(View<const T> Lam, View<T> X, int
     }
 }
 
-// Inverses of the 64 x 64 diagonal blocks of a lower-triangular Lam (n x n): block j of item b
-// goes to winv + b*winv_bs + (blk0 + j)*64*64 as a dense row-major 64 x 64 lower-triangular
-// matrix (zeros above the diagonal, identity padding when the last block is ragged).
-// Lane c solves Lam_jj x = e_c, i.e. owns column c of the inverse.
+// Inverses of the 64 x 64 diagonal blocks of a lower-triangular Lam (n x n), written onto the
+// diagonal blocks of Inv (lower triangle and zeros above it inside each block; a ragged last
+// block writes only its nb x nb part).  Lane c solves Lam_jj x = e_c: column c of the inverse.
 template <typename T>
-__global__ __launch_bounds__(WAVE) void k_tile_inv(View<const T> Lam, T *winv, int64_t winv_bs, int64_t batch, int n,
-                                                   int nblk, int blk0)
+__global__ __launch_bounds__(WAVE) void k_tile_inv(View<const T> Lam, View<T> Inv, int64_t batch, int n, int nblk)
 {
     constexpr int LDM = TileCfg<T>::LDM;
+    constexpr int LDX = TileCfg<T>::LDX;
     __shared__ __align__(16) T sM[NB * LDM];
+    __shared__ T sX[NB * LDX];
     __shared__ T sD[NB];
     const int lane = threadIdx.x;
     const int64_t b = blockIdx.x / nblk;
@@ -186,15 +186,23 @@ __global__ __launch_bounds__(WAVE) void k_tile_inv(View<const T> Lam, T *winv, i
         for (int i = k + 1; i < NB; ++i)
             x[i] = fma(-sM[k * LDM + i], x[k], x[i]);
     }
-    T *out = winv + b * winv_bs + (int64_t)(blk0 + j) * NB * NB;
+    // x[e] = inverse(e, lane); go through LDS so that the store walks Inv's contiguous direction
+    View<T> O = Inv.sub((int64_t)j * NB, (int64_t)j * NB);
+    T *op = O.p + b * O.bs;
 #pragma unroll
     for (int e = 0; e < NB; ++e)
-        out[e * NB + lane] = x[e];
+        sX[e * LDX + lane] = x[e];  // sX[row][col]
+    __syncthreads();
+    const bool colfast = (O.cs == 1);
+    for (int u = 0; u < NB; ++u) {
+        const int r = colfast ? u : lane, c = colfast ? lane : u;
+        if (r < nb && c < nb)
+            op[r * O.rs + c * O.cs] = sX[r * LDX + c];
+    }
 }
 
 template <typename T>
-la_status launch_tile_inverse(View<const T> Lam, T *winv, int64_t winv_bs, int64_t batch, int n, int blk0,
-                              hipStream_t st)
+la_status launch_tile_inverse(View<const T> Lam, View<T> Inv, int64_t batch, int n, hipStream_t st)
 {
     if (batch <= 0 || n <= 0)
         return LA_OK;
@@ -202,8 +210,7 @@ la_status launch_tile_inverse(View<const T> Lam, T *winv, int64_t winv_bs, int64
     const int64_t blocks = (int64_t)nblk * batch;
     if (blocks > 0x7fffffffll)
         return LA_ERR_UNSUPPORTED;
-    hipLaunchKernelGGL((k_tile_inv<T>), dim3((unsigned)blocks), dim3(WAVE), 0, st, Lam, winv, winv_bs, batch, n, nblk,
-                       blk0);
+    hipLaunchKernelGGL((k_tile_inv<T>), dim3((unsigned)blocks), dim3(WAVE), 0, st, Lam, Inv, batch, n, nblk);
     return launch_check("tile_inverse");
 }
 
@@ -246,8 +253,8 @@ la_status launch_tile_mult(View<const T> Lam, View<T> X, int64_t batch, int nb, 
     return launch_tile<T, 3>(Lam, X, batch, nb, nvec, 1, phi ? 1 : 0, st);
 }
 
-template la_status launch_tile_inverse<float>(View<const float>, float *, int64_t, int64_t, int, int, hipStream_t);
-template la_status launch_tile_inverse<double>(View<const double>, double *, int64_t, int64_t, int, int, hipStream_t);
+template la_status launch_tile_inverse<float>(View<const float>, View<float>, int64_t, int, hipStream_t);
+template la_status launch_tile_inverse<double>(View<const double>, View<double>, int64_t, int, hipStream_t);
 template la_status launch_tile_solve<float>(View<const float>, View<float>, int64_t, int, int64_t, bool, hipStream_t);
 template la_status launch_tile_solve<double>(View<const double>, View<double>, int64_t, int, int64_t, bool, hipStream_t);
 template la_status launch_tile_mult<float>(View<const float>, View<float>, int64_t, int, int64_t, bool, bool,
