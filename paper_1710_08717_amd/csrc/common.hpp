@@ -246,6 +246,7 @@ struct GemmOpts {
     int triB = 0;      // same on (k,j)
     int maskC = 0;     // 1: only entries with i >= j are written, 2: only i <= j
     int halfDiag = 0;  // 1: the update of entries with i == j is halved
+    int reverse = 0;   // 1: schedule the tiles last-to-first (heavy tiles of triangular work first)
 };
 template <typename T>
 la_status launch_gemm(View<const T> A, View<const T> B, View<T> C, int64_t batch, int M, int N, int K, T alpha,

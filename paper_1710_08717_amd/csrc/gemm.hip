@@ -57,18 +57,20 @@ __device__ __forceinline__ bool tri_keep(int tri, int o, int k)
 }
 
 // ---------------------------------------------------------------------------------------
-// Workgroup -> (batch item, tile) mapping shared by both kernels.  Consecutive workgroups are
-// dealt round-robin to the 8 XCDs (each with its own L2), so the 8 workgroups of one "round"
-// are given the same batch item and neighbouring tiles only after a regrouping: workgroup w
-// works on logical slot (w % 8) * (total / 8) + w / 8, which keeps each XCD on a contiguous
-// range of tiles (shared A / B panels stay in that XCD's L2).
+// Workgroup -> work slot mapping.  Consecutive workgroups are dealt round-robin to the 8 XCDs
+// (each with its own L2).  Slots are regrouped in chunks of 8 x 16: inside a chunk every XCD
+// gets 16 consecutive slots (neighbouring tiles of one tile row share their A panel in that
+// XCD's L2), while all XCDs still advance through the slot list at the same pace, which
+// matters because triangular operands make the work per tile vary along the list.
 // ---------------------------------------------------------------------------------------
 __device__ __forceinline__ int64_t xcd_slot(int64_t w, int64_t total)
 {
-    const int64_t per = total / 8;
-    if (per == 0 || w >= per * 8)
-        return w;  // tail (and tiny grids) keep their order
-    return (w % 8) * per + (w / 8);
+    constexpr int CH = 16;
+    const int64_t c = w / (8 * CH);
+    if ((c + 1) * 8 * CH > total)
+        return w;  // incomplete last chunk keeps its order
+    const int r = (int)(w % (8 * CH));
+    return c * 8 * CH + (r % 8) * CH + r / 8;
 }
 
 // ---------------------------------------------------------------------------------------
@@ -295,7 +297,7 @@ __device__ __forceinline__ void slab_commit(T *s, RV &r, int o0, int k0, int tri
 }
 
 template <typename T, int BM, int BN, int BK, int NBUF, bool AKF, bool BKF>
-__global__ __launch_bounds__(256) void k_gemm_fast(View<const T> A, View<const T> B, View<T> C, int64_t batch, int M,
+__global__ __launch_bounds__(256, 2) void k_gemm_fast(View<const T> A, View<const T> B, View<T> C, int64_t batch, int M,
                                                    int N, int K, T alpha, T beta, GemmOpts o, int tiles_m, int tiles_n)
 {
     using MF = Mfma<T>;
@@ -311,7 +313,9 @@ __global__ __launch_bounds__(256) void k_gemm_fast(View<const T> A, View<const T
     const int64_t per = (int64_t)tiles_m * tiles_n;
     const int64_t slot = xcd_slot(blockIdx.x, per * batch);
     const int64_t b = slot / per;
-    const int tile = (int)(slot % per);
+    int tile = (int)(slot % per);
+    if (o.reverse)
+        tile = (int)per - 1 - tile;  // heaviest tiles first when the work grows along the tile list
     const int tm = tile / tiles_n, tn = tile % tiles_n;
     const int i0 = tm * BM, j0 = tn * BN;
     if ((o.maskC == 1 && j0 > i0 + BM - 1) || (o.maskC == 2 && i0 > j0 + BN - 1))
@@ -430,6 +434,7 @@ la_status launch_gemm(View<const T> A, View<const T> B, View<T> C, int64_t batch
         t.triB = flip_tri(o.triA);
         t.maskC = flip_tri(o.maskC);
         t.halfDiag = o.halfDiag;
+        t.reverse = o.reverse;
         return launch_gemm<T>(B.t(), A.t(), C.t(), batch, N, M, K, alpha, beta, t, st);
     }
     constexpr int VW = Mfma<T>::VW;

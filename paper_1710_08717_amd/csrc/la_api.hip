@@ -239,6 +239,7 @@ static la_status backward_impl(View<const T> Lam, View<const T> G, View<T> W, in
     oz.triA = 1;
     oz.triB = 1;
     oz.maskC = 1;
+    oz.reverse = 1;  // K range of tile (i, j) grows with i - j: bottom rows first
     LA_TRY(launch_gemm<T>(cv(W), cv(Li), X, batch, n, n, n, T(1), T(0), oz, st));
     GemmOpts ow;
     ow.triA = 2;
