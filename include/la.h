@@ -86,6 +86,13 @@ la_status la_trmm_batched(la_dtype dt, int lower, int trans, int rightside, doub
 la_status la_syrk_batched(la_dtype dt, int trans, double alpha, int64_t batch, int n, int k,
                           const void *A, void *B, void *stream);
 
+/* gemm2 (section 4.2 "gemm2"): C = alpha * t_a(A) t_b(B), t_a(A): m x k, t_b(B): k x n.
+ * A: [batch, m, k] (ta == 0) or [batch, k, m] (ta != 0); B: [batch, k, n] (tb == 0) or
+ * [batch, n, k] (tb != 0); C: [batch, m, n].  C must not overlap A or B ("does not allow
+ * in-place computation"). */
+la_status la_gemm2_batched(la_dtype dt, int ta, int tb, double alpha, int64_t batch, int m, int n, int k,
+                           const void *A, const void *B, void *C, void *stream);
+
 /* log|L| = sum_i log l_ii (section 3.1, identity below the GP criterion code).
  * L: [batch, n, n]; out: [batch] of dt.  Plain log, no abs: a non-positive
  * diagonal gives NaN / -inf. n == 0 gives 0. */

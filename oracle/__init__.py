@@ -42,6 +42,7 @@ def _load():
         lib.orc_trmm.argtypes = [i32, i32, i32, f64, i64, i32, i32, dp, dp, dp]
         lib.orc_syrk.argtypes = [i32, f64, i64, i32, i32, dp, dp]
         lib.orc_sumlogdiag.argtypes = [i64, i32, dp, dp]
+        lib.orc_gemm2.argtypes = [i32, i32, f64, i64, i32, i32, i32, dp, dp, dp]
         lib.orc_gp_glue.argtypes = [i64, i32, dp, dp, dp, dp, dp, dp]
         lib.orc_llt_entry.argtypes = [i32, i32, dp, i32, i32]
         lib.orc_llt_entry.restype = f64
@@ -144,6 +145,17 @@ def syrk(A, trans=False, alpha=1.0):
     b = _batch_of(A, 2)
     out = np.empty(A.shape[:-2] + (n, n), dtype=np.float64)
     _check(_load().orc_syrk(int(trans), float(alpha), b, n, k, _p(A), _p(out)), "syrk")
+    return out
+
+
+def gemm2(A, B, ta=False, tb=False, alpha=1.0):
+    A, B = _f64(A), _f64(B)
+    m, k = (A.shape[-1], A.shape[-2]) if ta else (A.shape[-2], A.shape[-1])
+    n = B.shape[-2] if tb else B.shape[-1]
+    assert (B.shape[-1] if tb else B.shape[-2]) == k
+    b = _batch_of(A, 2)
+    out = np.empty(A.shape[:-2] + (m, n), dtype=np.float64)
+    _check(_load().orc_gemm2(int(ta), int(tb), float(alpha), b, m, n, k, _p(A), _p(B), _p(out)), "gemm2")
     return out
 
 

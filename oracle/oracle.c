@@ -324,6 +324,38 @@ int orc_syrk(int trans, double alpha, int64_t batch, int n, int k, const double 
 }
 
 /* ------------------------------------------------------------------------- */
+/* gemm2 forward (section 4.2, "gemm2"): C = alpha * t_a(A) t_b(B).
+ * t_a(A) is m x k, t_b(B) is k x n, C is m x n; A is stored m x k (ta == 0) or k x m (ta != 0),
+ * B is stored k x n (tb == 0) or n x k (tb != 0).  C must not overlap A or B. */
+int orc_gemm2(int ta, int tb, double alpha, int64_t batch, int m, int n, int k, const double *A,
+              const double *B, double *C)
+{
+    if (batch < 0 || m < 0 || n < 0 || k < 0)
+        return ORC_ERR_INVALID_ARG;
+    if (batch == 0 || m == 0 || n == 0)
+        return ORC_OK;
+    if (!C || (k > 0 && (!A || !B)))
+        return ORC_ERR_INVALID_ARG;
+    size_t sa = (size_t)m * k, sb = (size_t)k * n, sc = (size_t)m * n;
+#pragma omp parallel for schedule(dynamic) collapse(2)
+    for (int64_t b = 0; b < batch; ++b)
+        for (int i = 0; i < m; ++i) {
+            const double *Ab = A + b * sa, *Bb = B + b * sb;
+            double *Cb = C + b * sc;
+            for (int j = 0; j < n; ++j) {
+                double s = 0.0;
+                for (int p = 0; p < k; ++p) {
+                    double a = ta ? Ab[(size_t)p * m + i] : Ab[(size_t)i * k + p];
+                    double bb = tb ? Bb[(size_t)j * k + p] : Bb[(size_t)p * n + j];
+                    s += a * bb;
+                }
+                Cb[(size_t)i * n + j] = alpha * s;
+            }
+        }
+    return ORC_OK;
+}
+
+/* ------------------------------------------------------------------------- */
 /* log|L| = sum_i log l_ii (section 3.1, the identity below the GP code).
  * Plain log: a non-positive diagonal gives NaN / -inf as IEEE says. */
 int orc_sumlogdiag(int64_t batch, int n, const double *L, double *out)

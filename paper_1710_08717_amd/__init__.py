@@ -8,6 +8,7 @@ library is missing, importing the binding raises.
 """
 from .binding import (  # noqa: F401
     LaError,
+    gemm2,
     gp_glue,
     lib_path,
     load,
@@ -19,4 +20,4 @@ from .binding import (  # noqa: F401
     trsm,
 )
 
-__all__ = ["potrf", "potrf_backward", "trsm", "trmm", "syrk", "sumlogdiag", "gp_glue", "load", "lib_path", "LaError"]
+__all__ = ["potrf", "potrf_backward", "trsm", "trmm", "syrk", "sumlogdiag", "gp_glue", "gemm2", "load", "lib_path", "LaError"]

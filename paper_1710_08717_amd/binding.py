@@ -16,7 +16,7 @@ _lib = None
 
 SYMBOLS = [
     "la_potrf_batched", "la_potrf_backward", "la_trsm_batched", "la_trmm_batched", "la_syrk_batched",
-    "la_sumlogdiag", "la_gp_glue", "la_last_error", "la_version",
+    "la_sumlogdiag", "la_gp_glue", "la_gemm2_batched", "la_last_error", "la_version",
 ]
 
 
@@ -47,6 +47,8 @@ def load():
     lib.la_syrk_batched.argtypes = [i32, i32, f64, i64, i32, i32, vp, vp, vp]
     lib.la_sumlogdiag.argtypes = [i32, i64, i32, vp, vp, vp]
     lib.la_gp_glue.argtypes = [i32, i64, i32, vp, vp, vp, vp, vp, vp, vp]
+    lib.la_gemm2_batched.argtypes = [i32, i32, i32, f64, i64, i32, i32, i32, vp, vp, vp, vp]
+    lib.la_gemm2_batched.restype = i32
     lib.la_last_error.restype = ctypes.c_char_p
     lib.la_version.restype = i32
     for name in SYMBOLS[:7]:
@@ -160,6 +162,20 @@ def syrk(A, trans=False, alpha=1.0, out=None):
         _check(load().la_syrk_batched(_dt(A), int(trans), float(alpha), _batch(A), n, k, _ptr(A), _ptr(B), _stream(A)),
                "la_syrk_batched")
     return B
+
+
+def gemm2(A, B, ta=False, tb=False, alpha=1.0, out=None):
+    """la_gemm2_batched: C = alpha * t_a(A) t_b(B)."""
+    _chk(A, B)
+    m, k = (A.shape[-1], A.shape[-2]) if ta else (A.shape[-2], A.shape[-1])
+    n = B.shape[-2] if tb else B.shape[-1]
+    assert (B.shape[-1] if tb else B.shape[-2]) == k and _batch(A) == _batch(B)
+    C = torch.empty(A.shape[:-2] + (m, n), dtype=A.dtype, device=A.device) if out is None else out
+    _chk(A, C)
+    with torch.cuda.device(A.device):
+        _check(load().la_gemm2_batched(_dt(A), int(ta), int(tb), float(alpha), _batch(A), m, n, k, _ptr(A), _ptr(B),
+                                       _ptr(C), _stream(A)), "la_gemm2_batched")
+    return C
 
 
 def sumlogdiag(L, out=None):

@@ -247,6 +247,8 @@ struct GemmOpts {
     int maskC = 0;     // 1: only entries with i >= j are written, 2: only i <= j
     int halfDiag = 0;  // 1: the update of entries with i == j is halved
     int reverse = 0;   // 1: schedule the tiles last-to-first (heavy tiles of triangular work first)
+    int shells = 0;    // 1: square problem whose K range depends on max(i, j): schedule by shells
+    int order = 0;     // tile enumeration, chosen by the launcher
 };
 template <typename T>
 la_status launch_gemm(View<const T> A, View<const T> B, View<T> C, int64_t batch, int M, int N, int K, T alpha,

@@ -73,6 +73,58 @@ __device__ __forceinline__ int64_t xcd_slot(int64_t w, int64_t total)
     return c * 8 * CH + (r % 8) * CH + r / 8;
 }
 
+// Tile enumeration.  Workgroups go to XCDs in a fixed round-robin, so the list of tiles must be
+// (a) free of tiles that have nothing to do and (b) ordered so that the work per tile changes
+// slowly along it; then every XCD ends up with the same share.
+//   order 0: all tiles, row-major.
+//   order 1: tiles on or below the diagonal only (tn <= tm), row by row.
+//   order 2: tiles on or above the diagonal only (tm <= tn), column by column.
+//   order 3: all tiles of a square grid in "shells" max(tm, tn) = s, s ascending: every tile of
+//            a shell has the same K range when both operands are triangular.
+__device__ __forceinline__ void decode_tile(int order, int t, int tiles_n, int &tm, int &tn)
+{
+    if (order == 0) {
+        tm = t / tiles_n;
+        tn = t % tiles_n;
+    } else if (order == 3) {
+        int s_ = (int)sqrt((double)t);
+        while ((s_ + 1) * (s_ + 1) <= t)
+            ++s_;
+        while (s_ * s_ > t)
+            --s_;
+        const int r = t - s_ * s_;
+        if (r <= s_) {
+            tm = s_;
+            tn = r;
+        } else {
+            tm = r - s_ - 1;
+            tn = s_;
+        }
+    } else {
+        int a = (int)((sqrt(8.0 * (double)t + 1.0) - 1.0) * 0.5);
+        while ((a + 1) * (a + 2) / 2 <= t)
+            ++a;
+        while (a * (a + 1) / 2 > t)
+            --a;
+        const int b = t - a * (a + 1) / 2;
+        tm = order == 1 ? a : b;
+        tn = order == 1 ? b : a;
+    }
+}
+
+__device__ __forceinline__ int64_t tile_count_dev(int order, int tiles_m, int tiles_n)
+{
+    if (order == 1 || order == 2)
+        return (int64_t)tiles_m * (tiles_m + 1) / 2;
+    return (int64_t)tiles_m * tiles_n;
+}
+static inline int64_t tile_count(int order, int tiles_m, int tiles_n)
+{
+    if (order == 1 || order == 2)
+        return (int64_t)tiles_m * (tiles_m + 1) / 2;
+    return (int64_t)tiles_m * tiles_n;
+}
+
 // ---------------------------------------------------------------------------------------
 // Fallback kernel: element-wise staging, any strides / sizes.
 // ---------------------------------------------------------------------------------------
@@ -149,10 +201,13 @@ __global__ __launch_bounds__(256) void k_gemm(View<const T> A, View<const T> B, 
     __shared__ T sB[Cfg::B_ELEMS];
 
     const int64_t bid = blockIdx.x;
-    const int64_t per = (int64_t)tiles_m * tiles_n;
+    const int64_t per = tile_count_dev(o.order, tiles_m, tiles_n);
     const int64_t b = bid / per;
-    const int tile = (int)(bid % per);
-    const int tm = tile / tiles_n, tn = tile % tiles_n;
+    int tile = (int)(bid % per);
+    if (o.reverse)
+        tile = (int)per - 1 - tile;
+    int tm, tn;
+    decode_tile(o.order, tile, tiles_n, tm, tn);
     const int i0 = tm * BM, j0 = tn * BN;
     if ((o.maskC == 1 && j0 > i0 + BM - 1) || (o.maskC == 2 && i0 > j0 + BN - 1))
         return;  // tile entirely on the masked side of the diagonal
@@ -310,13 +365,14 @@ __global__ __launch_bounds__(256, 2) void k_gemm_fast(View<const T> A, View<cons
     __shared__ __align__(16) T sA[NBUF][SA::ELEMS];
     __shared__ __align__(16) T sB[NBUF][SB::ELEMS];
 
-    const int64_t per = (int64_t)tiles_m * tiles_n;
+    const int64_t per = tile_count_dev(o.order, tiles_m, tiles_n);
     const int64_t slot = xcd_slot(blockIdx.x, per * batch);
     const int64_t b = slot / per;
     int tile = (int)(slot % per);
     if (o.reverse)
         tile = (int)per - 1 - tile;  // heaviest tiles first when the work grows along the tile list
-    const int tm = tile / tiles_n, tn = tile % tiles_n;
+    int tm, tn;
+    decode_tile(o.order, tile, tiles_n, tm, tn);
     const int i0 = tm * BM, j0 = tn * BN;
     if ((o.maskC == 1 && j0 > i0 + BM - 1) || (o.maskC == 2 && i0 > j0 + BN - 1))
         return;
@@ -398,12 +454,24 @@ static bool aligned16(const View<const T> &V, int64_t lead)
     return (reinterpret_cast<uintptr_t>(V.p) & 15) == 0 && (lead % VW) == 0 && (V.bs % VW) == 0 && (V.bs2 % VW) == 0;
 }
 
+static inline int pick_order(const GemmOpts &o, int tiles_m, int tiles_n)
+{
+    if (tiles_m != tiles_n)
+        return 0;
+    if (o.maskC == 1)
+        return 1;
+    if (o.maskC == 2)
+        return 2;
+    return o.shells ? 3 : 0;
+}
+
 template <typename T, int BM, int BN, int BK, int NBUF>
 static void launch_fast(bool akf, bool bkf, View<const T> A, View<const T> B, View<T> C, int64_t batch, int M, int N,
                         int K, T alpha, T beta, GemmOpts o, hipStream_t st)
 {
     const int tiles_m = (M + BM - 1) / BM, tiles_n = (N + BN - 1) / BN;
-    const dim3 grid((unsigned)((int64_t)tiles_m * tiles_n * batch)), block(256);
+    o.order = pick_order(o, tiles_m, tiles_n);
+    const dim3 grid((unsigned)(tile_count(o.order, tiles_m, tiles_n) * batch)), block(256);
 #define LA_GO(AK, BKF_)                                                                                              \
     hipLaunchKernelGGL((k_gemm_fast<T, BM, BN, BK, NBUF, AK, BKF_>), grid, block, 0, st, A, B, C, batch, M, N, K,    \
                        alpha, beta, o, tiles_m, tiles_n)
@@ -435,6 +503,7 @@ la_status launch_gemm(View<const T> A, View<const T> B, View<T> C, int64_t batch
         t.maskC = flip_tri(o.maskC);
         t.halfDiag = o.halfDiag;
         t.reverse = o.reverse;
+        t.shells = o.shells;
         return launch_gemm<T>(B.t(), A.t(), C.t(), batch, N, M, K, alpha, beta, t, st);
     }
     constexpr int VW = Mfma<T>::VW;
@@ -456,7 +525,8 @@ la_status launch_gemm(View<const T> A, View<const T> B, View<T> C, int64_t batch
     }
     constexpr int BM = 64, BN = 64, BK = 16;
     const int tiles_m = (M + BM - 1) / BM, tiles_n = (N + BN - 1) / BN;
-    const int64_t blocks = (int64_t)tiles_m * tiles_n * batch;
+    o.order = pick_order(o, tiles_m, tiles_n);
+    const int64_t blocks = tile_count(o.order, tiles_m, tiles_n) * batch;
     if (blocks > 0x7fffffffll)
         return LA_ERR_UNSUPPORTED;
     hipLaunchKernelGGL((k_gemm<T, BM, BN, BK>), dim3((unsigned)blocks), dim3(256), 0, st, A, B, C, batch, M, N, K,

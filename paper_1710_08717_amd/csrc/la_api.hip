@@ -244,6 +244,7 @@ static la_status backward_impl(View<const T> Lam, View<const T> G, View<T> W, in
     GemmOpts ow;
     ow.triA = 2;
     ow.triB = 1;
+    ow.shells = 1;  // K range of tile (i, j) starts at max(i, j)
     LA_TRY(launch_gemm<T>(cv(Li).t(), cv(X), W, batch, n, n, n, T(1), T(0), ow, st));
     return launch_symmetrize<T>(W, batch, n, T(0.5), st);
 }
@@ -315,6 +316,18 @@ static la_status syrk_t(int trans, double alpha, int64_t batch, int n, int k, co
     o.maskC = 1;
     LA_TRY(launch_gemm<T>(Ank, Ank.t(), C, batch, n, n, k, (T)alpha, T(0), o, st));
     return launch_mirror_lower<T>(C, batch, n, st);
+}
+
+template <typename T>
+static la_status gemm2_t(int ta, int tb, double alpha, int64_t batch, int m, int n, int k, const void *A, const void *B,
+                         void *C, hipStream_t st)
+{
+    const int64_t sa = (int64_t)m * k, sb = (int64_t)k * n, sc = (int64_t)m * n;
+    View<const T> Av = ta ? View<const T>{(const T *)A, sa, 1, m} : View<const T>{(const T *)A, sa, k, 1};  // m x k
+    View<const T> Bv = tb ? View<const T>{(const T *)B, sb, 1, k} : View<const T>{(const T *)B, sb, n, 1};  // k x n
+    View<T> Cv{(T *)C, sc, n, 1};
+    GemmOpts o;
+    return launch_gemm<T>(Av, Bv, Cv, batch, m, n, k, (T)alpha, T(0), o, st);
 }
 
 }  // namespace la
@@ -408,6 +421,24 @@ la_status la_syrk_batched(la_dtype dt, int trans, double alpha, int64_t batch, i
     hipStream_t st = (hipStream_t)stream;
     return dt == LA_F32 ? syrk_t<float>(trans, alpha, batch, n, k, A, B, st)
                         : syrk_t<double>(trans, alpha, batch, n, k, A, B, st);
+}
+
+la_status la_gemm2_batched(la_dtype dt, int ta, int tb, double alpha, int64_t batch, int m, int n, int k, const void *A,
+                           const void *B, void *C, void *stream)
+{
+    if (bad_dtype(dt) || batch < 0 || m < 0 || n < 0 || k < 0 || m > MAX_N || n > MAX_N || k > MAX_N)
+        return LA_ERR_INVALID_ARG;
+    if (batch == 0 || m == 0 || n == 0)
+        return LA_OK;
+    if (!C || (k > 0 && (!A || !B)))
+        return LA_ERR_INVALID_ARG;
+    const size_t ab = (size_t)batch * m * k * esize(dt), bb = (size_t)batch * k * n * esize(dt),
+                 cb = (size_t)batch * m * n * esize(dt);
+    if (k > 0 && (overlap(A, ab, C, cb) || overlap(B, bb, C, cb)))
+        return LA_ERR_INVALID_ARG;
+    hipStream_t st = (hipStream_t)stream;
+    return dt == LA_F32 ? gemm2_t<float>(ta, tb, alpha, batch, m, n, k, A, B, C, st)
+                        : gemm2_t<double>(ta, tb, alpha, batch, m, n, k, A, B, C, st);
 }
 
 la_status la_sumlogdiag(la_dtype dt, int64_t batch, int n, const void *L, void *out, void *stream)

@@ -300,6 +300,23 @@ def test_syrk_parity(la, orc, dtype, trans, n, k):
 
 
 @pytest.mark.parametrize("dtype", ["f64", "f32"])
+@pytest.mark.parametrize("ta", [False, True])
+@pytest.mark.parametrize("tb", [False, True])
+@pytest.mark.parametrize("m,n,k", [(1, 1, 1), (5, 7, 3), (64, 64, 64), (130, 70, 96), (256, 384, 128), (200, 64, 0)])
+def test_gemm2_parity(la, orc, dtype, ta, tb, m, n, k):
+    batch = 3
+    rng = np.random.default_rng(m + 3 * n + 7 * k)
+    A = rng.standard_normal((batch, k, m) if ta else (batch, m, k)).astype(npdt(dtype))
+    B = rng.standard_normal((batch, n, k) if tb else (batch, k, n)).astype(npdt(dtype))
+    ref = orc.gemm2(A, B, ta=ta, tb=tb, alpha=1.5)
+    out = host(la.gemm2(dev(A), dev(B), ta=ta, tb=tb, alpha=1.5))
+    if k == 0:
+        assert np.all(out == 0)
+    else:
+        assert relerr(out, ref) <= TOL[dtype]
+
+
+@pytest.mark.parametrize("dtype", ["f64", "f32"])
 @pytest.mark.parametrize("n", [1, 16, 32, 100, 1000])
 def test_sumlogdiag_parity(la, orc, dtype, n):
     batch = 9

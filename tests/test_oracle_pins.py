@@ -326,6 +326,17 @@ def test_syrk_of_factor_gives_back_matrix(orc):
     assert relerr(orc.syrk(R, trans=True), A) < 1e-14
 
 
+@pytest.mark.parametrize("ta", [False, True])
+@pytest.mark.parametrize("tb", [False, True])
+@pytest.mark.parametrize("m,n,k", [(1, 1, 1), (3, 5, 4), (7, 2, 9)])
+def test_gemm2_against_numpy(orc, ta, tb, m, n, k):
+    rng = np.random.default_rng(m * 100 + n * 10 + k)
+    A = rng.standard_normal((2, k, m) if ta else (2, m, k))
+    B = rng.standard_normal((2, n, k) if tb else (2, k, n))
+    ref = -0.5 * (op(A, ta) @ op(B, tb))
+    assert relerr(orc.gemm2(A, B, ta=ta, tb=tb, alpha=-0.5), ref) < 1e-14
+
+
 # ----------------------------------------------------------------------------
 # potrf backward
 # ----------------------------------------------------------------------------
