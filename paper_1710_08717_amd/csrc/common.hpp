@@ -216,6 +216,12 @@ template <typename T>
 la_status launch_potrf_tiny(View<const T> A, View<T> L, int32_t *info, int info_off, int64_t batch, int nb,
                             hipStream_t st);
 
+// potrf of blocks of edge nb <= 64 together with the inverse of the factor (written to Inv,
+// lower triangle, zeros above inside the block); one workgroup per block.
+template <typename T>
+la_status launch_potrf_leaf(View<const T> A, View<T> L, View<T> Inv, int32_t *info, int info_off, int64_t batch, int nb,
+                            hipStream_t st);
+
 // Register-resident potrf backward for n <= 32: Abar = sym(L^-T Phi(L^T Lbar) L^-1).
 template <typename T>
 la_status launch_backward_tiny(View<const T> L, View<const T> G, View<T> Abar, int64_t batch, int n,

@@ -186,11 +186,8 @@ static la_status mult_rec(View<const T> Lam, View<T> X, int64_t batch, int n, in
 template <typename T>
 static la_status potrf_rec(View<T> W, int32_t *info, int off, int64_t batch, int n, View<T> Inv, hipStream_t st)
 {
-    if (n <= NB) {
-        LA_TRY(launch_potrf_tiny<T>(cv(W), W, info, off, batch, n, st));
-        // the inverse of the fresh diagonal block serves every later panel solve against it
-        return launch_tile_inverse<T>(cv(W), Inv, batch, n, st);
-    }
+    if (n <= NB)  // factor and inverse in one launch: the inverse serves every later panel solve
+        return launch_potrf_leaf<T>(cv(W), W, Inv, info, off, batch, n, st);
     const int n1 = split_point(n), n2 = n - n1;
     View<T> W21 = W.sub(n1, 0), W22 = W.sub(n1, n1);
     LA_TRY(potrf_rec<T>(W, info, off, batch, n1, Inv, st));
