@@ -15,16 +15,19 @@
 
 namespace la {
 
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef double f64x2 __attribute__((ext_vector_type(2)));
+
 template <typename T>
 struct VecOf;
 template <>
 struct VecOf<float> {
-    using type = float4;
+    using type = f32x4;
     static constexpr int N = 4;
 };
 template <>
 struct VecOf<double> {
-    using type = double2;
+    using type = f64x2;
     static constexpr int N = 2;
 };
 
@@ -63,6 +66,9 @@ __device__ __forceinline__ bool flat_ok(const T *p, int64_t bs, int64_t ld, int6
 
 // Fill the stage from global memory, in memory order.  Matrix q of the wave is item
 // (b0 + q); entries outside nb x nb, and whole matrices past the batch end, become identity.
+// (Leaving out the 16-byte pieces that lie entirely in the unused triangle was tried: the HBM
+// fetch counter did not move -- rows are fetched in units of at least 64 bytes -- and the
+// predicated loads made the kernels slower.)
 template <typename T, int G>
 __device__ __forceinline__ void stage_load(T *sm, Mem<const T> M, int64_t b0, int64_t batch, int nb)
 {
@@ -78,7 +84,8 @@ __device__ __forceinline__ void stage_load(T *sm, Mem<const T> M, int64_t b0, in
         for (int t = 0; t < NV / WAVE; ++t) {
             int e = (t * WAVE + lane) * VN;
             int q = e / (G * G), r = (e / G) % G, c = e % G;
-            *reinterpret_cast<V4 *>(sm + q * S::MS + r * S::LD + c) = src[t * WAVE + lane];
+            // streamed once: non-temporal, so the lines do not linger in the caches
+            *reinterpret_cast<V4 *>(sm + q * S::MS + r * S::LD + c) = __builtin_nontemporal_load(&src[t * WAVE + lane]);
         }
         return;
     }
@@ -108,7 +115,8 @@ __device__ __forceinline__ void stage_store(const T *sm, Mem<T> M, int64_t b0, i
         for (int t = 0; t < NV / WAVE; ++t) {
             int e = (t * WAVE + lane) * VN;
             int q = e / (G * G), r = (e / G) % G, c = e % G;
-            dst[t * WAVE + lane] = *reinterpret_cast<const V4 *>(sm + q * S::MS + r * S::LD + c);
+            __builtin_nontemporal_store(*reinterpret_cast<const V4 *>(sm + q * S::MS + r * S::LD + c),
+                                        &dst[t * WAVE + lane]);
         }
         return;
     }
