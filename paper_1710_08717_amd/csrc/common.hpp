@@ -191,6 +191,38 @@ __device__ __forceinline__ void dpp_settle1(T &v)
     }
 }
 
+// 16x16x4 matrix-core instruction of each element type and where its operands live:
+// lane l supplies A(l % 16, l / 16) and B(l / 16, l % 16); accumulator register v of lane l
+// holds D(row(l, v), l % 16).
+typedef double d4_t __attribute__((ext_vector_type(4)));
+typedef float f4_t __attribute__((ext_vector_type(4)));
+
+template <typename T>
+struct Mfma;
+template <>
+struct Mfma<double> {
+    using acc_t = d4_t;
+    using vec_t = double2;
+    static constexpr int VW = 2;
+    static __device__ __forceinline__ acc_t run(double a, double b, acc_t c)
+    {
+        return __builtin_amdgcn_mfma_f64_16x16x4f64(a, b, c, 0, 0, 0);
+    }
+    // accumulator register v of lane l holds D[row][l % 16]
+    static __device__ __forceinline__ int row(int l, int v) { return (l >> 4) + 4 * v; }
+};
+template <>
+struct Mfma<float> {
+    using acc_t = f4_t;
+    using vec_t = float4;
+    static constexpr int VW = 4;
+    static __device__ __forceinline__ acc_t run(float a, float b, acc_t c)
+    {
+        return __builtin_amdgcn_mfma_f32_16x16x4f32(a, b, c, 0, 0, 0);
+    }
+    static __device__ __forceinline__ int row(int l, int v) { return 4 * (l >> 4) + v; }
+};
+
 // Reciprocal square root and reciprocal accurate to a few ulp of T.
 __device__ __forceinline__ float rsqrt_acc(float x) { return __builtin_amdgcn_rsqf(x); }
 __device__ __forceinline__ double rsqrt_acc(double x)
@@ -216,8 +248,9 @@ template <typename T>
 la_status launch_potrf_tiny(View<const T> A, View<T> L, int32_t *info, int info_off, int64_t batch, int nb,
                             hipStream_t st);
 
-// potrf of blocks of edge nb <= 64 together with the inverse of the factor (written to Inv,
-// lower triangle, zeros above inside the block); one workgroup per block.
+// potrf of blocks of edge nb <= 128 together with the inverse of the factor (written to Inv,
+// lower triangle; zeros above the diagonal inside the 64 x 64 diagonal sub-blocks); one
+// workgroup per block.  L's block (0,1) of a 128-block is NOT written (the caller zeroed it).
 template <typename T>
 la_status launch_potrf_leaf(View<const T> A, View<T> L, View<T> Inv, int32_t *info, int info_off, int64_t batch, int nb,
                             hipStream_t st);
@@ -255,10 +288,14 @@ struct GemmOpts {
     int reverse = 0;   // 1: schedule the tiles last-to-first (heavy tiles of triangular work first)
     int shells = 0;    // 1: square problem whose K range depends on max(i, j): schedule by shells
     int order = 0;     // tile enumeration, chosen by the launcher
+    int force128 = 0;  // 1: use 128 x 128 workgroup tiles whatever the grid size
 };
 template <typename T>
 la_status launch_gemm(View<const T> A, View<const T> B, View<T> C, int64_t batch, int M, int N, int K, T alpha,
                       T beta, GemmOpts o, hipStream_t st);
+
+template <typename T>
+bool gemm_fast_eligible(View<const T> A, View<const T> B, View<T> C, int M, int N, int K);
 
 // Element-wise helpers.
 // dst(i,j) = alpha * src(i,j) on rows x cols; keep: 0 all, 1 only i >= j (rest written as 0).

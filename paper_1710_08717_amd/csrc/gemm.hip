@@ -21,35 +21,6 @@
 
 namespace la {
 
-typedef double d4_t __attribute__((ext_vector_type(4)));
-typedef float f4_t __attribute__((ext_vector_type(4)));
-
-template <typename T>
-struct Mfma;
-template <>
-struct Mfma<double> {
-    using acc_t = d4_t;
-    using vec_t = double2;
-    static constexpr int VW = 2;
-    static __device__ __forceinline__ acc_t run(double a, double b, acc_t c)
-    {
-        return __builtin_amdgcn_mfma_f64_16x16x4f64(a, b, c, 0, 0, 0);
-    }
-    // accumulator register v of lane l holds D[row][l % 16]
-    static __device__ __forceinline__ int row(int l, int v) { return (l >> 4) + 4 * v; }
-};
-template <>
-struct Mfma<float> {
-    using acc_t = f4_t;
-    using vec_t = float4;
-    static constexpr int VW = 4;
-    static __device__ __forceinline__ acc_t run(float a, float b, acc_t c)
-    {
-        return __builtin_amdgcn_mfma_f32_16x16x4f32(a, b, c, 0, 0, 0);
-    }
-    static __device__ __forceinline__ int row(int l, int v) { return 4 * (l >> 4) + v; }
-};
-
 __device__ __forceinline__ bool tri_keep(int tri, int o, int k)
 {
     // tri 1 keeps o >= k, tri 2 keeps o <= k
@@ -488,6 +459,22 @@ static void launch_fast(bool akf, bool bkf, View<const T> A, View<const T> B, Vi
 
 static inline int flip_tri(int t) { return t == 1 ? 2 : (t == 2 ? 1 : 0); }
 
+// Would launch_gemm take the vectorised kernel for these operands?  (Callers that update C in
+// place along a dimension of up to 128 rely on one 128 x 128 tile covering that dimension.)
+template <typename T>
+bool gemm_fast_eligible(View<const T> A, View<const T> B, View<T> C, int M, int N, int K)
+{
+    if (C.cs != 1 && C.rs == 1)
+        return gemm_fast_eligible<T>(B.t(), A.t(), C.t(), N, M, K);
+    constexpr int VW = Mfma<T>::VW;
+    const bool akf = (A.cs == 1), bkf = (B.rs == 1);
+    const bool a_ok = akf ? aligned16<T>(A, A.rs) : (A.rs == 1 && aligned16<T>(A, A.cs) && M % VW == 0);
+    const bool b_ok = bkf ? aligned16<T>(B, B.cs) : (B.cs == 1 && aligned16<T>(B, B.rs) && N % VW == 0);
+    return K > 0 && K % 16 == 0 && a_ok && b_ok;
+}
+template bool gemm_fast_eligible<float>(View<const float>, View<const float>, View<float>, int, int, int);
+template bool gemm_fast_eligible<double>(View<const double>, View<const double>, View<double>, int, int, int);
+
 template <typename T>
 la_status launch_gemm(View<const T> A, View<const T> B, View<T> C, int64_t batch, int M, int N, int K, T alpha, T beta,
                       GemmOpts o, hipStream_t st)
@@ -504,6 +491,7 @@ la_status launch_gemm(View<const T> A, View<const T> B, View<T> C, int64_t batch
         t.halfDiag = o.halfDiag;
         t.reverse = o.reverse;
         t.shells = o.shells;
+        t.force128 = o.force128;
         return launch_gemm<T>(B.t(), A.t(), C.t(), batch, N, M, K, alpha, beta, t, st);
     }
     constexpr int VW = Mfma<T>::VW;
@@ -515,7 +503,7 @@ la_status launch_gemm(View<const T> A, View<const T> B, View<T> C, int64_t batch
         const int64_t t64 = (int64_t)((M + 63) / 64) * ((N + 63) / 64) * batch;
         if (t64 > 0x7fffffffll)
             return LA_ERR_UNSUPPORTED;
-        if (t128 >= 192 && M >= 128 && N >= 128)
+        if (o.force128 || (t128 >= 192 && M >= 128 && N >= 128))
             launch_fast<T, 128, 128, 16, 2>(akf, bkf, A, B, C, batch, M, N, K, alpha, beta, o, st);
         else if (K % 64 == 0)  // small grids are latency bound: fewer, fatter K slabs
             launch_fast<T, 64, 64, 64, 1>(akf, bkf, A, B, C, batch, M, N, K, alpha, beta, o, st);

@@ -135,26 +135,37 @@ static la_status inverse_build(View<const T> Lam, View<T> Inv, View<T> Tmp, int6
 // diagonal block (Inv, whose diagonal 64-blocks hold those inverses), a product multiplies by
 // the masked block itself.  In place is safe there because one workgroup tile covers all
 // n <= 64 rows of its vectors.
+// leaf128: the 128 x 128 diagonal blocks of Inv hold complete inverses (true for a factor that
+// the blocked potrf has just produced); a block of exactly 128 is then one in-place GEMM too,
+// with a single 128 x 128 tile covering its rows.
 template <typename T>
 static la_status solve_rec(View<const T> Lam, View<T> X, int64_t batch, int n, int64_t nvec, bool fwd,
-                           View<const T> Inv, hipStream_t st)
+                           View<const T> Inv, bool leaf128, hipStream_t st)
 {
     GemmOpts o;
     if (n <= NB) {
         o.triA = fwd ? 1 : 2;
         return launch_gemm<T>(fwd ? Inv : Inv.t(), cv(X), X, batch, n, (int)nvec, n, T(1), T(0), o, st);
     }
+    if (leaf128 && n == 2 * NB) {
+        View<const T> Iv = fwd ? Inv : Inv.t();
+        if (gemm_fast_eligible<T>(Iv, cv(X), X, n, (int)nvec, n)) {
+            o.triA = fwd ? 1 : 2;
+            o.force128 = 1;
+            return launch_gemm<T>(Iv, cv(X), X, batch, n, (int)nvec, n, T(1), T(0), o, st);
+        }
+    }
     const int n1 = split_point(n), n2 = n - n1;
     View<const T> L11 = Lam, L21 = Lam.sub(n1, 0), L22 = Lam.sub(n1, n1);
     View<T> X1 = X, X2 = X.sub(n1, 0);
     if (fwd) {
-        LA_TRY(solve_rec<T>(L11, X1, batch, n1, nvec, true, Inv, st));
+        LA_TRY(solve_rec<T>(L11, X1, batch, n1, nvec, true, Inv, leaf128, st));
         LA_TRY(launch_gemm<T>(L21, cv(X1), X2, batch, n2, (int)nvec, n1, T(-1), T(1), o, st));
-        return solve_rec<T>(L22, X2, batch, n2, nvec, true, Inv.sub(n1, n1), st);
+        return solve_rec<T>(L22, X2, batch, n2, nvec, true, Inv.sub(n1, n1), leaf128, st);
     }
-    LA_TRY(solve_rec<T>(L22, X2, batch, n2, nvec, false, Inv.sub(n1, n1), st));
+    LA_TRY(solve_rec<T>(L22, X2, batch, n2, nvec, false, Inv.sub(n1, n1), leaf128, st));
     LA_TRY(launch_gemm<T>(L21.t(), cv(X2), X1, batch, n1, (int)nvec, n2, T(-1), T(1), o, st));
-    return solve_rec<T>(L11, X1, batch, n1, nvec, false, Inv, st);
+    return solve_rec<T>(L11, X1, batch, n1, nvec, false, Inv, leaf128, st);
 }
 
 template <typename T>
@@ -186,13 +197,13 @@ static la_status mult_rec(View<const T> Lam, View<T> X, int64_t batch, int n, in
 template <typename T>
 static la_status potrf_rec(View<T> W, int32_t *info, int off, int64_t batch, int n, View<T> Inv, hipStream_t st)
 {
-    if (n <= NB)  // factor and inverse in one launch: the inverse serves every later panel solve
+    if (n <= 2 * NB)  // factor and inverse in one launch: the inverse serves every later panel solve
         return launch_potrf_leaf<T>(cv(W), W, Inv, info, off, batch, n, st);
     const int n1 = split_point(n), n2 = n - n1;
     View<T> W21 = W.sub(n1, 0), W22 = W.sub(n1, n1);
     LA_TRY(potrf_rec<T>(W, info, off, batch, n1, Inv, st));
     // panel: L21 = A21 L11^-T, i.e. every row x of the panel solves L11 x^T = a^T
-    LA_TRY(solve_rec<T>(cv(W), W21.t(), batch, n1, n2, true, cv(Inv), st));
+    LA_TRY(solve_rec<T>(cv(W), W21.t(), batch, n1, n2, true, cv(Inv), true, st));
     // trailing update of the lower triangle: A22 -= L21 L21^T
     GemmOpts o;
     o.maskC = 1;
@@ -300,7 +311,7 @@ static la_status tri_apply_t(bool solve, int lower, int trans, int rightside, do
     View<T> Inv;
     LA_TRY(scratch_views<T>(batch, n, 1, &Inv));
     LA_TRY(launch_tile_inverse<T>(Lam, Inv, batch, n, st));
-    return solve_rec<T>(Lam, X, batch, n, m, fwd, cv(Inv), st);
+    return solve_rec<T>(Lam, X, batch, n, m, fwd, cv(Inv), false, st);
 }
 
 template <typename T>

@@ -19,36 +19,21 @@ constexpr int LEAF_CW = 4;                    // columns per thread
 constexpr int LEAF_GR = NB / LEAF_CW;         // column groups (threads per row)
 constexpr int LEAF_THREADS = NB * LEAF_GR;    // 1024
 
+// The 64 pivot steps on the calling workgroup's registers: a[] (row r, columns CW*g ..) holds the
+// lower triangle of the block on entry and the factor on exit, x[] the identity on entry and
+// the inverse of the factor on exit.  fail_base + (failing column + 1) goes to *s_fail once.
 template <typename T>
-__global__ __launch_bounds__(LEAF_THREADS) void k_potrf_leaf(View<const T> A, View<T> L, View<T> Inv, int32_t *info,
-                                                    int info_off, int64_t batch, int nb)
+__device__ __forceinline__ void leaf_factor(T (&a)[LEAF_CW], T (&x)[LEAF_CW], T (*colbuf)[NB], T (*rowbuf)[NB],
+                                            int *s_fail, int fail_base)
 {
-    __shared__ T colbuf[2][NB];
-    __shared__ T rowbuf[2][NB];
-    __shared__ int s_fail;
-    const int tid = threadIdx.x;
     constexpr int CW = LEAF_CW, GR = LEAF_GR;
+    const int tid = threadIdx.x;
     const int r = tid / GR, g = tid % GR;
-    const int64_t b = blockIdx.x;
-    const T *ap = A.p + b * A.bs;
-    if (tid == 0)
-        s_fail = 0;
-
-    // my CW entries of row r (lower triangle only; identity outside nb x nb).  a[] is the working
-    // copy, lf[] receives the finished entries of L, x[] is the inverse under construction.
-    T a[CW], lf[CW], x[CW];
+    T lf[CW];
     T myrs = T(1);
 #pragma unroll
-    for (int c = 0; c < CW; ++c) {
-        const int col = g * CW + c;
-        T v = (col == r) ? T(1) : T(0);
-        if (r < nb && col <= r)
-            v = ap[(int64_t)r * A.rs + (int64_t)col * A.cs];
-        a[c] = v;
+    for (int c = 0; c < CW; ++c)
         lf[c] = T(0);
-        x[c] = (col == r) ? T(1) : T(0);
-    }
-
     // Only clean values are ever broadcast: the column slot gets zeros for rows above the pivot,
     // and rows of the inverse are zero beyond their diagonal by construction.  The updates
     // below therefore need no masks: what they do to register entries above the diagonal, or to
@@ -68,8 +53,8 @@ __global__ __launch_bounds__(LEAF_THREADS) void k_potrf_leaf(View<const T> A, Vi
             }
             __syncthreads();
             const T akk = colbuf[slot][k];
-            if (tid == 0 && !(akk > T(0)) && s_fail == 0)
-                s_fail = k + 1;
+            if (tid == 0 && !(akk > T(0)) && *s_fail == 0)
+                *s_fail = fail_base + k + 1;
             const T rs = rsqrt_acc(akk);
             const T ark = colbuf[slot][r];
             const T t = (r > k) ? ark * (rs * rs) : T(0);  // a_rk / a_kk
@@ -100,6 +85,36 @@ __global__ __launch_bounds__(LEAF_THREADS) void k_potrf_leaf(View<const T> A, Vi
         a[c] = lf[c];
         x[c] *= myrs;
     }
+    __syncthreads();  // the broadcast slots may be reused by the caller
+}
+
+template <typename T>
+__global__ __launch_bounds__(LEAF_THREADS) void k_potrf_leaf(View<const T> A, View<T> L, View<T> Inv, int32_t *info,
+                                                             int info_off, int64_t batch, int nb)
+{
+    __shared__ T colbuf[2][NB];
+    __shared__ T rowbuf[2][NB];
+    __shared__ int s_fail;
+    constexpr int CW = LEAF_CW, GR = LEAF_GR;
+    const int tid = threadIdx.x;
+    const int r = tid / GR, g = tid % GR;
+    const int64_t b = blockIdx.x;
+    const T *ap = A.p + b * A.bs;
+    if (tid == 0)
+        s_fail = 0;
+
+    // my CW entries of row r (lower triangle only; identity outside nb x nb)
+    T a[CW], x[CW];
+#pragma unroll
+    for (int c = 0; c < CW; ++c) {
+        const int col = g * CW + c;
+        T v = (col == r) ? T(1) : T(0);
+        if (r < nb && col <= r)
+            v = ap[(int64_t)r * A.rs + (int64_t)col * A.cs];
+        a[c] = v;
+        x[c] = (col == r) ? T(1) : T(0);
+    }
+    leaf_factor<T>(a, x, colbuf, rowbuf, &s_fail, 0);
 
     T *lp = L.p + b * L.bs;
     T *ip = Inv.p + b * Inv.bs;
@@ -117,15 +132,156 @@ __global__ __launch_bounds__(LEAF_THREADS) void k_potrf_leaf(View<const T> A, Vi
     }
 }
 
+// ---------------------------------------------------------------------------------------
+// Blocks of edge 64 < nb <= 128 in one launch: [A00 0; A10 A11] with 64 x 64 sub-blocks,
+//   L00, Li00 = factor(A00);  L10 = A10 Li00^T;  L11, Li11 = factor(A11 - L10 L10^T);
+//   Li10 = -Li11 (L10 Li00)
+// The four 64 x 64 x 64 products run on the matrix cores, one 16 x 16 output tile per
+// wavefront, operands in LDS.
+// ---------------------------------------------------------------------------------------
+constexpr int LEAF_LD = NB + 1;
+
+// 16 x 16 tile (ti, tj) of  sum_k A(i,k) B(k,j)  with A(i,k) = sA[i*a_si + k*a_sk], B(k,j) = sB[k*b_sk + j*b_sj]
+template <typename T>
+__device__ __forceinline__ typename Mfma<T>::acc_t leaf_product(const T *sA, int a_si, int a_sk, const T *sB, int b_sk,
+                                                                 int b_sj, int ti, int tj, int lane)
+{
+    using MF = Mfma<T>;
+    typename MF::acc_t acc = {0, 0, 0, 0};
+    const int l16 = lane & 15, lk = lane >> 4;
+#pragma unroll
+    for (int kk = 0; kk < NB; kk += 4) {
+        const T av = sA[(ti * 16 + l16) * a_si + (kk + lk) * a_sk];
+        const T bv = sB[(kk + lk) * b_sk + (tj * 16 + l16) * b_sj];
+        acc = MF::run(av, bv, acc);
+    }
+    return acc;
+}
+
+template <typename T>
+__global__ __launch_bounds__(LEAF_THREADS) void k_potrf_leaf128(View<const T> A, View<T> L, View<T> Inv, int32_t *info,
+                                                                int info_off, int64_t batch, int nb)
+{
+    using MF = Mfma<T>;
+    __shared__ T sLi0[NB * LEAF_LD];
+    __shared__ T sLi1[NB * LEAF_LD];
+    __shared__ T sB1[NB * LEAF_LD];  // A10, then L10
+    __shared__ T sC[NB * LEAF_LD];   // A11 - L10 L10^T, then L10 Li00
+    __shared__ T colbuf[2][NB];
+    __shared__ T rowbuf[2][NB];
+    __shared__ int s_fail;
+    constexpr int CW = LEAF_CW, GR = LEAF_GR, LD = LEAF_LD;
+    const int tid = threadIdx.x;
+    const int r = tid / GR, g = tid % GR;
+    const int lane = tid & 63, w = tid >> 6;
+    const int ti = w >> 2, tj = w & 3;
+    const int l16 = lane & 15;
+    const int n2 = nb - NB;  // rows of the second block (1 .. 64)
+    const int64_t b = blockIdx.x;
+    const T *ap = A.p + b * A.bs;
+    T *lp = L.p + b * L.bs;
+    T *ip = Inv.p + b * Inv.bs;
+    if (tid == 0)
+        s_fail = 0;
+
+    // ---- block (0,0) --------------------------------------------------------------------
+    T a[CW], x[CW];
+#pragma unroll
+    for (int c = 0; c < CW; ++c) {
+        const int col = g * CW + c;
+        a[c] = (col <= r) ? ap[(int64_t)r * A.rs + (int64_t)col * A.cs] : T(0);
+        x[c] = (col == r) ? T(1) : T(0);
+        // A10 for the panel product (rows past the end of the block read as zero)
+        sB1[r * LD + col] = (r < n2) ? ap[(int64_t)(NB + r) * A.rs + (int64_t)col * A.cs] : T(0);
+    }
+    leaf_factor<T>(a, x, colbuf, rowbuf, &s_fail, 0);
+#pragma unroll
+    for (int c = 0; c < CW; ++c) {
+        const int col = g * CW + c;
+        const T lv = (col <= r) ? a[c] : T(0), iv = (col <= r) ? x[c] : T(0);
+        lp[(int64_t)r * L.rs + (int64_t)col * L.cs] = lv;
+        ip[(int64_t)r * Inv.rs + (int64_t)col * Inv.cs] = iv;
+        sLi0[r * LD + col] = iv;
+    }
+    __syncthreads();
+
+    // ---- panel: L10 = A10 Li00^T ------------------------------------------------------------
+    typename MF::acc_t acc = leaf_product<T>(sB1, LD, 1, sLi0, 1, LD, ti, tj, lane);
+    __syncthreads();  // everybody is done reading A10
+#pragma unroll
+    for (int v = 0; v < 4; ++v) {
+        const int i = ti * 16 + MF::row(lane, v), j = tj * 16 + l16;
+        sB1[i * LD + j] = acc[v];
+        if (i < n2)
+            lp[(int64_t)(NB + i) * L.rs + (int64_t)j * L.cs] = acc[v];
+    }
+    __syncthreads();
+
+    // ---- trailing block: A11 - L10 L10^T (lower triangle, identity padding) -------------------
+    acc = leaf_product<T>(sB1, LD, 1, sB1, 1, LD, ti, tj, lane);
+#pragma unroll
+    for (int v = 0; v < 4; ++v) {
+        const int i = ti * 16 + MF::row(lane, v), j = tj * 16 + l16;
+        T val = (i == j) ? T(1) : T(0);
+        if (i < n2 && j <= i)
+            val = ap[(int64_t)(NB + i) * A.rs + (int64_t)(NB + j) * A.cs] - acc[v];
+        sC[i * LD + j] = val;
+    }
+    __syncthreads();
+
+    // ---- block (1,1) --------------------------------------------------------------------
+#pragma unroll
+    for (int c = 0; c < CW; ++c) {
+        const int col = g * CW + c;
+        a[c] = (col <= r) ? sC[r * LD + col] : T(0);
+        x[c] = (col == r) ? T(1) : T(0);
+    }
+    leaf_factor<T>(a, x, colbuf, rowbuf, &s_fail, NB);
+#pragma unroll
+    for (int c = 0; c < CW; ++c) {
+        const int col = g * CW + c;
+        const T lv = (col <= r) ? a[c] : T(0), iv = (col <= r) ? x[c] : T(0);
+        if (r < n2 && col < n2) {
+            lp[(int64_t)(NB + r) * L.rs + (int64_t)(NB + col) * L.cs] = lv;
+            ip[(int64_t)(NB + r) * Inv.rs + (int64_t)(NB + col) * Inv.cs] = iv;
+        }
+        sLi1[r * LD + col] = iv;
+    }
+    __syncthreads();
+
+    // ---- inverse, block (1,0): -Li11 (L10 Li00) ------------------------------------------------
+    acc = leaf_product<T>(sB1, LD, 1, sLi0, LD, 1, ti, tj, lane);
+#pragma unroll
+    for (int v = 0; v < 4; ++v)
+        sC[(ti * 16 + MF::row(lane, v)) * LD + tj * 16 + l16] = acc[v];
+    __syncthreads();
+    acc = leaf_product<T>(sLi1, LD, 1, sC, LD, 1, ti, tj, lane);
+#pragma unroll
+    for (int v = 0; v < 4; ++v) {
+        const int i = ti * 16 + MF::row(lane, v), j = tj * 16 + l16;
+        if (i < n2)
+            ip[(int64_t)(NB + i) * Inv.rs + (int64_t)j * Inv.cs] = -acc[v];
+    }
+    if (info != nullptr && tid == 0 && s_fail != 0 && s_fail <= nb) {
+        if (info[b] == 0)
+            info[b] = info_off + s_fail;
+    }
+}
+
 template <typename T>
 la_status launch_potrf_leaf(View<const T> A, View<T> L, View<T> Inv, int32_t *info, int info_off, int64_t batch, int nb,
                             hipStream_t st)
 {
     if (batch <= 0 || nb <= 0)
         return LA_OK;
-    if (nb > NB || batch > 0x7fffffffll)
+    if (nb > 2 * NB || batch > 0x7fffffffll)
         return LA_ERR_UNSUPPORTED;
-    hipLaunchKernelGGL((k_potrf_leaf<T>), dim3((unsigned)batch), dim3(LEAF_THREADS), 0, st, A, L, Inv, info, info_off, batch, nb);
+    if (nb <= NB)
+        hipLaunchKernelGGL((k_potrf_leaf<T>), dim3((unsigned)batch), dim3(LEAF_THREADS), 0, st, A, L, Inv, info,
+                           info_off, batch, nb);
+    else
+        hipLaunchKernelGGL((k_potrf_leaf128<T>), dim3((unsigned)batch), dim3(LEAF_THREADS), 0, st, A, L, Inv, info,
+                           info_off, batch, nb);
     return launch_check("potrf_leaf");
 }
 
