@@ -503,7 +503,11 @@ la_status launch_gemm(View<const T> A, View<const T> B, View<T> C, int64_t batch
         const int64_t t64 = (int64_t)((M + 63) / 64) * ((N + 63) / 64) * batch;
         if (t64 > 0x7fffffffll)
             return LA_ERR_UNSUPPORTED;
-        if (o.force128 || (t128 >= 192 && M >= 128 && N >= 128))
+        // triangular operands / outputs: 128-tiles waste work along the diagonal and leave too few
+        // tiles to balance the uneven K ranges unless the matrices are large
+        const bool tri = (o.triA | o.triB | o.maskC) != 0;
+        const bool big = tri ? (M >= 2048 && N >= 2048) : (M >= 128 && N >= 128);
+        if (o.force128 || (t128 >= 192 && big))
             launch_fast<T, 128, 128, 16, 2>(akf, bkf, A, B, C, batch, M, N, K, alpha, beta, o, st);
         else if (K % 64 == 0)  // small grids are latency bound: fewer, fatter K slabs
             launch_fast<T, 64, 64, 64, 1>(akf, bkf, A, B, C, batch, M, N, K, alpha, beta, o, st);

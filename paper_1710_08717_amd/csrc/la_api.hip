@@ -126,15 +126,12 @@ static la_status inverse_build(View<const T> Lam, View<T> Inv, View<T> Tmp, int6
 }
 
 // ---------------------------------------------------------------------------------
-// Triangular solve / multiply with a logical lower-triangular Lam (n x n) applied to nvec
-// vectors held in X: element e of vector v at X(e, v).
-//   solve fwd: X <- Lam^-1 X      solve !fwd: X <- Lam^-T X
-//   mult  fwd: X <- Lam X         mult  !fwd: X <- Lam^T X
-// ---------------------------------------------------------------------------------
-// Leaves (n <= 64) are in-place GEMMs: a solve multiplies by the precomputed inverse of the
-// diagonal block (Inv, whose diagonal 64-blocks hold those inverses), a product multiplies by
-// the masked block itself.  In place is safe there because one workgroup tile covers all
-// n <= 64 rows of its vectors.
+// In-place triangular solve with a logical lower-triangular Lam (n x n) applied to nvec vectors
+// held in X: element e of vector v at X(e, v).
+//   fwd: X <- Lam^-1 X      !fwd: X <- Lam^-T X
+// Recursive halving; the leaves (n <= 64) multiply by the precomputed inverse of the diagonal
+// block (Inv, whose diagonal 64-blocks hold those inverses).  In place is safe there because one
+// workgroup tile covers all n <= 64 rows of its vectors.
 // leaf128: the 128 x 128 diagonal blocks of Inv hold complete inverses (true for a factor that
 // the blocked potrf has just produced); a block of exactly 128 is then one in-place GEMM too,
 // with a single 128 x 128 tile covering its rows.
@@ -166,28 +163,6 @@ static la_status solve_rec(View<const T> Lam, View<T> X, int64_t batch, int n, i
     LA_TRY(solve_rec<T>(L22, X2, batch, n2, nvec, false, Inv.sub(n1, n1), leaf128, st));
     LA_TRY(launch_gemm<T>(L21.t(), cv(X2), X1, batch, n1, (int)nvec, n2, T(-1), T(1), o, st));
     return solve_rec<T>(L11, X1, batch, n1, nvec, false, Inv, leaf128, st);
-}
-
-template <typename T>
-static la_status mult_rec(View<const T> Lam, View<T> X, int64_t batch, int n, int64_t nvec, bool fwd, hipStream_t st)
-{
-    GemmOpts o;
-    if (n <= NB) {
-        o.triA = fwd ? 1 : 2;  // Lam keeps i >= k, Lam^T keeps i <= k
-        return launch_gemm<T>(fwd ? Lam : Lam.t(), cv(X), X, batch, n, (int)nvec, n, T(1), T(0), o, st);
-    }
-    const int n1 = split_point(n), n2 = n - n1;
-    View<const T> L11 = Lam, L21 = Lam.sub(n1, 0), L22 = Lam.sub(n1, n1);
-    View<T> X1 = X, X2 = X.sub(n1, 0);
-    if (fwd) {  // y2 = Lam21 x1 + Lam22 x2 first (needs the old x1), then y1 = Lam11 x1
-        LA_TRY(mult_rec<T>(L22, X2, batch, n2, nvec, true, st));
-        LA_TRY(launch_gemm<T>(L21, cv(X1), X2, batch, n2, (int)nvec, n1, T(1), T(1), o, st));
-        return mult_rec<T>(L11, X1, batch, n1, nvec, true, st);
-    }
-    // y1 = Lam11^T x1 + Lam21^T x2 first (needs the old x2), then y2 = Lam22^T x2
-    LA_TRY(mult_rec<T>(L11, X1, batch, n1, nvec, false, st));
-    LA_TRY(launch_gemm<T>(L21.t(), cv(X2), X1, batch, n1, (int)nvec, n2, T(1), T(1), o, st));
-    return mult_rec<T>(L22, X2, batch, n2, nvec, false, st);
 }
 
 // ---------------------------------------------------------------------------------
@@ -291,27 +266,82 @@ static la_status potrf_t(int lower, int64_t batch, int n, const void *A, void *L
     return potrf_rec<T>(Lv, info, 0, batch, n, Inv, st);
 }
 
+// trsm / trmm (section 4.2).  vectors: columns of A/B (left) or rows (right); X(e, v) = element e
+// of vector v, so that every case is "apply Lam, Lam^T or one of their inverses to vectors".
+//   trmm: one GEMM with the triangular operand masked.
+//   trsm, n <= 64: product with the inverse of the single diagonal block.
+//   trsm, n <= 1024: explicit inverse of Lam (see inverse_build), then one masked GEMM.
+//   trsm, larger n: inverses of the 512 x 512 diagonal blocks, then block substitution with two
+//     GEMMs per block (the block's solution goes through a scratch panel because a product
+//     cannot overwrite its own operand across several tiles).
 template <typename T>
 static la_status tri_apply_t(bool solve, int lower, int trans, int rightside, double alpha, int64_t batch, int n, int m,
                              const void *L, const void *A, void *B, hipStream_t st)
 {
     View<const T> Lam = tri_view<const T>((const T *)L, n, lower);
-    const int64_t nm = (int64_t)n * m;
-    // data laid out as the caller gave it; alpha is applied while copying (or in place)
-    View<const T> Ain = rightside ? View<const T>{(const T *)A, nm, n, 1} : View<const T>{(const T *)A, nm, m, 1};
-    View<T> Bout = rightside ? View<T>{(T *)B, nm, n, 1} : View<T>{(T *)B, nm, m, 1};
-    if (A != B || alpha != 1.0)
-        LA_TRY(launch_copy<T>(Ain, Bout, batch, rightside ? m : n, rightside ? n : m, (T)alpha, 0, st));
-    // vectors: columns of B (left) or rows of B (right); X(e, v) = element e of vector v
+    const int64_t nm = (int64_t)n * m, nn = (int64_t)n * n;
+    View<const T> Xin = rightside ? View<const T>{(const T *)A, nm, 1, n} : View<const T>{(const T *)A, nm, m, 1};
     View<T> X = rightside ? View<T>{(T *)B, nm, 1, n} : View<T>{(T *)B, nm, m, 1};
+    const bool inplace = (A == B);
     const bool use_lt = (trans != 0) != (lower == 0);  // t(L) equals Lam^T
     const bool fwd = (use_lt == (rightside != 0));
-    if (!solve)
-        return mult_rec<T>(Lam, X, batch, n, m, fwd, st);
-    View<T> Inv;
-    LA_TRY(scratch_views<T>(batch, n, 1, &Inv));
-    LA_TRY(launch_tile_inverse<T>(Lam, Inv, batch, n, st));
-    return solve_rec<T>(Lam, X, batch, n, m, fwd, cv(Inv), false, st);
+    GemmOpts o;
+    o.triA = fwd ? 1 : 2;  // Lam keeps e >= k, Lam^T keeps e <= k; the same holds for their inverses
+
+    if (solve && n <= NB) {
+        if (!inplace || alpha != 1.0)
+            LA_TRY(launch_copy<T>(Xin, X, batch, n, m, (T)alpha, 0, st));
+        View<T> Inv;
+        LA_TRY(scratch_views<T>(batch, n, 1, &Inv));
+        LA_TRY(launch_tile_inverse<T>(Lam, Inv, batch, n, st));
+        return solve_rec<T>(Lam, X, batch, n, m, fwd, cv(Inv), false, st);
+    }
+
+    // scratch: [inverse n*n] [merge temporary n*n] (solve only), then a panel shaped like X
+    void *sp = nullptr;
+    const size_t per_item = (solve ? 2 * (size_t)nn : 0) + (size_t)nm;
+    LA_TRY(scratch_get(per_item * batch * sizeof(T), &sp));
+    T *base = (T *)sp;
+    View<T> Inv{base, nn, n, 1}, Tmp{base + (solve ? batch * nn : 0), nn, n, 1};
+    View<T> S{base + (solve ? 2 * batch * nn : 0), nm, X.rs, X.cs};
+
+    if (!solve || n <= 1024) {
+        View<const T> M = Lam;
+        if (solve) {
+            LA_TRY(inverse_build<T>(Lam, Inv, Tmp, batch, n, n, st));
+            M = cv(Inv);
+        }
+        View<const T> src = Xin;
+        if (inplace) {
+            LA_TRY(launch_copy<T>(Xin, S, batch, n, m, T(1), 0, st));
+            src = cv(S);
+        }
+        return launch_gemm<T>(fwd ? M : M.t(), src, X, batch, n, m, n, (T)alpha, T(0), o, st);
+    }
+
+    constexpr int NBI = 512;
+    LA_TRY(inverse_build<T>(Lam, Inv, Tmp, batch, n, NBI, st));
+    if (!inplace || alpha != 1.0)
+        LA_TRY(launch_copy<T>(Xin, X, batch, n, m, (T)alpha, 0, st));
+    const int nblk = (n + NBI - 1) / NBI;
+    GemmOpts plain;
+    for (int step = 0; step < nblk; ++step) {
+        const int j = fwd ? step : nblk - 1 - step;
+        const int64_t o0 = (int64_t)j * NBI;
+        const int nbj = (int)((n - o0) < NBI ? (n - o0) : NBI);
+        View<const T> Ij = cv(Inv).sub(o0, o0);
+        View<T> Xj = X.sub(o0, 0);
+        LA_TRY(launch_gemm<T>(fwd ? Ij : Ij.t(), cv(Xj), S, batch, nbj, m, nbj, T(1), T(0), o, st));
+        if (fwd && o0 + nbj < n) {  // rows below: X -= Lam[below, j] S
+            const int rest = (int)(n - o0 - nbj);
+            LA_TRY(launch_gemm<T>(Lam.sub(o0 + nbj, o0), cv(S), X.sub(o0 + nbj, 0), batch, rest, m, nbj, T(-1), T(1),
+                                  plain, st));
+        } else if (!fwd && o0 > 0) {  // rows above: X -= Lam[j, above]^T S
+            LA_TRY(launch_gemm<T>(Lam.sub(o0, 0).t(), cv(S), X, batch, (int)o0, m, nbj, T(-1), T(1), plain, st));
+        }
+        LA_TRY(launch_copy<T>(cv(S), Xj, batch, nbj, m, T(1), 0, st));
+    }
+    return LA_OK;
 }
 
 template <typename T>
