@@ -260,19 +260,11 @@ template <typename T>
 la_status launch_backward_tiny(View<const T> L, View<const T> G, View<T> Abar, int64_t batch, int n,
                                hipStream_t st);
 
-// Triangular base-case tiles.  Lam is a lower-triangular nb x nb block (nb <= 64), X holds
-// nvec vectors of length nb: element e of vector v at X.p + b*bs + e*rs + v*cs.
-//   solve, fwd:  Lam x = b        solve, !fwd: Lam^T x = b
-//   mult,  fwd:  x <- Lam x       mult,  !fwd: x <- Lam^T x
-// phi (mult only): the vectors are the columns of a lower-triangular block (entries above
-// the block's diagonal are taken as zero) and the result keeps only its lower triangle with
-// the diagonal halved.
+// X <- alpha * Lam^-1 Xin (fwd) or alpha * Lam^-T Xin (!fwd) for n <= 128 and m vectors X(e, v);
+// meant for a handful of right-hand sides (one wavefront each).  X may alias Xin.
 template <typename T>
-la_status launch_tile_solve(View<const T> Lam, View<T> X, int64_t batch, int nb, int64_t nvec, bool fwd,
-                            hipStream_t st);
-template <typename T>
-la_status launch_tile_mult(View<const T> Lam, View<T> X, int64_t batch, int nb, int64_t nvec, bool fwd, bool phi,
-                           hipStream_t st);
+la_status launch_trsm_small(View<const T> Lam, View<const T> Xin, View<T> X, int64_t batch, int n, int m, T alpha,
+                            bool fwd, hipStream_t st);
 
 // Inverses of the 64 x 64 diagonal blocks of Lam (n x n lower triangular) written onto the
 // diagonal blocks of Inv (n x n, entries off those blocks are left alone).

@@ -1,13 +1,12 @@
-// Triangular base-case tiles of the blocked algorithms (section 4.2 of arXiv 1710.08717:
-// trsm "backsubstitution with lower triangular matrix", trmm "multiplication with lower
-// triangular matrix"; the same tiles serve the panel solve of the blocked potrf and the
-// three triangular phases of the potrf backward expression).
-//
-// One wavefront takes 64 vectors of length nb <= 64; each lane keeps ITS vector in
-// registers and runs the substitution / product by itself, so there is no cross-lane
-// traffic at all: the triangular block sits in LDS and is read with wave-uniform
-// (broadcast) addresses.  Vectors that are contiguous in memory are transposed through
-// LDS so that global accesses stay coalesced.
+// Small triangular kernels (section 4.2 of arXiv 1710.08717, "trsm": backsubstitution with a
+// lower triangular matrix):
+//  * k_tile_inv: inverses of the 64 x 64 diagonal blocks of a factor, one wavefront per block,
+//    each lane running the forward substitution for its own column of the identity with the
+//    block read from LDS at wave-uniform addresses.  The blocked paths multiply by these.
+//  * k_trsm_small: the whole solve for n <= 128 and a handful of right-hand sides, one wavefront
+//    per right-hand side with the vector spread over the lanes: at step k the pivot entry is
+//    read with v_readlane and every lane updates its rows with column k of the matrix, which
+//    sits transposed in LDS.  No barrier inside the substitution.
 #include "common.hpp"
 
 namespace la {
@@ -36,123 +35,6 @@ __device__ __forceinline__ void load_tri(T *sM, View<const T> Lam, int64_t b, in
             v = p[r * ld + c];
         const int a = tflag ? k : i, bb = tflag ? i : k;
         sM[a * LDM + bb] = v;
-    }
-}
-
-// MODE 0: solve M x = b, M lower (k ascending)      sM[k][i] = M(i,k)
-// MODE 1: solve M x = b, M upper (k descending)     sM[k][i] = M(i,k)
-// MODE 2: x <- M x, M lower (rows descending)       sM[i][k] = M(i,k)
-// MODE 3: x <- M x, M upper (rows ascending)        sM[i][k] = M(i,k)
-template <typename T, int MODE>
-__global__ __launch_bounds__(WAVE) void k_tile(View<const T> Lam, View<T> X, int64_t batch, int nb, int64_t nvec,
-                                               int tflag, int phi)
-{
-    constexpr int LDM = TileCfg<T>::LDM;
-    constexpr int LDX = TileCfg<T>::LDX;
-    __shared__ __align__(16) T sM[NB * LDM];
-    __shared__ T sX[NB * LDX];
-    __shared__ T sD[NB];
-    const int lane = threadIdx.x;
-    const int64_t ntile = (nvec + NB - 1) / NB;
-    const int64_t b = blockIdx.x / ntile;
-    const int64_t v0 = (blockIdx.x % ntile) * NB;
-    const int64_t myv = v0 + lane;
-    const bool active = myv < nvec;
-
-    load_tri<T>(sM, Lam, b, nb, tflag != 0);
-
-    T *xp = X.p + b * X.bs;
-    const bool vec_adjacent = (X.cs == 1);  // consecutive vectors are consecutive in memory
-    T x[NB];
-    if (vec_adjacent) {
-#pragma unroll
-        for (int e = 0; e < NB; ++e)
-            x[e] = (active && e < nb) ? xp[e * X.rs + myv] : T(0);
-        __syncthreads();
-    } else {
-        for (int v = 0; v < NB; ++v) {
-            const int e = lane;
-            T val = T(0);
-            if (v0 + v < nvec && e < nb)
-                val = xp[e * X.rs + (v0 + v) * X.cs];
-            sX[v * LDX + e] = val;
-        }
-        __syncthreads();
-#pragma unroll
-        for (int e = 0; e < NB; ++e)
-            x[e] = sX[lane * LDX + e];
-    }
-
-    if constexpr (MODE <= 1) {
-        sD[lane] = rcp_acc(sM[lane * LDM + lane]);
-        __syncthreads();
-    }
-
-    if constexpr (MODE == 0) {
-#pragma unroll
-        for (int k = 0; k < NB; ++k) {
-            x[k] *= sD[k];
-#pragma unroll
-            for (int i = k + 1; i < NB; ++i)
-                x[i] = fma(-sM[k * LDM + i], x[k], x[i]);
-        }
-    } else if constexpr (MODE == 1) {
-#pragma unroll
-        for (int k = NB - 1; k >= 0; --k) {
-            x[k] *= sD[k];
-#pragma unroll
-            for (int i = 0; i < k; ++i)
-                x[i] = fma(-sM[k * LDM + i], x[k], x[i]);
-        }
-    } else if constexpr (MODE == 2) {
-#pragma unroll
-        for (int i = NB - 1; i >= 0; --i) {
-            T s = sM[i * LDM + i] * x[i];
-#pragma unroll
-            for (int k = 0; k < i; ++k)
-                s = fma(sM[i * LDM + k], x[k], s);
-            x[i] = s;
-        }
-    } else {
-        if (phi) {
-            // the vectors are columns of a lower-triangular block: entries above its diagonal are zero
-#pragma unroll
-            for (int e = 0; e < NB; ++e)
-                if (e < lane)
-                    x[e] = T(0);
-        }
-#pragma unroll
-        for (int i = 0; i < NB; ++i) {
-            T s = sM[i * LDM + i] * x[i];
-#pragma unroll
-            for (int k = i + 1; k < NB; ++k)
-                s = fma(sM[i * LDM + k], x[k], s);
-            x[i] = s;
-        }
-        if (phi) {
-            // keep the lower triangle, halve the diagonal (the map Phi of the backward expression)
-#pragma unroll
-            for (int e = 0; e < NB; ++e)
-                x[e] = (e > lane) ? x[e] : ((e == lane) ? T(0.5) * x[e] : T(0));
-        }
-    }
-
-    if (vec_adjacent) {
-#pragma unroll
-        for (int e = 0; e < NB; ++e)
-            if (active && e < nb)
-                xp[e * X.rs + myv] = x[e];
-    } else {
-        __syncthreads();
-#pragma unroll
-        for (int e = 0; e < NB; ++e)
-            sX[lane * LDX + e] = x[e];
-        __syncthreads();
-        for (int v = 0; v < NB; ++v) {
-            const int e = lane;
-            if (v0 + v < nvec && e < nb)
-                xp[e * X.rs + (v0 + v) * X.cs] = sX[v * LDX + e];
-        }
     }
 }
 
@@ -214,52 +96,117 @@ la_status launch_tile_inverse(View<const T> Lam, View<T> Inv, int64_t batch, int
     return launch_check("tile_inverse");
 }
 
-template <typename T, int MODE>
-static la_status launch_tile(View<const T> Lam, View<T> X, int64_t batch, int nb, int64_t nvec, int tflag, int phi,
-                             hipStream_t st)
+// ---------------------------------------------------------------------------------------
+// Whole solve for small n: X <- alpha * M^-1 Xin with M = Lam (fwd) or Lam^T (!fwd), n <= 128,
+// vectors X(e, v).  256 threads = 4 wavefronts = 4 vectors per workgroup; all of them first
+// stage sMt[k][i] = M(i,k) and the reciprocal diagonal in LDS.
+// ---------------------------------------------------------------------------------------
+constexpr int SMALL_N = 128;
+
+template <typename T>
+__global__ __launch_bounds__(256) void k_trsm_small(View<const T> Lam, View<const T> Xin, View<T> X, int64_t batch, int n,
+                                                    int m, T alpha, int fwd, int vchunks)
 {
-    if (batch <= 0 || nb <= 0 || nvec <= 0)
+    extern __shared__ __align__(16) unsigned char smem_raw[];
+    T *sMt = reinterpret_cast<T *>(smem_raw);  // n x (n + 1)
+    const int LD = n + 1;
+    T *sD = sMt + n * LD;  // n reciprocals of the diagonal
+    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+    const int64_t b = blockIdx.x / vchunks;
+    const int v = (int)(blockIdx.x % vchunks) * 4 + w;
+
+    // stage: walk Lam's memory along its contiguous direction
+    const bool tr = (Lam.cs != 1);
+    const int64_t ld = tr ? Lam.cs : Lam.rs;
+    const T *lp = Lam.p + b * Lam.bs;
+    for (int idx = tid; idx < n * n; idx += 256) {
+        const int r = idx / n, c = idx % n;          // memory entry (r, c)
+        const int i = tr ? c : r, k = tr ? r : c;    // logical Lam(i, k)
+        if (i >= k) {
+            const T val = lp[(int64_t)r * ld + c];
+            // M(i', k') with M = Lam: (i, k); with M = Lam^T: (k, i).  Stored as sMt[k'][i'].
+            if (fwd)
+                sMt[k * LD + i] = val;
+            else
+                sMt[i * LD + k] = val;
+            if (i == k)
+                sD[i] = rcp_acc(val);
+        }
+    }
+    __syncthreads();
+    if (v >= m)
+        return;
+
+    const T *xin = Xin.p + b * Xin.bs + (int64_t)v * Xin.cs;
+    T *xout = X.p + b * X.bs + (int64_t)v * X.cs;
+    const int r0 = lane, r1 = lane + 64;
+    const int c0 = min(r0, n - 1), c1 = min(r1, n - 1);  // in-range LDS columns for the idle lanes
+    T x0 = (r0 < n) ? alpha * xin[(int64_t)r0 * Xin.rs] : T(0);
+    T x1 = (r1 < n) ? alpha * xin[(int64_t)r1 * Xin.rs] : T(0);
+
+    if (fwd) {
+        for (int k = 0; k < n; ++k) {
+            const T src = (k < 64) ? x0 : x1;
+            const T xk = group_bcast<64>(src, k & 63) * sD[k];
+            const T *col = sMt + k * LD;  // M(i, k), i > k
+            if (k < 64) {
+                x0 = (r0 == k) ? xk : ((r0 > k && r0 < n) ? fma(-col[c0], xk, x0) : x0);
+                if (r1 < n)
+                    x1 = fma(-col[c1], xk, x1);
+            } else {
+                x1 = (r1 == k) ? xk : ((r1 > k && r1 < n) ? fma(-col[c1], xk, x1) : x1);
+            }
+        }
+    } else {
+        for (int k = n - 1; k >= 0; --k) {
+            const T src = (k < 64) ? x0 : x1;
+            const T xk = group_bcast<64>(src, k & 63) * sD[k];
+            const T *col = sMt + k * LD;  // M(i, k), i < k
+            if (k >= 64) {
+                x1 = (r1 == k) ? xk : ((r1 < k) ? fma(-col[c1], xk, x1) : x1);
+                x0 = fma(-col[c0], xk, x0);
+            } else {
+                x0 = (r0 == k) ? xk : ((r0 < k) ? fma(-col[c0], xk, x0) : x0);
+            }
+        }
+    }
+    if (r0 < n)
+        xout[(int64_t)r0 * X.rs] = x0;
+    if (r1 < n)
+        xout[(int64_t)r1 * X.rs] = x1;
+}
+
+template <typename T>
+la_status launch_trsm_small(View<const T> Lam, View<const T> Xin, View<T> X, int64_t batch, int n, int m, T alpha,
+                            bool fwd, hipStream_t st)
+{
+    if (batch <= 0 || n <= 0 || m <= 0)
         return LA_OK;
-    if (nb > NB)
+    if (n > SMALL_N)
         return LA_ERR_UNSUPPORTED;
-    const int64_t ntile = (nvec + NB - 1) / NB;
-    const int64_t blocks = ntile * batch;
+    const int vchunks = (m + 3) / 4;
+    const int64_t blocks = (int64_t)vchunks * batch;
     if (blocks > 0x7fffffffll)
         return LA_ERR_UNSUPPORTED;
-    hipLaunchKernelGGL((k_tile<T, MODE>), dim3((unsigned)blocks), dim3(WAVE), 0, st, Lam, X, batch, nb, nvec, tflag,
-                       phi);
-    return launch_check("tile");
-}
-
-template <typename T>
-la_status launch_tile_solve(View<const T> Lam, View<T> X, int64_t batch, int nb, int64_t nvec, bool fwd, hipStream_t st)
-{
-    // fwd: M = Lam (lower), sM[k][i] = Lam(i,k) -> transposed load.  !fwd: M = Lam^T (upper), sM[k][i] = Lam(k,i).
-    return fwd ? launch_tile<T, 0>(Lam, X, batch, nb, nvec, 1, 0, st) : launch_tile<T, 1>(Lam, X, batch, nb, nvec, 0, 0, st);
-}
-
-template <typename T>
-la_status launch_tile_mult(View<const T> Lam, View<T> X, int64_t batch, int nb, int64_t nvec, bool fwd, bool phi,
-                           hipStream_t st)
-{
-    // fwd: M = Lam, sM[i][k] = Lam(i,k).  !fwd: M = Lam^T, sM[i][k] = Lam(k,i) -> transposed load.
-    if (fwd) {
-        if (phi)
-            return LA_ERR_UNSUPPORTED;
-        return launch_tile<T, 2>(Lam, X, batch, nb, nvec, 0, 0, st);
+    const size_t lds = ((size_t)n * (n + 1) + n) * sizeof(T);
+    if (lds > 64 * 1024) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&k_trsm_small<T>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) {
+            set_error(e, "hipFuncSetAttribute(trsm_small)");
+            return LA_ERR_RUNTIME;
+        }
     }
-    if (phi && nvec != nb)
-        return LA_ERR_INVALID_ARG;
-    return launch_tile<T, 3>(Lam, X, batch, nb, nvec, 1, phi ? 1 : 0, st);
+    hipLaunchKernelGGL((k_trsm_small<T>), dim3((unsigned)blocks), dim3(256), lds, st, Lam, Xin, X, batch, n, m, alpha,
+                       fwd ? 1 : 0, vchunks);
+    return launch_check("trsm_small");
 }
 
+template la_status launch_trsm_small<float>(View<const float>, View<const float>, View<float>, int64_t, int, int, float,
+                                            bool, hipStream_t);
+template la_status launch_trsm_small<double>(View<const double>, View<const double>, View<double>, int64_t, int, int,
+                                             double, bool, hipStream_t);
 template la_status launch_tile_inverse<float>(View<const float>, View<float>, int64_t, int, hipStream_t);
 template la_status launch_tile_inverse<double>(View<const double>, View<double>, int64_t, int, hipStream_t);
-template la_status launch_tile_solve<float>(View<const float>, View<float>, int64_t, int, int64_t, bool, hipStream_t);
-template la_status launch_tile_solve<double>(View<const double>, View<double>, int64_t, int, int64_t, bool, hipStream_t);
-template la_status launch_tile_mult<float>(View<const float>, View<float>, int64_t, int, int64_t, bool, bool,
-                                           hipStream_t);
-template la_status launch_tile_mult<double>(View<const double>, View<double>, int64_t, int, int64_t, bool, bool,
-                                            hipStream_t);
 
 }  // namespace la

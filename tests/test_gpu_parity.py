@@ -280,6 +280,36 @@ def test_trmm_parity(la, orc, dtype, lower, trans, rightside, n, m):
     assert np.array_equal(out, out2)
 
 
+@pytest.mark.parametrize("dtype", ["f64", "f32"])
+@pytest.mark.parametrize("lower,trans,rightside", [(True, False, False), (True, True, False), (False, False, True),
+                                                   (True, True, True)])
+def test_trsm_block_substitution_path(la, orc, dtype, lower, trans, rightside):
+    """n > 1024 takes the 512-block-inverse path; 1300 leaves a ragged last block."""
+    n, m, batch = 1300, 70, 1
+    T = tri(n, batch, n, lower, dtype)
+    rng = np.random.default_rng(n + m)
+    A = rng.standard_normal((batch, m, n) if rightside else (batch, n, m)).astype(npdt(dtype))
+    ref = orc.trsm(T, A, lower=lower, trans=trans, rightside=rightside, alpha=0.5)
+    a = dev(A)
+    out = host(la.trsm(dev(T), a, lower=lower, trans=trans, rightside=rightside, alpha=0.5, out=a))  # in place
+    assert relerr(out, ref) <= TOL[dtype]
+
+
+@pytest.mark.parametrize("dtype", ["f64", "f32"])
+def test_potrf_backward_ragged_large(la, orc, dtype):
+    """A size that is no multiple of 64 above every small-matrix shortcut."""
+    n, batch = 1100, 1
+    A = spd(n, batch, n, dtype)
+    L = la.potrf(dev(A))
+    Lh = host(L)
+    assert relerr(Lh, orc.potrf(A)) <= TOL[dtype]
+    G = np.tril(np.random.default_rng(n).standard_normal((batch, n, n))).astype(npdt(dtype))
+    g = dev(G)
+    out = host(la.potrf_backward(L, g, out=g))
+    assert np.array_equal(out, out.transpose(0, 2, 1))
+    assert relerr(out, orc.potrf_backward(Lh, G)) <= TOL[dtype]
+
+
 # ----------------------------------------------------------------------------
 # syrk / sumlogdiag / GP glue
 # ----------------------------------------------------------------------------
