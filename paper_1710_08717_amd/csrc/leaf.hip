@@ -2,9 +2,10 @@
 // factors one block of edge nb <= 64 per workgroup AND inverts the factor in the same pass,
 // because every panel solve against this block later multiplies by that inverse.
 //
-// 1024 threads; thread (r, g) keeps the CW = 4 columns CW*g .. CW*g+CW-1 of row r of the block,
-// and of the inverse under construction, in registers (many threads with little work each:
-// the 64 pivots are strictly sequential, so the time of a step is what counts).  Both the right-looking factorisation and the
+// 512 threads; thread (r, g) keeps the CW = 8 columns CW*g .. CW*g+CW-1 of row r of the block,
+// and of the inverse under construction, in registers (two wavefronts per SIMD: the 64 pivots
+// are strictly sequential, so the time of a step is what counts, and that is the instructions
+// a SIMD has to issue per step plus one barrier).  Both the right-looking factorisation and the
 // right-looking triangular inversion need, at step k, one column (of A) and one row (of X)
 // broadcast to everybody: the owners drop them RAW into LDS, one barrier, and every thread
 // applies the pivot scaling itself:
@@ -15,16 +16,18 @@
 
 namespace la {
 
-constexpr int LEAF_CW = 4;                    // columns per thread
+constexpr int LEAF_CW = 8;                    // columns per thread
 constexpr int LEAF_GR = NB / LEAF_CW;         // column groups (threads per row)
-constexpr int LEAF_THREADS = NB * LEAF_GR;    // 1024
+constexpr int LEAF_THREADS = NB * LEAF_GR;    // 512
+constexpr int LEAF_TPW = 16 / (LEAF_THREADS / 64);  // 16 x 16 output tiles per wavefront in the block products
 
 // The 64 pivot steps on the calling workgroup's registers: a[] (row r, columns CW*g ..) holds the
 // lower triangle of the block on entry and the factor on exit, x[] the identity on entry and
-// the inverse of the factor on exit.  fail_base + (failing column + 1) goes to *s_fail once.
+// the inverse of the factor on exit.  fail becomes fail_base + (failing column + 1) at the first
+// pivot that is not > 0 (kept in a register of every thread: no shared-memory traffic).
 template <typename T>
 __device__ __forceinline__ void leaf_factor(T (&a)[LEAF_CW], T (&x)[LEAF_CW], T (*colbuf)[NB], T (*rowbuf)[NB],
-                                            int *s_fail, int fail_base)
+                                            T (*piv)[2], int &fail, int fail_base)
 {
     constexpr int CW = LEAF_CW, GR = LEAF_GR;
     const int tid = threadIdx.x;
@@ -50,13 +53,16 @@ __device__ __forceinline__ void leaf_factor(T (&a)[LEAF_CW], T (&x)[LEAF_CW], T 
 #pragma unroll
                 for (int c = 0; c < CW; ++c)
                     rowbuf[slot][g * CW + c] = x[c];  // raw row k of the inverse
+                if (g == kg) {  // the owner of the pivot works out 1 / sqrt(a_kk) for everybody
+                    piv[slot][0] = a[kk];
+                    piv[slot][1] = rsqrt_acc(a[kk]);
+                }
             }
             __syncthreads();
-            const T akk = colbuf[slot][k];
-            if (tid == 0 && !(akk > T(0)) && *s_fail == 0)
-                *s_fail = fail_base + k + 1;
-            const T rs = rsqrt_acc(akk);
+            const T akk = piv[slot][0];
+            const T rs = piv[slot][1];
             const T ark = colbuf[slot][r];
+            fail = (!(akk > T(0)) && fail == 0) ? fail_base + k + 1 : fail;  // every thread keeps its own copy
             const T t = (r > k) ? ark * (rs * rs) : T(0);  // a_rk / a_kk
             T cb[CW], rb[CW];
 #pragma unroll
@@ -94,14 +100,13 @@ __global__ __launch_bounds__(LEAF_THREADS) void k_potrf_leaf(View<const T> A, Vi
 {
     __shared__ T colbuf[2][NB];
     __shared__ T rowbuf[2][NB];
-    __shared__ int s_fail;
+    __shared__ __align__(16) T piv[2][2];
     constexpr int CW = LEAF_CW, GR = LEAF_GR;
     const int tid = threadIdx.x;
     const int r = tid / GR, g = tid % GR;
     const int64_t b = blockIdx.x;
     const T *ap = A.p + b * A.bs;
-    if (tid == 0)
-        s_fail = 0;
+    int fail = 0;
 
     // my CW entries of row r (lower triangle only; identity outside nb x nb)
     T a[CW], x[CW];
@@ -114,7 +119,7 @@ __global__ __launch_bounds__(LEAF_THREADS) void k_potrf_leaf(View<const T> A, Vi
         a[c] = v;
         x[c] = (col == r) ? T(1) : T(0);
     }
-    leaf_factor<T>(a, x, colbuf, rowbuf, &s_fail, 0);
+    leaf_factor<T>(a, x, colbuf, rowbuf, piv, fail, 0);
 
     T *lp = L.p + b * L.bs;
     T *ip = Inv.p + b * Inv.bs;
@@ -126,9 +131,9 @@ __global__ __launch_bounds__(LEAF_THREADS) void k_potrf_leaf(View<const T> A, Vi
             ip[(int64_t)r * Inv.rs + (int64_t)col * Inv.cs] = (col <= r) ? x[c] : T(0);
         }
     }
-    if (info != nullptr && tid == 0 && s_fail != 0 && s_fail <= nb) {
+    if (info != nullptr && tid == 0 && fail != 0 && fail <= nb) {
         if (info[b] == 0)
-            info[b] = info_off + s_fail;
+            info[b] = info_off + fail;
     }
 }
 
@@ -136,26 +141,31 @@ __global__ __launch_bounds__(LEAF_THREADS) void k_potrf_leaf(View<const T> A, Vi
 // Blocks of edge 64 < nb <= 128 in one launch: [A00 0; A10 A11] with 64 x 64 sub-blocks,
 //   L00, Li00 = factor(A00);  L10 = A10 Li00^T;  L11, Li11 = factor(A11 - L10 L10^T);
 //   Li10 = -Li11 (L10 Li00)
-// The four 64 x 64 x 64 products run on the matrix cores, one 16 x 16 output tile per
-// wavefront, operands in LDS.
+// The four 64 x 64 x 64 products run on the matrix cores, a row of four 16 x 16 output tiles
+// per wavefront, operands in LDS.
 // ---------------------------------------------------------------------------------------
 constexpr int LEAF_LD = NB + 1;
 
-// 16 x 16 tile (ti, tj) of  sum_k A(i,k) B(k,j)  with A(i,k) = sA[i*a_si + k*a_sk], B(k,j) = sB[k*b_sk + j*b_sj]
+// Tiles (ti, tj0 .. tj0 + TPW - 1), 16 x 16 each, of  sum_k A(i,k) B(k,j)  with
+// A(i,k) = sA[i*a_si + k*a_sk] and B(k,j) = sB[k*b_sk + j*b_sj].
 template <typename T>
-__device__ __forceinline__ typename Mfma<T>::acc_t leaf_product(const T *sA, int a_si, int a_sk, const T *sB, int b_sk,
-                                                                 int b_sj, int ti, int tj, int lane)
+__device__ __forceinline__ void leaf_product(typename Mfma<T>::acc_t (&acc)[LEAF_TPW], const T *sA, int a_si, int a_sk,
+                                             const T *sB, int b_sk, int b_sj, int ti, int tj0, int lane)
 {
     using MF = Mfma<T>;
-    typename MF::acc_t acc = {0, 0, 0, 0};
     const int l16 = lane & 15, lk = lane >> 4;
 #pragma unroll
+    for (int q = 0; q < LEAF_TPW; ++q)
+        acc[q] = typename MF::acc_t{0, 0, 0, 0};
+#pragma unroll 4
     for (int kk = 0; kk < NB; kk += 4) {
         const T av = sA[(ti * 16 + l16) * a_si + (kk + lk) * a_sk];
-        const T bv = sB[(kk + lk) * b_sk + (tj * 16 + l16) * b_sj];
-        acc = MF::run(av, bv, acc);
+#pragma unroll
+        for (int q = 0; q < LEAF_TPW; ++q) {
+            const T bv = sB[(kk + lk) * b_sk + ((tj0 + q) * 16 + l16) * b_sj];
+            acc[q] = MF::run(av, bv, acc[q]);
+        }
     }
-    return acc;
 }
 
 template <typename T>
@@ -169,20 +179,20 @@ __global__ __launch_bounds__(LEAF_THREADS) void k_potrf_leaf128(View<const T> A,
     __shared__ T sC[NB * LEAF_LD];   // A11 - L10 L10^T, then L10 Li00
     __shared__ T colbuf[2][NB];
     __shared__ T rowbuf[2][NB];
-    __shared__ int s_fail;
+    __shared__ __align__(16) T piv[2][2];
     constexpr int CW = LEAF_CW, GR = LEAF_GR, LD = LEAF_LD;
     const int tid = threadIdx.x;
     const int r = tid / GR, g = tid % GR;
+    constexpr int TPW = LEAF_TPW;
     const int lane = tid & 63, w = tid >> 6;
-    const int ti = w >> 2, tj = w & 3;
+    const int ti = w / (4 / TPW), tj0 = (w % (4 / TPW)) * TPW;  // this wavefront's output tiles
     const int l16 = lane & 15;
     const int n2 = nb - NB;  // rows of the second block (1 .. 64)
     const int64_t b = blockIdx.x;
     const T *ap = A.p + b * A.bs;
     T *lp = L.p + b * L.bs;
     T *ip = Inv.p + b * Inv.bs;
-    if (tid == 0)
-        s_fail = 0;
+    int fail = 0;
 
     // ---- block (0,0) --------------------------------------------------------------------
     T a[CW], x[CW];
@@ -194,7 +204,7 @@ __global__ __launch_bounds__(LEAF_THREADS) void k_potrf_leaf128(View<const T> A,
         // A10 for the panel product (rows past the end of the block read as zero)
         sB1[r * LD + col] = (r < n2) ? ap[(int64_t)(NB + r) * A.rs + (int64_t)col * A.cs] : T(0);
     }
-    leaf_factor<T>(a, x, colbuf, rowbuf, &s_fail, 0);
+    leaf_factor<T>(a, x, colbuf, rowbuf, piv, fail, 0);
 #pragma unroll
     for (int c = 0; c < CW; ++c) {
         const int col = g * CW + c;
@@ -206,27 +216,34 @@ __global__ __launch_bounds__(LEAF_THREADS) void k_potrf_leaf128(View<const T> A,
     __syncthreads();
 
     // ---- panel: L10 = A10 Li00^T ------------------------------------------------------------
-    typename MF::acc_t acc = leaf_product<T>(sB1, LD, 1, sLi0, 1, LD, ti, tj, lane);
+    typename MF::acc_t acc[TPW];
+    leaf_product<T>(acc, sB1, LD, 1, sLi0, 1, LD, ti, tj0, lane);
     __syncthreads();  // everybody is done reading A10
 #pragma unroll
-    for (int v = 0; v < 4; ++v) {
-        const int i = ti * 16 + MF::row(lane, v), j = tj * 16 + l16;
-        sB1[i * LD + j] = acc[v];
-        if (i < n2)
-            lp[(int64_t)(NB + i) * L.rs + (int64_t)j * L.cs] = acc[v];
-    }
+    for (int q = 0; q < TPW; ++q)
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+            const int tj = tj0 + q;
+            const int i = ti * 16 + MF::row(lane, v), j = tj * 16 + l16;
+            sB1[i * LD + j] = acc[q][v];
+            if (i < n2)
+                lp[(int64_t)(NB + i) * L.rs + (int64_t)j * L.cs] = acc[q][v];
+        }
     __syncthreads();
 
     // ---- trailing block: A11 - L10 L10^T (lower triangle, identity padding) -------------------
-    acc = leaf_product<T>(sB1, LD, 1, sB1, 1, LD, ti, tj, lane);
+    leaf_product<T>(acc, sB1, LD, 1, sB1, 1, LD, ti, tj0, lane);
 #pragma unroll
-    for (int v = 0; v < 4; ++v) {
-        const int i = ti * 16 + MF::row(lane, v), j = tj * 16 + l16;
-        T val = (i == j) ? T(1) : T(0);
-        if (i < n2 && j <= i)
-            val = ap[(int64_t)(NB + i) * A.rs + (int64_t)(NB + j) * A.cs] - acc[v];
-        sC[i * LD + j] = val;
-    }
+    for (int q = 0; q < TPW; ++q)
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+            const int tj = tj0 + q;
+            const int i = ti * 16 + MF::row(lane, v), j = tj * 16 + l16;
+            T val = (i == j) ? T(1) : T(0);
+            if (i < n2 && j <= i)
+                val = ap[(int64_t)(NB + i) * A.rs + (int64_t)(NB + j) * A.cs] - acc[q][v];
+            sC[i * LD + j] = val;
+        }
     __syncthreads();
 
     // ---- block (1,1) --------------------------------------------------------------------
@@ -236,7 +253,7 @@ __global__ __launch_bounds__(LEAF_THREADS) void k_potrf_leaf128(View<const T> A,
         a[c] = (col <= r) ? sC[r * LD + col] : T(0);
         x[c] = (col == r) ? T(1) : T(0);
     }
-    leaf_factor<T>(a, x, colbuf, rowbuf, &s_fail, NB);
+    leaf_factor<T>(a, x, colbuf, rowbuf, piv, fail, NB);
 #pragma unroll
     for (int c = 0; c < CW; ++c) {
         const int col = g * CW + c;
@@ -250,21 +267,26 @@ __global__ __launch_bounds__(LEAF_THREADS) void k_potrf_leaf128(View<const T> A,
     __syncthreads();
 
     // ---- inverse, block (1,0): -Li11 (L10 Li00) ------------------------------------------------
-    acc = leaf_product<T>(sB1, LD, 1, sLi0, LD, 1, ti, tj, lane);
+    leaf_product<T>(acc, sB1, LD, 1, sLi0, LD, 1, ti, tj0, lane);
 #pragma unroll
-    for (int v = 0; v < 4; ++v)
-        sC[(ti * 16 + MF::row(lane, v)) * LD + tj * 16 + l16] = acc[v];
+    for (int q = 0; q < TPW; ++q)
+#pragma unroll
+        for (int v = 0; v < 4; ++v)
+            sC[(ti * 16 + MF::row(lane, v)) * LD + (tj0 + q) * 16 + l16] = acc[q][v];
     __syncthreads();
-    acc = leaf_product<T>(sLi1, LD, 1, sC, LD, 1, ti, tj, lane);
+    leaf_product<T>(acc, sLi1, LD, 1, sC, LD, 1, ti, tj0, lane);
 #pragma unroll
-    for (int v = 0; v < 4; ++v) {
-        const int i = ti * 16 + MF::row(lane, v), j = tj * 16 + l16;
-        if (i < n2)
-            ip[(int64_t)(NB + i) * Inv.rs + (int64_t)j * Inv.cs] = -acc[v];
-    }
-    if (info != nullptr && tid == 0 && s_fail != 0 && s_fail <= nb) {
+    for (int q = 0; q < TPW; ++q)
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+            const int tj = tj0 + q;
+            const int i = ti * 16 + MF::row(lane, v), j = tj * 16 + l16;
+            if (i < n2)
+                ip[(int64_t)(NB + i) * Inv.rs + (int64_t)j * Inv.cs] = -acc[q][v];
+        }
+    if (info != nullptr && tid == 0 && fail != 0 && fail <= nb) {
         if (info[b] == 0)
-            info[b] = info_off + s_fail;
+            info[b] = info_off + fail;
     }
 }
 
