@@ -52,11 +52,16 @@ __device__ __forceinline__ int64_t xcd_slot(int64_t w, int64_t total)
 //   order 2: tiles on or above the diagonal only (tm <= tn), column by column.
 //   order 3: all tiles of a square grid in "shells" max(tm, tn) = s, s ascending: every tile of
 //            a shell has the same K range when both operands are triangular.
-__device__ __forceinline__ void decode_tile(int order, int t, int tiles_n, int &tm, int &tn)
+//   order 4: all tiles, column-major (the K range depends on the column only when just B is
+//            triangular).
+__device__ __forceinline__ void decode_tile(int order, int t, int tiles_m, int tiles_n, int &tm, int &tn)
 {
     if (order == 0) {
         tm = t / tiles_n;
         tn = t % tiles_n;
+    } else if (order == 4) {
+        tn = t / tiles_m;
+        tm = t % tiles_m;
     } else if (order == 3) {
         int s_ = (int)sqrt((double)t);
         while ((s_ + 1) * (s_ + 1) <= t)
@@ -178,7 +183,7 @@ __global__ __launch_bounds__(256) void k_gemm(View<const T> A, View<const T> B, 
     if (o.reverse)
         tile = (int)per - 1 - tile;
     int tm, tn;
-    decode_tile(o.order, tile, tiles_n, tm, tn);
+    decode_tile(o.order, tile, tiles_m, tiles_n, tm, tn);
     const int i0 = tm * BM, j0 = tn * BN;
     if ((o.maskC == 1 && j0 > i0 + BM - 1) || (o.maskC == 2 && i0 > j0 + BN - 1))
         return;  // tile entirely on the masked side of the diagonal
@@ -343,7 +348,7 @@ __global__ __launch_bounds__(256, 2) void k_gemm_fast(View<const T> A, View<cons
     if (o.reverse)
         tile = (int)per - 1 - tile;  // heaviest tiles first when the work grows along the tile list
     int tm, tn;
-    decode_tile(o.order, tile, tiles_n, tm, tn);
+    decode_tile(o.order, tile, tiles_m, tiles_n, tm, tn);
     const int i0 = tm * BM, j0 = tn * BN;
     if ((o.maskC == 1 && j0 > i0 + BM - 1) || (o.maskC == 2 && i0 > j0 + BN - 1))
         return;
@@ -427,6 +432,8 @@ static bool aligned16(const View<const T> &V, int64_t lead)
 
 static inline int pick_order(const GemmOpts &o, int tiles_m, int tiles_n)
 {
+    if (o.maskC == 0 && o.triA == 0 && o.triB != 0)
+        return 4;  // work depends on the column only
     if (tiles_m != tiles_n)
         return 0;
     if (o.maskC == 1)

@@ -116,8 +116,10 @@ static la_status inverse_build(View<const T> Lam, View<T> Inv, View<T> Tmp, int6
             View<T> O = Inv.sub(o0 + h, o0).level2(2 * h * (Inv.rs + Inv.cs), cnt);
             View<T> Tv{Tmp.p + (pass == 0 ? 0 : (int64_t)nfull * h * h), Tmp.bs, h, 1, h * h, cnt};
             GemmOpts o1, o2;
-            o1.triA = 1;  // D^-1 is lower triangular
-            o2.triB = 1;  // A^-1 is lower triangular
+            o1.triA = 1;     // D^-1 is lower triangular: the K range grows with the tile row,
+            o1.reverse = 1;  //   so the last rows go first
+            o2.triB = 1;     // A^-1 is lower triangular: the K range shrinks with the tile column
+                             //   (the launcher enumerates such tiles column by column)
             LA_TRY(launch_gemm<T>(D, C, Tv, batch * cnt, mr, (int)h, mr, T(1), T(0), o1, st));
             LA_TRY(launch_gemm<T>(cv(Tv), A, O, batch * cnt, mr, (int)h, (int)h, T(-1), T(0), o2, st));
         }
@@ -288,6 +290,7 @@ static la_status tri_apply_t(bool solve, int lower, int trans, int rightside, do
     const bool fwd = (use_lt == (rightside != 0));
     GemmOpts o;
     o.triA = fwd ? 1 : 2;  // Lam keeps e >= k, Lam^T keeps e <= k; the same holds for their inverses
+    o.reverse = fwd ? 1 : 0;  // heavy tile rows first: the last ones for a lower operand
 
     if (solve && n <= 128 && m <= 16)  // few right-hand sides: one wavefront per vector, no scratch
         return launch_trsm_small<T>(Lam, Xin, X, batch, n, m, (T)alpha, fwd, st);
