@@ -294,6 +294,10 @@ bool gemm_fast_eligible(View<const T> A, View<const T> B, View<T> C, int M, int 
 template <typename T>
 la_status launch_copy(View<const T> src, View<T> dst, int64_t batch, int rows, int cols, T alpha, int keep,
                       hipStream_t st);
+// work(i,j) = src(i,j) for i >= j and out(i,j) = 0 for i < j on n x n; nothing else is written
+// (out may alias src).
+template <typename T>
+la_status launch_tril_split(View<const T> src, View<T> work, View<T> out, int64_t batch, int n, hipStream_t st);
 // X <- scale * (X + X^T) on n x n (exactly symmetric result).
 template <typename T>
 la_status launch_symmetrize(View<T> X, int64_t batch, int n, T scale, hipStream_t st);

@@ -47,6 +47,45 @@ la_status launch_copy(View<const T> src, View<T> dst, int64_t batch, int rows, i
     return launch_check("copy");
 }
 
+// work(i,j) = src(i,j) for i >= j (nothing else of work is written) and out(i,j) = 0 for i < j
+// (nothing else of out is written).  out may alias src.
+template <typename T>
+__global__ __launch_bounds__(256) void k_tril_split(View<const T> src, View<T> work, View<T> out, int64_t batch, int n,
+                                                    int nt)
+{
+    const int64_t per = (int64_t)nt * nt;
+    const int64_t b = blockIdx.x / per;
+    const int tile = (int)(blockIdx.x % per);
+    const int r0 = (tile / nt) * ET, c0 = (tile % nt) * ET;
+    const bool colfast = (src.cs == 1) || (src.rs != 1);
+    const T *sp = src.p + b * src.bs;
+    T *wp = work.p + b * work.bs;
+    T *op = out.p + b * out.bs;
+    for (int t = threadIdx.x; t < ET * ET; t += 256) {
+        const int u = t / ET, w = t % ET;
+        const int r = r0 + (colfast ? u : w), c = c0 + (colfast ? w : u);
+        if (r < n && c < n) {
+            if (r >= c)
+                wp[(int64_t)r * work.rs + (int64_t)c * work.cs] = sp[(int64_t)r * src.rs + (int64_t)c * src.cs];
+            else
+                op[(int64_t)r * out.rs + (int64_t)c * out.cs] = T(0);
+        }
+    }
+}
+
+template <typename T>
+la_status launch_tril_split(View<const T> src, View<T> work, View<T> out, int64_t batch, int n, hipStream_t st)
+{
+    if (batch <= 0 || n <= 0)
+        return LA_OK;
+    const int nt = (n + ET - 1) / ET;
+    const int64_t blocks = (int64_t)nt * nt * batch;
+    if (blocks > 0x7fffffffll)
+        return LA_ERR_UNSUPPORTED;
+    hipLaunchKernelGGL((k_tril_split<T>), dim3((unsigned)blocks), dim3(256), 0, st, src, work, out, batch, n, nt);
+    return launch_check("tril_split");
+}
+
 // mode 0: X <- scale * (X + X^T).   mode 1: X(i,j) <- X(j,i) for i < j (lower copied to upper).
 // One block per tile pair (ti >= tj); both tiles pass through LDS so every global access is
 // along the contiguous direction.
@@ -220,6 +259,7 @@ la_status launch_fill_i32(int32_t *p, int64_t count, int32_t v, hipStream_t st)
 
 #define LA_INST(T)                                                                                              \
     template la_status launch_copy<T>(View<const T>, View<T>, int64_t, int, int, T, int, hipStream_t);          \
+    template la_status launch_tril_split<T>(View<const T>, View<T>, View<T>, int64_t, int, hipStream_t);        \
     template la_status launch_symmetrize<T>(View<T>, int64_t, int, T, hipStream_t);                             \
     template la_status launch_mirror_lower<T>(View<T>, int64_t, int, hipStream_t);                              \
     template la_status launch_sumlogdiag<T>(const T *, T *, int64_t, int, hipStream_t);                         \

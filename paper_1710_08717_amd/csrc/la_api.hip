@@ -168,24 +168,43 @@ static la_status solve_rec(View<const T> Lam, View<T> X, int64_t batch, int n, i
 }
 
 // ---------------------------------------------------------------------------------
-// Right-looking blocked potrf on the logical lower triangle held in W (section 4.2:
-// A = L L^T).  W already holds tril(A).  off is the index of W's first row in the whole matrix.
+// Blocked potrf by recursive halving (section 4.2: A = L L^T).  Wk holds the lower triangle of
+// the block still to be factored (a working copy, updated in place), L receives the factor, Inv
+// the inverses of the factors of the diagonal sub-blocks; off is the index of the block's first
+// row in the whole matrix.
+//   [A11 . ; A21 A22]:  L11, Li11 = rec(A11);  L21 = A21 Li11^T;  A22 -= L21 L21^T;  L22 = rec(A22)
+// Every panel solve is ONE product with the explicit inverse of the left factor, so a left
+// child always returns its complete inverse, merged from its own children's by
+//   Li21 = -Li22 (L21 Li11)
+// (need_inv; a right child needs it only if its parent does).  The extra products add one sixth
+// to the n^3 / 3 of the factorisation and remove every recursive solve.  The temporary
+// L21 Li11 lives in the unused upper-right block of the node's part of Inv.
 // ---------------------------------------------------------------------------------
 template <typename T>
-static la_status potrf_rec(View<T> W, int32_t *info, int off, int64_t batch, int n, View<T> Inv, hipStream_t st)
+static la_status potrf_rec(View<T> Wk, View<T> L, int32_t *info, int off, int64_t batch, int n, View<T> Inv,
+                           bool need_inv, hipStream_t st)
 {
-    if (n <= 2 * NB)  // factor and inverse in one launch: the inverse serves every later panel solve
-        return launch_potrf_leaf<T>(cv(W), W, Inv, info, off, batch, n, st);
+    if (n <= 2 * NB)  // factor and inverse in one launch
+        return launch_potrf_leaf<T>(cv(Wk), L, Inv, info, off, batch, n, st);
     const int n1 = split_point(n), n2 = n - n1;
-    View<T> W21 = W.sub(n1, 0), W22 = W.sub(n1, n1);
-    LA_TRY(potrf_rec<T>(W, info, off, batch, n1, Inv, st));
-    // panel: L21 = A21 L11^-T, i.e. every row x of the panel solves L11 x^T = a^T
-    LA_TRY(solve_rec<T>(cv(W), W21.t(), batch, n1, n2, true, cv(Inv), true, st));
-    // trailing update of the lower triangle: A22 -= L21 L21^T
-    GemmOpts o;
-    o.maskC = 1;
-    LA_TRY(launch_gemm<T>(cv(W21), cv(W21).t(), W22, batch, n2, n2, n1, T(-1), T(1), o, st));
-    return potrf_rec<T>(W22, info, off + n1, batch, n2, Inv.sub(n1, n1), st);
+    View<T> L21 = L.sub(n1, 0), Wk22 = Wk.sub(n1, n1);
+    LA_TRY(potrf_rec<T>(Wk, L, info, off, batch, n1, Inv, true, st));
+    GemmOpts op;
+    op.triB = 2;  // Li11^T is upper triangular
+    LA_TRY(launch_gemm<T>(cv(Wk).sub(n1, 0), cv(Inv).t(), L21, batch, n2, n1, n1, T(1), T(0), op, st));
+    GemmOpts ou;
+    ou.maskC = 1;  // trailing update of the lower triangle: A22 -= L21 L21^T
+    LA_TRY(launch_gemm<T>(cv(L21), cv(L21).t(), Wk22, batch, n2, n2, n1, T(-1), T(1), ou, st));
+    LA_TRY(potrf_rec<T>(Wk22, L.sub(n1, n1), info, off + n1, batch, n2, Inv.sub(n1, n1), need_inv, st));
+    if (!need_inv)
+        return LA_OK;
+    View<T> T1 = Inv.sub(0, n1).t();  // n2 x n1 temporary in the upper-right block
+    GemmOpts o1, o2;
+    o1.triB = 1;  // Li11 is lower triangular: the K range shrinks with the tile column
+    LA_TRY(launch_gemm<T>(cv(L21), cv(Inv), T1, batch, n2, n1, n1, T(1), T(0), o1, st));
+    o2.triA = 1;  // Li22 is lower triangular: the K range grows with the tile row
+    o2.reverse = 1;
+    return launch_gemm<T>(cv(Inv).sub(n1, n1), cv(T1), Inv.sub(n1, 0), batch, n2, n1, n2, T(-1), T(0), o2, st);
 }
 
 // ---------------------------------------------------------------------------------
@@ -262,10 +281,17 @@ static la_status potrf_t(int lower, int64_t batch, int n, const void *A, void *L
         LA_TRY(launch_fill_i32(info, batch, 0, st));
     if (n <= NB)
         return launch_potrf_tiny<T>(Av, Lv, info, 0, batch, n, st);
-    View<T> Inv;
-    LA_TRY(scratch_views<T>(batch, n, 1, &Inv));
-    LA_TRY(launch_copy<T>(Av, Lv, batch, n, n, T(1), 1, st));  // L = tril(A), zeros above
-    return potrf_rec<T>(Lv, info, 0, batch, n, Inv, st);
+    if (n <= 2 * NB) {  // one leaf: it reads A and writes L directly
+        View<T> Inv;
+        LA_TRY(scratch_views<T>(batch, n, 1, &Inv));
+        if (n > NB)  // the 128-leaf leaves L's block (0,1) alone
+            LA_TRY(launch_tril_split<T>(Av, Inv, Lv, batch, n, st));
+        return launch_potrf_leaf<T>(Av, Lv, Inv, info, 0, batch, n, st);
+    }
+    View<T> sc[2];  // inverses of the diagonal blocks; working copy of the lower triangle of A
+    LA_TRY(scratch_views<T>(batch, n, 2, sc));
+    LA_TRY(launch_tril_split<T>(Av, sc[1], Lv, batch, n, st));  // zeros above the diagonal of L
+    return potrf_rec<T>(sc[1], Lv, info, 0, batch, n, sc[0], false, st);
 }
 
 // trsm / trmm (section 4.2).  vectors: columns of A/B (left) or rows (right); X(e, v) = element e
