@@ -255,6 +255,14 @@ template <typename T>
 la_status launch_potrf_leaf(View<const T> A, View<T> L, View<T> Inv, int32_t *info, int info_off, int64_t batch, int nb,
                             hipStream_t st);
 
+// Same contract as launch_potrf_leaf with 16 x 16 tiles in LDS: the factor's lower triangle
+// (zeros above the diagonal inside the 16 x 16 diagonal tiles; nothing else above it is
+// written unless zero_upper, which zeroes all of L above the diagonal) and the lower triangle of
+// its inverse.  A may alias L.
+template <typename T>
+la_status launch_potrf_leaf16(View<const T> A, View<T> L, View<T> Inv, int32_t *info, int info_off, int64_t batch,
+                              int nb, bool zero_upper, hipStream_t st);
+
 // Register-resident potrf backward for n <= 32: Abar = sym(L^-T Phi(L^T Lbar) L^-1).
 template <typename T>
 la_status launch_backward_tiny(View<const T> L, View<const T> G, View<T> Abar, int64_t batch, int n,

@@ -185,7 +185,7 @@ static la_status potrf_rec(View<T> Wk, View<T> L, int32_t *info, int off, int64_
                            bool need_inv, hipStream_t st)
 {
     if (n <= 2 * NB)  // factor and inverse in one launch
-        return launch_potrf_leaf<T>(cv(Wk), L, Inv, info, off, batch, n, st);
+        return launch_potrf_leaf16<T>(cv(Wk), L, Inv, info, off, batch, n, false, st);
     const int n1 = split_point(n), n2 = n - n1;
     View<T> L21 = L.sub(n1, 0), Wk22 = Wk.sub(n1, n1);
     LA_TRY(potrf_rec<T>(Wk, L, info, off, batch, n1, Inv, true, st));
@@ -284,9 +284,7 @@ static la_status potrf_t(int lower, int64_t batch, int n, const void *A, void *L
     if (n <= 2 * NB) {  // one leaf: it reads A and writes L directly
         View<T> Inv;
         LA_TRY(scratch_views<T>(batch, n, 1, &Inv));
-        if (n > NB)  // the 128-leaf leaves L's block (0,1) alone
-            LA_TRY(launch_tril_split<T>(Av, Inv, Lv, batch, n, st));
-        return launch_potrf_leaf<T>(Av, Lv, Inv, info, 0, batch, n, st);
+        return launch_potrf_leaf16<T>(Av, Lv, Inv, info, 0, batch, n, true, st);
     }
     View<T> sc[2];  // inverses of the diagonal blocks; working copy of the lower triangle of A
     LA_TRY(scratch_views<T>(batch, n, 2, sc));
