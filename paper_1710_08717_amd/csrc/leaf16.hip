@@ -11,15 +11,21 @@
 //       completes row k of the inverse X = L^-1;
 //   (c) trailing   A_ij -= L_ik L_jk^T  (k < j <= i)   and   X_ij -= L_ik X_kj  (i > k, j <= k).
 // (b) and (c) are 16 x 16 x 16 products on the matrix cores, one tile per wavefront at a
-// time.  The 16 * K pivots are strictly sequential, so what counts is the length of (a); the
-// matrix-core phases are short and parallel.
+// time.  The 16 * K pivots are strictly sequential, so what counts is the chain
+//   (a) -> panel tile (k+1, k) -> update of tile (k+1, k+1) -> (a) of the next step:
+// wavefront 0 walks exactly that chain while the other seven do the rest of (b) and (c) of
+// step k behind it (two workgroup barriers per step).
 #include "common.hpp"
+
+#ifndef LEAF16_STAMP
+#define LEAF16_STAMP(i)
+#endif
 
 namespace la {
 
 constexpr int LT = 16;              // tile edge
 constexpr int LK = 8;               // tiles per block edge (128 / 16)
-constexpr int LEAF16_THREADS = 512;
+constexpr int LEAF16_THREADS = 1024;
 constexpr int LEAF16_WAVES = LEAF16_THREADS / 64;
 
 template <typename T>
@@ -103,36 +109,43 @@ __device__ __forceinline__ double rcp_newton(double x)
     return fma(r, e, r);
 }
 
-// Factor and invert one 16 x 16 tile held one row per lane (all four 16-lane rows of the
-// wavefront work on copies of the same tile).  In: a[c] = A(r, c) for c <= r (what lies above
-// the diagonal is never looked at).  Out: a[c] = L(r, c), x[c] = L^-1(r, c) for c <= r (entries
-// above the diagonal hold leftovers) and the return value is the 1-based index of the first pivot
-// that is not > 0, or 0.
+// Factor and invert one 16 x 16 tile held one row per lane.  All four 16-lane rows of the
+// wavefront factor copies of the same tile; the inverse is shared out between them: in lane row
+// g register x[j] is column 4 j + g of the inverse.
+// In: a[c] = A(r, c) for c <= r (what lies above the diagonal is never looked at).
+// Out: a[c] = L(r, c) for c <= r, x[j] = L^-1(r, 4 j + g) (entries above the diagonal hold
+// leftovers, respectively zero) and the return value is the 1-based index of the first pivot that
+// is not > 0, or 0.
 //
 // The pivots run on the unscaled matrix,   a_rc -= a_rk a_ck / a_kk,   x_rc -= a_rk x_kc / a_kk,
-// which needs only a reciprocal on the critical path; the square roots are taken for all 16
-// pivots at once afterwards:  L = A_raw diag(d)^-1/2,  L^-1 = diag(d)^-1/2 X_raw.
+// which needs only a reciprocal on the critical path (started as soon as the next pivot is final);
+// the square roots are taken for all 16 pivots at once afterwards:
+// L = A_raw diag(d)^-1/2,  L^-1 = diag(d)^-1/2 X_raw.
 template <typename T>
-__device__ __forceinline__ int diag_factor_invert(T (&a)[LT], T (&x)[LT], int r)
+__device__ __forceinline__ int diag_factor_invert(T (&a)[LT], T (&x)[4], int r, int g)
 {
     T d = T(1);
 #pragma unroll
-    for (int c = 0; c < LT; ++c)
-        x[c] = (c == r) ? T(1) : T(0);
+    for (int j = 0; j < 4; ++j)
+        x[j] = (4 * j + g == r) ? T(1) : T(0);
+    T rinv = rcp_newton(a[0]);  // meaningful in the pivot's lane only
     static_for<0, LT>([&](auto kc) {
         constexpr int k = decltype(kc)::value;
-        T rinv = rcp_newton(a[k]);  // meaningful in lane k only
         const T am = (r > k) ? a[k] : T(0);
         d = (r == k) ? a[k] : d;
         settle(rinv);
         const T t = mul_row<k>(rinv, am);  // a_rk / a_kk below the pivot, zero elsewhere
-        static_for<k + 1, LT>([&](auto cc) {
+        if constexpr (k + 1 < LT) {
+            fnmac_row<k + 1>(a[k + 1], a[k], t);
+            rinv = rcp_newton(a[k + 1]);  // overlaps the rest of this pivot's updates
+        }
+        static_for<k + 2, LT>([&](auto cc) {
             constexpr int c = decltype(cc)::value;
             fnmac_row<c>(a[c], a[k], t);  // a_rc -= a_ck t_r
         });
-        static_for<0, k + 1>([&](auto cc) {
-            constexpr int c = decltype(cc)::value;
-            fnmac_row_self<k>(x[c], t);  // x_rc -= x_kc t_r
+        static_for<0, k / 4 + 1>([&](auto jc) {
+            constexpr int j = decltype(jc)::value;
+            fnmac_row_self<k>(x[j], t);  // x_rc -= x_kc t_r (a no-op where column c > k)
         });
     });
     const unsigned long long bad = __ballot(!(d > T(0)));
@@ -141,66 +154,85 @@ __device__ __forceinline__ int diag_factor_invert(T (&a)[LT], T (&x)[LT], int r)
     static_for<0, LT>([&](auto cc) {
         constexpr int c = decltype(cc)::value;
         a[c] = mul_row<c>(rs, a[c]);  // column c times d_c^-1/2
-        x[c] *= rs;                   // row r times d_r^-1/2
     });
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+        x[j] *= rs;  // row r times d_r^-1/2
     const unsigned first = (unsigned)(bad & 0xffffu);
     return first ? __builtin_ctz(first) + 1 : 0;
 }
 
-// four consecutive elements starting at p (16-byte aligned for the strides used here)
+// ---------------------------------------------------------------------------------------
+// Tiles in LDS.  Diagonal tiles are stored with padded rows (stride PS) for the row-per-lane
+// accesses of the factorisation.  Off-diagonal tiles are 16 x 16 without padding, with the
+// 16-byte chunks of every row permuted by the row number, so that both access patterns of the
+// matrix-core operands sweep all banks: a lane reading four consecutive elements of "its" row
+// (rows 128 or 64 bytes apart would otherwise all start in the same bank), and 16 lanes reading
+// one row.
+// ---------------------------------------------------------------------------------------
 template <typename T>
-__device__ __forceinline__ void load4(const T *p, T (&v)[4])
+__device__ __forceinline__ int sw(int u, int w)  // element (u, w) of an off-diagonal tile
 {
-    using V = typename Mfma<T>::vec_t;
-    constexpr int VW = Mfma<T>::VW;
-    const V *q = reinterpret_cast<const V *>(p);
-#pragma unroll
-    for (int i = 0; i < 4 / VW; ++i) {
-        const V w = q[i];
-        if constexpr (VW == 2) {
-            v[2 * i] = w.x;
-            v[2 * i + 1] = w.y;
-        } else {
-            v[0] = w.x;
-            v[1] = w.y;
-            v[2] = w.z;
-            v[3] = w.w;
-        }
-    }
+    constexpr int EPC = 16 / (int)sizeof(T);  // elements per 16-byte chunk
+    constexpr int CPR = LT / EPC;             // chunks per row
+    const int key = (sizeof(T) == 8 ? u : (u >> 1)) & (CPR - 1);
+    return u * LT + (((w / EPC) ^ key) * EPC) + (w % EPC);
 }
 
-// One 16 x 16 x 16 product step on a tile.  Operand element k of the contraction is dealt to
-// lane group q = lane / 16 and register s as k = 4 q + s, the same for both operands, so that an
-// operand stored with k contiguous is read as four consecutive elements per lane.
-//   rowA / rowB: operand(i, k) = p[i * ld + k]        (this wavefront's lane supplies i = lane % 16)
-//   natB:        operand(k, j) = p[k * ld + j]
 template <typename T>
-__device__ __forceinline__ void op_rows(const T *p, int ld, int lane, T (&v)[4])
+struct TileRef {
+    T *p;
+    bool diag;  // padded diagonal tile (row stride PS, no permutation)
+    __device__ __forceinline__ int at(int u, int w) const { return diag ? u * Leaf16<T>::PS + w : sw<T>(u, w); }
+};
+
+// Operand element k of the 16 x 16 x 16 contraction is dealt to lane group q = lane / 16 and
+// register s as k = 4 q + s, the same for both operands, so that an operand stored with k
+// contiguous is read as four consecutive elements (one or two 16-byte chunks) per lane.
+//   op_rows: operand(i, k) = tile(i, k), this lane supplies i = lane % 16
+//   op_nat:  operand(k, j) = tile(k, j), this lane supplies j = lane % 16
+template <typename T>
+__device__ __forceinline__ void op_rows(TileRef<T> t, int lane, T (&v)[4])
 {
-    load4<T>(p + (lane & 15) * ld + 4 * (lane >> 4), v);
+    using V = typename Mfma<T>::vec_t;
+    const int u = lane & 15, q = lane >> 4;
+    if constexpr (sizeof(T) == 8) {
+        const V lo = *reinterpret_cast<const V *>(t.p + t.at(u, 4 * q));
+        const V hi = *reinterpret_cast<const V *>(t.p + t.at(u, 4 * q + 2));
+        v[0] = lo.x;
+        v[1] = lo.y;
+        v[2] = hi.x;
+        v[3] = hi.y;
+    } else {
+        const V w = *reinterpret_cast<const V *>(t.p + t.at(u, 4 * q));
+        v[0] = w.x;
+        v[1] = w.y;
+        v[2] = w.z;
+        v[3] = w.w;
+    }
 }
 template <typename T>
-__device__ __forceinline__ void op_nat(const T *p, int ld, int lane, T (&v)[4])
+__device__ __forceinline__ void op_nat(TileRef<T> t, int lane, T (&v)[4])
 {
 #pragma unroll
     for (int s = 0; s < 4; ++s)
-        v[s] = p[(4 * (lane >> 4) + s) * ld + (lane & 15)];
+        v[s] = t.p[t.at(4 * (lane >> 4) + s, lane & 15)];
 }
 template <typename T>
-__device__ __forceinline__ typename Mfma<T>::acc_t acc_load(const T *p, int ld, int lane)
+__device__ __forceinline__ typename Mfma<T>::acc_t acc_load(TileRef<T> t, int lane)
 {
     typename Mfma<T>::acc_t c;
 #pragma unroll
     for (int v = 0; v < 4; ++v)
-        c[v] = p[Mfma<T>::row(lane, v) * ld + (lane & 15)];
+        c[v] = t.p[t.at(Mfma<T>::row(lane, v), lane & 15)];
     return c;
 }
 template <typename T>
-__device__ __forceinline__ void acc_store(T *p, int ld, int lane, typename Mfma<T>::acc_t c)
+__device__ __forceinline__ void acc_store(TileRef<T> t, int lane, typename Mfma<T>::acc_t c)
 {
 #pragma unroll
     for (int v = 0; v < 4; ++v)
-        p[Mfma<T>::row(lane, v) * ld + (lane & 15)] = c[v];
+        t.p[t.at(Mfma<T>::row(lane, v), lane & 15)] = c[v];
 }
 template <typename T>
 __device__ __forceinline__ typename Mfma<T>::acc_t mma4(const T (&a)[4], const T (&b)[4], typename Mfma<T>::acc_t c,
@@ -213,163 +245,271 @@ __device__ __forceinline__ typename Mfma<T>::acc_t mma4(const T (&a)[4], const T
 }
 
 template <typename T>
+struct LeafLds {
+    T *sD, *sXD, *sA, *sX;
+    __device__ __forceinline__ TileRef<T> a(int i, int j) const  // tile (i, j) of A / L, i >= j
+    {
+        return i == j ? TileRef<T>{sD + i * Leaf16<T>::DT, true} : TileRef<T>{sA + tri_off(i, j) * Leaf16<T>::OT, false};
+    }
+    __device__ __forceinline__ TileRef<T> x(int i, int j) const  // tile (i, j) of the inverse, i >= j
+    {
+        return i == j ? TileRef<T>{sXD + i * Leaf16<T>::DT, true} : TileRef<T>{sX + tri_off(i, j) * Leaf16<T>::OT, false};
+    }
+};
+
+// (a): diagonal tile k, by one whole wavefront
+template <typename T>
+__device__ __forceinline__ int leaf_diag(const LeafLds<T> &m, int k, int lane)
+{
+    constexpr int PS = Leaf16<T>::PS;
+    const int r = lane & 15, g = lane >> 4;
+    T a[LT], x[4];
+    T *dk = m.sD + k * Leaf16<T>::DT + r * PS, *xk = m.sXD + k * Leaf16<T>::DT + r * PS;
+    using V = typename Mfma<T>::vec_t;
+    constexpr int VW = Mfma<T>::VW;
+#pragma unroll
+    for (int c = 0; c < LT; c += VW) {
+        const V w = *reinterpret_cast<const V *>(dk + c);
+        a[c] = w.x;
+        a[c + 1] = w.y;
+        if constexpr (VW == 4) {
+            a[c + 2] = w.z;
+            a[c + 3] = w.w;
+        }
+    }
+    const int f = diag_factor_invert<T>(a, x, r, g);
+    if (lane < LT) {
+#pragma unroll
+        for (int c = 0; c < LT; ++c)
+            dk[c] = (c <= r) ? a[c] : T(0);
+    }
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+        xk[4 * j + g] = (4 * j + g <= r) ? x[j] : T(0);
+    return f;
+}
+
+// (b): L_ik = A_ik Li_kk^T
+template <typename T>
+__device__ __forceinline__ void leaf_panel(const LeafLds<T> &m, int i, int k, int lane)
+{
+    T av[4], bv[4];
+    typename Mfma<T>::acc_t acc = {0, 0, 0, 0};
+    op_rows<T>(m.a(i, k), lane, av);
+    op_rows<T>(m.x(k, k), lane, bv);
+    acc = mma4<T>(av, bv, acc, false);
+    acc_store<T>(m.a(i, k), lane, acc);
+}
+// (b): X_kj <- Li_kk X_kj, j < k
+template <typename T>
+__device__ __forceinline__ void leaf_xrow(const LeafLds<T> &m, int k, int j, int lane)
+{
+    T av[4], bv[4];
+    typename Mfma<T>::acc_t acc = {0, 0, 0, 0};
+    op_rows<T>(m.x(k, k), lane, av);
+    op_nat<T>(m.x(k, j), lane, bv);
+    acc = mma4<T>(av, bv, acc, false);
+    acc_store<T>(m.x(k, j), lane, acc);
+}
+// (c): A_ij -= L_ik L_jk^T, k < j <= i
+template <typename T>
+__device__ __forceinline__ void leaf_update_a(const LeafLds<T> &m, int i, int j, int k, int lane)
+{
+    T av[4], bv[4];
+    op_rows<T>(m.a(i, k), lane, av);
+    op_rows<T>(m.a(j, k), lane, bv);
+    typename Mfma<T>::acc_t acc = acc_load<T>(m.a(i, j), lane);
+    acc = mma4<T>(av, bv, acc, true);
+    acc_store<T>(m.a(i, j), lane, acc);
+}
+// (c): X_ij -= L_ik X_kj, i > k, j <= k (tile (i, k) of the inverse starts from zero)
+template <typename T>
+__device__ __forceinline__ void leaf_update_x(const LeafLds<T> &m, int i, int j, int k, int lane)
+{
+    T av[4], bv[4];
+    op_rows<T>(m.a(i, k), lane, av);
+    op_nat<T>(m.x(k, j), lane, bv);
+    typename Mfma<T>::acc_t acc = {0, 0, 0, 0};
+    if (j < k)
+        acc = acc_load<T>(m.x(i, j), lane);
+    acc = mma4<T>(av, bv, acc, true);
+    acc_store<T>(m.x(i, j), lane, acc);
+}
+
+// tile (ti, tj) number t of the lower triangle counted row by row
+__device__ __forceinline__ void tri_decode(int t, int &ti, int &tj)
+{
+    ti = 0;
+    while (t > ti) {
+        t -= ti + 1;
+        ++ti;
+    }
+    tj = t;
+}
+
+template <typename T>
 __global__ __launch_bounds__(LEAF16_THREADS) void k_potrf_leaf16(View<const T> A, View<T> L, View<T> Inv, int32_t *info,
                                                                  int info_off, int64_t batch, int nb, int zero_upper)
 {
     using C = Leaf16<T>;
-    using MF = Mfma<T>;
     extern __shared__ __align__(16) unsigned char leaf16_lds[];
     T *lds = reinterpret_cast<T *>(leaf16_lds);
-    T *sD = lds + C::OFF_D, *sXD = lds + C::OFF_XD, *sA = lds + C::OFF_A, *sX = lds + C::OFF_X;
-    constexpr int PS = C::PS, DT = C::DT, OT = C::OT;
+    const LeafLds<T> m{lds + C::OFF_D, lds + C::OFF_XD, lds + C::OFF_A, lds + C::OFF_X};
+    constexpr int W = LEAF16_WAVES;
+    constexpr int TPW = (LK * (LK + 1) / 2 + W - 1) / W;  // lower tiles per wavefront, at most
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int K = (nb + LT - 1) / LT;  // tile columns in use
-    const int ne = K * LT;
+    const int ntl = K * (K + 1) / 2;
     const int64_t b = blockIdx.x;
-    const T *ap = A.p + b * A.bs;
+    LEAF16_STAMP(31);
 
-    // ---- lower triangle of the block into tiles (identity outside nb x nb) ------------------
+    // ---- lower triangle of the block into tiles (identity outside nb x nb).  Per tile a lane
+    //      moves four elements, 16 lanes along the contiguous direction of the operand. ---------
     {
+        const T *ap = A.p + b * A.bs;
         const bool colfast = (A.cs == 1) || (A.rs != 1);
-        for (int e = tid; e < ne * ne; e += LEAF16_THREADS) {
-            const int u = e / ne, w = e % ne;
-            const int r = colfast ? u : w, c = colfast ? w : u;
-            const int ti = r / LT, tj = c / LT;
-            if (tj > ti)
-                continue;
-            T v = (r == c) ? T(1) : T(0);
-            if (r < nb && c <= r)
-                v = ap[(int64_t)r * A.rs + (int64_t)c * A.cs];
-            if (ti == tj)
-                sD[ti * DT + (r % LT) * PS + (c % LT)] = v;
-            else
-                sA[tri_off(ti, tj) * OT + (r % LT) * LT + (c % LT)] = v;
+        const int f = lane & 15, s0 = lane >> 4;  // fast and slow coordinate inside the tile (slow: s0 + 4 v)
+        const int64_t fs = colfast ? A.cs : A.rs, ss = colfast ? A.rs : A.cs;  // their strides
+        const int64_t lane_off = (int64_t)f * fs + (int64_t)s0 * ss;
+        T val[TPW][4];
+#pragma unroll
+        for (int q = 0; q < TPW; ++q) {
+            const int t = wave + q * W;
+            int ti, tj;
+            tri_decode(t < ntl ? t : 0, ti, tj);
+            const T *tp = ap + (int64_t)(ti * LT) * A.rs + (int64_t)(tj * LT) * A.cs + lane_off;
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                const int u = colfast ? s0 + 4 * v : f, w = colfast ? f : s0 + 4 * v;
+                const int r = ti * LT + u, c = tj * LT + w;
+                T x = (r == c) ? T(1) : T(0);
+                if (t < ntl && r < nb && c <= r)
+                    x = *tp;
+                val[q][v] = x;
+                tp += 4 * ss;
+            }
+        }
+#pragma unroll
+        for (int q = 0; q < TPW; ++q) {
+            const int t = wave + q * W;
+            if (t < ntl) {
+                int ti, tj;
+                tri_decode(t, ti, tj);
+                const TileRef<T> tr = m.a(ti, tj);
+#pragma unroll
+                for (int v = 0; v < 4; ++v) {
+                    const int u = colfast ? s0 + 4 * v : f, w = colfast ? f : s0 + 4 * v;
+                    tr.p[tr.at(u, w)] = val[q][v];
+                }
+            }
         }
     }
     __syncthreads();
+    LEAF16_STAMP(0);
 
     int fail = 0;
+    if (wave == 0) {
+        const int f = leaf_diag<T>(m, 0, lane);
+        fail = f;
+    }
+    __syncthreads();
+    LEAF16_STAMP(1);
+
     for (int k = 0; k < K; ++k) {
-        // ---- (a) diagonal tile ------------------------------------------------------------
+        const int rows = K - 1 - k;  // tile rows below the pivot row
+        // ---- (b): wavefront 0 takes the panel tile the next diagonal tile depends on ------------
         if (wave == 0) {
-            const int r = lane & 15;
-            T a[LT], x[LT];
-            T *dk = sD + k * DT + r * PS, *xk = sXD + k * DT + r * PS;
-#pragma unroll
-            for (int c = 0; c < LT; c += 4) {
-                T v[4];
-                load4<T>(dk + c, v);
-                a[c] = v[0];
-                a[c + 1] = v[1];
-                a[c + 2] = v[2];
-                a[c + 3] = v[3];
+            if (rows > 0)
+                leaf_panel<T>(m, k + 1, k, lane);
+        } else {
+            const int np = rows > 0 ? rows - 1 : 0;
+            for (int it = wave - 1; it < np + k; it += W - 1) {
+                if (it < np)
+                    leaf_panel<T>(m, k + 2 + it, k, lane);
+                else
+                    leaf_xrow<T>(m, k, it - np, lane);
             }
-            const int f = diag_factor_invert<T>(a, x, r);
+        }
+        __syncthreads();
+        LEAF16_STAMP(2 + 2 * k);
+        if (rows == 0)
+            break;
+        // ---- (c): wavefront 0 updates the next diagonal tile and factors it -----------------------
+        if (wave == 0) {
+            leaf_update_a<T>(m, k + 1, k + 1, k, lane);
+            const int f = leaf_diag<T>(m, k + 1, lane);
             if (fail == 0 && f != 0)
-                fail = k * LT + f;
-            if (lane < LT) {
-#pragma unroll
-                for (int c = 0; c < LT; ++c) {
-                    dk[c] = (c <= r) ? a[c] : T(0);
-                    xk[c] = (c <= r) ? x[c] : T(0);
-                }
-            }
-        }
-        __syncthreads();
-
-        // ---- (b) panel below the diagonal tile, and row k of the inverse ------------------------
-        const T *lik = sXD + k * DT;  // Li_kk, row stride PS
-        for (int it = wave; it < K - 1; it += LEAF16_WAVES) {
-            T av[4], bv[4];
-            typename MF::acc_t acc = {0, 0, 0, 0};
-            if (it < K - 1 - k) {  // L_ik = A_ik Li_kk^T
-                const int i = k + 1 + it;
-                T *t = sA + tri_off(i, k) * OT;
-                op_rows<T>(t, LT, lane, av);
-                op_rows<T>(lik, PS, lane, bv);
-                acc = mma4<T>(av, bv, acc, false);
-                acc_store<T>(t, LT, lane, acc);
-            } else {  // X_kj <- Li_kk X_kj
-                const int j = it - (K - 1 - k);
-                T *t = sX + tri_off(k, j) * OT;
-                op_rows<T>(lik, PS, lane, av);
-                op_nat<T>(t, LT, lane, bv);
-                acc = mma4<T>(av, bv, acc, false);
-                acc_store<T>(t, LT, lane, acc);
-            }
-        }
-        __syncthreads();
-
-        // ---- (c) trailing updates --------------------------------------------------------------
-        const int m = K - 1 - k;         // tile rows below the pivot row
-        const int nx = m * (k + 1);      // tiles of X to update
-        const int na = m * (m + 1) / 2;  // tiles of A to update
-        for (int it = wave; it < nx + na; it += LEAF16_WAVES) {
-            T av[4], bv[4];
-            if (it < nx) {  // X_ij -= L_ik X_kj, j <= k
-                const int i = k + 1 + it / (k + 1), j = it % (k + 1);
-                T *t = sX + tri_off(i, j) * OT;
-                op_rows<T>(sA + tri_off(i, k) * OT, LT, lane, av);
-                typename MF::acc_t acc = {0, 0, 0, 0};
-                if (j == k) {
-                    op_nat<T>(lik, PS, lane, bv);
+                fail = (k + 1) * LT + f;
+        } else {
+            const int nx = rows * (k + 1);           // tiles of the inverse to update
+            const int na = rows * (rows + 1) / 2 - 1;  // tiles of A, without tile (k+1, k+1)
+            int xi = 0, xj = wave - 1;                // item number it = xi * (k + 1) + xj
+            for (int it = wave - 1; it < nx + na; it += W - 1) {
+                if (it < nx) {
+                    while (xj > k) {
+                        xj -= k + 1;
+                        ++xi;
+                    }
+                    leaf_update_x<T>(m, k + 1 + xi, xj, k, lane);
+                    xj += W - 1;
                 } else {
-                    op_nat<T>(sX + tri_off(k, j) * OT, LT, lane, bv);
-                    acc = acc_load<T>(t, LT, lane);
+                    int ii, jj;
+                    tri_decode(it - nx + 1, ii, jj);
+                    leaf_update_a<T>(m, k + 1 + ii, k + 1 + jj, k, lane);
                 }
-                acc = mma4<T>(av, bv, acc, true);
-                acc_store<T>(t, LT, lane, acc);
-            } else {  // A_ij -= L_ik L_jk^T, k < j <= i
-                int e = it - nx, ii = 0;
-                while (e > ii) {  // row ii of the triangle has ii + 1 tiles
-                    e -= ii + 1;
-                    ++ii;
-                }
-                const int i = k + 1 + ii, j = k + 1 + e;
-                T *t = (i == j) ? sD + i * DT : sA + tri_off(i, j) * OT;
-                const int ld = (i == j) ? PS : LT;
-                op_rows<T>(sA + tri_off(i, k) * OT, LT, lane, av);
-                op_rows<T>(sA + tri_off(j, k) * OT, LT, lane, bv);
-                typename MF::acc_t acc = acc_load<T>(t, ld, lane);
-                acc = mma4<T>(av, bv, acc, true);
-                acc_store<T>(t, ld, lane, acc);
             }
         }
         __syncthreads();
+        LEAF16_STAMP(3 + 2 * k);
     }
 
-    // ---- factor and inverse back to memory (lower tiles; zeros above the diagonal of the
-    //      diagonal tiles) ----------------------------------------------------------------------
+    // ---- factor and inverse back to memory (lower tiles; zeros above the diagonal inside the
+    //      diagonal tiles) -----------------------------------------------------------------------
     {
         T *lp = L.p + b * L.bs;
         T *ip = Inv.p + b * Inv.bs;
         const bool colfast = (L.cs == 1) || (L.rs != 1);
-        for (int e = tid; e < ne * ne; e += LEAF16_THREADS) {
-            const int u = e / ne, w = e % ne;
-            const int r = colfast ? u : w, c = colfast ? w : u;
-            const int ti = r / LT, tj = c / LT;
-            if (r >= nb || c >= nb)
-                continue;
-            if (tj > ti) {
-                if (zero_upper)
-                    lp[(int64_t)r * L.rs + (int64_t)c * L.cs] = T(0);
-                continue;
+        const int f = lane & 15, s0 = lane >> 4;
+        const int64_t lfs = colfast ? L.cs : L.rs, lss = colfast ? L.rs : L.cs;
+        const int64_t ifs = colfast ? Inv.cs : Inv.rs, iss = colfast ? Inv.rs : Inv.cs;
+        const int64_t l_off = (int64_t)f * lfs + (int64_t)s0 * lss, i_off = (int64_t)f * ifs + (int64_t)s0 * iss;
+        for (int t = wave; t < ntl; t += W) {
+            int ti, tj;
+            tri_decode(t, ti, tj);
+            const TileRef<T> ta = m.a(ti, tj), tx = m.x(ti, tj);
+            T *lt = lp + (int64_t)(ti * LT) * L.rs + (int64_t)(tj * LT) * L.cs + l_off;
+            T *it = ip + (int64_t)(ti * LT) * Inv.rs + (int64_t)(tj * LT) * Inv.cs + i_off;
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                const int u = colfast ? s0 + 4 * v : f, w = colfast ? f : s0 + 4 * v;
+                if (ti * LT + u < nb && tj * LT + w < nb) {
+                    *lt = ta.p[ta.at(u, w)];
+                    *it = tx.p[tx.at(u, w)];
+                }
+                lt += 4 * lss;
+                it += 4 * iss;
             }
-            T lv, xv;
-            if (ti == tj) {
-                lv = sD[ti * DT + (r % LT) * PS + (c % LT)];
-                xv = sXD[ti * DT + (r % LT) * PS + (c % LT)];
-            } else {
-                lv = sA[tri_off(ti, tj) * OT + (r % LT) * LT + (c % LT)];
-                xv = sX[tri_off(ti, tj) * OT + (r % LT) * LT + (c % LT)];
+        }
+        if (zero_upper) {  // the tiles above the diagonal of L
+            for (int t = wave; t < ntl - K; t += W) {
+                int tj, ti;
+                tri_decode(t, tj, ti);  // strictly lower (tj + 1, ti) mirrored
+                tj += 1;
+                T *lt = lp + (int64_t)(ti * LT) * L.rs + (int64_t)(tj * LT) * L.cs + l_off;
+#pragma unroll
+                for (int v = 0; v < 4; ++v) {
+                    const int u = colfast ? s0 + 4 * v : f, w = colfast ? f : s0 + 4 * v;
+                    if (ti * LT + u < nb && tj * LT + w < nb)
+                        *lt = T(0);
+                    lt += 4 * lss;
+                }
             }
-            lp[(int64_t)r * L.rs + (int64_t)c * L.cs] = lv;
-            ip[(int64_t)r * Inv.rs + (int64_t)c * Inv.cs] = xv;
         }
     }
+    LEAF16_STAMP(30);
     if (info != nullptr && tid == 0 && fail != 0 && fail <= nb) {
         if (info[b] == 0)
             info[b] = info_off + fail;

@@ -71,17 +71,39 @@ def test_checker_sees_a_planted_hazard():
     assert find_hazards(ok) == ([], 1)
 
 
-def test_small_matrix_kernels_respect_dpp_spacing():
+def _isa_text(name):
     from paper_1710_08717_amd import build
 
-    src = os.path.join(build.CSRC, "tiny.hip")
+    src = os.path.join(build.CSRC, name)
     with tempfile.TemporaryDirectory() as d:
-        out = os.path.join(d, "tiny.s")
+        out = os.path.join(d, "out.s")
         cmd = ["hipcc", *build.FLAGS, "--cuda-device-only", "-S", "-o", out, src]
         r = subprocess.run(cmd, capture_output=True, text=True)
         if r.returncode != 0:
             pytest.fail("hipcc -S failed:\n" + r.stderr[-2000:])
-        text = open(out).read()
+        return open(out).read()
+
+
+def test_checker_handles_64_bit_operands():
+    bad = "_Zk:\n v_fma_f64 v[4:5], v[0:1], v[2:3], v[4:5]\n v_fmac_f64_dpp v[8:9], -v[4:5], v[6:7] row_newbcast:4 row_mask:0xf bank_mask:0xf\n s_endpgm\n"
+    ok = "_Zk:\n v_fma_f64 v[4:5], v[0:1], v[2:3], v[4:5]\n s_nop 1\n v_fmac_f64_dpp v[8:9], -v[4:5], v[6:7] row_newbcast:4 row_mask:0xf bank_mask:0xf\n s_endpgm\n"
+    assert len(find_hazards(bad)[0]) == 1
+    assert find_hazards(ok) == ([], 1)
+
+
+def test_diagonal_block_leaf_respects_dpp_spacing():
+    text = _isa_text("leaf16.hip")
+    hazards, n_dpp = find_hazards(text)
+    # per element type two inlined copies of the 16 x 16 factor-and-invert routine, 192 broadcast
+    # multiply-adds each
+    assert text.count("v_fmac_f32_dpp") >= 384
+    assert text.count("v_fmac_f64_dpp") >= 384
+    assert n_dpp >= 768
+    assert hazards == []
+
+
+def test_small_matrix_kernels_respect_dpp_spacing():
+    text = _isa_text("tiny.hip")
     hazards, n_dpp = find_hazards(text)
     assert n_dpp > 600  # the fused v_fmac_f32_dpp of the fp32 16-lane kernels are really there
     assert text.count("v_fmac_f32_dpp") >= 600
