@@ -75,11 +75,39 @@ static la_status scratch_views(int64_t batch, int n, int count, View<T> *out)
     return LA_OK;
 }
 
+// Rough time, per unit of K, of the lower-triangle update C -= P P^T on n2 rows: the product
+// kernel runs two workgroups per compute unit (512 slots), with 128 x 128 tiles from 2048 rows on
+// and 64 x 64 tiles below, and a launch costs whole rounds of tiles: 528 tiles take twice as long
+// as 496.  (Relative figures measured on this kernel: a full round, a round that leaves half of
+// the compute units with a single workgroup.)
+static double lower_update_cost(int n2)
+{
+    const bool big = n2 >= 2048;
+    const int e = big ? 128 : 64;
+    const int64_t t = (n2 + e - 1) / e, c = t * (t + 1) / 2;
+    const double full = big ? 0.30 : 0.11, half = big ? 0.18 : 0.06;
+    const int64_t rounds = c / 512, rem = c % 512;
+    return rounds * full + (rem > 256 ? full : (rem > 0 ? half : 0.0));
+}
+
 static inline int split_point(int n)
 {
-    // first part: a multiple of the tile edge, about half of n, always < n for n > NB
-    int h = (n / 2 + NB - 1) / NB * NB;
-    return h;
+    // first part: a multiple of the tile edge (of 128 for larger n), about half of n, always < n
+    // for n > NB; moved up by at most n / 8 if that lets the trailing update run in full rounds
+    const int step = n >= 512 ? 2 * NB : NB;
+    const int h = (n / 2 + step - 1) / step * step;
+    if (n < 2048)
+        return h;
+    int best = h;
+    double best_score = lower_update_cost(n - h) / ((double)(n - h) * (n - h));
+    for (int n1 = h + step; n1 <= h + n / 8 && n1 < n; n1 += step) {
+        const double score = lower_update_cost(n - n1) / ((double)(n - n1) * (n - n1));
+        if (score < 0.95 * best_score) {
+            best = n1;
+            best_score = score;
+        }
+    }
+    return best;
 }
 
 template <typename T>
