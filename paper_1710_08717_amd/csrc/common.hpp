@@ -263,6 +263,11 @@ template <typename T>
 la_status launch_potrf_leaf16(View<const T> A, View<T> L, View<T> Inv, int32_t *info, int info_off, int64_t batch,
                               int nb, bool zero_upper, hipStream_t st);
 
+// Inverses of the 128 x 128 diagonal blocks of Lam (n x n lower triangular; the last block may be
+// smaller) written onto the diagonal blocks of Inv (lower triangles; nothing else is written).
+template <typename T>
+la_status launch_tri_inverse128(View<const T> Lam, View<T> Inv, int64_t batch, int n, hipStream_t st);
+
 // Register-resident potrf backward for n <= 32: Abar = sym(L^-T Phi(L^T Lbar) L^-1).
 template <typename T>
 la_status launch_backward_tiny(View<const T> L, View<const T> G, View<T> Abar, int64_t batch, int n,

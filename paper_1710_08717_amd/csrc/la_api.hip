@@ -118,7 +118,7 @@ static inline View<const T> cv(View<T> v)
 
 // ---------------------------------------------------------------------------------
 // Explicit inverse of a lower-triangular Lam (n x n) into Inv (n x n, lower triangle; what lies
-// above the diagonal is never written and never read).  First the 64 x 64 diagonal blocks (one
+// above the diagonal is never written and never read).  First the 128 x 128 diagonal blocks (one
 // launch for the whole batch), then level by level
 //     inv [A 0; C D] = [A^-1 0; -D^-1 C A^-1, D^-1]
 // with all pairs of one level in one batched GEMM pair.  Stops when blocks of `upto` are
@@ -128,8 +128,8 @@ template <typename T>
 static la_status inverse_build(View<const T> Lam, View<T> Inv, View<T> Tmp, int64_t batch, int n, int upto,
                                hipStream_t st)
 {
-    LA_TRY(launch_tile_inverse<T>(Lam, Inv, batch, n, st));
-    for (int64_t h = NB; h < upto && h < n; h *= 2) {
+    LA_TRY(launch_tri_inverse128<T>(Lam, Inv, batch, n, st));
+    for (int64_t h = 2 * NB; h < upto && h < n; h *= 2) {
         const int nfull = (int)(n / (2 * h));                       // pairs whose right block is a full h
         const int r = (int)(n - (int64_t)nfull * 2 * h - h);        // rows of a ragged right block (if > 0)
         for (int pass = 0; pass < 2; ++pass) {
@@ -352,7 +352,7 @@ static la_status tri_apply_t(bool solve, int lower, int trans, int rightside, do
             LA_TRY(launch_copy<T>(Xin, X, batch, n, m, (T)alpha, 0, st));
         View<T> Inv;
         LA_TRY(scratch_views<T>(batch, n, 1, &Inv));
-        LA_TRY(launch_tile_inverse<T>(Lam, Inv, batch, n, st));
+        LA_TRY(launch_tri_inverse128<T>(Lam, Inv, batch, n, st));
         return solve_rec<T>(Lam, X, batch, n, m, fwd, cv(Inv), false, st);
     }
 

@@ -347,6 +347,98 @@ __device__ __forceinline__ void tri_decode(int t, int &ti, int &tj)
     tj = t;
 }
 
+// Lower triangle of an nb x nb block at p (element strides rs, cs) into the tiles of A (identity
+// outside nb x nb).  Per tile a lane moves four elements, 16 lanes along the contiguous direction
+// of the operand; all loads of a wavefront are in flight together.
+template <typename T>
+__device__ __forceinline__ void leaf_load_lower(const LeafLds<T> &m, const T *p, int64_t rs, int64_t cs, int nb,
+                                                int wave, int lane)
+{
+    constexpr int W = LEAF16_WAVES;
+    constexpr int TPW = (LK * (LK + 1) / 2 + W - 1) / W;  // lower tiles per wavefront, at most
+    const int K = (nb + LT - 1) / LT;
+    const int ntl = K * (K + 1) / 2;
+    const bool colfast = (cs == 1) || (rs != 1);
+    const int f = lane & 15, s0 = lane >> 4;  // fast and slow coordinate inside the tile (slow: s0 + 4 v)
+    const int64_t fs = colfast ? cs : rs, ss = colfast ? rs : cs;  // their strides
+    const int64_t lane_off = (int64_t)f * fs + (int64_t)s0 * ss;
+    T val[TPW][4];
+#pragma unroll
+    for (int q = 0; q < TPW; ++q) {
+        const int t = wave + q * W;
+        int ti, tj;
+        tri_decode(t < ntl ? t : 0, ti, tj);
+        const T *tp = p + (int64_t)(ti * LT) * rs + (int64_t)(tj * LT) * cs + lane_off;
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+            const int u = colfast ? s0 + 4 * v : f, w = colfast ? f : s0 + 4 * v;
+            const int r = ti * LT + u, c = tj * LT + w;
+            T x = (r == c) ? T(1) : T(0);
+            if (t < ntl && r < nb && c <= r)
+                x = *tp;
+            val[q][v] = x;
+            tp += 4 * ss;
+        }
+    }
+#pragma unroll
+    for (int q = 0; q < TPW; ++q) {
+        const int t = wave + q * W;
+        if (t < ntl) {
+            int ti, tj;
+            tri_decode(t, ti, tj);
+            const TileRef<T> tr = m.a(ti, tj);
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                const int u = colfast ? s0 + 4 * v : f, w = colfast ? f : s0 + 4 * v;
+                tr.p[tr.at(u, w)] = val[q][v];
+            }
+        }
+    }
+}
+
+// The lower tiles of A / L (inverse == false) or of the inverse back to an nb x nb block at p;
+// zero_upper also writes zeros to the tiles above the diagonal.
+template <typename T>
+__device__ __forceinline__ void leaf_store_lower(const LeafLds<T> &m, bool inverse, T *p, int64_t rs, int64_t cs,
+                                                 int nb, bool zero_upper, int wave, int lane)
+{
+    constexpr int W = LEAF16_WAVES;
+    const int K = (nb + LT - 1) / LT;
+    const int ntl = K * (K + 1) / 2;
+    const bool colfast = (cs == 1) || (rs != 1);
+    const int f = lane & 15, s0 = lane >> 4;
+    const int64_t fs = colfast ? cs : rs, ss = colfast ? rs : cs;
+    const int64_t lane_off = (int64_t)f * fs + (int64_t)s0 * ss;
+    for (int t = wave; t < ntl; t += W) {
+        int ti, tj;
+        tri_decode(t, ti, tj);
+        const TileRef<T> tr = inverse ? m.x(ti, tj) : m.a(ti, tj);
+        T *tp = p + (int64_t)(ti * LT) * rs + (int64_t)(tj * LT) * cs + lane_off;
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+            const int u = colfast ? s0 + 4 * v : f, w = colfast ? f : s0 + 4 * v;
+            if (ti * LT + u < nb && tj * LT + w < nb)
+                *tp = tr.p[tr.at(u, w)];
+            tp += 4 * ss;
+        }
+    }
+    if (zero_upper) {
+        for (int t = wave; t < ntl - K; t += W) {
+            int tj, ti;
+            tri_decode(t, tj, ti);  // strictly lower (tj + 1, ti), mirrored
+            tj += 1;
+            T *tp = p + (int64_t)(ti * LT) * rs + (int64_t)(tj * LT) * cs + lane_off;
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                const int u = colfast ? s0 + 4 * v : f, w = colfast ? f : s0 + 4 * v;
+                if (ti * LT + u < nb && tj * LT + w < nb)
+                    *tp = T(0);
+                tp += 4 * ss;
+            }
+        }
+    }
+}
+
 template <typename T>
 __global__ __launch_bounds__(LEAF16_THREADS) void k_potrf_leaf16(View<const T> A, View<T> L, View<T> Inv, int32_t *info,
                                                                  int info_off, int64_t batch, int nb, int zero_upper)
@@ -356,57 +448,15 @@ __global__ __launch_bounds__(LEAF16_THREADS) void k_potrf_leaf16(View<const T> A
     T *lds = reinterpret_cast<T *>(leaf16_lds);
     const LeafLds<T> m{lds + C::OFF_D, lds + C::OFF_XD, lds + C::OFF_A, lds + C::OFF_X};
     constexpr int W = LEAF16_WAVES;
-    constexpr int TPW = (LK * (LK + 1) / 2 + W - 1) / W;  // lower tiles per wavefront, at most
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int K = (nb + LT - 1) / LT;  // tile columns in use
-    const int ntl = K * (K + 1) / 2;
     const int64_t b = blockIdx.x;
     LEAF16_STAMP(31);
 
-    // ---- lower triangle of the block into tiles (identity outside nb x nb).  Per tile a lane
-    //      moves four elements, 16 lanes along the contiguous direction of the operand. ---------
-    {
-        const T *ap = A.p + b * A.bs;
-        const bool colfast = (A.cs == 1) || (A.rs != 1);
-        const int f = lane & 15, s0 = lane >> 4;  // fast and slow coordinate inside the tile (slow: s0 + 4 v)
-        const int64_t fs = colfast ? A.cs : A.rs, ss = colfast ? A.rs : A.cs;  // their strides
-        const int64_t lane_off = (int64_t)f * fs + (int64_t)s0 * ss;
-        T val[TPW][4];
-#pragma unroll
-        for (int q = 0; q < TPW; ++q) {
-            const int t = wave + q * W;
-            int ti, tj;
-            tri_decode(t < ntl ? t : 0, ti, tj);
-            const T *tp = ap + (int64_t)(ti * LT) * A.rs + (int64_t)(tj * LT) * A.cs + lane_off;
-#pragma unroll
-            for (int v = 0; v < 4; ++v) {
-                const int u = colfast ? s0 + 4 * v : f, w = colfast ? f : s0 + 4 * v;
-                const int r = ti * LT + u, c = tj * LT + w;
-                T x = (r == c) ? T(1) : T(0);
-                if (t < ntl && r < nb && c <= r)
-                    x = *tp;
-                val[q][v] = x;
-                tp += 4 * ss;
-            }
-        }
-#pragma unroll
-        for (int q = 0; q < TPW; ++q) {
-            const int t = wave + q * W;
-            if (t < ntl) {
-                int ti, tj;
-                tri_decode(t, ti, tj);
-                const TileRef<T> tr = m.a(ti, tj);
-#pragma unroll
-                for (int v = 0; v < 4; ++v) {
-                    const int u = colfast ? s0 + 4 * v : f, w = colfast ? f : s0 + 4 * v;
-                    tr.p[tr.at(u, w)] = val[q][v];
-                }
-            }
-        }
-    }
+    leaf_load_lower<T>(m, A.p + b * A.bs, A.rs, A.cs, nb, wave, lane);
     __syncthreads();
     LEAF16_STAMP(0);
 
@@ -468,52 +518,105 @@ __global__ __launch_bounds__(LEAF16_THREADS) void k_potrf_leaf16(View<const T> A
 
     // ---- factor and inverse back to memory (lower tiles; zeros above the diagonal inside the
     //      diagonal tiles) -----------------------------------------------------------------------
-    {
-        T *lp = L.p + b * L.bs;
-        T *ip = Inv.p + b * Inv.bs;
-        const bool colfast = (L.cs == 1) || (L.rs != 1);
-        const int f = lane & 15, s0 = lane >> 4;
-        const int64_t lfs = colfast ? L.cs : L.rs, lss = colfast ? L.rs : L.cs;
-        const int64_t ifs = colfast ? Inv.cs : Inv.rs, iss = colfast ? Inv.rs : Inv.cs;
-        const int64_t l_off = (int64_t)f * lfs + (int64_t)s0 * lss, i_off = (int64_t)f * ifs + (int64_t)s0 * iss;
-        for (int t = wave; t < ntl; t += W) {
-            int ti, tj;
-            tri_decode(t, ti, tj);
-            const TileRef<T> ta = m.a(ti, tj), tx = m.x(ti, tj);
-            T *lt = lp + (int64_t)(ti * LT) * L.rs + (int64_t)(tj * LT) * L.cs + l_off;
-            T *it = ip + (int64_t)(ti * LT) * Inv.rs + (int64_t)(tj * LT) * Inv.cs + i_off;
-#pragma unroll
-            for (int v = 0; v < 4; ++v) {
-                const int u = colfast ? s0 + 4 * v : f, w = colfast ? f : s0 + 4 * v;
-                if (ti * LT + u < nb && tj * LT + w < nb) {
-                    *lt = ta.p[ta.at(u, w)];
-                    *it = tx.p[tx.at(u, w)];
-                }
-                lt += 4 * lss;
-                it += 4 * iss;
-            }
-        }
-        if (zero_upper) {  // the tiles above the diagonal of L
-            for (int t = wave; t < ntl - K; t += W) {
-                int tj, ti;
-                tri_decode(t, tj, ti);  // strictly lower (tj + 1, ti) mirrored
-                tj += 1;
-                T *lt = lp + (int64_t)(ti * LT) * L.rs + (int64_t)(tj * LT) * L.cs + l_off;
-#pragma unroll
-                for (int v = 0; v < 4; ++v) {
-                    const int u = colfast ? s0 + 4 * v : f, w = colfast ? f : s0 + 4 * v;
-                    if (ti * LT + u < nb && tj * LT + w < nb)
-                        *lt = T(0);
-                    lt += 4 * lss;
-                }
-            }
-        }
-    }
+    leaf_store_lower<T>(m, false, L.p + b * L.bs, L.rs, L.cs, nb, zero_upper != 0, wave, lane);
+    leaf_store_lower<T>(m, true, Inv.p + b * Inv.bs, Inv.rs, Inv.cs, nb, false, wave, lane);
     LEAF16_STAMP(30);
     if (info != nullptr && tid == 0 && fail != 0 && fail <= nb) {
         if (info[b] == 0)
             info[b] = info_off + fail;
     }
+}
+
+// ---------------------------------------------------------------------------------------
+// Inverse of a GIVEN lower-triangular factor (the potrf backward pass and trsm need L^-1 of their
+// input, section 4.2): the diagonal blocks of edge 128 of Lam (n x n), one workgroup each, written
+// onto the diagonal blocks of Inv.  Same tiles and matrix-core steps as above without the
+// factorisation, so the 16 x 16 diagonal tiles are inverted all at once.
+// ---------------------------------------------------------------------------------------
+
+// x = row r of the inverse of a 16 x 16 lower-triangular tile (a[c] = row r of the tile, dr its
+// diagonal entry), columns shared out over the lane rows as in diag_factor_invert.  With
+// m_rk = l_rk / l_kk the unit-triangular factor M = L diag(l)^-1 is inverted by
+//   y_r. -= m_rk y_k.  (r > k),   k = 0, 1, ...   and   L^-1 = diag(l)^-1 M^-1.
+template <typename T>
+__device__ __forceinline__ void diag_invert(const T (&a)[LT], T dr, T (&x)[4], int r, int g)
+{
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+        x[j] = (4 * j + g == r) ? T(1) : T(0);
+    T rinv = rcp_newton(dr);
+    settle(rinv);
+    static_for<0, LT - 1>([&](auto kc) {
+        constexpr int k = decltype(kc)::value;
+        const T am = (r > k) ? a[k] : T(0);
+        const T t = mul_row<k>(rinv, am);
+        static_for<0, k / 4 + 1>([&](auto jc) {
+            constexpr int j = decltype(jc)::value;
+            fnmac_row_self<k>(x[j], t);
+        });
+    });
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+        x[j] *= rinv;
+}
+
+template <typename T>
+__global__ __launch_bounds__(LEAF16_THREADS) void k_tri_inv_leaf16(View<const T> Lam, View<T> Inv, int64_t batch, int n,
+                                                                   int nblk)
+{
+    using C = Leaf16<T>;
+    extern __shared__ __align__(16) unsigned char leaf16_lds[];
+    T *lds = reinterpret_cast<T *>(leaf16_lds);
+    const LeafLds<T> m{lds + C::OFF_D, lds + C::OFF_XD, lds + C::OFF_A, lds + C::OFF_X};
+    constexpr int W = LEAF16_WAVES;
+    constexpr int PS = C::PS;
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int64_t b = blockIdx.x / nblk;
+    const int64_t o0 = (int64_t)(blockIdx.x % nblk) * (LT * LK);
+    const int nb = (int)((n - o0) < LT * LK ? (n - o0) : LT * LK);
+    const int K = (nb + LT - 1) / LT;
+
+    leaf_load_lower<T>(m, Lam.p + b * Lam.bs + o0 * (Lam.rs + Lam.cs), Lam.rs, Lam.cs, nb, wave, lane);
+    __syncthreads();
+
+    if (wave < K) {  // all diagonal tiles at once
+        const int r = lane & 15, g = lane >> 4;
+        const T *dk = m.sD + wave * C::DT + r * PS;
+        T *xk = m.sXD + wave * C::DT + r * PS;
+        T a[LT], x[4];
+#pragma unroll
+        for (int c = 0; c < LT; ++c)
+            a[c] = dk[c];
+        diag_invert<T>(a, dk[r], x, r, g);
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+            xk[4 * j + g] = (4 * j + g <= r) ? x[j] : T(0);
+    }
+    __syncthreads();
+
+    for (int k = 0; k < K; ++k) {
+        if (k > 0) {  // X_kj <- Li_kk X_kj, j < k
+            for (int j = wave; j < k; j += W)
+                leaf_xrow<T>(m, k, j, lane);
+            __syncthreads();
+        }
+        const int rows = K - 1 - k;
+        if (rows > 0) {  // X_ij -= L_ik X_kj, i > k, j <= k
+            int xi = 0, xj = wave;
+            for (int it = wave; it < rows * (k + 1); it += W) {
+                while (xj > k) {
+                    xj -= k + 1;
+                    ++xi;
+                }
+                leaf_update_x<T>(m, k + 1 + xi, xj, k, lane);
+                xj += W;
+            }
+            __syncthreads();
+        }
+    }
+    leaf_store_lower<T>(m, true, Inv.p + b * Inv.bs + o0 * (Inv.rs + Inv.cs), Inv.rs, Inv.cs, nb, false, wave, lane);
 }
 
 template <typename T>
@@ -542,5 +645,30 @@ template la_status launch_potrf_leaf16<float>(View<const float>, View<float>, Vi
                                               bool, hipStream_t);
 template la_status launch_potrf_leaf16<double>(View<const double>, View<double>, View<double>, int32_t *, int, int64_t,
                                                int, bool, hipStream_t);
+
+template <typename T>
+la_status launch_tri_inverse128(View<const T> Lam, View<T> Inv, int64_t batch, int n, hipStream_t st)
+{
+    if (batch <= 0 || n <= 0)
+        return LA_OK;
+    const int nblk = (n + LT * LK - 1) / (LT * LK);
+    if (batch * nblk > 0x7fffffffll)
+        return LA_ERR_UNSUPPORTED;
+    constexpr size_t lds_bytes = (size_t)Leaf16<T>::TOTAL * sizeof(T);
+    static bool configured[64] = {};
+    int dev = 0;
+    LA_HIP(hipGetDevice(&dev));
+    if (dev >= 0 && dev < 64 && !configured[dev]) {
+        LA_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&k_tri_inv_leaf16<T>),
+                                   hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes));
+        configured[dev] = true;
+    }
+    hipLaunchKernelGGL((k_tri_inv_leaf16<T>), dim3((unsigned)(batch * nblk)), dim3(LEAF16_THREADS), lds_bytes, st, Lam,
+                       Inv, batch, n, nblk);
+    return launch_check("tri_inverse128");
+}
+
+template la_status launch_tri_inverse128<float>(View<const float>, View<float>, int64_t, int, hipStream_t);
+template la_status launch_tri_inverse128<double>(View<const double>, View<double>, int64_t, int, hipStream_t);
 
 }  // namespace la
