@@ -248,17 +248,11 @@ template <typename T>
 la_status launch_potrf_tiny(View<const T> A, View<T> L, int32_t *info, int info_off, int64_t batch, int nb,
                             hipStream_t st);
 
-// potrf of blocks of edge nb <= 128 together with the inverse of the factor (written to Inv,
-// lower triangle; zeros above the diagonal inside the 64 x 64 diagonal sub-blocks); one
-// workgroup per block.  L's block (0,1) of a 128-block is NOT written (the caller zeroed it).
-template <typename T>
-la_status launch_potrf_leaf(View<const T> A, View<T> L, View<T> Inv, int32_t *info, int info_off, int64_t batch, int nb,
-                            hipStream_t st);
-
-// Same contract as launch_potrf_leaf with 16 x 16 tiles in LDS: the factor's lower triangle
-// (zeros above the diagonal inside the 16 x 16 diagonal tiles; nothing else above it is
-// written unless zero_upper, which zeroes all of L above the diagonal) and the lower triangle of
-// its inverse.  A may alias L.
+// potrf of blocks of edge nb <= 128 together with the inverse of the factor, one workgroup per
+// block: writes the factor's lower triangle (zeros above the diagonal inside the 16 x 16
+// diagonal tiles; nothing else above it is written unless zero_upper, which zeroes all of L
+// above the diagonal) and the lower triangle of its inverse.  A may alias L.
+// info (may be null): set to info_off + failing column (1-based) where it is still 0.
 template <typename T>
 la_status launch_potrf_leaf16(View<const T> A, View<T> L, View<T> Inv, int32_t *info, int info_off, int64_t batch,
                               int nb, bool zero_upper, hipStream_t st);
@@ -268,21 +262,16 @@ la_status launch_potrf_leaf16(View<const T> A, View<T> L, View<T> Inv, int32_t *
 template <typename T>
 la_status launch_tri_inverse128(View<const T> Lam, View<T> Inv, int64_t batch, int n, hipStream_t st);
 
+// X <- alpha * Lam^-1 Xin (fwd) or alpha * Lam^-T Xin (!fwd) for n <= 128 and m <= 48 vectors
+// X(e, v), one workgroup per batch item.  X may alias Xin.
+template <typename T>
+la_status launch_trsm_leaf16(View<const T> Lam, View<const T> Xin, View<T> X, int64_t batch, int n, int m, T alpha,
+                             bool fwd, hipStream_t st);
+
 // Register-resident potrf backward for n <= 32: Abar = sym(L^-T Phi(L^T Lbar) L^-1).
 template <typename T>
 la_status launch_backward_tiny(View<const T> L, View<const T> G, View<T> Abar, int64_t batch, int n,
                                hipStream_t st);
-
-// X <- alpha * Lam^-1 Xin (fwd) or alpha * Lam^-T Xin (!fwd) for n <= 128 and m vectors X(e, v);
-// meant for a handful of right-hand sides (one wavefront each).  X may alias Xin.
-template <typename T>
-la_status launch_trsm_small(View<const T> Lam, View<const T> Xin, View<T> X, int64_t batch, int n, int m, T alpha,
-                            bool fwd, hipStream_t st);
-
-// Inverses of the 64 x 64 diagonal blocks of Lam (n x n lower triangular) written onto the
-// diagonal blocks of Inv (n x n, entries off those blocks are left alone).
-template <typename T>
-la_status launch_tile_inverse(View<const T> Lam, View<T> Inv, int64_t batch, int n, hipStream_t st);
 
 // C(i,j) = beta*C(i,j) + alpha * sum_k A(i,k) B(k,j), i < M, j < N, k < K, per batch item.
 struct GemmOpts {

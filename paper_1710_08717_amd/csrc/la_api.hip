@@ -323,7 +323,7 @@ static la_status potrf_t(int lower, int64_t batch, int n, const void *A, void *L
 // trsm / trmm (section 4.2).  vectors: columns of A/B (left) or rows (right); X(e, v) = element e
 // of vector v, so that every case is "apply Lam, Lam^T or one of their inverses to vectors".
 //   trmm: one GEMM with the triangular operand masked.
-//   trsm, n <= 128 and at most 16 vectors: one substitution kernel.
+//   trsm, n <= 128 and at most 48 vectors: one block-substitution kernel.
 //   trsm, n <= 64: product with the inverse of the single diagonal block.
 //   trsm, n <= 1024: explicit inverse of Lam (see inverse_build), then one masked GEMM.
 //   trsm, larger n: inverses of the 512 x 512 diagonal blocks, then block substitution with two
@@ -344,8 +344,8 @@ static la_status tri_apply_t(bool solve, int lower, int trans, int rightside, do
     o.triA = fwd ? 1 : 2;  // Lam keeps e >= k, Lam^T keeps e <= k; the same holds for their inverses
     o.reverse = fwd ? 1 : 0;  // heavy tile rows first: the last ones for a lower operand
 
-    if (solve && n <= 128 && m <= 16)  // few right-hand sides: one wavefront per vector, no scratch
-        return launch_trsm_small<T>(Lam, Xin, X, batch, n, m, (T)alpha, fwd, st);
+    if (solve && n <= 128 && m <= 48)  // small: one workgroup per item does the whole substitution, no scratch
+        return launch_trsm_leaf16<T>(Lam, Xin, X, batch, n, m, (T)alpha, fwd, st);
 
     if (solve && n <= NB) {
         if (!inplace || alpha != 1.0)

@@ -1,315 +1,832 @@
 // Diagonal-block leaf of the blocked potrf (section 4.2 of arXiv 1710.08717: A = L L^T):
-// factors one block of edge nb <= 64 per workgroup AND inverts the factor in the same pass,
-// because every panel solve against this block later multiplies by that inverse.
+// one workgroup factors a block of edge nb <= 128 AND inverts the factor, because every panel
+// solve against this block later multiplies by that inverse.
 //
-// 512 threads; thread (r, g) keeps the CW = 8 columns CW*g .. CW*g+CW-1 of row r of the block,
-// and of the inverse under construction, in registers (two wavefronts per SIMD: the 64 pivots
-// are strictly sequential, so the time of a step is what counts, and that is the instructions
-// a SIMD has to issue per step plus one barrier).  Both the right-looking factorisation and the
-// right-looking triangular inversion need, at step k, one column (of A) and one row (of X)
-// broadcast to everybody: the owners drop them RAW into LDS, one barrier, and every thread
-// applies the pivot scaling itself:
-//     a_rc -= a_rk a_ck / a_kk        (rank-1 update of the trailing block)
-//     x_rc -= a_rk x_kc / a_kk        (row k of L^-1 times column k of L)
-// so a step costs one barrier.  Double-buffered broadcast slots make that single barrier enough.
+// The block is cut into 16 x 16 tiles that live in LDS for the whole kernel.  Step k of the
+// right-looking sweep over the K = ceil(nb / 16) tile columns:
+//   (a) one wavefront factors the diagonal tile A_kk and inverts the factor in registers
+//       (lane = row, registers = columns, column broadcasts are DPP operands of the
+//       multiply-adds): L_kk, Li_kk;
+//   (b) panel      L_ik = A_ik Li_kk^T  (i > k)   and   X_kj <- Li_kk X_kj  (j < k), which
+//       completes row k of the inverse X = L^-1;
+//   (c) trailing   A_ij -= L_ik L_jk^T  (k < j <= i)   and   X_ij -= L_ik X_kj  (i > k, j <= k).
+// (b) and (c) are 16 x 16 x 16 products on the matrix cores, one tile per wavefront at a
+// time.  The 16 * K pivots are strictly sequential, so what counts is the chain
+//   (a) -> panel tile (k+1, k) -> update of tile (k+1, k+1) -> (a) of the next step:
+// wavefront 0 walks exactly that chain while the other seven do the rest of (b) and (c) of
+// step k behind it (two workgroup barriers per step).
 #include "common.hpp"
+
+#ifndef LEAF16_STAMP
+#define LEAF16_STAMP(i)
+#endif
 
 namespace la {
 
-constexpr int LEAF_CW = 8;                    // columns per thread
-constexpr int LEAF_GR = NB / LEAF_CW;         // column groups (threads per row)
-constexpr int LEAF_THREADS = NB * LEAF_GR;    // 512
-constexpr int LEAF_TPW = 16 / (LEAF_THREADS / 64);  // 16 x 16 output tiles per wavefront in the block products
+constexpr int LT = 16;              // tile edge
+constexpr int LK = 8;               // tiles per block edge (128 / 16)
+constexpr int LEAF16_THREADS = 1024;
+constexpr int LEAF16_WAVES = LEAF16_THREADS / 64;
 
-// The 64 pivot steps on the calling workgroup's registers: a[] (row r, columns CW*g ..) holds the
-// lower triangle of the block on entry and the factor on exit, x[] the identity on entry and
-// the inverse of the factor on exit.  fail becomes fail_base + (failing column + 1) at the first
-// pivot that is not > 0 (kept in a register of every thread: no shared-memory traffic).
 template <typename T>
-__device__ __forceinline__ void leaf_factor(T (&a)[LEAF_CW], T (&x)[LEAF_CW], T (*colbuf)[NB], T (*rowbuf)[NB],
-                                            T (*piv)[2], int &fail, int fail_base)
+struct Leaf16 {
+    // row stride of the diagonal tiles (padded so that "lane = row" accesses spread over the
+    // banks and stay 16-byte aligned)
+    static constexpr int PS = LT + 16 / (int)sizeof(T);
+    static constexpr int DT = LT * PS;            // elements of a padded diagonal tile
+    static constexpr int OT = LT * LT;            // elements of an off-diagonal tile
+    static constexpr int NOFF = LK * (LK - 1) / 2;
+    // LDS map (elements): diagonal tiles of A/L, diagonal tiles of X, off-diagonal of A/L, of X
+    static constexpr int OFF_D = 0;
+    static constexpr int OFF_XD = OFF_D + LK * DT;
+    static constexpr int OFF_A = OFF_XD + LK * DT;
+    static constexpr int OFF_X = OFF_A + NOFF * OT;
+    static constexpr int TOTAL = OFF_X + NOFF * OT;
+};
+
+__device__ __forceinline__ int tri_off(int i, int j) { return i * (i - 1) / 2 + j; }  // i > j
+
+// acc -= (value of src in lane K of the 16-lane row) * other, one instruction.  The hardware
+// needs two wait states between a VALU write of src and this read of it; callers keep that.
+template <int K>
+__device__ __forceinline__ void fnmac_row(float &acc, float src, float other)
 {
-    constexpr int CW = LEAF_CW, GR = LEAF_GR;
+    asm volatile("v_fmac_f32_dpp %0, -%1, %2 row_newbcast:%3 row_mask:0xf bank_mask:0xf"
+                 : "+v"(acc)
+                 : "v"(src), "v"(other), "n"(K));
+}
+template <int K>
+__device__ __forceinline__ void fnmac_row(double &acc, double src, double other)
+{
+    asm volatile("v_fmac_f64_dpp %0, -%1, %2 row_newbcast:%3 row_mask:0xf bank_mask:0xf"
+                 : "+v"(acc)
+                 : "v"(src), "v"(other), "n"(K));
+}
+// acc -= (value of acc in lane K of the row) * other
+template <int K>
+__device__ __forceinline__ void fnmac_row_self(float &acc, float other)
+{
+    asm volatile("v_fmac_f32_dpp %0, -%0, %1 row_newbcast:%2 row_mask:0xf bank_mask:0xf" : "+v"(acc) : "v"(other), "n"(K));
+}
+template <int K>
+__device__ __forceinline__ void fnmac_row_self(double &acc, double other)
+{
+    asm volatile("v_fmac_f64_dpp %0, -%0, %1 row_newbcast:%2 row_mask:0xf bank_mask:0xf" : "+v"(acc) : "v"(other), "n"(K));
+}
+// (value of src in lane K of the row) * other
+template <int K>
+__device__ __forceinline__ float mul_row(float src, float other)
+{
+    float d = 0.0f;
+    asm volatile("v_fmac_f32_dpp %0, %1, %2 row_newbcast:%3 row_mask:0xf bank_mask:0xf"
+                 : "+v"(d)
+                 : "v"(src), "v"(other), "n"(K));
+    return d;
+}
+template <int K>
+__device__ __forceinline__ double mul_row(double src, double other)
+{
+    double d = 0.0;
+    asm volatile("v_fmac_f64_dpp %0, %1, %2 row_newbcast:%3 row_mask:0xf bank_mask:0xf"
+                 : "+v"(d)
+                 : "v"(src), "v"(other), "n"(K));
+    return d;
+}
+// two wait states, with v routed through the statement so that whatever computes it stays before
+template <typename T>
+__device__ __forceinline__ void settle(T &v)
+{
+    asm volatile("s_nop 1" : "+v"(v));
+}
+
+__device__ __forceinline__ float rcp_newton(float x) { return __builtin_amdgcn_rcpf(x); }
+__device__ __forceinline__ double rcp_newton(double x)
+{
+    double r = __builtin_amdgcn_rcp(x);
+    double e = fma(-x, r, 1.0);
+    r = fma(r, e, r);
+    e = fma(-x, r, 1.0);
+    return fma(r, e, r);
+}
+
+// Factor and invert one 16 x 16 tile held one row per lane.  All four 16-lane rows of the
+// wavefront factor copies of the same tile; the inverse is shared out between them: in lane row
+// g register x[j] is column 4 j + g of the inverse.
+// In: a[c] = A(r, c) for c <= r (what lies above the diagonal is never looked at).
+// Out: a[c] = L(r, c) for c <= r, x[j] = L^-1(r, 4 j + g) (entries above the diagonal hold
+// leftovers, respectively zero) and the return value is the 1-based index of the first pivot that
+// is not > 0, or 0.
+//
+// The pivots run on the unscaled matrix,   a_rc -= a_rk a_ck / a_kk,   x_rc -= a_rk x_kc / a_kk,
+// which needs only a reciprocal on the critical path (started as soon as the next pivot is final);
+// the square roots are taken for all 16 pivots at once afterwards:
+// L = A_raw diag(d)^-1/2,  L^-1 = diag(d)^-1/2 X_raw.
+template <typename T>
+__device__ __forceinline__ int diag_factor_invert(T (&a)[LT], T (&x)[4], int r, int g)
+{
+    T d = T(1);
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+        x[j] = (4 * j + g == r) ? T(1) : T(0);
+    T rinv = rcp_newton(a[0]);  // meaningful in the pivot's lane only
+    static_for<0, LT>([&](auto kc) {
+        constexpr int k = decltype(kc)::value;
+        const T am = (r > k) ? a[k] : T(0);
+        d = (r == k) ? a[k] : d;
+        settle(rinv);
+        const T t = mul_row<k>(rinv, am);  // a_rk / a_kk below the pivot, zero elsewhere
+        if constexpr (k + 1 < LT) {
+            fnmac_row<k + 1>(a[k + 1], a[k], t);
+            rinv = rcp_newton(a[k + 1]);  // overlaps the rest of this pivot's updates
+        }
+        static_for<k + 2, LT>([&](auto cc) {
+            constexpr int c = decltype(cc)::value;
+            fnmac_row<c>(a[c], a[k], t);  // a_rc -= a_ck t_r
+        });
+        static_for<0, k / 4 + 1>([&](auto jc) {
+            constexpr int j = decltype(jc)::value;
+            fnmac_row_self<k>(x[j], t);  // x_rc -= x_kc t_r (a no-op where column c > k)
+        });
+    });
+    const unsigned long long bad = __ballot(!(d > T(0)));
+    T rs = rsqrt_acc(d);
+    settle(rs);
+    static_for<0, LT>([&](auto cc) {
+        constexpr int c = decltype(cc)::value;
+        a[c] = mul_row<c>(rs, a[c]);  // column c times d_c^-1/2
+    });
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+        x[j] *= rs;  // row r times d_r^-1/2
+    const unsigned first = (unsigned)(bad & 0xffffu);
+    return first ? __builtin_ctz(first) + 1 : 0;
+}
+
+// ---------------------------------------------------------------------------------------
+// Tiles in LDS.  Diagonal tiles are stored with padded rows (stride PS) for the row-per-lane
+// accesses of the factorisation.  Off-diagonal tiles are 16 x 16 without padding, with the
+// 16-byte chunks of every row permuted by the row number, so that both access patterns of the
+// matrix-core operands sweep all banks: a lane reading four consecutive elements of "its" row
+// (rows 128 or 64 bytes apart would otherwise all start in the same bank), and 16 lanes reading
+// one row.
+// ---------------------------------------------------------------------------------------
+template <typename T>
+__device__ __forceinline__ int sw(int u, int w)  // element (u, w) of an off-diagonal tile
+{
+    constexpr int EPC = 16 / (int)sizeof(T);  // elements per 16-byte chunk
+    constexpr int CPR = LT / EPC;             // chunks per row
+    const int key = (sizeof(T) == 8 ? u : (u >> 1)) & (CPR - 1);
+    return u * LT + (((w / EPC) ^ key) * EPC) + (w % EPC);
+}
+
+template <typename T>
+struct TileRef {
+    T *p;
+    bool diag;  // padded diagonal tile (row stride PS, no permutation)
+    __device__ __forceinline__ int at(int u, int w) const { return diag ? u * Leaf16<T>::PS + w : sw<T>(u, w); }
+};
+
+// Operand element k of the 16 x 16 x 16 contraction is dealt to lane group q = lane / 16 and
+// register s as k = 4 q + s, the same for both operands, so that an operand stored with k
+// contiguous is read as four consecutive elements (one or two 16-byte chunks) per lane.
+//   op_rows: operand(i, k) = tile(i, k), this lane supplies i = lane % 16
+//   op_nat:  operand(k, j) = tile(k, j), this lane supplies j = lane % 16
+template <typename T>
+__device__ __forceinline__ void op_rows(TileRef<T> t, int lane, T (&v)[4])
+{
+    using V = typename Mfma<T>::vec_t;
+    const int u = lane & 15, q = lane >> 4;
+    if constexpr (sizeof(T) == 8) {
+        const V lo = *reinterpret_cast<const V *>(t.p + t.at(u, 4 * q));
+        const V hi = *reinterpret_cast<const V *>(t.p + t.at(u, 4 * q + 2));
+        v[0] = lo.x;
+        v[1] = lo.y;
+        v[2] = hi.x;
+        v[3] = hi.y;
+    } else {
+        const V w = *reinterpret_cast<const V *>(t.p + t.at(u, 4 * q));
+        v[0] = w.x;
+        v[1] = w.y;
+        v[2] = w.z;
+        v[3] = w.w;
+    }
+}
+template <typename T>
+__device__ __forceinline__ void op_nat(TileRef<T> t, int lane, T (&v)[4])
+{
+#pragma unroll
+    for (int s = 0; s < 4; ++s)
+        v[s] = t.p[t.at(4 * (lane >> 4) + s, lane & 15)];
+}
+template <typename T>
+__device__ __forceinline__ typename Mfma<T>::acc_t acc_load(TileRef<T> t, int lane)
+{
+    typename Mfma<T>::acc_t c;
+#pragma unroll
+    for (int v = 0; v < 4; ++v)
+        c[v] = t.p[t.at(Mfma<T>::row(lane, v), lane & 15)];
+    return c;
+}
+template <typename T>
+__device__ __forceinline__ void acc_store(TileRef<T> t, int lane, typename Mfma<T>::acc_t c)
+{
+#pragma unroll
+    for (int v = 0; v < 4; ++v)
+        t.p[t.at(Mfma<T>::row(lane, v), lane & 15)] = c[v];
+}
+template <typename T>
+__device__ __forceinline__ typename Mfma<T>::acc_t mma4(const T (&a)[4], const T (&b)[4], typename Mfma<T>::acc_t c,
+                                                        bool neg)
+{
+#pragma unroll
+    for (int s = 0; s < 4; ++s)
+        c = Mfma<T>::run(neg ? -a[s] : a[s], b[s], c);
+    return c;
+}
+
+template <typename T>
+struct LeafLds {
+    T *sD, *sXD, *sA, *sX;
+    __device__ __forceinline__ TileRef<T> a(int i, int j) const  // tile (i, j) of A / L, i >= j
+    {
+        return i == j ? TileRef<T>{sD + i * Leaf16<T>::DT, true} : TileRef<T>{sA + tri_off(i, j) * Leaf16<T>::OT, false};
+    }
+    __device__ __forceinline__ TileRef<T> x(int i, int j) const  // tile (i, j) of the inverse, i >= j
+    {
+        return i == j ? TileRef<T>{sXD + i * Leaf16<T>::DT, true} : TileRef<T>{sX + tri_off(i, j) * Leaf16<T>::OT, false};
+    }
+};
+
+// (a): diagonal tile k, by one whole wavefront
+template <typename T>
+__device__ __forceinline__ int leaf_diag(const LeafLds<T> &m, int k, int lane)
+{
+    constexpr int PS = Leaf16<T>::PS;
+    const int r = lane & 15, g = lane >> 4;
+    T a[LT], x[4];
+    T *dk = m.sD + k * Leaf16<T>::DT + r * PS, *xk = m.sXD + k * Leaf16<T>::DT + r * PS;
+    using V = typename Mfma<T>::vec_t;
+    constexpr int VW = Mfma<T>::VW;
+#pragma unroll
+    for (int c = 0; c < LT; c += VW) {
+        const V w = *reinterpret_cast<const V *>(dk + c);
+        a[c] = w.x;
+        a[c + 1] = w.y;
+        if constexpr (VW == 4) {
+            a[c + 2] = w.z;
+            a[c + 3] = w.w;
+        }
+    }
+    const int f = diag_factor_invert<T>(a, x, r, g);
+    if (lane < LT) {
+#pragma unroll
+        for (int c = 0; c < LT; ++c)
+            dk[c] = (c <= r) ? a[c] : T(0);
+    }
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+        xk[4 * j + g] = (4 * j + g <= r) ? x[j] : T(0);
+    return f;
+}
+
+// (b): L_ik = A_ik Li_kk^T
+template <typename T>
+__device__ __forceinline__ void leaf_panel(const LeafLds<T> &m, int i, int k, int lane)
+{
+    T av[4], bv[4];
+    typename Mfma<T>::acc_t acc = {0, 0, 0, 0};
+    op_rows<T>(m.a(i, k), lane, av);
+    op_rows<T>(m.x(k, k), lane, bv);
+    acc = mma4<T>(av, bv, acc, false);
+    acc_store<T>(m.a(i, k), lane, acc);
+}
+// (b): X_kj <- Li_kk X_kj, j < k
+template <typename T>
+__device__ __forceinline__ void leaf_xrow(const LeafLds<T> &m, int k, int j, int lane)
+{
+    T av[4], bv[4];
+    typename Mfma<T>::acc_t acc = {0, 0, 0, 0};
+    op_rows<T>(m.x(k, k), lane, av);
+    op_nat<T>(m.x(k, j), lane, bv);
+    acc = mma4<T>(av, bv, acc, false);
+    acc_store<T>(m.x(k, j), lane, acc);
+}
+// (c): A_ij -= L_ik L_jk^T, k < j <= i
+template <typename T>
+__device__ __forceinline__ void leaf_update_a(const LeafLds<T> &m, int i, int j, int k, int lane)
+{
+    T av[4], bv[4];
+    op_rows<T>(m.a(i, k), lane, av);
+    op_rows<T>(m.a(j, k), lane, bv);
+    typename Mfma<T>::acc_t acc = acc_load<T>(m.a(i, j), lane);
+    acc = mma4<T>(av, bv, acc, true);
+    acc_store<T>(m.a(i, j), lane, acc);
+}
+// (c): X_ij -= L_ik X_kj, i > k, j <= k (tile (i, k) of the inverse starts from zero)
+template <typename T>
+__device__ __forceinline__ void leaf_update_x(const LeafLds<T> &m, int i, int j, int k, int lane)
+{
+    T av[4], bv[4];
+    op_rows<T>(m.a(i, k), lane, av);
+    op_nat<T>(m.x(k, j), lane, bv);
+    typename Mfma<T>::acc_t acc = {0, 0, 0, 0};
+    if (j < k)
+        acc = acc_load<T>(m.x(i, j), lane);
+    acc = mma4<T>(av, bv, acc, true);
+    acc_store<T>(m.x(i, j), lane, acc);
+}
+
+// tile (ti, tj) number t of the lower triangle counted row by row
+__device__ __forceinline__ void tri_decode(int t, int &ti, int &tj)
+{
+    ti = 0;
+    while (t > ti) {
+        t -= ti + 1;
+        ++ti;
+    }
+    tj = t;
+}
+
+// Lower triangle of an nb x nb block at p (element strides rs, cs) into the tiles of A (identity
+// outside nb x nb).  Per tile a lane moves four elements, 16 lanes along the contiguous direction
+// of the operand; all loads of a wavefront are in flight together.
+template <typename T>
+__device__ __forceinline__ void leaf_load_lower(const LeafLds<T> &m, const T *p, int64_t rs, int64_t cs, int nb,
+                                                int wave, int lane)
+{
+    constexpr int W = LEAF16_WAVES;
+    constexpr int TPW = (LK * (LK + 1) / 2 + W - 1) / W;  // lower tiles per wavefront, at most
+    const int K = (nb + LT - 1) / LT;
+    const int ntl = K * (K + 1) / 2;
+    const bool colfast = (cs == 1) || (rs != 1);
+    const int f = lane & 15, s0 = lane >> 4;  // fast and slow coordinate inside the tile (slow: s0 + 4 v)
+    const int64_t fs = colfast ? cs : rs, ss = colfast ? rs : cs;  // their strides
+    const int64_t lane_off = (int64_t)f * fs + (int64_t)s0 * ss;
+    T val[TPW][4];
+#pragma unroll
+    for (int q = 0; q < TPW; ++q) {
+        const int t = wave + q * W;
+        int ti, tj;
+        tri_decode(t < ntl ? t : 0, ti, tj);
+        const T *tp = p + (int64_t)(ti * LT) * rs + (int64_t)(tj * LT) * cs + lane_off;
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+            const int u = colfast ? s0 + 4 * v : f, w = colfast ? f : s0 + 4 * v;
+            const int r = ti * LT + u, c = tj * LT + w;
+            T x = (r == c) ? T(1) : T(0);
+            if (t < ntl && r < nb && c <= r)
+                x = *tp;
+            val[q][v] = x;
+            tp += 4 * ss;
+        }
+    }
+#pragma unroll
+    for (int q = 0; q < TPW; ++q) {
+        const int t = wave + q * W;
+        if (t < ntl) {
+            int ti, tj;
+            tri_decode(t, ti, tj);
+            const TileRef<T> tr = m.a(ti, tj);
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                const int u = colfast ? s0 + 4 * v : f, w = colfast ? f : s0 + 4 * v;
+                tr.p[tr.at(u, w)] = val[q][v];
+            }
+        }
+    }
+}
+
+// The lower tiles of A / L (inverse == false) or of the inverse back to an nb x nb block at p;
+// zero_upper also writes zeros to the tiles above the diagonal.
+template <typename T>
+__device__ __forceinline__ void leaf_store_lower(const LeafLds<T> &m, bool inverse, T *p, int64_t rs, int64_t cs,
+                                                 int nb, bool zero_upper, int wave, int lane)
+{
+    constexpr int W = LEAF16_WAVES;
+    const int K = (nb + LT - 1) / LT;
+    const int ntl = K * (K + 1) / 2;
+    const bool colfast = (cs == 1) || (rs != 1);
+    const int f = lane & 15, s0 = lane >> 4;
+    const int64_t fs = colfast ? cs : rs, ss = colfast ? rs : cs;
+    const int64_t lane_off = (int64_t)f * fs + (int64_t)s0 * ss;
+    for (int t = wave; t < ntl; t += W) {
+        int ti, tj;
+        tri_decode(t, ti, tj);
+        const TileRef<T> tr = inverse ? m.x(ti, tj) : m.a(ti, tj);
+        T *tp = p + (int64_t)(ti * LT) * rs + (int64_t)(tj * LT) * cs + lane_off;
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+            const int u = colfast ? s0 + 4 * v : f, w = colfast ? f : s0 + 4 * v;
+            if (ti * LT + u < nb && tj * LT + w < nb)
+                *tp = tr.p[tr.at(u, w)];
+            tp += 4 * ss;
+        }
+    }
+    if (zero_upper) {
+        for (int t = wave; t < ntl - K; t += W) {
+            int tj, ti;
+            tri_decode(t, tj, ti);  // strictly lower (tj + 1, ti), mirrored
+            tj += 1;
+            T *tp = p + (int64_t)(ti * LT) * rs + (int64_t)(tj * LT) * cs + lane_off;
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                const int u = colfast ? s0 + 4 * v : f, w = colfast ? f : s0 + 4 * v;
+                if (ti * LT + u < nb && tj * LT + w < nb)
+                    *tp = T(0);
+                tp += 4 * ss;
+            }
+        }
+    }
+}
+
+template <typename T>
+__global__ __launch_bounds__(LEAF16_THREADS) void k_potrf_leaf16(View<const T> A, View<T> L, View<T> Inv, int32_t *info,
+                                                                 int info_off, int64_t batch, int nb, int zero_upper)
+{
+    using C = Leaf16<T>;
+    extern __shared__ __align__(16) unsigned char leaf16_lds[];
+    T *lds = reinterpret_cast<T *>(leaf16_lds);
+    const LeafLds<T> m{lds + C::OFF_D, lds + C::OFF_XD, lds + C::OFF_A, lds + C::OFF_X};
+    constexpr int W = LEAF16_WAVES;
+
     const int tid = threadIdx.x;
-    const int r = tid / GR, g = tid % GR;
-    T lf[CW];
-    T myrs = T(1);
-#pragma unroll
-    for (int c = 0; c < CW; ++c)
-        lf[c] = T(0);
-    // Only clean values are ever broadcast: the column slot gets zeros for rows above the pivot,
-    // and rows of the inverse are zero beyond their diagonal by construction.  The updates
-    // below therefore need no masks: what they do to register entries above the diagonal, or to
-    // entries of columns that are already finished (saved in lf[]), is never looked at again.
-#pragma unroll 1
-    for (int kg = 0; kg < GR; ++kg) {
-#pragma unroll
-        for (int kk = 0; kk < CW; ++kk) {
-            const int k = kg * CW + kk;
-            const int slot = k & 1;
-            if (g == kg)
-                colbuf[slot][r] = (r >= k) ? a[kk] : T(0);  // raw column k, rows >= k
-            if (r == k) {
-#pragma unroll
-                for (int c = 0; c < CW; ++c)
-                    rowbuf[slot][g * CW + c] = x[c];  // raw row k of the inverse
-                if (g == kg) {  // the owner of the pivot works out 1 / sqrt(a_kk) for everybody
-                    piv[slot][0] = a[kk];
-                    piv[slot][1] = rsqrt_acc(a[kk]);
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int K = (nb + LT - 1) / LT;  // tile columns in use
+    const int64_t b = blockIdx.x;
+    LEAF16_STAMP(31);
+
+    leaf_load_lower<T>(m, A.p + b * A.bs, A.rs, A.cs, nb, wave, lane);
+    __syncthreads();
+    LEAF16_STAMP(0);
+
+    int fail = 0;
+    if (wave == 0) {
+        const int f = leaf_diag<T>(m, 0, lane);
+        fail = f;
+    }
+    __syncthreads();
+    LEAF16_STAMP(1);
+
+    for (int k = 0; k < K; ++k) {
+        const int rows = K - 1 - k;  // tile rows below the pivot row
+        // ---- (b): wavefront 0 takes the panel tile the next diagonal tile depends on ------------
+        if (wave == 0) {
+            if (rows > 0)
+                leaf_panel<T>(m, k + 1, k, lane);
+        } else {
+            const int np = rows > 0 ? rows - 1 : 0;
+            for (int it = wave - 1; it < np + k; it += W - 1) {
+                if (it < np)
+                    leaf_panel<T>(m, k + 2 + it, k, lane);
+                else
+                    leaf_xrow<T>(m, k, it - np, lane);
+            }
+        }
+        __syncthreads();
+        LEAF16_STAMP(2 + 2 * k);
+        if (rows == 0)
+            break;
+        // ---- (c): wavefront 0 updates the next diagonal tile and factors it -----------------------
+        if (wave == 0) {
+            leaf_update_a<T>(m, k + 1, k + 1, k, lane);
+            const int f = leaf_diag<T>(m, k + 1, lane);
+            if (fail == 0 && f != 0)
+                fail = (k + 1) * LT + f;
+        } else {
+            const int nx = rows * (k + 1);           // tiles of the inverse to update
+            const int na = rows * (rows + 1) / 2 - 1;  // tiles of A, without tile (k+1, k+1)
+            int xi = 0, xj = wave - 1;                // item number it = xi * (k + 1) + xj
+            for (int it = wave - 1; it < nx + na; it += W - 1) {
+                if (it < nx) {
+                    while (xj > k) {
+                        xj -= k + 1;
+                        ++xi;
+                    }
+                    leaf_update_x<T>(m, k + 1 + xi, xj, k, lane);
+                    xj += W - 1;
+                } else {
+                    int ii, jj;
+                    tri_decode(it - nx + 1, ii, jj);
+                    leaf_update_a<T>(m, k + 1 + ii, k + 1 + jj, k, lane);
                 }
             }
+        }
+        __syncthreads();
+        LEAF16_STAMP(3 + 2 * k);
+    }
+
+    // ---- factor and inverse back to memory (lower tiles; zeros above the diagonal inside the
+    //      diagonal tiles) -----------------------------------------------------------------------
+    leaf_store_lower<T>(m, false, L.p + b * L.bs, L.rs, L.cs, nb, zero_upper != 0, wave, lane);
+    leaf_store_lower<T>(m, true, Inv.p + b * Inv.bs, Inv.rs, Inv.cs, nb, false, wave, lane);
+    LEAF16_STAMP(30);
+    if (info != nullptr && tid == 0 && fail != 0 && fail <= nb) {
+        if (info[b] == 0)
+            info[b] = info_off + fail;
+    }
+}
+
+// ---------------------------------------------------------------------------------------
+// Inverse of a GIVEN lower-triangular factor (the potrf backward pass and trsm need L^-1 of their
+// input, section 4.2): the diagonal blocks of edge 128 of Lam (n x n), one workgroup each, written
+// onto the diagonal blocks of Inv.  Same tiles and matrix-core steps as above without the
+// factorisation, so the 16 x 16 diagonal tiles are inverted all at once.
+// ---------------------------------------------------------------------------------------
+
+// x = row r of the inverse of a 16 x 16 lower-triangular tile (a[c] = row r of the tile, dr its
+// diagonal entry), columns shared out over the lane rows as in diag_factor_invert.  With
+// m_rk = l_rk / l_kk the unit-triangular factor M = L diag(l)^-1 is inverted by
+//   y_r. -= m_rk y_k.  (r > k),   k = 0, 1, ...   and   L^-1 = diag(l)^-1 M^-1.
+template <typename T>
+__device__ __forceinline__ void diag_invert(const T (&a)[LT], T dr, T (&x)[4], int r, int g)
+{
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+        x[j] = (4 * j + g == r) ? T(1) : T(0);
+    T rinv = rcp_newton(dr);
+    settle(rinv);
+    static_for<0, LT - 1>([&](auto kc) {
+        constexpr int k = decltype(kc)::value;
+        const T am = (r > k) ? a[k] : T(0);
+        const T t = mul_row<k>(rinv, am);
+        static_for<0, k / 4 + 1>([&](auto jc) {
+            constexpr int j = decltype(jc)::value;
+            fnmac_row_self<k>(x[j], t);
+        });
+    });
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+        x[j] *= rinv;
+}
+
+template <typename T>
+__global__ __launch_bounds__(LEAF16_THREADS) void k_tri_inv_leaf16(View<const T> Lam, View<T> Inv, int64_t batch, int n,
+                                                                   int nblk)
+{
+    using C = Leaf16<T>;
+    extern __shared__ __align__(16) unsigned char leaf16_lds[];
+    T *lds = reinterpret_cast<T *>(leaf16_lds);
+    const LeafLds<T> m{lds + C::OFF_D, lds + C::OFF_XD, lds + C::OFF_A, lds + C::OFF_X};
+    constexpr int W = LEAF16_WAVES;
+    constexpr int PS = C::PS;
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int64_t b = blockIdx.x / nblk;
+    const int64_t o0 = (int64_t)(blockIdx.x % nblk) * (LT * LK);
+    const int nb = (int)((n - o0) < LT * LK ? (n - o0) : LT * LK);
+    const int K = (nb + LT - 1) / LT;
+
+    leaf_load_lower<T>(m, Lam.p + b * Lam.bs + o0 * (Lam.rs + Lam.cs), Lam.rs, Lam.cs, nb, wave, lane);
+    __syncthreads();
+
+    if (wave < K) {  // all diagonal tiles at once
+        const int r = lane & 15, g = lane >> 4;
+        const T *dk = m.sD + wave * C::DT + r * PS;
+        T *xk = m.sXD + wave * C::DT + r * PS;
+        T a[LT], x[4];
+#pragma unroll
+        for (int c = 0; c < LT; ++c)
+            a[c] = dk[c];
+        diag_invert<T>(a, dk[r], x, r, g);
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+            xk[4 * j + g] = (4 * j + g <= r) ? x[j] : T(0);
+    }
+    __syncthreads();
+
+    for (int k = 0; k < K; ++k) {
+        if (k > 0) {  // X_kj <- Li_kk X_kj, j < k
+            for (int j = wave; j < k; j += W)
+                leaf_xrow<T>(m, k, j, lane);
             __syncthreads();
-            const T akk = piv[slot][0];
-            const T rs = piv[slot][1];
-            const T ark = colbuf[slot][r];
-            fail = (!(akk > T(0)) && fail == 0) ? fail_base + k + 1 : fail;  // every thread keeps its own copy
-            const T t = (r > k) ? ark * (rs * rs) : T(0);  // a_rk / a_kk
-            T cb[CW], rb[CW];
-#pragma unroll
-            for (int c = 0; c < CW; ++c) {
-                cb[c] = colbuf[slot][g * CW + c];
-                rb[c] = rowbuf[slot][g * CW + c];
+        }
+        const int rows = K - 1 - k;
+        if (rows > 0) {  // X_ij -= L_ik X_kj, i > k, j <= k
+            int xi = 0, xj = wave;
+            for (int it = wave; it < rows * (k + 1); it += W) {
+                while (xj > k) {
+                    xj -= k + 1;
+                    ++xi;
+                }
+                leaf_update_x<T>(m, k + 1 + xi, xj, k, lane);
+                xj += W;
             }
-#pragma unroll
-            for (int c = 0; c < CW; ++c) {
-                a[c] = fma(-t, cb[c], a[c]);  // a_rc -= a_rk a_ck / a_kk
-                x[c] = fma(-t, rb[c], x[c]);  // x_rc -= a_rk x_kc / a_kk
-            }
-            // keep the compiler from postponing these updates over several steps (which would hold
-            // every step's broadcast values in registers at once)
-#pragma unroll
-            for (int c = 0; c < CW; ++c) {
-                asm volatile("" : "+v"(a[c]));
-                asm volatile("" : "+v"(x[c]));
-            }
-            lf[kk] = (g == kg) ? ark * rs : lf[kk];  // column k of L: a_rk / sqrt(a_kk), zero above the pivot
-            myrs = (r == k) ? rs : myrs;             // row r of L^-1 is its raw row times 1 / l_rr
+            __syncthreads();
         }
     }
-#pragma unroll
-    for (int c = 0; c < CW; ++c) {
-        a[c] = lf[c];
-        x[c] *= myrs;
-    }
-    __syncthreads();  // the broadcast slots may be reused by the caller
-}
-
-template <typename T>
-__global__ __launch_bounds__(LEAF_THREADS) void k_potrf_leaf(View<const T> A, View<T> L, View<T> Inv, int32_t *info,
-                                                             int info_off, int64_t batch, int nb)
-{
-    __shared__ T colbuf[2][NB];
-    __shared__ T rowbuf[2][NB];
-    __shared__ __align__(16) T piv[2][2];
-    constexpr int CW = LEAF_CW, GR = LEAF_GR;
-    const int tid = threadIdx.x;
-    const int r = tid / GR, g = tid % GR;
-    const int64_t b = blockIdx.x;
-    const T *ap = A.p + b * A.bs;
-    int fail = 0;
-
-    // my CW entries of row r (lower triangle only; identity outside nb x nb)
-    T a[CW], x[CW];
-#pragma unroll
-    for (int c = 0; c < CW; ++c) {
-        const int col = g * CW + c;
-        T v = (col == r) ? T(1) : T(0);
-        if (r < nb && col <= r)
-            v = ap[(int64_t)r * A.rs + (int64_t)col * A.cs];
-        a[c] = v;
-        x[c] = (col == r) ? T(1) : T(0);
-    }
-    leaf_factor<T>(a, x, colbuf, rowbuf, piv, fail, 0);
-
-    T *lp = L.p + b * L.bs;
-    T *ip = Inv.p + b * Inv.bs;
-#pragma unroll
-    for (int c = 0; c < CW; ++c) {
-        const int col = g * CW + c;
-        if (r < nb && col < nb) {
-            lp[(int64_t)r * L.rs + (int64_t)col * L.cs] = (col <= r) ? a[c] : T(0);
-            ip[(int64_t)r * Inv.rs + (int64_t)col * Inv.cs] = (col <= r) ? x[c] : T(0);
-        }
-    }
-    if (info != nullptr && tid == 0 && fail != 0 && fail <= nb) {
-        if (info[b] == 0)
-            info[b] = info_off + fail;
-    }
+    leaf_store_lower<T>(m, true, Inv.p + b * Inv.bs + o0 * (Inv.rs + Inv.cs), Inv.rs, Inv.cs, nb, false, wave, lane);
 }
 
 // ---------------------------------------------------------------------------------------
-// Blocks of edge 64 < nb <= 128 in one launch: [A00 0; A10 A11] with 64 x 64 sub-blocks,
-//   L00, Li00 = factor(A00);  L10 = A10 Li00^T;  L11, Li11 = factor(A11 - L10 L10^T);
-//   Li10 = -Li11 (L10 Li00)
-// The four 64 x 64 x 64 products run on the matrix cores, a row of four 16 x 16 output tiles
-// per wavefront, operands in LDS.
+// trsm (section 4.2) with a small triangular matrix and a few right-hand sides: n <= 128 and
+// m <= 48 vectors X(e, v), one workgroup per batch item.  Block substitution over the 16-row
+// tiles with the inverted diagonal tiles:
+//   fwd:  X_k = Li_kk B_k,    B_i -= L_ik X_k   (i > k),   k = 0, 1, ...
+//   !fwd: X_k = Li_kk^T B_k,  B_i -= L_ki^T X_k (i < k),   k = K-1, K-2, ...
+// Each 16-column tile of right-hand sides has its own chain wavefront, which also applies the
+// update the next step depends on; the remaining updates belong to fixed other wavefronts (one
+// owner per tile, so successive updates of a tile are ordered).  One barrier per step.
 // ---------------------------------------------------------------------------------------
-constexpr int LEAF_LD = NB + 1;
-
-// Tiles (ti, tj0 .. tj0 + TPW - 1), 16 x 16 each, of  sum_k A(i,k) B(k,j)  with
-// A(i,k) = sA[i*a_si + k*a_sk] and B(k,j) = sB[k*b_sk + j*b_sj].
-template <typename T>
-__device__ __forceinline__ void leaf_product(typename Mfma<T>::acc_t (&acc)[LEAF_TPW], const T *sA, int a_si, int a_sk,
-                                             const T *sB, int b_sk, int b_sj, int ti, int tj0, int lane)
-{
-    using MF = Mfma<T>;
-    const int l16 = lane & 15, lk = lane >> 4;
-#pragma unroll
-    for (int q = 0; q < LEAF_TPW; ++q)
-        acc[q] = typename MF::acc_t{0, 0, 0, 0};
-#pragma unroll 4
-    for (int kk = 0; kk < NB; kk += 4) {
-        const T av = sA[(ti * 16 + l16) * a_si + (kk + lk) * a_sk];
-#pragma unroll
-        for (int q = 0; q < LEAF_TPW; ++q) {
-            const T bv = sB[(kk + lk) * b_sk + ((tj0 + q) * 16 + l16) * b_sj];
-            acc[q] = MF::run(av, bv, acc[q]);
-        }
-    }
-}
+constexpr int TRSM16_MAX_CT = 3;  // column tiles of right-hand sides (they live in the inverse's tile area)
 
 template <typename T>
-__global__ __launch_bounds__(LEAF_THREADS) void k_potrf_leaf128(View<const T> A, View<T> L, View<T> Inv, int32_t *info,
-                                                                int info_off, int64_t batch, int nb)
+__global__ __launch_bounds__(LEAF16_THREADS) void k_trsm_leaf16(View<const T> Lam, View<const T> Xin, View<T> X,
+                                                                int64_t batch, int n, int m, T alpha, int fwd)
 {
-    using MF = Mfma<T>;
-    __shared__ T sLi0[NB * LEAF_LD];
-    __shared__ T sLi1[NB * LEAF_LD];
-    __shared__ T sB1[NB * LEAF_LD];  // A10, then L10
-    __shared__ T sC[NB * LEAF_LD];   // A11 - L10 L10^T, then L10 Li00
-    __shared__ T colbuf[2][NB];
-    __shared__ T rowbuf[2][NB];
-    __shared__ __align__(16) T piv[2][2];
-    constexpr int CW = LEAF_CW, GR = LEAF_GR, LD = LEAF_LD;
+    using C = Leaf16<T>;
+    extern __shared__ __align__(16) unsigned char leaf16_lds[];
+    T *lds = reinterpret_cast<T *>(leaf16_lds);
+    const LeafLds<T> mm{lds + C::OFF_D, lds + C::OFF_XD, lds + C::OFF_A, lds + C::OFF_X};
+    constexpr int W = LEAF16_WAVES;
+    constexpr int PS = C::PS, OT = C::OT;
     const int tid = threadIdx.x;
-    const int r = tid / GR, g = tid % GR;
-    constexpr int TPW = LEAF_TPW;
-    const int lane = tid & 63, w = tid >> 6;
-    const int ti = w / (4 / TPW), tj0 = (w % (4 / TPW)) * TPW;  // this wavefront's output tiles
-    const int l16 = lane & 15;
-    const int n2 = nb - NB;  // rows of the second block (1 .. 64)
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int64_t b = blockIdx.x;
-    const T *ap = A.p + b * A.bs;
-    T *lp = L.p + b * L.bs;
-    T *ip = Inv.p + b * Inv.bs;
-    int fail = 0;
+    const int K = (n + LT - 1) / LT, MT = (m + LT - 1) / LT;
+    auto btile = [&](int k, int ct) { return TileRef<T>{mm.sX + (k * MT + ct) * OT, false}; };
 
-    // ---- block (0,0) --------------------------------------------------------------------
-    T a[CW], x[CW];
+    leaf_load_lower<T>(mm, Lam.p + b * Lam.bs, Lam.rs, Lam.cs, n, wave, lane);
+    {  // right-hand sides, scaled by alpha, zero outside n x m
+        const T *xp = Xin.p + b * Xin.bs;
+        const bool colfast = (Xin.cs == 1) || (Xin.rs != 1);
+        const int f = lane & 15, s0 = lane >> 4;
+        for (int t = wave; t < K * MT; t += W) {
+            const int k = t / MT, ct = t % MT;
+            const TileRef<T> tr = btile(k, ct);
 #pragma unroll
-    for (int c = 0; c < CW; ++c) {
-        const int col = g * CW + c;
-        a[c] = (col <= r) ? ap[(int64_t)r * A.rs + (int64_t)col * A.cs] : T(0);
-        x[c] = (col == r) ? T(1) : T(0);
-        // A10 for the panel product (rows past the end of the block read as zero)
-        sB1[r * LD + col] = (r < n2) ? ap[(int64_t)(NB + r) * A.rs + (int64_t)col * A.cs] : T(0);
-    }
-    leaf_factor<T>(a, x, colbuf, rowbuf, piv, fail, 0);
-#pragma unroll
-    for (int c = 0; c < CW; ++c) {
-        const int col = g * CW + c;
-        const T lv = (col <= r) ? a[c] : T(0), iv = (col <= r) ? x[c] : T(0);
-        lp[(int64_t)r * L.rs + (int64_t)col * L.cs] = lv;
-        ip[(int64_t)r * Inv.rs + (int64_t)col * Inv.cs] = iv;
-        sLi0[r * LD + col] = iv;
+            for (int v = 0; v < 4; ++v) {
+                const int u = colfast ? s0 + 4 * v : f, w = colfast ? f : s0 + 4 * v;
+                const int e = k * LT + u, vec = ct * LT + w;
+                T val = T(0);
+                if (e < n && vec < m)
+                    val = alpha * xp[(int64_t)e * Xin.rs + (int64_t)vec * Xin.cs];
+                tr.p[tr.at(u, w)] = val;
+            }
+        }
     }
     __syncthreads();
 
-    // ---- panel: L10 = A10 Li00^T ------------------------------------------------------------
-    typename MF::acc_t acc[TPW];
-    leaf_product<T>(acc, sB1, LD, 1, sLi0, 1, LD, ti, tj0, lane);
-    __syncthreads();  // everybody is done reading A10
+    if (wave < K) {  // all diagonal tiles at once
+        const int r = lane & 15, g = lane >> 4;
+        const T *dk = mm.sD + wave * C::DT + r * PS;
+        T *xk = mm.sXD + wave * C::DT + r * PS;
+        T a[LT], x[4];
 #pragma unroll
-    for (int q = 0; q < TPW; ++q)
+        for (int c = 0; c < LT; ++c)
+            a[c] = dk[c];
+        diag_invert<T>(a, dk[r], x, r, g);
 #pragma unroll
-        for (int v = 0; v < 4; ++v) {
-            const int tj = tj0 + q;
-            const int i = ti * 16 + MF::row(lane, v), j = tj * 16 + l16;
-            sB1[i * LD + j] = acc[q][v];
-            if (i < n2)
-                lp[(int64_t)(NB + i) * L.rs + (int64_t)j * L.cs] = acc[q][v];
-        }
-    __syncthreads();
-
-    // ---- trailing block: A11 - L10 L10^T (lower triangle, identity padding) -------------------
-    leaf_product<T>(acc, sB1, LD, 1, sB1, 1, LD, ti, tj0, lane);
-#pragma unroll
-    for (int q = 0; q < TPW; ++q)
-#pragma unroll
-        for (int v = 0; v < 4; ++v) {
-            const int tj = tj0 + q;
-            const int i = ti * 16 + MF::row(lane, v), j = tj * 16 + l16;
-            T val = (i == j) ? T(1) : T(0);
-            if (i < n2 && j <= i)
-                val = ap[(int64_t)(NB + i) * A.rs + (int64_t)(NB + j) * A.cs] - acc[q][v];
-            sC[i * LD + j] = val;
-        }
-    __syncthreads();
-
-    // ---- block (1,1) --------------------------------------------------------------------
-#pragma unroll
-    for (int c = 0; c < CW; ++c) {
-        const int col = g * CW + c;
-        a[c] = (col <= r) ? sC[r * LD + col] : T(0);
-        x[c] = (col == r) ? T(1) : T(0);
-    }
-    leaf_factor<T>(a, x, colbuf, rowbuf, piv, fail, NB);
-#pragma unroll
-    for (int c = 0; c < CW; ++c) {
-        const int col = g * CW + c;
-        const T lv = (col <= r) ? a[c] : T(0), iv = (col <= r) ? x[c] : T(0);
-        if (r < n2 && col < n2) {
-            lp[(int64_t)(NB + r) * L.rs + (int64_t)(NB + col) * L.cs] = lv;
-            ip[(int64_t)(NB + r) * Inv.rs + (int64_t)(NB + col) * Inv.cs] = iv;
-        }
-        sLi1[r * LD + col] = iv;
+        for (int j = 0; j < 4; ++j)
+            xk[4 * j + g] = (4 * j + g <= r) ? x[j] : T(0);
     }
     __syncthreads();
 
-    // ---- inverse, block (1,0): -Li11 (L10 Li00) ------------------------------------------------
-    leaf_product<T>(acc, sB1, LD, 1, sLi0, LD, 1, ti, tj0, lane);
-#pragma unroll
-    for (int q = 0; q < TPW; ++q)
-#pragma unroll
-        for (int v = 0; v < 4; ++v)
-            sC[(ti * 16 + MF::row(lane, v)) * LD + (tj0 + q) * 16 + l16] = acc[q][v];
-    __syncthreads();
-    leaf_product<T>(acc, sLi1, LD, 1, sC, LD, 1, ti, tj0, lane);
-#pragma unroll
-    for (int q = 0; q < TPW; ++q)
-#pragma unroll
-        for (int v = 0; v < 4; ++v) {
-            const int tj = tj0 + q;
-            const int i = ti * 16 + MF::row(lane, v), j = tj * 16 + l16;
-            if (i < n2)
-                ip[(int64_t)(NB + i) * Inv.rs + (int64_t)j * Inv.cs] = -acc[q][v];
+    const int NW = W - MT;  // wavefronts that own the far updates
+    for (int s = 0; s < K; ++s) {
+        const int k = fwd ? s : K - 1 - s;
+        if (wave < MT) {  // X_k = Li_kk B_k  (Li_kk^T when solving with the transpose)
+            T av[4], bv[4];
+            typename Mfma<T>::acc_t acc = {0, 0, 0, 0};
+            if (fwd)
+                op_rows<T>(mm.x(k, k), lane, av);
+            else
+                op_nat<T>(mm.x(k, k), lane, av);
+            op_nat<T>(btile(k, wave), lane, bv);
+            acc = mma4<T>(av, bv, acc, false);
+            acc_store<T>(btile(k, wave), lane, acc);
         }
-    if (info != nullptr && tid == 0 && fail != 0 && fail <= nb) {
-        if (info[b] == 0)
-            info[b] = info_off + fail;
+        __syncthreads();
+        if (s + 1 == K)
+            break;
+        if (wave < MT) {  // the tile the next step starts from
+            const int i = fwd ? k + 1 : k - 1;
+            T av[4], bv[4];
+            if (fwd)
+                op_rows<T>(mm.a(i, k), lane, av);
+            else
+                op_nat<T>(mm.a(k, i), lane, av);
+            op_nat<T>(btile(k, wave), lane, bv);
+            typename Mfma<T>::acc_t acc = acc_load<T>(btile(i, wave), lane);
+            acc = mma4<T>(av, bv, acc, true);
+            acc_store<T>(btile(i, wave), lane, acc);
+        } else {
+            for (int d = 2; s + d < K; ++d) {
+                const int i = fwd ? k + d : k - d;
+                for (int ct = 0; ct < MT; ++ct) {
+                    if ((i * MT + ct) % NW != wave - MT)
+                        continue;
+                    T av[4], bv[4];
+                    if (fwd)
+                        op_rows<T>(mm.a(i, k), lane, av);
+                    else
+                        op_nat<T>(mm.a(k, i), lane, av);
+                    op_nat<T>(btile(k, ct), lane, bv);
+                    typename Mfma<T>::acc_t acc = acc_load<T>(btile(i, ct), lane);
+                    acc = mma4<T>(av, bv, acc, true);
+                    acc_store<T>(btile(i, ct), lane, acc);
+                }
+            }
+        }
+    }
+    __syncthreads();
+    {
+        T *xp = X.p + b * X.bs;
+        const bool colfast = (X.cs == 1) || (X.rs != 1);
+        const int f = lane & 15, s0 = lane >> 4;
+        for (int t = wave; t < K * MT; t += W) {
+            const int k = t / MT, ct = t % MT;
+            const TileRef<T> tr = btile(k, ct);
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                const int u = colfast ? s0 + 4 * v : f, w = colfast ? f : s0 + 4 * v;
+                const int e = k * LT + u, vec = ct * LT + w;
+                if (e < n && vec < m)
+                    xp[(int64_t)e * X.rs + (int64_t)vec * X.cs] = tr.p[tr.at(u, w)];
+            }
+        }
     }
 }
 
 template <typename T>
-la_status launch_potrf_leaf(View<const T> A, View<T> L, View<T> Inv, int32_t *info, int info_off, int64_t batch, int nb,
-                            hipStream_t st)
+la_status launch_potrf_leaf16(View<const T> A, View<T> L, View<T> Inv, int32_t *info, int info_off, int64_t batch,
+                              int nb, bool zero_upper, hipStream_t st)
 {
     if (batch <= 0 || nb <= 0)
         return LA_OK;
-    if (nb > 2 * NB || batch > 0x7fffffffll)
+    if (nb > LT * LK || batch > 0x7fffffffll)
         return LA_ERR_UNSUPPORTED;
-    if (nb <= NB)
-        hipLaunchKernelGGL((k_potrf_leaf<T>), dim3((unsigned)batch), dim3(LEAF_THREADS), 0, st, A, L, Inv, info,
-                           info_off, batch, nb);
-    else
-        hipLaunchKernelGGL((k_potrf_leaf128<T>), dim3((unsigned)batch), dim3(LEAF_THREADS), 0, st, A, L, Inv, info,
-                           info_off, batch, nb);
-    return launch_check("potrf_leaf");
+    constexpr size_t lds_bytes = (size_t)Leaf16<T>::TOTAL * sizeof(T);
+    static bool configured[64] = {};
+    int dev = 0;
+    LA_HIP(hipGetDevice(&dev));
+    if (dev >= 0 && dev < 64 && !configured[dev]) {
+        LA_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&k_potrf_leaf16<T>),
+                                   hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes));
+        configured[dev] = true;
+    }
+    hipLaunchKernelGGL((k_potrf_leaf16<T>), dim3((unsigned)batch), dim3(LEAF16_THREADS), lds_bytes, st, A, L, Inv, info,
+                       info_off, batch, nb, zero_upper ? 1 : 0);
+    return launch_check("potrf_leaf16");
 }
 
-template la_status launch_potrf_leaf<float>(View<const float>, View<float>, View<float>, int32_t *, int, int64_t, int,
-                                            hipStream_t);
-template la_status launch_potrf_leaf<double>(View<const double>, View<double>, View<double>, int32_t *, int, int64_t,
-                                             int, hipStream_t);
+template la_status launch_potrf_leaf16<float>(View<const float>, View<float>, View<float>, int32_t *, int, int64_t, int,
+                                              bool, hipStream_t);
+template la_status launch_potrf_leaf16<double>(View<const double>, View<double>, View<double>, int32_t *, int, int64_t,
+                                               int, bool, hipStream_t);
+
+template <typename T>
+la_status launch_tri_inverse128(View<const T> Lam, View<T> Inv, int64_t batch, int n, hipStream_t st)
+{
+    if (batch <= 0 || n <= 0)
+        return LA_OK;
+    const int nblk = (n + LT * LK - 1) / (LT * LK);
+    if (batch * nblk > 0x7fffffffll)
+        return LA_ERR_UNSUPPORTED;
+    constexpr size_t lds_bytes = (size_t)Leaf16<T>::TOTAL * sizeof(T);
+    static bool configured[64] = {};
+    int dev = 0;
+    LA_HIP(hipGetDevice(&dev));
+    if (dev >= 0 && dev < 64 && !configured[dev]) {
+        LA_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&k_tri_inv_leaf16<T>),
+                                   hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes));
+        configured[dev] = true;
+    }
+    hipLaunchKernelGGL((k_tri_inv_leaf16<T>), dim3((unsigned)(batch * nblk)), dim3(LEAF16_THREADS), lds_bytes, st, Lam,
+                       Inv, batch, n, nblk);
+    return launch_check("tri_inverse128");
+}
+
+template la_status launch_tri_inverse128<float>(View<const float>, View<float>, int64_t, int, hipStream_t);
+template la_status launch_tri_inverse128<double>(View<const double>, View<double>, int64_t, int, hipStream_t);
+
+template <typename T>
+la_status launch_trsm_leaf16(View<const T> Lam, View<const T> Xin, View<T> X, int64_t batch, int n, int m, T alpha,
+                             bool fwd, hipStream_t st)
+{
+    if (batch <= 0 || n <= 0 || m <= 0)
+        return LA_OK;
+    if (n > LT * LK || m > LT * TRSM16_MAX_CT || batch > 0x7fffffffll)
+        return LA_ERR_UNSUPPORTED;
+    constexpr size_t lds_bytes = (size_t)Leaf16<T>::TOTAL * sizeof(T);
+    static bool configured[64] = {};
+    int dev = 0;
+    LA_HIP(hipGetDevice(&dev));
+    if (dev >= 0 && dev < 64 && !configured[dev]) {
+        LA_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&k_trsm_leaf16<T>),
+                                   hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes));
+        configured[dev] = true;
+    }
+    hipLaunchKernelGGL((k_trsm_leaf16<T>), dim3((unsigned)batch), dim3(LEAF16_THREADS), lds_bytes, st, Lam, Xin, X,
+                       batch, n, m, alpha, fwd ? 1 : 0);
+    return launch_check("trsm_leaf16");
+}
+
+template la_status launch_trsm_leaf16<float>(View<const float>, View<const float>, View<float>, int64_t, int, int, float,
+                                             bool, hipStream_t);
+template la_status launch_trsm_leaf16<double>(View<const double>, View<const double>, View<double>, int64_t, int, int,
+                                              double, bool, hipStream_t);
 
 }  // namespace la

@@ -92,7 +92,7 @@ def test_checker_handles_64_bit_operands():
 
 
 def test_diagonal_block_leaf_respects_dpp_spacing():
-    text = _isa_text("leaf16.hip")
+    text = _isa_text("leaf.hip")
     hazards, n_dpp = find_hazards(text)
     # per element type two inlined copies of the 16 x 16 factor-and-invert routine, 192 broadcast
     # multiply-adds each
