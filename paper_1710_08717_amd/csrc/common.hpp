@@ -282,14 +282,12 @@ struct GemmOpts {
     int reverse = 0;   // 1: schedule the tiles last-to-first (heavy tiles of triangular work first)
     int shells = 0;    // 1: square problem whose K range depends on max(i, j): schedule by shells
     int order = 0;     // tile enumeration, chosen by the launcher
-    int force128 = 0;  // 1: use 128 x 128 workgroup tiles whatever the grid size
+    int min_tile64 = 0;  // 1: no workgroup tiles smaller than 64 x 64 (a caller that updates C in place over <= 64 rows)
 };
 template <typename T>
 la_status launch_gemm(View<const T> A, View<const T> B, View<T> C, int64_t batch, int M, int N, int K, T alpha,
                       T beta, GemmOpts o, hipStream_t st);
 
-template <typename T>
-bool gemm_fast_eligible(View<const T> A, View<const T> B, View<T> C, int M, int N, int K);
 
 // Element-wise helpers.
 // dst(i,j) = alpha * src(i,j) on rows x cols; keep: 0 all, 1 only i >= j (rest written as 0).

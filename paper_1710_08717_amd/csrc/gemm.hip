@@ -12,8 +12,9 @@
 // Two kernels:
 //  * k_gemm_fast: 16-byte vector loads, register prefetch of the next K slab while the
 //    current one is multiplied out of LDS, 128x128 (K slabs of 16, double-buffered LDS, one
-//    barrier per slab) or 64x64 workgroup tiles (K slabs of 64 for the small, latency-bound
-//    grids of the recursion's lower levels), four wavefronts in a 2 x 2 arrangement, 16x16x4
+//    barrier per slab), 64x64 or 32x32 workgroup tiles (K slabs of 64 for the small,
+//    latency-bound grids of the recursion's lower levels; 32x32 when 64x64 tiles would leave
+//    most compute units idle), four wavefronts in a 2 x 2 arrangement, 16x16x4
 //    MFMA (v_mfma_f64_16x16x4_f64 / v_mfma_f32_16x16x4_f32).  Needs 16-byte aligned operands
 //    and K a multiple of 16.
 //  * k_gemm: element-wise staged fallback for everything else (ragged / unaligned shapes).
@@ -466,22 +467,6 @@ static void launch_fast(bool akf, bool bkf, View<const T> A, View<const T> B, Vi
 
 static inline int flip_tri(int t) { return t == 1 ? 2 : (t == 2 ? 1 : 0); }
 
-// Would launch_gemm take the vectorised kernel for these operands?  (Callers that update C in
-// place along a dimension of up to 128 rely on one 128 x 128 tile covering that dimension.)
-template <typename T>
-bool gemm_fast_eligible(View<const T> A, View<const T> B, View<T> C, int M, int N, int K)
-{
-    if (C.cs != 1 && C.rs == 1)
-        return gemm_fast_eligible<T>(B.t(), A.t(), C.t(), N, M, K);
-    constexpr int VW = Mfma<T>::VW;
-    const bool akf = (A.cs == 1), bkf = (B.rs == 1);
-    const bool a_ok = akf ? aligned16<T>(A, A.rs) : (A.rs == 1 && aligned16<T>(A, A.cs) && M % VW == 0);
-    const bool b_ok = bkf ? aligned16<T>(B, B.cs) : (B.cs == 1 && aligned16<T>(B, B.rs) && N % VW == 0);
-    return K > 0 && K % 16 == 0 && a_ok && b_ok;
-}
-template bool gemm_fast_eligible<float>(View<const float>, View<const float>, View<float>, int, int, int);
-template bool gemm_fast_eligible<double>(View<const double>, View<const double>, View<double>, int, int, int);
-
 template <typename T>
 la_status launch_gemm(View<const T> A, View<const T> B, View<T> C, int64_t batch, int M, int N, int K, T alpha, T beta,
                       GemmOpts o, hipStream_t st)
@@ -498,7 +483,7 @@ la_status launch_gemm(View<const T> A, View<const T> B, View<T> C, int64_t batch
         t.halfDiag = o.halfDiag;
         t.reverse = o.reverse;
         t.shells = o.shells;
-        t.force128 = o.force128;
+        t.min_tile64 = o.min_tile64;
         return launch_gemm<T>(B.t(), A.t(), C.t(), batch, N, M, K, alpha, beta, t, st);
     }
     constexpr int VW = Mfma<T>::VW;
@@ -514,8 +499,13 @@ la_status launch_gemm(View<const T> A, View<const T> B, View<T> C, int64_t batch
         // tiles to balance the uneven K ranges unless the matrices are large
         const bool tri = (o.triA | o.triB | o.maskC) != 0;
         const bool big = tri ? (M >= 2048 && N >= 2048) : (M >= 128 && N >= 128);
-        if (o.force128 || (t128 >= 192 && big))
+        // workgroups a launch with 64 x 64 tiles would have (empty tiles of triangular outputs left out)
+        const int tm64 = (M + 63) / 64, tn64 = (N + 63) / 64;
+        const int64_t wg64 = tile_count(pick_order(o, tm64, tn64), tm64, tn64) * batch;
+        if (t128 >= 192 && big)
             launch_fast<T, 128, 128, 16, 2>(akf, bkf, A, B, C, batch, M, N, K, alpha, beta, o, st);
+        else if (K % 64 == 0 && wg64 <= 256 && !o.min_tile64)  // too few tiles to fill the chip: quarter tiles
+            launch_fast<T, 32, 32, 64, 1>(akf, bkf, A, B, C, batch, M, N, K, alpha, beta, o, st);
         else if (K % 64 == 0)  // small grids are latency bound: fewer, fatter K slabs
             launch_fast<T, 64, 64, 64, 1>(akf, bkf, A, B, C, batch, M, N, K, alpha, beta, o, st);
         else

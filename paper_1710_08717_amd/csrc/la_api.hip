@@ -156,46 +156,6 @@ static la_status inverse_build(View<const T> Lam, View<T> Inv, View<T> Tmp, int6
 }
 
 // ---------------------------------------------------------------------------------
-// In-place triangular solve with a logical lower-triangular Lam (n x n) applied to nvec vectors
-// held in X: element e of vector v at X(e, v).
-//   fwd: X <- Lam^-1 X      !fwd: X <- Lam^-T X
-// Recursive halving; the leaves (n <= 64) multiply by the precomputed inverse of the diagonal
-// block (Inv, whose diagonal 64-blocks hold those inverses).  In place is safe there because one
-// workgroup tile covers all n <= 64 rows of its vectors.
-// leaf128: the 128 x 128 diagonal blocks of Inv hold complete inverses (true for a factor that
-// the blocked potrf has just produced); a block of exactly 128 is then one in-place GEMM too,
-// with a single 128 x 128 tile covering its rows.
-template <typename T>
-static la_status solve_rec(View<const T> Lam, View<T> X, int64_t batch, int n, int64_t nvec, bool fwd,
-                           View<const T> Inv, bool leaf128, hipStream_t st)
-{
-    GemmOpts o;
-    if (n <= NB) {
-        o.triA = fwd ? 1 : 2;
-        return launch_gemm<T>(fwd ? Inv : Inv.t(), cv(X), X, batch, n, (int)nvec, n, T(1), T(0), o, st);
-    }
-    if (leaf128 && n == 2 * NB) {
-        View<const T> Iv = fwd ? Inv : Inv.t();
-        if (gemm_fast_eligible<T>(Iv, cv(X), X, n, (int)nvec, n)) {
-            o.triA = fwd ? 1 : 2;
-            o.force128 = 1;
-            return launch_gemm<T>(Iv, cv(X), X, batch, n, (int)nvec, n, T(1), T(0), o, st);
-        }
-    }
-    const int n1 = split_point(n), n2 = n - n1;
-    View<const T> L11 = Lam, L21 = Lam.sub(n1, 0), L22 = Lam.sub(n1, n1);
-    View<T> X1 = X, X2 = X.sub(n1, 0);
-    if (fwd) {
-        LA_TRY(solve_rec<T>(L11, X1, batch, n1, nvec, true, Inv, leaf128, st));
-        LA_TRY(launch_gemm<T>(L21, cv(X1), X2, batch, n2, (int)nvec, n1, T(-1), T(1), o, st));
-        return solve_rec<T>(L22, X2, batch, n2, nvec, true, Inv.sub(n1, n1), leaf128, st);
-    }
-    LA_TRY(solve_rec<T>(L22, X2, batch, n2, nvec, false, Inv.sub(n1, n1), leaf128, st));
-    LA_TRY(launch_gemm<T>(L21.t(), cv(X2), X1, batch, n1, (int)nvec, n2, T(-1), T(1), o, st));
-    return solve_rec<T>(L11, X1, batch, n1, nvec, false, Inv, leaf128, st);
-}
-
-// ---------------------------------------------------------------------------------
 // Blocked potrf by recursive halving (section 4.2: A = L L^T).  Wk holds the lower triangle of
 // the block still to be factored (a working copy, updated in place), L receives the factor, Inv
 // the inverses of the factors of the diagonal sub-blocks; off is the index of the block's first
@@ -324,7 +284,7 @@ static la_status potrf_t(int lower, int64_t batch, int n, const void *A, void *L
 // of vector v, so that every case is "apply Lam, Lam^T or one of their inverses to vectors".
 //   trmm: one GEMM with the triangular operand masked.
 //   trsm, n <= 128 and at most 48 vectors: one block-substitution kernel.
-//   trsm, n <= 64: product with the inverse of the single diagonal block.
+//   trsm, n <= 64: product (in place) with the inverse of the single diagonal block.
 //   trsm, n <= 1024: explicit inverse of Lam (see inverse_build), then one masked GEMM.
 //   trsm, larger n: inverses of the 512 x 512 diagonal blocks, then block substitution with two
 //     GEMMs per block (the block's solution goes through a scratch panel because a product
@@ -347,13 +307,16 @@ static la_status tri_apply_t(bool solve, int lower, int trans, int rightside, do
     if (solve && n <= 128 && m <= 48)  // small: one workgroup per item does the whole substitution, no scratch
         return launch_trsm_leaf16<T>(Lam, Xin, X, batch, n, m, (T)alpha, fwd, st);
 
-    if (solve && n <= NB) {
+    if (solve && n <= NB) {  // inverse of the single block, then one product in place
         if (!inplace || alpha != 1.0)
             LA_TRY(launch_copy<T>(Xin, X, batch, n, m, (T)alpha, 0, st));
         View<T> Inv;
         LA_TRY(scratch_views<T>(batch, n, 1, &Inv));
         LA_TRY(launch_tri_inverse128<T>(Lam, Inv, batch, n, st));
-        return solve_rec<T>(Lam, X, batch, n, m, fwd, cv(Inv), false, st);
+        GemmOpts oi;
+        oi.triA = fwd ? 1 : 2;
+        oi.min_tile64 = 1;  // in place is safe because one 64 x 64 workgroup tile covers all n rows of its vectors
+        return launch_gemm<T>(fwd ? cv(Inv) : cv(Inv).t(), cv(X), X, batch, n, m, n, T(1), T(0), oi, st);
     }
 
     // scratch: [inverse n*n] [merge temporary n*n] (solve only), then a panel shaped like X

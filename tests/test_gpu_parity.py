@@ -85,7 +85,7 @@ def tri(seed, batch, n, lower, dtype):
     return T.astype(npdt(dtype))
 
 
-SIZES = [1, 2, 5, 15, 16, 17, 31, 32, 33, 48, 64, 65, 100, 128, 129, 200, 256, 321]
+SIZES = [1, 2, 5, 15, 16, 17, 31, 32, 33, 48, 64, 65, 80, 97, 100, 112, 113, 127, 128, 129, 192, 200, 256, 321, 384]
 
 
 # ----------------------------------------------------------------------------
@@ -110,7 +110,7 @@ def test_potrf_parity(la, orc, dtype, n, lower):
 
 
 @pytest.mark.parametrize("dtype", ["f64", "f32"])
-@pytest.mark.parametrize("n", [8, 16, 32, 50, 150])
+@pytest.mark.parametrize("n", [8, 16, 32, 50, 100, 128, 150])
 @pytest.mark.parametrize("lower", [True, False])
 def test_potrf_in_place_and_other_triangle_ignored(la, orc, dtype, n, lower):
     A = spd(n + 11, 5, n, dtype)
@@ -126,7 +126,7 @@ def test_potrf_in_place_and_other_triangle_ignored(la, orc, dtype, n, lower):
 
 
 @pytest.mark.parametrize("dtype", ["f64", "f32"])
-@pytest.mark.parametrize("n,bad", [(6, 3), (16, 15), (32, 0), (64, 40), (200, 130)])
+@pytest.mark.parametrize("n,bad", [(6, 3), (16, 15), (32, 0), (64, 40), (100, 0), (100, 70), (128, 127), (200, 130)])
 def test_potrf_info_first_bad_pivot(la, orc, dtype, n, bad):
     import torch
 
@@ -242,7 +242,8 @@ def test_backward_closed_forms(la, orc):
 # ----------------------------------------------------------------------------
 @pytest.mark.parametrize("dtype", ["f64", "f32"])
 @pytest.mark.parametrize("lower,trans,rightside", FLAGS)
-@pytest.mark.parametrize("n,m", [(1, 1), (5, 3), (32, 8), (64, 64), (65, 7), (100, 130), (200, 33), (257, 70)])
+@pytest.mark.parametrize("n,m", [(1, 1), (5, 3), (17, 17), (32, 8), (64, 64), (65, 7), (100, 33), (100, 130), (113, 20), (128, 1),
+                                 (128, 48), (128, 49), (200, 33), (257, 70)])
 def test_trsm_parity(la, orc, dtype, lower, trans, rightside, n, m):
     batch = 3
     T = tri(n + m, batch, n, lower, dtype)
