@@ -26,10 +26,12 @@
  *  - Return value: LA_OK, or LA_ERR_INVALID_ARG (null pointer with non-empty
  *    work, negative size, bad enum, forbidden aliasing), LA_ERR_UNSUPPORTED,
  *    LA_ERR_RUNTIME (a HIP call failed; see la_last_error()).
- *  - Small problems (potrf with n <= 64, backward with n <= 32, syrk, gemm2,
- *    sumlogdiag, gp_glue) allocate nothing.  The blocked paths for larger n keep one
- *    scratch buffer per device (explicit inverses of the factor or of its diagonal
- *    blocks and one work panel, at most 3*batch*n*n elements), allocated with
+ *  - Small problems (potrf with n <= 64, backward with n <= 32, trsm with n <= 128
+ *    and at most 48 right-hand sides, syrk, gemm2, sumlogdiag, gp_glue) allocate
+ *    nothing.  The blocked paths for larger n keep one scratch buffer per device
+ *    (explicit inverses of the factor or of its diagonal blocks, a working copy of
+ *    the triangle being factored or one work panel, at most 3*batch*n*n elements),
+ *    allocated with
  *    hipMalloc on first use, grown on demand and kept until the process ends.
  *    Calls that use it must not overlap on different streams of one device.
  */
