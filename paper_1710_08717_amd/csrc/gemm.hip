@@ -343,9 +343,24 @@ __global__ __launch_bounds__(256, 2) void k_gemm_fast(View<const T> A, View<cons
     __shared__ __align__(16) T sB[NBUF][SB::ELEMS];
 
     const int64_t per = tile_count_dev(o.order, tiles_m, tiles_n);
-    const int64_t slot = xcd_slot(blockIdx.x, per * batch);
-    const int64_t b = slot / per;
-    int tile = (int)(slot % per);
+    int64_t b;
+    int tile;
+    if (o.xcd_batch) {
+        // Batched launch: XCD x (workgroups x, x + 8, ...) owns the items b = x, x + 8, ... and
+        // goes through the tile list once for all of them, tile by tile.  The tile lists are
+        // heaviest-first, so the uneven tiles of triangular problems pack well over the
+        // workgroup slots, and the tiles of one item still meet in one L2.
+        const int x = (int)(blockIdx.x & 7);
+        const int64_t q = blockIdx.x >> 3, mpx = (batch + 7) >> 3;
+        tile = (int)(q / mpx);
+        b = (q % mpx) * 8 + x;
+        if (b >= batch)
+            return;
+    } else {
+        const int64_t slot = xcd_slot(blockIdx.x, per * batch);
+        b = slot / per;
+        tile = (int)(slot % per);
+    }
     if (o.reverse)
         tile = (int)per - 1 - tile;  // heaviest tiles first when the work grows along the tile list
     int tm, tn;
@@ -450,7 +465,10 @@ static void launch_fast(bool akf, bool bkf, View<const T> A, View<const T> B, Vi
 {
     const int tiles_m = (M + BM - 1) / BM, tiles_n = (N + BN - 1) / BN;
     o.order = pick_order(o, tiles_m, tiles_n);
-    const dim3 grid((unsigned)(tile_count(o.order, tiles_m, tiles_n) * batch)), block(256);
+    const int64_t per = tile_count(o.order, tiles_m, tiles_n);
+    o.xcd_batch = (batch >= 8 && per > 1) ? 1 : 0;
+    const int64_t wgs = o.xcd_batch ? 8 * ((batch + 7) / 8) * per : per * batch;
+    const dim3 grid((unsigned)wgs), block(256);
 #define LA_GO(AK, BKF_)                                                                                              \
     hipLaunchKernelGGL((k_gemm_fast<T, BM, BN, BK, NBUF, AK, BKF_>), grid, block, 0, st, A, B, C, batch, M, N, K,    \
                        alpha, beta, o, tiles_m, tiles_n)
@@ -493,7 +511,7 @@ la_status launch_gemm(View<const T> A, View<const T> B, View<T> C, int64_t batch
     if (K > 0 && K % 16 == 0 && a_ok && b_ok) {
         const int64_t t128 = (int64_t)((M + 127) / 128) * ((N + 127) / 128) * batch;
         const int64_t t64 = (int64_t)((M + 63) / 64) * ((N + 63) / 64) * batch;
-        if (t64 > 0x7fffffffll)
+        if (t64 > 0x1fffffffll)  // (quarter tiles and the batched mapping round the grid up)
             return LA_ERR_UNSUPPORTED;
         // triangular operands / outputs: 128-tiles waste work along the diagonal and leave too few
         // tiles to balance the uneven K ranges unless the matrices are large
