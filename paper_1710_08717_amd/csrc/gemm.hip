@@ -357,9 +357,10 @@ __global__ __launch_bounds__(256, 2) void k_gemm_fast(View<const T> A, View<cons
         if (b >= batch)
             return;
     } else {
+        // a few items: tile-major too (tile t of every item, then tile t + 1, ...)
         const int64_t slot = xcd_slot(blockIdx.x, per * batch);
-        b = slot / per;
-        tile = (int)(slot % per);
+        tile = (int)(slot / batch);
+        b = slot % batch;
     }
     if (o.reverse)
         tile = (int)per - 1 - tile;  // heaviest tiles first when the work grows along the tile list
@@ -509,22 +510,35 @@ la_status launch_gemm(View<const T> A, View<const T> B, View<T> C, int64_t batch
     const bool a_ok = akf ? aligned16<T>(A, A.rs) : (A.rs == 1 && aligned16<T>(A, A.cs) && M % VW == 0);
     const bool b_ok = bkf ? aligned16<T>(B, B.cs) : (B.cs == 1 && aligned16<T>(B, B.rs) && N % VW == 0);
     if (K > 0 && K % 16 == 0 && a_ok && b_ok) {
-        const int64_t t128 = (int64_t)((M + 127) / 128) * ((N + 127) / 128) * batch;
         const int64_t t64 = (int64_t)((M + 63) / 64) * ((N + 63) / 64) * batch;
         if (t64 > 0x1fffffffll)  // (quarter tiles and the batched mapping round the grid up)
             return LA_ERR_UNSUPPORTED;
-        // triangular operands / outputs: 128-tiles waste work along the diagonal and leave too few
-        // tiles to balance the uneven K ranges unless the matrices are large
-        const bool tri = (o.triA | o.triB | o.maskC) != 0;
-        const bool big = tri ? (M >= 2048 && N >= 2048) : (M >= 128 && N >= 128);
-        // workgroups a launch with 64 x 64 tiles would have (empty tiles of triangular outputs left out)
-        const int tm64 = (M + 63) / 64, tn64 = (N + 63) / 64;
-        const int64_t wg64 = tile_count(pick_order(o, tm64, tn64), tm64, tn64) * batch;
-        if (t128 >= 192 && big)
+        // Workgroups a launch would have with each tile size (empty tiles of triangular outputs
+        // left out).
+        auto wgs = [&](int e) {
+            const int tm = (M + e - 1) / e, tn = (N + e - 1) / e;
+            return tile_count(pick_order(o, tm, tn), tm, tn) * batch;
+        };
+        const int64_t wg128 = wgs(128), wg64 = wgs(64);
+        const bool k64 = (K % 64 == 0);
+        int e;
+        if (o.triA | o.triB) {
+            // Triangular operands make the K range, hence the time, of a tile vary along the tile
+            // list (heaviest first): the 512 workgroup slots only fill evenly if there are several
+            // rounds of tiles, so take the largest tile that still gives 1024 workgroups.
+            e = wg128 >= 1024 ? 128 : ((wg64 >= 1024 || !k64 || o.min_tile64) ? 64 : 32);
+        } else {
+            // Equal tiles: big tiles once they fill most of the chip, quarter tiles when 64 x 64
+            // tiles would leave most compute units idle.
+            const int64_t t128 = (int64_t)((M + 127) / 128) * ((N + 127) / 128) * batch;
+            const bool big = o.maskC ? (M >= 2048 && N >= 2048) : (M >= 128 && N >= 128);
+            e = (t128 >= 192 && big) ? 128 : ((wg64 <= 256 && k64 && !o.min_tile64) ? 32 : 64);
+        }
+        if (e == 128)
             launch_fast<T, 128, 128, 16, 2>(akf, bkf, A, B, C, batch, M, N, K, alpha, beta, o, st);
-        else if (K % 64 == 0 && wg64 <= 256 && !o.min_tile64)  // too few tiles to fill the chip: quarter tiles
+        else if (e == 32)
             launch_fast<T, 32, 32, 64, 1>(akf, bkf, A, B, C, batch, M, N, K, alpha, beta, o, st);
-        else if (K % 64 == 0)  // small grids are latency bound: fewer, fatter K slabs
+        else if (k64)  // small grids are latency bound: fewer, fatter K slabs
             launch_fast<T, 64, 64, 64, 1>(akf, bkf, A, B, C, batch, M, N, K, alpha, beta, o, st);
         else
             launch_fast<T, 64, 64, 16, 2>(akf, bkf, A, B, C, batch, M, N, K, alpha, beta, o, st);
