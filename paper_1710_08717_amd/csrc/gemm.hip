@@ -35,9 +35,8 @@ __device__ __forceinline__ bool tri_keep(int tri, int o, int k)
 // XCD's L2), while all XCDs still advance through the slot list at the same pace, which
 // matters because triangular operands make the work per tile vary along the list.
 // ---------------------------------------------------------------------------------------
-__device__ __forceinline__ int64_t xcd_slot(int64_t w, int64_t total)
+__device__ __forceinline__ int64_t xcd_slot(int64_t w, int64_t total, int CH = 16)
 {
-    constexpr int CH = 16;
     const int64_t c = w / (8 * CH);
     if ((c + 1) * 8 * CH > total)
         return w;  // incomplete last chunk keeps its order
@@ -55,6 +54,12 @@ __device__ __forceinline__ int64_t xcd_slot(int64_t w, int64_t total)
 //            a shell has the same K range when both operands are triangular.
 //   order 4: all tiles, column-major (the K range depends on the column only when just B is
 //            triangular).
+//   order 5: tiles on or below the diagonal in bands of 8 diagonals tm - tn = d, the band with the
+//            largest d first; inside a band row by row from the last row up, a row's tiles by
+//            falling d.  For lower x lower = lower products the K range of a tile is d + 1 tile
+//            edges, so this list is nearly sorted by work (which the slots need to fill evenly:
+//            the heaviest tile is three times the mean) while the (up to) 8 consecutive tiles of a
+//            row still share their A panel.
 __device__ __forceinline__ void decode_tile(int order, int t, int tiles_m, int tiles_n, int &tm, int &tn)
 {
     if (order == 0) {
@@ -63,6 +68,26 @@ __device__ __forceinline__ void decode_tile(int order, int t, int tiles_m, int t
     } else if (order == 4) {
         tn = t / tiles_m;
         tm = t % tiles_m;
+    } else if (order == 5) {
+        const int T = tiles_m;
+        int b = (T - 1) / 8;
+        for (;; --b) {  // band: diagonals 8 b .. min(T - 1, 8 b + 7)
+            const int dlo = 8 * b, dhi = min(T - 1, dlo + 7);
+            const int cnt = (dhi - dlo + 1) * T - (dlo + dhi) * (dhi - dlo + 1) / 2;  // sum of T - d
+            if (t < cnt || b == 0)
+                break;
+            t -= cnt;
+        }
+        const int dlo = 8 * b, dhi = min(T - 1, dlo + 7);
+        int i = T - 1;
+        for (;; --i) {  // row i holds the diagonals min(dhi, i) .. dlo of the band
+            const int cnt = min(dhi, i) - dlo + 1;
+            if (t < cnt || i == dlo)
+                break;
+            t -= cnt;
+        }
+        tm = i;
+        tn = i - (min(dhi, i) - t);
     } else if (order == 3) {
         int s_ = (int)sqrt((double)t);
         while ((s_ + 1) * (s_ + 1) <= t)
@@ -91,13 +116,13 @@ __device__ __forceinline__ void decode_tile(int order, int t, int tiles_m, int t
 
 __device__ __forceinline__ int64_t tile_count_dev(int order, int tiles_m, int tiles_n)
 {
-    if (order == 1 || order == 2)
+    if (order == 1 || order == 2 || order == 5)
         return (int64_t)tiles_m * (tiles_m + 1) / 2;
     return (int64_t)tiles_m * tiles_n;
 }
 static inline int64_t tile_count(int order, int tiles_m, int tiles_n)
 {
-    if (order == 1 || order == 2)
+    if (order == 1 || order == 2 || order == 5)
         return (int64_t)tiles_m * (tiles_m + 1) / 2;
     return (int64_t)tiles_m * tiles_n;
 }
@@ -181,7 +206,7 @@ __global__ __launch_bounds__(256) void k_gemm(View<const T> A, View<const T> B, 
     const int64_t per = tile_count_dev(o.order, tiles_m, tiles_n);
     const int64_t b = bid / per;
     int tile = (int)(bid % per);
-    if (o.reverse)
+    if (o.reverse && o.order != 5)
         tile = (int)per - 1 - tile;
     int tm, tn;
     decode_tile(o.order, tile, tiles_m, tiles_n, tm, tn);
@@ -358,11 +383,11 @@ __global__ __launch_bounds__(256, 2) void k_gemm_fast(View<const T> A, View<cons
             return;
     } else {
         // a few items: tile-major too (tile t of every item, then tile t + 1, ...)
-        const int64_t slot = xcd_slot(blockIdx.x, per * batch);
+        const int64_t slot = xcd_slot(blockIdx.x, per * batch, o.order == 5 ? 8 : 16);
         tile = (int)(slot / batch);
         b = slot % batch;
     }
-    if (o.reverse)
+    if (o.reverse && o.order != 5)
         tile = (int)per - 1 - tile;  // heaviest tiles first when the work grows along the tile list
     int tm, tn;
     decode_tile(o.order, tile, tiles_m, tiles_n, tm, tn);
@@ -453,6 +478,8 @@ static inline int pick_order(const GemmOpts &o, int tiles_m, int tiles_n)
         return 4;  // work depends on the column only
     if (tiles_m != tiles_n)
         return 0;
+    if (o.maskC == 1 && o.triA == 1 && o.triB == 1 && tiles_m >= 16)
+        return 5;
     if (o.maskC == 1)
         return 1;
     if (o.maskC == 2)
