@@ -41,6 +41,9 @@ def _load():
         lib.orc_trsm.argtypes = [i32, i32, i32, f64, i64, i32, i32, dp, dp, dp]
         lib.orc_trmm.argtypes = [i32, i32, i32, f64, i64, i32, i32, dp, dp, dp]
         lib.orc_syrk.argtypes = [i32, f64, i64, i32, i32, dp, dp]
+        lib.orc_trmm_backward.argtypes = [i32, i32, i32, f64, i64, i32, i32, dp, dp, dp, dp, dp]
+        lib.orc_trsm_backward.argtypes = [i32, i32, i32, f64, i64, i32, i32, dp, dp, dp, dp, dp]
+        lib.orc_syrk_backward.argtypes = [i32, f64, i64, i32, i32, dp, dp, dp]
         lib.orc_sumlogdiag.argtypes = [i64, i32, dp, dp]
         lib.orc_gemm2.argtypes = [i32, i32, f64, i64, i32, i32, i32, dp, dp, dp]
         lib.orc_gp_glue.argtypes = [i64, i32, dp, dp, dp, dp, dp, dp]
@@ -145,6 +148,41 @@ def syrk(A, trans=False, alpha=1.0):
     b = _batch_of(A, 2)
     out = np.empty(A.shape[:-2] + (n, n), dtype=np.float64)
     _check(_load().orc_syrk(int(trans), float(alpha), b, n, k, _p(A), _p(out)), "syrk")
+    return out
+
+
+def _tri_backward(fn, name, L, X, Bbar, lower, trans, rightside, alpha):
+    L, X, Bbar = _f64(L), _f64(X), _f64(Bbar)
+    n = L.shape[-1]
+    assert L.shape[-2] == n and X.shape == Bbar.shape
+    m = X.shape[-2] if rightside else X.shape[-1]
+    assert (X.shape[-1] if rightside else X.shape[-2]) == n
+    b = _batch_of(L, 2)
+    assert _batch_of(X, 2) == b
+    Abar = np.empty_like(X)
+    Lbar = np.empty_like(L)
+    _check(fn(int(lower), int(trans), int(rightside), float(alpha), b, n, m, _p(L), _p(X), _p(Bbar), _p(Abar), _p(Lbar)),
+           name)
+    return Abar, Lbar
+
+
+def trmm_backward(L, A, Bbar, lower=True, trans=False, rightside=False, alpha=1.0):
+    """(Abar, Lbar) of B = alpha t(L) A / alpha A t(L); needs the forward input A."""
+    return _tri_backward(_load().orc_trmm_backward, "trmm_backward", L, A, Bbar, lower, trans, rightside, alpha)
+
+
+def trsm_backward(L, B, Bbar, lower=True, trans=False, rightside=False, alpha=1.0):
+    """(Abar, Lbar) of B = alpha t(L)^-1 A / alpha A t(L)^-1; needs the forward OUTPUT B."""
+    return _tri_backward(_load().orc_trsm_backward, "trsm_backward", L, B, Bbar, lower, trans, rightside, alpha)
+
+
+def syrk_backward(A, Bbar, trans=False, alpha=1.0):
+    A, Bbar = _f64(A), _f64(Bbar)
+    n, k = (A.shape[-1], A.shape[-2]) if trans else (A.shape[-2], A.shape[-1])
+    assert Bbar.shape[-2:] == (n, n)
+    out = np.empty_like(A)
+    _check(_load().orc_syrk_backward(int(trans), float(alpha), _batch_of(A, 2), n, k, _p(A), _p(Bbar), _p(out)),
+           "syrk_backward")
     return out
 
 

@@ -324,6 +324,123 @@ int orc_syrk(int trans, double alpha, int64_t batch, int n, int k, const double 
 }
 
 /* ------------------------------------------------------------------------- */
+/* Outer product that carries the gradient of the triangular operand in the trmm and
+ * trsm backward rules (section 4.2; appendix "trsm", "trmm", also for an upper
+ * factor): with P, Q of the shape of A (n x m for a left-side operator, m x n for a
+ * right-side one) and (X1, X2) = (P, Q) without transposition, (Q, P) with it,
+ *   left:  G = X1 X2^T,     right:  G = X2^T X1     (n x n),
+ * of which the triangle of the factor is kept (tril for a lower factor, triu for an
+ * upper one), scaled by `scale`; the other triangle of out is set to zero. */
+static void tri_outer(int lower, int trans, int rightside, double scale, int n, int m, const double *P,
+                      const double *Q, double *out)
+{
+    const double *X1 = trans ? Q : P, *X2 = trans ? P : Q;
+    for (int i = 0; i < n; ++i)
+        for (int j = 0; j < n; ++j) {
+            double s = 0.0;
+            int keep = lower ? (i >= j) : (i <= j);
+            if (keep) {
+                if (!rightside)
+                    for (int c = 0; c < m; ++c)
+                        s += X1[(size_t)i * m + c] * X2[(size_t)j * m + c];
+                else
+                    for (int r = 0; r < m; ++r)
+                        s += X2[(size_t)r * n + i] * X1[(size_t)r * n + j];
+                s *= scale;
+            }
+            out[(size_t)i * n + j] = s;
+        }
+}
+
+/* trmm backward (section 4.2, "trmm"; appendix "trmm"): for B = alpha t(L) A (left) or
+ * B = alpha A t(L) (right),
+ *   Abar = alpha t(L)^T Bbar  resp.  alpha Bbar t(L)^T,
+ *   Lbar = alpha tri( Bbar A^T | A Bbar^T | A^T Bbar | Bbar^T A )   for (left, t=no | left, t=yes |
+ *          right, t=no | right, t=yes), tri = tril for a lower factor, triu for an upper one.
+ * Lbar is computed first, so Abar may be the same memory as Bbar. */
+int orc_trmm_backward(int lower, int trans, int rightside, double alpha, int64_t batch, int n, int m,
+                      const double *L, const double *A, const double *Bbar, double *Abar, double *Lbar)
+{
+    if (batch < 0 || n < 0 || m < 0)
+        return ORC_ERR_INVALID_ARG;
+    if (batch == 0 || n == 0)
+        return ORC_OK;
+    if (!L || !Lbar || (m > 0 && (!A || !Bbar || !Abar)))
+        return ORC_ERR_INVALID_ARG;
+    size_t nn = (size_t)n * n, nm = (size_t)n * m;
+    for (int64_t b = 0; b < batch; ++b)
+        tri_outer(lower, trans, rightside, alpha, n, m, Bbar + b * nm, A + b * nm, Lbar + b * nn);
+    if (m == 0)
+        return ORC_OK;
+    return orc_trmm(lower, !trans, rightside, alpha, batch, n, m, L, Bbar, Abar);
+}
+
+/* trsm backward (section 4.2, "trsm"; appendix "trsm"): for B = alpha t(L)^-1 A (left) or
+ * B = alpha A t(L)^-1 (right), with Y = t(L)^-T Bbar resp. Bbar t(L)^-T,
+ *   Abar = alpha Y,
+ *   Lbar = -tri( Y B^T | B Y^T | B^T Y | Y^T B )   (same four cases as above).
+ * For alpha = 1 this is the paper's rule with Abar in place of Y.  Needs the forward OUTPUT B,
+ * not A.  Abar may be the same memory as Bbar. */
+int orc_trsm_backward(int lower, int trans, int rightside, double alpha, int64_t batch, int n, int m,
+                      const double *L, const double *B, const double *Bbar, double *Abar, double *Lbar)
+{
+    if (batch < 0 || n < 0 || m < 0)
+        return ORC_ERR_INVALID_ARG;
+    if (batch == 0 || n == 0)
+        return ORC_OK;
+    if (!L || !Lbar || (m > 0 && (!B || !Bbar || !Abar)))
+        return ORC_ERR_INVALID_ARG;
+    size_t nn = (size_t)n * n, nm = (size_t)n * m;
+    if (m > 0) {
+        int rc = orc_trsm(lower, !trans, rightside, 1.0, batch, n, m, L, Bbar, Abar); /* Y */
+        if (rc != ORC_OK)
+            return rc;
+    }
+    for (int64_t b = 0; b < batch; ++b)
+        tri_outer(lower, trans, rightside, -1.0, n, m, Abar + b * nm, B + b * nm, Lbar + b * nn);
+    for (size_t e = 0; e < (size_t)batch * nm; ++e)
+        Abar[e] *= alpha;
+    return ORC_OK;
+}
+
+/* syrk backward (section 4.2, "syrk"): Bbar need not be symmetric;
+ *   B = alpha A A^T  (A n x k):  Abar = 2 alpha sym(Bbar) A = alpha (Bbar + Bbar^T) A
+ *   B = alpha A^T A  (A k x n):  Abar = alpha A (Bbar + Bbar^T) */
+int orc_syrk_backward(int trans, double alpha, int64_t batch, int n, int k, const double *A,
+                      const double *Bbar, double *Abar)
+{
+    if (batch < 0 || n < 0 || k < 0)
+        return ORC_ERR_INVALID_ARG;
+    if (batch == 0 || n == 0 || k == 0)
+        return ORC_OK;
+    if (!A || !Bbar || !Abar)
+        return ORC_ERR_INVALID_ARG;
+    size_t nn = (size_t)n * n, nk = (size_t)n * k;
+    for (int64_t b = 0; b < batch; ++b) {
+        const double *Ab = A + b * nk, *G = Bbar + b * nn;
+        double *O = Abar + b * nk;
+        if (!trans) {
+            for (int i = 0; i < n; ++i)
+                for (int p = 0; p < k; ++p) {
+                    double s = 0.0;
+                    for (int j = 0; j < n; ++j)
+                        s += (G[(size_t)i * n + j] + G[(size_t)j * n + i]) * Ab[(size_t)j * k + p];
+                    O[(size_t)i * k + p] = alpha * s;
+                }
+        } else {
+            for (int p = 0; p < k; ++p)
+                for (int j = 0; j < n; ++j) {
+                    double s = 0.0;
+                    for (int i = 0; i < n; ++i)
+                        s += Ab[(size_t)p * n + i] * (G[(size_t)i * n + j] + G[(size_t)j * n + i]);
+                    O[(size_t)p * n + j] = alpha * s;
+                }
+        }
+    }
+    return ORC_OK;
+}
+
+/* ------------------------------------------------------------------------- */
 /* gemm2 forward (section 4.2, "gemm2"): C = alpha * t_a(A) t_b(B).
  * t_a(A) is m x k, t_b(B) is k x n, C is m x n; A is stored m x k (ta == 0) or k x m (ta != 0),
  * B is stored k x n (tb == 0) or n x k (tb != 0).  C must not overlap A or B. */
