@@ -84,6 +84,39 @@ la_status la_trmm_batched(la_dtype dt, int lower, int trans, int rightside, doub
                           int64_t batch, int n, int m, const void *L, const void *A, void *B,
                           void *stream);
 
+/* trsm backward (section 4.2 "trsm", backward; appendix "trsm", also for an upper factor).
+ * For the forward B = alpha t(L)^{-1} A (or alpha A t(L)^{-1}), with Y = t(L)^{-T} Bbar (or
+ * Bbar t(L)^{-T}):
+ *   Abar = alpha Y,
+ *   Lbar = -tri(Y B^T), -tri(B Y^T), -tri(B^T Y), -tri(Y^T B)   for (left, t = no), (left, t = yes),
+ *          (right, t = no), (right, t = yes); tri = tril for lower != 0, triu for lower == 0.
+ * With alpha = 1 these are the paper's four cases with Abar in place of Y.
+ * L, Lbar: [batch, n, n]; B (the forward OUTPUT), Bbar, Abar: [batch, n, m] or [batch, m, n] as
+ * in la_trsm_batched.  Lbar is written in full (zeros in the other triangle).  Abar may be the
+ * same buffer as Bbar and Lbar the same buffer as L ("Abar can overwrite Bbar", "Lbar can
+ * overwrite L"); any other overlap is an error. */
+la_status la_trsm_backward(la_dtype dt, int lower, int trans, int rightside, double alpha, int64_t batch,
+                           int n, int m, const void *L, const void *B, const void *Bbar, void *Abar,
+                           void *Lbar, void *stream);
+
+/* trmm backward (section 4.2 "trmm", backward; appendix "trmm"): for the forward
+ * B = alpha t(L) A (or alpha A t(L)):
+ *   Abar = alpha t(L)^T Bbar  (or alpha Bbar t(L)^T),
+ *   Lbar = alpha tri(Bbar A^T), tri(A Bbar^T), tri(A^T Bbar), tri(Bbar^T A)   (same four cases).
+ * A is the forward INPUT.  Shapes as above.  Lbar is computed first, so Abar may be the same
+ * buffer as Bbar; Lbar must not overlap L or anything else. */
+la_status la_trmm_backward(la_dtype dt, int lower, int trans, int rightside, double alpha, int64_t batch,
+                           int n, int m, const void *L, const void *A, const void *Bbar, void *Abar,
+                           void *Lbar, void *stream);
+
+/* syrk backward (section 4.2 "syrk", backward; Bbar need not be symmetric):
+ *   B = alpha A A^T (trans == 0):  Abar = 2 alpha sym(Bbar) A = alpha (Bbar + Bbar^T) A
+ *   B = alpha A^T A (trans != 0):  Abar = alpha A (Bbar + Bbar^T)
+ * A, Abar: [batch, n, k] (trans == 0) or [batch, k, n]; Bbar: [batch, n, n].  Abar must not
+ * overlap A or Bbar. */
+la_status la_syrk_backward(la_dtype dt, int trans, double alpha, int64_t batch, int n, int k, const void *A,
+                           const void *Bbar, void *Abar, void *stream);
+
 /* syrk (section 4.2 "syrk"): B = alpha * A A^T  (trans == 0, A: [batch, n, k])
  *                            B = alpha * A^T A  (trans != 0, A: [batch, k, n])
  * B: [batch, n, n], both triangles written, exactly symmetric.  B must not

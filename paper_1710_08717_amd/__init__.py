@@ -16,8 +16,12 @@ from .binding import (  # noqa: F401
     potrf_backward,
     sumlogdiag,
     syrk,
+    syrk_backward,
     trmm,
+    trmm_backward,
     trsm,
+    trsm_backward,
 )
 
-__all__ = ["potrf", "potrf_backward", "trsm", "trmm", "syrk", "sumlogdiag", "gp_glue", "gemm2", "load", "lib_path", "LaError"]
+__all__ = ["potrf", "potrf_backward", "trsm", "trmm", "syrk", "trsm_backward", "trmm_backward", "syrk_backward", "sumlogdiag",
+           "gp_glue", "gemm2", "load", "lib_path", "LaError"]

@@ -16,7 +16,8 @@ _lib = None
 
 SYMBOLS = [
     "la_potrf_batched", "la_potrf_backward", "la_trsm_batched", "la_trmm_batched", "la_syrk_batched",
-    "la_sumlogdiag", "la_gp_glue", "la_gemm2_batched", "la_last_error", "la_version",
+    "la_sumlogdiag", "la_gp_glue", "la_gemm2_batched", "la_trsm_backward", "la_trmm_backward", "la_syrk_backward",
+    "la_last_error", "la_version",
 ]
 
 
@@ -49,6 +50,11 @@ def load():
     lib.la_gp_glue.argtypes = [i32, i64, i32, vp, vp, vp, vp, vp, vp, vp]
     lib.la_gemm2_batched.argtypes = [i32, i32, i32, f64, i64, i32, i32, i32, vp, vp, vp, vp]
     lib.la_gemm2_batched.restype = i32
+    lib.la_trsm_backward.argtypes = [i32, i32, i32, i32, f64, i64, i32, i32, vp, vp, vp, vp, vp, vp]
+    lib.la_trmm_backward.argtypes = [i32, i32, i32, i32, f64, i64, i32, i32, vp, vp, vp, vp, vp, vp]
+    lib.la_syrk_backward.argtypes = [i32, i32, f64, i64, i32, i32, vp, vp, vp, vp]
+    for name in ("la_trsm_backward", "la_trmm_backward", "la_syrk_backward"):
+        getattr(lib, name).restype = i32
     lib.la_last_error.restype = ctypes.c_char_p
     lib.la_version.restype = i32
     for name in SYMBOLS[:7]:
@@ -151,6 +157,48 @@ def trsm(L, A, lower=True, trans=False, rightside=False, alpha=1.0, out=None):
 
 def trmm(L, A, lower=True, trans=False, rightside=False, alpha=1.0, out=None):
     return _tri(load().la_trmm_batched, "la_trmm_batched", L, A, lower, trans, rightside, alpha, out)
+
+
+def _tri_backward(fn, name, L, X, Bbar, lower, trans, rightside, alpha, out_a, out_l):
+    _chk(L, X)
+    _chk(L, Bbar)
+    n = L.shape[-1]
+    assert L.shape[-2] == n and X.shape == Bbar.shape
+    m = X.shape[-2] if rightside else X.shape[-1]
+    assert (X.shape[-1] if rightside else X.shape[-2]) == n and _batch(L) == _batch(X)
+    Abar = torch.empty_like(Bbar) if out_a is None else out_a
+    Lbar = torch.empty_like(L) if out_l is None else out_l
+    _chk(L, Abar)
+    _chk(L, Lbar)
+    with torch.cuda.device(L.device):
+        _check(fn(_dt(L), int(lower), int(trans), int(rightside), float(alpha), _batch(L), n, m, _ptr(L), _ptr(X),
+                  _ptr(Bbar), _ptr(Abar), _ptr(Lbar), _stream(L)), name)
+    return Abar, Lbar
+
+
+def trsm_backward(L, B, Bbar, lower=True, trans=False, rightside=False, alpha=1.0, out_a=None, out_l=None):
+    """la_trsm_backward: (Abar, Lbar) from the forward OUTPUT B.  out_a may be Bbar, out_l may be L."""
+    return _tri_backward(load().la_trsm_backward, "la_trsm_backward", L, B, Bbar, lower, trans, rightside, alpha, out_a,
+                         out_l)
+
+
+def trmm_backward(L, A, Bbar, lower=True, trans=False, rightside=False, alpha=1.0, out_a=None, out_l=None):
+    """la_trmm_backward: (Abar, Lbar) from the forward INPUT A.  out_a may be Bbar."""
+    return _tri_backward(load().la_trmm_backward, "la_trmm_backward", L, A, Bbar, lower, trans, rightside, alpha, out_a,
+                         out_l)
+
+
+def syrk_backward(A, Bbar, trans=False, alpha=1.0, out=None):
+    """la_syrk_backward: Abar = alpha (Bbar + Bbar^T) A  or  alpha A (Bbar + Bbar^T)."""
+    _chk(A, Bbar)
+    n, k = (A.shape[-1], A.shape[-2]) if trans else (A.shape[-2], A.shape[-1])
+    assert Bbar.shape[-2:] == (n, n) and _batch(A) == _batch(Bbar)
+    Abar = torch.empty_like(A) if out is None else out
+    _chk(A, Abar)
+    with torch.cuda.device(A.device):
+        _check(load().la_syrk_backward(_dt(A), int(trans), float(alpha), _batch(A), n, k, _ptr(A), _ptr(Bbar),
+                                       _ptr(Abar), _stream(A)), "la_syrk_backward")
+    return Abar
 
 
 def syrk(A, trans=False, alpha=1.0, out=None):

@@ -299,6 +299,9 @@ la_status launch_copy(View<const T> src, View<T> dst, int64_t batch, int rows, i
 // (out may alias src).
 template <typename T>
 la_status launch_tril_split(View<const T> src, View<T> work, View<T> out, int64_t batch, int n, hipStream_t st);
+// X(i,j) = 0 for i < j on n x n; nothing else is written (pass X.t() to clear below the diagonal).
+template <typename T>
+la_status launch_zero_strict_upper(View<T> X, int64_t batch, int n, hipStream_t st);
 // X <- scale * (X + X^T) on n x n (exactly symmetric result).
 template <typename T>
 la_status launch_symmetrize(View<T> X, int64_t batch, int n, T scale, hipStream_t st);

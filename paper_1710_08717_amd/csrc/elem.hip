@@ -86,6 +86,39 @@ la_status launch_tril_split(View<const T> src, View<T> work, View<T> out, int64_
     return launch_check("tril_split");
 }
 
+// X(i,j) = 0 for i < j on n x n (nothing else is written).
+template <typename T>
+__global__ __launch_bounds__(256) void k_zero_strict_upper(View<T> X, int64_t batch, int n, int nt)
+{
+    const int64_t per = (int64_t)nt * nt;
+    const int64_t b = blockIdx.x / per;
+    const int tile = (int)(blockIdx.x % per);
+    const int r0 = (tile / nt) * ET, c0 = (tile % nt) * ET;
+    if (r0 > c0 + ET - 1)
+        return;  // tile entirely below the diagonal
+    const bool colfast = (X.cs == 1) || (X.rs != 1);
+    T *xp = X.p + b * X.bs;
+    for (int t = threadIdx.x; t < ET * ET; t += 256) {
+        const int u = t / ET, w = t % ET;
+        const int r = r0 + (colfast ? u : w), c = c0 + (colfast ? w : u);
+        if (r < n && c < n && r < c)
+            xp[(int64_t)r * X.rs + (int64_t)c * X.cs] = T(0);
+    }
+}
+
+template <typename T>
+la_status launch_zero_strict_upper(View<T> X, int64_t batch, int n, hipStream_t st)
+{
+    if (batch <= 0 || n <= 0)
+        return LA_OK;
+    const int nt = (n + ET - 1) / ET;
+    const int64_t blocks = (int64_t)nt * nt * batch;
+    if (blocks > 0x7fffffffll)
+        return LA_ERR_UNSUPPORTED;
+    hipLaunchKernelGGL((k_zero_strict_upper<T>), dim3((unsigned)blocks), dim3(256), 0, st, X, batch, n, nt);
+    return launch_check("zero_strict_upper");
+}
+
 // mode 0: X <- scale * (X + X^T).   mode 1: X(i,j) <- X(j,i) for i < j (lower copied to upper).
 // One block per tile pair (ti >= tj); both tiles pass through LDS so every global access is
 // along the contiguous direction.
@@ -260,6 +293,7 @@ la_status launch_fill_i32(int32_t *p, int64_t count, int32_t v, hipStream_t st)
 #define LA_INST(T)                                                                                              \
     template la_status launch_copy<T>(View<const T>, View<T>, int64_t, int, int, T, int, hipStream_t);          \
     template la_status launch_tril_split<T>(View<const T>, View<T>, View<T>, int64_t, int, hipStream_t);        \
+    template la_status launch_zero_strict_upper<T>(View<T>, int64_t, int, hipStream_t);                         \
     template la_status launch_symmetrize<T>(View<T>, int64_t, int, T, hipStream_t);                             \
     template la_status launch_mirror_lower<T>(View<T>, int64_t, int, hipStream_t);                              \
     template la_status launch_sumlogdiag<T>(const T *, T *, int64_t, int, hipStream_t);                         \

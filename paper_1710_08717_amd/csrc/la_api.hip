@@ -394,6 +394,108 @@ static la_status gemm2_t(int ta, int tb, double alpha, int64_t batch, int m, int
 
 using namespace la;
 
+// ---------------------------------------------------------------------------------
+// Backward rules of trmm and trsm (section 4.2; appendix "trmm", "trsm", both for a lower and an
+// upper factor).  The gradient of the triangular operand is the factor's triangle of an outer
+// product of two matrices P, Q of the shape of A: with (X1, X2) = (P, Q), or (Q, P) when the
+// operator transposes L,
+//   left:  G = X1 X2^T,     right:  G = X2^T X1.
+// ---------------------------------------------------------------------------------
+template <typename T>
+static la_status tri_outer_t(int lower, int trans, int rightside, T scale, int64_t batch, int n, int m, const T *P,
+                             const T *Q, T *out, hipStream_t st)
+{
+    const int64_t nn = (int64_t)n * n, nm = (int64_t)n * m;
+    View<T> G{out, nn, n, 1};
+    LA_TRY(launch_zero_strict_upper<T>(lower ? G : G.t(), batch, n, st));  // the other triangle of the result
+    GemmOpts o;
+    o.maskC = lower ? 1 : 2;
+    if (m == 0)  // empty product: the kept triangle is zero too
+        return launch_copy<T>(cv(G), G, batch, n, n, T(0), 0, st);
+    const T *X1 = trans ? Q : P, *X2 = trans ? P : Q;
+    if (!rightside)
+        return launch_gemm<T>(View<const T>{X1, nm, m, 1}, View<const T>{X2, nm, 1, m}, G, batch, n, n, m, scale, T(0), o,
+                              st);
+    return launch_gemm<T>(View<const T>{X2, nm, 1, n}, View<const T>{X1, nm, n, 1}, G, batch, n, n, m, scale, T(0), o,
+                          st);
+}
+
+template <typename T>
+static la_status trmm_backward_t(int lower, int trans, int rightside, double alpha, int64_t batch, int n, int m,
+                                 const void *L, const void *A, const void *Bbar, void *Abar, void *Lbar, hipStream_t st)
+{
+    // Lbar = alpha tri(outer(Bbar, A)) first, then Abar = alpha t(L)^T Bbar (which may overwrite Bbar)
+    LA_TRY(tri_outer_t<T>(lower, trans, rightside, (T)alpha, batch, n, m, (const T *)Bbar, (const T *)A, (T *)Lbar, st));
+    if (m == 0)
+        return LA_OK;
+    return tri_apply_t<T>(false, lower, !trans, rightside, alpha, batch, n, m, L, Bbar, Abar, st);
+}
+
+template <typename T>
+static la_status trsm_backward_t(int lower, int trans, int rightside, double alpha, int64_t batch, int n, int m,
+                                 const void *L, const void *B, const void *Bbar, void *Abar, void *Lbar, hipStream_t st)
+{
+    // Y = t(L)^-T Bbar into Abar (which may overwrite Bbar), Lbar = -tri(outer(Y, B)) (which may
+    // overwrite L: L is not needed any more), Abar = alpha Y
+    if (m > 0)
+        LA_TRY(tri_apply_t<T>(true, lower, !trans, rightside, 1.0, batch, n, m, L, Bbar, Abar, st));
+    LA_TRY(tri_outer_t<T>(lower, trans, rightside, T(-1), batch, n, m, (const T *)Abar, (const T *)B, (T *)Lbar, st));
+    if (m > 0 && alpha != 1.0) {
+        View<T> Y{(T *)Abar, (int64_t)n * m, rightside ? n : m, 1};
+        LA_TRY(launch_copy<T>(cv(Y), Y, batch, rightside ? m : n, rightside ? n : m, (T)alpha, 0, st));
+    }
+    return LA_OK;
+}
+
+// syrk backward (section 4.2 "syrk"): Abar = alpha (Bbar + Bbar^T) A  resp.  alpha A (Bbar + Bbar^T),
+// two products accumulated in Abar.
+template <typename T>
+static la_status syrk_backward_t(int trans, double alpha, int64_t batch, int n, int k, const void *A, const void *Bbar,
+                                 void *Abar, hipStream_t st)
+{
+    const int64_t nk = (int64_t)n * k, nn = (int64_t)n * n;
+    View<const T> G{(const T *)Bbar, nn, n, 1};
+    GemmOpts o;
+    if (!trans) {
+        View<const T> Av{(const T *)A, nk, k, 1};
+        View<T> Ov{(T *)Abar, nk, k, 1};
+        LA_TRY(launch_gemm<T>(G, Av, Ov, batch, n, k, n, (T)alpha, T(0), o, st));
+        return launch_gemm<T>(G.t(), Av, Ov, batch, n, k, n, (T)alpha, T(1), o, st);
+    }
+    View<const T> Av{(const T *)A, nk, n, 1};
+    View<T> Ov{(T *)Abar, nk, n, 1};
+    LA_TRY(launch_gemm<T>(Av, G, Ov, batch, k, n, n, (T)alpha, T(0), o, st));
+    return launch_gemm<T>(Av, G.t(), Ov, batch, k, n, n, (T)alpha, T(1), o, st);
+}
+
+static la_status tri_backward(bool solve, la_dtype dt, int lower, int trans, int rightside, double alpha, int64_t batch,
+                              int n, int m, const void *L, const void *X, const void *Bbar, void *Abar, void *Lbar,
+                              void *stream)
+{
+    if (bad_dtype(dt) || batch < 0 || n < 0 || m < 0 || n > MAX_N || m > MAX_N)
+        return LA_ERR_INVALID_ARG;
+    if (batch == 0 || n == 0)
+        return LA_OK;
+    if (!L || !Lbar || (m > 0 && (!X || !Bbar || !Abar)))
+        return LA_ERR_INVALID_ARG;
+    const size_t lb = (size_t)batch * n * n * esize(dt), ab = (size_t)batch * n * m * esize(dt);
+    // Abar may be Bbar itself; Lbar may be L itself for trsm (L is consumed first).  Everything else
+    // must be disjoint.
+    if (m > 0) {
+        if (overlap(Abar, ab, L, lb) || overlap(Abar, ab, X, ab) || (Abar != Bbar && overlap(Abar, ab, Bbar, ab)) ||
+            overlap(Lbar, lb, X, ab) || overlap(Lbar, lb, Bbar, ab) || overlap(Lbar, lb, Abar, ab))
+            return LA_ERR_INVALID_ARG;
+    }
+    if (overlap(Lbar, lb, L, lb) && !(solve && Lbar == L))
+        return LA_ERR_INVALID_ARG;
+    hipStream_t st = (hipStream_t)stream;
+    if (solve)
+        return dt == LA_F32 ? trsm_backward_t<float>(lower, trans, rightside, alpha, batch, n, m, L, X, Bbar, Abar, Lbar, st)
+                            : trsm_backward_t<double>(lower, trans, rightside, alpha, batch, n, m, L, X, Bbar, Abar, Lbar, st);
+    return dt == LA_F32 ? trmm_backward_t<float>(lower, trans, rightside, alpha, batch, n, m, L, X, Bbar, Abar, Lbar, st)
+                        : trmm_backward_t<double>(lower, trans, rightside, alpha, batch, n, m, L, X, Bbar, Abar, Lbar, st);
+}
+
 extern "C" {
 
 la_status la_potrf_batched(la_dtype dt, int lower, int64_t batch, int n, const void *A, void *L, int32_t *info,
@@ -464,6 +566,35 @@ la_status la_trmm_batched(la_dtype dt, int lower, int trans, int rightside, doub
                           const void *L, const void *A, void *B, void *stream)
 {
     return tri_apply(false, dt, lower, trans, rightside, alpha, batch, n, m, L, A, B, stream);
+}
+
+la_status la_trsm_backward(la_dtype dt, int lower, int trans, int rightside, double alpha, int64_t batch, int n, int m,
+                           const void *L, const void *B, const void *Bbar, void *Abar, void *Lbar, void *stream)
+{
+    return tri_backward(true, dt, lower, trans, rightside, alpha, batch, n, m, L, B, Bbar, Abar, Lbar, stream);
+}
+
+la_status la_trmm_backward(la_dtype dt, int lower, int trans, int rightside, double alpha, int64_t batch, int n, int m,
+                           const void *L, const void *A, const void *Bbar, void *Abar, void *Lbar, void *stream)
+{
+    return tri_backward(false, dt, lower, trans, rightside, alpha, batch, n, m, L, A, Bbar, Abar, Lbar, stream);
+}
+
+la_status la_syrk_backward(la_dtype dt, int trans, double alpha, int64_t batch, int n, int k, const void *A,
+                           const void *Bbar, void *Abar, void *stream)
+{
+    if (bad_dtype(dt) || batch < 0 || n < 0 || k < 0 || n > MAX_N || k > MAX_N)
+        return LA_ERR_INVALID_ARG;
+    if (batch == 0 || n == 0 || k == 0)
+        return LA_OK;
+    if (!A || !Bbar || !Abar)
+        return LA_ERR_INVALID_ARG;
+    const size_t ab = (size_t)batch * n * k * esize(dt), bb = (size_t)batch * n * n * esize(dt);
+    if (overlap(Abar, ab, A, ab) || overlap(Abar, ab, Bbar, bb))
+        return LA_ERR_INVALID_ARG;
+    hipStream_t st = (hipStream_t)stream;
+    return dt == LA_F32 ? syrk_backward_t<float>(trans, alpha, batch, n, k, A, Bbar, Abar, st)
+                        : syrk_backward_t<double>(trans, alpha, batch, n, k, A, Bbar, Abar, st);
 }
 
 la_status la_syrk_batched(la_dtype dt, int trans, double alpha, int64_t batch, int n, int k, const void *A, void *B,

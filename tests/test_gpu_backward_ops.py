@@ -1,0 +1,172 @@
+"""Parity of la_trsm_backward, la_trmm_backward and la_syrk_backward (through the C ABI / ctypes
+binding) against the CPU oracle on the same seeded inputs: every (lower, trans, rightside) case,
+both element types, sizes on both sides of every dispatch threshold, the aliasing the paper
+allows, junk in the triangle that must not be read.  Tolerances as for the other operators:
+relative Frobenius error per matrix <= 1e-10 (fp64), <= 2e-4 (fp32); structural zeros exact.
+"""
+import itertools
+import sys
+
+import numpy as np
+import pytest
+
+import workloads
+
+pytestmark = pytest.mark.gpu
+
+TOL = {"f32": 2e-4, "f64": 1e-10}
+FLAGS = list(itertools.product([True, False], [False, True], [False, True]))  # lower, trans, rightside
+SHAPES = [(1, 1), (5, 3), (16, 16), (48, 64), (64, 20), (100, 130), (128, 48), (200, 33), (260, 96)]
+
+
+@pytest.fixture(scope="module")
+def la():
+    import torch
+
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    import paper_1710_08717_amd as la_mod
+
+    la_mod.load()  # raises if the HIP library is missing: there is no fallback
+    return la_mod
+
+
+@pytest.fixture(autouse=True)
+def _announce(request):
+    sys.stderr.write(f"\n[gpu-case] {request.node.nodeid}\n")
+    sys.stderr.flush()
+    yield
+
+
+def dev(a):
+    import torch
+
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+def host(t):
+    import torch
+
+    torch.cuda.synchronize()
+    return t.cpu().numpy()
+
+
+def npdt(dtype):
+    return workloads.np_dtype(dtype)
+
+
+def relerr(x, ref):
+    x = np.asarray(x, dtype=np.float64).reshape(x.shape[0], -1)
+    ref = np.asarray(ref, dtype=np.float64).reshape(ref.shape[0], -1)
+    num = np.linalg.norm(x - ref, axis=1)
+    den = np.maximum(np.linalg.norm(ref, axis=1), 1e-300)
+    return float(np.max(num / den)) if len(num) else 0.0
+
+
+def tri(seed, batch, n, lower, dtype):
+    rng = np.random.default_rng(seed)
+    T = rng.standard_normal((batch, n, n)) * (0.5 / np.sqrt(max(n, 1)))
+    T = np.tril(T) if lower else np.triu(T)
+    idx = np.arange(n)
+    T[:, idx, idx] = 1.0 + rng.uniform(0.0, 1.0, size=(batch, n))
+    return T.astype(npdt(dtype))
+
+
+def case(seed, n, m, lower, rightside, dtype, batch=3):
+    T = tri(seed, batch, n, lower, dtype)
+    rng = np.random.default_rng(seed + 1)
+    shape = (batch, m, n) if rightside else (batch, n, m)
+    X = rng.standard_normal(shape).astype(npdt(dtype))
+    G = rng.standard_normal(shape).astype(npdt(dtype))
+    other = np.triu_indices(n, 1) if lower else np.tril_indices(n, -1)
+    Tj = T.copy()
+    Tj[:, other[0], other[1]] = np.nan  # never read
+    return T, Tj, X, G, other
+
+
+@pytest.mark.parametrize("dtype", ["f64", "f32"])
+@pytest.mark.parametrize("lower,trans,rightside", FLAGS)
+@pytest.mark.parametrize("n,m", SHAPES)
+def test_trmm_backward_parity(la, orc, dtype, lower, trans, rightside, n, m):
+    T, Tj, A, G, other = case(1000 + n + m, n, m, lower, rightside, dtype)
+    alpha = -1.5 if (n + m) % 2 else 1.0
+    ra, rl = orc.trmm_backward(T, A, G, lower=lower, trans=trans, rightside=rightside, alpha=alpha)
+    ga, gl = la.trmm_backward(dev(Tj), dev(A), dev(G), lower=lower, trans=trans, rightside=rightside, alpha=alpha)
+    ga, gl = host(ga), host(gl)
+    assert relerr(ga, ra) <= TOL[dtype]
+    assert relerr(gl, rl) <= TOL[dtype]
+    assert np.all(gl[:, other[0], other[1]] == 0.0)
+    g = dev(G)  # Abar over Bbar
+    ga2, gl2 = la.trmm_backward(dev(Tj), dev(A), g, lower=lower, trans=trans, rightside=rightside, alpha=alpha, out_a=g)
+    assert np.array_equal(host(ga2), ga) and np.array_equal(host(gl2), gl)
+
+
+@pytest.mark.parametrize("dtype", ["f64", "f32"])
+@pytest.mark.parametrize("lower,trans,rightside", FLAGS)
+@pytest.mark.parametrize("n,m", SHAPES)
+def test_trsm_backward_parity(la, orc, dtype, lower, trans, rightside, n, m):
+    T, Tj, A, G, other = case(2000 + n + m, n, m, lower, rightside, dtype)
+    alpha = 0.5 if (n + m) % 2 else 1.0
+    B = orc.trsm(T, A, lower=lower, trans=trans, rightside=rightside, alpha=alpha).astype(npdt(dtype))
+    ra, rl = orc.trsm_backward(T, B, G, lower=lower, trans=trans, rightside=rightside, alpha=alpha)
+    ga, gl = la.trsm_backward(dev(Tj), dev(B), dev(G), lower=lower, trans=trans, rightside=rightside, alpha=alpha)
+    ga, gl = host(ga), host(gl)
+    assert relerr(ga, ra) <= TOL[dtype]
+    assert relerr(gl, rl) <= TOL[dtype]
+    assert np.all(gl[:, other[0], other[1]] == 0.0)
+    g, t = dev(G), dev(T)  # Abar over Bbar, Lbar over L (L holds zeros, not junk, in its other triangle here)
+    ga2, gl2 = la.trsm_backward(t, dev(B), g, lower=lower, trans=trans, rightside=rightside, alpha=alpha, out_a=g,
+                                out_l=t)
+    assert np.array_equal(host(ga2), ga) and np.array_equal(host(gl2), gl)
+
+
+@pytest.mark.parametrize("dtype", ["f64", "f32"])
+@pytest.mark.parametrize("trans", [False, True])
+@pytest.mark.parametrize("n,k", [(1, 1), (6, 3), (16, 64), (70, 64), (100, 37), (256, 128), (300, 50)])
+def test_syrk_backward_parity(la, orc, dtype, trans, n, k):
+    batch = 3
+    rng = np.random.default_rng(3000 + n + k)
+    A = rng.standard_normal((batch, k, n) if trans else (batch, n, k)).astype(npdt(dtype))
+    G = (rng.standard_normal((batch, n, n)) / np.sqrt(n)).astype(npdt(dtype))  # not symmetric
+    alpha = 0.7
+    ref = orc.syrk_backward(A, G, trans=trans, alpha=alpha)
+    out = host(la.syrk_backward(dev(A), dev(G), trans=trans, alpha=alpha))
+    assert relerr(out, ref) <= TOL[dtype]
+
+
+def test_backward_ops_gp_chain(la, orc):
+    """The chain the GP criterion of section 3.1 differentiates through: z = L^-1 y, then the trsm
+    rule gives ybar and Lbar; checked against the oracle with one right-hand side per matrix."""
+    batch, n = 8, 128
+    inp = workloads.make("C3", batch=batch)
+    L = orc.potrf(inp["A"]).astype(np.float32)
+    y = inp["y"].reshape(batch, n, 1).astype(np.float32)
+    z = orc.trsm(L, y).astype(np.float32)
+    zbar = z.copy()  # gradient of 1/2 z^T z
+    ra, rl = orc.trsm_backward(L, z, zbar)
+    ga, gl = la.trsm_backward(dev(L), dev(z), dev(zbar))
+    assert relerr(host(ga), ra) <= TOL["f32"] and relerr(host(gl), rl) <= TOL["f32"]
+
+
+def test_backward_ops_empty_and_errors(la):
+    import torch
+
+    for dt in (torch.float32, torch.float64):
+        L = torch.eye(4, dtype=dt, device="cuda").repeat(2, 1, 1)
+        e = torch.zeros((2, 4, 0), dtype=dt, device="cuda")
+        ab, lb = la.trsm_backward(L, e, e)
+        assert ab.shape == (2, 4, 0) and torch.all(lb == 0)
+        ab, lb = la.trmm_backward(L, e, e)
+        assert torch.all(lb == 0)
+        z = torch.zeros((0, 4, 4), dtype=dt, device="cuda")
+        la.trsm_backward(z, torch.zeros((0, 4, 2), dtype=dt, device="cuda"), torch.zeros((0, 4, 2), dtype=dt, device="cuda"))
+        la.syrk_backward(torch.zeros((2, 0, 3), dtype=dt, device="cuda"), torch.zeros((2, 0, 0), dtype=dt, device="cuda"))
+    L = torch.eye(4, dtype=torch.float64, device="cuda").repeat(2, 1, 1)
+    X = torch.ones((2, 4, 3), dtype=torch.float64, device="cuda")
+    G = torch.ones((2, 4, 3), dtype=torch.float64, device="cuda")
+    with pytest.raises(la.LaError):
+        la.trmm_backward(L, X, G, out_l=L)  # Lbar over L is allowed for trsm only
+    with pytest.raises(la.LaError):
+        la.trsm_backward(L, X, G, out_a=X)  # Abar over B
+    with pytest.raises(la.LaError):
+        la.syrk_backward(X, torch.ones((2, 4, 4), dtype=torch.float64, device="cuda"), out=X)
