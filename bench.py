@@ -61,6 +61,8 @@ def main():
     ap.add_argument("--steps", type=int, default=None)
     ap.add_argument("--warmup", type=int, default=None)
     ap.add_argument("--config", default="C2", choices=["C1", "C2", "C3", "C4", "C5"])
+    ap.add_argument("--with-backward-ops", action="store_true",
+                    help="C4 only: also run trmm / trsm / syrk backward on the step's operands")
     ap.add_argument("--dtype", default=None, choices=["f32", "f64"])
     ap.add_argument("--batch", type=int, default=None)
     ap.add_argument("--n", type=int, default=None)
@@ -90,6 +92,7 @@ def main():
     warmup = args.warmup if args.warmup is not None else {"C1": 20, "C2": 20, "C3": 10, "C4": 3, "C5": 1}[name]
     log(f"[bench] {name}: batch={batch} n={n} dtype={dtype} m={m} steps={steps} warmup={warmup}")
 
+    extra = bool(args.with_backward_ops) and name == "C4"
     # ---- resident inputs, several rotating buffer sets -----------------------------
     set_bytes = 4 * batch * n * n * s
     nsets = int(max(1, min(8, (1 << 31) // max(set_bytes, 1)))) if name != "C5" else 1
@@ -110,6 +113,12 @@ def main():
             d["loss"] = torch.empty(batch, dtype=A0.dtype, device="cuda")
         if name == "C1":
             d["sld"] = torch.empty(batch, dtype=A0.dtype, device="cuda")
+        if extra:
+            d["Ybar"] = torch.from_numpy(w["rhs"][:, ::-1, :].copy()).cuda()  # any fixed upstream gradient
+            for k_ in ("Xbar", "Rbar", "Sbar"):
+                d[k_] = torch.empty_like(d["rhs"])
+            d["Lb1"] = torch.empty_like(A0)
+            d["Lb2"] = torch.empty_like(A0)
         sets.append(d)
     torch.cuda.synchronize()
 
@@ -139,6 +148,12 @@ def main():
         elif name == "C4":
             call("trsm", lambda: la.trsm(d["L"], d["rhs"], out=d["X"]), timed)
             call("trmm", lambda: la.trmm(d["L"], d["X"], out=d["Y"]), timed)
+            if extra:
+                call("trmm_backward", lambda: la.trmm_backward(d["L"], d["X"], d["Ybar"], out_a=d["Xbar"], out_l=d["Lb1"]),
+                     timed)
+                call("trsm_backward", lambda: la.trsm_backward(d["L"], d["X"], d["Xbar"], out_a=d["Rbar"], out_l=d["Lb2"]),
+                     timed)
+                call("syrk_backward", lambda: la.syrk_backward(d["rhs"], d["G"], out=d["Sbar"]), timed)
         elif name == "C5":
             call("trsm", lambda: la.trsm(d["L"], d["rhs"], out=d["X"]), timed)
         call("backward", lambda: la.potrf_backward(d["L"], d["G"], out=d["Abar"]), timed)
@@ -168,6 +183,8 @@ def main():
         torch.cuda.synchronize()
 
     fm = flops_model(name, n, m)
+    if extra:  # product with the triangle + kept triangle of an n x n outer product; two n x n x m products
+        fm.update({"trmm_backward": 2.0 * n * n * m, "trsm_backward": 2.0 * n * n * m, "syrk_backward": 4.0 * n * n * m})
     total_flops = batch * sum(fm.values())
     mats_per_s = batch / (ms_per_step * 1e-3)
     gflops = total_flops / (ms_per_step * 1e-3) / 1e9
@@ -222,6 +239,10 @@ def main():
                     X = oracle.trsm(Lr, Rs)
                     if name == "C4":
                         oracle.trmm(Lr, X)
+                    if extra:
+                        xb, _ = oracle.trmm_backward(Lr, X, Rs[:, ::-1, :])
+                        oracle.trsm_backward(Lr, X, xb)
+                        oracle.syrk_backward(Rs, Gs)
                 passes += 1
                 dt_cpu = time.perf_counter() - t0
                 if dt_cpu >= 10.0 or passes >= 200:
