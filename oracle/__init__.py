@@ -44,6 +44,9 @@ def _load():
         lib.orc_trmm_backward.argtypes = [i32, i32, i32, f64, i64, i32, i32, dp, dp, dp, dp, dp]
         lib.orc_trsm_backward.argtypes = [i32, i32, i32, f64, i64, i32, i32, dp, dp, dp, dp, dp]
         lib.orc_syrk_backward.argtypes = [i32, f64, i64, i32, i32, dp, dp, dp]
+        lib.orc_gemm2_backward.argtypes = [i32, i32, f64, i64, i32, i32, i32, dp, dp, dp, dp, dp]
+        lib.orc_potri.argtypes = [i32, i64, i32, dp, dp]
+        lib.orc_potri_backward.argtypes = [i32, i64, i32, dp, dp, dp, dp]
         lib.orc_sumlogdiag.argtypes = [i64, i32, dp, dp]
         lib.orc_gemm2.argtypes = [i32, i32, f64, i64, i32, i32, i32, dp, dp, dp]
         lib.orc_gp_glue.argtypes = [i64, i32, dp, dp, dp, dp, dp, dp]
@@ -194,6 +197,35 @@ def gemm2(A, B, ta=False, tb=False, alpha=1.0):
     b = _batch_of(A, 2)
     out = np.empty(A.shape[:-2] + (m, n), dtype=np.float64)
     _check(_load().orc_gemm2(int(ta), int(tb), float(alpha), b, m, n, k, _p(A), _p(B), _p(out)), "gemm2")
+    return out
+
+
+def gemm2_backward(A, B, Cbar, ta=False, tb=False, alpha=1.0):
+    """(Abar, Bbar) of C = alpha t_a(A) t_b(B), each in the shape of its operand."""
+    A, B, Cbar = _f64(A), _f64(B), _f64(Cbar)
+    m, k = (A.shape[-1], A.shape[-2]) if ta else (A.shape[-2], A.shape[-1])
+    n = B.shape[-2] if tb else B.shape[-1]
+    assert Cbar.shape[-2:] == (m, n)
+    Abar, Bbar = np.empty_like(A), np.empty_like(B)
+    _check(_load().orc_gemm2_backward(int(ta), int(tb), float(alpha), _batch_of(A, 2), m, n, k, _p(A), _p(B), _p(Cbar),
+                                      _p(Abar), _p(Bbar)), "gemm2_backward")
+    return Abar, Bbar
+
+
+def potri(L, lower=True):
+    """A^-1 from the Cholesky factor of A."""
+    L = _f64(L)
+    n = L.shape[-1]
+    out = np.empty_like(L)
+    _check(_load().orc_potri(int(lower), _batch_of(L, 2), n, _p(L), _p(out)), "potri")
+    return out
+
+
+def potri_backward(L, B, Bbar, lower=True):
+    L, B, Bbar = _f64(L), _f64(B), _f64(Bbar)
+    n = L.shape[-1]
+    out = np.empty_like(L)
+    _check(_load().orc_potri_backward(int(lower), _batch_of(L, 2), n, _p(L), _p(B), _p(Bbar), _p(out)), "potri_backward")
     return out
 
 

@@ -473,6 +473,134 @@ int orc_gemm2(int ta, int tb, double alpha, int64_t batch, int m, int n, int k, 
 }
 
 /* ------------------------------------------------------------------------- */
+/* gemm2 backward (section 4.2, "gemm2"): for C = alpha t_a(A) t_b(B),
+ *   Abar = alpha Cbar t_b(B)^T      (ta == 0)     or  alpha t_b(B) Cbar^T   (ta != 0),
+ *   Bbar = alpha t_a(A)^T Cbar      (tb == 0)     or  alpha Cbar^T t_a(A)   (tb != 0),
+ * each in the storage shape of its operand, written as sums over the definition. */
+int orc_gemm2_backward(int ta, int tb, double alpha, int64_t batch, int m, int n, int k, const double *A,
+                       const double *B, const double *Cbar, double *Abar, double *Bbar)
+{
+    if (batch < 0 || m < 0 || n < 0 || k < 0)
+        return ORC_ERR_INVALID_ARG;
+    if (batch == 0)
+        return ORC_OK;
+    size_t sa = (size_t)m * k, sb = (size_t)k * n, sc = (size_t)m * n;
+    if ((sa && (!A || !Abar)) || (sb && (!B || !Bbar)) || (sc && !Cbar))
+        return ORC_ERR_INVALID_ARG;
+    for (int64_t b = 0; b < batch; ++b) {
+        const double *Ab = A + b * sa, *Bb = B + b * sb, *G = Cbar + b * sc;
+        double *Ao = Abar + b * sa, *Bo = Bbar + b * sb;
+        /* d phi / d t_a(A)(i,p) = alpha sum_j Cbar(i,j) t_b(B)(p,j) */
+        for (int i = 0; i < m; ++i)
+            for (int p = 0; p < k; ++p) {
+                double s = 0.0;
+                for (int j = 0; j < n; ++j)
+                    s += G[(size_t)i * n + j] * (tb ? Bb[(size_t)j * k + p] : Bb[(size_t)p * n + j]);
+                if (ta)
+                    Ao[(size_t)p * m + i] = alpha * s;
+                else
+                    Ao[(size_t)i * k + p] = alpha * s;
+            }
+        /* d phi / d t_b(B)(p,j) = alpha sum_i t_a(A)(i,p) Cbar(i,j) */
+        for (int p = 0; p < k; ++p)
+            for (int j = 0; j < n; ++j) {
+                double s = 0.0;
+                for (int i = 0; i < m; ++i)
+                    s += (ta ? Ab[(size_t)p * m + i] : Ab[(size_t)i * k + p]) * G[(size_t)i * n + j];
+                if (tb)
+                    Bo[(size_t)j * k + p] = alpha * s;
+                else
+                    Bo[(size_t)p * n + j] = alpha * s;
+            }
+    }
+    return ORC_OK;
+}
+
+/* ------------------------------------------------------------------------- */
+/* potri (section 4.2, "potri"): B = A^-1 from the Cholesky factor of A.
+ *   lower != 0: A = L L^T, B = L^-T L^-1;   lower == 0: A = R^T R, B = R^-1 R^-T.
+ * Column j of B solves A b = e_j: two substitutions with the factor per column.
+ * Both triangles of B are written. */
+int orc_potri(int lower, int64_t batch, int n, const double *L, double *B)
+{
+    if (batch < 0 || n < 0)
+        return ORC_ERR_INVALID_ARG;
+    if (batch == 0 || n == 0)
+        return ORC_OK;
+    if (!L || !B)
+        return ORC_ERR_INVALID_ARG;
+    size_t nn = (size_t)n * n;
+    int fail = 0;
+#pragma omp parallel for schedule(dynamic)
+    for (int64_t b = 0; b < batch; ++b) {
+        double *E = (double *)malloc(nn * sizeof(double));
+        if (!E) {
+            fail = 1;
+            continue;
+        }
+        for (size_t e = 0; e < nn; ++e)
+            E[e] = 0.0;
+        for (int i = 0; i < n; ++i)
+            E[(size_t)i * n + i] = 1.0;
+        /* A = F F^T with F = L (lower) or F = R^T (upper, i.e. t(R) with trans):
+         * F Y = I, then F^T X = Y */
+        trsm_one(lower, lower ? 0 : 1, 0, 1.0, n, n, L + b * nn, E, E);
+        trsm_one(lower, lower ? 1 : 0, 0, 1.0, n, n, L + b * nn, E, B + b * nn);
+        free(E);
+    }
+    return fail ? ORC_ERR_INVALID_ARG : ORC_OK;
+}
+
+/* potri backward (section 4.2, "potri"; appendix "potri"; Bbar need not be symmetric):
+ *   lower != 0:  Lbar = -2 tril( B sym(Bbar) L^-T )
+ *   lower == 0:  Rbar = -2 triu( R^-T sym(Bbar) B )
+ * with B = A^-1 the forward output.  The other triangle of the result is zero. */
+int orc_potri_backward(int lower, int64_t batch, int n, const double *L, const double *B, const double *Bbar,
+                       double *Lbar)
+{
+    if (batch < 0 || n < 0)
+        return ORC_ERR_INVALID_ARG;
+    if (batch == 0 || n == 0)
+        return ORC_OK;
+    if (!L || !B || !Bbar || !Lbar)
+        return ORC_ERR_INVALID_ARG;
+    size_t nn = (size_t)n * n;
+    int fail = 0;
+#pragma omp parallel for schedule(dynamic)
+    for (int64_t b = 0; b < batch; ++b) {
+        double *M = (double *)malloc(nn * sizeof(double));
+        if (!M) {
+            fail = 1;
+            continue;
+        }
+        const double *Bb = B + b * nn, *G = Bbar + b * nn;
+        for (int i = 0; i < n; ++i)
+            for (int j = 0; j < n; ++j) {
+                double s = 0.0;
+                if (lower) /* 2 B sym(Bbar) */
+                    for (int p = 0; p < n; ++p)
+                        s += Bb[(size_t)i * n + p] * (G[(size_t)p * n + j] + G[(size_t)j * n + p]);
+                else /* 2 sym(Bbar) B */
+                    for (int p = 0; p < n; ++p)
+                        s += (G[(size_t)i * n + p] + G[(size_t)p * n + i]) * Bb[(size_t)p * n + j];
+                M[(size_t)i * n + j] = s;
+            }
+        /* lower: X = M L^-T (right solve with the transpose); upper: X = R^-T M (left solve) */
+        double *X = Lbar + b * nn;
+        if (lower)
+            trsm_one(1, 1, 1, -1.0, n, n, L + b * nn, M, X);
+        else
+            trsm_one(0, 1, 0, -1.0, n, n, L + b * nn, M, X);
+        for (int i = 0; i < n; ++i)
+            for (int j = 0; j < n; ++j)
+                if (lower ? (i < j) : (i > j))
+                    X[(size_t)i * n + j] = 0.0;
+        free(M);
+    }
+    return fail ? ORC_ERR_INVALID_ARG : ORC_OK;
+}
+
+/* ------------------------------------------------------------------------- */
 /* log|L| = sum_i log l_ii (section 3.1, the identity below the GP code).
  * Plain log: a non-positive diagonal gives NaN / -inf as IEEE says. */
 int orc_sumlogdiag(int64_t batch, int n, const double *L, double *out)

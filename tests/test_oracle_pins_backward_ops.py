@@ -197,3 +197,90 @@ def test_backward_ops_empty(orc):
     a, l = orc.trsm_backward(z, np.zeros((0, 3, 2)), np.zeros((0, 3, 2)))
     assert a.shape == (0, 3, 2) and l.shape == (0, 3, 3)
     assert orc.syrk_backward(np.zeros((2, 0, 4)), np.zeros((2, 0, 0))).shape == (2, 0, 4)
+
+
+# ----------------------------------------------------------------------------
+# gemm2 backward, potri forward / backward
+# ----------------------------------------------------------------------------
+@pytest.mark.parametrize("ta", [False, True])
+@pytest.mark.parametrize("tb", [False, True])
+@pytest.mark.parametrize("m,n,k", [(1, 1, 1), (3, 5, 4), (6, 2, 7)])
+def test_gemm2_backward(orc, ta, tb, m, n, k):
+    rng = np.random.default_rng(600 + m + 10 * n + 100 * k)
+    A = rng.standard_normal((k, m) if ta else (m, k))
+    B = rng.standard_normal((n, k) if tb else (k, n))
+    Cbar = rng.standard_normal((m, n))
+    alpha = 1.3
+    fwd = lambda a, b: alpha * (a.T if ta else a) @ (b.T if tb else b)
+    h = 1e-6
+    gA, gB = np.zeros_like(A), np.zeros_like(B)
+    for idx in np.ndindex(*A.shape):
+        Ap, Am = A.copy(), A.copy()
+        Ap[idx] += h
+        Am[idx] -= h
+        gA[idx] = (np.sum(Cbar * fwd(Ap, B)) - np.sum(Cbar * fwd(Am, B))) / (2 * h)
+    for idx in np.ndindex(*B.shape):
+        Bp, Bm = B.copy(), B.copy()
+        Bp[idx] += h
+        Bm[idx] -= h
+        gB[idx] = (np.sum(Cbar * fwd(A, Bp)) - np.sum(Cbar * fwd(A, Bm))) / (2 * h)
+    Abar, Bbar = orc.gemm2_backward(A, B, Cbar, ta=ta, tb=tb, alpha=alpha)
+    assert relerr(Abar, gA) < 1e-7 and relerr(Bbar, gB) < 1e-7
+    # the printed rule: each gradient is itself a gemm2 of Cbar with the other operand
+    tB = B.T if tb else B
+    tA = A.T if ta else A
+    cA = alpha * (tB @ Cbar.T if ta else Cbar @ tB.T)
+    cB = alpha * (Cbar.T @ tA if tb else tA.T @ Cbar)
+    assert relerr(Abar, cA) < 1e-13 and relerr(Bbar, cB) < 1e-13
+
+
+@pytest.mark.parametrize("lower", [True, False])
+@pytest.mark.parametrize("n", [1, 2, 5, 12, 40])
+def test_potri_is_the_inverse(orc, lower, n):
+    rng = np.random.default_rng(700 + n)
+    X = rng.standard_normal((n, 2 * n))
+    A = X @ X.T / (2 * n) + np.eye(n)
+    F = np.linalg.cholesky(A)
+    F = F if lower else F.T.copy()
+    junk = F.copy()
+    other = np.triu_indices(n, 1) if lower else np.tril_indices(n, -1)
+    junk[other] = np.nan  # the other triangle of the factor is never read
+    B = orc.potri(junk, lower=lower)
+    assert relerr(B @ A, np.eye(n)) < 1e-12
+    assert relerr(B, B.T) < 1e-13
+    assert relerr(B, np.linalg.inv(A)) < 1e-12
+
+
+def test_potri_closed_form(orc):
+    # A = [[4, 2], [2, 5]]: L = [[2, 0], [1, 2]], A^-1 = 1/16 [[5, -2], [-2, 4]]
+    L = np.array([[2.0, 0.0], [1.0, 2.0]])
+    assert np.allclose(orc.potri(L), np.array([[5.0, -2.0], [-2.0, 4.0]]) / 16.0, rtol=0, atol=1e-15)
+    assert np.allclose(orc.potri(np.array([[3.0]])), [[1.0 / 9.0]])
+
+
+@pytest.mark.parametrize("lower", [True, False])
+@pytest.mark.parametrize("n", [1, 3, 6])
+def test_potri_backward_finite_differences(orc, lower, n):
+    rng = np.random.default_rng(800 + n)
+    F = rand_tri(rng, n, lower)
+    Bbar = rng.standard_normal((n, n))  # not symmetric
+    inv_of = (lambda f: np.linalg.inv(f @ f.T)) if lower else (lambda f: np.linalg.inv(f.T @ f))
+    g = np.zeros_like(F)
+    h = 1e-6
+    for i in range(n):
+        for j in range(n):
+            if (i >= j) if lower else (i <= j):
+                Fp, Fm = F.copy(), F.copy()
+                Fp[i, j] += h
+                Fm[i, j] -= h
+                g[i, j] = (np.sum(Bbar * inv_of(Fp)) - np.sum(Bbar * inv_of(Fm))) / (2 * h)
+    B = inv_of(F)
+    Lbar = orc.potri_backward(F, B, Bbar, lower=lower)
+    assert relerr(Lbar, g) < 1e-6
+    other = np.triu_indices(n, 1) if lower else np.tril_indices(n, -1)
+    assert np.all(Lbar[other] == 0.0)
+    # the printed expressions with dense inverses
+    S = 0.5 * (Bbar + Bbar.T)
+    Fi = np.linalg.inv(F)
+    closed = -2 * np.tril(B @ S @ Fi.T) if lower else -2 * np.triu(Fi.T @ S @ B)
+    assert relerr(Lbar, closed) < 1e-12
