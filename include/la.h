@@ -131,6 +131,29 @@ la_status la_syrk_batched(la_dtype dt, int trans, double alpha, int64_t batch, i
 la_status la_gemm2_batched(la_dtype dt, int ta, int tb, double alpha, int64_t batch, int m, int n, int k,
                            const void *A, const void *B, void *C, void *stream);
 
+/* gemm2 backward (section 4.2 "gemm2", backward): for C = alpha t_a(A) t_b(B),
+ *   Abar = alpha Cbar t_b(B)^T  (ta == 0)  or  alpha t_b(B) Cbar^T  (ta != 0),
+ *   Bbar = alpha t_a(A)^T Cbar  (tb == 0)  or  alpha Cbar^T t_a(A)  (tb != 0),
+ * each in the storage shape of its operand (see la_gemm2_batched); Cbar: [batch, m, n].
+ * Abar and Bbar must not overlap each other or any input. */
+la_status la_gemm2_backward(la_dtype dt, int ta, int tb, double alpha, int64_t batch, int m, int n, int k,
+                            const void *A, const void *B, const void *Cbar, void *Abar, void *Bbar,
+                            void *stream);
+
+/* potri (section 4.2 "potri"): B = A^{-1} from the Cholesky factor of A,
+ *   A = L L^T (lower != 0)  or  A = R^T R (lower == 0).
+ * L, B: [batch, n, n]; only the named triangle of the factor is read; B is written in full and is
+ * exactly symmetric.  B may be the same buffer as L ("B can overwrite L"). */
+la_status la_potri(la_dtype dt, int lower, int64_t batch, int n, const void *L, void *B, void *stream);
+
+/* potri backward (section 4.2 "potri", backward; appendix "potri"; Bbar need not be symmetric):
+ *   Lbar = -2 tril(B sym(Bbar) L^{-T})   (lower != 0)
+ *   Rbar = -2 triu(R^{-T} sym(Bbar) B)   (lower == 0)
+ * B is the forward output A^{-1}.  All operands [batch, n, n]; Lbar is written in full (zeros in the
+ * other triangle) and must not overlap any input. */
+la_status la_potri_backward(la_dtype dt, int lower, int64_t batch, int n, const void *L, const void *B,
+                            const void *Bbar, void *Lbar, void *stream);
+
 /* log|L| = sum_i log l_ii (section 3.1, identity below the GP criterion code).
  * L: [batch, n, n]; out: [batch] of dt.  Plain log, no abs: a non-positive
  * diagonal gives NaN / -inf. n == 0 gives 0. */

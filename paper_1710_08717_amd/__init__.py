@@ -9,10 +9,13 @@ library is missing, importing the binding raises.
 from .binding import (  # noqa: F401
     LaError,
     gemm2,
+    gemm2_backward,
     gp_glue,
     lib_path,
     load,
     potrf,
+    potri,
+    potri_backward,
     potrf_backward,
     sumlogdiag,
     syrk,
@@ -23,5 +26,5 @@ from .binding import (  # noqa: F401
     trsm_backward,
 )
 
-__all__ = ["potrf", "potrf_backward", "trsm", "trmm", "syrk", "trsm_backward", "trmm_backward", "syrk_backward", "sumlogdiag",
+__all__ = ["potrf", "potrf_backward", "trsm", "trmm", "syrk", "trsm_backward", "trmm_backward", "syrk_backward", "gemm2_backward", "potri", "potri_backward", "sumlogdiag",
            "gp_glue", "gemm2", "load", "lib_path", "LaError"]

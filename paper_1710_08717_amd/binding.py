@@ -17,7 +17,7 @@ _lib = None
 SYMBOLS = [
     "la_potrf_batched", "la_potrf_backward", "la_trsm_batched", "la_trmm_batched", "la_syrk_batched",
     "la_sumlogdiag", "la_gp_glue", "la_gemm2_batched", "la_trsm_backward", "la_trmm_backward", "la_syrk_backward",
-    "la_last_error", "la_version",
+    "la_gemm2_backward", "la_potri", "la_potri_backward", "la_last_error", "la_version",
 ]
 
 
@@ -53,7 +53,11 @@ def load():
     lib.la_trsm_backward.argtypes = [i32, i32, i32, i32, f64, i64, i32, i32, vp, vp, vp, vp, vp, vp]
     lib.la_trmm_backward.argtypes = [i32, i32, i32, i32, f64, i64, i32, i32, vp, vp, vp, vp, vp, vp]
     lib.la_syrk_backward.argtypes = [i32, i32, f64, i64, i32, i32, vp, vp, vp, vp]
-    for name in ("la_trsm_backward", "la_trmm_backward", "la_syrk_backward"):
+    lib.la_gemm2_backward.argtypes = [i32, i32, i32, f64, i64, i32, i32, i32, vp, vp, vp, vp, vp, vp]
+    lib.la_potri.argtypes = [i32, i32, i64, i32, vp, vp, vp]
+    lib.la_potri_backward.argtypes = [i32, i32, i64, i32, vp, vp, vp, vp, vp]
+    for name in ("la_trsm_backward", "la_trmm_backward", "la_syrk_backward", "la_gemm2_backward", "la_potri",
+                 "la_potri_backward"):
         getattr(lib, name).restype = i32
     lib.la_last_error.restype = ctypes.c_char_p
     lib.la_version.restype = i32
@@ -199,6 +203,46 @@ def syrk_backward(A, Bbar, trans=False, alpha=1.0, out=None):
         _check(load().la_syrk_backward(_dt(A), int(trans), float(alpha), _batch(A), n, k, _ptr(A), _ptr(Bbar),
                                        _ptr(Abar), _stream(A)), "la_syrk_backward")
     return Abar
+
+
+def gemm2_backward(A, B, Cbar, ta=False, tb=False, alpha=1.0):
+    """la_gemm2_backward: (Abar, Bbar) of C = alpha t_a(A) t_b(B)."""
+    _chk(A, B)
+    _chk(A, Cbar)
+    m, k = (A.shape[-1], A.shape[-2]) if ta else (A.shape[-2], A.shape[-1])
+    n = B.shape[-2] if tb else B.shape[-1]
+    assert Cbar.shape[-2:] == (m, n) and _batch(A) == _batch(B) == _batch(Cbar)
+    Abar, Bbar = torch.empty_like(A), torch.empty_like(B)
+    with torch.cuda.device(A.device):
+        _check(load().la_gemm2_backward(_dt(A), int(ta), int(tb), float(alpha), _batch(A), m, n, k, _ptr(A), _ptr(B),
+                                        _ptr(Cbar), _ptr(Abar), _ptr(Bbar), _stream(A)), "la_gemm2_backward")
+    return Abar, Bbar
+
+
+def potri(L, lower=True, out=None):
+    """la_potri: A^-1 from the Cholesky factor of A.  ``out`` may be ``L`` itself."""
+    _chk(L)
+    n = L.shape[-1]
+    assert L.shape[-2] == n
+    B = torch.empty_like(L) if out is None else out
+    _chk(L, B)
+    with torch.cuda.device(L.device):
+        _check(load().la_potri(_dt(L), int(lower), _batch(L), n, _ptr(L), _ptr(B), _stream(L)), "la_potri")
+    return B
+
+
+def potri_backward(L, B, Bbar, lower=True, out=None):
+    """la_potri_backward: gradient of the factor from B = A^-1 and Bbar."""
+    _chk(L, B)
+    _chk(L, Bbar)
+    n = L.shape[-1]
+    assert L.shape == B.shape == Bbar.shape
+    Lbar = torch.empty_like(L) if out is None else out
+    _chk(L, Lbar)
+    with torch.cuda.device(L.device):
+        _check(load().la_potri_backward(_dt(L), int(lower), _batch(L), n, _ptr(L), _ptr(B), _ptr(Bbar), _ptr(Lbar),
+                                        _stream(L)), "la_potri_backward")
+    return Lbar
 
 
 def syrk(A, trans=False, alpha=1.0, out=None):

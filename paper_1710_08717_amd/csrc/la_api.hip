@@ -468,6 +468,63 @@ static la_status syrk_backward_t(int trans, double alpha, int64_t batch, int n, 
     return launch_gemm<T>(Av, G.t(), Ov, batch, k, n, n, (T)alpha, T(1), o, st);
 }
 
+// potri (section 4.2 "potri"): A^-1 = Lam^-T Lam^-1 for A = Lam Lam^T (Lam = L, or R^T for an upper
+// factor: the same symmetric matrix either way).  Explicit inverse of the factor, then the lower
+// tiles of Li^T Li (K range from max(i, j) on), mirrored.
+template <typename T>
+static la_status potri_t(int lower, int64_t batch, int n, const void *L, void *B, hipStream_t st)
+{
+    View<const T> Lam = tri_view<const T>((const T *)L, n, lower);
+    View<T> sc[2];
+    LA_TRY(scratch_views<T>(batch, n, 2, sc));
+    LA_TRY(inverse_build<T>(Lam, sc[0], sc[1], batch, n, n, st));
+    View<T> Bv{(T *)B, (int64_t)n * n, n, 1};
+    GemmOpts o;
+    o.triA = 2;
+    o.triB = 1;
+    o.maskC = 1;
+    LA_TRY(launch_gemm<T>(cv(sc[0]).t(), cv(sc[0]), Bv, batch, n, n, n, T(1), T(0), o, st));
+    return launch_mirror_lower<T>(Bv, batch, n, st);
+}
+
+// potri backward (section 4.2 "potri"; appendix "potri"):
+//   Lbar = -2 tril(B sym(Bbar) L^-T) = -tril((B Bbar + B Bbar^T) L^-T)      (lower factor)
+//   Rbar = -2 triu(R^-T sym(Bbar) B) = -triu(R^-T (Bbar B + Bbar^T B))      (upper factor)
+// The two products accumulate in Lbar, the solve runs in place there, the other triangle is cleared.
+template <typename T>
+static la_status potri_backward_t(int lower, int64_t batch, int n, const void *L, const void *B, const void *Bbar,
+                                  void *Lbar, hipStream_t st)
+{
+    const int64_t nn = (int64_t)n * n;
+    View<const T> Bv{(const T *)B, nn, n, 1}, G{(const T *)Bbar, nn, n, 1};
+    View<T> X{(T *)Lbar, nn, n, 1};
+    GemmOpts o;
+    if (lower) {
+        LA_TRY(launch_gemm<T>(Bv, G, X, batch, n, n, n, T(1), T(0), o, st));
+        LA_TRY(launch_gemm<T>(Bv, G.t(), X, batch, n, n, n, T(1), T(1), o, st));
+        LA_TRY(tri_apply_t<T>(true, 1, 1, 1, -1.0, batch, n, n, L, Lbar, Lbar, st));
+        return launch_zero_strict_upper<T>(X, batch, n, st);
+    }
+    LA_TRY(launch_gemm<T>(G, Bv, X, batch, n, n, n, T(1), T(0), o, st));
+    LA_TRY(launch_gemm<T>(G.t(), Bv, X, batch, n, n, n, T(1), T(1), o, st));
+    LA_TRY(tri_apply_t<T>(true, 0, 1, 0, -1.0, batch, n, n, L, Lbar, Lbar, st));
+    return launch_zero_strict_upper<T>(X.t(), batch, n, st);
+}
+
+// gemm2 backward (section 4.2 "gemm2"): each gradient is a gemm2 of Cbar with the other operand.
+template <typename T>
+static la_status gemm2_backward_t(int ta, int tb, double alpha, int64_t batch, int m, int n, int k, const void *A,
+                                  const void *B, const void *Cbar, void *Abar, void *Bbar, hipStream_t st)
+{
+    if (!ta)  // Abar (m x k) = alpha Cbar t_b(B)^T
+        LA_TRY(gemm2_t<T>(0, !tb, alpha, batch, m, k, n, Cbar, B, Abar, st));
+    else  // Abar (k x m) = alpha t_b(B) Cbar^T
+        LA_TRY(gemm2_t<T>(tb, 1, alpha, batch, k, m, n, B, Cbar, Abar, st));
+    if (!tb)  // Bbar (k x n) = alpha t_a(A)^T Cbar
+        return gemm2_t<T>(!ta, 0, alpha, batch, k, n, m, A, Cbar, Bbar, st);
+    return gemm2_t<T>(1, ta, alpha, batch, n, k, m, Cbar, A, Bbar, st);  // Bbar (n x k) = alpha Cbar^T t_a(A)
+}
+
 static la_status tri_backward(bool solve, la_dtype dt, int lower, int trans, int rightside, double alpha, int64_t batch,
                               int n, int m, const void *L, const void *X, const void *Bbar, void *Abar, void *Lbar,
                               void *stream)
@@ -578,6 +635,64 @@ la_status la_trmm_backward(la_dtype dt, int lower, int trans, int rightside, dou
                            const void *L, const void *A, const void *Bbar, void *Abar, void *Lbar, void *stream)
 {
     return tri_backward(false, dt, lower, trans, rightside, alpha, batch, n, m, L, A, Bbar, Abar, Lbar, stream);
+}
+
+la_status la_gemm2_backward(la_dtype dt, int ta, int tb, double alpha, int64_t batch, int m, int n, int k,
+                            const void *A, const void *B, const void *Cbar, void *Abar, void *Bbar, void *stream)
+{
+    if (bad_dtype(dt) || batch < 0 || m < 0 || n < 0 || k < 0 || m > MAX_N || n > MAX_N || k > MAX_N)
+        return LA_ERR_INVALID_ARG;
+    if (batch == 0)
+        return LA_OK;
+    const size_t sa = (size_t)batch * m * k * esize(dt), sb = (size_t)batch * k * n * esize(dt),
+                 sc = (size_t)batch * m * n * esize(dt);
+    if ((sa && (!A || !Abar)) || (sb && (!B || !Bbar)) || (sc && !Cbar))
+        return LA_ERR_INVALID_ARG;
+    if (overlap(Abar, sa, A, sa) || overlap(Abar, sa, B, sb) || overlap(Abar, sa, Cbar, sc) || overlap(Bbar, sb, A, sa) ||
+        overlap(Bbar, sb, B, sb) || overlap(Bbar, sb, Cbar, sc) || overlap(Abar, sa, Bbar, sb))
+        return LA_ERR_INVALID_ARG;
+    hipStream_t st = (hipStream_t)stream;
+    if (m == 0 || n == 0 || k == 0) {  // empty products: the gradients that exist are zero
+        if (sa)
+            LA_TRY(launch_fill_i32((int32_t *)Abar, (int64_t)(sa / 4), 0, st));
+        if (sb)
+            LA_TRY(launch_fill_i32((int32_t *)Bbar, (int64_t)(sb / 4), 0, st));
+        return LA_OK;
+    }
+    return dt == LA_F32 ? gemm2_backward_t<float>(ta, tb, alpha, batch, m, n, k, A, B, Cbar, Abar, Bbar, st)
+                        : gemm2_backward_t<double>(ta, tb, alpha, batch, m, n, k, A, B, Cbar, Abar, Bbar, st);
+}
+
+la_status la_potri(la_dtype dt, int lower, int64_t batch, int n, const void *L, void *B, void *stream)
+{
+    if (bad_dtype(dt) || batch < 0 || n < 0 || n > MAX_N)
+        return LA_ERR_INVALID_ARG;
+    if (batch == 0 || n == 0)
+        return LA_OK;
+    if (!L || !B)
+        return LA_ERR_INVALID_ARG;
+    const size_t nb = (size_t)batch * n * n * esize(dt);
+    if (L != B && overlap(L, nb, B, nb))
+        return LA_ERR_INVALID_ARG;
+    hipStream_t st = (hipStream_t)stream;
+    return dt == LA_F32 ? potri_t<float>(lower, batch, n, L, B, st) : potri_t<double>(lower, batch, n, L, B, st);
+}
+
+la_status la_potri_backward(la_dtype dt, int lower, int64_t batch, int n, const void *L, const void *B,
+                            const void *Bbar, void *Lbar, void *stream)
+{
+    if (bad_dtype(dt) || batch < 0 || n < 0 || n > MAX_N)
+        return LA_ERR_INVALID_ARG;
+    if (batch == 0 || n == 0)
+        return LA_OK;
+    if (!L || !B || !Bbar || !Lbar)
+        return LA_ERR_INVALID_ARG;
+    const size_t nb = (size_t)batch * n * n * esize(dt);
+    if (overlap(Lbar, nb, L, nb) || overlap(Lbar, nb, B, nb) || overlap(Lbar, nb, Bbar, nb))
+        return LA_ERR_INVALID_ARG;
+    hipStream_t st = (hipStream_t)stream;
+    return dt == LA_F32 ? potri_backward_t<float>(lower, batch, n, L, B, Bbar, Lbar, st)
+                        : potri_backward_t<double>(lower, batch, n, L, B, Bbar, Lbar, st);
 }
 
 la_status la_syrk_backward(la_dtype dt, int trans, double alpha, int64_t batch, int n, int k, const void *A,

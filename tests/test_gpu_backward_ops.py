@@ -170,3 +170,87 @@ def test_backward_ops_empty_and_errors(la):
         la.trsm_backward(L, X, G, out_a=X)  # Abar over B
     with pytest.raises(la.LaError):
         la.syrk_backward(X, torch.ones((2, 4, 4), dtype=torch.float64, device="cuda"), out=X)
+
+
+# ----------------------------------------------------------------------------
+# gemm2 backward, potri forward / backward
+# ----------------------------------------------------------------------------
+@pytest.mark.parametrize("dtype", ["f64", "f32"])
+@pytest.mark.parametrize("ta", [False, True])
+@pytest.mark.parametrize("tb", [False, True])
+@pytest.mark.parametrize("m,n,k", [(1, 1, 1), (3, 5, 4), (64, 64, 64), (70, 33, 130), (256, 128, 192)])
+def test_gemm2_backward_parity(la, orc, dtype, ta, tb, m, n, k):
+    batch = 3
+    rng = np.random.default_rng(4000 + m + n + k)
+    A = (rng.standard_normal((batch, k, m) if ta else (batch, m, k)) / np.sqrt(k)).astype(npdt(dtype))
+    B = rng.standard_normal((batch, n, k) if tb else (batch, k, n)).astype(npdt(dtype))
+    G = rng.standard_normal((batch, m, n)).astype(npdt(dtype))
+    ra, rb = orc.gemm2_backward(A, B, G, ta=ta, tb=tb, alpha=0.9)
+    ga, gb = la.gemm2_backward(dev(A), dev(B), dev(G), ta=ta, tb=tb, alpha=0.9)
+    assert relerr(host(ga), ra) <= TOL[dtype]
+    assert relerr(host(gb), rb) <= TOL[dtype]
+
+
+def spd(seed, batch, n, dtype):
+    rng = np.random.default_rng(seed)
+    X = rng.standard_normal((batch, n, 2 * n))
+    A = X @ X.transpose(0, 2, 1) / (2 * n) + np.eye(n)
+    return (0.5 * (A + A.transpose(0, 2, 1))).astype(npdt(dtype))
+
+
+@pytest.mark.parametrize("dtype", ["f64", "f32"])
+@pytest.mark.parametrize("lower", [True, False])
+@pytest.mark.parametrize("n", [1, 5, 16, 33, 64, 100, 128, 200, 384])
+def test_potri_parity(la, orc, dtype, lower, n):
+    batch = 3
+    A = spd(5000 + n, batch, n, dtype)
+    F = orc.potrf(A, lower=lower).astype(npdt(dtype))
+    other = np.triu_indices(n, 1) if lower else np.tril_indices(n, -1)
+    Fj = F.copy()
+    Fj[:, other[0], other[1]] = np.nan  # never read
+    ref = orc.potri(F, lower=lower)
+    out = host(la.potri(dev(Fj), lower=lower))
+    assert np.array_equal(out, out.transpose(0, 2, 1))  # exactly symmetric
+    # the explicit inverse carries cond(A) <= 4 times the error of a solve: 10 tol is ample here
+    assert relerr(out, ref) <= 10 * TOL[dtype]
+    t = dev(F)  # B over L
+    out2 = host(la.potri(t, lower=lower, out=t))
+    assert np.array_equal(out2, out)
+
+
+@pytest.mark.parametrize("dtype", ["f64", "f32"])
+@pytest.mark.parametrize("lower", [True, False])
+@pytest.mark.parametrize("n", [1, 5, 16, 33, 64, 100, 128, 200])
+def test_potri_backward_parity(la, orc, dtype, lower, n):
+    batch = 3
+    A = spd(6000 + n, batch, n, dtype)
+    F = orc.potrf(A, lower=lower).astype(npdt(dtype))
+    B = orc.potri(F, lower=lower).astype(npdt(dtype))
+    rng = np.random.default_rng(n)
+    G = rng.standard_normal((batch, n, n)).astype(npdt(dtype))  # not symmetric
+    ref = orc.potri_backward(F, B, G, lower=lower)
+    other = np.triu_indices(n, 1) if lower else np.tril_indices(n, -1)
+    Fj = F.copy()
+    Fj[:, other[0], other[1]] = np.nan
+    out = host(la.potri_backward(dev(Fj), dev(B), dev(G), lower=lower))
+    assert np.all(out[:, other[0], other[1]] == 0.0)
+    assert relerr(out, ref) <= 10 * TOL[dtype]
+
+
+def test_rank2_ops_empty_and_errors(la):
+    import torch
+
+    z = torch.zeros((0, 3, 3), dtype=torch.float64, device="cuda")
+    assert la.potri(z).shape == (0, 3, 3)
+    assert la.potri_backward(z, z.clone(), z.clone()).shape == (0, 3, 3)
+    A = torch.ones((2, 3, 0), dtype=torch.float64, device="cuda")
+    B = torch.ones((2, 0, 4), dtype=torch.float64, device="cuda")
+    ga, gb = la.gemm2_backward(A, B, torch.ones((2, 3, 4), dtype=torch.float64, device="cuda"))
+    assert ga.shape == (2, 3, 0) and gb.shape == (2, 0, 4)
+    A = torch.ones((2, 3, 5), dtype=torch.float64, device="cuda")
+    B = torch.ones((2, 5, 0), dtype=torch.float64, device="cuda")
+    ga, gb = la.gemm2_backward(A, B, torch.ones((2, 3, 0), dtype=torch.float64, device="cuda"))
+    assert torch.all(ga == 0) and gb.shape == (2, 5, 0)
+    L = torch.eye(4, dtype=torch.float64, device="cuda").repeat(2, 1, 1)
+    with pytest.raises(la.LaError):
+        la.potri_backward(L, L.clone(), L.clone(), out=L)
