@@ -144,11 +144,26 @@ __device__ __forceinline__ void fnmac_dpp16(float &acc, float src, float other)
                  : "+v"(acc)
                  : "v"(src), "v"(other), "n"(K));
 }
+// fp64: the same single instruction exists (64-bit DPP supports exactly this broadcast control)
+template <int K>
+__device__ __forceinline__ void fmac_dpp16(double &acc, double src, double other)
+{
+    asm volatile("v_fmac_f64_dpp %0, %1, %2 row_newbcast:%3 row_mask:0xf bank_mask:0xf"
+                 : "+v"(acc)
+                 : "v"(src), "v"(other), "n"(K));
+}
+template <int K>
+__device__ __forceinline__ void fnmac_dpp16(double &acc, double src, double other)
+{
+    asm volatile("v_fmac_f64_dpp %0, -%1, %2 row_newbcast:%3 row_mask:0xf bank_mask:0xf"
+                 : "+v"(acc)
+                 : "v"(src), "v"(other), "n"(K));
+}
 
 template <int G, int K, typename T>
 __device__ __forceinline__ void fma_bcast(T &acc, T src, T other, bool neg)
 {
-    if constexpr (G == 16 && sizeof(T) == 4) {
+    if constexpr (G == 16) {
         if (neg)
             fnmac_dpp16<K>(acc, src, other);
         else
@@ -176,7 +191,7 @@ __device__ __forceinline__ void static_for(F &&f)
 template <int G, typename T, int N>
 __device__ __forceinline__ void dpp_settle(T (&v)[N])
 {
-    if constexpr (G == 16 && sizeof(T) == 4) {
+    if constexpr (G == 16) {
 #pragma unroll
         for (int i = 0; i < N; ++i)
             asm volatile("" : "+v"(v[i]));
@@ -186,7 +201,7 @@ __device__ __forceinline__ void dpp_settle(T (&v)[N])
 template <int G, typename T>
 __device__ __forceinline__ void dpp_settle1(T &v)
 {
-    if constexpr (G == 16 && sizeof(T) == 4) {
+    if constexpr (G == 16) {
         asm volatile("s_nop 1" : "+v"(v));
     }
 }
