@@ -283,6 +283,13 @@ template <typename T>
 la_status launch_trsm_leaf16(View<const T> Lam, View<const T> Xin, View<T> X, int64_t batch, int n, int m, T alpha,
                              bool fwd, hipStream_t st);
 
+// potrf backward with one workgroup per matrix, everything in LDS as 16 x 16 tiles, for
+// n <= backward_leaf16_max_n<T>() (128 in fp32, 96 in fp64).  Abar may alias G.
+template <typename T>
+int backward_leaf16_max_n();
+template <typename T>
+la_status launch_backward_leaf16(View<const T> Lam, View<const T> G, View<T> Abar, int64_t batch, int n, hipStream_t st);
+
 // Register-resident potrf backward for n <= 32: Abar = sym(L^-T Phi(L^T Lbar) L^-1).
 template <typename T>
 la_status launch_backward_tiny(View<const T> L, View<const T> G, View<T> Abar, int64_t batch, int n,

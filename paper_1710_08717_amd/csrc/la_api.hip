@@ -212,6 +212,8 @@ static la_status backward_impl(View<const T> Lam, View<const T> G, View<T> W, in
 {
     if (n <= 32)
         return launch_backward_tiny<T>(Lam, G, W, batch, n, st);
+    if (n <= backward_leaf16_max_n<T>())  // one workgroup per matrix, no scratch
+        return launch_backward_leaf16<T>(Lam, G, W, batch, n, st);
     View<T> sc[2];
     LA_TRY(scratch_views<T>(batch, n, 2, sc));
     View<T> Li = sc[0], X = sc[1];

@@ -347,12 +347,13 @@ __device__ __forceinline__ void tri_decode(int t, int &ti, int &tj)
     tj = t;
 }
 
-// Lower triangle of an nb x nb block at p (element strides rs, cs) into the tiles of A (identity
-// outside nb x nb).  Per tile a lane moves four elements, 16 lanes along the contiguous direction
-// of the operand; all loads of a wavefront are in flight together.
+// Lower triangle of an nb x nb block at p (element strides rs, cs) into the tiles of A (or of the
+// inverse's area with into_x); outside nb x nb the tiles get pad_diag on the diagonal and zero
+// elsewhere.  Per tile a lane moves four elements, 16 lanes along the contiguous direction of the
+// operand; all loads of a wavefront are in flight together.
 template <typename T>
 __device__ __forceinline__ void leaf_load_lower(const LeafLds<T> &m, const T *p, int64_t rs, int64_t cs, int nb,
-                                                int wave, int lane)
+                                                int wave, int lane, bool into_x = false, T pad_diag = T(1))
 {
     constexpr int W = LEAF16_WAVES;
     constexpr int TPW = (LK * (LK + 1) / 2 + W - 1) / W;  // lower tiles per wavefront, at most
@@ -373,7 +374,7 @@ __device__ __forceinline__ void leaf_load_lower(const LeafLds<T> &m, const T *p,
         for (int v = 0; v < 4; ++v) {
             const int u = colfast ? s0 + 4 * v : f, w = colfast ? f : s0 + 4 * v;
             const int r = ti * LT + u, c = tj * LT + w;
-            T x = (r == c) ? T(1) : T(0);
+            T x = (r == c) ? pad_diag : T(0);
             if (t < ntl && r < nb && c <= r)
                 x = *tp;
             val[q][v] = x;
@@ -386,7 +387,7 @@ __device__ __forceinline__ void leaf_load_lower(const LeafLds<T> &m, const T *p,
         if (t < ntl) {
             int ti, tj;
             tri_decode(t, ti, tj);
-            const TileRef<T> tr = m.a(ti, tj);
+            const TileRef<T> tr = into_x ? m.x(ti, tj) : m.a(ti, tj);
 #pragma unroll
             for (int v = 0; v < 4; ++v) {
                 const int u = colfast ? s0 + 4 * v : f, w = colfast ? f : s0 + 4 * v;
@@ -620,6 +621,163 @@ __global__ __launch_bounds__(LEAF16_THREADS) void k_tri_inv_leaf16(View<const T>
 }
 
 // ---------------------------------------------------------------------------------------
+// potrf backward (section 4.2; appendix "potrf") for one matrix per workgroup, everything in
+// LDS:  Abar = sym(L^-T Phi(L^T Lbar) L^-1),  Phi = lower triangle with halved diagonal.
+//   P = Phi(tril(L^T Lbar));   Li = L^-1 (as in k_tri_inv_leaf16);   Z = P Li;
+//   Abar_ij = 1/2 sum_{k >= i} (Li_ki^T Z_kj + Z_ki^T Li_kj)   for tiles i >= j, mirrored,
+// which is the symmetrised W = Li^T Z without ever forming W.  Three tile areas are enough:
+// [L, later Z], [Lbar, later Li], [P, later staging for the mirrored store].
+// ---------------------------------------------------------------------------------------
+template <typename T>
+__host__ __device__ constexpr int backward16_area(int K)  // elements of one tile area for K tile rows
+{
+    return K * Leaf16<T>::DT + K * (K - 1) / 2 * Leaf16<T>::OT;
+}
+
+template <typename T>
+__global__ __launch_bounds__(LEAF16_THREADS) void k_backward_leaf16(View<const T> Lam, View<const T> G, View<T> Abar,
+                                                                    int64_t batch, int n)
+{
+    using C = Leaf16<T>;
+    using MF = Mfma<T>;
+    extern __shared__ __align__(16) unsigned char leaf16_lds[];
+    T *lds = reinterpret_cast<T *>(leaf16_lds);
+    constexpr int W = LEAF16_WAVES;
+    constexpr int PS = C::PS, DT = C::DT, OT = C::OT;
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int64_t b = blockIdx.x;
+    const int K = (n + LT - 1) / LT;
+    const int ntl = K * (K + 1) / 2;
+    const int area = backward16_area<T>(K);
+    // a: L, later Z.  x: Lbar, later Li.
+    const LeafLds<T> m{lds, lds + area, lds + K * DT, lds + area + K * DT};
+    T *pD = lds + 2 * area, *pO = pD + K * DT;
+    auto ptile = [&](int i, int j) { return i == j ? TileRef<T>{pD + i * DT, true} : TileRef<T>{pO + tri_off(i, j) * OT, false}; };
+
+    leaf_load_lower<T>(m, Lam.p + b * Lam.bs, Lam.rs, Lam.cs, n, wave, lane, false, T(1));
+    leaf_load_lower<T>(m, G.p + b * G.bs, G.rs, G.cs, n, wave, lane, true, T(0));
+    __syncthreads();
+
+    // ---- P_ij = sum_{k >= i} L_ki^T Lbar_kj, i >= j; Phi on the diagonal tiles ------------------
+    for (int t = wave; t < ntl; t += W) {
+        int i, j;
+        tri_decode(t, i, j);
+        typename MF::acc_t acc = {0, 0, 0, 0};
+        for (int k = i; k < K; ++k) {
+            T av[4], bv[4];
+            op_nat<T>(m.a(k, i), lane, av);
+            op_nat<T>(m.x(k, j), lane, bv);
+            acc = mma4<T>(av, bv, acc, false);
+        }
+        if (i == j) {
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                const int row = MF::row(lane, v), col = lane & 15;
+                acc[v] = row < col ? T(0) : (row == col ? T(0.5) * acc[v] : acc[v]);
+            }
+        }
+        acc_store<T>(ptile(i, j), lane, acc);
+    }
+    __syncthreads();
+
+    // ---- Li = L^-1 into the area Lbar occupied ------------------------------------------------
+    if (wave < K) {
+        const int r = lane & 15, g = lane >> 4;
+        const T *dk = m.sD + wave * DT + r * PS;
+        T *xk = m.sXD + wave * DT + r * PS;
+        T a[LT], x[4];
+#pragma unroll
+        for (int c = 0; c < LT; ++c)
+            a[c] = dk[c];
+        diag_invert<T>(a, dk[r], x, r, g);
+#pragma unroll
+        for (int jj = 0; jj < 4; ++jj)
+            xk[4 * jj + g] = (4 * jj + g <= r) ? x[jj] : T(0);
+    }
+    __syncthreads();
+    for (int k = 0; k < K; ++k) {
+        if (k > 0) {  // X_kj <- Li_kk X_kj, j < k
+            for (int j = wave; j < k; j += W)
+                leaf_xrow<T>(m, k, j, lane);
+            __syncthreads();
+        }
+        const int rows = K - 1 - k;
+        if (rows > 0) {  // X_ij -= L_ik X_kj, i > k, j <= k
+            int xi = 0, xj = wave;
+            for (int it = wave; it < rows * (k + 1); it += W) {
+                while (xj > k) {
+                    xj -= k + 1;
+                    ++xi;
+                }
+                leaf_update_x<T>(m, k + 1 + xi, xj, k, lane);
+                xj += W;
+            }
+            __syncthreads();
+        }
+    }
+
+    // ---- Z_ij = sum_{k = j..i} P_ik Li_kj, i >= j, into the area L occupied -----------------------
+    for (int t = wave; t < ntl; t += W) {
+        int i, j;
+        tri_decode(t, i, j);
+        typename MF::acc_t acc = {0, 0, 0, 0};
+        for (int k = j; k <= i; ++k) {
+            T av[4], bv[4];
+            op_rows<T>(ptile(i, k), lane, av);
+            op_nat<T>(m.x(k, j), lane, bv);
+            acc = mma4<T>(av, bv, acc, false);
+        }
+        acc_store<T>(m.a(i, j), lane, acc);
+    }
+    __syncthreads();
+
+    // ---- Abar_ij = 1/2 sum_{k >= i} (Li_ki^T Z_kj + Z_ki^T Li_kj), i >= j, stored with its mirror ----
+    {
+        T *op = Abar.p + b * Abar.bs;
+        const bool colfast = (Abar.cs == 1) || (Abar.rs != 1);
+        const int f = lane & 15, s0 = lane >> 4;
+        for (int t = wave; t < ntl; t += W) {
+            int i, j;
+            tri_decode(t, i, j);
+            typename MF::acc_t acc = {0, 0, 0, 0};
+            for (int k = i; k < K; ++k) {
+                T av[4], bv[4];
+                op_nat<T>(m.x(k, i), lane, av);
+                op_nat<T>(m.a(k, j), lane, bv);
+                acc = mma4<T>(av, bv, acc, false);
+                op_nat<T>(m.a(k, i), lane, av);
+                op_nat<T>(m.x(k, j), lane, bv);
+                acc = mma4<T>(av, bv, acc, false);
+            }
+#pragma unroll
+            for (int v = 0; v < 4; ++v)
+                acc[v] *= T(0.5);
+            // through this tile's slot of the (finished) P area: the mirror image is read back
+            // transposed; on diagonal tiles both halves take the lower half's values, which makes
+            // the result exactly symmetric
+            const TileRef<T> st = ptile(i, j);
+            acc_store<T>(st, lane, acc);
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                const int u = colfast ? s0 + 4 * v : f, w = colfast ? f : s0 + 4 * v;
+                const T direct = st.p[st.at(u, w)], mirror = st.p[st.at(w, u)];
+                const int r = i * LT + u, c = j * LT + w;
+                if (r < n && c < n)
+                    op[(int64_t)r * Abar.rs + (int64_t)c * Abar.cs] = (i == j && u < w) ? mirror : direct;
+                const int r2 = j * LT + u, c2 = i * LT + w;
+                if (i != j && r2 < n && c2 < n)
+                    op[(int64_t)r2 * Abar.rs + (int64_t)c2 * Abar.cs] = mirror;
+            }
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------------
 // trsm (section 4.2) with a small triangular matrix and a few right-hand sides: n <= 128 and
 // m <= 48 vectors X(e, v), one workgroup per batch item.  Block substitution over the 16-row
 // tiles with the inverted diagonal tiles:
@@ -828,5 +986,44 @@ template la_status launch_trsm_leaf16<float>(View<const float>, View<const float
                                              bool, hipStream_t);
 template la_status launch_trsm_leaf16<double>(View<const double>, View<const double>, View<double>, int64_t, int, int,
                                               double, bool, hipStream_t);
+
+// largest n the one-workgroup backward kernel takes: three tile areas must fit the 160 KB of LDS
+template <typename T>
+int backward_leaf16_max_n()
+{
+    int K = LK;
+    while (K > 0 && 3 * (size_t)backward16_area<T>(K) * sizeof(T) > 160 * 1024)
+        --K;
+    return K * LT;
+}
+template int backward_leaf16_max_n<float>();
+template int backward_leaf16_max_n<double>();
+
+template <typename T>
+la_status launch_backward_leaf16(View<const T> Lam, View<const T> G, View<T> Abar, int64_t batch, int n, hipStream_t st)
+{
+    if (batch <= 0 || n <= 0)
+        return LA_OK;
+    if (n > backward_leaf16_max_n<T>() || batch > 0x7fffffffll)
+        return LA_ERR_UNSUPPORTED;
+    const int K = (n + LT - 1) / LT;
+    const size_t lds_bytes = 3 * (size_t)backward16_area<T>(K) * sizeof(T);
+    static bool configured[64] = {};
+    int dev = 0;
+    LA_HIP(hipGetDevice(&dev));
+    if (dev >= 0 && dev < 64 && !configured[dev]) {
+        LA_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&k_backward_leaf16<T>),
+                                   hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024));
+        configured[dev] = true;
+    }
+    hipLaunchKernelGGL((k_backward_leaf16<T>), dim3((unsigned)batch), dim3(LEAF16_THREADS), lds_bytes, st, Lam, G, Abar,
+                       batch, n);
+    return launch_check("backward_leaf16");
+}
+
+template la_status launch_backward_leaf16<float>(View<const float>, View<const float>, View<float>, int64_t, int,
+                                                 hipStream_t);
+template la_status launch_backward_leaf16<double>(View<const double>, View<const double>, View<double>, int64_t, int,
+                                                  hipStream_t);
 
 }  // namespace la
