@@ -210,9 +210,12 @@ template <typename T>
 static la_status backward_impl(View<const T> Lam, View<const T> G, View<T> W, int64_t batch, int n, bool aliased,
                                hipStream_t st)
 {
-    if (n <= 32)
+    // n <= 16: 16 lanes per matrix, HBM bound.  16 < n <= 32: the register kernel has the higher
+    // throughput (11 against 16 ns per fp32 matrix), the one-workgroup kernel the shorter latency
+    // (25 against 37 us), so the batch size decides.
+    if (n <= 16 || (n <= 32 && batch > 2048))
         return launch_backward_tiny<T>(Lam, G, W, batch, n, st);
-    if (n <= backward_leaf16_max_n<T>())  // one workgroup per matrix, no scratch
+    if (n <= backward_leaf16_max_n<T>())  // one workgroup per matrix, everything in LDS, no scratch
         return launch_backward_leaf16<T>(Lam, G, W, batch, n, st);
     View<T> sc[2];
     LA_TRY(scratch_views<T>(batch, n, 2, sc));

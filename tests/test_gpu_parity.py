@@ -201,6 +201,23 @@ def test_backward_parity(la, orc, dtype, n, lower):
 
 
 @pytest.mark.parametrize("dtype", ["f64", "f32"])
+@pytest.mark.parametrize("n", [17, 24, 32])
+@pytest.mark.parametrize("lower", [True, False])
+def test_backward_parity_large_batch_register_kernel(la, orc, dtype, n, lower):
+    """Above 2048 matrices sizes 17..32 take the register kernel instead of the one-workgroup one."""
+    batch = 2100
+    A = spd(n * 7 + lower, batch, n, dtype)
+    Lf = orc.potrf(A, lower=lower).astype(npdt(dtype))
+    rng = np.random.default_rng(n + 5)
+    G = rng.standard_normal((batch, n, n))
+    G = (np.tril(G) if lower else np.triu(G)).astype(npdt(dtype))
+    ref = orc.potrf_backward(Lf, G, lower=lower)
+    out = host(la.potrf_backward(dev(Lf), dev(G), lower=lower))
+    assert np.array_equal(out, out.transpose(0, 2, 1))
+    assert relerr(out, ref) <= TOL[dtype]
+
+
+@pytest.mark.parametrize("dtype", ["f64", "f32"])
 @pytest.mark.parametrize("n", [7, 16, 32, 40, 130])
 @pytest.mark.parametrize("lower", [True, False])
 def test_backward_aliasing_and_junk_triangles(la, orc, dtype, n, lower):
