@@ -231,35 +231,43 @@ la_status launch_sumlogdiag(const T *L, T *out, int64_t batch, int n, hipStream_
 }
 
 // One workgroup per matrix: loss = 1/2 y.alpha + sum log l_ii, Lbar = -tril(alpha z^T) + diag(1/l_ii).
+// A wavefront writes whole rows of Lbar (no index arithmetic beyond the row loop).
+constexpr int GLUE_THREADS = 1024;
 template <typename T>
-__global__ __launch_bounds__(256) void k_gp_glue(const T *L, const T *y, const T *z, const T *alpha, T *loss, T *Lbar,
-                                                 int64_t batch, int n)
+__global__ __launch_bounds__(GLUE_THREADS) void k_gp_glue(const T *L, const T *y, const T *z, const T *alpha, T *loss,
+                                                          T *Lbar, int64_t batch, int n)
 {
-    __shared__ double red[4];
+    __shared__ double red[GLUE_THREADS / WAVE];
     const int64_t b = blockIdx.x;
     const T *lp = L + b * (int64_t)n * n;
     const T *yp = y + b * n, *zp = z + b * n, *ap = alpha + b * n;
     T *gp = Lbar + b * (int64_t)n * n;
+    const int w = threadIdx.x / WAVE, l = threadIdx.x % WAVE;
     double s = 0.0;
-    for (int i = threadIdx.x; i < n; i += 256)
+    for (int i = threadIdx.x; i < n; i += GLUE_THREADS)
         s += 0.5 * (double)yp[i] * (double)ap[i] + (double)log(lp[(int64_t)i * n + i]);
 #pragma unroll
     for (int off = 32; off >= 1; off >>= 1)
         s += __shfl_xor(s, off, WAVE);
-    if ((threadIdx.x & 63) == 0)
-        red[threadIdx.x >> 6] = s;
+    if (l == 0)
+        red[w] = s;
+    for (int i = w; i < n; i += GLUE_THREADS / WAVE) {
+        const T ai = ap[i];
+        const T dinv = T(1) / lp[(int64_t)i * n + i];
+        T *row = gp + (int64_t)i * n;
+        for (int j = l; j < n; j += WAVE) {
+            T g = (j <= i) ? -ai * zp[j] : T(0);
+            if (j == i)
+                g += dinv;
+            row[j] = g;
+        }
+    }
     __syncthreads();
-    if (threadIdx.x == 0)
-        loss[b] = (T)(red[0] + red[1] + red[2] + red[3]);
-    const int64_t nn = (int64_t)n * n;
-    for (int64_t e = threadIdx.x; e < nn; e += 256) {
-        const int i = (int)(e / n), j = (int)(e % n);
-        T g = T(0);
-        if (i >= j)
-            g = -ap[i] * zp[j];
-        if (i == j)
-            g += T(1) / lp[e];
-        gp[e] = g;
+    if (threadIdx.x == 0) {
+        double t = 0.0;
+        for (int q = 0; q < GLUE_THREADS / WAVE; ++q)
+            t += red[q];
+        loss[b] = (T)t;
     }
 }
 
@@ -271,7 +279,7 @@ la_status launch_gp_glue(const T *L, const T *y, const T *z, const T *alpha, T *
         return LA_OK;
     if (batch > 0x7fffffffll)
         return LA_ERR_UNSUPPORTED;
-    hipLaunchKernelGGL((k_gp_glue<T>), dim3((unsigned)batch), dim3(256), 0, st, L, y, z, alpha, loss, Lbar, batch, n);
+    hipLaunchKernelGGL((k_gp_glue<T>), dim3((unsigned)batch), dim3(GLUE_THREADS), 0, st, L, y, z, alpha, loss, Lbar, batch, n);
     return launch_check("gp_glue");
 }
 
