@@ -47,6 +47,7 @@ def _load():
         lib.orc_gemm2_backward.argtypes = [i32, i32, f64, i64, i32, i32, i32, dp, dp, dp, dp, dp]
         lib.orc_potri.argtypes = [i32, i64, i32, dp, dp]
         lib.orc_potri_backward.argtypes = [i32, i64, i32, dp, dp, dp, dp]
+        lib.orc_sgp_criterion.argtypes = [i32, i32, dp, dp, dp, dp, f64, dp, dp, dp, dp, dp, dp]
         lib.orc_sumlogdiag.argtypes = [i64, i32, dp, dp]
         lib.orc_gemm2.argtypes = [i32, i32, f64, i64, i32, i32, i32, dp, dp, dp]
         lib.orc_gp_glue.argtypes = [i64, i32, dp, dp, dp, dp, dp, dp]
@@ -226,6 +227,22 @@ def potri_backward(L, B, Bbar, lower=True):
     n = L.shape[-1]
     out = np.empty_like(L)
     _check(_load().orc_potri_backward(int(lower), _batch_of(L, 2), n, _p(L), _p(B), _p(Bbar), _p(out)), "potri_backward")
+    return out
+
+
+def sgp_criterion(Kuu, Kuf, Kff_diag, y, noise_var):
+    """Sparse-GP criterion of section 3.2 and its gradient: dict with phi, Kuu_bar, Kuf_bar,
+    Kff_diag_bar, y_bar, noise_bar."""
+    Kuu, Kuf, Kff_diag, y = _f64(Kuu), _f64(Kuf), _f64(Kff_diag), _f64(y)
+    U, n = Kuf.shape
+    assert Kuu.shape == (U, U) and Kff_diag.shape == (n,) and y.shape == (n,)
+    phi, lb = np.zeros(1), np.zeros(1)
+    out = {"Kuu_bar": np.empty_like(Kuu), "Kuf_bar": np.empty_like(Kuf), "Kff_diag_bar": np.empty_like(Kff_diag),
+           "y_bar": np.empty_like(y)}
+    _check(_load().orc_sgp_criterion(U, n, _p(Kuu), _p(Kuf), _p(Kff_diag), _p(y), float(noise_var), _p(phi),
+                                     _p(out["Kuu_bar"]), _p(out["Kuf_bar"]), _p(out["Kff_diag_bar"]), _p(out["y_bar"]),
+                                     _p(lb)), "sgp_criterion")
+    out["phi"], out["noise_bar"] = float(phi[0]), float(lb[0])
     return out
 
 

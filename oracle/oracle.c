@@ -760,6 +760,92 @@ int orc_potrf_backward_phi(int64_t batch, int n, const double *L, const double *
 }
 
 /* ------------------------------------------------------------------------- */
+/* Variational sparse Gaussian-process criterion (section 3.2) and its gradient.
+ * Inputs: Kuu (U x U, symmetric positive definite, lower triangle read), Kuf (U x n),
+ * Kff_diag (n), y (n), noise variance lam.  Forward, in the order of the section's listing:
+ *   Lu = potrf(Kuu);  B = Lu^-1 Kuf;  A = B B^T / lam + I;  La = potrf(A);
+ *   w = La^-1 (B y);
+ *   phi = (log 2 pi + log lam) n / 2 + sum_i log La_ii + |y|^2 / (2 lam) - |w|^2 / (2 lam^2)
+ *         - (|B|_F^2 - sum Kff_diag) / (2 lam).
+ * Backward: the chain rule through the same steps with the operators' backward rules
+ * (section 4.2): trsm, gemm2, potrf, syrk, trsm, potrf.  Outputs: phi, Kuu_bar (symmetric,
+ * d phi = <Kuu_bar, dKuu> for symmetric dKuu), Kuf_bar, Kff_diag_bar, y_bar, lam_bar. */
+int orc_sgp_criterion(int U, int n, const double *Kuu, const double *Kuf, const double *Kff_diag, const double *y,
+                      double lam, double *phi, double *Kuu_bar, double *Kuf_bar, double *Kff_diag_bar, double *y_bar,
+                      double *lam_bar)
+{
+    if (U <= 0 || n <= 0 || !Kuu || !Kuf || !Kff_diag || !y || !phi || !Kuu_bar || !Kuf_bar || !Kff_diag_bar ||
+        !y_bar || !lam_bar || !(lam > 0.0))
+        return ORC_ERR_INVALID_ARG;
+    size_t uu = (size_t)U * U, un = (size_t)U * n;
+    double *Lu = malloc(uu * sizeof(double)), *B = malloc(un * sizeof(double)), *A = malloc(uu * sizeof(double));
+    double *La = malloc(uu * sizeof(double)), *Lab = malloc(uu * sizeof(double)), *Ab = malloc(uu * sizeof(double));
+    double *v = malloc(U * sizeof(double)), *w = malloc(U * sizeof(double)), *vb = malloc(U * sizeof(double));
+    double *Lub = malloc(uu * sizeof(double)), *G = malloc(un * sizeof(double));
+    int rc = ORC_ERR_INVALID_ARG;
+    if (!Lu || !B || !A || !La || !Lab || !Ab || !v || !w || !vb || !Lub || !G)
+        goto done;
+    /* forward */
+    if (orc_potrf(1, 1, U, Kuu, Lu, NULL) || orc_trsm(1, 0, 0, 1.0, 1, U, n, Lu, Kuf, B) ||
+        orc_syrk(0, 1.0 / lam, 1, U, n, B, A))
+        goto done;
+    for (int i = 0; i < U; ++i)
+        A[(size_t)i * U + i] += 1.0;
+    if (orc_potrf(1, 1, U, A, La, NULL) || orc_gemm2(0, 0, 1.0, 1, U, 1, n, B, y, v) ||
+        orc_trsm(1, 0, 0, 1.0, 1, U, 1, La, v, w))
+        goto done;
+    double logdet = 0.0, yy = 0.0, ww = 0.0, bb = 0.0, kk = 0.0;
+    for (int i = 0; i < U; ++i)
+        logdet += log(La[(size_t)i * U + i]);
+    for (int i = 0; i < n; ++i) {
+        yy += y[i] * y[i];
+        kk += Kff_diag[i];
+    }
+    for (int i = 0; i < U; ++i)
+        ww += w[i] * w[i];
+    for (size_t e = 0; e < un; ++e)
+        bb += B[e] * B[e];
+    const double l2pi = 1.8378770664093454835606594728112; /* log(2 pi) */
+    *phi = (l2pi + log(lam)) * n / 2.0 + logdet + yy / (2.0 * lam) - ww / (2.0 * lam * lam) - (bb - kk) / (2.0 * lam);
+    /* backward */
+    for (int i = 0; i < U; ++i)
+        vb[i] = -w[i] / (lam * lam); /* w_bar */
+    /* w = La^-1 v:  v_bar = La^-T w_bar,  La_bar = -tril(v_bar w^T);  log det adds diag(1 / La_ii) */
+    if (orc_trsm_backward(1, 0, 0, 1.0, 1, U, 1, La, w, vb, vb, Lab))
+        goto done;
+    for (int i = 0; i < U; ++i)
+        Lab[(size_t)i * U + i] += 1.0 / La[(size_t)i * U + i];
+    if (orc_potrf_backward(1, 1, U, La, Lab, Ab)) /* A_bar, symmetric */
+        goto done;
+    double sa = 0.0;
+    for (int i = 0; i < U; ++i)
+        for (int j = 0; j < U; ++j)
+            sa += Ab[(size_t)i * U + j] * (A[(size_t)i * U + j] - (i == j ? 1.0 : 0.0));
+    *lam_bar = n / (2.0 * lam) - yy / (2.0 * lam * lam) + ww / (lam * lam * lam) + (bb - kk) / (2.0 * lam * lam) - sa / lam;
+    /* B_bar = syrk backward of S = B B^T with S_bar = A_bar / lam, + v_bar y^T, - B / lam */
+    if (orc_syrk_backward(0, 1.0, 1, U, n, B, Ab, G))
+        goto done;
+    for (int i = 0; i < U; ++i)
+        for (int c = 0; c < n; ++c)
+            G[(size_t)i * n + c] = G[(size_t)i * n + c] / lam + vb[i] * y[c] - B[(size_t)i * n + c] / lam;
+    /* y_bar = B^T v_bar + y / lam */
+    for (int c = 0; c < n; ++c) {
+        double t = 0.0;
+        for (int i = 0; i < U; ++i)
+            t += B[(size_t)i * n + c] * vb[i];
+        y_bar[c] = t + y[c] / lam;
+        Kff_diag_bar[c] = 1.0 / (2.0 * lam);
+    }
+    /* B = Lu^-1 Kuf */
+    if (orc_trsm_backward(1, 0, 0, 1.0, 1, U, n, Lu, B, G, Kuf_bar, Lub) || orc_potrf_backward(1, 1, U, Lu, Lub, Kuu_bar))
+        goto done;
+    rc = ORC_OK;
+done:
+    free(Lu); free(B); free(A); free(La); free(Lab); free(Ab); free(v); free(w); free(vb); free(Lub); free(G);
+    return rc;
+}
+
+/* ------------------------------------------------------------------------- */
 /* Gaussian-process criterion pieces (section 3.1) for one noisy kernel matrix
  * A = L L^T and targets y:
  *   z = L^{-1} y, alpha = L^{-T} z,
