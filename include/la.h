@@ -38,6 +38,7 @@
 #ifndef LA_MI355X_H
 #define LA_MI355X_H
 
+#include <stddef.h>
 #include <stdint.h>
 
 #ifdef __cplusplus
@@ -168,6 +169,22 @@ la_status la_sumlogdiag(la_dtype dt, int64_t batch, int n, const void *L, void *
  * in full (zeros above the diagonal) and must not overlap L.  Lower factor only. */
 la_status la_gp_glue(la_dtype dt, int64_t batch, int n, const void *L, const void *y, const void *z,
                      const void *alpha, void *loss, void *Lbar, void *stream);
+
+/* Variational sparse Gaussian-process criterion and its gradient (section 3.2; the backward sweep
+ * applies the backward rules of section 4.2 to the listing's steps in reverse).  One problem per call:
+ *   Lu = potrf(Kuu);  B = Lu^{-1} Kuf;  A = B B^T / lam + I;  La = potrf(A);  w = La^{-1} (B y);
+ *   phi = (log 2 pi + log lam) n / 2 + sum_i log La_ii + |y|^2 / (2 lam) - |w|^2 / (2 lam^2)
+ *         - (|B|_F^2 - sum Kff_diag) / (2 lam),            lam = noise_var > 0.
+ * Device inputs: Kuu [U, U] (lower triangle read), Kuf [U, n], Kff_diag [n], y [n].  Device outputs:
+ * phi [1], Kuu_bar [U, U] (symmetric: d phi = <Kuu_bar, dKuu> for symmetric dKuu), Kuf_bar [U, n],
+ * Kff_diag_bar [n], y_bar [n], noise_bar [1].  workspace: device memory, 16-byte aligned, at least
+ * la_sgp_workspace_bytes(dt, U, n) bytes; outputs and workspace must not overlap the inputs or each
+ * other.  The blocked operators inside also use the library's own scratch buffer. */
+size_t la_sgp_workspace_bytes(la_dtype dt, int U, int n);
+la_status la_sgp_criterion(la_dtype dt, int U, int n, const void *Kuu, const void *Kuf, const void *Kff_diag,
+                           const void *y, double noise_var, void *phi, void *Kuu_bar, void *Kuf_bar,
+                           void *Kff_diag_bar, void *y_bar, void *noise_bar, void *workspace,
+                           size_t workspace_bytes, void *stream);
 
 /* Text of the last HIP error seen by this thread's calls (host pointer, never NULL). */
 const char *la_last_error(void);

@@ -14,6 +14,7 @@ from .binding import (  # noqa: F401
     lib_path,
     load,
     potrf,
+    sgp_criterion,
     potri,
     potri_backward,
     potrf_backward,
@@ -26,5 +27,5 @@ from .binding import (  # noqa: F401
     trsm_backward,
 )
 
-__all__ = ["potrf", "potrf_backward", "trsm", "trmm", "syrk", "trsm_backward", "trmm_backward", "syrk_backward", "gemm2_backward", "potri", "potri_backward", "sumlogdiag",
+__all__ = ["potrf", "potrf_backward", "trsm", "trmm", "syrk", "trsm_backward", "trmm_backward", "syrk_backward", "gemm2_backward", "potri", "potri_backward", "sgp_criterion", "sumlogdiag",
            "gp_glue", "gemm2", "load", "lib_path", "LaError"]

@@ -17,7 +17,8 @@ _lib = None
 SYMBOLS = [
     "la_potrf_batched", "la_potrf_backward", "la_trsm_batched", "la_trmm_batched", "la_syrk_batched",
     "la_sumlogdiag", "la_gp_glue", "la_gemm2_batched", "la_trsm_backward", "la_trmm_backward", "la_syrk_backward",
-    "la_gemm2_backward", "la_potri", "la_potri_backward", "la_last_error", "la_version",
+    "la_gemm2_backward", "la_potri", "la_potri_backward", "la_sgp_workspace_bytes", "la_sgp_criterion",
+    "la_last_error", "la_version",
 ]
 
 
@@ -59,6 +60,10 @@ def load():
     for name in ("la_trsm_backward", "la_trmm_backward", "la_syrk_backward", "la_gemm2_backward", "la_potri",
                  "la_potri_backward"):
         getattr(lib, name).restype = i32
+    lib.la_sgp_workspace_bytes.argtypes = [i32, i32, i32]
+    lib.la_sgp_workspace_bytes.restype = ctypes.c_size_t
+    lib.la_sgp_criterion.argtypes = [i32, i32, i32, vp, vp, vp, vp, f64, vp, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
+    lib.la_sgp_criterion.restype = i32
     lib.la_last_error.restype = ctypes.c_char_p
     lib.la_version.restype = i32
     for name in SYMBOLS[:7]:
@@ -243,6 +248,28 @@ def potri_backward(L, B, Bbar, lower=True, out=None):
         _check(load().la_potri_backward(_dt(L), int(lower), _batch(L), n, _ptr(L), _ptr(B), _ptr(Bbar), _ptr(Lbar),
                                         _stream(L)), "la_potri_backward")
     return Lbar
+
+
+def sgp_criterion(Kuu, Kuf, Kff_diag, y, noise_var, workspace=None):
+    """la_sgp_criterion: dict with phi, Kuu_bar, Kuf_bar, Kff_diag_bar, y_bar, noise_bar (device tensors).
+    ``workspace``: a uint8 device tensor of at least la_sgp_workspace_bytes bytes (allocated here if absent)."""
+    _chk(Kuu, Kuf)
+    _chk(Kuu, Kff_diag)
+    _chk(Kuu, y)
+    U, n = Kuf.shape
+    assert Kuu.shape == (U, U) and Kff_diag.shape == (n,) and y.shape == (n,)
+    need = int(load().la_sgp_workspace_bytes(_dt(Kuu), U, n))
+    if workspace is None:
+        workspace = torch.empty(need, dtype=torch.uint8, device=Kuu.device)
+    out = {"phi": torch.empty(1, dtype=Kuu.dtype, device=Kuu.device), "Kuu_bar": torch.empty_like(Kuu),
+           "Kuf_bar": torch.empty_like(Kuf), "Kff_diag_bar": torch.empty_like(Kff_diag), "y_bar": torch.empty_like(y),
+           "noise_bar": torch.empty(1, dtype=Kuu.dtype, device=Kuu.device)}
+    with torch.cuda.device(Kuu.device):
+        _check(load().la_sgp_criterion(_dt(Kuu), U, n, _ptr(Kuu), _ptr(Kuf), _ptr(Kff_diag), _ptr(y), float(noise_var),
+                                       _ptr(out["phi"]), _ptr(out["Kuu_bar"]), _ptr(out["Kuf_bar"]),
+                                       _ptr(out["Kff_diag_bar"]), _ptr(out["y_bar"]), _ptr(out["noise_bar"]),
+                                       workspace.data_ptr(), workspace.numel(), _stream(Kuu)), "la_sgp_criterion")
+    return out
 
 
 def syrk(A, trans=False, alpha=1.0, out=None):

@@ -337,4 +337,21 @@ la_status launch_gp_glue(const T *L, const T *y, const T *z, const T *alpha, T *
                          hipStream_t st);
 la_status launch_fill_i32(int32_t *p, int64_t count, int32_t v, hipStream_t st);
 
+// Pieces of the sparse-GP criterion (section 3.2).
+constexpr int SGP_PARTIALS = 256;  // fp64 partial sums per reduced quantity
+// kind 0: sum a^2, 1: sum a, 2: sum a b, 3: trace of the ld x ld matrix a (count = ld), 4: sum of the
+// logs of its diagonal; writes SGP_PARTIALS partial sums
+template <typename T>
+la_status launch_partial_sums(int kind, const T *a, const T *b, int64_t count, int64_t ld, double *partial,
+                              hipStream_t st);
+template <typename T>
+la_status launch_add_diag(T *A, int n, T v, hipStream_t st);
+template <typename T>
+la_status launch_rank1_add(T *C, const T *u, const T *v, int rows, int cols, hipStream_t st);
+// sums: 7 x SGP_PARTIALS partial sums (|y|^2, |w|^2, |B|^2, sum Kff_diag, sum log La_ii, sum Abar o A,
+// trace Abar); stage 0 writes phi, stage 1 noise_bar and the constant Kff_diag_bar
+template <typename T>
+la_status launch_sgp_scalars(int stage, const double *sums, double lam, int n, T *phi, T *noise_bar, T *kff_bar, int nk,
+                             hipStream_t st);
+
 }  // namespace la

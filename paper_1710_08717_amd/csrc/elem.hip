@@ -283,6 +283,119 @@ la_status launch_gp_glue(const T *L, const T *y, const T *z, const T *alpha, T *
     return launch_check("gp_glue");
 }
 
+// ---------------------------------------------------------------------------------------
+// Small pieces of the sparse-GP criterion (section 3.2): sums, a diagonal shift, a rank-1 update,
+// the scalar formulas.
+// ---------------------------------------------------------------------------------------
+constexpr int RED_BLOCKS = SGP_PARTIALS;  // partial sums per quantity
+
+// kind 0: sum a_i^2, 1: sum a_i, 2: sum a_i b_i, 3: sum of a_{i (ld + 1)} (trace of an ld x ld matrix),
+// 4: sum log a_{i (ld + 1)}.  One fp64 partial sum per block; k_sgp_scalars adds them up.
+template <typename T>
+__global__ __launch_bounds__(256) void k_partial_sums(int kind, const T *a, const T *b, int64_t count, int64_t ld,
+                                                      double *partial)
+{
+    __shared__ double red[4];
+    double s = 0.0;
+    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < count; i += (int64_t)gridDim.x * 256) {
+        if (kind == 0)
+            s += (double)a[i] * (double)a[i];
+        else if (kind == 1)
+            s += (double)a[i];
+        else if (kind == 2)
+            s += (double)a[i] * (double)b[i];
+        else if (kind == 3)
+            s += (double)a[i * (ld + 1)];
+        else
+            s += log((double)a[i * (ld + 1)]);
+    }
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1)
+        s += __shfl_xor(s, off, WAVE);
+    if ((threadIdx.x & 63) == 0)
+        red[threadIdx.x >> 6] = s;
+    __syncthreads();
+    if (threadIdx.x == 0)
+        partial[blockIdx.x] = red[0] + red[1] + red[2] + red[3];
+}
+
+template <typename T>
+la_status launch_partial_sums(int kind, const T *a, const T *b, int64_t count, int64_t ld, double *partial,
+                              hipStream_t st)
+{
+    hipLaunchKernelGGL((k_partial_sums<T>), dim3(RED_BLOCKS), dim3(256), 0, st, kind, a, b, count, ld, partial);
+    return launch_check("partial_sums");
+}
+
+// A(i,i) += v on an n x n row-major matrix
+template <typename T>
+__global__ void k_add_diag(T *A, int n, T v)
+{
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n)
+        A[(int64_t)i * n + i] += v;
+}
+template <typename T>
+la_status launch_add_diag(T *A, int n, T v, hipStream_t st)
+{
+    hipLaunchKernelGGL((k_add_diag<T>), dim3((n + 255) / 256), dim3(256), 0, st, A, n, v);
+    return launch_check("add_diag");
+}
+
+// C(i,j) += u_i v_j on rows x cols (row-major); fill != 0: C(i, j) = value instead (rows = 1)
+template <typename T>
+__global__ __launch_bounds__(256) void k_rank1_add(T *C, const T *u, const T *v, int rows, int cols)
+{
+    const int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    const int64_t row = e / cols;  // one division per thread
+    if (row < rows)
+        C[e] += u[row] * v[e - row * cols];
+}
+template <typename T>
+la_status launch_rank1_add(T *C, const T *u, const T *v, int rows, int cols, hipStream_t st)
+{
+    const int64_t total = (int64_t)rows * cols;
+    hipLaunchKernelGGL((k_rank1_add<T>), dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, C, u, v, rows, cols);
+    return launch_check("rank1_add");
+}
+
+// Scalars of the criterion from the partial sums.  sums[q * RED_BLOCKS ..]: q = 0 |y|^2, 1 |w|^2,
+// 2 |B|_F^2, 3 sum Kff_diag, 4 sum log La_ii, 5 sum Abar o A, 6 trace Abar.
+// stage 0: phi.  stage 1: noise_bar and the constant Kff_diag_bar (first entry; a copy kernel spreads it).
+template <typename T>
+__global__ void k_sgp_scalars(int stage, const double *sums, double lam, int n, T *phi, T *noise_bar, T *kff_bar, int nk)
+{
+    __shared__ double tot[7];
+    if (threadIdx.x < 7) {
+        double t = 0.0;
+        for (int i = 0; i < RED_BLOCKS; ++i)
+            t += sums[threadIdx.x * RED_BLOCKS + i];
+        tot[threadIdx.x] = t;
+    }
+    __syncthreads();
+    const double yy = tot[0], ww = tot[1], bb = tot[2], kk = tot[3], logdet = tot[4], sa = tot[5] - tot[6];
+    if (stage == 0) {
+        if (threadIdx.x == 0)
+            phi[0] = (T)((1.8378770664093454835606594728112 + log(lam)) * n / 2.0 + logdet + yy / (2.0 * lam) -
+                         ww / (2.0 * lam * lam) - (bb - kk) / (2.0 * lam));
+    } else {
+        if (threadIdx.x == 0 && blockIdx.x == 0)
+            noise_bar[0] = (T)(n / (2.0 * lam) - yy / (2.0 * lam * lam) + ww / (lam * lam * lam) +
+                               (bb - kk) / (2.0 * lam * lam) - sa / lam);
+        for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < nk; i += gridDim.x * blockDim.x)
+            kff_bar[i] = (T)(1.0 / (2.0 * lam));
+    }
+}
+template <typename T>
+la_status launch_sgp_scalars(int stage, const double *sums, double lam, int n, T *phi, T *noise_bar, T *kff_bar, int nk,
+                             hipStream_t st)
+{
+    const int blocks = stage == 0 ? 1 : (nk + 255) / 256;
+    hipLaunchKernelGGL((k_sgp_scalars<T>), dim3(blocks > 0 ? blocks : 1), dim3(256), 0, st, stage, sums, lam, n, phi,
+                       noise_bar, kff_bar, nk);
+    return launch_check("sgp_scalars");
+}
+
 __global__ void k_fill_i32(int32_t *p, int64_t count, int32_t v)
 {
     const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -305,6 +418,10 @@ la_status launch_fill_i32(int32_t *p, int64_t count, int32_t v, hipStream_t st)
     template la_status launch_symmetrize<T>(View<T>, int64_t, int, T, hipStream_t);                             \
     template la_status launch_mirror_lower<T>(View<T>, int64_t, int, hipStream_t);                              \
     template la_status launch_sumlogdiag<T>(const T *, T *, int64_t, int, hipStream_t);                         \
+    template la_status launch_partial_sums<T>(int, const T *, const T *, int64_t, int64_t, double *, hipStream_t); \
+    template la_status launch_add_diag<T>(T *, int, T, hipStream_t);                                            \
+    template la_status launch_rank1_add<T>(T *, const T *, const T *, int, int, hipStream_t);                   \
+    template la_status launch_sgp_scalars<T>(int, const double *, double, int, T *, T *, T *, int, hipStream_t); \
     template la_status launch_gp_glue<T>(const T *, const T *, const T *, const T *, T *, T *, int64_t, int,    \
                                          hipStream_t);
 LA_INST(float)

@@ -530,6 +530,76 @@ static la_status gemm2_backward_t(int ta, int tb, double alpha, int64_t batch, i
     return gemm2_t<T>(1, ta, alpha, batch, n, k, m, Cbar, A, Bbar, st);  // Bbar (n x k) = alpha Cbar^T t_a(A)
 }
 
+// ---------------------------------------------------------------------------------
+// Variational sparse Gaussian-process criterion (section 3.2) and its gradient, composed of the
+// operators above in the order of the section's listing; the backward sweep applies their
+// backward rules (section 4.2) in reverse.  One problem per call.  The caller's workspace holds
+//   Lu (U^2), B (U n), A (U^2), La (U^2), La_bar -> A_bar (U^2), v, w, v_bar (U each), one scalar,
+// then 7 x SGP_PARTIALS fp64 partial sums.
+// ---------------------------------------------------------------------------------
+template <typename T>
+static size_t sgp_workspace_elems(int U, int n)
+{
+    return 4 * (size_t)U * U + (size_t)U * n + 3 * (size_t)U + 16;
+}
+
+template <typename T>
+static la_status sgp_t(int U, int n, const void *Kuu_, const void *Kuf_, const void *Kff_, const void *y_, double lam,
+                       void *phi_, void *Kuu_bar_, void *Kuf_bar_, void *Kff_bar_, void *y_bar_, void *lam_bar_,
+                       void *ws, hipStream_t st)
+{
+    const int64_t uu = (int64_t)U * U, un = (int64_t)U * n;
+    T *Lu = (T *)ws, *B = Lu + uu, *A = B + un, *La = A + uu, *Ab = La + uu, *v = Ab + uu, *w = v + U, *vb = w + U,
+      *dummy = vb + U;
+    double *sums = reinterpret_cast<double *>(((uintptr_t)(dummy + 16) + 7) & ~(uintptr_t)7);
+    const T *Kuf = (const T *)Kuf_, *y = (const T *)y_, *Kff = (const T *)Kff_;
+    T *Kuf_bar = (T *)Kuf_bar_, *Kuu_bar = (T *)Kuu_bar_, *y_bar = (T *)y_bar_;
+    auto S = [&](int q) { return sums + q * SGP_PARTIALS; };
+
+    // ---- forward ----------------------------------------------------------------------------
+    LA_TRY(potrf_t<T>(1, 1, U, Kuu_, Lu, nullptr, st));                                        // Lu
+    LA_TRY(tri_apply_t<T>(true, 1, 0, 0, 1.0, 1, U, n, Lu, Kuf, B, st));                       // B = Lu^-1 Kuf
+    LA_TRY(syrk_t<T>(0, 1.0 / lam, 1, U, n, B, A, st));                                        // A = B B^T / lam ...
+    LA_TRY(launch_add_diag<T>(A, U, T(1), st));                                                //     ... + I
+    LA_TRY(potrf_t<T>(1, 1, U, A, La, nullptr, st));                                           // La
+    LA_TRY(gemm2_t<T>(0, 0, 1.0, 1, U, 1, n, B, y, v, st));                                    // v = B y
+    LA_TRY(tri_apply_t<T>(true, 1, 0, 0, 1.0, 1, U, 1, La, v, w, st));                         // w = La^-1 v
+    LA_TRY(launch_partial_sums<T>(0, y, nullptr, n, 0, S(0), st));
+    LA_TRY(launch_partial_sums<T>(0, w, nullptr, U, 0, S(1), st));
+    LA_TRY(launch_partial_sums<T>(0, B, nullptr, un, 0, S(2), st));
+    LA_TRY(launch_partial_sums<T>(1, Kff, nullptr, n, 0, S(3), st));
+    LA_TRY(launch_partial_sums<T>(4, La, nullptr, U, U, S(4), st));
+    LA_TRY(launch_partial_sums<T>(1, Kff, nullptr, 0, 0, S(5), st));  // zero until the backward sweep fills them
+    LA_TRY(launch_partial_sums<T>(1, Kff, nullptr, 0, 0, S(6), st));
+    LA_TRY(launch_sgp_scalars<T>(0, sums, lam, n, (T *)phi_, (T *)nullptr, (T *)nullptr, 0, st));
+
+    // ---- backward ---------------------------------------------------------------------------
+    // w = La^-1 v with w_bar = -w / lam^2:  v_bar = La^-T w_bar;  La_bar = -tril(v_bar w^T) + diag(1 / La_ii)
+    LA_TRY(tri_apply_t<T>(true, 1, 1, 0, -1.0 / (lam * lam), 1, U, 1, La, w, vb, st));
+    LA_TRY(launch_gp_glue<T>(La, w, w, vb, dummy, Ab, 1, U, st));
+    LA_TRY(backward_impl<T>(View<const T>{La, uu, U, 1}, View<const T>{Ab, uu, U, 1}, View<T>{Ab, uu, U, 1}, 1, U, true,
+                            st));                                                              // A_bar (symmetric)
+    LA_TRY(launch_partial_sums<T>(2, Ab, A, uu, 0, S(5), st));
+    LA_TRY(launch_partial_sums<T>(3, Ab, nullptr, U, U, S(6), st));
+    LA_TRY(launch_sgp_scalars<T>(1, sums, lam, n, (T *)nullptr, (T *)lam_bar_, (T *)Kff_bar_, n, st));
+    // B_bar = (2 / lam) A_bar B - B / lam + v_bar y^T   (into Kuf_bar's buffer)
+    View<T> Gb{Kuf_bar, un, n, 1};
+    LA_TRY(launch_copy<T>(View<const T>{B, un, n, 1}, Gb, 1, U, n, (T)(-1.0 / lam), 0, st));
+    GemmOpts o;
+    LA_TRY(launch_gemm<T>(View<const T>{Ab, uu, U, 1}, View<const T>{B, un, n, 1}, Gb, 1, U, n, U, (T)(2.0 / lam), T(1), o,
+                          st));
+    LA_TRY(launch_rank1_add<T>(Kuf_bar, vb, y, U, n, st));
+    // y_bar = B^T v_bar + y / lam
+    View<T> yb{y_bar, n, 1, 1};
+    LA_TRY(launch_copy<T>(View<const T>{y, n, 1, 1}, yb, 1, n, 1, (T)(1.0 / lam), 0, st));
+    LA_TRY(launch_gemm<T>(View<const T>{B, un, 1, n}, View<const T>{vb, U, 1, 1}, yb, 1, n, 1, U, T(1), T(1), o, st));
+    // B = Lu^-1 Kuf:  Kuf_bar = Lu^-T B_bar (in place),  Lu_bar = -tril(Kuf_bar B^T);  then Kuu_bar
+    LA_TRY(tri_apply_t<T>(true, 1, 1, 0, 1.0, 1, U, n, Lu, Kuf_bar, Kuf_bar, st));
+    LA_TRY(tri_outer_t<T>(1, 0, 0, T(-1), 1, U, n, Kuf_bar, B, Kuu_bar, st));
+    return backward_impl<T>(View<const T>{Lu, uu, U, 1}, View<const T>{Kuu_bar, uu, U, 1}, View<T>{Kuu_bar, uu, U, 1}, 1, U,
+                            true, st);
+}
+
 static la_status tri_backward(bool solve, la_dtype dt, int lower, int trans, int rightside, double alpha, int64_t batch,
                               int n, int m, const void *L, const void *X, const void *Bbar, void *Abar, void *Lbar,
                               void *stream)
@@ -698,6 +768,35 @@ la_status la_potri_backward(la_dtype dt, int lower, int64_t batch, int n, const 
     hipStream_t st = (hipStream_t)stream;
     return dt == LA_F32 ? potri_backward_t<float>(lower, batch, n, L, B, Bbar, Lbar, st)
                         : potri_backward_t<double>(lower, batch, n, L, B, Bbar, Lbar, st);
+}
+
+size_t la_sgp_workspace_bytes(la_dtype dt, int U, int n)
+{
+    if (bad_dtype(dt) || U <= 0 || n <= 0)
+        return 0;
+    const size_t e = dt == LA_F32 ? sgp_workspace_elems<float>(U, n) : sgp_workspace_elems<double>(U, n);
+    return e * esize(dt) + 8 + 7 * SGP_PARTIALS * sizeof(double);
+}
+
+la_status la_sgp_criterion(la_dtype dt, int U, int n, const void *Kuu, const void *Kuf, const void *Kff_diag,
+                           const void *y, double noise_var, void *phi, void *Kuu_bar, void *Kuf_bar, void *Kff_diag_bar,
+                           void *y_bar, void *noise_bar, void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (bad_dtype(dt) || U <= 0 || n <= 0 || U > MAX_N || n > MAX_N || !(noise_var > 0.0))
+        return LA_ERR_INVALID_ARG;
+    if (!Kuu || !Kuf || !Kff_diag || !y || !phi || !Kuu_bar || !Kuf_bar || !Kff_diag_bar || !y_bar || !noise_bar ||
+        !workspace || workspace_bytes < la_sgp_workspace_bytes(dt, U, n) || ((uintptr_t)workspace & 15))
+        return LA_ERR_INVALID_ARG;
+    const size_t uu = (size_t)U * U * esize(dt), un = (size_t)U * n * esize(dt);
+    if (overlap(Kuu_bar, uu, Kuu, uu) || overlap(Kuf_bar, un, Kuf, un) || overlap(Kuu_bar, uu, Kuf_bar, un) ||
+        overlap(workspace, workspace_bytes, Kuu_bar, uu) || overlap(workspace, workspace_bytes, Kuf_bar, un) ||
+        overlap(workspace, workspace_bytes, Kuu, uu) || overlap(workspace, workspace_bytes, Kuf, un))
+        return LA_ERR_INVALID_ARG;
+    hipStream_t st = (hipStream_t)stream;
+    return dt == LA_F32 ? sgp_t<float>(U, n, Kuu, Kuf, Kff_diag, y, noise_var, phi, Kuu_bar, Kuf_bar, Kff_diag_bar, y_bar,
+                                       noise_bar, workspace, st)
+                        : sgp_t<double>(U, n, Kuu, Kuf, Kff_diag, y, noise_var, phi, Kuu_bar, Kuf_bar, Kff_diag_bar, y_bar,
+                                        noise_bar, workspace, st);
 }
 
 la_status la_syrk_backward(la_dtype dt, int trans, double alpha, int64_t batch, int n, int k, const void *A,

@@ -121,6 +121,26 @@ def make(name, batch=None, n=None, dtype=None, m=None, lengthscale=1.0, jitter=1
     return out
 
 
+def make_sgp(U, n, dims=4, dtype="f64", lengthscale=1.0, jitter=0.1, noise_var=0.1):
+    """Synthetic inputs of the sparse-GP criterion (section 3.2) with the shape of the paper's
+    "power" experiment (n = 9568 cases of input dimension four, U inducing points): inputs and
+    inducing points ~ U[-2, 2]^dims, RBF kernel of unit variance, Kuu with ``jitter`` on its
+    diagonal (which keeps cond(Kuu) within a few hundred), targets ~ N(0, 1)."""
+    rng = np.random.default_rng(SEED0 + 9000 + U + n)
+    X = rng.uniform(-2.0, 2.0, size=(n, dims))
+    Z = rng.uniform(-2.0, 2.0, size=(U, dims))
+
+    def k(a, b):
+        d2 = np.sum(a * a, axis=1)[:, None] + np.sum(b * b, axis=1)[None, :] - 2.0 * (a @ b.T)
+        return np.exp(-0.5 * np.maximum(d2, 0.0) / (lengthscale * lengthscale))
+
+    Kuu = k(Z, Z)
+    Kuu = 0.5 * (Kuu + Kuu.T) + jitter * np.eye(U)
+    dt = np_dtype(dtype)
+    return {"U": U, "n": n, "dtype": dtype, "Kuu": Kuu.astype(dt), "Kuf": k(Z, X).astype(dt),
+            "Kff_diag": np.ones(n, dtype=dt), "y": rng.standard_normal(n).astype(dt), "noise_var": float(noise_var)}
+
+
 def cond_estimate(A, sample=4):
     """2-norm condition numbers of the first ``sample`` matrices (eigvalsh, fp64)."""
     A = np.asarray(A, dtype=np.float64).reshape(-1, A.shape[-2], A.shape[-1])[:sample]
