@@ -55,12 +55,66 @@ def bytes_model(n, s):
     return {"potrf": (tri + n * n) * s, "backward": (2 * tri + n * n) * s}
 
 
+def bench_sgp(args, la, torch, np, workloads):
+    """Second workload (section 3.2; the paper times it on n = 9568 cases with U inducing points):
+    one step = the sparse-GP criterion and its full gradient, one call of la_sgp_criterion."""
+    U, n = args.inducing, (args.n or 9568)
+    dtype = args.dtype or "f64"
+    steps = args.steps if args.steps is not None else 5
+    warmup = args.warmup if args.warmup is not None else 1
+    w = workloads.make_sgp(U, n, dtype=dtype)
+    dev = lambda a: torch.from_numpy(np.ascontiguousarray(a)).cuda()
+    Kuu, Kuf, kff, y = dev(w["Kuu"]), dev(w["Kuf"]), dev(w["Kff_diag"]), dev(w["y"])
+    ws = torch.empty(int(la.load().la_sgp_workspace_bytes(0 if dtype == "f32" else 1, U, n)), dtype=torch.uint8,
+                     device="cuda")
+    run = lambda: la.sgp_criterion(Kuu, Kuf, kff, y, w["noise_var"], workspace=ws)
+    for _ in range(warmup):
+        run()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        out = run()
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) * 1e3 / steps
+    # useful flops: two potrf (U^3 / 3 each), two potrf backward (2 U^3 each), trsm and its backward solve
+    # (U^2 n each), syrk (U^2 n), its backward product (2 U^2 n), the triangular outer product (U^2 n)
+    flops = (2.0 / 3.0 + 4.0) * U ** 3 + 6.0 * U * U * n
+    log(f"[bench] SGP U={U} n={n} {dtype}: {ms:.3f} ms per criterion+gradient, phi = {float(out['phi'][0]):.6f}")
+    cpu = None
+    if not args.no_cpu_baseline:
+        import oracle
+
+        Us, ns = max(1, U // 8), max(1, n // 8)
+        ws_ = workloads.make_sgp(Us, ns, dtype=dtype)
+        t0, passes = time.perf_counter(), 0
+        while True:
+            oracle.sgp_criterion(ws_["Kuu"], ws_["Kuf"], ws_["Kff_diag"], ws_["y"], ws_["noise_var"])
+            passes += 1
+            dt_cpu = time.perf_counter() - t0
+            if dt_cpu >= 10.0 or passes >= 50:
+                break
+        cpu = {"value": passes / dt_cpu, "unit": "evaluations/s", "cores": oracle.num_threads(), "kind": "oracle",
+               "sample": f"U={Us}, n={ns} (one eighth of each dimension, about 1/512 of the work), {passes} passes, "
+                         f"{dt_cpu:.2f} s in total"}
+    peak = PEAK_TFLOPS[dtype]
+    print(json.dumps({
+        "metric": "sparse-GP criterion+gradient evaluations/s", "value": 1e3 / ms, "unit": "evaluations/s", "n_gpus": 1,
+        "steps": steps, "warmup": warmup, "ms_per_step": ms, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": dtype, "data": "synthetic",
+        "config": {"workload": f"SGP: U={U} n={n} {dtype} (shape of the paper's 'power' experiment)"},
+        "gflops": flops / (ms * 1e-3) / 1e9, "useful_flops_per_step": flops,
+        "roofline": {"bound": "mfma", "kernel": "la_sgp_criterion (all launches)", "achieved": flops / (ms * 1e-3) / 1e12,
+                     "peak": peak, "unit": "TFLOP/s", "frac": flops / (ms * 1e-3) / 1e12 / peak, "traffic": None},
+        "cpu_baseline": cpu}), flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=None)
     ap.add_argument("--warmup", type=int, default=None)
-    ap.add_argument("--config", default="C2", choices=["C1", "C2", "C3", "C4", "C5"])
+    ap.add_argument("--config", default="C2", choices=["C1", "C2", "C3", "C4", "C5", "SGP"])
+    ap.add_argument("--inducing", type=int, default=3200, help="SGP only: number of inducing points U")
     ap.add_argument("--with-backward-ops", action="store_true",
                     help="C4 only: also run trmm / trsm / syrk backward on the step's operands")
     ap.add_argument("--dtype", default=None, choices=["f32", "f64"])
@@ -85,6 +139,8 @@ def main():
     torch.cuda.set_device(0)
 
     name = args.config
+    if name == "SGP":
+        return bench_sgp(args, la, torch, np, workloads)
     w = workloads.make(name, batch=args.batch, n=args.n, dtype=args.dtype)
     batch, n, dtype, m = w["batch"], w["n"], w["dtype"], w["m"]
     s = 4 if dtype == "f32" else 8

@@ -230,28 +230,24 @@ la_status launch_sumlogdiag(const T *L, T *out, int64_t batch, int n, hipStream_
     return launch_check("sumlogdiag");
 }
 
-// One workgroup per matrix: loss = 1/2 y.alpha + sum log l_ii, Lbar = -tril(alpha z^T) + diag(1/l_ii).
-// A wavefront writes whole rows of Lbar (no index arithmetic beyond the row loop).
+// loss = 1/2 y.alpha + sum log l_ii, Lbar = -tril(alpha z^T) + diag(1/l_ii).  A workgroup writes
+// GLUE_ROWS rows of Lbar, a wavefront whole rows (no index arithmetic beyond the row loop); the
+// first workgroup of a matrix also computes its loss.
 constexpr int GLUE_THREADS = 1024;
+constexpr int GLUE_ROWS = 64;
 template <typename T>
 __global__ __launch_bounds__(GLUE_THREADS) void k_gp_glue(const T *L, const T *y, const T *z, const T *alpha, T *loss,
-                                                          T *Lbar, int64_t batch, int n)
+                                                          T *Lbar, int64_t batch, int n, int chunks)
 {
     __shared__ double red[GLUE_THREADS / WAVE];
-    const int64_t b = blockIdx.x;
+    const int64_t b = blockIdx.x / chunks;
+    const int chunk = (int)(blockIdx.x % chunks);
     const T *lp = L + b * (int64_t)n * n;
     const T *yp = y + b * n, *zp = z + b * n, *ap = alpha + b * n;
     T *gp = Lbar + b * (int64_t)n * n;
     const int w = threadIdx.x / WAVE, l = threadIdx.x % WAVE;
-    double s = 0.0;
-    for (int i = threadIdx.x; i < n; i += GLUE_THREADS)
-        s += 0.5 * (double)yp[i] * (double)ap[i] + (double)log(lp[(int64_t)i * n + i]);
-#pragma unroll
-    for (int off = 32; off >= 1; off >>= 1)
-        s += __shfl_xor(s, off, WAVE);
-    if (l == 0)
-        red[w] = s;
-    for (int i = w; i < n; i += GLUE_THREADS / WAVE) {
+    const int r1 = min(n, (chunk + 1) * GLUE_ROWS);
+    for (int i = chunk * GLUE_ROWS + w; i < r1; i += GLUE_THREADS / WAVE) {
         const T ai = ap[i];
         const T dinv = T(1) / lp[(int64_t)i * n + i];
         T *row = gp + (int64_t)i * n;
@@ -262,6 +258,16 @@ __global__ __launch_bounds__(GLUE_THREADS) void k_gp_glue(const T *L, const T *y
             row[j] = g;
         }
     }
+    if (chunk != 0)
+        return;
+    double s = 0.0;
+    for (int i = threadIdx.x; i < n; i += GLUE_THREADS)
+        s += 0.5 * (double)yp[i] * (double)ap[i] + (double)log(lp[(int64_t)i * n + i]);
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1)
+        s += __shfl_xor(s, off, WAVE);
+    if (l == 0)
+        red[w] = s;
     __syncthreads();
     if (threadIdx.x == 0) {
         double t = 0.0;
@@ -277,9 +283,11 @@ la_status launch_gp_glue(const T *L, const T *y, const T *z, const T *alpha, T *
 {
     if (batch <= 0)
         return LA_OK;
-    if (batch > 0x7fffffffll)
+    const int chunks = n > 0 ? (n + GLUE_ROWS - 1) / GLUE_ROWS : 1;
+    if (batch * chunks > 0x7fffffffll)
         return LA_ERR_UNSUPPORTED;
-    hipLaunchKernelGGL((k_gp_glue<T>), dim3((unsigned)batch), dim3(GLUE_THREADS), 0, st, L, y, z, alpha, loss, Lbar, batch, n);
+    hipLaunchKernelGGL((k_gp_glue<T>), dim3((unsigned)(batch * chunks)), dim3(GLUE_THREADS), 0, st, L, y, z, alpha, loss,
+                       Lbar, batch, n, chunks);
     return launch_check("gp_glue");
 }
 

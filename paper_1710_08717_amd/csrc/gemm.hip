@@ -465,6 +465,98 @@ __global__ __launch_bounds__(256, 2) void k_gemm_fast(View<const T> A, View<cons
                            acc[x][y][v], alpha, beta, o);
 }
 
+// ---------------------------------------------------------------------------------------
+// Thin products: at most GEMV_N columns (matrix times a few vectors).  They are bound by reading A
+// once, which the tile kernels above are not built for.  A may be masked (triA); B and C are plain.
+//   A with k contiguous: one wavefront per row, lanes stride over k, shuffle reduction.
+//   A with i contiguous: a block takes 64 rows, its four wavefronts a quarter of the k range each
+//   (every load is 64 consecutive elements), LDS reduction.
+// ---------------------------------------------------------------------------------------
+constexpr int GEMV_N = 8;
+
+template <typename T>
+__global__ __launch_bounds__(256) void k_gemv(View<const T> A, View<const T> B, View<T> C, int64_t batch, int M, int N,
+                                              int K, T alpha, T beta, int triA, int tiles)
+{
+    __shared__ T red[4][64][GEMV_N];
+    const int64_t b = blockIdx.x / tiles;
+    const int tile = (int)(blockIdx.x % tiles);
+    const T *Ap = A.item(b);
+    const T *Bp = B.item(b);
+    T *Cp = C.item(b);
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+    T acc[GEMV_N];
+#pragma unroll
+    for (int j = 0; j < GEMV_N; ++j)
+        acc[j] = T(0);
+    if (A.cs == 1) {
+        const int i = tile * 4 + w;
+        if (i < M) {
+            const int kb = triA == 2 ? i : 0, ke = triA == 1 ? min(K, i + 1) : K;
+            const T *ar = Ap + (int64_t)i * A.rs;
+            for (int k = kb + lane; k < ke; k += 64) {
+                const T a = ar[k];
+#pragma unroll
+                for (int j = 0; j < GEMV_N; ++j)
+                    if (j < N)
+                        acc[j] = fma(a, Bp[(int64_t)k * B.rs + (int64_t)j * B.cs], acc[j]);
+            }
+#pragma unroll
+            for (int j = 0; j < GEMV_N; ++j) {
+#pragma unroll
+                for (int off = 32; off >= 1; off >>= 1)
+                    acc[j] += __shfl_xor(acc[j], off, WAVE);
+                if (lane == 0 && j < N) {
+                    T *c = Cp + (int64_t)i * C.rs + (int64_t)j * C.cs;
+                    const T upd = alpha * acc[j];
+                    *c = (beta == T(0)) ? upd : fma(beta, *c, upd);
+                }
+            }
+        }
+        return;
+    }
+    const int i = tile * 64 + lane;
+    if (i < M) {
+        const int kb = triA == 2 ? i : 0, ke = triA == 1 ? min(K, i + 1) : K;
+        for (int k = w; k < K; k += 4) {
+            if (k < kb || k >= ke)
+                continue;
+            const T a = Ap[(int64_t)i * A.rs + (int64_t)k * A.cs];
+#pragma unroll
+            for (int j = 0; j < GEMV_N; ++j)
+                if (j < N)
+                    acc[j] = fma(a, Bp[(int64_t)k * B.rs + (int64_t)j * B.cs], acc[j]);
+        }
+    }
+#pragma unroll
+    for (int j = 0; j < GEMV_N; ++j)
+        red[w][lane][j] = acc[j];
+    __syncthreads();
+    if (w == 0 && i < M) {
+#pragma unroll
+        for (int j = 0; j < GEMV_N; ++j)
+            if (j < N) {
+                const T sum = (red[0][lane][j] + red[1][lane][j]) + (red[2][lane][j] + red[3][lane][j]);
+                T *c = Cp + (int64_t)i * C.rs + (int64_t)j * C.cs;
+                const T upd = alpha * sum;
+                *c = (beta == T(0)) ? upd : fma(beta, *c, upd);
+            }
+    }
+}
+
+template <typename T>
+static la_status launch_gemv(View<const T> A, View<const T> B, View<T> C, int64_t batch, int M, int N, int K, T alpha,
+                             T beta, int triA, hipStream_t st)
+{
+    const int tiles = (A.cs == 1) ? (M + 3) / 4 : (M + 63) / 64;
+    const int64_t blocks = (int64_t)tiles * batch;
+    if (blocks > 0x7fffffffll)
+        return LA_ERR_UNSUPPORTED;
+    hipLaunchKernelGGL((k_gemv<T>), dim3((unsigned)blocks), dim3(256), 0, st, A, B, C, batch, M, N, K, alpha, beta, triA,
+                       tiles);
+    return launch_check("gemv");
+}
+
 template <typename T>
 static bool aligned16(const View<const T> &V, int64_t lead)
 {
@@ -519,6 +611,13 @@ la_status launch_gemm(View<const T> A, View<const T> B, View<T> C, int64_t batch
 {
     if (batch <= 0 || M <= 0 || N <= 0)
         return LA_OK;
+    // a few vectors on either side: one pass over the big operand
+    if (!o.maskC && !o.halfDiag && !o.min_tile64 && K > 0) {
+        if (N <= GEMV_N && o.triB == 0)
+            return launch_gemv<T>(A, B, C, batch, M, N, K, alpha, beta, o.triA, st);
+        if (M <= GEMV_N && o.triA == 0)  // C^T = B^T A^T
+            return launch_gemv<T>(B.t(), A.t(), C.t(), batch, N, M, K, alpha, beta, flip_tri(o.triB), st);
+    }
     // Keep the stores of C along its contiguous direction: if C is stored with i contiguous,
     // compute C^T = B^T A^T instead (a pure re-labelling of the views).
     if (C.cs != 1 && C.rs == 1) {
