@@ -30,8 +30,9 @@
  *    and at most 48 right-hand sides, syrk, gemm2, sumlogdiag, gp_glue) allocate
  *    nothing.  The blocked paths for larger n keep one scratch buffer per device
  *    (explicit inverses of the factor or of its diagonal blocks, a working copy of
- *    the triangle being factored or one work panel, at most 3*batch*n*n elements),
- *    allocated with
+ *    the triangle being factored or one work panel, at most 3*batch*n*n elements; and,
+ *    for products with few output tiles and a long inner dimension, a buffer of partial
+ *    results of at most 64 MB), allocated with
  *    hipMalloc on first use, grown on demand and kept until the process ends.
  *    Calls that use it must not overlap on different streams of one device.
  */

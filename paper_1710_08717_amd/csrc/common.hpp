@@ -304,6 +304,8 @@ struct GemmOpts {
     int reverse = 0;   // 1: schedule the tiles last-to-first (heavy tiles of triangular work first)
     int shells = 0;    // 1: square problem whose K range depends on max(i, j): schedule by shells
     int order = 0;     // tile enumeration, chosen by the launcher
+    int ksplit = 0;      // set by the launcher: the batch index also counts `ksplit` slices of a K range of `ktotal`
+    int ktotal = 0;
     int xcd_batch = 0;   // set by the launcher: batched launch, items dealt to the XCDs, tile-major inside
     int min_tile64 = 0;  // 1: no workgroup tiles smaller than 64 x 64 (a caller that updates C in place over <= 64 rows)
 };

@@ -18,6 +18,10 @@
 //    MFMA (v_mfma_f64_16x16x4_f64 / v_mfma_f32_16x16x4_f32).  Needs 16-byte aligned operands
 //    and K a multiple of 16.
 //  * k_gemm: element-wise staged fallback for everything else (ragged / unaligned shapes).
+#include <algorithm>
+#include <mutex>
+#include <vector>
+
 #include "common.hpp"
 
 namespace la {
@@ -395,8 +399,11 @@ __global__ __launch_bounds__(256, 2) void k_gemm_fast(View<const T> A, View<cons
     if ((o.maskC == 1 && j0 > i0 + BM - 1) || (o.maskC == 2 && i0 > j0 + BN - 1))
         return;
 
+    int Kl = K;  // slice s of a split K range: K elements from s * K on, fewer for the last slice
+    if (o.ksplit > 1)
+        Kl = min(K, o.ktotal - (int)(b % o.ksplit) * K);
     int kbeg, kend;
-    k_range(o, i0, j0, BM, BN, K, kbeg, kend);
+    k_range(o, i0, j0, BM, BN, Kl, kbeg, kend);
     kbeg = (kbeg / BK) * BK;
     kend = ((kend + BK - 1) / BK) * BK;  // K is a multiple of BK, so this stays <= K
 
@@ -557,6 +564,58 @@ static la_status launch_gemv(View<const T> A, View<const T> B, View<T> C, int64_
     return launch_check("gemv");
 }
 
+// ---------------------------------------------------------------------------------------
+// Split along K for products with few output tiles and a long K (A^T A of a tall A, the syrk of a
+// wide panel): the K range is cut into slices that run as extra batch items into a buffer of
+// partial results, which a second kernel sums in a fixed order (no atomics: results are
+// reproducible) while applying alpha, beta and the output mask.  The buffer belongs to the
+// library, one per device, grown on demand and never freed while work may still use it.
+// ---------------------------------------------------------------------------------------
+static std::mutex g_splitk_mutex;
+static void *g_splitk_buf[64] = {};
+static size_t g_splitk_bytes[64] = {};
+static std::vector<void *> g_splitk_parked;
+constexpr size_t SPLITK_MAX_BYTES = (size_t)64 << 20;
+
+static la_status splitk_buffer(size_t bytes, void **out)
+{
+    int dev = 0;
+    LA_HIP(hipGetDevice(&dev));
+    if (dev < 0 || dev >= 64)
+        return LA_ERR_UNSUPPORTED;
+    std::lock_guard<std::mutex> lock(g_splitk_mutex);
+    if (g_splitk_bytes[dev] < bytes) {
+        void *np = nullptr;
+        LA_HIP(hipMalloc(&np, bytes));
+        if (g_splitk_buf[dev])
+            g_splitk_parked.push_back(g_splitk_buf[dev]);
+        g_splitk_buf[dev] = np;
+        g_splitk_bytes[dev] = bytes;
+    }
+    *out = g_splitk_buf[dev];
+    return LA_OK;
+}
+
+template <typename T>
+__global__ __launch_bounds__(256) void k_splitk_reduce(const T *partial, View<T> C, int64_t batch, int M, int N,
+                                                       int splits, T alpha, T beta, GemmOpts o)
+{
+    const int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    const int64_t mn = (int64_t)M * N;
+    if (e >= batch * mn)
+        return;
+    const int64_t b = e / mn;
+    const int64_t r = e - b * mn;
+    const int i = (int)(r / N), j = (int)(r - (int64_t)i * N);
+    if ((o.maskC == 1 && i < j) || (o.maskC == 2 && i > j))
+        return;
+    const T *p = partial + b * splits * mn + r;
+    T s = T(0);
+    for (int q = 0; q < splits; ++q)
+        s += p[q * mn];
+    store_c<T>(C.item(b), C.rs, C.cs, i, j, M, N, s, alpha, beta, o);
+}
+
 template <typename T>
 static bool aligned16(const View<const T> &V, int64_t lead)
 {
@@ -647,6 +706,30 @@ la_status launch_gemm(View<const T> A, View<const T> B, View<T> C, int64_t batch
         };
         const int64_t wg128 = wgs(128), wg64 = wgs(64);
         const bool k64 = (K % 64 == 0);
+        if (!o.triA && !o.triB && !o.min_tile64 && !o.ksplit && wg64 <= 128 && K >= 2048 && A.nb2 == 1 && B.nb2 == 1 &&
+            C.nb2 == 1) {
+            int splits = (int)std::min<int64_t>(512 / wg64, K / 256);
+            const int Kc = ((K / 16 + splits - 1) / splits) * 16;
+            splits = (K + Kc - 1) / Kc;
+            const size_t bytes = (size_t)batch * splits * M * N * sizeof(T);
+            if (splits >= 2 && bytes <= SPLITK_MAX_BYTES) {
+                void *buf = nullptr;
+                LA_TRY(splitk_buffer(bytes, &buf));
+                const int64_t mn = (int64_t)M * N;
+                View<const T> As = A.level2((int64_t)Kc * A.cs, splits), Bs = B.level2((int64_t)Kc * B.rs, splits);
+                View<T> Ps{(T *)buf, (int64_t)splits * mn, N, 1, mn, splits};
+                GemmOpts ps;
+                ps.maskC = o.maskC;  // tiles beyond the kept triangle are not computed (nor read back)
+                ps.ksplit = splits;
+                ps.ktotal = K;
+                launch_fast<T, 64, 64, 16, 2>(akf, bkf, As, Bs, Ps, batch * splits, M, N, Kc, T(1), T(0), ps, st);
+                LA_TRY(launch_check("gemm_splitk"));
+                const int64_t total = batch * mn;
+                hipLaunchKernelGGL((k_splitk_reduce<T>), dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st,
+                                   (const T *)buf, C, batch, M, N, splits, alpha, beta, o);
+                return launch_check("splitk_reduce");
+            }
+        }
         int e;
         if (o.triA | o.triB) {
             // Triangular operands make the K range, hence the time, of a tile vary along the tile

@@ -333,7 +333,8 @@ def test_potrf_backward_ragged_large(la, orc, dtype):
 # ----------------------------------------------------------------------------
 @pytest.mark.parametrize("dtype", ["f64", "f32"])
 @pytest.mark.parametrize("trans", [False, True])
-@pytest.mark.parametrize("n,k", [(1, 1), (4, 9), (16, 32), (32, 64), (65, 17), (130, 200), (64, 0)])
+@pytest.mark.parametrize("n,k", [(1, 1), (4, 9), (16, 32), (32, 64), (65, 17), (130, 200), (64, 0), (50, 9568), (200, 2064),
+                                 (64, 4096)])
 def test_syrk_parity(la, orc, dtype, trans, n, k):
     batch = 3
     rng = np.random.default_rng(n + k)
@@ -350,7 +351,8 @@ def test_syrk_parity(la, orc, dtype, trans, n, k):
 @pytest.mark.parametrize("dtype", ["f64", "f32"])
 @pytest.mark.parametrize("ta", [False, True])
 @pytest.mark.parametrize("tb", [False, True])
-@pytest.mark.parametrize("m,n,k", [(1, 1, 1), (5, 7, 3), (64, 64, 64), (130, 70, 96), (256, 384, 128), (200, 64, 0)])
+@pytest.mark.parametrize("m,n,k", [(1, 1, 1), (5, 7, 3), (64, 64, 64), (130, 70, 96), (256, 384, 128), (200, 64, 0),
+                                   (96, 64, 4112), (3, 200, 2048), (200, 5, 2500)])
 def test_gemm2_parity(la, orc, dtype, ta, tb, m, n, k):
     batch = 3
     rng = np.random.default_rng(m + 3 * n + 7 * k)
