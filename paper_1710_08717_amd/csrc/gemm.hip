@@ -476,16 +476,18 @@ __global__ __launch_bounds__(256, 2) void k_gemm_fast(View<const T> A, View<cons
 // Thin products: at most GEMV_N columns (matrix times a few vectors).  They are bound by reading A
 // once, which the tile kernels above are not built for.  A may be masked (triA); B and C are plain.
 //   A with k contiguous: one wavefront per row, lanes stride over k, shuffle reduction.
-//   A with i contiguous: a block takes 64 rows, its four wavefronts a quarter of the k range each
+//   A with i contiguous: a block takes 64 rows, its eight wavefronts an eighth of the k range each
 //   (every load is 64 consecutive elements), LDS reduction.
 // ---------------------------------------------------------------------------------------
 constexpr int GEMV_N = 8;
+constexpr int GEMV_THREADS = 512;
 
 template <typename T>
-__global__ __launch_bounds__(256) void k_gemv(View<const T> A, View<const T> B, View<T> C, int64_t batch, int M, int N,
+__global__ __launch_bounds__(GEMV_THREADS) void k_gemv(View<const T> A, View<const T> B, View<T> C, int64_t batch, int M, int N,
                                               int K, T alpha, T beta, int triA, int tiles)
 {
-    __shared__ T red[4][64][GEMV_N];
+    constexpr int NW = GEMV_THREADS / 64;  // wavefronts: rows per block (k contiguous) or slices of k
+    __shared__ T red[NW][64][GEMV_N];
     const int64_t b = blockIdx.x / tiles;
     const int tile = (int)(blockIdx.x % tiles);
     const T *Ap = A.item(b);
@@ -497,7 +499,7 @@ __global__ __launch_bounds__(256) void k_gemv(View<const T> A, View<const T> B, 
     for (int j = 0; j < GEMV_N; ++j)
         acc[j] = T(0);
     if (A.cs == 1) {
-        const int i = tile * 4 + w;
+        const int i = tile * NW + w;
         if (i < M) {
             const int kb = triA == 2 ? i : 0, ke = triA == 1 ? min(K, i + 1) : K;
             const T *ar = Ap + (int64_t)i * A.rs;
@@ -525,7 +527,7 @@ __global__ __launch_bounds__(256) void k_gemv(View<const T> A, View<const T> B, 
     const int i = tile * 64 + lane;
     if (i < M) {
         const int kb = triA == 2 ? i : 0, ke = triA == 1 ? min(K, i + 1) : K;
-        for (int k = w; k < K; k += 4) {
+        for (int k = w; k < K; k += NW) {
             if (k < kb || k >= ke)
                 continue;
             const T a = Ap[(int64_t)i * A.rs + (int64_t)k * A.cs];
@@ -543,7 +545,10 @@ __global__ __launch_bounds__(256) void k_gemv(View<const T> A, View<const T> B, 
 #pragma unroll
         for (int j = 0; j < GEMV_N; ++j)
             if (j < N) {
-                const T sum = (red[0][lane][j] + red[1][lane][j]) + (red[2][lane][j] + red[3][lane][j]);
+                T sum = T(0);
+#pragma unroll
+                for (int q = 0; q < NW; ++q)
+                    sum += red[q][lane][j];
                 T *c = Cp + (int64_t)i * C.rs + (int64_t)j * C.cs;
                 const T upd = alpha * sum;
                 *c = (beta == T(0)) ? upd : fma(beta, *c, upd);
@@ -555,11 +560,11 @@ template <typename T>
 static la_status launch_gemv(View<const T> A, View<const T> B, View<T> C, int64_t batch, int M, int N, int K, T alpha,
                              T beta, int triA, hipStream_t st)
 {
-    const int tiles = (A.cs == 1) ? (M + 3) / 4 : (M + 63) / 64;
+    const int tiles = (A.cs == 1) ? (M + GEMV_THREADS / 64 - 1) / (GEMV_THREADS / 64) : (M + 63) / 64;
     const int64_t blocks = (int64_t)tiles * batch;
     if (blocks > 0x7fffffffll)
         return LA_ERR_UNSUPPORTED;
-    hipLaunchKernelGGL((k_gemv<T>), dim3((unsigned)blocks), dim3(256), 0, st, A, B, C, batch, M, N, K, alpha, beta, triA,
+    hipLaunchKernelGGL((k_gemv<T>), dim3((unsigned)blocks), dim3(GEMV_THREADS), 0, st, A, B, C, batch, M, N, K, alpha, beta, triA,
                        tiles);
     return launch_check("gemv");
 }
