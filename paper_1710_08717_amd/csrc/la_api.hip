@@ -291,7 +291,7 @@ static la_status potrf_t(int lower, int64_t batch, int n, const void *A, void *L
 //   trsm, n <= 128 and at most 48 vectors: one block-substitution kernel.
 //   trsm, n <= 64: product (in place) with the inverse of the single diagonal block.
 //   trsm, n <= 1024: explicit inverse of Lam (see inverse_build), then one masked GEMM.
-//   trsm, larger n: inverses of the 512 x 512 diagonal blocks, then block substitution with two
+//   trsm, larger n: inverses of the 1024 x 1024 diagonal blocks, then block substitution with two
 //     GEMMs per block (the block's solution goes through a scratch panel because a product
 //     cannot overwrite its own operand across several tiles).
 template <typename T>
@@ -346,7 +346,7 @@ static la_status tri_apply_t(bool solve, int lower, int trans, int rightside, do
         return launch_gemm<T>(fwd ? M : M.t(), src, X, batch, n, m, n, (T)alpha, T(0), o, st);
     }
 
-    constexpr int NBI = 512;
+    constexpr int NBI = 1024;
     LA_TRY(inverse_build<T>(Lam, Inv, Tmp, batch, n, NBI, st));
     if (!inplace || alpha != 1.0)
         LA_TRY(launch_copy<T>(Xin, X, batch, n, m, (T)alpha, 0, st));

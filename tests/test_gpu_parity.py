@@ -302,7 +302,7 @@ def test_trmm_parity(la, orc, dtype, lower, trans, rightside, n, m):
 @pytest.mark.parametrize("lower,trans,rightside", [(True, False, False), (True, True, False), (False, False, True),
                                                    (True, True, True)])
 def test_trsm_block_substitution_path(la, orc, dtype, lower, trans, rightside):
-    """n > 1024 takes the 512-block-inverse path; 1300 leaves a ragged last block."""
+    """n > 1024 takes the block-inverse path (blocks of 1024); 1300 leaves a ragged last block."""
     n, m, batch = 1300, 70, 1
     T = tri(n, batch, n, lower, dtype)
     rng = np.random.default_rng(n + m)
