@@ -1,0 +1,131 @@
+"""Seeded random shapes and flags through every exported operator, against the oracle.  The fixed
+lists of the other parity files sit on the dispatch thresholds; this one samples between them
+(odd sizes, unaligned leading dimensions, every flag combination) so that a path chosen by size
+arithmetic is exercised with sizes nobody picked by hand."""
+import sys
+
+import numpy as np
+import pytest
+
+import workloads
+
+pytestmark = pytest.mark.gpu
+TOL = {"f32": 2e-4, "f64": 1e-10}
+
+
+@pytest.fixture(scope="module")
+def la():
+    import torch
+
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    import paper_1710_08717_amd as la_mod
+
+    la_mod.load()
+    return la_mod
+
+
+def dev(a):
+    import torch
+
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+def host(t):
+    import torch
+
+    torch.cuda.synchronize()
+    return t.cpu().numpy()
+
+
+def relerr(x, ref):
+    x = np.asarray(x, dtype=np.float64).reshape(x.shape[0], -1)
+    ref = np.asarray(ref, dtype=np.float64).reshape(ref.shape[0], -1)
+    num = np.linalg.norm(x - ref, axis=1)
+    den = np.maximum(np.linalg.norm(ref, axis=1), 1e-300)
+    return float(np.max(num / den)) if len(num) else 0.0
+
+
+def spd(rng, batch, n, dt):
+    X = rng.standard_normal((batch, n, 2 * n))
+    A = X @ X.transpose(0, 2, 1) / (2 * n) + np.eye(n)
+    return (0.5 * (A + A.transpose(0, 2, 1))).astype(dt)
+
+
+def tri(rng, batch, n, lower, dt):
+    T = rng.standard_normal((batch, n, n)) * (0.5 / np.sqrt(n))
+    T = np.tril(T) if lower else np.triu(T)
+    idx = np.arange(n)
+    T[:, idx, idx] = 1.0 + rng.uniform(0.0, 1.0, size=(batch, n))
+    return T.astype(dt)
+
+
+def size(rng):
+    # a size class first, so that small, mid and blocked paths all get their share
+    lo, hi = [(1, 16), (17, 64), (65, 128), (129, 400), (401, 700)][int(rng.integers(0, 5))]
+    return int(rng.integers(lo, hi + 1))
+
+
+CASES = list(range(120))
+
+
+@pytest.mark.parametrize("case", CASES)
+def test_random_case(la, orc, case):
+    rng = np.random.default_rng(77000 + case)
+    dtype = "f64" if rng.integers(0, 2) else "f32"
+    dt = workloads.np_dtype(dtype)
+    tol = TOL[dtype]
+    n = size(rng)
+    batch = int(rng.integers(1, 5)) if n > 128 else int(rng.integers(1, 40))
+    lower, trans, right = bool(rng.integers(0, 2)), bool(rng.integers(0, 2)), bool(rng.integers(0, 2))
+    m = int(rng.integers(1, 90))
+    op = ["potrf", "backward", "trsm", "trmm", "syrk", "gemm2", "trsm_backward", "trmm_backward", "syrk_backward",
+          "potri"][case % 10]
+    sys.stderr.write(f"\n[gpu-case] random {case}: {op} {dtype} n={n} m={m} batch={batch} lower={lower} trans={trans} "
+                     f"right={right}\n")
+    sys.stderr.flush()
+    other = np.triu_indices(n, 1) if lower else np.tril_indices(n, -1)
+    if op == "potrf":
+        A = spd(rng, batch, n, dt)
+        assert relerr(host(la.potrf(dev(A), lower=lower)), orc.potrf(A, lower=lower)) <= tol
+    elif op == "backward":
+        F = orc.potrf(spd(rng, batch, n, dt), lower=lower).astype(dt)
+        G = rng.standard_normal((batch, n, n)).astype(dt)
+        ref = orc.potrf_backward(F, np.tril(G) if lower else np.triu(G), lower=lower)
+        out = host(la.potrf_backward(dev(F), dev(G), lower=lower))
+        assert np.array_equal(out, out.transpose(0, 2, 1)) and relerr(out, ref) <= tol
+    elif op in ("trsm", "trmm"):
+        T = tri(rng, batch, n, lower, dt)
+        A = rng.standard_normal((batch, m, n) if right else (batch, n, m)).astype(dt)
+        f_o, f_g = (orc.trsm, la.trsm) if op == "trsm" else (orc.trmm, la.trmm)
+        ref = f_o(T, A, lower=lower, trans=trans, rightside=right, alpha=0.5)
+        assert relerr(host(f_g(dev(T), dev(A), lower=lower, trans=trans, rightside=right, alpha=0.5)), ref) <= tol
+    elif op == "syrk":
+        A = rng.standard_normal((batch, m, n) if trans else (batch, n, m)).astype(dt)
+        assert relerr(host(la.syrk(dev(A), trans=trans, alpha=0.3)), orc.syrk(A, trans=trans, alpha=0.3)) <= tol
+    elif op == "gemm2":
+        k = int(rng.integers(1, 200))
+        A = rng.standard_normal((batch, k, n) if lower else (batch, n, k)).astype(dt)
+        B = rng.standard_normal((batch, m, k) if trans else (batch, k, m)).astype(dt)
+        ref = orc.gemm2(A, B, ta=lower, tb=trans, alpha=1.1)
+        assert relerr(host(la.gemm2(dev(A), dev(B), ta=lower, tb=trans, alpha=1.1)), ref) <= tol
+    elif op in ("trsm_backward", "trmm_backward"):
+        T = tri(rng, batch, n, lower, dt)
+        X = rng.standard_normal((batch, m, n) if right else (batch, n, m)).astype(dt)
+        G = rng.standard_normal(X.shape).astype(dt)
+        f_o, f_g = (orc.trsm_backward, la.trsm_backward) if op == "trsm_backward" else (orc.trmm_backward,
+                                                                                      la.trmm_backward)
+        ra, rl = f_o(T, X, G, lower=lower, trans=trans, rightside=right, alpha=0.8)
+        ga, gl = f_g(dev(T), dev(X), dev(G), lower=lower, trans=trans, rightside=right, alpha=0.8)
+        ga, gl = host(ga), host(gl)
+        assert relerr(ga, ra) <= tol and relerr(gl, rl) <= tol
+        assert np.all(gl[:, other[0], other[1]] == 0.0)
+    elif op == "syrk_backward":
+        A = rng.standard_normal((batch, m, n) if trans else (batch, n, m)).astype(dt)
+        G = (rng.standard_normal((batch, n, n)) / np.sqrt(n)).astype(dt)
+        ref = orc.syrk_backward(A, G, trans=trans, alpha=0.7)
+        assert relerr(host(la.syrk_backward(dev(A), dev(G), trans=trans, alpha=0.7)), ref) <= tol
+    else:
+        F = orc.potrf(spd(rng, batch, n, dt), lower=lower).astype(dt)
+        out = host(la.potri(dev(F), lower=lower))
+        assert relerr(out, orc.potri(F, lower=lower)) <= 10 * tol
