@@ -129,3 +129,26 @@ def test_random_case(la, orc, case):
         F = orc.potrf(spd(rng, batch, n, dt), lower=lower).astype(dt)
         out = host(la.potri(dev(F), lower=lower))
         assert relerr(out, orc.potri(F, lower=lower)) <= 10 * tol
+
+
+@pytest.mark.parametrize("dtype", ["f64", "f32"])
+def test_one_workgroup_kernels_with_many_matrices(la, orc, dtype):
+    """Thousands of workgroups of the LDS-resident kernels (several per compute unit in flight, many
+    rounds): potrf, trsm and the backward pass at sizes between 33 and 128."""
+    dt = workloads.np_dtype(dtype)
+    tol = TOL[dtype]
+    rng = np.random.default_rng(4242)
+    batch, n = 3000, 100
+    A = spd(rng, batch, n, dt)
+    Lr = orc.potrf(A)
+    assert relerr(host(la.potrf(dev(A))), Lr) <= tol
+    batch, n, m = 5000, 64, 3
+    T = tri(rng, batch, n, True, dt)
+    B = rng.standard_normal((batch, n, m)).astype(dt)
+    assert relerr(host(la.trsm(dev(T), dev(B), trans=True)), orc.trsm(T, B, trans=True)) <= tol
+    batch, n = 3000, 40
+    F = orc.potrf(spd(rng, batch, n, dt)).astype(dt)
+    G = np.tril(rng.standard_normal((batch, n, n))).astype(dt)
+    out = host(la.potrf_backward(dev(F), dev(G)))
+    assert np.array_equal(out, out.transpose(0, 2, 1))
+    assert relerr(out, orc.potrf_backward(F, G)) <= tol
