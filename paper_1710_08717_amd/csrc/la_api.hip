@@ -207,9 +207,28 @@ static la_status potrf_rec(View<T> Wk, View<T> L, int32_t *info, int off, int64_
 //   W = Li^T Z                     upper x lower = full
 //   Abar = 1/2 (W + W^T)
 template <typename T>
+static la_status backward_blocked(View<const T> Lam, View<const T> G, View<T> W, int64_t batch, int n, bool aliased,
+                                  hipStream_t st);
+
+// Largest block the inverse-based expression is used on.  Its 5 n^3 / 3 flops run in a few large
+// products; the blocked sweep needs 2 n^3 / 3 but in many smaller, dependent ones, so it pays once
+// the products of a block fill the chip: from about 8 M (fp64; 16 M fp32) matrix elements per
+// level over the whole batch (measured: 2048 for one matrix, 1024 for 4 to 8, 256 for 256).
+static int bwd_base(int64_t batch, size_t elem)
+{
+    const double budget = (elem == 4 ? 16.0 : 8.0) * 1048576.0;
+    int b = 2048;
+    while (b > 256 && (double)b * b * (double)batch > budget)
+        b /= 2;
+    return b;
+}
+
+template <typename T>
 static la_status backward_impl(View<const T> Lam, View<const T> G, View<T> W, int64_t batch, int n, bool aliased,
                                hipStream_t st)
 {
+    if (n > bwd_base(batch, sizeof(T)))
+        return backward_blocked<T>(Lam, G, W, batch, n, aliased, st);
     // n <= 16: 16 lanes per matrix, HBM bound.  16 < n <= 32: the register kernel has the higher
     // throughput (11 against 16 ns per fp32 matrix), the one-workgroup kernel the shorter latency
     // (25 against 37 us), so the batch size decides.
@@ -244,6 +263,55 @@ static la_status backward_impl(View<const T> Lam, View<const T> G, View<T> W, in
     ow.shells = 1;  // K range of tile (i, j) starts at max(i, j)
     LA_TRY(launch_gemm<T>(cv(Li).t(), cv(X), W, batch, n, n, n, T(1), T(0), ow, st));
     return launch_symmetrize<T>(W, batch, n, T(0.5), st);
+}
+
+template <typename T>
+static la_status tri_apply_v(bool solve, bool fwd, T alpha, int64_t batch, int n, int m, View<const T> Lam,
+                             View<const T> Xin, View<T> X, bool inplace, hipStream_t st);
+
+// ---------------------------------------------------------------------------------
+// Large n: reverse sweep over the blocked factorisation (section 4.2 names differentiating the
+// blocked algorithm itself as the cheaper route).  For the split
+//   L11 = chol(A11),  L21 = A21 L11^-T,  S = A22 - L21 L21^T,  L22 = chol(S)
+// the adjoints follow in reverse order (W holds Lbar's lower triangle on entry and the symmetric
+// Abar on return, block by block, in place):
+//   W22 <- backward(L22, W22)                       symmetric, both triangles
+//   W21 <- W21 - 2 W22 L21                          adjoint of the update S
+//   W21 <- 1/2 W21 L11^-1                           adjoint of the panel solve, halved because A21
+//                                                   enters the symmetric A twice
+//   W11 <- W11 - 2 tril(W21^T L21)                  the panel solve's effect on L11
+//   W11 <- backward(L11, W11)
+//   W12 <- W21^T
+// 2 n^3 / 3 flops at the blocked levels instead of 5 n^3 / 3 with the full inverse; blocks of at
+// most bwd_base(batch) rows take the inverse-based path.
+// ---------------------------------------------------------------------------------
+template <typename T>
+static la_status backward_rec(View<const T> Lam, View<T> W, int64_t batch, int n, hipStream_t st)
+{
+    if (n <= bwd_base(batch, sizeof(T)))
+        return backward_impl<T>(Lam, cv(W), W, batch, n, true, st);
+    const int n1 = (n / 2 + 127) / 128 * 128, n2 = n - n1;  // other splits within n / 8 of this one: no gain measured
+    View<T> W21 = W.sub(n1, 0), W22 = W.sub(n1, n1);
+    View<const T> L21 = Lam.sub(n1, 0);
+    LA_TRY(backward_rec<T>(Lam.sub(n1, n1), W22, batch, n2, st));
+    GemmOpts plain;
+    LA_TRY(launch_gemm<T>(cv(W22), L21, W21, batch, n2, n1, n2, T(-2), T(1), plain, st));
+    // rows of W21 are the vectors; x <- x L11^-1 is L11^-T applied to x^T
+    LA_TRY(tri_apply_v<T>(true, false, T(0.5), batch, n1, n2, Lam, cv(W21).t(), W21.t(), true, st));
+    GemmOpts om;
+    om.maskC = 1;
+    LA_TRY(launch_gemm<T>(cv(W21).t(), L21, W, batch, n1, n1, n2, T(-2), T(1), om, st));
+    LA_TRY(backward_rec<T>(Lam, W, batch, n1, st));
+    return launch_copy<T>(cv(W21).t(), W.sub(0, n1), batch, n1, n2, T(1), 0, st);
+}
+
+template <typename T>
+static la_status backward_blocked(View<const T> Lam, View<const T> G, View<T> W, int64_t batch, int n, bool aliased,
+                                  hipStream_t st)
+{
+    if (!aliased)  // lower triangle of Lbar into the output, which is then updated in place
+        LA_TRY(launch_copy<T>(G, W, batch, n, n, T(1), 1, st));
+    return backward_rec<T>(Lam, W, batch, n, st);
 }
 
 // ---------------------------------------------------------------------------------
@@ -295,26 +363,20 @@ static la_status potrf_t(int lower, int64_t batch, int n, const void *A, void *L
 //     GEMMs per block (the block's solution goes through a scratch panel because a product
 //     cannot overwrite its own operand across several tiles).
 template <typename T>
-static la_status tri_apply_t(bool solve, int lower, int trans, int rightside, double alpha, int64_t batch, int n, int m,
-                             const void *L, const void *A, void *B, hipStream_t st)
+static la_status tri_apply_v(bool solve, bool fwd, T alpha, int64_t batch, int n, int m, View<const T> Lam,
+                             View<const T> Xin, View<T> X, bool inplace, hipStream_t st)
 {
-    View<const T> Lam = tri_view<const T>((const T *)L, n, lower);
     const int64_t nm = (int64_t)n * m, nn = (int64_t)n * n;
-    View<const T> Xin = rightside ? View<const T>{(const T *)A, nm, 1, n} : View<const T>{(const T *)A, nm, m, 1};
-    View<T> X = rightside ? View<T>{(T *)B, nm, 1, n} : View<T>{(T *)B, nm, m, 1};
-    const bool inplace = (A == B);
-    const bool use_lt = (trans != 0) != (lower == 0);  // t(L) equals Lam^T
-    const bool fwd = (use_lt == (rightside != 0));
     GemmOpts o;
     o.triA = fwd ? 1 : 2;  // Lam keeps e >= k, Lam^T keeps e <= k; the same holds for their inverses
     o.reverse = fwd ? 1 : 0;  // heavy tile rows first: the last ones for a lower operand
 
     if (solve && n <= 128 && m <= 48)  // small: one workgroup per item does the whole substitution, no scratch
-        return launch_trsm_leaf16<T>(Lam, Xin, X, batch, n, m, (T)alpha, fwd, st);
+        return launch_trsm_leaf16<T>(Lam, Xin, X, batch, n, m, alpha, fwd, st);
 
     if (solve && n <= NB) {  // inverse of the single block, then one product in place
-        if (!inplace || alpha != 1.0)
-            LA_TRY(launch_copy<T>(Xin, X, batch, n, m, (T)alpha, 0, st));
+        if (!inplace || alpha != T(1))
+            LA_TRY(launch_copy<T>(Xin, X, batch, n, m, alpha, 0, st));
         View<T> Inv;
         LA_TRY(scratch_views<T>(batch, n, 1, &Inv));
         LA_TRY(launch_tri_inverse128<T>(Lam, Inv, batch, n, st));
@@ -330,7 +392,9 @@ static la_status tri_apply_t(bool solve, int lower, int trans, int rightside, do
     LA_TRY(scratch_get(per_item * batch * sizeof(T), &sp));
     T *base = (T *)sp;
     View<T> Inv{base, nn, n, 1}, Tmp{base + (solve ? batch * nn : 0), nn, n, 1};
-    View<T> S{base + (solve ? 2 * batch * nn : 0), nm, X.rs, X.cs};
+    // a compact panel whose fast index is the one X has
+    View<T> S = X.rs <= X.cs ? View<T>{base + (solve ? 2 * batch * nn : 0), nm, 1, n}
+                             : View<T>{base + (solve ? 2 * batch * nn : 0), nm, m, 1};
 
     if (!solve || n <= 1024) {
         View<const T> M = Lam;
@@ -343,13 +407,13 @@ static la_status tri_apply_t(bool solve, int lower, int trans, int rightside, do
             LA_TRY(launch_copy<T>(Xin, S, batch, n, m, T(1), 0, st));
             src = cv(S);
         }
-        return launch_gemm<T>(fwd ? M : M.t(), src, X, batch, n, m, n, (T)alpha, T(0), o, st);
+        return launch_gemm<T>(fwd ? M : M.t(), src, X, batch, n, m, n, alpha, T(0), o, st);
     }
 
     constexpr int NBI = 1024;
     LA_TRY(inverse_build<T>(Lam, Inv, Tmp, batch, n, NBI, st));
-    if (!inplace || alpha != 1.0)
-        LA_TRY(launch_copy<T>(Xin, X, batch, n, m, (T)alpha, 0, st));
+    if (!inplace || alpha != T(1))
+        LA_TRY(launch_copy<T>(Xin, X, batch, n, m, alpha, 0, st));
     const int nblk = (n + NBI - 1) / NBI;
     GemmOpts plain;
     for (int step = 0; step < nblk; ++step) {
@@ -369,6 +433,19 @@ static la_status tri_apply_t(bool solve, int lower, int trans, int rightside, do
         LA_TRY(launch_copy<T>(cv(S), Xj, batch, nbj, m, T(1), 0, st));
     }
     return LA_OK;
+}
+
+template <typename T>
+static la_status tri_apply_t(bool solve, int lower, int trans, int rightside, double alpha, int64_t batch, int n, int m,
+                             const void *L, const void *A, void *B, hipStream_t st)
+{
+    View<const T> Lam = tri_view<const T>((const T *)L, n, lower);
+    const int64_t nm = (int64_t)n * m;
+    View<const T> Xin = rightside ? View<const T>{(const T *)A, nm, 1, n} : View<const T>{(const T *)A, nm, m, 1};
+    View<T> X = rightside ? View<T>{(T *)B, nm, 1, n} : View<T>{(T *)B, nm, m, 1};
+    const bool use_lt = (trans != 0) != (lower == 0);  // t(L) equals Lam^T
+    const bool fwd = (use_lt == (rightside != 0));
+    return tri_apply_v<T>(solve, fwd, (T)alpha, batch, n, m, Lam, Xin, X, A == B, st);
 }
 
 template <typename T>

@@ -328,6 +328,30 @@ def test_potrf_backward_ragged_large(la, orc, dtype):
     assert relerr(out, orc.potrf_backward(Lh, G)) <= TOL[dtype]
 
 
+@pytest.mark.parametrize("dtype", ["f64", "f32"])
+@pytest.mark.parametrize("lower", [True, False])
+@pytest.mark.parametrize("batch,n", [(40, 600), (3, 1300), (160, 300)])
+def test_potrf_backward_blocked_sweep(la, orc, dtype, lower, batch, n):
+    """Sizes above the largest block of the inverse-based expression for their batch (256 rows for
+    40 and more matrices, 1024 for 3): the reverse sweep over the blocked factorisation, two levels
+    deep for n = 600, with a trailing block small enough for the one-workgroup kernel for n = 300;
+    once into a separate output, once over Lbar itself."""
+    rng = np.random.default_rng(batch * n)
+    F = np.tril(rng.standard_normal((batch, n, n))) / np.sqrt(n) + np.eye(n)
+    G = np.tril(rng.standard_normal((batch, n, n)))
+    if not lower:
+        F, G = F.transpose(0, 2, 1), G.transpose(0, 2, 1)
+    F, G = np.ascontiguousarray(F).astype(npdt(dtype)), np.ascontiguousarray(G).astype(npdt(dtype))
+    ref = orc.potrf_backward(F, G, lower=lower)
+    f, g = dev(F), dev(G)
+    out = host(la.potrf_backward(f, g, lower=lower))
+    assert np.array_equal(host(g), G)  # the input is left alone
+    assert np.array_equal(out, out.transpose(0, 2, 1))
+    assert relerr(out, ref) <= TOL[dtype]
+    again = host(la.potrf_backward(f, g, lower=lower, out=g))
+    assert np.array_equal(again, out)
+
+
 # ----------------------------------------------------------------------------
 # syrk / sumlogdiag / GP glue
 # ----------------------------------------------------------------------------
