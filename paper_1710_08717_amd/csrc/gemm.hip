@@ -423,24 +423,15 @@ __global__ __launch_bounds__(256, 2) void k_gemm_fast(View<const T> A, View<cons
         for (int y = 0; y < TN; ++y)
             acc[x][y] = acc_t{0, 0, 0, 0};
 
-    // Software pipeline: slab s+1 is fetched into registers while slab s is multiplied out of LDS.
-    // With two LDS buffers one barrier per slab is enough (the barrier of slab s+1 separates the
-    // reads of slab s from the overwrite by slab s+2); with one buffer a second barrier is needed.
+    // Software pipeline.  Slabs travel global memory -> registers -> LDS -> matrix cores.
+    // Two LDS buffers: while slab s is multiplied out of one buffer, slab s+1 (already in
+    // registers) is written into the other and slab s+2 is requested from memory, so the only
+    // thing between two blocks of MFMAs is one barrier: it orders the reads of slab s before
+    // the overwrite by slab s+2 and the writes of slab s+1 before their reads.
+    // One LDS buffer: slab s+1 is fetched into registers while slab s is multiplied, and written
+    // once everybody is done reading (two barriers per slab).
     V ra[SA::NCH], rb[SB::NCH];
-    if (kbeg < kend) {
-        slab_fetch<T, BM, BK, AKF>(ra, Ap, A.rs, A.cs, i0, M, kbeg);
-        slab_fetch<T, BN, BK, BKF>(rb, Bp, B.cs, B.rs, j0, N, kbeg);
-    }
-    int buf = 0;
-    for (int k0 = kbeg; k0 < kend; k0 += BK) {
-        slab_commit<T, BM, BK, AKF>(sA[buf], ra, i0, k0, o.triA);
-        slab_commit<T, BN, BK, BKF>(sB[buf], rb, j0, k0, triB_o);
-        __syncthreads();
-        if (k0 + BK < kend) {
-            slab_fetch<T, BM, BK, AKF>(ra, Ap, A.rs, A.cs, i0, M, k0 + BK);
-            slab_fetch<T, BN, BK, BKF>(rb, Bp, B.cs, B.rs, j0, N, k0 + BK);
-        }
-        const T *a_s = sA[buf], *b_s = sB[buf];
+    auto multiply = [&](const T *a_s, const T *b_s) {
 #pragma unroll
         for (int kk = 0; kk < BK; kk += 4) {
             T af[TM], bf[TN];
@@ -456,10 +447,49 @@ __global__ __launch_bounds__(256, 2) void k_gemm_fast(View<const T> A, View<cons
                 for (int y = 0; y < TN; ++y)
                     acc[x][y] = MF::run(af[x], bf[y], acc[x][y]);
         }
-        if constexpr (NBUF == 1)
+    };
+    if constexpr (NBUF == 2) {
+        if (kbeg < kend) {
+            slab_fetch<T, BM, BK, AKF>(ra, Ap, A.rs, A.cs, i0, M, kbeg);
+            slab_fetch<T, BN, BK, BKF>(rb, Bp, B.cs, B.rs, j0, N, kbeg);
+            slab_commit<T, BM, BK, AKF>(sA[0], ra, i0, kbeg, o.triA);
+            slab_commit<T, BN, BK, BKF>(sB[0], rb, j0, kbeg, triB_o);
+            if (kbeg + BK < kend) {
+                slab_fetch<T, BM, BK, AKF>(ra, Ap, A.rs, A.cs, i0, M, kbeg + BK);
+                slab_fetch<T, BN, BK, BKF>(rb, Bp, B.cs, B.rs, j0, N, kbeg + BK);
+            }
             __syncthreads();
-        else
+        }
+        int buf = 0;
+        for (int k0 = kbeg; k0 < kend; k0 += BK) {
+            if (k0 + BK < kend) {
+                slab_commit<T, BM, BK, AKF>(sA[buf ^ 1], ra, i0, k0 + BK, o.triA);
+                slab_commit<T, BN, BK, BKF>(sB[buf ^ 1], rb, j0, k0 + BK, triB_o);
+            }
+            if (k0 + 2 * BK < kend) {
+                slab_fetch<T, BM, BK, AKF>(ra, Ap, A.rs, A.cs, i0, M, k0 + 2 * BK);
+                slab_fetch<T, BN, BK, BKF>(rb, Bp, B.cs, B.rs, j0, N, k0 + 2 * BK);
+            }
+            multiply(sA[buf], sB[buf]);
+            __syncthreads();
             buf ^= 1;
+        }
+    } else {
+        if (kbeg < kend) {
+            slab_fetch<T, BM, BK, AKF>(ra, Ap, A.rs, A.cs, i0, M, kbeg);
+            slab_fetch<T, BN, BK, BKF>(rb, Bp, B.cs, B.rs, j0, N, kbeg);
+        }
+        for (int k0 = kbeg; k0 < kend; k0 += BK) {
+            slab_commit<T, BM, BK, AKF>(sA[0], ra, i0, k0, o.triA);
+            slab_commit<T, BN, BK, BKF>(sB[0], rb, j0, k0, triB_o);
+            __syncthreads();
+            if (k0 + BK < kend) {
+                slab_fetch<T, BM, BK, AKF>(ra, Ap, A.rs, A.cs, i0, M, k0 + BK);
+                slab_fetch<T, BN, BK, BKF>(rb, Bp, B.cs, B.rs, j0, N, k0 + BK);
+            }
+            multiply(sA[0], sB[0]);
+            __syncthreads();
+        }
     }
 
 #pragma unroll
