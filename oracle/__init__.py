@@ -49,6 +49,7 @@ def _load():
         lib.orc_potri_backward.argtypes = [i32, i64, i32, dp, dp, dp, dp]
         lib.orc_sgp_criterion.argtypes = [i32, i32, dp, dp, dp, dp, f64, dp, dp, dp, dp, dp, dp]
         lib.orc_sumlogdiag.argtypes = [i64, i32, dp, dp]
+        lib.orc_kalman_filter.argtypes = [i64, i32, i32, i32, i32, dp, dp, dp, dp, dp, dp, dp, dp, dp, dp, ip]
         lib.orc_gemm2.argtypes = [i32, i32, f64, i64, i32, i32, i32, dp, dp, dp]
         lib.orc_gp_glue.argtypes = [i64, i32, dp, dp, dp, dp, dp, dp]
         lib.orc_llt_entry.argtypes = [i32, i32, dp, i32, i32]
@@ -244,6 +245,28 @@ def sgp_criterion(Kuu, Kuf, Kff_diag, y, noise_var):
                                      _p(lb)), "sgp_criterion")
     out["phi"], out["noise_bar"] = float(phi[0]), float(lb[0])
     return out
+
+
+def kalman_filter(A, B, Sh, Sv, mu0, S0, v, want_states=True):
+    """Section 3.4.  Parameters either without a batch axis (shared by all sequences) or with
+    the batch axis of v ([batch, T, dv]).  Returns (nll [batch], f [batch, T, dh] or None,
+    F [batch, T, dh, dh] or None, info [batch])."""
+    v = _f64(v)
+    batch, T, dv = v.shape
+    A, B, Sh, Sv, mu0, S0 = (_f64(x) for x in (A, B, Sh, Sv, mu0, S0))
+    shared = A.ndim == 2
+    dh = A.shape[-1]
+    pb = () if shared else (batch,)
+    assert A.shape == pb + (dh, dh) and B.shape == pb + (dv, dh) and Sh.shape == pb + (dh, dh)
+    assert Sv.shape == pb + (dv, dv) and mu0.shape == pb + (dh,) and S0.shape == pb + (dh, dh)
+    nll = np.empty(batch)
+    f = np.empty((batch, T, dh)) if want_states else None
+    F = np.empty((batch, T, dh, dh)) if want_states else None
+    info = np.zeros(batch, dtype=np.int32)
+    _check(_load().orc_kalman_filter(batch, T, dh, dv, int(shared), _p(A), _p(B), _p(Sh), _p(Sv), _p(mu0), _p(S0),
+                                     _p(v), _p(f) if want_states else None, _p(F) if want_states else None, _p(nll),
+                                     info.ctypes.data_as(ctypes.POINTER(ctypes.c_int32))), "kalman_filter")
+    return nll, f, F, info
 
 
 def sumlogdiag(L):

@@ -931,6 +931,153 @@ double orc_ltlbar_entry(int n, const double *L, const double *Lbar, int i, int j
 }
 
 /* Number of threads the batch loops above will use. */
+/* ------------------------------------------------------------------------- */
+/* Kalman filter (section 3.4, "Kalman Filtering").  Gaussian linear dynamical system
+ *   h_t ~ N(A h_{t-1}, S_h),   v_t ~ N(B h_t, S_v),   h_0 ~ N(mu_0, S_0),
+ * h of dimension dh, v of dimension dv.  For t = 0 the predicted state is the prior
+ * (mu_h = mu_0, S_hh = S_0); for t > 0
+ *   mu_h = A f_{t-1},  S_hh = A F_{t-1} A^T + S_h.
+ * Then, in the order of the section's equations:
+ *   mu_v = B mu_h,  S_vv = B S_hh B^T + S_v = L L^T (potrf),
+ *   K = (S_hh B^T) L^{-T} L^{-1}   (two right-side trsm),
+ *   f_t = mu_h + K (v_t - mu_v),
+ *   F_t = (I - K B) S_hh (I - K B)^T + K S_v K^T.
+ * The negative log likelihood the section speaks of is the sum over t of
+ * -log N(v_t | mu_v, S_vv) = dv/2 log(2 pi) + sum_i log L_ii + 1/2 |L^{-1}(v_t - mu_v)|^2
+ * (the formula is not printed there; it is the density of the predicted observation).
+ *
+ * Parameters: one set for every sequence (shared != 0) or one per sequence.
+ * v: [batch, T, dv].  f: [batch, T, dh] or NULL.  F: [batch, T, dh, dh] or NULL.
+ * nll: [batch].  info: [batch] or NULL; 0, or 1 + the first t whose S_vv has a pivot <= 0. */
+static void matmul_nn(int m, int n, int k, const double *X, const double *Y, double *Z)
+{
+    for (int i = 0; i < m; ++i)
+        for (int j = 0; j < n; ++j) {
+            double s = 0.0;
+            for (int p = 0; p < k; ++p)
+                s += X[i * k + p] * Y[p * n + j];
+            Z[i * n + j] = s;
+        }
+}
+static void matmul_nt(int m, int n, int k, const double *X, const double *Y, double *Z)
+{
+    /* Z = X Y^T, X is m x k, Y is n x k */
+    for (int i = 0; i < m; ++i)
+        for (int j = 0; j < n; ++j) {
+            double s = 0.0;
+            for (int p = 0; p < k; ++p)
+                s += X[i * k + p] * Y[j * k + p];
+            Z[i * n + j] = s;
+        }
+}
+
+static void kalman_one(int T, int dh, int dv, const double *A, const double *B, const double *Sh,
+                       const double *Sv, const double *mu0, const double *S0, const double *v, double *f,
+                       double *F, double *nll, int32_t *info, double *w)
+{
+    /* work space: all dh x dh unless noted */
+    double *fcur = w, *Fcur = fcur + dh, *muh = Fcur + dh * dh, *Shh = muh + dh, *T1 = Shh + dh * dh;
+    double *muv = T1 + dh * dh;                 /* dv */
+    double *M = muv + dv;                       /* dh x dv: S_hh B^T */
+    double *Svv = M + dh * dv, *L = Svv + dv * dv; /* dv x dv */
+    double *K = L + dv * dv;                    /* dh x dv */
+    double *delta = K + dh * dv, *z = delta + dv; /* dv */
+    double *G = z + dv, *T2 = G + dh * dh;      /* dh x dh */
+    double *T3 = T2 + dh * dh;                  /* dv x dh: S_v K^T */
+    double total = 0.0;
+    int32_t bad = 0;
+    for (int t = 0; t < T; ++t) {
+        if (t == 0) {
+            memcpy(muh, mu0, sizeof(double) * dh);
+            memcpy(Shh, S0, sizeof(double) * dh * dh);
+        } else {
+            matmul_nn(dh, 1, dh, A, fcur, muh);
+            matmul_nt(dh, dh, dh, Fcur, A, T1);  /* F A^T */
+            matmul_nn(dh, dh, dh, A, T1, Shh);
+            for (int i = 0; i < dh * dh; ++i)
+                Shh[i] += Sh[i];
+        }
+        matmul_nn(dv, 1, dh, B, muh, muv);
+        matmul_nt(dh, dv, dh, Shh, B, M);
+        matmul_nn(dv, dv, dh, B, M, Svv);
+        for (int i = 0; i < dv * dv; ++i)
+            Svv[i] += Sv[i];
+        int32_t inf = 0;
+        potrf_one_lower(dv, Svv, L, &inf);
+        if (inf != 0 && bad == 0)
+            bad = t + 1;
+        /* K = M L^-T L^-1: X L^T = M, then K L = X */
+        trsm_one(1, 1, 1, 1.0, dv, dh, L, M, K);
+        trsm_one(1, 0, 1, 1.0, dv, dh, L, K, K);
+        for (int i = 0; i < dv; ++i)
+            delta[i] = v[(size_t)t * dv + i] - muv[i];
+        for (int i = 0; i < dh; ++i) {
+            double s = muh[i];
+            for (int j = 0; j < dv; ++j)
+                s += K[i * dv + j] * delta[j];
+            fcur[i] = s;
+        }
+        matmul_nn(dh, dh, dv, K, B, G);
+        for (int i = 0; i < dh; ++i)
+            for (int j = 0; j < dh; ++j)
+                G[i * dh + j] = (i == j ? 1.0 : 0.0) - G[i * dh + j];
+        matmul_nt(dh, dh, dh, Shh, G, T2);   /* S_hh (I - K B)^T */
+        matmul_nn(dh, dh, dh, G, T2, Fcur);
+        matmul_nt(dv, dh, dv, Sv, K, T3);    /* S_v K^T */
+        matmul_nn(dh, dh, dv, K, T3, T2);
+        for (int i = 0; i < dh * dh; ++i)
+            Fcur[i] += T2[i];
+        /* likelihood term */
+        trsm_one(1, 0, 0, 1.0, dv, 1, L, delta, z);
+        double q = 0.0, ld = 0.0;
+        for (int i = 0; i < dv; ++i) {
+            q += z[i] * z[i];
+            ld += log(L[i * dv + i]);
+        }
+        total += 0.5 * dv * log(2.0 * M_PI) + ld + 0.5 * q;
+        if (f)
+            memcpy(f + (size_t)t * dh, fcur, sizeof(double) * dh);
+        if (F)
+            memcpy(F + (size_t)t * dh * dh, Fcur, sizeof(double) * dh * dh);
+    }
+    *nll = total;
+    if (info)
+        *info = bad;
+}
+
+int orc_kalman_filter(int64_t batch, int T, int dh, int dv, int shared, const double *A, const double *B,
+                      const double *Sh, const double *Sv, const double *mu0, const double *S0, const double *v,
+                      double *f, double *F, double *nll, int32_t *info)
+{
+    if (batch < 0 || T < 0 || dh < 1 || dv < 1)
+        return ORC_ERR_INVALID_ARG;
+    if (batch == 0)
+        return ORC_OK;
+    if (!A || !B || !Sh || !Sv || !mu0 || !S0 || !nll || (T > 0 && !v))
+        return ORC_ERR_INVALID_ARG;
+    size_t words = (size_t)dh * 2 + (size_t)dh * dh * 6 + (size_t)dv * 3 + (size_t)dh * dv * 3 + (size_t)dv * dv * 2;
+    int fail = 0;
+#pragma omp parallel
+    {
+        double *w = (double *)malloc(sizeof(double) * words);
+        if (!w) {
+#pragma omp atomic write
+            fail = 1;
+        }
+#pragma omp for schedule(static)
+        for (int64_t b = 0; b < batch; ++b) {
+            if (!w)
+                continue;
+            size_t pb = shared ? 0 : (size_t)b;
+            kalman_one(T, dh, dv, A + pb * dh * dh, B + pb * dv * dh, Sh + pb * dh * dh, Sv + pb * dv * dv,
+                       mu0 + pb * dh, S0 + pb * dh * dh, v + (size_t)b * T * dv, f ? f + (size_t)b * T * dh : NULL,
+                       F ? F + (size_t)b * T * dh * dh : NULL, nll + b, info ? info + b : NULL, w);
+        }
+        free(w);
+    }
+    return fail ? ORC_ERR_INVALID_ARG : ORC_OK;
+}
+
 int orc_num_threads(void)
 {
 #ifdef _OPENMP

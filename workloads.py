@@ -141,6 +141,41 @@ def make_sgp(U, n, dims=4, dtype="f64", lengthscale=1.0, jitter=0.1, noise_var=0
             "Kff_diag": np.ones(n, dtype=dt), "y": rng.standard_normal(n).astype(dt), "noise_var": float(noise_var)}
 
 
+def make_kalman(batch, T, dh, dv, dtype="f32", shared=True, seed=0):
+    """Synthetic inputs of the Kalman filter (section 3.4): a Gaussian linear dynamical system
+    with a stable transition matrix (0.9 times a random rotation plus a small perturbation),
+    an emission matrix ~ N(0, 1/dh), covariances W W^T / (2 d) + c I (c = 0.05 for the state
+    noise, 0.2 for the observation noise, 1 for the prior), mu_0 ~ N(0, 1), and observations
+    drawn from that very model -- the use the section describes is fitting one model to many
+    time series, so the parameters are shared by default; ``shared=False`` draws one set per
+    sequence."""
+    rng = np.random.default_rng(SEED0 + 7000 + 131 * dh + 17 * dv + seed)
+    pb = 1 if shared else batch
+
+    def spd(d, c):
+        W = rng.standard_normal((pb, d, 2 * d))
+        return W @ W.transpose(0, 2, 1) / (4.0 * d) + c * np.eye(d)
+
+    Q, _ = np.linalg.qr(rng.standard_normal((pb, dh, dh)))
+    A = 0.9 * Q + 0.02 * rng.standard_normal((pb, dh, dh))
+    B = rng.standard_normal((pb, dv, dh)) / np.sqrt(dh)
+    Sh, Sv, S0 = spd(dh, 0.05), spd(dv, 0.2), spd(dh, 1.0)
+    mu0 = rng.standard_normal((pb, dh))
+    # simulate
+    ch, cv, c0 = np.linalg.cholesky(Sh), np.linalg.cholesky(Sv), np.linalg.cholesky(S0)
+    h = mu0 + np.einsum("bij,bj->bi", c0, rng.standard_normal((batch, dh)))
+    v = np.empty((batch, T, dv))
+    for t in range(T):
+        if t > 0:
+            h = np.einsum("bij,bj->bi", A, h) + np.einsum("bij,bj->bi", ch, rng.standard_normal((batch, dh)))
+        v[:, t] = np.einsum("bij,bj->bi", B, h) + np.einsum("bij,bj->bi", cv, rng.standard_normal((batch, dv)))
+    dt = np_dtype(dtype)
+    sq = (lambda x: x[0]) if shared else (lambda x: x)
+    return {"batch": batch, "T": T, "dh": dh, "dv": dv, "dtype": dtype, "shared": shared,
+            "A": sq(A).astype(dt), "B": sq(B).astype(dt), "Sh": sq(Sh).astype(dt), "Sv": sq(Sv).astype(dt),
+            "mu0": sq(mu0).astype(dt), "S0": sq(S0).astype(dt), "v": v.astype(dt)}
+
+
 def cond_estimate(A, sample=4):
     """2-norm condition numbers of the first ``sample`` matrices (eigvalsh, fp64)."""
     A = np.asarray(A, dtype=np.float64).reshape(-1, A.shape[-2], A.shape[-1])[:sample]
