@@ -187,6 +187,24 @@ la_status la_sgp_criterion(la_dtype dt, int U, int n, const void *Kuu, const voi
                            void *Kff_diag_bar, void *y_bar, void *noise_bar, void *workspace,
                            size_t workspace_bytes, void *stream);
 
+/* Kalman filter over a batch of sequences (section 3.4): Gaussian linear dynamical system
+ *   h_t ~ N(A h_{t-1}, S_h),  v_t ~ N(B h_t, S_v),  h_0 ~ N(mu_0, S_0),   h in R^dh, v in R^dv.
+ * For every sequence and t = 0 .. T-1, in the order of the section's equations:
+ *   mu_h = A f_{t-1}, S_hh = A F_{t-1} A^T + S_h   (t = 0: mu_h = mu_0, S_hh = S_0);
+ *   mu_v = B mu_h;  S_vv = B S_hh B^T + S_v = L L^T;  K = (S_hh B^T) L^{-T} L^{-1};
+ *   f_t = mu_h + K (v_t - mu_v);  F_t = (I - K B) S_hh (I - K B)^T + K S_v K^T;
+ * and the negative log likelihood the section trains on,
+ *   nll = sum_t [ dv/2 log 2 pi + sum_i log L_ii + 1/2 |L^{-1} (v_t - mu_v)|^2 ].
+ * 1 <= dh, dv <= 16 (anything else: LA_ERR_UNSUPPORTED).  All pointers are device memory, row-major.
+ * Parameters A [dh,dh], B [dv,dh], S_h [dh,dh], S_v [dv,dv], mu_0 [dh], S_0 [dh,dh]: one set for every
+ * sequence (shared_params != 0) or one per sequence with a leading [batch] axis.  v: [batch, T, dv].
+ * Outputs: nll [batch]; f [batch, T, dh] or NULL; F [batch, T, dh, dh] or NULL; info: NULL or int32
+ * [batch]: 0, or 1 + the first step whose S_vv has a pivot that is not > 0 (that sequence's outputs
+ * are then unspecified from that step on; the call still returns LA_OK).  No scratch memory. */
+la_status la_kalman_filter(la_dtype dt, int64_t batch, int T, int dh, int dv, int shared_params, const void *A,
+                           const void *B, const void *Sh, const void *Sv, const void *mu0, const void *S0,
+                           const void *v, void *f, void *F, void *nll, int32_t *info, void *stream);
+
 /* Text of the last HIP error seen by this thread's calls (host pointer, never NULL). */
 const char *la_last_error(void);
 

@@ -15,6 +15,7 @@ from .binding import (  # noqa: F401
     load,
     potrf,
     sgp_criterion,
+    kalman_filter,
     potri,
     potri_backward,
     potrf_backward,
@@ -27,5 +28,5 @@ from .binding import (  # noqa: F401
     trsm_backward,
 )
 
-__all__ = ["potrf", "potrf_backward", "trsm", "trmm", "syrk", "trsm_backward", "trmm_backward", "syrk_backward", "gemm2_backward", "potri", "potri_backward", "sgp_criterion", "sumlogdiag",
+__all__ = ["potrf", "potrf_backward", "trsm", "trmm", "syrk", "trsm_backward", "trmm_backward", "syrk_backward", "gemm2_backward", "potri", "potri_backward", "sgp_criterion", "kalman_filter", "sumlogdiag",
            "gp_glue", "gemm2", "load", "lib_path", "LaError"]

@@ -18,6 +18,7 @@ SYMBOLS = [
     "la_potrf_batched", "la_potrf_backward", "la_trsm_batched", "la_trmm_batched", "la_syrk_batched",
     "la_sumlogdiag", "la_gp_glue", "la_gemm2_batched", "la_trsm_backward", "la_trmm_backward", "la_syrk_backward",
     "la_gemm2_backward", "la_potri", "la_potri_backward", "la_sgp_workspace_bytes", "la_sgp_criterion",
+    "la_kalman_filter",
     "la_last_error", "la_version",
 ]
 
@@ -64,6 +65,8 @@ def load():
     lib.la_sgp_workspace_bytes.restype = ctypes.c_size_t
     lib.la_sgp_criterion.argtypes = [i32, i32, i32, vp, vp, vp, vp, f64, vp, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
     lib.la_sgp_criterion.restype = i32
+    lib.la_kalman_filter.argtypes = [i32, i64, i32, i32, i32, i32] + [vp] * 12
+    lib.la_kalman_filter.restype = i32
     lib.la_last_error.restype = ctypes.c_char_p
     lib.la_version.restype = i32
     for name in SYMBOLS[:7]:
@@ -270,6 +273,29 @@ def sgp_criterion(Kuu, Kuf, Kff_diag, y, noise_var, workspace=None):
                                        _ptr(out["Kff_diag_bar"]), _ptr(out["y_bar"]), _ptr(out["noise_bar"]),
                                        workspace.data_ptr(), workspace.numel(), _stream(Kuu)), "la_sgp_criterion")
     return out
+
+
+def kalman_filter(A, B, Sh, Sv, mu0, S0, v, want_states=True, info=None):
+    """la_kalman_filter.  Parameters without a batch axis are shared by all sequences of v [batch, T, dv];
+    otherwise they carry v's batch axis.  Returns (nll [batch], f [batch, T, dh] or None, F [batch, T, dh, dh] or None)."""
+    for x in (B, Sh, Sv, mu0, S0, v):
+        _chk(A, x)
+    batch, T, dv = v.shape
+    shared = A.dim() == 2
+    dh = A.shape[-1]
+    pb = () if shared else (batch,)
+    assert tuple(A.shape) == pb + (dh, dh) and tuple(B.shape) == pb + (dv, dh) and tuple(Sh.shape) == pb + (dh, dh)
+    assert tuple(Sv.shape) == pb + (dv, dv) and tuple(mu0.shape) == pb + (dh,) and tuple(S0.shape) == pb + (dh, dh)
+    nll = torch.empty(batch, dtype=v.dtype, device=v.device)
+    f = torch.empty((batch, T, dh), dtype=v.dtype, device=v.device) if want_states else None
+    F = torch.empty((batch, T, dh, dh), dtype=v.dtype, device=v.device) if want_states else None
+    if info is not None:
+        assert info.dtype == torch.int32 and info.is_cuda and info.numel() == batch
+    with torch.cuda.device(v.device):
+        _check(load().la_kalman_filter(_dt(v), batch, T, dh, dv, int(shared), _ptr(A), _ptr(B), _ptr(Sh), _ptr(Sv),
+                                       _ptr(mu0), _ptr(S0), _ptr(v), _ptr(f), _ptr(F), _ptr(nll), _ptr(info),
+                                       _stream(v)), "la_kalman_filter")
+    return nll, f, F
 
 
 def syrk(A, trans=False, alpha=1.0, out=None):

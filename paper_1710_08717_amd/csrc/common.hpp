@@ -356,4 +356,10 @@ template <typename T>
 la_status launch_sgp_scalars(int stage, const double *sums, double lam, int n, T *phi, T *noise_bar, T *kff_bar, int nk,
                              hipStream_t st);
 
+// Kalman filter over a batch of sequences, dimensions up to 16 (kalman.hip).
+template <typename T>
+la_status launch_kalman(const T *A, const T *B, const T *Sh, const T *Sv, const T *mu0, const T *S0, const T *v, T *f,
+                        T *F, T *nll, int32_t *info, int64_t batch, int steps, int dh, int dv, int shared,
+                        hipStream_t st);
+
 }  // namespace la

@@ -876,6 +876,28 @@ la_status la_sgp_criterion(la_dtype dt, int U, int n, const void *Kuu, const voi
                                         noise_bar, workspace, st);
 }
 
+la_status la_kalman_filter(la_dtype dt, int64_t batch, int T, int dh, int dv, int shared_params, const void *A,
+                           const void *B, const void *Sh, const void *Sv, const void *mu0, const void *S0,
+                           const void *v, void *f, void *F, void *nll, int32_t *info, void *stream)
+{
+    if (bad_dtype(dt) || batch < 0 || T < 0 || dh < 1 || dv < 1)
+        return LA_ERR_INVALID_ARG;
+    if (dh > 16 || dv > 16)
+        return LA_ERR_UNSUPPORTED;
+    if (batch == 0)
+        return LA_OK;
+    if (!A || !B || !Sh || !Sv || !mu0 || !S0 || !nll || (T > 0 && !v))
+        return LA_ERR_INVALID_ARG;
+    hipStream_t st = (hipStream_t)stream;
+    if (dt == LA_F32)
+        return launch_kalman<float>((const float *)A, (const float *)B, (const float *)Sh, (const float *)Sv,
+                                    (const float *)mu0, (const float *)S0, (const float *)v, (float *)f, (float *)F,
+                                    (float *)nll, info, batch, T, dh, dv, shared_params != 0, st);
+    return launch_kalman<double>((const double *)A, (const double *)B, (const double *)Sh, (const double *)Sv,
+                                 (const double *)mu0, (const double *)S0, (const double *)v, (double *)f, (double *)F,
+                                 (double *)nll, info, batch, T, dh, dv, shared_params != 0, st);
+}
+
 la_status la_syrk_backward(la_dtype dt, int trans, double alpha, int64_t batch, int n, int k, const void *A,
                            const void *Bbar, void *Abar, void *stream)
 {

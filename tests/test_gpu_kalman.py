@@ -1,0 +1,120 @@
+"""Parity of la_kalman_filter (section 3.4) against the oracle's filter on the same seeded
+synthetic sequences.  The recursion is contractive here (stable transition matrix, every step
+conditions on a new observation), so rounding errors do not build up over the steps and the
+operators' tolerance applies to every output; the likelihood is a sum of T terms of size O(dv)
+and is compared relative to its value."""
+import sys
+
+import numpy as np
+import pytest
+
+import workloads
+
+pytestmark = pytest.mark.gpu
+TOL = {"f32": 2e-4, "f64": 1e-10}
+
+
+@pytest.fixture(scope="module")
+def la():
+    import torch
+
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    import paper_1710_08717_amd as la_mod
+
+    la_mod.load()
+    return la_mod
+
+
+@pytest.fixture(autouse=True)
+def _announce(request):
+    sys.stderr.write(f"\n[gpu-case] {request.node.nodeid}\n")
+    sys.stderr.flush()
+    yield
+
+
+def rel(a, b):
+    return float(np.linalg.norm(np.asarray(a, dtype=np.float64) - b) / max(np.linalg.norm(b), 1e-300))
+
+
+def run(la, w, want_states=True, with_info=True):
+    import torch
+
+    dev = lambda a: torch.from_numpy(np.ascontiguousarray(a)).cuda()
+    info = torch.full((w["batch"],), -1, dtype=torch.int32, device="cuda") if with_info else None
+    nll, f, F = la.kalman_filter(dev(w["A"]), dev(w["B"]), dev(w["Sh"]), dev(w["Sv"]), dev(w["mu0"]), dev(w["S0"]),
+                                 dev(w["v"]), want_states=want_states, info=info)
+    torch.cuda.synchronize()
+    host = lambda t: None if t is None else t.cpu().numpy()
+    return host(nll), host(f), host(F), host(info)
+
+
+@pytest.mark.parametrize("dtype", ["f64", "f32"])
+@pytest.mark.parametrize("shared", [True, False])
+@pytest.mark.parametrize("batch,T,dh,dv", [(1, 1, 1, 1), (3, 5, 2, 1), (5, 7, 3, 5), (9, 12, 4, 4), (6, 9, 7, 3),
+                                           (4, 20, 16, 16), (7, 6, 16, 5), (5, 6, 5, 16), (130, 8, 8, 8),
+                                           (2, 0, 3, 2)])
+def test_kalman_parity(la, orc, dtype, shared, batch, T, dh, dv):
+    w = workloads.make_kalman(batch, T, dh, dv, dtype=dtype, shared=shared, seed=batch + T)
+    ref_nll, ref_f, ref_F, ref_info = orc.kalman_filter(w["A"], w["B"], w["Sh"], w["Sv"], w["mu0"], w["S0"], w["v"])
+    nll, f, F, info = run(la, w)
+    tol = TOL[dtype]
+    assert np.array_equal(info, ref_info) and np.all(info == 0)
+    assert np.all(np.abs(nll - ref_nll) <= 4 * tol * np.maximum(1.0, np.abs(ref_nll)))
+    if T > 0:
+        assert rel(f, ref_f) <= 4 * tol
+        assert rel(F, ref_F) <= 4 * tol
+        # per sequence and step as well, so that one bad item cannot hide in the norm of many
+        per = np.linalg.norm((F - ref_F).reshape(batch, T, -1), axis=2) / np.linalg.norm(ref_F.reshape(batch, T, -1), axis=2)
+        assert per.max() <= 20 * tol
+    # likelihood only: same value, no state outputs written
+    nll2, f2, F2, _ = run(la, w, want_states=False, with_info=False)
+    assert f2 is None and F2 is None
+    assert np.array_equal(nll2, nll)
+
+
+@pytest.mark.parametrize("dtype", ["f64", "f32"])
+def test_kalman_many_long_sequences(la, orc, dtype):
+    """Thousands of workgroups and a few hundred steps; a batch that is no multiple of the four
+    sequences a workgroup carries."""
+    w = workloads.make_kalman(4099, 64, 6, 4, dtype=dtype, shared=True, seed=11)
+    ref_nll, ref_f, ref_F, _ = orc.kalman_filter(w["A"], w["B"], w["Sh"], w["Sv"], w["mu0"], w["S0"], w["v"])
+    nll, f, F, info = run(la, w)
+    tol = TOL[dtype]
+    assert np.all(info == 0)
+    assert np.all(np.abs(nll - ref_nll) <= 4 * tol * np.maximum(1.0, np.abs(ref_nll)))
+    assert rel(f, ref_f) <= 4 * tol and rel(F, ref_F) <= 4 * tol
+    w = workloads.make_kalman(3, 400, 16, 8, dtype=dtype, shared=False, seed=12)
+    ref_nll, ref_f, ref_F, _ = orc.kalman_filter(w["A"], w["B"], w["Sh"], w["Sv"], w["mu0"], w["S0"], w["v"])
+    nll, f, F, info = run(la, w)
+    assert np.all(np.abs(nll - ref_nll) <= 4 * tol * np.maximum(1.0, np.abs(ref_nll)))
+    assert rel(f[:, -1], ref_f[:, -1]) <= 4 * tol and rel(F[:, -1], ref_F[:, -1]) <= 4 * tol
+
+
+def test_kalman_reports_a_failing_pivot(la, orc):
+    w = workloads.make_kalman(6, 5, 3, 2, dtype="f64", shared=False, seed=3)
+    w["Sv"][4] = -50.0 * np.eye(2)  # sequence 4: S_vv is not positive definite from the first step on
+    _, _, _, ref_info = orc.kalman_filter(w["A"], w["B"], w["Sh"], w["Sv"], w["mu0"], w["S0"], w["v"])
+    nll, f, F, info = run(la, w)
+    assert np.array_equal(info, ref_info) and info[4] == 1 and np.all(np.delete(info, 4) == 0)
+    ok = np.delete(np.arange(6), 4)
+    ref = orc.kalman_filter(w["A"][ok], w["B"][ok], w["Sh"][ok], w["Sv"][ok], w["mu0"][ok], w["S0"][ok], w["v"][ok])
+    assert np.all(np.abs(nll[ok] - ref[0]) <= 1e-9 * np.maximum(1.0, np.abs(ref[0])))
+
+
+def test_kalman_argument_errors(la):
+    import ctypes
+
+    import torch
+
+    lib = la.load()
+    x = torch.zeros(64, dtype=torch.float32, device="cuda")
+    p = ctypes.c_void_p(x.data_ptr())
+    z = ctypes.c_void_p(0)
+    args = lambda dh, dv, nll: (0, 1, 1, dh, dv, 1, p, p, p, p, p, p, p, z, z, nll, z, z)
+    assert lib.la_kalman_filter(*args(17, 2, p)) == 2   # LA_ERR_UNSUPPORTED
+    assert lib.la_kalman_filter(*args(2, 17, p)) == 2
+    assert lib.la_kalman_filter(*args(0, 2, p)) == 1    # LA_ERR_INVALID_ARG
+    assert lib.la_kalman_filter(*args(2, 2, z)) == 1
+    assert lib.la_kalman_filter(7, 1, 1, 2, 2, 1, p, p, p, p, p, p, p, z, z, p, z, z) == 1
+    assert lib.la_kalman_filter(0, 0, 1, 2, 2, 1, z, z, z, z, z, z, z, z, z, z, z, z) == 0  # empty batch

@@ -108,3 +108,12 @@ def test_small_matrix_kernels_respect_dpp_spacing():
     assert n_dpp > 600  # the fused v_fmac_f32_dpp of the fp32 16-lane kernels are really there
     assert text.count("v_fmac_f32_dpp") >= 600
     assert hazards == []
+
+
+def test_kalman_filter_kernel_respects_dpp_spacing():
+    text = _isa_text("kalman.hip")
+    hazards, n_dpp = find_hazards(text)
+    # nine 16 x 16 products of 256 broadcast multiply-adds each per step and element type, plus the solves
+    assert text.count("v_fmac_f32_dpp") >= 2000
+    assert text.count("v_fmac_f64_dpp") >= 2000
+    assert hazards == []
