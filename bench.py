@@ -131,12 +131,85 @@ def bench_sgp(args, la, torch, np, workloads):
         "cpu_baseline": cpu}), flush=True)
 
 
+def bench_kalman(args, la, torch, np, workloads):
+    """Third workload (section 3.4): one step = one call of la_kalman_filter over a batch of
+    sequences: likelihood, filtered means and covariances of every time step."""
+    dh, dv = (int(x) for x in args.kf_dims.split(","))
+    T = args.kf_steps
+    batch = args.batch or 65536
+    dtype = args.dtype or "f32"
+    steps = args.steps if args.steps is not None else 10
+    warmup = args.warmup if args.warmup is not None else 2
+    w = workloads.make_kalman(batch, T, dh, dv, dtype=dtype, shared=True)
+    dev = lambda a: torch.from_numpy(np.ascontiguousarray(a)).cuda()
+    ops = [dev(w[k]) for k in ("A", "B", "Sh", "Sv", "mu0", "S0", "v")]
+    run = lambda: la.kalman_filter(*ops)
+    for _ in range(warmup):
+        run()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        out = run()
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) * 1e3 / steps
+    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(steps)]
+    for a, b in ev:
+        a.record()
+        run()
+        b.record()
+    torch.cuda.synchronize()
+    kms = float(np.mean([a.elapsed_time(b) for a, b in ev]))
+    # dense flop counts of the step's products and solves (the prediction is skipped at t = 0)
+    predict = 2.0 * dh * dh + 4.0 * dh ** 3
+    update = (2.0 * dv * dh + 2.0 * dh * dh * dv + 2.0 * dv * dv * dh + dv ** 3 / 3.0 + 2.0 * dh * dv * dv + 2.0 * dh * dv
+              + dv * dv + 2.0 * dh * dh * dv + 4.0 * dh ** 3 + 2.0 * dv * dv * dh + 2.0 * dh * dh * dv)
+    flops = batch * (T * update + (T - 1) * predict)
+    s = 4 if dtype == "f32" else 8
+    alg_bytes = batch * T * (dv + dh + dh * dh) * s
+    seqsteps = batch * T
+    log(f"[bench] KF batch={batch} T={T} dh={dh} dv={dv} {dtype}: {ms:.3f} ms per call (kernel {kms:.3f} ms), "
+        f"mean nll = {float(out[0].double().mean()):.6f}")
+    cpu = None
+    if not args.no_cpu_baseline:
+        import oracle
+
+        sb = min(batch, 4096)
+        ws_ = {k: (w[k][:sb] if k == "v" else w[k]) for k in ("A", "B", "Sh", "Sv", "mu0", "S0", "v")}
+        t0, passes = time.perf_counter(), 0
+        while True:
+            oracle.kalman_filter(ws_["A"], ws_["B"], ws_["Sh"], ws_["Sv"], ws_["mu0"], ws_["S0"], ws_["v"])
+            passes += 1
+            dt_cpu = time.perf_counter() - t0
+            if dt_cpu >= 10.0 or passes >= 50:
+                break
+        cpu = {"value": passes * sb * T / dt_cpu, "unit": "sequence-steps/s", "cores": oracle.num_threads(),
+               "kind": "oracle", "sample": f"the first {sb} sequences, {passes} passes, {dt_cpu:.2f} s in total"}
+    # vector FMA rate: 256 CUs x 4 SIMDs x 16 lanes x 2 flops x 2.4 GHz = 78.6 TFLOP/s for fp64 and for
+    # one-per-lane fp32 multiply-adds; the published fp32 figure (157.3) counts two per lane (packed), a
+    # form the lane-broadcast multiply-adds of this kernel do not have
+    peak = PEAK_TFLOPS[dtype]
+    ach = flops / (kms * 1e-3) / 1e12
+    print(json.dumps({
+        "metric": "Kalman filter sequence-steps/s", "value": seqsteps / (ms * 1e-3), "unit": "sequence-steps/s",
+        "n_gpus": 1, "steps": steps, "warmup": warmup, "ms_per_step": ms, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": dtype, "data": "synthetic",
+        "config": {"workload": f"KF: batch={batch} T={T} dh={dh} dv={dv} {dtype}, one parameter set for all sequences"},
+        "gflops": flops / (ms * 1e-3) / 1e9, "useful_flops_per_step": flops,
+        "roofline": {"bound": "alu", "kernel": "k_kalman", "achieved": ach, "peak": peak, "unit": "TFLOP/s",
+                     "frac": ach / peak, "traffic": None, "avg_launch_ms": kms,
+                     "frac_of_unpacked_fma_rate": ach / 78.6,
+                     "hbm_frac_on_algorithmic_bytes": alg_bytes / (kms * 1e-3) / 1e9 / HBM_PEAK_GBS},
+        "cpu_baseline": cpu}), flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=None)
     ap.add_argument("--warmup", type=int, default=None)
-    ap.add_argument("--config", default="C2", choices=["C1", "C2", "C3", "C4", "C5", "SGP"])
+    ap.add_argument("--config", default="C2", choices=["C1", "C2", "C3", "C4", "C5", "SGP", "KF"])
+    ap.add_argument("--kf-dims", default="16,16", help="KF only: state and observation dimension, dh,dv (each <= 16)")
+    ap.add_argument("--kf-steps", type=int, default=32, help="KF only: time steps per sequence")
     ap.add_argument("--inducing", type=int, default=3200, help="SGP only: number of inducing points U")
     ap.add_argument("--with-backward-ops", action="store_true",
                     help="C4 only: also run trmm / trsm / syrk backward on the step's operands")
@@ -164,6 +237,8 @@ def main():
     name = args.config
     if name == "SGP":
         return bench_sgp(args, la, torch, np, workloads)
+    if name == "KF":
+        return bench_kalman(args, la, torch, np, workloads)
     w = workloads.make(name, batch=args.batch, n=args.n, dtype=args.dtype)
     batch, n, dtype, m = w["batch"], w["n"], w["dtype"], w["m"]
     s = 4 if dtype == "f32" else 8

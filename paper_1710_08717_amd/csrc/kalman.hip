@@ -34,19 +34,42 @@ struct KfArgs {
     int T_, dh, dv, shared;
 };
 
-// C[r][j] += sum_{k < kdim} X[r][k] Y[k][j]   (sign: -1 subtracts)
+// f(k) for k = 0 .. 15 in ascending (or descending) order, in blocks of four; a block is skipped
+// when all of it lies at or beyond `dim`.  (One uniform branch per block: a branch per index
+// costs more scalar registers than there are.)  Indices between dim and the end of its block
+// see the zero / identity padding.
+template <class Fn>
+__device__ __forceinline__ void kf_upto(int dim, Fn &&fn)
+{
+    static_for<0, 4>([&](auto bc) {
+        constexpr int b0 = 4 * decltype(bc)::value;
+        if (b0 < dim) {
+            static_for<0, 4>([&](auto ic) { fn(std::integral_constant<int, b0 + decltype(ic)::value>{}); });
+        }
+    });
+}
+template <class Fn>
+__device__ __forceinline__ void kf_downfrom(int dim, Fn &&fn)
+{
+    static_for<0, 4>([&](auto bc) {
+        constexpr int b0 = 12 - 4 * decltype(bc)::value;
+        if (b0 < dim) {
+            static_for<0, 4>([&](auto ic) { fn(std::integral_constant<int, b0 + 3 - decltype(ic)::value>{}); });
+        }
+    });
+}
+
+// C[r][j] += sum_{k < kdim} X[r][k] Y[k][j]   (neg: subtract)
 template <typename T>
 __device__ __forceinline__ void kf_nn(T (&C)[KF_D], const T (&X)[KF_D], T (&Y)[KF_D], int kdim, bool neg = false)
 {
     dpp_settle<KF_D>(Y);
-    static_for<0, KF_D>([&](auto kc) {
+    kf_upto(kdim, [&](auto kc) {
         constexpr int k = decltype(kc)::value;
-        if (k < kdim) {
-            static_for<0, KF_D>([&](auto jc) {
-                constexpr int j = decltype(jc)::value;
-                fma_bcast<KF_D, k>(C[j], Y[j], X[k], neg);
-            });
-        }
+        static_for<0, KF_D>([&](auto jc) {
+            constexpr int j = decltype(jc)::value;
+            fma_bcast<KF_D, k>(C[j], Y[j], X[k], neg);
+        });
     });
 }
 
@@ -55,12 +78,15 @@ template <typename T>
 __device__ __forceinline__ void kf_nt(T (&C)[KF_D], const T (&X)[KF_D], T (&Y)[KF_D], int jdim)
 {
     dpp_settle<KF_D>(Y);
-    static_for<0, KF_D>([&](auto jc) {
-        constexpr int j = decltype(jc)::value;
-        if (j < jdim) {
+    static_for<0, 4>([&](auto bc) {  // four columns at a time: their chains of multiply-adds interleave
+        constexpr int b0 = 4 * decltype(bc)::value;
+        if (b0 < jdim) {
             static_for<0, KF_D>([&](auto kc) {
                 constexpr int k = decltype(kc)::value;
-                fma_bcast<KF_D, j>(C[j], Y[k], X[k], false);
+                static_for<0, 4>([&](auto ic) {
+                    constexpr int j = b0 + decltype(ic)::value;
+                    fma_bcast<KF_D, j>(C[j], Y[k], X[k], false);
+                });
             });
         }
     });
@@ -71,10 +97,9 @@ template <typename T>
 __device__ __forceinline__ void kf_mv(T &c, const T (&X)[KF_D], T &y, int kdim)
 {
     dpp_settle1<KF_D>(y);
-    static_for<0, KF_D>([&](auto kc) {
+    kf_upto(kdim, [&](auto kc) {
         constexpr int k = decltype(kc)::value;
-        if (k < kdim)
-            fma_bcast<KF_D, k>(c, y, X[k], false);
+        fma_bcast<KF_D, k>(c, y, X[k], false);
     });
 }
 
@@ -106,9 +131,10 @@ __global__ __launch_bounds__(64) void k_kalman(KfArgs<T> a)
     const int64_t b = live ? b_raw : a.batch - 1;  // a spare group repeats the last sequence and stores nothing
     const int64_t pb = a.shared ? 0 : b;
 
-    T *sA = reinterpret_cast<T *>(kf_smem) + g * Lds::GROUP, *sB = sA + Lds::MAT, *sSh = sB + Lds::MAT,
-      *sSv = sSh + Lds::MAT;
-    {   // parameters, zero padded (S_v: identity padded, so that the padded S_vv keeps a unit pivot)
+    // one copy of the parameters per sequence, or one for the workgroup when all sequences share them
+    T *sA = reinterpret_cast<T *>(kf_smem) + (a.shared ? 0 : g * Lds::GROUP), *sB = sA + Lds::MAT,
+      *sSh = sB + Lds::MAT, *sSv = sSh + Lds::MAT;
+    if (!a.shared || g == 0) {   // parameters, zero padded (S_v: identity padded, so that the padded S_vv keeps a unit pivot)
         const T *Ap = a.A + pb * dh * dh, *Bp = a.B + pb * dv * dh, *Shp = a.Sh + pb * dh * dh, *Svp = a.Sv + pb * dv * dv;
 #pragma unroll
         for (int j = 0; j < KF_D; ++j) {
@@ -171,24 +197,22 @@ __global__ __launch_bounds__(64) void k_kalman(KfArgs<T> a)
 
         // ---- S_vv = L L^T in place (lower triangle of S; lane r keeps 1 / L_rr) ----
         T invd = one;
-        static_for<0, KF_D>([&](auto kc) {
+        kf_upto(dv, [&](auto kc) {
             constexpr int k = decltype(kc)::value;
-            if (k < dv) {
-                dpp_settle1<KF_D>(S[k]);
-                T d = T(0);
-                fma_bcast<KF_D, k>(d, S[k], one, false);  // pivot, from lane k
-                if (!(d > T(0)) && bad == 0)
-                    bad = t + 1;
-                const T rs = one / sqrt(d);
-                S[k] *= rs;
-                if (r == k)
-                    invd = rs;
-                dpp_settle1<KF_D>(S[k]);
-                static_for<k + 1, KF_D>([&](auto jc) {
-                    constexpr int j = decltype(jc)::value;
-                    fma_bcast<KF_D, j>(S[j], S[k], S[k], true);  // S[r][j] -= L[r][k] L[j][k]
-                });
-            }
+            dpp_settle1<KF_D>(S[k]);
+            T d = T(0);
+            fma_bcast<KF_D, k>(d, S[k], one, false);  // pivot, from lane k
+            if (!(d > T(0)) && bad == 0)
+                bad = t + 1;
+            const T rs = one / sqrt(d);
+            S[k] *= rs;
+            if (r == k)
+                invd = rs;
+            dpp_settle1<KF_D>(S[k]);
+            static_for<k + 1, KF_D>([&](auto jc) {
+                constexpr int j = decltype(jc)::value;
+                fma_bcast<KF_D, j>(S[j], S[k], S[k], true);  // S[r][j] -= L[r][k] L[j][k]
+            });
         });
 #pragma unroll
         for (int j = 0; j < KF_D; ++j)
@@ -197,29 +221,25 @@ __global__ __launch_bounds__(64) void k_kalman(KfArgs<T> a)
         // ---- gain K = M L^-T L^-1, row by row inside each lane ----
         dpp_settle<KF_D>(S);
         dpp_settle1<KF_D>(invd);
-        static_for<0, KF_D>([&](auto jc) {  // X L^T = M
+        kf_upto(dv, [&](auto jc) {  // X L^T = M
             constexpr int j = decltype(jc)::value;
-            if (j < dv) {
-                T x = T(0);
-                fma_bcast<KF_D, j>(x, invd, M[j], false);
-                M[j] = x;
-                static_for<j + 1, KF_D>([&](auto ic) {
-                    constexpr int i = decltype(ic)::value;
-                    fma_bcast<KF_D, i>(M[i], S[j], x, true);  // M[r][i] -= x L[i][j]
-                });
-            }
+            T x = T(0);
+            fma_bcast<KF_D, j>(x, invd, M[j], false);
+            M[j] = x;
+            static_for<j + 1, KF_D>([&](auto ic) {
+                constexpr int i = decltype(ic)::value;
+                fma_bcast<KF_D, i>(M[i], S[j], x, true);  // M[r][i] -= x L[i][j]
+            });
         });
-        static_for<0, KF_D>([&](auto jc) {  // K L = X
-            constexpr int j = KF_D - 1 - decltype(jc)::value;
-            if (j < dv) {
-                T y = T(0);
-                fma_bcast<KF_D, j>(y, invd, M[j], false);
-                M[j] = y;
-                static_for<0, j>([&](auto ic) {
-                    constexpr int i = decltype(ic)::value;
-                    fma_bcast<KF_D, j>(M[i], S[i], y, true);  // M[r][i] -= y L[j][i]
-                });
-            }
+        kf_downfrom(dv, [&](auto jc) {  // K L = X
+            constexpr int j = decltype(jc)::value;
+            T y = T(0);
+            fma_bcast<KF_D, j>(y, invd, M[j], false);
+            M[j] = y;
+            static_for<0, j>([&](auto ic) {
+                constexpr int i = decltype(ic)::value;
+                fma_bcast<KF_D, j>(M[i], S[i], y, true);  // M[r][i] -= y L[j][i]
+            });
         });
         // M now holds K
 
@@ -229,15 +249,13 @@ __global__ __launch_bounds__(64) void k_kalman(KfArgs<T> a)
         kf_mv(fn, M, delta, dv);  // mu_h + K delta
         {
             T dl = delta, zfin = T(0);
-            static_for<0, KF_D>([&](auto kc) {  // z = L^-1 delta, one element per lane
+            kf_upto(dv, [&](auto kc) {  // z = L^-1 delta, one element per lane
                 constexpr int k = decltype(kc)::value;
-                if (k < dv) {
-                    T zs = dl * invd;
-                    if (r == k)
-                        zfin = zs;
-                    dpp_settle1<KF_D>(zs);
-                    fma_bcast<KF_D, k>(dl, zs, S[k], true);  // dl[r] -= L[r][k] z[k]
-                }
+                T zs = dl * invd;
+                if (r == k)
+                    zfin = zs;
+                dpp_settle1<KF_D>(zs);
+                fma_bcast<KF_D, k>(dl, zs, S[k], true);  // dl[r] -= L[r][k] z[k]
             });
             if (r < dv)
                 nll_acc += 0.5 * (double)zfin * (double)zfin - (double)log(invd);
@@ -304,7 +322,8 @@ la_status launch_kalman(const T *A, const T *B, const T *Sh, const T *Sv, const 
     if (blocks > 0x7fffffffll || dh < 1 || dv < 1 || dh > KF_D || dv > KF_D)
         return LA_ERR_UNSUPPORTED;
     KfArgs<T> a{A, B, Sh, Sv, mu0, S0, v, f, F, nll, info, batch, steps, dh, dv, shared};
-    hipLaunchKernelGGL((k_kalman<T>), dim3((unsigned)blocks), dim3(64), KfLds<T>::BYTES, st, a);
+    const size_t lds = shared ? KfLds<T>::BYTES / KF_GROUPS : KfLds<T>::BYTES;
+    hipLaunchKernelGGL((k_kalman<T>), dim3((unsigned)blocks), dim3(64), lds, st, a);
     return launch_check("kalman");
 }
 
