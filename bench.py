@@ -211,6 +211,8 @@ def main():
     ap.add_argument("--kf-dims", default="16,16", help="KF only: state and observation dimension, dh,dv (each <= 16)")
     ap.add_argument("--kf-steps", type=int, default=32, help="KF only: time steps per sequence")
     ap.add_argument("--inducing", type=int, default=3200, help="SGP only: number of inducing points U")
+    ap.add_argument("--unfused", action="store_true",
+                    help="C3 only: the operator chain potrf, 2 x trsm, glue, backward instead of the one-launch la_gp_criterion")
     ap.add_argument("--with-backward-ops", action="store_true",
                     help="C4 only: also run trmm / trsm / syrk backward on the step's operands")
     ap.add_argument("--dtype", default=None, choices=["f32", "f64"])
@@ -247,6 +249,7 @@ def main():
     log(f"[bench] {name}: batch={batch} n={n} dtype={dtype} m={m} steps={steps} warmup={warmup}")
 
     extra = bool(args.with_backward_ops) and name == "C4"
+    fused_gp = name == "C3" and not args.unfused
     # ---- resident inputs, several rotating buffer sets -----------------------------
     set_bytes = 4 * batch * n * n * s
     nsets = int(max(1, min(8, (1 << 31) // max(set_bytes, 1)))) if name != "C5" else 1
@@ -291,6 +294,9 @@ def main():
 
     def step(i, timed=False):
         d = sets[i % nsets]
+        if fused_gp:  # C3: the whole criterion + gradient is one launch
+            call("gp_criterion", lambda: la.gp_criterion(d["A"], d["y"], out=d["Abar"], loss=d["loss"]), timed)
+            return
         call("potrf", lambda: la.potrf(d["A"], out=d["L"]), timed)
         if name == "C1":
             call("trsm", lambda: la.trsm(d["L"], d["rhs"], out=d["X"]), timed)
@@ -344,7 +350,14 @@ def main():
     gflops = total_flops / (ms_per_step * 1e-3) / 1e9
 
     # ---- roofline of the dominant kernel -------------------------------------------
-    if name in ("C1", "C2", "C3"):
+    if fused_gp:
+        alg_bytes = (n * (n + 1) // 2 + n + n * n + 1) * s * batch  # lower triangle of A, y; Abar in full, loss
+        achieved = alg_bytes / (kern_ms["gp_criterion"] * 1e-3) / 1e9
+        roof = {"bound": "hbm", "kernel": "k_gp_leaf16 (la_gp_criterion)", "achieved": achieved, "peak": HBM_PEAK_GBS,
+                "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                "algorithmic_bytes_per_launch": alg_bytes, "avg_launch_ms": kern_ms["gp_criterion"],
+                "note": "latency bound: one workgroup per matrix walks the 8 tile columns of the factorisation in turn"}
+    elif name in ("C1", "C2", "C3"):
         bm = bytes_model(n, s)
         dom = "backward"
         alg_bytes = bm[dom] * batch
@@ -440,7 +453,8 @@ def main():
         "dtype": dtype,
         "data": "synthetic",
         "config": {"workload": f"{name}: batch={batch} n={n} {dtype}" + (f" rhs={m}" if m else ""),
-                   "ops": list(fm.keys()) + (["gp_glue"] if name == "C3" else []), "buffer_sets": nsets},
+                   "ops": (["gp_criterion (potrf, 2 x trsm, sumlogdiag, glue, backward in one launch)"] if fused_gp
+                           else list(fm.keys()) + (["gp_glue"] if name == "C3" else [])), "buffer_sets": nsets},
         "gflops": gflops,
         "useful_flops_per_step": total_flops,
         "kernel_ms": kern_ms,

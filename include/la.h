@@ -171,6 +171,22 @@ la_status la_sumlogdiag(la_dtype dt, int64_t batch, int n, const void *L, void *
 la_status la_gp_glue(la_dtype dt, int64_t batch, int n, const void *L, const void *y, const void *z,
                      const void *alpha, void *loss, void *Lbar, void *stream);
 
+/* Gaussian-process criterion and its gradient in one call (section 3.1; backward rules of section
+ * 4.2): for each item, with A the kernel matrix plus noise (symmetric positive definite; its lower
+ * triangle is read) and targets y,
+ *   L = potrf(A),  z = L^{-1} y,  alpha = L^{-T} z,
+ *   loss = 1/2 y^T alpha + sum_i log l_ii           (the criterion minus n/2 log 2 pi),
+ *   Abar = d loss / d A = 1/2 (A^{-1} - alpha alpha^T), obtained as the potrf backward of
+ *          Lbar = -tril(alpha z^T) + diag(1 / l_ii); written in full, exactly symmetric.
+ * A, Abar: [batch, n, n]; y: [batch, n]; loss: [batch]; info: NULL or int32 [batch] as for potrf.
+ * Abar may be the same buffer as A.  Up to n = 128 (fp32) / 96 (fp64) this is ONE kernel per call
+ * and needs no workspace; beyond that it is the sequence la_potrf_batched, two la_trsm_batched,
+ * la_gp_glue, la_potrf_backward on `workspace` (device memory, 16-byte aligned, at least
+ * la_gp_workspace_bytes(dt, batch, n) bytes, not overlapping the other arguments). */
+size_t la_gp_workspace_bytes(la_dtype dt, int64_t batch, int n);
+la_status la_gp_criterion(la_dtype dt, int64_t batch, int n, const void *A, const void *y, void *loss, void *Abar,
+                          int32_t *info, void *workspace, size_t workspace_bytes, void *stream);
+
 /* Variational sparse Gaussian-process criterion and its gradient (section 3.2; the backward sweep
  * applies the backward rules of section 4.2 to the listing's steps in reverse).  One problem per call:
  *   Lu = potrf(Kuu);  B = Lu^{-1} Kuf;  A = B B^T / lam + I;  La = potrf(A);  w = La^{-1} (B y);

@@ -16,6 +16,7 @@ from .binding import (  # noqa: F401
     potrf,
     sgp_criterion,
     kalman_filter,
+    gp_criterion,
     potri,
     potri_backward,
     potrf_backward,
@@ -28,5 +29,5 @@ from .binding import (  # noqa: F401
     trsm_backward,
 )
 
-__all__ = ["potrf", "potrf_backward", "trsm", "trmm", "syrk", "trsm_backward", "trmm_backward", "syrk_backward", "gemm2_backward", "potri", "potri_backward", "sgp_criterion", "kalman_filter", "sumlogdiag",
+__all__ = ["potrf", "potrf_backward", "trsm", "trmm", "syrk", "trsm_backward", "trmm_backward", "syrk_backward", "gemm2_backward", "potri", "potri_backward", "sgp_criterion", "kalman_filter", "gp_criterion", "sumlogdiag",
            "gp_glue", "gemm2", "load", "lib_path", "LaError"]

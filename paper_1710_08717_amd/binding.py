@@ -18,7 +18,7 @@ SYMBOLS = [
     "la_potrf_batched", "la_potrf_backward", "la_trsm_batched", "la_trmm_batched", "la_syrk_batched",
     "la_sumlogdiag", "la_gp_glue", "la_gemm2_batched", "la_trsm_backward", "la_trmm_backward", "la_syrk_backward",
     "la_gemm2_backward", "la_potri", "la_potri_backward", "la_sgp_workspace_bytes", "la_sgp_criterion",
-    "la_kalman_filter",
+    "la_kalman_filter", "la_gp_workspace_bytes", "la_gp_criterion",
     "la_last_error", "la_version",
 ]
 
@@ -67,6 +67,10 @@ def load():
     lib.la_sgp_criterion.restype = i32
     lib.la_kalman_filter.argtypes = [i32, i64, i32, i32, i32, i32] + [vp] * 12
     lib.la_kalman_filter.restype = i32
+    lib.la_gp_workspace_bytes.argtypes = [i32, i64, i32]
+    lib.la_gp_workspace_bytes.restype = ctypes.c_size_t
+    lib.la_gp_criterion.argtypes = [i32, i64, i32, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
+    lib.la_gp_criterion.restype = i32
     lib.la_last_error.restype = ctypes.c_char_p
     lib.la_version.restype = i32
     for name in SYMBOLS[:7]:
@@ -273,6 +277,29 @@ def sgp_criterion(Kuu, Kuf, Kff_diag, y, noise_var, workspace=None):
                                        _ptr(out["Kff_diag_bar"]), _ptr(out["y_bar"]), _ptr(out["noise_bar"]),
                                        workspace.data_ptr(), workspace.numel(), _stream(Kuu)), "la_sgp_criterion")
     return out
+
+
+def gp_criterion(A, y, out=None, loss=None, info=None, workspace=None):
+    """la_gp_criterion: (loss [batch], Abar [batch, n, n]).  ``out`` may be ``A`` itself."""
+    _chk(A, y)
+    n = A.shape[-1]
+    batch = _batch(A)
+    assert A.shape[-2] == n and y.shape[-1] == n and _batch(y, 1) == batch
+    Abar = torch.empty_like(A) if out is None else out
+    _chk(A, Abar)
+    if loss is None:
+        loss = torch.empty(A.shape[:-2], dtype=A.dtype, device=A.device)
+    _chk(A, loss)
+    need = int(load().la_gp_workspace_bytes(_dt(A), batch, n))
+    if need and workspace is None:
+        workspace = torch.empty(need, dtype=torch.uint8, device=A.device)
+    if info is not None:
+        assert info.dtype == torch.int32 and info.is_cuda and info.numel() == batch
+    with torch.cuda.device(A.device):
+        _check(load().la_gp_criterion(_dt(A), batch, n, _ptr(A), _ptr(y), _ptr(loss), _ptr(Abar), _ptr(info),
+                                      ctypes.c_void_p(workspace.data_ptr() if need else 0),
+                                      workspace.numel() if need else 0, _stream(A)), "la_gp_criterion")
+    return loss, Abar
 
 
 def kalman_filter(A, B, Sh, Sv, mu0, S0, v, want_states=True, info=None):

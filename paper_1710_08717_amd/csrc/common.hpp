@@ -356,6 +356,11 @@ template <typename T>
 la_status launch_sgp_scalars(int stage, const double *sums, double lam, int n, T *phi, T *noise_bar, T *kff_bar, int nk,
                              hipStream_t st);
 
+// Gaussian-process criterion and gradient, one workgroup per matrix (leaf.hip); n <= backward_leaf16_max_n.
+template <typename T>
+la_status launch_gp_leaf16(View<const T> A, const T *y, T *loss, View<T> Abar, int32_t *info, int64_t batch, int n,
+                           hipStream_t st);
+
 // Kalman filter over a batch of sequences, dimensions up to 16 (kalman.hip).
 template <typename T>
 la_status launch_kalman(const T *A, const T *B, const T *Sh, const T *Sv, const T *mu0, const T *S0, const T *v, T *f,

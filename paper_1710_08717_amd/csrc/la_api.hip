@@ -705,6 +705,26 @@ static la_status tri_backward(bool solve, la_dtype dt, int lower, int trans, int
                         : trmm_backward_t<double>(lower, trans, rightside, alpha, batch, n, m, L, X, Bbar, Abar, Lbar, st);
 }
 
+template <typename T>
+static la_status gp_t(int64_t batch, int n, const void *A, const void *y, void *loss, void *Abar, int32_t *info,
+                      void *workspace, hipStream_t st)
+{
+    if (n <= backward_leaf16_max_n<T>()) {
+        if (info)
+            LA_TRY(launch_fill_i32(info, batch, 0, st));
+        return launch_gp_leaf16<T>(tri_view<const T>((const T *)A, n, 1), (const T *)y, (T *)loss,
+                                   tri_view<T>((T *)Abar, n, 1), info, batch, n, st);
+    }
+    const int64_t nn = (int64_t)n * n;
+    T *Lw = (T *)workspace, *Gw = Lw + batch * nn, *z = Gw + batch * nn, *al = z + batch * n;
+    LA_TRY(potrf_t<T>(1, batch, n, A, Lw, info, st));
+    LA_TRY(tri_apply_t<T>(true, 1, 0, 0, 1.0, batch, n, 1, Lw, y, z, st));
+    LA_TRY(tri_apply_t<T>(true, 1, 1, 0, 1.0, batch, n, 1, Lw, z, al, st));
+    LA_TRY(launch_gp_glue<T>(Lw, (const T *)y, z, al, (T *)loss, Gw, batch, n, st));
+    return backward_impl<T>(tri_view<const T>(Lw, n, 1), tri_view<const T>(Gw, n, 1), tri_view<T>((T *)Abar, n, 1), batch,
+                            n, false, st);
+}
+
 extern "C" {
 
 la_status la_potrf_batched(la_dtype dt, int lower, int64_t batch, int n, const void *A, void *L, int32_t *info,
@@ -980,6 +1000,41 @@ la_status la_gp_glue(la_dtype dt, int64_t batch, int n, const void *L, const voi
                                                 (const float *)alpha, (float *)loss, (float *)Lbar, batch, n, st)
                         : launch_gp_glue<double>((const double *)L, (const double *)y, (const double *)z,
                                                  (const double *)alpha, (double *)loss, (double *)Lbar, batch, n, st);
+}
+
+size_t la_gp_workspace_bytes(la_dtype dt, int64_t batch, int n)
+{
+    if (bad_dtype(dt) || batch <= 0 || n <= 0)
+        return 0;
+    const int fused = dt == LA_F32 ? backward_leaf16_max_n<float>() : backward_leaf16_max_n<double>();
+    if (n <= fused)
+        return 0;
+    return ((size_t)batch * n * n * 2 + (size_t)batch * n * 2) * esize(dt);
+}
+
+la_status la_gp_criterion(la_dtype dt, int64_t batch, int n, const void *A, const void *y, void *loss, void *Abar,
+                          int32_t *info, void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (bad_dtype(dt) || batch < 0 || n < 0 || n > MAX_N)
+        return LA_ERR_INVALID_ARG;
+    if (batch == 0)
+        return LA_OK;
+    if (!loss || (n > 0 && (!A || !y || !Abar)))
+        return LA_ERR_INVALID_ARG;
+    hipStream_t st = (hipStream_t)stream;
+    if (n == 0)  // empty sums
+        return dt == LA_F32 ? launch_gp_glue<float>(nullptr, nullptr, nullptr, nullptr, (float *)loss, nullptr, batch, 0, st)
+                            : launch_gp_glue<double>(nullptr, nullptr, nullptr, nullptr, (double *)loss, nullptr, batch, 0,
+                                                     st);
+    const size_t need = la_gp_workspace_bytes(dt, batch, n);
+    const size_t bytes = (size_t)batch * n * n * esize(dt);
+    if (need > 0 && (!workspace || workspace_bytes < need || ((uintptr_t)workspace & 15) ||
+                     overlap(workspace, need, A, bytes) || overlap(workspace, need, Abar, bytes)))
+        return LA_ERR_INVALID_ARG;
+    if (A != Abar && overlap(A, bytes, Abar, bytes))
+        return LA_ERR_INVALID_ARG;
+    return dt == LA_F32 ? gp_t<float>(batch, n, A, y, loss, Abar, info, workspace, st)
+                        : gp_t<double>(batch, n, A, y, loss, Abar, info, workspace, st);
 }
 
 const char *la_last_error(void) { return g_err; }

@@ -778,6 +778,231 @@ __global__ __launch_bounds__(LEAF16_THREADS) void k_backward_leaf16(View<const T
 }
 
 // ---------------------------------------------------------------------------------------
+// Gaussian-process criterion and its gradient in one launch (section 3.1: potrf, two trsm,
+// sumlogdiag; backward of trsm (first case) and of potrf from section 4.2), one workgroup per
+// matrix, everything in LDS.  For A = K + noise, targets y:
+//   L = potrf(A) with Li = L^-1 (the factorisation loop of k_potrf_leaf16);
+//   z = Li y,  alpha = Li^T z,  loss = 1/2 |z|^2 + sum_i log l_ii;
+//   Lbar = -tril(alpha z^T) + diag(1 / l_ii) is never stored: its tiles are built in registers
+//   where P = Phi(tril(L^T Lbar)) needs them;
+//   Z = P Li;  Abar_ij = 1/2 sum_{k >= i} (Li_ki^T Z_kj + Z_ki^T Li_kj)   (as in k_backward_leaf16).
+// Three tile areas: [A -> L -> Z], [Li], [P -> staging of the mirrored store], and 4 vectors.
+// ---------------------------------------------------------------------------------------
+template <typename T>
+__global__ __launch_bounds__(LEAF16_THREADS) void k_gp_leaf16(View<const T> A, const T *y, T *loss, View<T> Abar,
+                                                              int32_t *info, int64_t batch, int n)
+{
+    using C = Leaf16<T>;
+    using MF = Mfma<T>;
+    extern __shared__ __align__(16) unsigned char leaf16_lds[];
+    T *lds = reinterpret_cast<T *>(leaf16_lds);
+    constexpr int W = LEAF16_WAVES;
+    constexpr int DT = C::DT, OT = C::OT, PS = C::PS;
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int64_t b = blockIdx.x;
+    const int K = (n + LT - 1) / LT;
+    const int ntl = K * (K + 1) / 2;
+    const int area = backward16_area<T>(K);
+    const LeafLds<T> m{lds, lds + area, lds + K * DT, lds + area + K * DT};
+    T *pD = lds + 2 * area, *pO = pD + K * DT;
+    T *sy = lds + 3 * area, *sz = sy + LT * LK, *sal = sz + LT * LK, *sdi = sal + LT * LK;  // y, z, alpha, 1 / l_ii
+    auto ptile = [&](int i, int j) { return i == j ? TileRef<T>{pD + i * DT, true} : TileRef<T>{pO + tri_off(i, j) * OT, false}; };
+
+    leaf_load_lower<T>(m, A.p + b * A.bs, A.rs, A.cs, n, wave, lane);
+    if (tid < LT * LK)
+        sy[tid] = tid < n ? y[b * n + tid] : T(0);
+    __syncthreads();
+
+    // ---- L and Li: the loop of k_potrf_leaf16 --------------------------------------------------
+    int fail = 0;
+    if (wave == 0)
+        fail = leaf_diag<T>(m, 0, lane);
+    __syncthreads();
+    for (int k = 0; k < K; ++k) {
+        const int rows = K - 1 - k;
+        if (wave == 0) {
+            if (rows > 0)
+                leaf_panel<T>(m, k + 1, k, lane);
+        } else {
+            const int np = rows > 0 ? rows - 1 : 0;
+            for (int it = wave - 1; it < np + k; it += W - 1) {
+                if (it < np)
+                    leaf_panel<T>(m, k + 2 + it, k, lane);
+                else
+                    leaf_xrow<T>(m, k, it - np, lane);
+            }
+        }
+        __syncthreads();
+        if (rows == 0)
+            break;
+        if (wave == 0) {
+            leaf_update_a<T>(m, k + 1, k + 1, k, lane);
+            const int f = leaf_diag<T>(m, k + 1, lane);
+            if (fail == 0 && f != 0)
+                fail = (k + 1) * LT + f;
+        } else {
+            const int nx = rows * (k + 1);
+            const int na = rows * (rows + 1) / 2 - 1;
+            int xi = 0, xj = wave - 1;
+            for (int it = wave - 1; it < nx + na; it += W - 1) {
+                if (it < nx) {
+                    while (xj > k) {
+                        xj -= k + 1;
+                        ++xi;
+                    }
+                    leaf_update_x<T>(m, k + 1 + xi, xj, k, lane);
+                    xj += W - 1;
+                } else {
+                    int ii, jj;
+                    tri_decode(it - nx + 1, ii, jj);
+                    leaf_update_a<T>(m, k + 1 + ii, k + 1 + jj, k, lane);
+                }
+            }
+        }
+        __syncthreads();
+    }
+    if (info != nullptr && tid == 0 && fail != 0 && fail <= n)
+        info[b] = fail;
+
+    // ---- z = Li y: eight threads per row, one tile column each ----------------------------------
+    {
+        const int r = tid >> 3, tj = tid & 7, ti = r >> 4, u = r & 15;
+        T part = T(0);
+        if (ti < K && tj <= ti) {
+            const TileRef<T> t = m.x(ti, tj);
+#pragma unroll
+            for (int w = 0; w < LT; ++w)
+                part = fma(t.p[t.at(u, w)], sy[tj * LT + w], part);
+        }
+        part += __shfl_xor(part, 1, 8);
+        part += __shfl_xor(part, 2, 8);
+        part += __shfl_xor(part, 4, 8);
+        if (tj == 0) {
+            sz[r] = part;
+            const TileRef<T> d = m.x(ti < K ? ti : 0, ti < K ? ti : 0);
+            sdi[r] = (r < n) ? d.p[d.at(u, u)] : T(0);
+        }
+    }
+    __syncthreads();
+    // ---- alpha = Li^T z: eight threads per column, one tile row each; the loss -------------------
+    {
+        const int c = tid >> 3, ti = tid & 7, tj = c >> 4, w = c & 15;
+        T part = T(0);
+        if (ti < K && tj <= ti) {
+            const TileRef<T> t = m.x(ti, tj);
+#pragma unroll
+            for (int u = 0; u < LT; ++u)
+                part = fma(t.p[t.at(u, w)], sz[ti * LT + u], part);
+        }
+        part += __shfl_xor(part, 1, 8);
+        part += __shfl_xor(part, 2, 8);
+        part += __shfl_xor(part, 4, 8);
+        if (ti == 0)
+            sal[c] = part;
+    }
+    if (wave == 0) {  // loss = 1/2 |z|^2 - sum log(1 / l_ii)
+        double acc = 0.0;
+        for (int r = lane; r < n; r += 64)
+            acc += 0.5 * (double)sz[r] * (double)sz[r] - (double)log(sdi[r]);
+#pragma unroll
+        for (int off = 32; off >= 1; off >>= 1)
+            acc += __shfl_xor(acc, off, 64);
+        if (lane == 0)
+            loss[b] = (T)acc;
+    }
+    __syncthreads();
+
+    // ---- P_ij = sum_{k >= i} L_ki^T Lbar_kj, i >= j, with Lbar_kj built in registers; Phi ----------
+    for (int t = wave; t < ntl; t += W) {
+        int i, j;
+        tri_decode(t, i, j);
+        typename MF::acc_t acc = {0, 0, 0, 0};
+        const int w = lane & 15;
+        const T zc = sz[j * LT + w];
+        for (int k = i; k < K; ++k) {
+            T av[4], bv[4];
+            op_nat<T>(m.a(k, i), lane, av);
+#pragma unroll
+            for (int s = 0; s < 4; ++s) {  // element (u, w) of tile (k, j) of Lbar, u = 4 (lane / 16) + s
+                const int u = 4 * (lane >> 4) + s;
+                const int r = k * LT + u, c = j * LT + w;
+                T v = -sal[r] * zc;
+                if (r == c)
+                    v += sdi[r];
+                bv[s] = (r >= c) ? v : T(0);
+            }
+            acc = mma4<T>(av, bv, acc, false);
+        }
+        if (i == j) {
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                const int row = MF::row(lane, v), col = lane & 15;
+                acc[v] = row < col ? T(0) : (row == col ? T(0.5) * acc[v] : acc[v]);
+            }
+        }
+        acc_store<T>(ptile(i, j), lane, acc);
+    }
+    __syncthreads();
+
+    // ---- Z_ij = sum_{k = j..i} P_ik Li_kj, i >= j, into the area L occupied -----------------------
+    for (int t = wave; t < ntl; t += W) {
+        int i, j;
+        tri_decode(t, i, j);
+        typename MF::acc_t acc = {0, 0, 0, 0};
+        for (int k = j; k <= i; ++k) {
+            T av[4], bv[4];
+            op_rows<T>(ptile(i, k), lane, av);
+            op_nat<T>(m.x(k, j), lane, bv);
+            acc = mma4<T>(av, bv, acc, false);
+        }
+        acc_store<T>(m.a(i, j), lane, acc);
+    }
+    __syncthreads();
+
+    // ---- Abar_ij = 1/2 sum_{k >= i} (Li_ki^T Z_kj + Z_ki^T Li_kj), i >= j, stored with its mirror ----
+    {
+        T *op = Abar.p + b * Abar.bs;
+        const bool colfast = (Abar.cs == 1) || (Abar.rs != 1);
+        const int f = lane & 15, s0 = lane >> 4;
+        for (int t = wave; t < ntl; t += W) {
+            int i, j;
+            tri_decode(t, i, j);
+            typename MF::acc_t acc = {0, 0, 0, 0};
+            for (int k = i; k < K; ++k) {
+                T av[4], bv[4];
+                op_nat<T>(m.x(k, i), lane, av);
+                op_nat<T>(m.a(k, j), lane, bv);
+                acc = mma4<T>(av, bv, acc, false);
+                op_nat<T>(m.a(k, i), lane, av);
+                op_nat<T>(m.x(k, j), lane, bv);
+                acc = mma4<T>(av, bv, acc, false);
+            }
+#pragma unroll
+            for (int v = 0; v < 4; ++v)
+                acc[v] *= T(0.5);
+            const TileRef<T> st = ptile(i, j);
+            acc_store<T>(st, lane, acc);
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                const int u = colfast ? s0 + 4 * v : f, w = colfast ? f : s0 + 4 * v;
+                const T direct = st.p[st.at(u, w)], mirror = st.p[st.at(w, u)];
+                const int r = i * LT + u, c = j * LT + w;
+                if (r < n && c < n)
+                    op[(int64_t)r * Abar.rs + (int64_t)c * Abar.cs] = (i == j && u < w) ? mirror : direct;
+                const int r2 = j * LT + u, c2 = i * LT + w;
+                if (i != j && r2 < n && c2 < n)
+                    op[(int64_t)r2 * Abar.rs + (int64_t)c2 * Abar.cs] = mirror;
+            }
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------------
 // trsm (section 4.2) with a small triangular matrix and a few right-hand sides: n <= 128 and
 // m <= 48 vectors X(e, v), one workgroup per batch item.  Block substitution over the 16-row
 // tiles with the inverted diagonal tiles:
@@ -1025,5 +1250,33 @@ template la_status launch_backward_leaf16<float>(View<const float>, View<const f
                                                  hipStream_t);
 template la_status launch_backward_leaf16<double>(View<const double>, View<const double>, View<double>, int64_t, int,
                                                   hipStream_t);
+
+template <typename T>
+la_status launch_gp_leaf16(View<const T> A, const T *y, T *loss, View<T> Abar, int32_t *info, int64_t batch, int n,
+                           hipStream_t st)
+{
+    if (batch <= 0 || n <= 0)
+        return LA_OK;
+    if (n > backward_leaf16_max_n<T>() || batch > 0x7fffffffll)
+        return LA_ERR_UNSUPPORTED;
+    const int K = (n + LT - 1) / LT;
+    const size_t lds_bytes = (3 * (size_t)backward16_area<T>(K) + 4 * LT * LK) * sizeof(T);
+    static bool configured[64] = {};
+    int dev = 0;
+    LA_HIP(hipGetDevice(&dev));
+    if (dev >= 0 && dev < 64 && !configured[dev]) {
+        const size_t most = (3 * (size_t)backward16_area<T>(backward_leaf16_max_n<T>() / LT) + 4 * LT * LK) * sizeof(T);
+        LA_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&k_gp_leaf16<T>),
+                                   hipFuncAttributeMaxDynamicSharedMemorySize, (int)most));
+        configured[dev] = true;
+    }
+    hipLaunchKernelGGL((k_gp_leaf16<T>), dim3((unsigned)batch), dim3(LEAF16_THREADS), lds_bytes, st, A, y, loss, Abar,
+                       info, batch, n);
+    return launch_check("gp_leaf16");
+}
+template la_status launch_gp_leaf16<float>(View<const float>, const float *, float *, View<float>, int32_t *, int64_t,
+                                           int, hipStream_t);
+template la_status launch_gp_leaf16<double>(View<const double>, const double *, double *, View<double>, int32_t *,
+                                            int64_t, int, hipStream_t);
 
 }  // namespace la
