@@ -131,6 +131,42 @@ def test_random_case(la, orc, case):
         assert relerr(out, orc.potri(F, lower=lower)) <= 10 * tol
 
 
+@pytest.mark.parametrize("case", list(range(40)))
+def test_random_workload_case(la, orc, case):
+    """The two one-launch workloads at random shapes: GP criterion + gradient, Kalman filter."""
+    rng = np.random.default_rng(99000 + case)
+    dtype = "f64" if rng.integers(0, 2) else "f32"
+    dt = workloads.np_dtype(dtype)
+    tol = 4 * TOL[dtype]
+    if case % 2 == 0:
+        n = int(rng.integers(1, 161))
+        batch = int(rng.integers(1, 20))
+        sys.stderr.write(f"\n[gpu-case] random workload {case}: gp_criterion {dtype} n={n} batch={batch}\n")
+        sys.stderr.flush()
+        A, y = spd(rng, batch, n, dt), rng.standard_normal((batch, n)).astype(dt)
+        L = orc.potrf(A)
+        z = orc.trsm(L, y[..., None])
+        al = orc.trsm(L, z, trans=True)
+        loss_r, Lbar = orc.gp_glue(L, y, z[..., 0], al[..., 0])
+        loss, Abar = la.gp_criterion(dev(A), dev(y))
+        assert np.max(np.abs(host(loss) - loss_r) / np.maximum(np.abs(loss_r), 1.0)) <= tol
+        assert relerr(host(Abar), orc.potrf_backward(L, Lbar)) <= tol
+    else:
+        batch, T = int(rng.integers(1, 70)), int(rng.integers(1, 30))
+        dh, dv = int(rng.integers(1, 17)), int(rng.integers(1, 17))
+        shared = bool(rng.integers(0, 2))
+        sys.stderr.write(f"\n[gpu-case] random workload {case}: kalman {dtype} batch={batch} T={T} dh={dh} dv={dv} "
+                         f"shared={shared}\n")
+        sys.stderr.flush()
+        w = workloads.make_kalman(batch, T, dh, dv, dtype=dtype, shared=shared, seed=case)
+        keys = ("A", "B", "Sh", "Sv", "mu0", "S0", "v")
+        nll_r, f_r, F_r, _ = orc.kalman_filter(*(w[k] for k in keys))
+        nll, f, F = la.kalman_filter(*(dev(w[k]) for k in keys))
+        assert np.all(np.abs(host(nll) - nll_r) <= tol * np.maximum(1.0, np.abs(nll_r)))
+        assert relerr(host(f).reshape(batch, -1), f_r.reshape(batch, -1)) <= tol
+        assert relerr(host(F).reshape(batch, -1), F_r.reshape(batch, -1)) <= tol
+
+
 @pytest.mark.parametrize("dtype", ["f64", "f32"])
 def test_one_workgroup_kernels_with_many_matrices(la, orc, dtype):
     """Thousands of workgroups of the LDS-resident kernels (several per compute unit in flight, many
