@@ -125,10 +125,22 @@ static inline View<const T> cv(View<T> v)
 // inverted (upto >= n: the whole matrix).  Tmp: scratch of at least n*n/2 per item.
 // ---------------------------------------------------------------------------------
 template <typename T>
+static la_status inverse_merge(View<const T> Lam, View<T> Inv, View<T> Tmp, int64_t batch, int n, int upto,
+                               hipStream_t st);
+
+template <typename T>
 static la_status inverse_build(View<const T> Lam, View<T> Inv, View<T> Tmp, int64_t batch, int n, int upto,
                                hipStream_t st)
 {
     LA_TRY(launch_tri_inverse128<T>(Lam, Inv, batch, n, st));
+    return inverse_merge<T>(Lam, Inv, Tmp, batch, n, upto, st);
+}
+
+// The merge levels of inverse_build alone: Inv already holds the inverses of the 128 x 128 diagonal blocks.
+template <typename T>
+static la_status inverse_merge(View<const T> Lam, View<T> Inv, View<T> Tmp, int64_t batch, int n, int upto,
+                               hipStream_t st)
+{
     for (int64_t h = 2 * NB; h < upto && h < n; h *= 2) {
         const int nfull = (int)(n / (2 * h));                       // pairs whose right block is a full h
         const int r = (int)(n - (int64_t)nfull * 2 * h - h);        // rows of a ragged right block (if > 0)
@@ -156,6 +168,34 @@ static la_status inverse_build(View<const T> Lam, View<T> Inv, View<T> Tmp, int6
 }
 
 // ---------------------------------------------------------------------------------
+// Right-looking blocked potrf with panels of 128 columns: per panel one leaf launch (factor and
+// inverse of the diagonal block), one product for the rows below (L21 = A21 Li11^T) and one for
+// the trailing lower triangle.  No merged inverses, so fewer launches than the recursion for a
+// stand-alone problem of a few panels; every update has K = 128 only, which is why large
+// matrices take the recursion.
+// ---------------------------------------------------------------------------------
+template <typename T>
+static la_status potrf_right_looking(View<T> Wk, View<T> L, int32_t *info, int off, int64_t batch, int n, View<T> Inv,
+                                     hipStream_t st)
+{
+    constexpr int P = 2 * NB;
+    for (int o = 0; o < n; o += P) {
+        const int nb = n - o < P ? n - o : P, r = n - o - nb;
+        LA_TRY(launch_potrf_leaf16<T>(cv(Wk).sub(o, o), L.sub(o, o), Inv.sub(o, o), info, off + o, batch, nb, false, st));
+        if (r == 0)
+            break;
+        View<T> L21 = L.sub(o + nb, o);
+        GemmOpts op;
+        op.triB = 2;  // Li11^T is upper triangular
+        LA_TRY(launch_gemm<T>(cv(Wk).sub(o + nb, o), cv(Inv).sub(o, o).t(), L21, batch, r, nb, nb, T(1), T(0), op, st));
+        GemmOpts ou;
+        ou.maskC = 1;
+        LA_TRY(launch_gemm<T>(cv(L21), cv(L21).t(), Wk.sub(o + nb, o + nb), batch, r, r, nb, T(-1), T(1), ou, st));
+    }
+    return LA_OK;
+}
+
+// ---------------------------------------------------------------------------------
 // Blocked potrf by recursive halving (section 4.2: A = L L^T).  Wk holds the lower triangle of
 // the block still to be factored (a working copy, updated in place), L receives the factor, Inv
 // the inverses of the factors of the diagonal sub-blocks; off is the index of the block's first
@@ -167,23 +207,34 @@ static la_status inverse_build(View<const T> Lam, View<T> Inv, View<T> Tmp, int6
 // (need_inv; a right child needs it only if its parent does).  The extra products add one sixth
 // to the n^3 / 3 of the factorisation and remove every recursive solve.  The temporary
 // L21 Li11 lives in the unused upper-right block of the node's part of Inv.
+// The halving stops at blocks of about 2000 rows, which are factored panel by panel
+// (potrf_right_looking) and, where the parent needs it, inverted level by level with all pairs
+// of a level in one launch (inverse_merge, temporary in Tmp): the long dependent chain of small
+// launches at the bottom of the recursion is what a large factorisation waits for.
 // ---------------------------------------------------------------------------------
 template <typename T>
 static la_status potrf_rec(View<T> Wk, View<T> L, int32_t *info, int off, int64_t batch, int n, View<T> Inv,
-                           bool need_inv, hipStream_t st)
+                           View<T> Tmp, bool need_inv, hipStream_t st)
 {
     if (n <= 2 * NB)  // factor and inverse in one launch
         return launch_potrf_leaf16<T>(cv(Wk), L, Inv, info, off, batch, n, false, st);
+    // Blocks of up to 2304 rows: panel by panel.  Measured against halving all the way down: one matrix
+    // of n = 2048 0.95 -> 0.77 ms, 3000 1.78 -> 1.38, 4096 2.58 -> 2.19, 8192 8.62 -> 7.89 (fp64); with many
+    // matrices in the batch the short products of the panels stop paying (32 x 1024: 0.91 -> 0.93).
+    if (n <= 2304 && (double)batch * n * n < 24e6) {
+        LA_TRY(potrf_right_looking<T>(Wk, L, info, off, batch, n, Inv, st));
+        return need_inv ? inverse_merge<T>(cv(L), Inv, Tmp, batch, n, n, st) : LA_OK;
+    }
     const int n1 = split_point(n), n2 = n - n1;
     View<T> L21 = L.sub(n1, 0), Wk22 = Wk.sub(n1, n1);
-    LA_TRY(potrf_rec<T>(Wk, L, info, off, batch, n1, Inv, true, st));
+    LA_TRY(potrf_rec<T>(Wk, L, info, off, batch, n1, Inv, Tmp, true, st));
     GemmOpts op;
     op.triB = 2;  // Li11^T is upper triangular
     LA_TRY(launch_gemm<T>(cv(Wk).sub(n1, 0), cv(Inv).t(), L21, batch, n2, n1, n1, T(1), T(0), op, st));
     GemmOpts ou;
     ou.maskC = 1;  // trailing update of the lower triangle: A22 -= L21 L21^T
     LA_TRY(launch_gemm<T>(cv(L21), cv(L21).t(), Wk22, batch, n2, n2, n1, T(-1), T(1), ou, st));
-    LA_TRY(potrf_rec<T>(Wk22, L.sub(n1, n1), info, off + n1, batch, n2, Inv.sub(n1, n1), need_inv, st));
+    LA_TRY(potrf_rec<T>(Wk22, L.sub(n1, n1), info, off + n1, batch, n2, Inv.sub(n1, n1), Tmp, need_inv, st));
     if (!need_inv)
         return LA_OK;
     View<T> T1 = Inv.sub(0, n1).t();  // n2 x n1 temporary in the upper-right block
@@ -347,10 +398,10 @@ static la_status potrf_t(int lower, int64_t batch, int n, const void *A, void *L
         LA_TRY(scratch_views<T>(batch, n, 1, &Inv));
         return launch_potrf_leaf16<T>(Av, Lv, Inv, info, 0, batch, n, true, st);
     }
-    View<T> sc[2];  // inverses of the diagonal blocks; working copy of the lower triangle of A
-    LA_TRY(scratch_views<T>(batch, n, 2, sc));
+    View<T> sc[3];  // inverses of the diagonal blocks; working copy of the lower triangle of A; merge temporary
+    LA_TRY(scratch_views<T>(batch, n, 3, sc));
     LA_TRY(launch_tril_split<T>(Av, sc[1], Lv, batch, n, st));  // zeros above the diagonal of L
-    return potrf_rec<T>(sc[1], Lv, info, 0, batch, n, sc[0], false, st);
+    return potrf_rec<T>(sc[1], Lv, info, 0, batch, n, sc[0], sc[2], false, st);
 }
 
 // trsm / trmm (section 4.2).  vectors: columns of A/B (left) or rows (right); X(e, v) = element e
