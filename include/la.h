@@ -26,8 +26,9 @@
  *  - Return value: LA_OK, or LA_ERR_INVALID_ARG (null pointer with non-empty
  *    work, negative size, bad enum, forbidden aliasing), LA_ERR_UNSUPPORTED,
  *    LA_ERR_RUNTIME (a HIP call failed; see la_last_error()).
- *  - Small problems (potrf with n <= 64, backward with n <= 32, trsm with n <= 128
- *    and at most 48 right-hand sides, syrk, gemm2, sumlogdiag, gp_glue) allocate
+ *  - Small problems (potrf with n <= 64, backward with n <= 128 in fp32 and <= 96 in
+ *    fp64, trsm with n <= 128 and at most 48 right-hand sides, syrk, gemm2, sumlogdiag,
+ *    gp_glue, gp_criterion up to the same n as backward, kalman_filter) allocate
  *    nothing.  The blocked paths for larger n keep one scratch buffer per device
  *    (explicit inverses of the factor or of its diagonal blocks, a working copy of
  *    the triangle being factored or one work panel, at most 3*batch*n*n elements; and,

@@ -27,9 +27,9 @@ void set_error(hipError_t e, const char *where)
 }
 
 // ---------------------------------------------------------------------------------
-// Scratch memory of the blocked paths (n > 64 for potrf / trsm, n > 32 for the backward pass):
-// inverses of (diagonal blocks of) the triangular factor and one work matrix, at most
-// 2 * batch * n * n elements.  One buffer per device, grown on demand with hipMalloc and kept
+// Scratch memory of the blocked paths (n > 64 for potrf / trsm, n > 128 (fp64: 96) for the backward
+// pass): inverses of (diagonal blocks of) the triangular factor, a work matrix and a temporary of
+// the inverse merges, at most 3 * batch * n * n elements.  One buffer per device, grown on demand with hipMalloc and kept
 // until the process ends; a buffer that is outgrown is parked, not freed, because work queued
 // on a stream may still be using it.  Calls that use it must therefore not run concurrently
 // on several streams of one device.
