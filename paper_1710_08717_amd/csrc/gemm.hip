@@ -333,25 +333,35 @@ __device__ __forceinline__ void slab_commit(T *s, RV &r, int o0, int k0, int tri
 {
     using S = Slab<T, OUT, BK, KF>;
     using V = typename Mfma<T>::vec_t;
-    // does this slab touch the zero side of a triangular operand at all?
+    // Does this slab touch the zero side of a triangular operand at all?  Decided once per slab
+    // (a scalar branch); most slabs do not and take the plain copy below.
     bool need_mask = false;
     if (tri == 1)
         need_mask = (o0 < k0 + BK - 1);  // keep o >= k: some (o, k) with o < k exists
     else if (tri == 2)
         need_mask = (o0 + OUT - 1 > k0);
+    if (!need_mask) {
+#pragma unroll
+        for (int c = 0; c < S::NCH; ++c) {
+            int o, k;
+            S::coords(c, o, k);
+            *reinterpret_cast<V *>(s + o * S::so + k * S::sk) = r[c];
+        }
+        return;
+    }
+    // keep o >= k (tri 1) or o <= k (tri 2): with d = (o - k) for tri 1 and (k - o) for tri 2, keep d >= 0
+    const int sgn = tri == 1 ? 1 : -1;
 #pragma unroll
     for (int c = 0; c < S::NCH; ++c) {
         int o, k;
         S::coords(c, o, k);
         V v = r[c];
-        if (need_mask) {
-            T *e = reinterpret_cast<T *>(&v);
+        T *e = reinterpret_cast<T *>(&v);
+        const int d0 = sgn * ((o0 + o) - (k0 + k));
 #pragma unroll
-            for (int u = 0; u < S::VW; ++u) {
-                const int og = o0 + o + (KF ? 0 : u), kg = k0 + k + (KF ? u : 0);
-                if (!tri_keep(tri, og, kg))
-                    e[u] = T(0);
-            }
+        for (int u = 0; u < S::VW; ++u) {
+            const int d = d0 + (KF ? -sgn * u : sgn * u);  // element u moves along k (KF) or along o
+            e[u] = d >= 0 ? e[u] : T(0);
         }
         *reinterpret_cast<V *>(s + o * S::so + k * S::sk) = v;
     }
