@@ -299,7 +299,8 @@ la_status launch_backward_tiny(View<const T> L, View<const T> G, View<T> Abar, i
 struct GemmOpts {
     int triA = 0;      // 1: A(i,k) is zero for i < k (lower), 2: zero for i > k (upper)
     int triB = 0;      // same on (k,j)
-    int maskC = 0;     // 1: only entries with i >= j are written, 2: only i <= j
+    int maskC = 0;     // 1: only entries with i >= j are written, 2: only i <= j; 3 (set by the launcher): only the
+                       // tiles with tile column <= tile row, written whole
     int halfDiag = 0;  // 1: the update of entries with i == j is halved
     int reverse = 0;   // 1: schedule the tiles last-to-first (heavy tiles of triangular work first)
     int shells = 0;    // 1: square problem whose K range depends on max(i, j): schedule by shells
