@@ -784,26 +784,32 @@ la_status launch_gemm(View<const T> A, View<const T> B, View<T> C, int64_t batch
         } else {
             // Equal tiles: big tiles once they fill most of the chip, quarter tiles when 64 x 64
             // tiles would leave most compute units idle.
-            const int64_t t128 = (int64_t)((M + 127) / 128) * ((N + 127) / 128) * batch;
+            const int64_t t128 = o.maskC ? wg128 : (int64_t)((M + 127) / 128) * ((N + 127) / 128) * batch;
             const bool big = o.maskC ? (M >= 2048 && N >= 2048) : (M >= 128 && N >= 128);
             e = (t128 >= 192 && big) ? 128 : ((wg64 <= 256 && k64 && !o.min_tile64) ? 32 : 64);
         }
-        if (e == 128 && o.maskC == 1 && !o.triA && !o.triB && !o.halfDiag && !o.shells && M == N && M % 128 == 0 &&
-            A.nb2 == 1 && B.nb2 == 1 && C.nb2 == 1) {
-            // Lower triangle in 128 x 128 tiles: T (T + 1) / 2 of them.  When that is a few tiles more than
+        if (e >= 64 && o.maskC == 1 && !o.triA && !o.triB && !o.halfDiag && !o.shells && !o.min_tile64 && M == N &&
+            M % e == 0 && A.nb2 == 1 && B.nb2 == 1 && C.nb2 == 1) {
+            // Lower triangle in e x e tiles: T (T + 1) / 2 of them.  When that is a few tiles more than
             // whole rounds of the 512 workgroup slots (T = 32: 528), the last round runs nearly empty.
             // The T diagonal tiles only need their lower halves anyway: take the T (T - 1) / 2 tiles
             // below the diagonal in one launch (whole tiles, no masking) and the diagonal blocks as a
             // batch of T small lower-triangle products.
-            const int64_t Tt = M / 128, per = Tt * (Tt + 1) / 2, spill = per % 512, below = (per - Tt) % 512;
+            const int64_t Tt = M / e, per = Tt * (Tt + 1) / 2, spill = per % 512, below = (per - Tt) % 512;
             if (batch == 1 && per > 512 && spill > 0 && spill <= 64 && (below == 0 || below > 256)) {
                 GemmOpts lo = o;
-                lo.maskC = 3;  // tiles with tn <= tm of the view that starts 128 rows down, nothing masked inside
-                launch_fast<T, 128, 128, 16, 2>(akf, bkf, A.sub(128, 0), B, C.sub(128, 0), batch, M - 128, N - 128, K, alpha,
-                                                beta, lo, st);
+                lo.maskC = 3;  // tiles with tn <= tm of the view that starts e rows down, nothing masked inside
+                View<const T> A1 = A.sub(e, 0);
+                View<T> C1 = C.sub(e, 0);
+                if (e == 128)
+                    launch_fast<T, 128, 128, 16, 2>(akf, bkf, A1, B, C1, batch, M - e, N - e, K, alpha, beta, lo, st);
+                else if (k64)
+                    launch_fast<T, 64, 64, 64, 1>(akf, bkf, A1, B, C1, batch, M - e, N - e, K, alpha, beta, lo, st);
+                else
+                    launch_fast<T, 64, 64, 16, 2>(akf, bkf, A1, B, C1, batch, M - e, N - e, K, alpha, beta, lo, st);
                 LA_TRY(launch_check("gemm_fast"));
-                return launch_gemm<T>(A.level2(128 * A.rs, (int)Tt), B.level2(128 * B.cs, (int)Tt),
-                                      C.level2(128 * (C.rs + C.cs), (int)Tt), batch * Tt, 128, 128, K, alpha, beta, o, st);
+                return launch_gemm<T>(A.level2((int64_t)e * A.rs, (int)Tt), B.level2((int64_t)e * B.cs, (int)Tt),
+                                      C.level2((int64_t)e * (C.rs + C.cs), (int)Tt), batch * Tt, e, e, K, alpha, beta, o, st);
             }
         }
         if (e == 128)
