@@ -356,6 +356,20 @@ def test_potrf_backward_blocked_sweep(la, orc, dtype, lower, batch, n):
 # syrk / sumlogdiag / GP glue
 # ----------------------------------------------------------------------------
 @pytest.mark.parametrize("dtype", ["f64", "f32"])
+@pytest.mark.parametrize("n,k", [(2048, 64), (2880, 32), (4096, 48), (4096, 2064)])
+def test_syrk_large_lower_triangle_tile_counts(la, orc, dtype, n, k):
+    """Outputs whose lower-triangle tile count is a few tiles over whole rounds of workgroup slots
+    (32 or 45 tile rows): the launcher issues the tiles below the diagonal and the diagonal blocks
+    separately."""
+    rng = np.random.default_rng(n + k)
+    A = rng.standard_normal((1, n, k)).astype(npdt(dtype))
+    ref = orc.syrk(A, alpha=0.25)
+    out = host(la.syrk(dev(A), alpha=0.25))
+    assert np.array_equal(out, out.transpose(0, 2, 1))
+    assert relerr(out, ref) <= TOL[dtype]
+
+
+@pytest.mark.parametrize("dtype", ["f64", "f32"])
 @pytest.mark.parametrize("trans", [False, True])
 @pytest.mark.parametrize("n,k", [(1, 1), (4, 9), (16, 32), (32, 64), (65, 17), (130, 200), (64, 0), (50, 9568), (200, 2064),
                                  (64, 4096)])
