@@ -427,3 +427,25 @@ def test_gp_glue_parity(la, orc, dtype, n):
     assert np.all(np.triu(G, 1) == 0.0)
     assert relerr(G, ref_G) <= TOL[dtype]
     assert np.max(np.abs(loss - ref_loss) / np.maximum(np.abs(ref_loss), 1.0)) <= TOL[dtype]
+
+
+@pytest.mark.parametrize("dtype", ["f64", "f32"])
+def test_blocked_paths_at_condition_1e3(la, orc, dtype):
+    """The blocked paths lean on explicit inverses of (blocks of) the factor; the tolerances are
+    stated for condition numbers up to 1e3, so here is a matrix with exactly that spectrum
+    (eigenvalues spread evenly in the logarithm from 1 to 1000) at a size where potrf goes panel
+    by panel with merged inverses, the backward pass sweeps the blocked factorisation and trsm
+    substitutes block by block."""
+    rng = np.random.default_rng(1003)
+    batch, n = 3, 1400
+    Q, _ = np.linalg.qr(rng.standard_normal((batch, n, n)))
+    A = (Q * np.logspace(0, 3, n)[None, None, :]) @ Q.transpose(0, 2, 1)
+    A = (0.5 * (A + A.transpose(0, 2, 1))).astype(npdt(dtype))
+    assert 900 <= np.linalg.cond(A[0].astype(np.float64)) <= 1100
+    G = np.tril(rng.standard_normal((batch, n, n))).astype(npdt(dtype))
+    R = rng.standard_normal((batch, n, 70)).astype(npdt(dtype))
+    L = la.potrf(dev(A))
+    Lh = host(L)
+    assert relerr(Lh, orc.potrf(A)) <= TOL[dtype]
+    assert relerr(host(la.potrf_backward(L, dev(G))), orc.potrf_backward(Lh, G)) <= TOL[dtype]
+    assert relerr(host(la.trsm(L, dev(R))), orc.trsm(Lh, R)) <= TOL[dtype]
