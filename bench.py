@@ -48,7 +48,9 @@ def backward_flops(n, batch, elem_size):
     def rec(k):
         if k <= base:
             return 2.0 * k ** 3
-        k1 = (k // 2 + 127) // 128 * 128
+        q = k // 2048
+        halves_fit = k % 2048 == 0 and q & (q - 1) == 0
+        k1 = 2048 if (k > 4096 and not halves_fit) else (k // 2 + 127) // 128 * 128
         k2 = k - k1
         return 2.0 * k1 * k2 * k + rec(k1) + rec(k2)
 
