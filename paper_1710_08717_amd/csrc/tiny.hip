@@ -33,9 +33,9 @@ struct VecOf<double> {
 
 // LDS staging area of one wave: MPW matrices of G x G, rows padded by 16 bytes and
 // matrices by 64 bytes so row reads, column reads and the flat fill are conflict-poor.
-template <typename T, int G>
+template <typename T, int G, int MPW_ = WAVE / G>
 struct Stage {
-    static constexpr int MPW = WAVE / G;
+    static constexpr int MPW = MPW_;
     static constexpr int PAD = 16 / sizeof(T);
     static constexpr int LD = G + PAD;
     static constexpr int MS = G * LD + 64 / sizeof(T);
@@ -57,10 +57,10 @@ __device__ __forceinline__ Mem<T> mem_of(View<T> V)
     return {V.p, V.bs, tr ? V.cs : V.rs, tr};
 }
 
-template <typename T, int G>
+template <typename T, int G, int MPW = WAVE / G>
 __device__ __forceinline__ bool flat_ok(const T *p, int64_t bs, int64_t ld, int64_t b0, int64_t batch, int nb)
 {
-    return nb == G && ld == G && bs == G * G && b0 + Stage<T, G>::MPW <= batch &&
+    return nb == G && ld == G && bs == G * G && b0 + MPW <= batch &&
            (reinterpret_cast<uintptr_t>(p) & 15) == 0;
 }
 
@@ -69,13 +69,13 @@ __device__ __forceinline__ bool flat_ok(const T *p, int64_t bs, int64_t ld, int6
 // (Leaving out the 16-byte pieces that lie entirely in the unused triangle was tried: the HBM
 // fetch counter did not move -- rows are fetched in units of at least 64 bytes -- and the
 // predicated loads made the kernels slower.)
-template <typename T, int G>
+template <typename T, int G, int MPW = WAVE / G>
 __device__ __forceinline__ void stage_load(T *sm, Mem<const T> M, int64_t b0, int64_t batch, int nb)
 {
-    using S = Stage<T, G>;
+    using S = Stage<T, G, MPW>;
     const int lane = threadIdx.x;
     // fast path: full G x G matrices stored back to back -> one flat vectorised copy
-    if (flat_ok<T, G>(M.p, M.bs, M.ld, b0, batch, nb)) {
+    if (flat_ok<T, G, MPW>(M.p, M.bs, M.ld, b0, batch, nb)) {
         using V4 = typename VecOf<T>::type;
         constexpr int VN = VecOf<T>::N;
         const V4 *src = reinterpret_cast<const V4 *>(M.p + b0 * M.bs);
@@ -89,24 +89,33 @@ __device__ __forceinline__ void stage_load(T *sm, Mem<const T> M, int64_t b0, in
         }
         return;
     }
-#pragma unroll 4
-    for (int t = 0; t < S::MPW * G * G / WAVE; ++t) {
-        int e = t * WAVE + lane;
-        int q = e / (G * G);
-        int r = (e / G) % G, c = e % G;
-        T v = (r == c) ? T(1) : T(0);
-        if (b0 + q < batch && r < nb && c < nb)
-            v = M.p[(b0 + q) * M.bs + r * M.ld + c];
-        sm[q * S::MS + r * S::LD + c] = v;
+    // all loads of a batch of 16 first, then the LDS writes: the loads are in flight together
+    constexpr int NIT = S::MPW * G * G / WAVE, CH = NIT < 16 ? NIT : 16;
+    for (int t0 = 0; t0 < NIT; t0 += CH) {
+        T v[CH];
+#pragma unroll
+        for (int u = 0; u < CH; ++u) {
+            const int e = (t0 + u) * WAVE + lane;
+            const int q = e / (G * G), r = (e / G) % G, c = e % G;
+            v[u] = (r == c) ? T(1) : T(0);
+            if (b0 + q < batch && r < nb && c < nb)
+                v[u] = M.p[(b0 + q) * M.bs + r * M.ld + c];
+        }
+#pragma unroll
+        for (int u = 0; u < CH; ++u) {
+            const int e = (t0 + u) * WAVE + lane;
+            const int q = e / (G * G), r = (e / G) % G, c = e % G;
+            sm[q * S::MS + r * S::LD + c] = v[u];
+        }
     }
 }
 
-template <typename T, int G>
+template <typename T, int G, int MPW = WAVE / G>
 __device__ __forceinline__ void stage_store(const T *sm, Mem<T> M, int64_t b0, int64_t batch, int nb)
 {
-    using S = Stage<T, G>;
+    using S = Stage<T, G, MPW>;
     const int lane = threadIdx.x;
-    if (flat_ok<T, G>(M.p, M.bs, M.ld, b0, batch, nb)) {
+    if (flat_ok<T, G, MPW>(M.p, M.bs, M.ld, b0, batch, nb)) {
         using V4 = typename VecOf<T>::type;
         constexpr int VN = VecOf<T>::N;
         V4 *dst = reinterpret_cast<V4 *>(M.p + b0 * M.bs);
@@ -257,6 +266,92 @@ __global__ __launch_bounds__(WAVE) void k_potrf_tiny(View<const T> A, View<T> L,
 }
 
 // ---------------------------------------------------------------------------------
+// potrf forward for 16 < n <= 32 in 16 lanes per matrix: lane i holds rows i and i + 16, so that
+// every broadcast stays inside a 16-lane DPP row (one instruction with the multiply-add) instead
+// of going through the LDS crossbar as with 32 lanes per matrix; four matrices per wavefront.
+// Column j = 16 jh + jl: its entries sit in register j of row slot jh of lane jl.
+// ---------------------------------------------------------------------------------
+template <typename T>
+__global__ __launch_bounds__(WAVE) void k_potrf_tiny2(View<const T> A, View<T> L, int32_t *info, int info_off,
+                                                       int64_t batch, int nb)
+{
+    constexpr int N = 32, G = 16, MPW = WAVE / G;
+    using S = Stage<T, N, MPW>;
+    __shared__ __align__(16) T sm[S::ELEMS];
+    const int lane = threadIdx.x;
+    const int q = lane / G, i = lane % G;
+    const int64_t b0 = (int64_t)blockIdx.x * MPW;
+
+    const Mem<const T> Am = mem_of(A);
+    const Mem<T> Lm = mem_of(L);
+    stage_load<T, N, MPW>(sm, Am, b0, batch, nb);
+    __syncthreads();
+    T a0[N], a1[N];  // rows i and i + 16
+    read_lrow<T, N>(sm + q * S::MS, i, Am.tr, a0);
+    read_lrow<T, N>(sm + q * S::MS, i + G, Am.tr, a1);
+#pragma unroll
+    for (int k = 0; k < N; ++k) {
+        if (k > i)
+            a0[k] = T(0);  // the other triangle of A is never used
+        if (k > i + G)
+            a1[k] = T(0);
+    }
+
+    int fail = 0;
+    static_for<0, N>([&](auto J) {
+        constexpr int j = decltype(J)::value;
+        constexpr int jl = j % G, jh = j / G;
+        T piv = group_bcast<G>(jh ? a1[j] : a0[j], jl);  // a_jj after the updates of columns < j
+        if (!(piv > T(0)) && fail == 0)
+            fail = j + 1;
+        T r = rsqrt_acc(piv);
+        if constexpr (jh == 0)
+            a0[j] = (i >= j) ? a0[j] * r : T(0);  // column j of L (row j gets sqrt(piv))
+        a1[j] = (i + G >= j) ? a1[j] * r : T(0);
+        if constexpr (jh == 0)
+            dpp_settle1<G>(a0[j]);
+        dpp_settle1<G>(a1[j]);
+        static_for<j + 1, N>([&](auto K) {
+            constexpr int k = decltype(K)::value;
+            constexpr int kl = k % G, kh = k / G;
+            // a_rk -= l_rj l_kj, with l_kj in row slot kh of lane kl
+            if constexpr (jh == 0) {  // rows below 16 have nothing left of columns >= 16
+                if constexpr (kh == 0)
+                    fma_bcast<G, kl>(a0[k], a0[j], a0[j], true);
+                else
+                    fma_bcast<G, kl>(a0[k], a1[j], a0[j], true);
+            }
+            if constexpr (kh == 0)
+                fma_bcast<G, kl>(a1[k], a0[j], a1[j], true);
+            else
+                fma_bcast<G, kl>(a1[k], a1[j], a1[j], true);
+        });
+    });
+#pragma unroll
+    for (int k = 0; k < N; ++k) {
+        if (k > i)
+            a0[k] = T(0);
+        if (k > i + G)
+            a1[k] = T(0);
+    }
+
+    __syncthreads();
+    if (Lm.tr) {
+        write_col<T, N>(sm + q * S::MS, i, a0);
+        write_col<T, N>(sm + q * S::MS, i + G, a1);
+    } else {
+        write_row<T, N>(sm + q * S::MS, i, a0);
+        write_row<T, N>(sm + q * S::MS, i + G, a1);
+    }
+    __syncthreads();
+    stage_store<T, N, MPW>(sm, Lm, b0, batch, nb);
+    if (info != nullptr && i == 0 && b0 + q < batch && fail != 0 && fail <= nb) {
+        if (info[b0 + q] == 0)
+            info[b0 + q] = info_off + fail;
+    }
+}
+
+// ---------------------------------------------------------------------------------
 // potrf backward for n <= G.  Views give the logical lower-triangular L and Lbar.
 // ---------------------------------------------------------------------------------
 template <typename T, int G>
@@ -372,9 +467,8 @@ la_status launch_potrf_tiny(View<const T> A, View<T> L, int32_t *info, int info_
         hipLaunchKernelGGL((k_potrf_tiny<T, 16>), dim3((unsigned)((batch + MPW - 1) / MPW)), dim3(WAVE), 0, st, A, L,
                            info, info_off, batch, nb);
     } else if (nb <= 32) {
-        constexpr int MPW = Stage<T, 32>::MPW;
-        hipLaunchKernelGGL((k_potrf_tiny<T, 32>), dim3((unsigned)((batch + MPW - 1) / MPW)), dim3(WAVE), 0, st, A, L,
-                           info, info_off, batch, nb);
+        hipLaunchKernelGGL((k_potrf_tiny2<T>), dim3((unsigned)((batch + 3) / 4)), dim3(WAVE), 0, st, A, L, info,
+                           info_off, batch, nb);
     } else {
         hipLaunchKernelGGL((k_potrf_tiny<T, 64>), dim3((unsigned)batch), dim3(WAVE), 0, st, A, L, info, info_off,
                            batch, nb);
