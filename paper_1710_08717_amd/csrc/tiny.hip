@@ -454,6 +454,156 @@ __global__ __launch_bounds__(WAVE) void k_backward_tiny(View<const T> Lv, View<c
     stage_store<T, G>(sm, mem_of(Av), b0, batch, n);  // symmetric: orientation is immaterial
 }
 
+// ---------------------------------------------------------------------------------
+// potrf backward for 16 < n <= 32 in 16 lanes per matrix (fp32): lane i owns rows i and i + 16 of
+// P, Y, W and columns i and i + 16 of L (slot h = 0, 1), so all broadcasts are DPP row broadcasts.
+// Same steps as k_backward_tiny; row / column k = 16 kh + kl lives in slot kh of lane kl.
+// ---------------------------------------------------------------------------------
+template <typename T>
+__global__ __launch_bounds__(WAVE) void k_backward_tiny2(View<const T> Lv, View<const T> Gv, View<T> Av,
+                                                          int64_t batch, int n)
+{
+    constexpr int N = 32, G = 16, MPW = WAVE / G;
+    using S = Stage<T, N, MPW>;
+    __shared__ __align__(16) T sm[S::ELEMS];
+    const int lane = threadIdx.x;
+    const int q = lane / G, i = lane % G;
+    const int64_t b0 = (int64_t)blockIdx.x * MPW;
+    T *smq = sm + q * S::MS;
+    const Mem<const T> Lm = mem_of(Lv);
+    const Mem<const T> Gm = mem_of(Gv);
+
+    // columns i and i + 16 of L: lc_h[k] = l_{k, i + 16 h} (k >= i + 16 h), reciprocal diagonals
+    T lc0[N], lc1[N];
+    stage_load<T, N, MPW>(sm, Lm, b0, batch, n);
+    __syncthreads();
+    read_lcol<T, N>(smq, i, Lm.tr, lc0);
+    read_lcol<T, N>(smq, i + G, Lm.tr, lc1);
+    T d0 = T(1), d1 = T(1);
+#pragma unroll
+    for (int k = 0; k < N; ++k) {
+        if (k == i)
+            d0 = lc0[k];
+        if (k == i + G)
+            d1 = lc1[k];
+        if (k < i)
+            lc0[k] = T(0);
+        if (k < i + G)
+            lc1[k] = T(0);
+    }
+    T rd0 = rcp_acc(d0), rd1 = rcp_acc(d1);
+    __syncthreads();
+
+    // rows i and i + 16 of Lbar
+    T g0[N], g1[N];
+    stage_load<T, N, MPW>(sm, Gm, b0, batch, n);
+    __syncthreads();
+    read_lrow<T, N>(smq, i, Gm.tr, g0);
+    read_lrow<T, N>(smq, i + G, Gm.tr, g1);
+#pragma unroll
+    for (int j = 0; j < N; ++j) {
+        if (j > i || i >= n)
+            g0[j] = T(0);  // also drops the identity padding of the stage
+        if (j > i + G || i + G >= n)
+            g1[j] = T(0);
+    }
+
+    // P = L^T Lbar: p_rj = sum_k l_kr lbar_kj (k >= r, j <= k)
+    T y0[N], y1[N];
+#pragma unroll
+    for (int j = 0; j < N; ++j) {
+        y0[j] = T(0);
+        y1[j] = T(0);
+    }
+    dpp_settle<G>(g0);
+    dpp_settle<G>(g1);
+    static_for<0, N>([&](auto K) {
+        constexpr int k = decltype(K)::value;
+        constexpr int kl = k % G, kh = k / G;
+        static_for<0, k + 1>([&](auto J) {
+            constexpr int j = decltype(J)::value;
+            if constexpr (kh == 0) {
+                fma_bcast<G, kl>(y0[j], g0[j], lc0[k], false);  // rows >= 16 have l_kr = 0 for k < 16
+            } else {
+                fma_bcast<G, kl>(y0[j], g1[j], lc0[k], false);
+                fma_bcast<G, kl>(y1[j], g1[j], lc1[k], false);
+            }
+        });
+    });
+    // Phi, then the row scaling D^-1 of L = Lt D (Lt unit lower triangular)
+#pragma unroll
+    for (int j = 0; j < N; ++j) {
+        const T v0 = (j < i) ? y0[j] : ((j == i) ? T(0.5) * y0[j] : T(0));
+        const T v1 = (j < i + G) ? y1[j] : ((j == i + G) ? T(0.5) * y1[j] : T(0));
+        y0[j] = v0 * rd0;
+        y1[j] = v1 * rd1;
+    }
+    // lt_h[k] = l_kr / l_rr for k > r, zero otherwise
+#pragma unroll
+    for (int k = 0; k < N; ++k) {
+        lc0[k] = (k > i) ? lc0[k] * rd0 : T(0);
+        lc1[k] = (k > i + G) ? lc1[k] * rd1 : T(0);
+    }
+
+    // Y = Lt^-T (D^-1 Phi): rows from the bottom; row k is final when it is broadcast
+    dpp_settle<G>(y0);
+    dpp_settle<G>(y1);
+    static_for<0, N - 1>([&](auto Tt) {
+        constexpr int k = N - 1 - decltype(Tt)::value;
+        constexpr int kl = k % G, kh = k / G;
+        static_for<0, N>([&](auto C) {
+            constexpr int c = decltype(C)::value;
+            if constexpr (kh == 0) {
+                fma_bcast<G, kl>(y0[c], y0[c], lc0[k], true);  // rows >= 16: lt[k] = 0 for k <= 16
+            } else {
+                fma_bcast<G, kl>(y0[c], y1[c], lc0[k], true);
+                fma_bcast<G, kl>(y1[c], y1[c], lc1[k], true);
+            }
+        });
+    });
+    // V = Y D^-1 (column c scaled by 1 / l_cc), then W = V Lt^-1 from the last column back
+#pragma unroll
+    for (int c = 0; c < N; ++c) {
+        const T s = group_bcast<G>(c < G ? rd0 : rd1, c % G);
+        y0[c] *= s;
+        y1[c] *= s;
+    }
+    dpp_settle<G>(lc0);
+    dpp_settle<G>(lc1);
+    static_for<0, N - 1>([&](auto Tt) {
+        constexpr int c = N - 2 - decltype(Tt)::value;
+        constexpr int cl = c % G, ch = c / G;
+        static_for<c + 1, N>([&](auto K) {
+            constexpr int k = decltype(K)::value;
+            if constexpr (ch == 0) {
+                fma_bcast<G, cl>(y0[c], lc0[k], y0[k], true);
+                fma_bcast<G, cl>(y1[c], lc0[k], y1[k], true);
+            } else {
+                fma_bcast<G, cl>(y0[c], lc1[k], y0[k], true);
+                fma_bcast<G, cl>(y1[c], lc1[k], y1[k], true);
+            }
+        });
+    });
+
+    // Abar = 1/2 (W + W^T): rows out to LDS, columns back in
+    __syncthreads();
+    write_row<T, N>(smq, i, y0);
+    write_row<T, N>(smq, i + G, y1);
+    __syncthreads();
+    read_col<T, N>(smq, i, g0);
+    read_col<T, N>(smq, i + G, g1);
+#pragma unroll
+    for (int c = 0; c < N; ++c) {
+        y0[c] = T(0.5) * (y0[c] + g0[c]);
+        y1[c] = T(0.5) * (y1[c] + g1[c]);
+    }
+    __syncthreads();
+    write_row<T, N>(smq, i, y0);
+    write_row<T, N>(smq, i + G, y1);
+    __syncthreads();
+    stage_store<T, N, MPW>(sm, mem_of(Av), b0, batch, n);  // symmetric: orientation is immaterial
+}
+
 template <typename T>
 la_status launch_potrf_tiny(View<const T> A, View<T> L, int32_t *info, int info_off, int64_t batch, int nb,
                             hipStream_t st)
@@ -487,6 +637,9 @@ la_status launch_backward_tiny(View<const T> L, View<const T> G, View<T> Abar, i
         constexpr int MPW = Stage<T, 16>::MPW;
         hipLaunchKernelGGL((k_backward_tiny<T, 16>), dim3((unsigned)((batch + MPW - 1) / MPW)), dim3(WAVE), 0, st, L,
                            G, Abar, batch, n);
+    } else if constexpr (sizeof(T) == 4) {  // 16 lanes per matrix, two rows per lane (its registers do not fit in fp64)
+        hipLaunchKernelGGL((k_backward_tiny2<T>), dim3((unsigned)((batch + 3) / 4)), dim3(WAVE), 0, st, L, G, Abar,
+                           batch, n);
     } else {
         constexpr int MPW = Stage<T, 32>::MPW;
         hipLaunchKernelGGL((k_backward_tiny<T, 32>), dim3((unsigned)((batch + MPW - 1) / MPW)), dim3(WAVE), 0, st, L,
