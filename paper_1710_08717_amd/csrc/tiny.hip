@@ -266,18 +266,20 @@ __global__ __launch_bounds__(WAVE) void k_potrf_tiny(View<const T> A, View<T> L,
 }
 
 // ---------------------------------------------------------------------------------
-// potrf forward for 16 < n <= 32 in 16 lanes per matrix: lane i holds rows i and i + 16, so that
-// every broadcast stays inside a 16-lane DPP row (one instruction with the multiply-add) instead
-// of going through the LDS crossbar as with 32 lanes per matrix; four matrices per wavefront.
-// Column j = 16 jh + jl: its entries sit in register j of row slot jh of lane jl.
+// potrf forward for 16 < n <= 16 R in 16 lanes per matrix: lane i holds the R rows i, i + 16, ...
+// so that every broadcast stays inside a 16-lane DPP row (one instruction with the multiply-add)
+// instead of going through the LDS crossbar or a scalar register as with 32 or 64 lanes per
+// matrix; four matrices per wavefront.  Column j = 16 jh + jl: its entries sit in register j of
+// row slot jh of lane jl.  R = 2 in fp32 and fp64, R = 3 (n <= 48) in fp32 (R N registers per lane).
 // ---------------------------------------------------------------------------------
-template <typename T>
-__global__ __launch_bounds__(WAVE) void k_potrf_tiny2(View<const T> A, View<T> L, int32_t *info, int info_off,
-                                                       int64_t batch, int nb)
+template <typename T, int R>
+__global__ __launch_bounds__(WAVE) void k_potrf_tiny_rows(View<const T> A, View<T> L, int32_t *info, int info_off,
+                                                           int64_t batch, int nb)
 {
-    constexpr int N = 32, G = 16, MPW = WAVE / G;
+    constexpr int G = 16, N = G * R, MPW = WAVE / G;
     using S = Stage<T, N, MPW>;
-    __shared__ __align__(16) T sm[S::ELEMS];
+    extern __shared__ __align__(16) unsigned char tiny_lds[];
+    T *sm = reinterpret_cast<T *>(tiny_lds);
     const int lane = threadIdx.x;
     const int q = lane / G, i = lane % G;
     const int64_t b0 = (int64_t)blockIdx.x * MPW;
@@ -286,63 +288,51 @@ __global__ __launch_bounds__(WAVE) void k_potrf_tiny2(View<const T> A, View<T> L
     const Mem<T> Lm = mem_of(L);
     stage_load<T, N, MPW>(sm, Am, b0, batch, nb);
     __syncthreads();
-    T a0[N], a1[N];  // rows i and i + 16
-    read_lrow<T, N>(sm + q * S::MS, i, Am.tr, a0);
-    read_lrow<T, N>(sm + q * S::MS, i + G, Am.tr, a1);
+    T a[R][N];  // a[h] = row i + 16 h
+    static_for<0, R>([&](auto H) {
+        constexpr int h = decltype(H)::value;
+        read_lrow<T, N>(sm + q * S::MS, i + G * h, Am.tr, a[h]);
 #pragma unroll
-    for (int k = 0; k < N; ++k) {
-        if (k > i)
-            a0[k] = T(0);  // the other triangle of A is never used
-        if (k > i + G)
-            a1[k] = T(0);
-    }
+        for (int k = 0; k < N; ++k)
+            if (k > i + G * h)
+                a[h][k] = T(0);  // the other triangle of A is never used
+    });
 
     int fail = 0;
     static_for<0, N>([&](auto J) {
         constexpr int j = decltype(J)::value;
         constexpr int jl = j % G, jh = j / G;
-        T piv = group_bcast<G>(jh ? a1[j] : a0[j], jl);  // a_jj after the updates of columns < j
+        T piv = group_bcast<G>(a[jh][j], jl);  // a_jj after the updates of columns < j
         if (!(piv > T(0)) && fail == 0)
             fail = j + 1;
         T r = rsqrt_acc(piv);
-        if constexpr (jh == 0)
-            a0[j] = (i >= j) ? a0[j] * r : T(0);  // column j of L (row j gets sqrt(piv))
-        a1[j] = (i + G >= j) ? a1[j] * r : T(0);
-        if constexpr (jh == 0)
-            dpp_settle1<G>(a0[j]);
-        dpp_settle1<G>(a1[j]);
+        static_for<jh, R>([&](auto H) {  // rows above slot jh have nothing in column j
+            constexpr int h = decltype(H)::value;
+            a[h][j] = (i + G * h >= j) ? a[h][j] * r : T(0);  // column j of L (row j gets sqrt(piv))
+            dpp_settle1<G>(a[h][j]);
+        });
         static_for<j + 1, N>([&](auto K) {
             constexpr int k = decltype(K)::value;
             constexpr int kl = k % G, kh = k / G;
-            // a_rk -= l_rj l_kj, with l_kj in row slot kh of lane kl
-            if constexpr (jh == 0) {  // rows below 16 have nothing left of columns >= 16
-                if constexpr (kh == 0)
-                    fma_bcast<G, kl>(a0[k], a0[j], a0[j], true);
-                else
-                    fma_bcast<G, kl>(a0[k], a1[j], a0[j], true);
-            }
-            if constexpr (kh == 0)
-                fma_bcast<G, kl>(a1[k], a0[j], a1[j], true);
-            else
-                fma_bcast<G, kl>(a1[k], a1[j], a1[j], true);
+            static_for<jh, R>([&](auto H) {  // a_rk -= l_rj l_kj, with l_kj in row slot kh of lane kl
+                constexpr int h = decltype(H)::value;
+                fma_bcast<G, kl>(a[h][k], a[kh][j], a[h][j], true);
+            });
         });
     });
-#pragma unroll
-    for (int k = 0; k < N; ++k) {
-        if (k > i)
-            a0[k] = T(0);
-        if (k > i + G)
-            a1[k] = T(0);
-    }
 
     __syncthreads();
-    if (Lm.tr) {
-        write_col<T, N>(sm + q * S::MS, i, a0);
-        write_col<T, N>(sm + q * S::MS, i + G, a1);
-    } else {
-        write_row<T, N>(sm + q * S::MS, i, a0);
-        write_row<T, N>(sm + q * S::MS, i + G, a1);
-    }
+    static_for<0, R>([&](auto H) {
+        constexpr int h = decltype(H)::value;
+#pragma unroll
+        for (int k = 0; k < N; ++k)
+            if (k > i + G * h)
+                a[h][k] = T(0);
+        if (Lm.tr)
+            write_col<T, N>(sm + q * S::MS, i + G * h, a[h]);
+        else
+            write_row<T, N>(sm + q * S::MS, i + G * h, a[h]);
+    });
     __syncthreads();
     stage_store<T, N, MPW>(sm, Lm, b0, batch, nb);
     if (info != nullptr && i == 0 && b0 + q < batch && fail != 0 && fail <= nb) {
@@ -616,9 +606,18 @@ la_status launch_potrf_tiny(View<const T> A, View<T> L, int32_t *info, int info_
         constexpr int MPW = Stage<T, 16>::MPW;
         hipLaunchKernelGGL((k_potrf_tiny<T, 16>), dim3((unsigned)((batch + MPW - 1) / MPW)), dim3(WAVE), 0, st, A, L,
                            info, info_off, batch, nb);
-    } else if (nb <= 32) {
-        hipLaunchKernelGGL((k_potrf_tiny2<T>), dim3((unsigned)((batch + 3) / 4)), dim3(WAVE), 0, st, A, L, info,
-                           info_off, batch, nb);
+    } else if (nb <= 32 || (sizeof(T) == 4 && nb <= 48)) {
+        // 16 lanes per matrix, 2 or 3 rows per lane.  (4 rows per lane for n <= 64 need all 256
+        // registers and one wavefront per SIMD: no faster than 64 lanes per matrix at n = 64,
+        // slower below.)
+        constexpr int MPW = 4;
+        const dim3 grid((unsigned)((batch + MPW - 1) / MPW));
+        constexpr size_t lds2 = sizeof(T) * Stage<T, 32, MPW>::ELEMS, lds3 = sizeof(T) * Stage<T, 48, MPW>::ELEMS;
+        if (nb <= 32) {
+            hipLaunchKernelGGL((k_potrf_tiny_rows<T, 2>), grid, dim3(WAVE), lds2, st, A, L, info, info_off, batch, nb);
+        } else if constexpr (sizeof(T) == 4) {
+            hipLaunchKernelGGL((k_potrf_tiny_rows<T, 3>), grid, dim3(WAVE), lds3, st, A, L, info, info_off, batch, nb);
+        }
     } else {
         hipLaunchKernelGGL((k_potrf_tiny<T, 64>), dim3((unsigned)batch), dim3(WAVE), 0, st, A, L, info, info_off,
                            batch, nb);
