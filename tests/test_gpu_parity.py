@@ -126,7 +126,8 @@ def test_potrf_in_place_and_other_triangle_ignored(la, orc, dtype, n, lower):
 
 
 @pytest.mark.parametrize("dtype", ["f64", "f32"])
-@pytest.mark.parametrize("n,bad", [(6, 3), (16, 15), (32, 0), (64, 40), (100, 0), (100, 70), (128, 127), (200, 130)])
+@pytest.mark.parametrize("n,bad", [(6, 3), (16, 15), (32, 0), (32, 20), (24, 23), (48, 17), (48, 40), (40, 39),
+                                   (64, 40), (100, 0), (100, 70), (128, 127), (200, 130)])
 def test_potrf_info_first_bad_pivot(la, orc, dtype, n, bad):
     import torch
 
@@ -142,7 +143,8 @@ def test_potrf_info_first_bad_pivot(la, orc, dtype, n, bad):
 
 def test_potrf_ragged_batch_and_large_batch(la, orc):
     # batches that do not fill the last wavefront, and more items than one grid dimension holds
-    for n, batch, dtype in [(16, 5, "f32"), (16, 70001, "f32"), (9, 3, "f64"), (32, 3, "f64"), (20, 4097, "f32")]:
+    for n, batch, dtype in [(16, 5, "f32"), (16, 70001, "f32"), (9, 3, "f64"), (32, 3, "f64"), (20, 4097, "f32"),
+                            (24, 4098, "f64"), (40, 4099, "f32"), (33, 1, "f32"), (48, 9, "f32"), (47, 2, "f64")]:
         A = spd(n + batch, batch, n, dtype)
         assert relerr(host(la.potrf(dev(A))), orc.potrf(A)) <= TOL[dtype]
 
