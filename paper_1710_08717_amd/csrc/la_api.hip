@@ -477,7 +477,15 @@ static la_status tri_apply_v(bool solve, bool fwd, T alpha, int64_t batch, int n
     View<T> S = X.rs <= X.cs ? View<T>{base + (solve ? 2 * batch * nn : 0), nm, 1, n}
                              : View<T>{base + (solve ? 2 * batch * nn : 0), nm, m, 1};
 
-    if (!solve || n <= 1024) {
+    // Edge of the diagonal blocks that get an explicit inverse; block substitution above it.  A merge
+    // level of the inverse costs n b^2 multiply-adds per matrix whatever the number of vectors, a
+    // substitution step three short launches: with few vectors the merges stop paying early.
+    // Measured (fp64, us; edge 256 / 512 / 1024): 32 x 512, 64 vectors 93 / 118 / 118; 8 x 1024, 64:
+    // 112 / 118 / 166; 4 x 2048, 128: 223 / 196 / 234; 1 x 4096, 512: 548 / 431 / 396.
+    int NBI = 256;
+    while (NBI < 1024 && NBI < 4 * m)
+        NBI *= 2;
+    if (!solve || n <= NBI) {
         View<const T> M = Lam;
         if (solve) {
             LA_TRY(inverse_build<T>(Lam, Inv, Tmp, batch, n, n, st));
@@ -491,7 +499,6 @@ static la_status tri_apply_v(bool solve, bool fwd, T alpha, int64_t batch, int n
         return launch_gemm<T>(fwd ? M : M.t(), src, X, batch, n, m, n, alpha, T(0), o, st);
     }
 
-    constexpr int NBI = 1024;
     LA_TRY(inverse_build<T>(Lam, Inv, Tmp, batch, n, NBI, st));
     if (!inplace || alpha != T(1))
         LA_TRY(launch_copy<T>(Xin, X, batch, n, m, alpha, 0, st));

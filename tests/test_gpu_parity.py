@@ -303,9 +303,10 @@ def test_trmm_parity(la, orc, dtype, lower, trans, rightside, n, m):
 @pytest.mark.parametrize("dtype", ["f64", "f32"])
 @pytest.mark.parametrize("lower,trans,rightside", [(True, False, False), (True, True, False), (False, False, True),
                                                    (True, True, True)])
-def test_trsm_block_substitution_path(la, orc, dtype, lower, trans, rightside):
-    """n > 1024 takes the block-inverse path (blocks of 1024); 1300 leaves a ragged last block."""
-    n, m, batch = 1300, 70, 1
+@pytest.mark.parametrize("n,m,batch", [(1300, 70, 1), (700, 5, 2), (300, 60, 3), (1100, 300, 1), (2100, 130, 1)])
+def test_trsm_block_substitution_path(la, orc, dtype, lower, trans, rightside, n, m, batch):
+    """Above the edge of the explicitly inverted diagonal blocks (256, 512 or 1024 rows, growing with
+    the number of vectors) the solve is a block substitution; every size here leaves a ragged last block."""
     T = tri(n, batch, n, lower, dtype)
     rng = np.random.default_rng(n + m)
     A = rng.standard_normal((batch, m, n) if rightside else (batch, n, m)).astype(npdt(dtype))
