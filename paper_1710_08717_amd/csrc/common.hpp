@@ -61,8 +61,9 @@ inline la_status launch_check(const char *where)
 }
 
 // ---------------------------------------------------------------------------------
-// Broadcast of one lane's value to the G lanes of its group (G = 16, 32 or 64).
-// G = 16: DPP row_newbcast, folded by the compiler into the consuming VALU op.
+// Broadcast of one lane's value to the G lanes of its group (G = 4, 8, 16, 32 or 64).
+// G = 16: DPP row_newbcast, folded by the compiler into the consuming VALU op.  G = 8: two such
+// moves, one per half of the 16-lane row (bank mask).  G = 4: DPP quad_perm.
 // G = 32: ds_bpermute through the LDS crossbar.  G = 64: v_readlane into an SGPR.
 // ---------------------------------------------------------------------------------
 template <int K>
@@ -93,11 +94,48 @@ __device__ __forceinline__ int row_bcast_i(int x, int k)
     }
 }
 
+// lane K of its own HALF of the 16-lane row to all 8 lanes of that half: the row broadcast of
+// lane K written to banks 0-1 (lanes 0..7), that of lane 8 + K to banks 2-3 (lanes 8..15)
+template <int K>
+__device__ __forceinline__ int dpp_half_bcast_i(int x)
+{
+    const int lo = __builtin_amdgcn_update_dpp(x, x, 0x150 + K, 0xf, 0x3, false);
+    return __builtin_amdgcn_update_dpp(lo, x, 0x158 + K, 0xf, 0xc, false);
+}
+__device__ __forceinline__ int half_bcast_i(int x, int k)
+{
+    switch (k) {
+    case 0: return dpp_half_bcast_i<0>(x);
+    case 1: return dpp_half_bcast_i<1>(x);
+    case 2: return dpp_half_bcast_i<2>(x);
+    case 3: return dpp_half_bcast_i<3>(x);
+    case 4: return dpp_half_bcast_i<4>(x);
+    case 5: return dpp_half_bcast_i<5>(x);
+    case 6: return dpp_half_bcast_i<6>(x);
+    default: return dpp_half_bcast_i<7>(x);
+    }
+}
+
+// lane k of each group of four lanes to the four of them (DPP quad_perm)
+__device__ __forceinline__ int quad_bcast_i(int x, int k)
+{
+    switch (k & 3) {
+    case 0: return __builtin_amdgcn_update_dpp(0, x, 0x00, 0xf, 0xf, false);
+    case 1: return __builtin_amdgcn_update_dpp(0, x, 0x55, 0xf, 0xf, false);
+    case 2: return __builtin_amdgcn_update_dpp(0, x, 0xaa, 0xf, 0xf, false);
+    default: return __builtin_amdgcn_update_dpp(0, x, 0xff, 0xf, 0xf, false);
+    }
+}
+
 template <int G>
 __device__ __forceinline__ int group_bcast_i(int x, int k)
 {
     if constexpr (G == 16) {
         return row_bcast_i(x, k);
+    } else if constexpr (G == 8) {
+        return half_bcast_i(x, k);
+    } else if constexpr (G == 4) {
+        return quad_bcast_i(x, k);
     } else if constexpr (G == 32) {
         int lane = __lane_id();
         return __builtin_amdgcn_ds_bpermute(((lane & 32) | k) << 2, x);
@@ -160,6 +198,39 @@ __device__ __forceinline__ void fnmac_dpp16(double &acc, double src, double othe
                  : "v"(src), "v"(other), "n"(K));
 }
 
+// 8 lanes per group, two groups per 16-lane row: the same instruction twice, each writing one
+// half of the row (bank mask) with the broadcast of that half's lane K.
+template <int K>
+__device__ __forceinline__ void fmac_dpp8(float &acc, float src, float other)
+{
+    asm volatile("v_fmac_f32_dpp %0, %1, %2 row_newbcast:%3 row_mask:0xf bank_mask:0x3\n\t"
+                 "v_fmac_f32_dpp %0, %1, %2 row_newbcast:%4 row_mask:0xf bank_mask:0xc"
+                 : "+v"(acc)
+                 : "v"(src), "v"(other), "n"(K), "n"(K + 8));
+}
+template <int K>
+__device__ __forceinline__ void fnmac_dpp8(float &acc, float src, float other)
+{
+    asm volatile("v_fmac_f32_dpp %0, -%1, %2 row_newbcast:%3 row_mask:0xf bank_mask:0x3\n\t"
+                 "v_fmac_f32_dpp %0, -%1, %2 row_newbcast:%4 row_mask:0xf bank_mask:0xc"
+                 : "+v"(acc)
+                 : "v"(src), "v"(other), "n"(K), "n"(K + 8));
+}
+// 4 lanes per group: the broadcast is a quad permutation (fp32 only; 64-bit DPP has no such control)
+template <int K>
+__device__ __forceinline__ void fmac_dpp4(float &acc, float src, float other)
+{
+    asm volatile("v_fmac_f32_dpp %0, %1, %2 quad_perm:[%3,%3,%3,%3] row_mask:0xf bank_mask:0xf"
+                 : "+v"(acc)
+                 : "v"(src), "v"(other), "n"(K));
+}
+template <int K>
+__device__ __forceinline__ void fnmac_dpp4(float &acc, float src, float other)
+{
+    asm volatile("v_fmac_f32_dpp %0, -%1, %2 quad_perm:[%3,%3,%3,%3] row_mask:0xf bank_mask:0xf"
+                 : "+v"(acc)
+                 : "v"(src), "v"(other), "n"(K));
+}
 template <int G, int K, typename T>
 __device__ __forceinline__ void fma_bcast(T &acc, T src, T other, bool neg)
 {
@@ -168,9 +239,41 @@ __device__ __forceinline__ void fma_bcast(T &acc, T src, T other, bool neg)
             fnmac_dpp16<K>(acc, src, other);
         else
             fmac_dpp16<K>(acc, src, other);
-    } else {
+    } else if constexpr (G == 8 && sizeof(T) == 4) {
+        if (neg)
+            fnmac_dpp8<K>(acc, src, other);
+        else
+            fmac_dpp8<K>(acc, src, other);
+    } else if constexpr (G == 4 && sizeof(T) == 4) {
+        if (neg)
+            fnmac_dpp4<K>(acc, src, other);
+        else
+            fmac_dpp4<K>(acc, src, other);
+    } else {  // (fp64 with 8-lane groups too: the 64-bit DPP form gave wrong values with a partial bank mask)
         const T b = group_bcast<G>(src, K);
         acc = fma(neg ? -other : other, b, acc);
+    }
+}
+
+// acc <- acc -/+ other * (acc's own value in lane K of the group).  With 8-lane groups the first
+// instruction of the pair writes the register the second one reads through DPP (other lanes of
+// it, but the wait states go by register), hence the s_nop between them.
+template <int G, int K, typename T>
+__device__ __forceinline__ void fma_bcast_self(T &acc, T other, bool neg)
+{
+    if constexpr (G == 8 && sizeof(T) == 4) {
+        if (neg)
+            asm volatile("v_fmac_f32_dpp %0, -%0, %1 row_newbcast:%2 row_mask:0xf bank_mask:0x3\n\ts_nop 1\n\t"
+                         "v_fmac_f32_dpp %0, -%0, %1 row_newbcast:%3 row_mask:0xf bank_mask:0xc"
+                         : "+v"(acc)
+                         : "v"(other), "n"(K), "n"(K + 8));
+        else
+            asm volatile("v_fmac_f32_dpp %0, %0, %1 row_newbcast:%2 row_mask:0xf bank_mask:0x3\n\ts_nop 1\n\t"
+                         "v_fmac_f32_dpp %0, %0, %1 row_newbcast:%3 row_mask:0xf bank_mask:0xc"
+                         : "+v"(acc)
+                         : "v"(other), "n"(K), "n"(K + 8));
+    } else {
+        fma_bcast<G, K, T>(acc, acc, other, neg);
     }
 }
 
@@ -191,7 +294,7 @@ __device__ __forceinline__ void static_for(F &&f)
 template <int G, typename T, int N>
 __device__ __forceinline__ void dpp_settle(T (&v)[N])
 {
-    if constexpr (G == 16) {
+    if constexpr (G == 16 || (G <= 8 && sizeof(T) == 4)) {
 #pragma unroll
         for (int i = 0; i < N; ++i)
             asm volatile("" : "+v"(v[i]));
@@ -201,7 +304,7 @@ __device__ __forceinline__ void dpp_settle(T (&v)[N])
 template <int G, typename T>
 __device__ __forceinline__ void dpp_settle1(T &v)
 {
-    if constexpr (G == 16) {
+    if constexpr (G == 16 || (G <= 8 && sizeof(T) == 4)) {
         asm volatile("s_nop 1" : "+v"(v));
     }
 }

@@ -413,7 +413,7 @@ __global__ __launch_bounds__(WAVE) void k_backward_tiny(View<const T> Lv, View<c
         constexpr int k = G - 1 - decltype(Tt)::value;
         static_for<0, G>([&](auto C) {
             constexpr int c = decltype(C)::value;
-            fma_bcast<G, k>(y[c], y[c], lc[k], true);  // G instructions lie between two touches of y[c]
+            fma_bcast_self<G, k>(y[c], lc[k], true);  // G instructions lie between two touches of y[c]
         });
     });
     // V = Y D^-1 (column c scaled by 1 / l_cc), then W = V Lt^-1 from the last column back
@@ -602,7 +602,15 @@ la_status launch_potrf_tiny(View<const T> A, View<T> L, int32_t *info, int info_
         return LA_OK;
     if (nb > 64)
         return LA_ERR_UNSUPPORTED;
-    if (nb <= 16) {
+    if (nb <= 4) {
+        constexpr int MPW = Stage<T, 4>::MPW;
+        hipLaunchKernelGGL((k_potrf_tiny<T, 4>), dim3((unsigned)((batch + MPW - 1) / MPW)), dim3(WAVE), 0, st, A, L,
+                           info, info_off, batch, nb);
+    } else if (nb <= 8) {  // 8 lanes per matrix: half the pivots and twice the matrices per wavefront of the 16-lane form
+        constexpr int MPW = Stage<T, 8>::MPW;
+        hipLaunchKernelGGL((k_potrf_tiny<T, 8>), dim3((unsigned)((batch + MPW - 1) / MPW)), dim3(WAVE), 0, st, A, L,
+                           info, info_off, batch, nb);
+    } else if (nb <= 16) {
         constexpr int MPW = Stage<T, 16>::MPW;
         hipLaunchKernelGGL((k_potrf_tiny<T, 16>), dim3((unsigned)((batch + MPW - 1) / MPW)), dim3(WAVE), 0, st, A, L,
                            info, info_off, batch, nb);
@@ -632,7 +640,15 @@ la_status launch_backward_tiny(View<const T> L, View<const T> G, View<T> Abar, i
         return LA_OK;
     if (n > 32)
         return LA_ERR_UNSUPPORTED;
-    if (n <= 16) {
+    if (n <= 4) {
+        constexpr int MPW = Stage<T, 4>::MPW;
+        hipLaunchKernelGGL((k_backward_tiny<T, 4>), dim3((unsigned)((batch + MPW - 1) / MPW)), dim3(WAVE), 0, st, L,
+                           G, Abar, batch, n);
+    } else if (n <= 8) {
+        constexpr int MPW = Stage<T, 8>::MPW;
+        hipLaunchKernelGGL((k_backward_tiny<T, 8>), dim3((unsigned)((batch + MPW - 1) / MPW)), dim3(WAVE), 0, st, L,
+                           G, Abar, batch, n);
+    } else if (n <= 16) {
         constexpr int MPW = Stage<T, 16>::MPW;
         hipLaunchKernelGGL((k_backward_tiny<T, 16>), dim3((unsigned)((batch + MPW - 1) / MPW)), dim3(WAVE), 0, st, L,
                            G, Abar, batch, n);

@@ -85,7 +85,7 @@ def tri(seed, batch, n, lower, dtype):
     return T.astype(npdt(dtype))
 
 
-SIZES = [1, 2, 5, 15, 16, 17, 31, 32, 33, 48, 64, 65, 80, 97, 100, 112, 113, 127, 128, 129, 192, 200, 256, 321, 384]
+SIZES = [1, 2, 3, 4, 5, 7, 8, 9, 15, 16, 17, 31, 32, 33, 48, 64, 65, 80, 97, 100, 112, 113, 127, 128, 129, 192, 200, 256, 321, 384]
 
 
 # ----------------------------------------------------------------------------
@@ -126,7 +126,7 @@ def test_potrf_in_place_and_other_triangle_ignored(la, orc, dtype, n, lower):
 
 
 @pytest.mark.parametrize("dtype", ["f64", "f32"])
-@pytest.mark.parametrize("n,bad", [(6, 3), (16, 15), (32, 0), (32, 20), (24, 23), (48, 17), (48, 40), (40, 39),
+@pytest.mark.parametrize("n,bad", [(1, 0), (3, 1), (4, 3), (6, 3), (8, 0), (8, 7), (16, 15), (32, 0), (32, 20), (24, 23), (48, 17), (48, 40), (40, 39),
                                    (64, 40), (100, 0), (100, 70), (128, 127), (200, 130)])
 def test_potrf_info_first_bad_pivot(la, orc, dtype, n, bad):
     import torch
@@ -144,7 +144,9 @@ def test_potrf_info_first_bad_pivot(la, orc, dtype, n, bad):
 def test_potrf_ragged_batch_and_large_batch(la, orc):
     # batches that do not fill the last wavefront, and more items than one grid dimension holds
     for n, batch, dtype in [(16, 5, "f32"), (16, 70001, "f32"), (9, 3, "f64"), (32, 3, "f64"), (20, 4097, "f32"),
-                            (24, 4098, "f64"), (40, 4099, "f32"), (33, 1, "f32"), (48, 9, "f32"), (47, 2, "f64")]:
+                            (24, 4098, "f64"), (40, 4099, "f32"), (33, 1, "f32"), (48, 9, "f32"), (47, 2, "f64"),
+                            (8, 70003, "f32"), (8, 13, "f64"), (7, 9, "f32"), (4, 70001, "f32"), (4, 33, "f64"), (3, 5, "f32"),
+                            (2, 17, "f64"), (1, 70, "f32")]:
         A = spd(n + batch, batch, n, dtype)
         assert relerr(host(la.potrf(dev(A))), orc.potrf(A)) <= TOL[dtype]
 
@@ -203,10 +205,11 @@ def test_backward_parity(la, orc, dtype, n, lower):
 
 
 @pytest.mark.parametrize("dtype", ["f64", "f32"])
-@pytest.mark.parametrize("n", [17, 24, 32])
+@pytest.mark.parametrize("n", [3, 4, 6, 8, 17, 24, 32])
 @pytest.mark.parametrize("lower", [True, False])
 def test_backward_parity_large_batch_register_kernel(la, orc, dtype, n, lower):
-    """Above 2048 matrices sizes 17..32 take the register kernel instead of the one-workgroup one."""
+    """Above 2048 matrices sizes 17..32 take the register kernel instead of the one-workgroup one; sizes
+    up to 4 and up to 8 sit in 4 and 8 lanes per matrix (16 and 8 matrices per wavefront, last one ragged)."""
     batch = 2100
     A = spd(n * 7 + lower, batch, n, dtype)
     Lf = orc.potrf(A, lower=lower).astype(npdt(dtype))
