@@ -663,6 +663,206 @@ la_status launch_backward_tiny(View<const T> L, View<const T> G, View<T> Abar, i
     return launch_check("backward_tiny");
 }
 
+// ---------------------------------------------------------------------------------
+// trsm / trmm for n <= 16 and at most 16 vectors (section 4.2 "trsm", "trmm"), G lanes per matrix:
+// lane i holds row i of M (M = Lam or Lam^T, whichever the operator applies) and row i of the
+// n x m operand, registers = its m columns.  The operand travels as its flat memory image (n x m
+// or, for right-side operators, m x n per item, items back to back): 16-byte loads into LDS,
+// rows or columns picked out of LDS by the lanes, the result back the same way.
+//   solve: with D = diag(M), M x = b  <=>  (D^-1 M) x = D^-1 b, unit diagonal; for k in solve order
+//          b_i -= (m_ik / m_ii) b_k (i != k): ONE broadcast multiply-add per column and step, row k is
+//          final when it is broadcast.  multiply: x_i = sum_k m_ik b_k.
+// LDS index of image element e is e + e / 16, so that 16 lanes reading a column of a 16-wide image
+// (stride 16) fall into different banks.
+// ---------------------------------------------------------------------------------
+constexpr int TRI_MC = 16;  // vectors per matrix, at most
+
+__device__ __forceinline__ int img_idx(int e) { return e + (e >> 4); }
+
+template <typename T, int G, bool SOLVE>
+__global__ __launch_bounds__(WAVE) void k_tri_tiny(View<const T> Lam, const T *Bin, T *Bout, int64_t batch, int n, int m,
+                                                    int fwd, int img_tr, T alpha)
+{
+    using S = Stage<T, G>;
+    using V4 = typename VecOf<T>::type;
+    constexpr int VN = VecOf<T>::N;
+    constexpr int MPW = S::MPW;
+    constexpr int IMG = MPW * G * TRI_MC;  // image elements of one wavefront, at most
+    __shared__ __align__(16) T sm[S::ELEMS];
+    __shared__ __align__(16) T img[IMG + IMG / 16 + 4];
+    const int lane = threadIdx.x;
+    const int q = lane / G, i = lane % G;
+    const int64_t b0 = (int64_t)blockIdx.x * MPW;
+    const int cnt = (int)((batch - b0) < MPW ? (batch - b0) : MPW);  // items of this wavefront
+    const int nm = n * m, tot = cnt * nm;
+
+    // ---- the operand's image: vector loads when the wavefront has all its items ----
+    const T *src = Bin + b0 * nm;
+    const bool vec = (cnt == MPW) && ((reinterpret_cast<uintptr_t>(Bin) & 15) == 0);
+    if (vec) {
+        constexpr int ITV = (IMG / VN + WAVE - 1) / WAVE;
+        const int nvec = tot / VN;  // MPW n m is a multiple of VN
+        V4 v[ITV];
+#pragma unroll
+        for (int t = 0; t < ITV; ++t)
+            if (t * WAVE + lane < nvec)
+                v[t] = __builtin_nontemporal_load(reinterpret_cast<const V4 *>(src) + t * WAVE + lane);
+#pragma unroll
+        for (int t = 0; t < ITV; ++t)
+            if (t * WAVE + lane < nvec) {
+                const int e = (t * WAVE + lane) * VN;
+                img[img_idx(e)] = v[t].x;
+                img[img_idx(e + 1)] = v[t].y;
+                if constexpr (VN == 4) {
+                    img[img_idx(e + 2)] = v[t].z;
+                    img[img_idx(e + 3)] = v[t].w;
+                }
+            }
+    } else {
+        for (int e = lane; e < tot; e += WAVE)
+            img[img_idx(e)] = src[e];
+    }
+    const Mem<const T> Lm = mem_of(Lam);
+    stage_load<T, G>(sm, Lm, b0, batch, n);
+    __syncthreads();
+
+    // ---- row i of M and of the operand ----
+    T mr[G];
+    if (fwd)
+        read_lrow<T, G>(sm + q * S::MS, i, Lm.tr, mr);  // M = Lam: entries k <= i
+    else
+        read_lcol<T, G>(sm + q * S::MS, i, Lm.tr, mr);  // M = Lam^T: entries k >= i
+    T dii = T(1);
+#pragma unroll
+    for (int k = 0; k < G; ++k) {
+        if (k == i)
+            dii = mr[k];
+        if (fwd ? (k > i) : (k < i))
+            mr[k] = T(0);  // the other triangle is never used
+    }
+    T b[TRI_MC];
+    const bool live = (i < n) && (q < cnt);
+    const int ebase = q * nm + (img_tr ? i : i * m), estep = img_tr ? n : 1;
+#pragma unroll
+    for (int c = 0; c < TRI_MC; ++c)
+        b[c] = (live && c < m) ? img[img_idx(ebase + c * estep)] : T(0);
+
+    if constexpr (SOLVE) {
+        const T rinv = rcp_acc(dii);
+#pragma unroll
+        for (int k = 0; k < G; ++k)
+            mr[k] = (k == i) ? T(0) : mr[k] * rinv;
+        const T sc = rinv * alpha;
+#pragma unroll
+        for (int c = 0; c < TRI_MC; ++c)
+            b[c] *= sc;
+        dpp_settle<G>(b);
+        static_for<0, TRI_MC / 4>([&](auto CB) {
+            constexpr int c0 = 4 * decltype(CB)::value;
+            if (c0 < m) {
+                static_for<0, G>([&](auto Kk) {
+                    constexpr int kk = decltype(Kk)::value;
+                    // forward: k = 0, 1, ...; backward: k = G-1, G-2, ... (rows >= n are identity padding)
+                    if (fwd) {
+                        static_for<0, 4>([&](auto J) { fma_bcast_self<G, kk>(b[c0 + decltype(J)::value], mr[kk], true); });
+                    } else {
+                        static_for<0, 4>([&](auto J) {
+                            fma_bcast_self<G, G - 1 - kk>(b[c0 + decltype(J)::value], mr[G - 1 - kk], true);
+                        });
+                    }
+                });
+            }
+        });
+    } else {
+        T x[TRI_MC];
+#pragma unroll
+        for (int c = 0; c < TRI_MC; ++c)
+            x[c] = T(0);
+        dpp_settle<G>(b);
+        static_for<0, TRI_MC / 4>([&](auto CB) {
+            constexpr int c0 = 4 * decltype(CB)::value;
+            if (c0 < m) {
+                static_for<0, G>([&](auto Kk) {
+                    constexpr int kk = decltype(Kk)::value;
+                    static_for<0, 4>([&](auto J) {
+                        constexpr int c = c0 + decltype(J)::value;
+                        fma_bcast<G, kk>(x[c], b[c], mr[kk], false);
+                    });
+                });
+            }
+        });
+#pragma unroll
+        for (int c = 0; c < TRI_MC; ++c)
+            b[c] = alpha * x[c];
+    }
+
+    // ---- result into the image, image back to memory ----
+    __syncthreads();
+#pragma unroll
+    for (int c = 0; c < TRI_MC; ++c)
+        if (live && c < m)
+            img[img_idx(ebase + c * estep)] = b[c];
+    __syncthreads();
+    T *dst = Bout + b0 * nm;
+    if (vec && (reinterpret_cast<uintptr_t>(Bout) & 15) == 0) {
+        constexpr int ITV = (IMG / VN + WAVE - 1) / WAVE;
+        const int nvec = tot / VN;
+#pragma unroll
+        for (int t = 0; t < ITV; ++t)
+            if (t * WAVE + lane < nvec) {
+                const int e = (t * WAVE + lane) * VN;
+                V4 v;
+                v.x = img[img_idx(e)];
+                v.y = img[img_idx(e + 1)];
+                if constexpr (VN == 4) {
+                    v.z = img[img_idx(e + 2)];
+                    v.w = img[img_idx(e + 3)];
+                }
+                __builtin_nontemporal_store(v, reinterpret_cast<V4 *>(dst) + t * WAVE + lane);
+            }
+    } else {
+        for (int e = lane; e < tot; e += WAVE)
+            dst[e] = img[img_idx(e)];
+    }
+}
+
+template <typename T, int G>
+static la_status launch_tri_tiny_g(bool solve, View<const T> Lam, const T *Bin, T *Bout, int64_t batch, int n, int m,
+                                   bool fwd, bool img_tr, T alpha, hipStream_t st)
+{
+    constexpr int MPW = Stage<T, G>::MPW;
+    const dim3 grid((unsigned)((batch + MPW - 1) / MPW));
+    if (solve)
+        hipLaunchKernelGGL((k_tri_tiny<T, G, true>), grid, dim3(WAVE), 0, st, Lam, Bin, Bout, batch, n, m, fwd ? 1 : 0,
+                           img_tr ? 1 : 0, alpha);
+    else
+        hipLaunchKernelGGL((k_tri_tiny<T, G, false>), grid, dim3(WAVE), 0, st, Lam, Bin, Bout, batch, n, m, fwd ? 1 : 0,
+                           img_tr ? 1 : 0, alpha);
+    return launch_check("tri_tiny");
+}
+
+// Bin / Bout: items of n * m elements back to back; img_tr says an item is stored m x n (the
+// right-side operators) instead of n x m.
+template <typename T>
+la_status launch_tri_tiny(bool solve, bool fwd, T alpha, int64_t batch, int n, int m, View<const T> Lam, const T *Bin,
+                          T *Bout, bool img_tr, hipStream_t st)
+{
+    if (batch <= 0 || n <= 0 || m <= 0)
+        return LA_OK;
+    if (n > 16 || m > TRI_MC || (batch + 3) / 4 > 0x7fffffffll)
+        return LA_ERR_UNSUPPORTED;
+    if (n <= 4)
+        return launch_tri_tiny_g<T, 4>(solve, Lam, Bin, Bout, batch, n, m, fwd, img_tr, alpha, st);
+    if (n <= 8)
+        return launch_tri_tiny_g<T, 8>(solve, Lam, Bin, Bout, batch, n, m, fwd, img_tr, alpha, st);
+    return launch_tri_tiny_g<T, 16>(solve, Lam, Bin, Bout, batch, n, m, fwd, img_tr, alpha, st);
+}
+
+template la_status launch_tri_tiny<float>(bool, bool, float, int64_t, int, int, View<const float>, const float *, float *,
+                                          bool, hipStream_t);
+template la_status launch_tri_tiny<double>(bool, bool, double, int64_t, int, int, View<const double>, const double *,
+                                           double *, bool, hipStream_t);
+
 template la_status launch_potrf_tiny<float>(View<const float>, View<float>, int32_t *, int, int64_t, int, hipStream_t);
 template la_status launch_potrf_tiny<double>(View<const double>, View<double>, int32_t *, int, int64_t, int,
                                              hipStream_t);

@@ -285,6 +285,29 @@ def test_trsm_parity(la, orc, dtype, lower, trans, rightside, n, m):
 
 @pytest.mark.parametrize("dtype", ["f64", "f32"])
 @pytest.mark.parametrize("lower,trans,rightside", FLAGS)
+@pytest.mark.parametrize("op", ["trsm", "trmm"])
+@pytest.mark.parametrize("n,m,batch", [(16, 16, 4099), (16, 1, 70001), (13, 7, 1030), (8, 8, 4101), (7, 16, 259), (5, 3, 66),
+                                       (4, 4, 4111), (3, 16, 1037), (2, 5, 19), (1, 1, 5)])
+def test_small_triangular_operators_with_many_matrices(la, orc, dtype, lower, trans, rightside, op, n, m, batch):
+    """n <= 16 with at most 16 vectors: 16, 8 or 4 lanes per matrix, operands moved as flat images; batches that
+    leave the last wavefront ragged, more items than one grid dimension holds, in place and out of place."""
+    T = tri(n * 3 + m, batch, n, lower, dtype)
+    other = np.triu_indices(n, 1) if lower else np.tril_indices(n, -1)
+    Tj = T.copy()
+    Tj[:, other[0], other[1]] = np.nan  # never read
+    rng = np.random.default_rng(n * 100 + m)
+    A = rng.standard_normal((batch, m, n) if rightside else (batch, n, m)).astype(npdt(dtype))
+    f_o, f_g = (orc.trsm, la.trsm) if op == "trsm" else (orc.trmm, la.trmm)
+    ref = f_o(T, A, lower=lower, trans=trans, rightside=rightside, alpha=0.75)
+    out = host(f_g(dev(Tj), dev(A), lower=lower, trans=trans, rightside=rightside, alpha=0.75))
+    assert relerr(out, ref) <= TOL[dtype]
+    a = dev(A)
+    out2 = host(f_g(dev(Tj), a, lower=lower, trans=trans, rightside=rightside, alpha=0.75, out=a))
+    assert np.array_equal(out, out2)
+
+
+@pytest.mark.parametrize("dtype", ["f64", "f32"])
+@pytest.mark.parametrize("lower,trans,rightside", FLAGS)
 @pytest.mark.parametrize("n,m", [(1, 2), (6, 3), (64, 5), (70, 64), (150, 150), (260, 9)])
 def test_trmm_parity(la, orc, dtype, lower, trans, rightside, n, m):
     batch = 3
