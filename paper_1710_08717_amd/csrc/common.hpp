@@ -398,6 +398,9 @@ la_status launch_backward_leaf16(View<const T> Lam, View<const T> G, View<T> Aba
 template <typename T>
 la_status launch_tri_tiny(bool solve, bool fwd, T alpha, int64_t batch, int n, int m, View<const T> Lam, const T *Bin,
                           T *Bout, bool img_tr, hipStream_t st);
+// syrk for n <= 16 and inner dimension <= 32: A as flat items of n * k elements (stored k x n when img_tr)
+template <typename T>
+la_status launch_syrk_tiny(bool img_tr, T alpha, int64_t batch, int n, int k, const T *A, View<T> C, hipStream_t st);
 // Register-resident potrf backward for n <= 32: Abar = sym(L^-T Phi(L^T Lbar) L^-1).
 template <typename T>
 la_status launch_backward_tiny(View<const T> L, View<const T> G, View<T> Abar, int64_t batch, int n,

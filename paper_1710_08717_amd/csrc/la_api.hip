@@ -550,6 +550,8 @@ static la_status syrk_t(int trans, double alpha, int64_t batch, int n, int k, co
     const int64_t nk = (int64_t)n * k, nn = (int64_t)n * n;
     View<const T> Ank = trans ? View<const T>{(const T *)A, nk, 1, n} : View<const T>{(const T *)A, nk, k, 1};  // n x k
     View<T> C{(T *)B, nn, n, 1};
+    if (n <= 16 && k >= 1 && k <= 32)  // G lanes per matrix, HBM bound
+        return launch_syrk_tiny<T>(trans != 0, (T)alpha, batch, n, k, (const T *)A, C, st);
     GemmOpts o;
     o.maskC = 1;
     LA_TRY(launch_gemm<T>(Ank, Ank.t(), C, batch, n, n, k, (T)alpha, T(0), o, st));

@@ -863,6 +863,115 @@ template la_status launch_tri_tiny<float>(bool, bool, float, int64_t, int, int, 
 template la_status launch_tri_tiny<double>(bool, bool, double, int64_t, int, int, View<const double>, const double *,
                                            double *, bool, hipStream_t);
 
+// ---------------------------------------------------------------------------------
+// syrk for n <= 16 and inner dimension <= 32 (section 4.2 "syrk"), G lanes per matrix: lane i holds
+// row i of the n x k operand (column i of the k x n one when trans), b_ij = sum_c a_ic a_jc with
+// a_jc broadcast from lane j.  Lane i and lane j form the same products in the same order, so the
+// result is exactly symmetric.  Operand in as its flat image (as in k_tri_tiny), result out through
+// the padded stage.
+// ---------------------------------------------------------------------------------
+constexpr int SYRK_KC = 32;
+
+template <typename T, int G>
+__global__ __launch_bounds__(WAVE) void k_syrk_tiny(const T *Ain, View<T> C, int64_t batch, int n, int k, int img_tr, T alpha)
+{
+    using S = Stage<T, G>;
+    using V4 = typename VecOf<T>::type;
+    constexpr int VN = VecOf<T>::N;
+    constexpr int MPW = S::MPW;
+    constexpr int IMG = MPW * G * SYRK_KC;
+    __shared__ __align__(16) T sm[S::ELEMS];
+    __shared__ __align__(16) T img[IMG + IMG / 16 + 4];
+    const int lane = threadIdx.x;
+    const int q = lane / G, i = lane % G;
+    const int64_t b0 = (int64_t)blockIdx.x * MPW;
+    const int cnt = (int)((batch - b0) < MPW ? (batch - b0) : MPW);
+    const int nk = n * k, tot = cnt * nk;
+    const T *src = Ain + b0 * nk;
+    if ((cnt == MPW) && ((reinterpret_cast<uintptr_t>(Ain) & 15) == 0)) {
+        constexpr int ITV = (IMG / VN + WAVE - 1) / WAVE;
+        const int nvec = tot / VN;
+        V4 v[ITV];
+#pragma unroll
+        for (int t = 0; t < ITV; ++t)
+            if (t * WAVE + lane < nvec)
+                v[t] = __builtin_nontemporal_load(reinterpret_cast<const V4 *>(src) + t * WAVE + lane);
+#pragma unroll
+        for (int t = 0; t < ITV; ++t)
+            if (t * WAVE + lane < nvec) {
+                const int e = (t * WAVE + lane) * VN;
+                img[img_idx(e)] = v[t].x;
+                img[img_idx(e + 1)] = v[t].y;
+                if constexpr (VN == 4) {
+                    img[img_idx(e + 2)] = v[t].z;
+                    img[img_idx(e + 3)] = v[t].w;
+                }
+            }
+    } else {
+        for (int e = lane; e < tot; e += WAVE)
+            img[img_idx(e)] = src[e];
+    }
+    __syncthreads();
+
+    T a[SYRK_KC];
+    const bool live = (i < n) && (q < cnt);
+    const int ebase = q * nk + (img_tr ? i : i * k), estep = img_tr ? n : 1;
+#pragma unroll
+    for (int c = 0; c < SYRK_KC; ++c)
+        a[c] = (live && c < k) ? img[img_idx(ebase + c * estep)] : T(0);
+    T out[G];
+#pragma unroll
+    for (int j = 0; j < G; ++j)
+        out[j] = T(0);
+    dpp_settle<G>(a);
+    static_for<0, G>([&](auto Jj) {
+        constexpr int j = decltype(Jj)::value;
+        if (j < n) {
+            static_for<0, SYRK_KC / 4>([&](auto CB) {
+                constexpr int c0 = 4 * decltype(CB)::value;
+                if (c0 < k) {
+                    static_for<0, 4>([&](auto U) {
+                        constexpr int c = c0 + decltype(U)::value;
+                        fma_bcast<G, j>(out[j], a[c], a[c], false);
+                    });
+                }
+            });
+        }
+    });
+#pragma unroll
+    for (int j = 0; j < G; ++j)
+        out[j] *= alpha;
+    write_row<T, G>(sm + q * S::MS, i, out);
+    __syncthreads();
+    stage_store<T, G>(sm, mem_of(C), b0, batch, n);
+}
+
+template <typename T>
+la_status launch_syrk_tiny(bool img_tr, T alpha, int64_t batch, int n, int k, const T *A, View<T> C, hipStream_t st)
+{
+    if (batch <= 0 || n <= 0)
+        return LA_OK;
+    if (n > 16 || k > SYRK_KC || k < 1 || (batch + 3) / 4 > 0x7fffffffll)
+        return LA_ERR_UNSUPPORTED;
+    if (n <= 4) {
+        constexpr int MPW = Stage<T, 4>::MPW;
+        hipLaunchKernelGGL((k_syrk_tiny<T, 4>), dim3((unsigned)((batch + MPW - 1) / MPW)), dim3(WAVE), 0, st, A, C, batch,
+                           n, k, img_tr ? 1 : 0, alpha);
+    } else if (n <= 8) {
+        constexpr int MPW = Stage<T, 8>::MPW;
+        hipLaunchKernelGGL((k_syrk_tiny<T, 8>), dim3((unsigned)((batch + MPW - 1) / MPW)), dim3(WAVE), 0, st, A, C, batch,
+                           n, k, img_tr ? 1 : 0, alpha);
+    } else {
+        constexpr int MPW = Stage<T, 16>::MPW;
+        hipLaunchKernelGGL((k_syrk_tiny<T, 16>), dim3((unsigned)((batch + MPW - 1) / MPW)), dim3(WAVE), 0, st, A, C, batch,
+                           n, k, img_tr ? 1 : 0, alpha);
+    }
+    return launch_check("syrk_tiny");
+}
+
+template la_status launch_syrk_tiny<float>(bool, float, int64_t, int, int, const float *, View<float>, hipStream_t);
+template la_status launch_syrk_tiny<double>(bool, double, int64_t, int, int, const double *, View<double>, hipStream_t);
+
 template la_status launch_potrf_tiny<float>(View<const float>, View<float>, int32_t *, int, int64_t, int, hipStream_t);
 template la_status launch_potrf_tiny<double>(View<const double>, View<double>, int32_t *, int, int64_t, int,
                                              hipStream_t);

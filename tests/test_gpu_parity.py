@@ -400,6 +400,20 @@ def test_syrk_large_lower_triangle_tile_counts(la, orc, dtype, n, k):
 
 @pytest.mark.parametrize("dtype", ["f64", "f32"])
 @pytest.mark.parametrize("trans", [False, True])
+@pytest.mark.parametrize("n,k,batch", [(16, 32, 4099), (16, 1, 70001), (13, 31, 1030), (8, 16, 4101), (7, 5, 259), (4, 8, 4111),
+                                       (3, 32, 1037), (2, 2, 19), (1, 7, 5), (16, 33, 7)])
+def test_small_syrk_with_many_matrices(la, orc, dtype, trans, n, k, batch):
+    """n <= 16 with an inner dimension up to 32 runs in 16, 8 or 4 lanes per matrix (k = 33 does not)."""
+    rng = np.random.default_rng(n * 50 + k)
+    A = rng.standard_normal((batch, k, n) if trans else (batch, n, k)).astype(npdt(dtype))
+    ref = orc.syrk(A, trans=trans, alpha=0.5)
+    out = host(la.syrk(dev(A), trans=trans, alpha=0.5))
+    assert np.array_equal(out, out.transpose(0, 2, 1))
+    assert relerr(out, ref) <= TOL[dtype]
+
+
+@pytest.mark.parametrize("dtype", ["f64", "f32"])
+@pytest.mark.parametrize("trans", [False, True])
 @pytest.mark.parametrize("n,k", [(1, 1), (4, 9), (16, 32), (32, 64), (65, 17), (130, 200), (64, 0), (50, 9568), (200, 2064),
                                  (64, 4096)])
 def test_syrk_parity(la, orc, dtype, trans, n, k):
