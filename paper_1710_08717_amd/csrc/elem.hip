@@ -219,6 +219,23 @@ __global__ __launch_bounds__(WAVE) void k_sumlogdiag(const T *L, T *out, int64_t
         out[b] = (T)s;
 }
 
+// n <= 32: G = 2^g >= n lanes per matrix, 64 / G matrices per wavefront (a wavefront per matrix
+// leaves most lanes idle and needs a workgroup per matrix).
+template <typename T>
+__global__ __launch_bounds__(256) void k_sumlogdiag_small(const T *L, T *out, int64_t batch, int n, int G)
+{
+    const int64_t t = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    const int64_t b = t / G;
+    const int i = (int)(t % G);
+    double s = 0.0;
+    if (b < batch && i < n)
+        s = (double)log(L[b * (int64_t)n * n + (int64_t)i * n + i]);
+    for (int off = G >> 1; off >= 1; off >>= 1)
+        s += __shfl_xor(s, off, WAVE);
+    if (b < batch && i == 0)
+        out[b] = (T)s;
+}
+
 template <typename T>
 la_status launch_sumlogdiag(const T *L, T *out, int64_t batch, int n, hipStream_t st)
 {
@@ -226,6 +243,16 @@ la_status launch_sumlogdiag(const T *L, T *out, int64_t batch, int n, hipStream_
         return LA_OK;
     if (batch > 0x7fffffffll)
         return LA_ERR_UNSUPPORTED;
+    if (n >= 1 && n <= 32) {
+        int G = 1;
+        while (G < n)
+            G *= 2;
+        const int64_t blocks = (batch * G + 255) / 256;
+        if (blocks > 0x7fffffffll)
+            return LA_ERR_UNSUPPORTED;
+        hipLaunchKernelGGL((k_sumlogdiag_small<T>), dim3((unsigned)blocks), dim3(256), 0, st, L, out, batch, n, G);
+        return launch_check("sumlogdiag_small");
+    }
     hipLaunchKernelGGL((k_sumlogdiag<T>), dim3((unsigned)batch), dim3(WAVE), 0, st, L, out, batch, n);
     return launch_check("sumlogdiag");
 }

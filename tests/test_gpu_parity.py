@@ -458,6 +458,18 @@ def test_sumlogdiag_parity(la, orc, dtype, n):
 
 
 @pytest.mark.parametrize("dtype", ["f64", "f32"])
+@pytest.mark.parametrize("n,batch", [(1, 300), (2, 70001), (3, 1001), (4, 4099), (7, 513), (16, 70001), (17, 99), (32, 1027),
+                                     (33, 70)])
+def test_sumlogdiag_small_sizes_with_many_matrices(la, orc, dtype, n, batch):
+    """Up to n = 32 several matrices share a wavefront (lane groups of 1 .. 32); 33 takes a wavefront each."""
+    T = tri(n + batch, batch, n, True, dtype)
+    ref = orc.sumlogdiag(T)
+    out = host(la.sumlogdiag(dev(T))).astype(np.float64)
+    assert out.shape == (batch,)
+    assert np.max(np.abs(out - ref) / np.maximum(np.abs(ref), 1.0)) <= TOL[dtype]
+
+
+@pytest.mark.parametrize("dtype", ["f64", "f32"])
 @pytest.mark.parametrize("n", [3, 32, 128, 150])
 def test_gp_glue_parity(la, orc, dtype, n):
     batch = 4
