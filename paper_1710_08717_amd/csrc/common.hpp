@@ -393,7 +393,7 @@ int backward_leaf16_max_n();
 template <typename T>
 la_status launch_backward_leaf16(View<const T> Lam, View<const T> G, View<T> Abar, int64_t batch, int n, hipStream_t st);
 
-// trsm / trmm for n <= 16 with at most 16 vectors, any batch: the operand as flat items of n * m
+// trsm / trmm for n <= 64 with at most 16 vectors, any batch: the operand as flat items of n * m
 // elements (stored m x n when img_tr), M = Lam (fwd) or Lam^T
 template <typename T>
 la_status launch_tri_tiny(bool solve, bool fwd, T alpha, int64_t batch, int n, int m, View<const T> Lam, const T *Bin,

@@ -664,7 +664,7 @@ la_status launch_backward_tiny(View<const T> L, View<const T> G, View<T> Abar, i
 }
 
 // ---------------------------------------------------------------------------------
-// trsm / trmm for n <= 16 and at most 16 vectors (section 4.2 "trsm", "trmm"), G lanes per matrix:
+// trsm / trmm for n <= 64 and at most 16 vectors (section 4.2 "trsm", "trmm"), G lanes per matrix:
 // lane i holds row i of M (M = Lam or Lam^T, whichever the operator applies) and row i of the
 // n x m operand, registers = its m columns.  The operand travels as its flat memory image (n x m
 // or, for right-side operators, m x n per item, items back to back): 16-byte loads into LDS,
@@ -698,10 +698,11 @@ __global__ __launch_bounds__(WAVE) void k_tri_tiny(View<const T> Lam, const T *B
 
     // ---- the operand's image: vector loads when the wavefront has all its items ----
     const T *src = Bin + b0 * nm;
-    const bool vec = (cnt == MPW) && ((reinterpret_cast<uintptr_t>(Bin) & 15) == 0);
+    // (every wavefront's chunk must start on a 16-byte boundary and hold whole vectors)
+    const bool vec = (cnt == MPW) && ((MPW * nm) % VN == 0) && ((reinterpret_cast<uintptr_t>(Bin) & 15) == 0);
     if (vec) {
         constexpr int ITV = (IMG / VN + WAVE - 1) / WAVE;
-        const int nvec = tot / VN;  // MPW n m is a multiple of VN
+        const int nvec = tot / VN;
         V4 v[ITV];
 #pragma unroll
         for (int t = 0; t < ITV; ++t)
@@ -849,13 +850,17 @@ la_status launch_tri_tiny(bool solve, bool fwd, T alpha, int64_t batch, int n, i
 {
     if (batch <= 0 || n <= 0 || m <= 0)
         return LA_OK;
-    if (n > 16 || m > TRI_MC || (batch + 3) / 4 > 0x7fffffffll)
+    if (n > 64 || m > TRI_MC || batch > 0x7fffffffll)
         return LA_ERR_UNSUPPORTED;
     if (n <= 4)
         return launch_tri_tiny_g<T, 4>(solve, Lam, Bin, Bout, batch, n, m, fwd, img_tr, alpha, st);
     if (n <= 8)
         return launch_tri_tiny_g<T, 8>(solve, Lam, Bin, Bout, batch, n, m, fwd, img_tr, alpha, st);
-    return launch_tri_tiny_g<T, 16>(solve, Lam, Bin, Bout, batch, n, m, fwd, img_tr, alpha, st);
+    if (n <= 16)
+        return launch_tri_tiny_g<T, 16>(solve, Lam, Bin, Bout, batch, n, m, fwd, img_tr, alpha, st);
+    if (n <= 32)  // broadcasts through ds_bpermute
+        return launch_tri_tiny_g<T, 32>(solve, Lam, Bin, Bout, batch, n, m, fwd, img_tr, alpha, st);
+    return launch_tri_tiny_g<T, 64>(solve, Lam, Bin, Bout, batch, n, m, fwd, img_tr, alpha, st);  // v_readlane
 }
 
 template la_status launch_tri_tiny<float>(bool, bool, float, int64_t, int, int, View<const float>, const float *, float *,
@@ -888,7 +893,7 @@ __global__ __launch_bounds__(WAVE) void k_syrk_tiny(const T *Ain, View<T> C, int
     const int cnt = (int)((batch - b0) < MPW ? (batch - b0) : MPW);
     const int nk = n * k, tot = cnt * nk;
     const T *src = Ain + b0 * nk;
-    if ((cnt == MPW) && ((reinterpret_cast<uintptr_t>(Ain) & 15) == 0)) {
+    if ((cnt == MPW) && ((MPW * nk) % VN == 0) && ((reinterpret_cast<uintptr_t>(Ain) & 15) == 0)) {
         constexpr int ITV = (IMG / VN + WAVE - 1) / WAVE;
         const int nvec = tot / VN;
         V4 v[ITV];
