@@ -401,6 +401,9 @@ la_status launch_tri_tiny(bool solve, bool fwd, T alpha, int64_t batch, int n, i
 // syrk for n <= 16 and inner dimension <= 32: A as flat items of n * k elements (stored k x n when img_tr)
 template <typename T>
 la_status launch_syrk_tiny(bool img_tr, T alpha, int64_t batch, int n, int k, const T *A, View<T> C, hipStream_t st);
+// potri for n <= 16: B = Lam^-T Lam^-1, exactly symmetric
+template <typename T>
+la_status launch_potri_tiny(View<const T> Lam, View<T> B, int64_t batch, int n, hipStream_t st);
 // Register-resident potrf backward for n <= 32: Abar = sym(L^-T Phi(L^T Lbar) L^-1).
 template <typename T>
 la_status launch_backward_tiny(View<const T> L, View<const T> G, View<T> Abar, int64_t batch, int n,

@@ -658,6 +658,8 @@ template <typename T>
 static la_status potri_t(int lower, int64_t batch, int n, const void *L, void *B, hipStream_t st)
 {
     View<const T> Lam = tri_view<const T>((const T *)L, n, lower);
+    if (n <= 16)  // both solves on the identity in registers, G lanes per matrix
+        return launch_potri_tiny<T>(Lam, View<T>{(T *)B, (int64_t)n * n, n, 1}, batch, n, st);
     View<T> sc[2];
     LA_TRY(scratch_views<T>(batch, n, 2, sc));
     LA_TRY(inverse_build<T>(Lam, sc[0], sc[1], batch, n, n, st));

@@ -977,6 +977,98 @@ la_status launch_syrk_tiny(bool img_tr, T alpha, int64_t batch, int n, int k, co
 template la_status launch_syrk_tiny<float>(bool, float, int64_t, int, int, const float *, View<float>, hipStream_t);
 template la_status launch_syrk_tiny<double>(bool, double, int64_t, int, int, const double *, View<double>, hipStream_t);
 
+// ---------------------------------------------------------------------------------
+// potri for n <= 16 (section 4.2 "potri": A^-1 from the factor by two triangular solves), G lanes
+// per matrix, both solves of k_tri_tiny on the identity in registers:
+//   X = Lam^-1,  B = Lam^-T X;  the upper triangle of B is then taken from the lower one through
+// the stage (exactly symmetric result).
+// ---------------------------------------------------------------------------------
+template <typename T, int G>
+__global__ __launch_bounds__(WAVE) void k_potri_tiny(View<const T> Lam, View<T> B, int64_t batch, int n)
+{
+    using S = Stage<T, G>;
+    __shared__ __align__(16) T sm[S::ELEMS];
+    const int lane = threadIdx.x;
+    const int q = lane / G, i = lane % G;
+    const int64_t b0 = (int64_t)blockIdx.x * S::MPW;
+    T *smq = sm + q * S::MS;
+    const Mem<const T> Lm = mem_of(Lam);
+    stage_load<T, G>(sm, Lm, b0, batch, n);
+    __syncthreads();
+    T m1[G], m2[G];  // row i of Lam, row i of Lam^T
+    read_lrow<T, G>(smq, i, Lm.tr, m1);
+    read_lcol<T, G>(smq, i, Lm.tr, m2);
+    T dii = T(1);
+#pragma unroll
+    for (int k = 0; k < G; ++k)
+        if (k == i)
+            dii = m1[k];
+    const T rinv = rcp_acc(dii);
+#pragma unroll
+    for (int k = 0; k < G; ++k) {
+        m1[k] = (k < i) ? m1[k] * rinv : T(0);
+        m2[k] = (k > i) ? m2[k] * rinv : T(0);
+    }
+    T b[G];
+#pragma unroll
+    for (int c = 0; c < G; ++c)
+        b[c] = (c == i) ? rinv : T(0);
+    dpp_settle<G>(b);
+    static_for<0, G / 4>([&](auto CB) {
+        constexpr int c0 = 4 * decltype(CB)::value;
+        static_for<0, G>([&](auto Kk) {
+            constexpr int kk = decltype(Kk)::value;
+            static_for<0, 4>([&](auto J) { fma_bcast_self<G, kk>(b[c0 + decltype(J)::value], m1[kk], true); });
+        });
+    });
+#pragma unroll
+    for (int c = 0; c < G; ++c)
+        b[c] *= rinv;
+    dpp_settle<G>(b);
+    static_for<0, G / 4>([&](auto CB) {
+        constexpr int c0 = 4 * decltype(CB)::value;
+        static_for<0, G>([&](auto Kk) {
+            constexpr int kk = G - 1 - decltype(Kk)::value;
+            static_for<0, 4>([&](auto J) { fma_bcast_self<G, kk>(b[c0 + decltype(J)::value], m2[kk], true); });
+        });
+    });
+    __syncthreads();
+    write_row<T, G>(smq, i, b);
+    __syncthreads();
+    T bt[G];
+    read_col<T, G>(smq, i, bt);
+#pragma unroll
+    for (int c = 0; c < G; ++c)
+        b[c] = (c <= i) ? b[c] : bt[c];
+    __syncthreads();
+    write_row<T, G>(smq, i, b);
+    __syncthreads();
+    stage_store<T, G>(sm, mem_of(B), b0, batch, n);  // symmetric: orientation is immaterial
+}
+
+template <typename T>
+la_status launch_potri_tiny(View<const T> Lam, View<T> B, int64_t batch, int n, hipStream_t st)
+{
+    if (batch <= 0 || n <= 0)
+        return LA_OK;
+    if (n > 16 || (batch + 3) / 4 > 0x7fffffffll)
+        return LA_ERR_UNSUPPORTED;
+    if (n <= 4) {
+        constexpr int MPW = Stage<T, 4>::MPW;
+        hipLaunchKernelGGL((k_potri_tiny<T, 4>), dim3((unsigned)((batch + MPW - 1) / MPW)), dim3(WAVE), 0, st, Lam, B, batch, n);
+    } else if (n <= 8) {
+        constexpr int MPW = Stage<T, 8>::MPW;
+        hipLaunchKernelGGL((k_potri_tiny<T, 8>), dim3((unsigned)((batch + MPW - 1) / MPW)), dim3(WAVE), 0, st, Lam, B, batch, n);
+    } else {
+        constexpr int MPW = Stage<T, 16>::MPW;
+        hipLaunchKernelGGL((k_potri_tiny<T, 16>), dim3((unsigned)((batch + MPW - 1) / MPW)), dim3(WAVE), 0, st, Lam, B, batch, n);
+    }
+    return launch_check("potri_tiny");
+}
+
+template la_status launch_potri_tiny<float>(View<const float>, View<float>, int64_t, int, hipStream_t);
+template la_status launch_potri_tiny<double>(View<const double>, View<double>, int64_t, int, hipStream_t);
+
 template la_status launch_potrf_tiny<float>(View<const float>, View<float>, int32_t *, int, int64_t, int, hipStream_t);
 template la_status launch_potrf_tiny<double>(View<const double>, View<double>, int32_t *, int, int64_t, int,
                                              hipStream_t);

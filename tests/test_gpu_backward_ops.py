@@ -220,6 +220,20 @@ def test_potri_parity(la, orc, dtype, lower, n):
 
 @pytest.mark.parametrize("dtype", ["f64", "f32"])
 @pytest.mark.parametrize("lower", [True, False])
+@pytest.mark.parametrize("n,batch", [(16, 4099), (13, 1030), (8, 4101), (6, 259), (4, 4111), (3, 70001), (2, 19), (1, 70)])
+def test_potri_small_sizes_with_many_matrices(la, orc, dtype, lower, n, batch):
+    """n <= 16: 16, 8 or 4 lanes per matrix, both solves in registers; ragged last wavefronts."""
+    A = spd(7000 + n, batch, n, dtype)
+    F = orc.potrf(A, lower=lower).astype(npdt(dtype))
+    ref = orc.potri(F, lower=lower)
+    t = dev(F)
+    out = host(la.potri(t, lower=lower, out=t))  # B over L
+    assert np.array_equal(out, out.transpose(0, 2, 1))
+    assert relerr(out, ref) <= 10 * TOL[dtype]
+
+
+@pytest.mark.parametrize("dtype", ["f64", "f32"])
+@pytest.mark.parametrize("lower", [True, False])
 @pytest.mark.parametrize("n", [1, 5, 16, 33, 64, 100, 128, 200])
 def test_potri_backward_parity(la, orc, dtype, lower, n):
     batch = 3
