@@ -401,6 +401,10 @@ la_status launch_tri_tiny(bool solve, bool fwd, T alpha, int64_t batch, int n, i
 // syrk for n <= 16 and inner dimension <= 32: A as flat items of n * k elements (stored k x n when img_tr)
 template <typename T>
 la_status launch_syrk_tiny(bool img_tr, T alpha, int64_t batch, int n, int k, const T *A, View<T> C, hipStream_t st);
+// C = alpha U V^T (same shapes and limits; tri: 0 whole square, 1 / 2 lower / upper triangle kept, zeros elsewhere)
+template <typename T>
+la_status launch_outer_tiny(bool img_tr, int tri, T alpha, int64_t batch, int n, int k, const T *U, const T *V, View<T> C,
+                            hipStream_t st);
 // potri for n <= 16: B = Lam^-T Lam^-1, exactly symmetric
 template <typename T>
 la_status launch_potri_tiny(View<const T> Lam, View<T> B, int64_t batch, int n, hipStream_t st);

@@ -590,6 +590,10 @@ static la_status tri_outer_t(int lower, int trans, int rightside, T scale, int64
 {
     const int64_t nn = (int64_t)n * n, nm = (int64_t)n * m;
     View<T> G{out, nn, n, 1};
+    if (n <= 16 && m >= 1 && m <= 32) {  // G lanes per matrix: product, mask and zeros in one launch
+        const T *U = rightside ? (trans ? P : Q) : (trans ? Q : P), *V = rightside ? (trans ? Q : P) : (trans ? P : Q);
+        return launch_outer_tiny<T>(rightside != 0, lower ? 1 : 2, scale, batch, n, m, U, V, G, st);
+    }
     LA_TRY(launch_zero_strict_upper<T>(lower ? G : G.t(), batch, n, st));  // the other triangle of the result
     GemmOpts o;
     o.maskC = lower ? 1 : 2;

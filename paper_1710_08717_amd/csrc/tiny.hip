@@ -877,23 +877,15 @@ template la_status launch_tri_tiny<double>(bool, bool, double, int64_t, int, int
 // ---------------------------------------------------------------------------------
 constexpr int SYRK_KC = 32;
 
-template <typename T, int G>
-__global__ __launch_bounds__(WAVE) void k_syrk_tiny(const T *Ain, View<T> C, int64_t batch, int n, int k, int img_tr, T alpha)
+// flat image of cnt items of `per` elements each into LDS (16-byte loads when whole and aligned)
+template <typename T, int IMG, int MPW>
+__device__ __forceinline__ void image_load(T *img, const T *base, int64_t b0, int cnt, int per, int lane)
 {
-    using S = Stage<T, G>;
     using V4 = typename VecOf<T>::type;
     constexpr int VN = VecOf<T>::N;
-    constexpr int MPW = S::MPW;
-    constexpr int IMG = MPW * G * SYRK_KC;
-    __shared__ __align__(16) T sm[S::ELEMS];
-    __shared__ __align__(16) T img[IMG + IMG / 16 + 4];
-    const int lane = threadIdx.x;
-    const int q = lane / G, i = lane % G;
-    const int64_t b0 = (int64_t)blockIdx.x * MPW;
-    const int cnt = (int)((batch - b0) < MPW ? (batch - b0) : MPW);
-    const int nk = n * k, tot = cnt * nk;
-    const T *src = Ain + b0 * nk;
-    if ((cnt == MPW) && ((MPW * nk) % VN == 0) && ((reinterpret_cast<uintptr_t>(Ain) & 15) == 0)) {
+    const int tot = cnt * per;
+    const T *src = base + b0 * per;
+    if ((cnt == MPW) && ((MPW * per) % VN == 0) && ((reinterpret_cast<uintptr_t>(base) & 15) == 0)) {
         constexpr int ITV = (IMG / VN + WAVE - 1) / WAVE;
         const int nvec = tot / VN;
         V4 v[ITV];
@@ -916,19 +908,50 @@ __global__ __launch_bounds__(WAVE) void k_syrk_tiny(const T *Ain, View<T> C, int
         for (int e = lane; e < tot; e += WAVE)
             img[img_idx(e)] = src[e];
     }
+}
+
+// C = alpha U V^T for n x k operands U, V (V == U: syrk); tri = 0 writes the whole square, 1 / 2 keep
+// the lower / upper triangle and write zeros to the other one (the gradient of a triangular
+// operand in the trmm / trsm backward rules, section 4.2).
+template <typename T, int G, bool TWO>
+__global__ __launch_bounds__(WAVE) void k_syrk_tiny(const T *Uin, const T *Vin, View<T> C, int64_t batch, int n, int k,
+                                                     int img_tr, int tri, T alpha)
+{
+    using S = Stage<T, G>;
+    constexpr int MPW = S::MPW;
+    constexpr int IMG = MPW * G * SYRK_KC;
+    constexpr int IMGP = (IMG + IMG / 16 + 4 + 3) / 4 * 4;  // padded image, a multiple of 16 bytes
+    constexpr int SMP = (S::ELEMS + 3) / 4 * 4;
+    extern __shared__ __align__(16) unsigned char tiny_lds[];
+    T *sm = reinterpret_cast<T *>(tiny_lds), *img = sm + SMP, *img2 = img + IMGP;  // img2 only when V != U
+    const int lane = threadIdx.x;
+    const int q = lane / G, i = lane % G;
+    const int64_t b0 = (int64_t)blockIdx.x * MPW;
+    const int cnt = (int)((batch - b0) < MPW ? (batch - b0) : MPW);
+    const int nk = n * k;
+    image_load<T, IMG, MPW>(img, Uin, b0, cnt, nk, lane);
+    if constexpr (TWO)
+        image_load<T, IMG, MPW>(img2, Vin, b0, cnt, nk, lane);
     __syncthreads();
 
-    T a[SYRK_KC];
+    T a[SYRK_KC], v[TWO ? SYRK_KC : 1];
     const bool live = (i < n) && (q < cnt);
     const int ebase = q * nk + (img_tr ? i : i * k), estep = img_tr ? n : 1;
 #pragma unroll
     for (int c = 0; c < SYRK_KC; ++c)
         a[c] = (live && c < k) ? img[img_idx(ebase + c * estep)] : T(0);
+    if constexpr (TWO) {
+#pragma unroll
+        for (int c = 0; c < SYRK_KC; ++c)
+            v[c] = (live && c < k) ? img2[img_idx(ebase + c * estep)] : T(0);
+        dpp_settle<G>(v);
+    } else {
+        dpp_settle<G>(a);
+    }
     T out[G];
 #pragma unroll
     for (int j = 0; j < G; ++j)
         out[j] = T(0);
-    dpp_settle<G>(a);
     static_for<0, G>([&](auto Jj) {
         constexpr int j = decltype(Jj)::value;
         if (j < n) {
@@ -937,43 +960,71 @@ __global__ __launch_bounds__(WAVE) void k_syrk_tiny(const T *Ain, View<T> C, int
                 if (c0 < k) {
                     static_for<0, 4>([&](auto U) {
                         constexpr int c = c0 + decltype(U)::value;
-                        fma_bcast<G, j>(out[j], a[c], a[c], false);
+                        if constexpr (TWO)
+                            fma_bcast<G, j>(out[j], v[c], a[c], false);  // u_ic v_jc
+                        else
+                            fma_bcast<G, j>(out[j], a[c], a[c], false);
                     });
                 }
             });
         }
     });
 #pragma unroll
-    for (int j = 0; j < G; ++j)
-        out[j] *= alpha;
+    for (int j = 0; j < G; ++j) {
+        const bool keep = tri == 0 || (tri == 1 ? j <= i : j >= i);
+        out[j] = keep ? out[j] * alpha : T(0);
+    }
     write_row<T, G>(sm + q * S::MS, i, out);
     __syncthreads();
-    stage_store<T, G>(sm, mem_of(C), b0, batch, n);
+    stage_store<T, G>(sm, Mem<T>{C.p, C.bs, C.rs, false}, b0, batch, n);
+}
+
+template <typename T>
+la_status launch_outer_tiny(bool img_tr, int tri, T alpha, int64_t batch, int n, int k, const T *U, const T *V, View<T> C,
+                            hipStream_t st)
+{
+    if (batch <= 0 || n <= 0)
+        return LA_OK;
+    if (n > 16 || k > SYRK_KC || k < 1 || (batch + 3) / 4 > 0x7fffffffll || C.cs != 1)
+        return LA_ERR_UNSUPPORTED;
+    const int images = (U == V) ? 1 : 2;
+    auto lds = [&](int g, int elems) {  // stage + images, as laid out in the kernel
+        const int img = (64 / g) * g * SYRK_KC, imgp = (img + img / 16 + 4 + 3) / 4 * 4;
+        return (size_t)((elems + 3) / 4 * 4 + images * imgp) * sizeof(T);
+    };
+    const dim3 blk(WAVE);
+    const int itr = img_tr ? 1 : 0;
+#define LA_SYRK_TINY(GG)                                                                                                  \
+    do {                                                                                                                  \
+        constexpr int MPW = Stage<T, GG>::MPW;                                                                            \
+        const dim3 grid((unsigned)((batch + MPW - 1) / MPW));                                                             \
+        if (images == 2)                                                                                                  \
+            hipLaunchKernelGGL((k_syrk_tiny<T, GG, true>), grid, blk, lds(GG, Stage<T, GG>::ELEMS), st, U, V, C, batch, n, \
+                               k, itr, tri, alpha);                                                                       \
+        else                                                                                                              \
+            hipLaunchKernelGGL((k_syrk_tiny<T, GG, false>), grid, blk, lds(GG, Stage<T, GG>::ELEMS), st, U, V, C, batch,   \
+                               n, k, itr, tri, alpha);                                                                    \
+    } while (0)
+    if (n <= 4)
+        LA_SYRK_TINY(4);
+    else if (n <= 8)
+        LA_SYRK_TINY(8);
+    else
+        LA_SYRK_TINY(16);
+#undef LA_SYRK_TINY
+    return launch_check("syrk_tiny");
 }
 
 template <typename T>
 la_status launch_syrk_tiny(bool img_tr, T alpha, int64_t batch, int n, int k, const T *A, View<T> C, hipStream_t st)
 {
-    if (batch <= 0 || n <= 0)
-        return LA_OK;
-    if (n > 16 || k > SYRK_KC || k < 1 || (batch + 3) / 4 > 0x7fffffffll)
-        return LA_ERR_UNSUPPORTED;
-    if (n <= 4) {
-        constexpr int MPW = Stage<T, 4>::MPW;
-        hipLaunchKernelGGL((k_syrk_tiny<T, 4>), dim3((unsigned)((batch + MPW - 1) / MPW)), dim3(WAVE), 0, st, A, C, batch,
-                           n, k, img_tr ? 1 : 0, alpha);
-    } else if (n <= 8) {
-        constexpr int MPW = Stage<T, 8>::MPW;
-        hipLaunchKernelGGL((k_syrk_tiny<T, 8>), dim3((unsigned)((batch + MPW - 1) / MPW)), dim3(WAVE), 0, st, A, C, batch,
-                           n, k, img_tr ? 1 : 0, alpha);
-    } else {
-        constexpr int MPW = Stage<T, 16>::MPW;
-        hipLaunchKernelGGL((k_syrk_tiny<T, 16>), dim3((unsigned)((batch + MPW - 1) / MPW)), dim3(WAVE), 0, st, A, C, batch,
-                           n, k, img_tr ? 1 : 0, alpha);
-    }
-    return launch_check("syrk_tiny");
+    return launch_outer_tiny<T>(img_tr, 0, alpha, batch, n, k, A, A, C, st);
 }
 
+template la_status launch_outer_tiny<float>(bool, int, float, int64_t, int, int, const float *, const float *, View<float>,
+                                            hipStream_t);
+template la_status launch_outer_tiny<double>(bool, int, double, int64_t, int, int, const double *, const double *,
+                                             View<double>, hipStream_t);
 template la_status launch_syrk_tiny<float>(bool, float, int64_t, int, int, const float *, View<float>, hipStream_t);
 template la_status launch_syrk_tiny<double>(bool, double, int64_t, int, int, const double *, View<double>, hipStream_t);
 
