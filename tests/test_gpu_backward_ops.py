@@ -121,6 +121,29 @@ def test_trsm_backward_parity(la, orc, dtype, lower, trans, rightside, n, m):
 
 
 @pytest.mark.parametrize("dtype", ["f64", "f32"])
+@pytest.mark.parametrize("lower,trans,rightside", FLAGS)
+@pytest.mark.parametrize("op", ["trsm", "trmm"])
+@pytest.mark.parametrize("n,m,batch", [(16, 16, 1031), (16, 32, 70), (13, 7, 515), (8, 8, 4101), (5, 20, 66), (4, 4, 4111),
+                                       (3, 1, 1037), (1, 1, 5), (16, 33, 9)])
+def test_small_backward_rules_with_many_matrices(la, orc, dtype, lower, trans, rightside, op, n, m, batch):
+    """n <= 16: the solve / multiply and the triangular operand's gradient (outer product over up to 32 vectors, masked)
+    run in lane groups of 16, 8 or 4 per matrix; ragged last wavefronts.  m = 33 falls back to the tiled path."""
+    T, Tj, A, G, other = case(4000 + n + m, n, m, lower, rightside, dtype, batch=batch)
+    alpha = 0.5
+    if op == "trsm":
+        X = orc.trsm(T, A, lower=lower, trans=trans, rightside=rightside, alpha=alpha).astype(npdt(dtype))
+        ra, rl = orc.trsm_backward(T, X, G, lower=lower, trans=trans, rightside=rightside, alpha=alpha)
+        ga, gl = la.trsm_backward(dev(Tj), dev(X), dev(G), lower=lower, trans=trans, rightside=rightside, alpha=alpha)
+    else:
+        ra, rl = orc.trmm_backward(T, A, G, lower=lower, trans=trans, rightside=rightside, alpha=alpha)
+        ga, gl = la.trmm_backward(dev(Tj), dev(A), dev(G), lower=lower, trans=trans, rightside=rightside, alpha=alpha)
+    ga, gl = host(ga), host(gl)
+    assert relerr(ga, ra) <= TOL[dtype]
+    assert relerr(gl, rl) <= TOL[dtype]
+    assert np.all(gl[:, other[0], other[1]] == 0.0)
+
+
+@pytest.mark.parametrize("dtype", ["f64", "f32"])
 @pytest.mark.parametrize("trans", [False, True])
 @pytest.mark.parametrize("n,k", [(1, 1), (6, 3), (16, 64), (70, 64), (100, 37), (256, 128), (300, 50)])
 def test_syrk_backward_parity(la, orc, dtype, trans, n, k):
