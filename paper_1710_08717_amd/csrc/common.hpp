@@ -405,6 +405,10 @@ la_status launch_syrk_tiny(bool img_tr, T alpha, int64_t batch, int n, int k, co
 template <typename T>
 la_status launch_outer_tiny(bool img_tr, int tri, T alpha, int64_t batch, int n, int k, const T *U, const T *V, View<T> C,
                             hipStream_t st);
+// gemm2 for m, n, k <= 16: C = alpha op(A) op(B), contiguous row-major items
+template <typename T>
+la_status launch_gemm2_tiny(int ta, int tb, T alpha, int64_t batch, int m, int n, int k, const T *A, const T *B, T *C,
+                            hipStream_t st);
 // potri for n <= 16: B = Lam^-T Lam^-1, exactly symmetric
 template <typename T>
 la_status launch_potri_tiny(View<const T> Lam, View<T> B, int64_t batch, int n, hipStream_t st);

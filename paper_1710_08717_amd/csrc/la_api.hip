@@ -569,6 +569,8 @@ static la_status gemm2_t(int ta, int tb, double alpha, int64_t batch, int m, int
     View<const T> Av = ta ? View<const T>{(const T *)A, sa, 1, m} : View<const T>{(const T *)A, sa, k, 1};  // m x k
     View<const T> Bv = tb ? View<const T>{(const T *)B, sb, 1, k} : View<const T>{(const T *)B, sb, n, 1};  // k x n
     View<T> Cv{(T *)C, sc, n, 1};
+    if (m <= 16 && n <= 16 && k >= 1 && k <= 16)  // lane groups of 4, 8 or 16 per item, HBM bound
+        return launch_gemm2_tiny<T>(ta, tb, (T)alpha, batch, m, n, k, (const T *)A, (const T *)B, (T *)C, st);
     GemmOpts o;
     return launch_gemm<T>(Av, Bv, Cv, batch, m, n, k, (T)alpha, T(0), o, st);
 }

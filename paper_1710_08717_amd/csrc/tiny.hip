@@ -1028,6 +1028,121 @@ template la_status launch_outer_tiny<double>(bool, int, double, int64_t, int, in
 template la_status launch_syrk_tiny<float>(bool, float, int64_t, int, int, const float *, View<float>, hipStream_t);
 template la_status launch_syrk_tiny<double>(bool, double, int64_t, int, int, const double *, View<double>, hipStream_t);
 
+// flat image back to memory (the mirror of image_load)
+template <typename T, int IMG, int MPW>
+__device__ __forceinline__ void image_store(const T *img, T *base, int64_t b0, int cnt, int per, int lane)
+{
+    using V4 = typename VecOf<T>::type;
+    constexpr int VN = VecOf<T>::N;
+    const int tot = cnt * per;
+    T *dst = base + b0 * per;
+    if ((cnt == MPW) && ((MPW * per) % VN == 0) && ((reinterpret_cast<uintptr_t>(base) & 15) == 0)) {
+        constexpr int ITV = (IMG / VN + WAVE - 1) / WAVE;
+        const int nvec = tot / VN;
+#pragma unroll
+        for (int t = 0; t < ITV; ++t)
+            if (t * WAVE + lane < nvec) {
+                const int e = (t * WAVE + lane) * VN;
+                V4 v;
+                v.x = img[img_idx(e)];
+                v.y = img[img_idx(e + 1)];
+                if constexpr (VN == 4) {
+                    v.z = img[img_idx(e + 2)];
+                    v.w = img[img_idx(e + 3)];
+                }
+                __builtin_nontemporal_store(v, reinterpret_cast<V4 *>(dst) + t * WAVE + lane);
+            }
+    } else {
+        for (int e = lane; e < tot; e += WAVE)
+            dst[e] = img[img_idx(e)];
+    }
+}
+
+// ---------------------------------------------------------------------------------
+// gemm2 for m, n, k <= 16 (section 4.2 "gemm2"): C = alpha op(A) op(B), G >= max(m, k) lanes per
+// item.  Lane i holds row i of op(A) (k registers) and row i of op(B) (n registers);
+// c_ij = sum_c a_ic b_cj with b_cj broadcast from lane c.  All three operands travel as flat images.
+// ---------------------------------------------------------------------------------
+constexpr int GEMM2_MC = 16;
+
+template <typename T, int G>
+__global__ __launch_bounds__(WAVE) void k_gemm2_tiny(const T *A, const T *B, T *C, int64_t batch, int m, int n, int k,
+                                                      int ta, int tb, T alpha)
+{
+    constexpr int MPW = WAVE / G;
+    constexpr int IMG = MPW * G * GEMM2_MC;
+    __shared__ __align__(16) T imga[IMG + IMG / 16 + 4];
+    __shared__ __align__(16) T imgb[IMG + IMG / 16 + 4];
+    const int lane = threadIdx.x;
+    const int q = lane / G, i = lane % G;
+    const int64_t b0 = (int64_t)blockIdx.x * MPW;
+    const int cnt = (int)((batch - b0) < MPW ? (batch - b0) : MPW);
+    image_load<T, IMG, MPW>(imga, A, b0, cnt, m * k, lane);
+    image_load<T, IMG, MPW>(imgb, B, b0, cnt, k * n, lane);
+    __syncthreads();
+    T a[G], br[GEMM2_MC], out[GEMM2_MC];
+    const bool la_ = (q < cnt) && (i < m), lb = (q < cnt) && (i < k);
+    const int ea = q * m * k + (ta ? i : i * k), sa = ta ? m : 1;  // op(A)(i, c)
+    const int eb = q * k * n + (tb ? i : i * n), sb = tb ? k : 1;  // op(B)(i, j)
+#pragma unroll
+    for (int c = 0; c < G; ++c)
+        a[c] = (la_ && c < k) ? imga[img_idx(ea + c * sa)] : T(0);
+#pragma unroll
+    for (int j = 0; j < GEMM2_MC; ++j) {
+        br[j] = (lb && j < n) ? imgb[img_idx(eb + j * sb)] : T(0);
+        out[j] = T(0);
+    }
+    dpp_settle<G>(br);
+    static_for<0, G>([&](auto Cc) {
+        constexpr int c = decltype(Cc)::value;
+        if (c < k) {
+            static_for<0, GEMM2_MC / 4>([&](auto JB) {
+                constexpr int j0 = 4 * decltype(JB)::value;
+                if (j0 < n) {
+                    static_for<0, 4>([&](auto U) {
+                        constexpr int j = j0 + decltype(U)::value;
+                        fma_bcast<G, c>(out[j], br[j], a[c], false);
+                    });
+                }
+            });
+        }
+    });
+    __syncthreads();
+    const int ec = q * m * n + i * n;
+#pragma unroll
+    for (int j = 0; j < GEMM2_MC; ++j)
+        if (la_ && j < n)
+            imga[img_idx(ec + j)] = alpha * out[j];
+    __syncthreads();
+    image_store<T, IMG, MPW>(imga, C, b0, cnt, m * n, lane);
+}
+
+template <typename T>
+la_status launch_gemm2_tiny(int ta, int tb, T alpha, int64_t batch, int m, int n, int k, const T *A, const T *B, T *C,
+                            hipStream_t st)
+{
+    if (batch <= 0 || m <= 0 || n <= 0)
+        return LA_OK;
+    if (m > 16 || n > GEMM2_MC || k > 16 || k < 1 || (batch + 3) / 4 > 0x7fffffffll)
+        return LA_ERR_UNSUPPORTED;
+    const int d = m > k ? m : k;
+    if (d <= 4)
+        hipLaunchKernelGGL((k_gemm2_tiny<T, 4>), dim3((unsigned)((batch + 15) / 16)), dim3(WAVE), 0, st, A, B, C, batch, m, n,
+                           k, ta, tb, alpha);
+    else if (d <= 8)
+        hipLaunchKernelGGL((k_gemm2_tiny<T, 8>), dim3((unsigned)((batch + 7) / 8)), dim3(WAVE), 0, st, A, B, C, batch, m, n, k,
+                           ta, tb, alpha);
+    else
+        hipLaunchKernelGGL((k_gemm2_tiny<T, 16>), dim3((unsigned)((batch + 3) / 4)), dim3(WAVE), 0, st, A, B, C, batch, m, n,
+                           k, ta, tb, alpha);
+    return launch_check("gemm2_tiny");
+}
+
+template la_status launch_gemm2_tiny<float>(int, int, float, int64_t, int, int, int, const float *, const float *, float *,
+                                            hipStream_t);
+template la_status launch_gemm2_tiny<double>(int, int, double, int64_t, int, int, int, const double *, const double *,
+                                             double *, hipStream_t);
+
 // ---------------------------------------------------------------------------------
 // potri for n <= 16 (section 4.2 "potri": A^-1 from the factor by two triangular solves), G lanes
 // per matrix, both solves of k_tri_tiny on the identity in registers:
