@@ -409,6 +409,10 @@ la_status launch_outer_tiny(bool img_tr, int tri, T alpha, int64_t batch, int n,
 template <typename T>
 la_status launch_gemm2_tiny(int ta, int tb, T alpha, int64_t batch, int m, int n, int k, const T *A, const T *B, T *C,
                             hipStream_t st);
+// syrk backward for n <= 16, inner dimension <= 32: Out = alpha (Gb + Gb^T) A on flat items (stored k x n when img_tr)
+template <typename T>
+la_status launch_symm_tiny(bool img_tr, T alpha, int64_t batch, int n, int k, View<const T> Gb, const T *A, T *Out,
+                           hipStream_t st);
 // potri for n <= 16: B = Lam^-T Lam^-1, exactly symmetric
 template <typename T>
 la_status launch_potri_tiny(View<const T> Lam, View<T> B, int64_t batch, int n, hipStream_t st);

@@ -644,6 +644,8 @@ static la_status syrk_backward_t(int trans, double alpha, int64_t batch, int n, 
 {
     const int64_t nk = (int64_t)n * k, nn = (int64_t)n * n;
     View<const T> G{(const T *)Bbar, nn, n, 1};
+    if (n <= 16 && k >= 1 && k <= 32)  // lane groups of 4, 8 or 16 per matrix, one launch
+        return launch_symm_tiny<T>(trans != 0, (T)alpha, batch, n, k, G, (const T *)A, (T *)Abar, st);
     GemmOpts o;
     if (!trans) {
         View<const T> Av{(const T *)A, nk, k, 1};

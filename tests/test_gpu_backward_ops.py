@@ -145,6 +145,21 @@ def test_small_backward_rules_with_many_matrices(la, orc, dtype, lower, trans, r
 
 @pytest.mark.parametrize("dtype", ["f64", "f32"])
 @pytest.mark.parametrize("trans", [False, True])
+@pytest.mark.parametrize("n,k,batch", [(16, 32, 1031), (16, 1, 70001), (13, 31, 515), (8, 16, 4101), (5, 20, 66), (4, 8, 4111),
+                                       (3, 32, 1037), (1, 1, 5), (16, 33, 9)])
+def test_small_syrk_backward_with_many_matrices(la, orc, dtype, trans, n, k, batch):
+    """n <= 16 with an inner dimension up to 32: one lane-group launch (k = 33 takes the tiled path)."""
+    rng = np.random.default_rng(5000 + n + k)
+    A = rng.standard_normal((batch, k, n) if trans else (batch, n, k)).astype(npdt(dtype))
+    G = (rng.standard_normal((batch, n, n)) / np.sqrt(n)).astype(npdt(dtype))  # not symmetric
+    ref = orc.syrk_backward(A, G, trans=trans, alpha=0.7)
+    out = host(la.syrk_backward(dev(A), dev(G), trans=trans, alpha=0.7))
+    assert out.shape == A.shape
+    assert relerr(out, ref) <= TOL[dtype]
+
+
+@pytest.mark.parametrize("dtype", ["f64", "f32"])
+@pytest.mark.parametrize("trans", [False, True])
 @pytest.mark.parametrize("n,k", [(1, 1), (6, 3), (16, 64), (70, 64), (100, 37), (256, 128), (300, 50)])
 def test_syrk_backward_parity(la, orc, dtype, trans, n, k):
     batch = 3

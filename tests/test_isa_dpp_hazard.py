@@ -71,7 +71,7 @@ def test_checker_sees_a_planted_hazard():
     assert find_hazards(ok) == ([], 1)
 
 
-def _isa_text(name):
+def _compile_isa(name):
     from paper_1710_08717_amd import build
 
     src = os.path.join(build.CSRC, name)
@@ -80,8 +80,26 @@ def _isa_text(name):
         cmd = ["hipcc", *build.FLAGS, "--cuda-device-only", "-S", "-o", out, src]
         r = subprocess.run(cmd, capture_output=True, text=True)
         if r.returncode != 0:
-            pytest.fail("hipcc -S failed:\n" + r.stderr[-2000:])
-        return open(out).read()
+            return None, r.stderr[-2000:]
+        return open(out).read(), ""
+
+
+_ISA_FILES = ["leaf.hip", "tiny.hip", "tiny_ops.hip", "kalman.hip"]
+_isa_cache = {}
+
+
+def _isa_text(name):
+    """ISA text of one source; all four files with hand-written DPP are compiled side by side on first use."""
+    if not _isa_cache:
+        from concurrent.futures import ThreadPoolExecutor
+
+        with ThreadPoolExecutor(max_workers=4) as ex:
+            for f, res in zip(_ISA_FILES, ex.map(_compile_isa, _ISA_FILES)):
+                _isa_cache[f] = res
+    text, err = _isa_cache[name]
+    if text is None:
+        pytest.fail("hipcc -S failed:\n" + err)
+    return text
 
 
 def test_checker_handles_64_bit_operands():
@@ -107,6 +125,15 @@ def test_small_matrix_kernels_respect_dpp_spacing():
     hazards, n_dpp = find_hazards(text)
     assert n_dpp > 600  # the fused v_fmac_f32_dpp of the fp32 16-lane kernels are really there
     assert text.count("v_fmac_f32_dpp") >= 600
+    assert hazards == []
+
+
+def test_small_matrix_operator_kernels_respect_dpp_spacing():
+    text = _isa_text("tiny_ops.hip")
+    hazards, n_dpp = find_hazards(text)
+    # trsm / trmm, syrk and outer products, gemm2, syrk backward, potri in 4, 8 and 16 lanes per matrix
+    assert text.count("v_fmac_f32_dpp") >= 2000
+    assert text.count("v_fmac_f64_dpp") >= 1000
     assert hazards == []
 
 
