@@ -204,12 +204,105 @@ def bench_kalman(args, la, torch, np, workloads):
         "cpu_baseline": cpu}), flush=True)
 
 
+def bench_small(args, la, torch, np, workloads):
+    """Operators of the path on many small matrices (batch mode, section 4.1): one step = potrf, trsm, trmm,
+    syrk, sumlogdiag, potrf backward, gemm2, potri and the trsm / trmm / syrk backward rules, each once
+    over the whole batch.  Inputs are seeded like the C2 workload (A = X X^T / 2n + I / 2)."""
+    n = args.n or 16
+    dtype = args.dtype or "f32"
+    batch = args.batch or 65536 * 256 // (n * n)
+    m, k = min(n, 16), min(2 * n, 32)
+    steps = args.steps if args.steps is not None else 20
+    warmup = args.warmup if args.warmup is not None else 3
+    s = 4 if dtype == "f32" else 8
+    rng = np.random.default_rng(171008717 + 9000 + n)
+    dt = workloads.np_dtype(dtype)
+    X = rng.standard_normal((batch, n, k)).astype(dt)
+    A = torch.from_numpy(X).cuda()
+    Aspd = (A @ A.transpose(1, 2) / k + 0.5 * torch.eye(n, dtype=A.dtype, device="cuda")).contiguous()
+    B = torch.from_numpy(rng.standard_normal((batch, n, m)).astype(dt)).cuda()
+    Gb = torch.from_numpy(rng.standard_normal((batch, n, m)).astype(dt)).cuda()
+    Lbar = torch.tril(torch.from_numpy(rng.standard_normal((batch, n, n)).astype(dt)).cuda())
+    Gs = torch.from_numpy(rng.standard_normal((batch, n, n)).astype(dt)).cuda()
+    L = la.potrf(Aspd)
+    o_nn = [torch.empty_like(Aspd) for _ in range(4)]
+    o_nm = [torch.empty_like(B) for _ in range(4)]
+    o_nk = torch.empty_like(A)
+    o_b = torch.empty(batch, dtype=A.dtype, device="cuda")
+    nn, nm, nk = n * n * s * batch, n * m * s * batch, n * k * s * batch
+    ops = {  # name -> (call, bytes of its operands and results as full rectangles)
+        "potrf": (lambda: la.potrf(Aspd, out=o_nn[0]), 2 * nn),
+        "backward": (lambda: la.potrf_backward(L, Lbar, out=o_nn[1]), 3 * nn),
+        "trsm": (lambda: la.trsm(L, B, out=o_nm[0]), nn + 2 * nm),
+        "trmm": (lambda: la.trmm(L, B, out=o_nm[1]), nn + 2 * nm),
+        "syrk": (lambda: la.syrk(A, out=o_nn[2]), nk + nn),
+        "sumlogdiag": (lambda: la.sumlogdiag(L, out=o_b), nn),
+        "gemm2": (lambda: la.gemm2(L, B, out=o_nm[2]), nn + 2 * nm),
+        "potri": (lambda: la.potri(L, out=o_nn[3]), 2 * nn),
+        "trsm_backward": (lambda: la.trsm_backward(L, o_nm[0], Gb, out_a=o_nm[3], out_l=o_nn[2]), 2 * nn + 3 * nm),
+        "trmm_backward": (lambda: la.trmm_backward(L, B, Gb, out_a=o_nm[3], out_l=o_nn[2]), 2 * nn + 3 * nm),
+        "syrk_backward": (lambda: la.syrk_backward(A, Gs, out=o_nk), nn + 2 * nk),
+    }
+
+    def step():
+        for f, _ in ops.values():
+            f()
+
+    for _ in range(warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        step()
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) * 1e3 / steps
+    kernel_ms = {}
+    for name, (f, _) in ops.items():
+        ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(steps)]
+        for a, b in ev:
+            a.record()
+            f()
+            b.record()
+        torch.cuda.synchronize()
+        kernel_ms[name] = float(np.mean([a.elapsed_time(b) for a, b in ev]))
+    tbs = {name: ops[name][1] / (kernel_ms[name] * 1e-3) / 1e12 for name in ops}
+    log(f"[bench] SMALL batch={batch} n={n} m={m} k={k} {dtype}: {ms:.3f} ms per step; per operator (us, TB/s): "
+        + ", ".join(f"{nm_} {kernel_ms[nm_] * 1e3:.0f} {tbs[nm_]:.2f}" for nm_ in ops))
+    cpu = None
+    if not args.no_cpu_baseline:
+        import oracle
+
+        sb = min(batch, 4096)
+        Lh, Bh, lb_h = L[:sb].cpu().numpy(), B[:sb].cpu().numpy(), Lbar[:sb].cpu().numpy()
+        t0, passes = time.perf_counter(), 0
+        while True:
+            oracle.trsm(Lh, Bh)
+            oracle.potrf_backward(Lh, lb_h)
+            passes += 1
+            dt_cpu = time.perf_counter() - t0
+            if dt_cpu >= 10.0 or passes >= 200:
+                break
+        cpu = {"value": passes * sb / dt_cpu, "unit": "matrices/s", "cores": oracle.num_threads(), "kind": "oracle",
+               "sample": f"trsm + potrf backward on the first {sb} matrices, {passes} passes, {dt_cpu:.2f} s in total"}
+    dom = "backward"
+    ach = ops[dom][1] / (kernel_ms[dom] * 1e-3) / 1e9
+    print(json.dumps({
+        "metric": "small-matrix operator set, matrices/s", "value": batch / (ms * 1e-3), "unit": "matrices/s",
+        "n_gpus": 1, "steps": steps, "warmup": warmup, "ms_per_step": ms, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": dtype, "data": "synthetic",
+        "config": {"workload": f"SMALL: batch={batch} n={n} vectors={m} inner={k} {dtype}", "ops": list(ops)},
+        "kernel_ms": kernel_ms, "tb_per_s_full_rectangles": tbs,
+        "roofline": {"bound": "hbm", "kernel": "la_potrf_backward", "achieved": ach, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": ach / HBM_PEAK_GBS, "traffic": None, "byte_model": "operands and results as full squares"},
+        "cpu_baseline": cpu}), flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=None)
     ap.add_argument("--warmup", type=int, default=None)
-    ap.add_argument("--config", default="C2", choices=["C1", "C2", "C3", "C4", "C5", "SGP", "KF"])
+    ap.add_argument("--config", default="C2", choices=["C1", "C2", "C3", "C4", "C5", "SGP", "KF", "SMALL"])
     ap.add_argument("--kf-dims", default="16,16", help="KF only: state and observation dimension, dh,dv (each <= 16)")
     ap.add_argument("--kf-steps", type=int, default=32, help="KF only: time steps per sequence")
     ap.add_argument("--inducing", type=int, default=3200, help="SGP only: number of inducing points U")
@@ -243,6 +336,8 @@ def main():
         return bench_sgp(args, la, torch, np, workloads)
     if name == "KF":
         return bench_kalman(args, la, torch, np, workloads)
+    if name == "SMALL":
+        return bench_small(args, la, torch, np, workloads)
     w = workloads.make(name, batch=args.batch, n=args.n, dtype=args.dtype)
     batch, n, dtype, m = w["batch"], w["n"], w["dtype"], w["m"]
     s = 4 if dtype == "f32" else 8
