@@ -263,10 +263,10 @@ __global__ __launch_bounds__(WAVE) void k_syrk_tiny(const T *Uin, const T *Vin, 
     using S = Stage<T, G>;
     constexpr int MPW = S::MPW;
     constexpr int IMG = MPW * G * SYRK_KC;
-    constexpr int IMGP = (IMG + IMG / 16 + 4 + 3) / 4 * 4;  // padded image, a multiple of 16 bytes
     constexpr int SMP = (S::ELEMS + 3) / 4 * 4;
+    const int imgp = (MPW * n * k * 17 / 16 + 4 + 3) / 4 * 4;  // image of this n, k with its padding, a multiple of 16 bytes
     extern __shared__ __align__(16) unsigned char tiny_lds[];
-    T *sm = reinterpret_cast<T *>(tiny_lds), *img = sm + SMP, *img2 = img + IMGP;  // img2 only when V != U
+    T *sm = reinterpret_cast<T *>(tiny_lds), *img = sm + SMP, *img2 = img + imgp;  // img2 only when V != U
     const int lane = threadIdx.x;
     const int q = lane / G, i = lane % G;
     const int64_t b0 = (int64_t)blockIdx.x * MPW;
@@ -332,7 +332,7 @@ la_status launch_outer_tiny(bool img_tr, int tri, T alpha, int64_t batch, int n,
         return LA_ERR_UNSUPPORTED;
     const int images = (U == V) ? 1 : 2;
     auto lds = [&](int g, int elems) {  // stage + images, as laid out in the kernel
-        const int img = (64 / g) * g * SYRK_KC, imgp = (img + img / 16 + 4 + 3) / 4 * 4;
+        const int imgp = ((64 / g) * n * k * 17 / 16 + 4 + 3) / 4 * 4;
         return (size_t)((elems + 3) / 4 * 4 + images * imgp) * sizeof(T);
     };
     const dim3 blk(WAVE);
