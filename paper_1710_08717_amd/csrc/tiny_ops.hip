@@ -263,10 +263,10 @@ __global__ __launch_bounds__(WAVE) void k_syrk_tiny(const T *Uin, const T *Vin, 
     using S = Stage<T, G>;
     constexpr int MPW = S::MPW;
     constexpr int IMG = MPW * G * SYRK_KC;
-    constexpr int SMP = (S::ELEMS + 3) / 4 * 4;
     const int imgp = (MPW * n * k * 17 / 16 + 4 + 3) / 4 * 4;  // image of this n, k with its padding, a multiple of 16 bytes
     extern __shared__ __align__(16) unsigned char tiny_lds[];
-    T *sm = reinterpret_cast<T *>(tiny_lds), *img = sm + SMP, *img2 = img + imgp;  // img2 only when V != U
+    // the result's stage overlays the images: they are dead (in registers) by the time it is written
+    T *sm = reinterpret_cast<T *>(tiny_lds), *img = sm, *img2 = img + imgp;  // img2 only when V != U
     const int lane = threadIdx.x;
     const int q = lane / G, i = lane % G;
     const int64_t b0 = (int64_t)blockIdx.x * MPW;
@@ -317,6 +317,7 @@ __global__ __launch_bounds__(WAVE) void k_syrk_tiny(const T *Uin, const T *Vin, 
         const bool keep = tri == 0 || (tri == 1 ? j <= i : j >= i);
         out[j] = keep ? out[j] * alpha : T(0);
     }
+    __syncthreads();
     write_row<T, G>(sm + q * S::MS, i, out);
     __syncthreads();
     stage_store<T, G>(sm, Mem<T>{C.p, C.bs, C.rs, false}, b0, batch, n);
@@ -332,8 +333,8 @@ la_status launch_outer_tiny(bool img_tr, int tri, T alpha, int64_t batch, int n,
         return LA_ERR_UNSUPPORTED;
     const int images = (U == V) ? 1 : 2;
     auto lds = [&](int g, int elems) {  // stage + images, as laid out in the kernel
-        const int imgp = ((64 / g) * n * k * 17 / 16 + 4 + 3) / 4 * 4;
-        return (size_t)((elems + 3) / 4 * 4 + images * imgp) * sizeof(T);
+        const int imgp = ((64 / g) * n * k * 17 / 16 + 4 + 3) / 4 * 4, smp = (elems + 3) / 4 * 4;
+        return (size_t)(smp > images * imgp ? smp : images * imgp) * sizeof(T);
     };
     const dim3 blk(WAVE);
     const int itr = img_tr ? 1 : 0;
