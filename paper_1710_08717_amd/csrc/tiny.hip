@@ -78,7 +78,8 @@ __global__ __launch_bounds__(WAVE) void k_potrf_tiny(View<const T> A, View<T> L,
 // so that every broadcast stays inside a 16-lane DPP row (one instruction with the multiply-add)
 // instead of going through the LDS crossbar or a scalar register as with 32 or 64 lanes per
 // matrix; four matrices per wavefront.  Column j = 16 jh + jl: its entries sit in register j of
-// row slot jh of lane jl.  R = 2 in fp32 and fp64, R = 3 (n <= 48) in fp32 (R N registers per lane).
+// row slot jh of lane jl.  R = 2 for n <= 32, R = 3 for n <= 48 (R N registers per lane; in fp64 R = 3 overflows
+// into accumulation registers and is still 1.4 to 2.3 times faster than 64 lanes per matrix).
 // ---------------------------------------------------------------------------------
 template <typename T, int R>
 __global__ __launch_bounds__(WAVE) void k_potrf_tiny_rows(View<const T> A, View<T> L, int32_t *info, int info_off,
@@ -422,7 +423,7 @@ la_status launch_potrf_tiny(View<const T> A, View<T> L, int32_t *info, int info_
         constexpr int MPW = Stage<T, 16>::MPW;
         hipLaunchKernelGGL((k_potrf_tiny<T, 16>), dim3((unsigned)((batch + MPW - 1) / MPW)), dim3(WAVE), 0, st, A, L,
                            info, info_off, batch, nb);
-    } else if (nb <= 32 || (sizeof(T) == 4 && nb <= 48)) {
+    } else if (nb <= 48) {
         // 16 lanes per matrix, 2 or 3 rows per lane.  (4 rows per lane for n <= 64 need all 256
         // registers and one wavefront per SIMD: no faster than 64 lanes per matrix at n = 64,
         // slower below.)
@@ -431,7 +432,7 @@ la_status launch_potrf_tiny(View<const T> A, View<T> L, int32_t *info, int info_
         constexpr size_t lds2 = sizeof(T) * Stage<T, 32, MPW>::ELEMS, lds3 = sizeof(T) * Stage<T, 48, MPW>::ELEMS;
         if (nb <= 32) {
             hipLaunchKernelGGL((k_potrf_tiny_rows<T, 2>), grid, dim3(WAVE), lds2, st, A, L, info, info_off, batch, nb);
-        } else if constexpr (sizeof(T) == 4) {
+        } else {
             hipLaunchKernelGGL((k_potrf_tiny_rows<T, 3>), grid, dim3(WAVE), lds3, st, A, L, info, info_off, batch, nb);
         }
     } else {
