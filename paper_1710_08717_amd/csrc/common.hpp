@@ -255,6 +255,27 @@ __device__ __forceinline__ void fma_bcast(T &acc, T src, T other, bool neg)
     }
 }
 
+// The 16-lane form for kernels whose fp64 state overflows the 256 vector registers: the compiler
+// then parks values in accumulation registers and may copy one back (a vector write) right before
+// the inline asm that reads it through DPP, which it cannot see; an s_nop inside the asm statement
+// restores the two wait states.  fp32 kernels of that kind do not overflow and take the plain form.
+template <int K, typename T>
+__device__ __forceinline__ void fma_bcast16_guarded(T &acc, T src, T other, bool neg)
+{
+    if constexpr (sizeof(T) == 8) {
+        if (neg)
+            asm volatile("s_nop 1\n\tv_fmac_f64_dpp %0, -%1, %2 row_newbcast:%3 row_mask:0xf bank_mask:0xf"
+                         : "+v"(acc)
+                         : "v"(src), "v"(other), "n"(K));
+        else
+            asm volatile("s_nop 1\n\tv_fmac_f64_dpp %0, %1, %2 row_newbcast:%3 row_mask:0xf bank_mask:0xf"
+                         : "+v"(acc)
+                         : "v"(src), "v"(other), "n"(K));
+    } else {
+        fma_bcast<16, K, T>(acc, src, other, neg);
+    }
+}
+
 // acc <- acc -/+ other * (acc's own value in lane K of the group).  With 8-lane groups the first
 // instruction of the pair writes the register the second one reads through DPP (other lanes of
 // it, but the wait states go by register), hence the s_nop between them.

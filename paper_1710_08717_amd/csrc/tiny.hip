@@ -79,7 +79,8 @@ __global__ __launch_bounds__(WAVE) void k_potrf_tiny(View<const T> A, View<T> L,
 // instead of going through the LDS crossbar or a scalar register as with 32 or 64 lanes per
 // matrix; four matrices per wavefront.  Column j = 16 jh + jl: its entries sit in register j of
 // row slot jh of lane jl.  R = 2 for n <= 32, R = 3 for n <= 48 (R N registers per lane; in fp64 R = 3 overflows
-// into accumulation registers and is still 1.4 to 2.3 times faster than 64 lanes per matrix).
+// into accumulation registers, takes the guarded broadcast multiply-add and is still 1.1 to 1.8 times faster
+// than 64 lanes per matrix).
 // ---------------------------------------------------------------------------------
 template <typename T, int R>
 __global__ __launch_bounds__(WAVE) void k_potrf_tiny_rows(View<const T> A, View<T> L, int32_t *info, int info_off,
@@ -125,7 +126,10 @@ __global__ __launch_bounds__(WAVE) void k_potrf_tiny_rows(View<const T> A, View<
             constexpr int kl = k % G, kh = k / G;
             static_for<jh, R>([&](auto H) {  // a_rk -= l_rj l_kj, with l_kj in row slot kh of lane kl
                 constexpr int h = decltype(H)::value;
-                fma_bcast<G, kl>(a[h][k], a[kh][j], a[h][j], true);
+                if constexpr (R >= 3)
+                    fma_bcast16_guarded<kl>(a[h][k], a[kh][j], a[h][j], true);
+                else
+                    fma_bcast<G, kl>(a[h][k], a[kh][j], a[h][j], true);
             });
         });
     });
@@ -322,10 +326,10 @@ __global__ __launch_bounds__(WAVE) void k_backward_tiny2(View<const T> Lv, View<
         static_for<0, k + 1>([&](auto J) {
             constexpr int j = decltype(J)::value;
             if constexpr (kh == 0) {
-                fma_bcast<G, kl>(y0[j], g0[j], lc0[k], false);  // rows >= 16 have l_kr = 0 for k < 16
+                fma_bcast16_guarded<kl>(y0[j], g0[j], lc0[k], false);  // rows >= 16 have l_kr = 0 for k < 16
             } else {
-                fma_bcast<G, kl>(y0[j], g1[j], lc0[k], false);
-                fma_bcast<G, kl>(y1[j], g1[j], lc1[k], false);
+                fma_bcast16_guarded<kl>(y0[j], g1[j], lc0[k], false);
+                fma_bcast16_guarded<kl>(y1[j], g1[j], lc1[k], false);
             }
         });
     });
@@ -353,10 +357,10 @@ __global__ __launch_bounds__(WAVE) void k_backward_tiny2(View<const T> Lv, View<
         static_for<0, N>([&](auto C) {
             constexpr int c = decltype(C)::value;
             if constexpr (kh == 0) {
-                fma_bcast<G, kl>(y0[c], y0[c], lc0[k], true);  // rows >= 16: lt[k] = 0 for k <= 16
+                fma_bcast16_guarded<kl>(y0[c], y0[c], lc0[k], true);  // rows >= 16: lt[k] = 0 for k <= 16
             } else {
-                fma_bcast<G, kl>(y0[c], y1[c], lc0[k], true);
-                fma_bcast<G, kl>(y1[c], y1[c], lc1[k], true);
+                fma_bcast16_guarded<kl>(y0[c], y1[c], lc0[k], true);
+                fma_bcast16_guarded<kl>(y1[c], y1[c], lc1[k], true);
             }
         });
     });
@@ -375,11 +379,11 @@ __global__ __launch_bounds__(WAVE) void k_backward_tiny2(View<const T> Lv, View<
         static_for<c + 1, N>([&](auto K) {
             constexpr int k = decltype(K)::value;
             if constexpr (ch == 0) {
-                fma_bcast<G, cl>(y0[c], lc0[k], y0[k], true);
-                fma_bcast<G, cl>(y1[c], lc0[k], y1[k], true);
+                fma_bcast16_guarded<cl>(y0[c], lc0[k], y0[k], true);
+                fma_bcast16_guarded<cl>(y1[c], lc0[k], y1[k], true);
             } else {
-                fma_bcast<G, cl>(y0[c], lc1[k], y0[k], true);
-                fma_bcast<G, cl>(y1[c], lc1[k], y1[k], true);
+                fma_bcast16_guarded<cl>(y0[c], lc1[k], y0[k], true);
+                fma_bcast16_guarded<cl>(y1[c], lc1[k], y1[k], true);
             }
         });
     });
@@ -463,8 +467,8 @@ la_status launch_backward_tiny(View<const T> L, View<const T> G, View<T> Abar, i
                            G, Abar, batch, n);
     } else {
         // 16 lanes per matrix, two rows per lane.  In fp64 the kernel needs 294 registers; the overflow lives in
-        // accumulation registers, which still beats 32 lanes per matrix with ds_bpermute broadcasts by 3.4 times
-        // (16384 matrices of n = 32: 357 -> 103 us).
+        // accumulation registers (hence the guarded broadcast multiply-adds), which still beats 32 lanes per
+        // matrix with ds_bpermute broadcasts by 2.5 times (16384 matrices of n = 32: 357 -> 140 us).
         hipLaunchKernelGGL((k_backward_tiny2<T>), dim3((unsigned)((batch + 3) / 4)), dim3(WAVE), 0, st, L, G, Abar,
                            batch, n);
     }
