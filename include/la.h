@@ -26,16 +26,22 @@
  *  - Return value: LA_OK, or LA_ERR_INVALID_ARG (null pointer with non-empty
  *    work, negative size, bad enum, forbidden aliasing), LA_ERR_UNSUPPORTED,
  *    LA_ERR_RUNTIME (a HIP call failed; see la_last_error()).
- *  - Small problems (potrf with n <= 64, backward with n <= 128 in fp32 and <= 96 in
- *    fp64, trsm with n <= 128 and at most 48 right-hand sides, syrk, gemm2, sumlogdiag,
- *    gp_glue, gp_criterion up to the same n as backward, kalman_filter) allocate
- *    nothing.  The blocked paths for larger n keep one scratch buffer per device
- *    (explicit inverses of the factor or of its diagonal blocks, a working copy of
- *    the triangle being factored or one work panel, at most 3*batch*n*n elements; and,
- *    for products with few output tiles and a long inner dimension, a buffer of partial
- *    results of at most 64 MB), allocated with
- *    hipMalloc on first use, grown on demand and kept until the process ends.
- *    Calls that use it must not overlap on different streams of one device.
+ *    LA_ERR_WORKSPACE: the call needs more scratch memory than it was given.
+ *  - The library allocates nothing and keeps no device memory or other state between
+ *    calls; it is re-entrant, and calls on different streams may overlap as long as
+ *    their workspaces differ.  Small problems (potrf with n <= 128, backward with
+ *    n <= 128 in fp32 and <= 96 in fp64, trsm with n <= 128 and at most 48 right-hand
+ *    sides, every operator with n <= 16, sumlogdiag, gp_glue, gp_criterion up to the same
+ *    n as backward, kalman_filter) need no scratch memory.  The blocked paths for larger
+ *    n do (explicit inverses of the factor or of its diagonal blocks, a working copy of
+ *    the triangle being factored or one work panel, partial results of products split
+ *    along a long inner dimension): la_workspace_bytes() says how many bytes a call
+ *    takes, and the caller passes that much device memory to the entry point's _ws form.
+ *    The plain form of an entry point is its _ws form without a workspace: it returns
+ *    LA_ERR_WORKSPACE (and launches nothing) when the call needs one.
+ *    A workspace is device memory, 256-byte aligned, disjoint from every operand; its
+ *    contents are undefined after the call; it may be reused by the next call on the
+ *    same stream and must not be shared by calls that may run at the same time.
  */
 #ifndef LA_MI355X_H
 #define LA_MI355X_H
@@ -47,8 +53,38 @@
 extern "C" {
 #endif
 
-typedef enum { LA_OK = 0, LA_ERR_INVALID_ARG = 1, LA_ERR_UNSUPPORTED = 2, LA_ERR_RUNTIME = 3 } la_status;
+typedef enum {
+    LA_OK = 0,
+    LA_ERR_INVALID_ARG = 1,
+    LA_ERR_UNSUPPORTED = 2,
+    LA_ERR_RUNTIME = 3,
+    LA_ERR_WORKSPACE = 4
+} la_status;
 typedef enum { LA_F32 = 0, LA_F64 = 1 } la_dtype;
+typedef enum {
+    LA_OP_POTRF = 0,
+    LA_OP_POTRF_BACKWARD = 1,
+    LA_OP_TRSM = 2,
+    LA_OP_TRMM = 3,
+    LA_OP_SYRK = 4,
+    LA_OP_GEMM2 = 5,
+    LA_OP_TRSM_BACKWARD = 6,
+    LA_OP_TRMM_BACKWARD = 7,
+    LA_OP_SYRK_BACKWARD = 8,
+    LA_OP_GEMM2_BACKWARD = 9,
+    LA_OP_POTRI = 10,
+    LA_OP_POTRI_BACKWARD = 11
+} la_op;
+
+/* Scratch memory, in bytes, that one call of operator `op` takes for these sizes (0: none).  The
+ * sizes carry the names they have in the operator's own signature: n for potrf, its backward,
+ * potri and its backward; n and m for trsm / trmm and their backward rules; n and k for syrk and
+ * its backward; m, n and k for gemm2 and its backward; the others are ignored.  The answer holds
+ * for every value of the operator's flags and alpha and for every aliasing it permits (the
+ * section 4.2 operators "need no extra memory" when built on vendor solvers; here the blocked
+ * paths trade scratch for work that runs on the matrix cores).  Host-only: no GPU call is made.
+ * Bad arguments give 0. */
+size_t la_workspace_bytes(la_op op, la_dtype dt, int64_t batch, int n, int m, int k);
 
 /* potrf forward (operator table row "potrf"; section 4.2): for each item,
  * L lower triangular with positive diagonal and A = L L^T (lower != 0), or R upper
@@ -60,6 +96,9 @@ typedef enum { LA_F32 = 0, LA_F64 = 1 } la_dtype;
  * that column on; the call still returns LA_OK). */
 la_status la_potrf_batched(la_dtype dt, int lower, int64_t batch, int n, const void *A, void *L,
                            int32_t *info, void *stream);
+la_status la_potrf_batched_ws(la_dtype dt, int lower, int64_t batch, int n, const void *A, void *L,
+                           int32_t *info, void *workspace,
+        size_t workspace_bytes, void *stream);
 
 /* potrf backward (section 4.2, backward of potrf; appendix "potrf"):
  *   Abar = 1/2 L^{-T} copyltu(L^T Lbar) L^{-1}                      (lower != 0)
@@ -71,6 +110,9 @@ la_status la_potrf_batched(la_dtype dt, int lower, int64_t batch, int n, const v
  * as Lbar ("Abar can overwrite Lbar"); it must not overlap L. */
 la_status la_potrf_backward(la_dtype dt, int lower, int64_t batch, int n, const void *L,
                             const void *Lbar, void *Abar, void *stream);
+la_status la_potrf_backward_ws(la_dtype dt, int lower, int64_t batch, int n, const void *L,
+                            const void *Lbar, void *Abar, void *workspace,
+        size_t workspace_bytes, void *stream);
 
 /* trsm (section 4.2 "trsm"): B = alpha * t(L)^{-1} A   (rightside == 0, A,B: [batch, n, m])
  *                            B = alpha * A t(L)^{-1}   (rightside != 0, A,B: [batch, m, n])
@@ -79,6 +121,10 @@ la_status la_potrf_backward(la_dtype dt, int lower, int64_t batch, int n, const 
 la_status la_trsm_batched(la_dtype dt, int lower, int trans, int rightside, double alpha,
                           int64_t batch, int n, int m, const void *L, const void *A, void *B,
                           void *stream);
+la_status la_trsm_batched_ws(la_dtype dt, int lower, int trans, int rightside, double alpha,
+                          int64_t batch, int n, int m, const void *L, const void *A, void *B,
+                          void *workspace,
+        size_t workspace_bytes, void *stream);
 
 /* trmm (section 4.2 "trmm"): B = alpha * t(L) A   (rightside == 0, A,B: [batch, n, m])
  *                            B = alpha * A t(L)   (rightside != 0, A,B: [batch, m, n])
@@ -86,6 +132,10 @@ la_status la_trsm_batched(la_dtype dt, int lower, int trans, int rightside, doub
 la_status la_trmm_batched(la_dtype dt, int lower, int trans, int rightside, double alpha,
                           int64_t batch, int n, int m, const void *L, const void *A, void *B,
                           void *stream);
+la_status la_trmm_batched_ws(la_dtype dt, int lower, int trans, int rightside, double alpha,
+                          int64_t batch, int n, int m, const void *L, const void *A, void *B,
+                          void *workspace,
+        size_t workspace_bytes, void *stream);
 
 /* trsm backward (section 4.2 "trsm", backward; appendix "trsm", also for an upper factor).
  * For the forward B = alpha t(L)^{-1} A (or alpha A t(L)^{-1}), with Y = t(L)^{-T} Bbar (or
@@ -101,6 +151,10 @@ la_status la_trmm_batched(la_dtype dt, int lower, int trans, int rightside, doub
 la_status la_trsm_backward(la_dtype dt, int lower, int trans, int rightside, double alpha, int64_t batch,
                            int n, int m, const void *L, const void *B, const void *Bbar, void *Abar,
                            void *Lbar, void *stream);
+la_status la_trsm_backward_ws(la_dtype dt, int lower, int trans, int rightside, double alpha, int64_t batch,
+                           int n, int m, const void *L, const void *B, const void *Bbar, void *Abar,
+                           void *Lbar, void *workspace,
+        size_t workspace_bytes, void *stream);
 
 /* trmm backward (section 4.2 "trmm", backward; appendix "trmm"): for the forward
  * B = alpha t(L) A (or alpha A t(L)):
@@ -111,6 +165,10 @@ la_status la_trsm_backward(la_dtype dt, int lower, int trans, int rightside, dou
 la_status la_trmm_backward(la_dtype dt, int lower, int trans, int rightside, double alpha, int64_t batch,
                            int n, int m, const void *L, const void *A, const void *Bbar, void *Abar,
                            void *Lbar, void *stream);
+la_status la_trmm_backward_ws(la_dtype dt, int lower, int trans, int rightside, double alpha, int64_t batch,
+                           int n, int m, const void *L, const void *A, const void *Bbar, void *Abar,
+                           void *Lbar, void *workspace,
+        size_t workspace_bytes, void *stream);
 
 /* syrk backward (section 4.2 "syrk", backward; Bbar need not be symmetric):
  *   B = alpha A A^T (trans == 0):  Abar = 2 alpha sym(Bbar) A = alpha (Bbar + Bbar^T) A
@@ -119,6 +177,9 @@ la_status la_trmm_backward(la_dtype dt, int lower, int trans, int rightside, dou
  * overlap A or Bbar. */
 la_status la_syrk_backward(la_dtype dt, int trans, double alpha, int64_t batch, int n, int k, const void *A,
                            const void *Bbar, void *Abar, void *stream);
+la_status la_syrk_backward_ws(la_dtype dt, int trans, double alpha, int64_t batch, int n, int k, const void *A,
+                           const void *Bbar, void *Abar, void *workspace,
+        size_t workspace_bytes, void *stream);
 
 /* syrk (section 4.2 "syrk"): B = alpha * A A^T  (trans == 0, A: [batch, n, k])
  *                            B = alpha * A^T A  (trans != 0, A: [batch, k, n])
@@ -126,6 +187,9 @@ la_status la_syrk_backward(la_dtype dt, int trans, double alpha, int64_t batch, 
  * overlap A. */
 la_status la_syrk_batched(la_dtype dt, int trans, double alpha, int64_t batch, int n, int k,
                           const void *A, void *B, void *stream);
+la_status la_syrk_batched_ws(la_dtype dt, int trans, double alpha, int64_t batch, int n, int k,
+                          const void *A, void *B, void *workspace,
+        size_t workspace_bytes, void *stream);
 
 /* gemm2 (section 4.2 "gemm2"): C = alpha * t_a(A) t_b(B), t_a(A): m x k, t_b(B): k x n.
  * A: [batch, m, k] (ta == 0) or [batch, k, m] (ta != 0); B: [batch, k, n] (tb == 0) or
@@ -133,6 +197,9 @@ la_status la_syrk_batched(la_dtype dt, int trans, double alpha, int64_t batch, i
  * in-place computation"). */
 la_status la_gemm2_batched(la_dtype dt, int ta, int tb, double alpha, int64_t batch, int m, int n, int k,
                            const void *A, const void *B, void *C, void *stream);
+la_status la_gemm2_batched_ws(la_dtype dt, int ta, int tb, double alpha, int64_t batch, int m, int n, int k,
+                           const void *A, const void *B, void *C, void *workspace,
+        size_t workspace_bytes, void *stream);
 
 /* gemm2 backward (section 4.2 "gemm2", backward): for C = alpha t_a(A) t_b(B),
  *   Abar = alpha Cbar t_b(B)^T  (ta == 0)  or  alpha t_b(B) Cbar^T  (ta != 0),
@@ -142,12 +209,18 @@ la_status la_gemm2_batched(la_dtype dt, int ta, int tb, double alpha, int64_t ba
 la_status la_gemm2_backward(la_dtype dt, int ta, int tb, double alpha, int64_t batch, int m, int n, int k,
                             const void *A, const void *B, const void *Cbar, void *Abar, void *Bbar,
                             void *stream);
+la_status la_gemm2_backward_ws(la_dtype dt, int ta, int tb, double alpha, int64_t batch, int m, int n, int k,
+                            const void *A, const void *B, const void *Cbar, void *Abar, void *Bbar,
+                            void *workspace,
+        size_t workspace_bytes, void *stream);
 
 /* potri (section 4.2 "potri"): B = A^{-1} from the Cholesky factor of A,
  *   A = L L^T (lower != 0)  or  A = R^T R (lower == 0).
  * L, B: [batch, n, n]; only the named triangle of the factor is read; B is written in full and is
  * exactly symmetric.  B may be the same buffer as L ("B can overwrite L"). */
 la_status la_potri(la_dtype dt, int lower, int64_t batch, int n, const void *L, void *B, void *stream);
+la_status la_potri_ws(la_dtype dt, int lower, int64_t batch, int n, const void *L, void *B, void *workspace,
+        size_t workspace_bytes, void *stream);
 
 /* potri backward (section 4.2 "potri", backward; appendix "potri"; Bbar need not be symmetric):
  *   Lbar = -2 tril(B sym(Bbar) L^{-T})   (lower != 0)
@@ -156,6 +229,9 @@ la_status la_potri(la_dtype dt, int lower, int64_t batch, int n, const void *L, 
  * other triangle) and must not overlap any input. */
 la_status la_potri_backward(la_dtype dt, int lower, int64_t batch, int n, const void *L, const void *B,
                             const void *Bbar, void *Lbar, void *stream);
+la_status la_potri_backward_ws(la_dtype dt, int lower, int64_t batch, int n, const void *L, const void *B,
+                            const void *Bbar, void *Lbar, void *workspace,
+        size_t workspace_bytes, void *stream);
 
 /* log|L| = sum_i log l_ii (section 3.1, identity below the GP criterion code).
  * L: [batch, n, n]; out: [batch] of dt.  Plain log, no abs: a non-positive
@@ -182,7 +258,7 @@ la_status la_gp_glue(la_dtype dt, int64_t batch, int n, const void *L, const voi
  * A, Abar: [batch, n, n]; y: [batch, n]; loss: [batch]; info: NULL or int32 [batch] as for potrf.
  * Abar may be the same buffer as A.  Up to n = 128 (fp32) / 96 (fp64) this is ONE kernel per call
  * and needs no workspace; beyond that it is the sequence la_potrf_batched, two la_trsm_batched,
- * la_gp_glue, la_potrf_backward on `workspace` (device memory, 16-byte aligned, at least
+ * la_gp_glue, la_potrf_backward on `workspace` (device memory, 256-byte aligned, at least
  * la_gp_workspace_bytes(dt, batch, n) bytes, not overlapping the other arguments). */
 size_t la_gp_workspace_bytes(la_dtype dt, int64_t batch, int n);
 la_status la_gp_criterion(la_dtype dt, int64_t batch, int n, const void *A, const void *y, void *loss, void *Abar,
@@ -195,9 +271,10 @@ la_status la_gp_criterion(la_dtype dt, int64_t batch, int n, const void *A, cons
  *         - (|B|_F^2 - sum Kff_diag) / (2 lam),            lam = noise_var > 0.
  * Device inputs: Kuu [U, U] (lower triangle read), Kuf [U, n], Kff_diag [n], y [n].  Device outputs:
  * phi [1], Kuu_bar [U, U] (symmetric: d phi = <Kuu_bar, dKuu> for symmetric dKuu), Kuf_bar [U, n],
- * Kff_diag_bar [n], y_bar [n], noise_bar [1].  workspace: device memory, 16-byte aligned, at least
- * la_sgp_workspace_bytes(dt, U, n) bytes; outputs and workspace must not overlap the inputs or each
- * other.  The blocked operators inside also use the library's own scratch buffer. */
+ * Kff_diag_bar [n], y_bar [n], noise_bar [1].  workspace: device memory, at least
+ * la_sgp_workspace_bytes(dt, U, n) bytes (intermediate results plus the scratch of the blocked
+ * operators inside), 256-byte aligned; outputs and workspace must not overlap the inputs or each
+ * other. */
 size_t la_sgp_workspace_bytes(la_dtype dt, int U, int n);
 la_status la_sgp_criterion(la_dtype dt, int U, int n, const void *Kuu, const void *Kuf, const void *Kff_diag,
                            const void *y, double noise_var, void *phi, void *Kuu_bar, void *Kuf_bar,

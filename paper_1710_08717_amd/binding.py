@@ -20,7 +20,14 @@ SYMBOLS = [
     "la_gemm2_backward", "la_potri", "la_potri_backward", "la_sgp_workspace_bytes", "la_sgp_criterion",
     "la_kalman_filter", "la_gp_workspace_bytes", "la_gp_criterion",
     "la_last_error", "la_version",
+    "la_workspace_bytes", "la_potrf_batched_ws", "la_potrf_backward_ws", "la_trsm_batched_ws", "la_trmm_batched_ws",
+    "la_syrk_batched_ws", "la_gemm2_batched_ws", "la_trsm_backward_ws", "la_trmm_backward_ws", "la_syrk_backward_ws",
+    "la_gemm2_backward_ws", "la_potri_ws", "la_potri_backward_ws",
 ]
+
+# la_op of include/la.h
+OP_POTRF, OP_POTRF_BACKWARD, OP_TRSM, OP_TRMM, OP_SYRK, OP_GEMM2 = 0, 1, 2, 3, 4, 5
+OP_TRSM_BACKWARD, OP_TRMM_BACKWARD, OP_SYRK_BACKWARD, OP_GEMM2_BACKWARD, OP_POTRI, OP_POTRI_BACKWARD = 6, 7, 8, 9, 10, 11
 
 
 class LaError(RuntimeError):
@@ -75,17 +82,26 @@ def load():
     lib.la_version.restype = i32
     for name in SYMBOLS[:7]:
         getattr(lib, name).restype = i32
+    lib.la_workspace_bytes.argtypes = [i32, i32, i64, i32, i32, i32]
+    lib.la_workspace_bytes.restype = ctypes.c_size_t
+    # the _ws form of an entry point: its arguments with (workspace, workspace_bytes) before the stream
+    for name in SYMBOLS:
+        if name.endswith("_ws"):
+            plain = getattr(lib, name[:-3])
+            f = getattr(lib, name)
+            f.argtypes = plain.argtypes[:-1] + [vp, ctypes.c_size_t, vp]
+            f.restype = i32
     _lib = lib
     return lib
 
 
-_STATUS = {1: "LA_ERR_INVALID_ARG", 2: "LA_ERR_UNSUPPORTED", 3: "LA_ERR_RUNTIME"}
+_STATUS = {1: "LA_ERR_INVALID_ARG", 2: "LA_ERR_UNSUPPORTED", 3: "LA_ERR_RUNTIME", 4: "LA_ERR_WORKSPACE"}
 
 
 def _check(rc, name):
     if rc != 0:
         msg = f"{name}: {_STATUS.get(rc, rc)}"
-        if rc == 3:
+        if rc in (3, 4):
             msg += f" ({load().la_last_error().decode()})"
         raise LaError(msg)
 
@@ -124,7 +140,32 @@ def _batch(t, trailing=2):
     return b
 
 
-def potrf(A, lower=True, out=None, info=None):
+_ws_sizes = {}
+
+
+def workspace_bytes(op, t, batch, n=0, m=0, k=0):
+    """la_workspace_bytes for tensors of t's dtype (the answers are remembered: they depend on the sizes only)."""
+    key = (op, t.dtype, batch, n, m, k)
+    need = _ws_sizes.get(key)
+    if need is None:
+        need = _ws_sizes[key] = int(load().la_workspace_bytes(op, _dt(t), batch, n, m, k))
+    return need
+
+
+def _ws(workspace, op, t, batch, n=0, m=0, k=0):
+    """(tensor, pointer, bytes) of the scratch memory of one call: the caller's uint8 device tensor, or, when the call
+    needs one and none was given, a fresh one from torch's allocator (stream-ordered on the current stream)."""
+    if workspace is not None:
+        assert workspace.dtype == torch.uint8 and workspace.is_cuda and workspace.is_contiguous()
+        return workspace, ctypes.c_void_p(workspace.data_ptr()), workspace.numel()
+    need = workspace_bytes(op, t, batch, n, m, k)
+    if need == 0:
+        return None, ctypes.c_void_p(0), 0
+    buf = torch.empty(need, dtype=torch.uint8, device=t.device)
+    return buf, ctypes.c_void_p(buf.data_ptr()), need  # the caller keeps buf until the call is enqueued
+
+
+def potrf(A, lower=True, out=None, info=None, workspace=None):
     """la_potrf_batched.  ``out`` may be ``A`` itself (in place).  ``info``: int32 [batch] or None."""
     _chk(A)
     n = A.shape[-1]
@@ -134,12 +175,13 @@ def potrf(A, lower=True, out=None, info=None):
     if info is not None:
         assert info.dtype == torch.int32 and info.is_cuda and info.numel() == _batch(A)
     with torch.cuda.device(A.device):
-        _check(load().la_potrf_batched(_dt(A), int(lower), _batch(A), n, _ptr(A), _ptr(L), _ptr(info), _stream(A)),
-               "la_potrf_batched")
+        keep, wp, wb = _ws(workspace, OP_POTRF, A, _batch(A), n)
+        _check(load().la_potrf_batched_ws(_dt(A), int(lower), _batch(A), n, _ptr(A), _ptr(L), _ptr(info), wp, wb,
+                                          _stream(A)), "la_potrf_batched_ws")
     return L
 
 
-def potrf_backward(L, Lbar, lower=True, out=None):
+def potrf_backward(L, Lbar, lower=True, out=None, workspace=None):
     """la_potrf_backward.  ``out`` may be ``Lbar`` itself."""
     _chk(L, Lbar)
     n = L.shape[-1]
@@ -147,12 +189,13 @@ def potrf_backward(L, Lbar, lower=True, out=None):
     Abar = torch.empty_like(Lbar) if out is None else out
     _chk(L, Abar)
     with torch.cuda.device(L.device):
-        _check(load().la_potrf_backward(_dt(L), int(lower), _batch(L), n, _ptr(L), _ptr(Lbar), _ptr(Abar), _stream(L)),
-               "la_potrf_backward")
+        keep, wp, wb = _ws(workspace, OP_POTRF_BACKWARD, L, _batch(L), n)
+        _check(load().la_potrf_backward_ws(_dt(L), int(lower), _batch(L), n, _ptr(L), _ptr(Lbar), _ptr(Abar), wp, wb,
+                                           _stream(L)), "la_potrf_backward_ws")
     return Abar
 
 
-def _tri(fn, name, L, A, lower, trans, rightside, alpha, out):
+def _tri(op, name, L, A, lower, trans, rightside, alpha, out, workspace):
     _chk(L, A)
     n = L.shape[-1]
     assert L.shape[-2] == n
@@ -162,20 +205,21 @@ def _tri(fn, name, L, A, lower, trans, rightside, alpha, out):
     B = torch.empty_like(A) if out is None else out
     _chk(A, B)
     with torch.cuda.device(L.device):
-        _check(fn(_dt(L), int(lower), int(trans), int(rightside), float(alpha), _batch(L), n, m, _ptr(L), _ptr(A),
-                  _ptr(B), _stream(L)), name)
+        keep, wp, wb = _ws(workspace, op, L, _batch(L), n, m)
+        _check(getattr(load(), name)(_dt(L), int(lower), int(trans), int(rightside), float(alpha), _batch(L), n, m,
+                                     _ptr(L), _ptr(A), _ptr(B), wp, wb, _stream(L)), name)
     return B
 
 
-def trsm(L, A, lower=True, trans=False, rightside=False, alpha=1.0, out=None):
-    return _tri(load().la_trsm_batched, "la_trsm_batched", L, A, lower, trans, rightside, alpha, out)
+def trsm(L, A, lower=True, trans=False, rightside=False, alpha=1.0, out=None, workspace=None):
+    return _tri(OP_TRSM, "la_trsm_batched_ws", L, A, lower, trans, rightside, alpha, out, workspace)
 
 
-def trmm(L, A, lower=True, trans=False, rightside=False, alpha=1.0, out=None):
-    return _tri(load().la_trmm_batched, "la_trmm_batched", L, A, lower, trans, rightside, alpha, out)
+def trmm(L, A, lower=True, trans=False, rightside=False, alpha=1.0, out=None, workspace=None):
+    return _tri(OP_TRMM, "la_trmm_batched_ws", L, A, lower, trans, rightside, alpha, out, workspace)
 
 
-def _tri_backward(fn, name, L, X, Bbar, lower, trans, rightside, alpha, out_a, out_l):
+def _tri_backward(op, name, L, X, Bbar, lower, trans, rightside, alpha, out_a, out_l, workspace):
     _chk(L, X)
     _chk(L, Bbar)
     n = L.shape[-1]
@@ -187,24 +231,27 @@ def _tri_backward(fn, name, L, X, Bbar, lower, trans, rightside, alpha, out_a, o
     _chk(L, Abar)
     _chk(L, Lbar)
     with torch.cuda.device(L.device):
-        _check(fn(_dt(L), int(lower), int(trans), int(rightside), float(alpha), _batch(L), n, m, _ptr(L), _ptr(X),
-                  _ptr(Bbar), _ptr(Abar), _ptr(Lbar), _stream(L)), name)
+        keep, wp, wb = _ws(workspace, op, L, _batch(L), n, m)
+        _check(getattr(load(), name)(_dt(L), int(lower), int(trans), int(rightside), float(alpha), _batch(L), n, m,
+                                     _ptr(L), _ptr(X), _ptr(Bbar), _ptr(Abar), _ptr(Lbar), wp, wb, _stream(L)), name)
     return Abar, Lbar
 
 
-def trsm_backward(L, B, Bbar, lower=True, trans=False, rightside=False, alpha=1.0, out_a=None, out_l=None):
+def trsm_backward(L, B, Bbar, lower=True, trans=False, rightside=False, alpha=1.0, out_a=None, out_l=None,
+                  workspace=None):
     """la_trsm_backward: (Abar, Lbar) from the forward OUTPUT B.  out_a may be Bbar, out_l may be L."""
-    return _tri_backward(load().la_trsm_backward, "la_trsm_backward", L, B, Bbar, lower, trans, rightside, alpha, out_a,
-                         out_l)
+    return _tri_backward(OP_TRSM_BACKWARD, "la_trsm_backward_ws", L, B, Bbar, lower, trans, rightside, alpha, out_a,
+                         out_l, workspace)
 
 
-def trmm_backward(L, A, Bbar, lower=True, trans=False, rightside=False, alpha=1.0, out_a=None, out_l=None):
+def trmm_backward(L, A, Bbar, lower=True, trans=False, rightside=False, alpha=1.0, out_a=None, out_l=None,
+                  workspace=None):
     """la_trmm_backward: (Abar, Lbar) from the forward INPUT A.  out_a may be Bbar."""
-    return _tri_backward(load().la_trmm_backward, "la_trmm_backward", L, A, Bbar, lower, trans, rightside, alpha, out_a,
-                         out_l)
+    return _tri_backward(OP_TRMM_BACKWARD, "la_trmm_backward_ws", L, A, Bbar, lower, trans, rightside, alpha, out_a,
+                         out_l, workspace)
 
 
-def syrk_backward(A, Bbar, trans=False, alpha=1.0, out=None):
+def syrk_backward(A, Bbar, trans=False, alpha=1.0, out=None, workspace=None):
     """la_syrk_backward: Abar = alpha (Bbar + Bbar^T) A  or  alpha A (Bbar + Bbar^T)."""
     _chk(A, Bbar)
     n, k = (A.shape[-1], A.shape[-2]) if trans else (A.shape[-2], A.shape[-1])
@@ -212,12 +259,13 @@ def syrk_backward(A, Bbar, trans=False, alpha=1.0, out=None):
     Abar = torch.empty_like(A) if out is None else out
     _chk(A, Abar)
     with torch.cuda.device(A.device):
-        _check(load().la_syrk_backward(_dt(A), int(trans), float(alpha), _batch(A), n, k, _ptr(A), _ptr(Bbar),
-                                       _ptr(Abar), _stream(A)), "la_syrk_backward")
+        keep, wp, wb = _ws(workspace, OP_SYRK_BACKWARD, A, _batch(A), n, 0, k)
+        _check(load().la_syrk_backward_ws(_dt(A), int(trans), float(alpha), _batch(A), n, k, _ptr(A), _ptr(Bbar),
+                                          _ptr(Abar), wp, wb, _stream(A)), "la_syrk_backward_ws")
     return Abar
 
 
-def gemm2_backward(A, B, Cbar, ta=False, tb=False, alpha=1.0):
+def gemm2_backward(A, B, Cbar, ta=False, tb=False, alpha=1.0, workspace=None):
     """la_gemm2_backward: (Abar, Bbar) of C = alpha t_a(A) t_b(B)."""
     _chk(A, B)
     _chk(A, Cbar)
@@ -226,12 +274,14 @@ def gemm2_backward(A, B, Cbar, ta=False, tb=False, alpha=1.0):
     assert Cbar.shape[-2:] == (m, n) and _batch(A) == _batch(B) == _batch(Cbar)
     Abar, Bbar = torch.empty_like(A), torch.empty_like(B)
     with torch.cuda.device(A.device):
-        _check(load().la_gemm2_backward(_dt(A), int(ta), int(tb), float(alpha), _batch(A), m, n, k, _ptr(A), _ptr(B),
-                                        _ptr(Cbar), _ptr(Abar), _ptr(Bbar), _stream(A)), "la_gemm2_backward")
+        keep, wp, wb = _ws(workspace, OP_GEMM2_BACKWARD, A, _batch(A), n, m, k)
+        _check(load().la_gemm2_backward_ws(_dt(A), int(ta), int(tb), float(alpha), _batch(A), m, n, k, _ptr(A), _ptr(B),
+                                           _ptr(Cbar), _ptr(Abar), _ptr(Bbar), wp, wb, _stream(A)),
+               "la_gemm2_backward_ws")
     return Abar, Bbar
 
 
-def potri(L, lower=True, out=None):
+def potri(L, lower=True, out=None, workspace=None):
     """la_potri: A^-1 from the Cholesky factor of A.  ``out`` may be ``L`` itself."""
     _chk(L)
     n = L.shape[-1]
@@ -239,11 +289,12 @@ def potri(L, lower=True, out=None):
     B = torch.empty_like(L) if out is None else out
     _chk(L, B)
     with torch.cuda.device(L.device):
-        _check(load().la_potri(_dt(L), int(lower), _batch(L), n, _ptr(L), _ptr(B), _stream(L)), "la_potri")
+        keep, wp, wb = _ws(workspace, OP_POTRI, L, _batch(L), n)
+        _check(load().la_potri_ws(_dt(L), int(lower), _batch(L), n, _ptr(L), _ptr(B), wp, wb, _stream(L)), "la_potri_ws")
     return B
 
 
-def potri_backward(L, B, Bbar, lower=True, out=None):
+def potri_backward(L, B, Bbar, lower=True, out=None, workspace=None):
     """la_potri_backward: gradient of the factor from B = A^-1 and Bbar."""
     _chk(L, B)
     _chk(L, Bbar)
@@ -252,8 +303,9 @@ def potri_backward(L, B, Bbar, lower=True, out=None):
     Lbar = torch.empty_like(L) if out is None else out
     _chk(L, Lbar)
     with torch.cuda.device(L.device):
-        _check(load().la_potri_backward(_dt(L), int(lower), _batch(L), n, _ptr(L), _ptr(B), _ptr(Bbar), _ptr(Lbar),
-                                        _stream(L)), "la_potri_backward")
+        keep, wp, wb = _ws(workspace, OP_POTRI_BACKWARD, L, _batch(L), n)
+        _check(load().la_potri_backward_ws(_dt(L), int(lower), _batch(L), n, _ptr(L), _ptr(B), _ptr(Bbar), _ptr(Lbar),
+                                           wp, wb, _stream(L)), "la_potri_backward_ws")
     return Lbar
 
 
@@ -325,18 +377,19 @@ def kalman_filter(A, B, Sh, Sv, mu0, S0, v, want_states=True, info=None):
     return nll, f, F
 
 
-def syrk(A, trans=False, alpha=1.0, out=None):
+def syrk(A, trans=False, alpha=1.0, out=None, workspace=None):
     _chk(A)
     n, k = (A.shape[-1], A.shape[-2]) if trans else (A.shape[-2], A.shape[-1])
     B = torch.empty(A.shape[:-2] + (n, n), dtype=A.dtype, device=A.device) if out is None else out
     _chk(A, B)
     with torch.cuda.device(A.device):
-        _check(load().la_syrk_batched(_dt(A), int(trans), float(alpha), _batch(A), n, k, _ptr(A), _ptr(B), _stream(A)),
-               "la_syrk_batched")
+        keep, wp, wb = _ws(workspace, OP_SYRK, A, _batch(A), n, 0, k)
+        _check(load().la_syrk_batched_ws(_dt(A), int(trans), float(alpha), _batch(A), n, k, _ptr(A), _ptr(B), wp, wb,
+                                         _stream(A)), "la_syrk_batched_ws")
     return B
 
 
-def gemm2(A, B, ta=False, tb=False, alpha=1.0, out=None):
+def gemm2(A, B, ta=False, tb=False, alpha=1.0, out=None, workspace=None):
     """la_gemm2_batched: C = alpha * t_a(A) t_b(B)."""
     _chk(A, B)
     m, k = (A.shape[-1], A.shape[-2]) if ta else (A.shape[-2], A.shape[-1])
@@ -345,8 +398,9 @@ def gemm2(A, B, ta=False, tb=False, alpha=1.0, out=None):
     C = torch.empty(A.shape[:-2] + (m, n), dtype=A.dtype, device=A.device) if out is None else out
     _chk(A, C)
     with torch.cuda.device(A.device):
-        _check(load().la_gemm2_batched(_dt(A), int(ta), int(tb), float(alpha), _batch(A), m, n, k, _ptr(A), _ptr(B),
-                                       _ptr(C), _stream(A)), "la_gemm2_batched")
+        keep, wp, wb = _ws(workspace, OP_GEMM2, A, _batch(A), n, m, k)
+        _check(load().la_gemm2_batched_ws(_dt(A), int(ta), int(tb), float(alpha), _batch(A), m, n, k, _ptr(A), _ptr(B),
+                                          _ptr(C), wp, wb, _stream(A)), "la_gemm2_batched_ws")
     return C
 
 

@@ -50,8 +50,49 @@ void set_error(hipError_t e, const char *where);
             return s__;             \
     } while (0)
 
+// ---------------------------------------------------------------------------------
+// Scratch memory of one call.  The library owns no device memory: whatever a blocked path needs
+// beyond its inputs and outputs (explicit inverses, working copies, partial results of products
+// split along K) is carved out of the workspace the caller passed to that call, by a bump
+// allocator that lives on the calling thread for the duration of the call.  A function that
+// takes memory opens an ArenaFrame; what it took is handed back when the frame ends, so
+// consecutive steps reuse the same bytes (the work is ordered by the stream).
+// In a SIZING pass (dry) nothing is launched and no HIP call is made: the host code of the
+// operator runs as usual and the arena only records the most it was asked for.
+// ---------------------------------------------------------------------------------
+struct Arena {
+    char *base = nullptr;
+    size_t cap = 0, used = 0, peak = 0;
+    bool dry = false;
+};
+Arena *&current_arena();
+inline bool dry_run()
+{
+    const Arena *a = current_arena();
+    return a && a->dry;
+}
+// `bytes` of scratch (256-byte aligned) from the current call's workspace; LA_ERR_WORKSPACE if it is too small
+la_status arena_take(size_t bytes, void **out);
+struct ArenaFrame {
+    size_t mark;
+    ArenaFrame() : mark(current_arena() ? current_arena()->used : 0) {}
+    ~ArenaFrame()
+    {
+        if (current_arena())
+            current_arena()->used = mark;
+    }
+};
+// every kernel launch of the library goes through here: a sizing pass launches nothing
+#define LA_LAUNCH(...)                      \
+    do {                                    \
+        if (!::la::dry_run())               \
+            hipLaunchKernelGGL(__VA_ARGS__); \
+    } while (0)
+
 inline la_status launch_check(const char *where)
 {
+    if (dry_run())
+        return LA_OK;
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) {
         set_error(e, where);
@@ -390,7 +431,8 @@ la_status launch_potrf_tiny(View<const T> A, View<T> L, int32_t *info, int info_
 // potrf of blocks of edge nb <= 128 together with the inverse of the factor, one workgroup per
 // block: writes the factor's lower triangle (zeros above the diagonal inside the 16 x 16
 // diagonal tiles; nothing else above it is written unless zero_upper, which zeroes all of L
-// above the diagonal) and the lower triangle of its inverse.  A may alias L.
+// above the diagonal) and the lower triangle of its inverse (not stored when Inv.p is null).
+// A may alias L.
 // info (may be null): set to info_off + failing column (1-based) where it is still 0.
 template <typename T>
 la_status launch_potrf_leaf16(View<const T> A, View<T> L, View<T> Inv, int32_t *info, int info_off, int64_t batch,

@@ -42,7 +42,7 @@ la_status launch_copy(View<const T> src, View<T> dst, int64_t batch, int rows, i
     const int64_t blocks = (int64_t)tr * tc * batch;
     if (blocks > 0x7fffffffll)
         return LA_ERR_UNSUPPORTED;
-    hipLaunchKernelGGL((k_copy<T>), dim3((unsigned)blocks), dim3(256), 0, st, src, dst, batch, rows, cols, alpha, keep,
+    LA_LAUNCH((k_copy<T>), dim3((unsigned)blocks), dim3(256), 0, st, src, dst, batch, rows, cols, alpha, keep,
                        tr, tc);
     return launch_check("copy");
 }
@@ -82,7 +82,7 @@ la_status launch_tril_split(View<const T> src, View<T> work, View<T> out, int64_
     const int64_t blocks = (int64_t)nt * nt * batch;
     if (blocks > 0x7fffffffll)
         return LA_ERR_UNSUPPORTED;
-    hipLaunchKernelGGL((k_tril_split<T>), dim3((unsigned)blocks), dim3(256), 0, st, src, work, out, batch, n, nt);
+    LA_LAUNCH((k_tril_split<T>), dim3((unsigned)blocks), dim3(256), 0, st, src, work, out, batch, n, nt);
     return launch_check("tril_split");
 }
 
@@ -115,7 +115,7 @@ la_status launch_zero_strict_upper(View<T> X, int64_t batch, int n, hipStream_t 
     const int64_t blocks = (int64_t)nt * nt * batch;
     if (blocks > 0x7fffffffll)
         return LA_ERR_UNSUPPORTED;
-    hipLaunchKernelGGL((k_zero_strict_upper<T>), dim3((unsigned)blocks), dim3(256), 0, st, X, batch, n, nt);
+    LA_LAUNCH((k_zero_strict_upper<T>), dim3((unsigned)blocks), dim3(256), 0, st, X, batch, n, nt);
     return launch_check("zero_strict_upper");
 }
 
@@ -189,7 +189,7 @@ static la_status launch_sym(View<T> X, int64_t batch, int n, T scale, int mode, 
     const int64_t blocks = (int64_t)nt * nt * batch;
     if (blocks > 0x7fffffffll)
         return LA_ERR_UNSUPPORTED;
-    hipLaunchKernelGGL((k_sym<T>), dim3((unsigned)blocks), dim3(256), 0, st, X, batch, n, scale, mode, nt);
+    LA_LAUNCH((k_sym<T>), dim3((unsigned)blocks), dim3(256), 0, st, X, batch, n, scale, mode, nt);
     return launch_check("sym");
 }
 template <typename T>
@@ -250,10 +250,10 @@ la_status launch_sumlogdiag(const T *L, T *out, int64_t batch, int n, hipStream_
         const int64_t blocks = (batch * G + 255) / 256;
         if (blocks > 0x7fffffffll)
             return LA_ERR_UNSUPPORTED;
-        hipLaunchKernelGGL((k_sumlogdiag_small<T>), dim3((unsigned)blocks), dim3(256), 0, st, L, out, batch, n, G);
+        LA_LAUNCH((k_sumlogdiag_small<T>), dim3((unsigned)blocks), dim3(256), 0, st, L, out, batch, n, G);
         return launch_check("sumlogdiag_small");
     }
-    hipLaunchKernelGGL((k_sumlogdiag<T>), dim3((unsigned)batch), dim3(WAVE), 0, st, L, out, batch, n);
+    LA_LAUNCH((k_sumlogdiag<T>), dim3((unsigned)batch), dim3(WAVE), 0, st, L, out, batch, n);
     return launch_check("sumlogdiag");
 }
 
@@ -313,7 +313,7 @@ la_status launch_gp_glue(const T *L, const T *y, const T *z, const T *alpha, T *
     const int chunks = n > 0 ? (n + GLUE_ROWS - 1) / GLUE_ROWS : 1;
     if (batch * chunks > 0x7fffffffll)
         return LA_ERR_UNSUPPORTED;
-    hipLaunchKernelGGL((k_gp_glue<T>), dim3((unsigned)(batch * chunks)), dim3(GLUE_THREADS), 0, st, L, y, z, alpha, loss,
+    LA_LAUNCH((k_gp_glue<T>), dim3((unsigned)(batch * chunks)), dim3(GLUE_THREADS), 0, st, L, y, z, alpha, loss,
                        Lbar, batch, n, chunks);
     return launch_check("gp_glue");
 }
@@ -358,7 +358,7 @@ template <typename T>
 la_status launch_partial_sums(int kind, const T *a, const T *b, int64_t count, int64_t ld, double *partial,
                               hipStream_t st)
 {
-    hipLaunchKernelGGL((k_partial_sums<T>), dim3(RED_BLOCKS), dim3(256), 0, st, kind, a, b, count, ld, partial);
+    LA_LAUNCH((k_partial_sums<T>), dim3(RED_BLOCKS), dim3(256), 0, st, kind, a, b, count, ld, partial);
     return launch_check("partial_sums");
 }
 
@@ -373,7 +373,7 @@ __global__ void k_add_diag(T *A, int n, T v)
 template <typename T>
 la_status launch_add_diag(T *A, int n, T v, hipStream_t st)
 {
-    hipLaunchKernelGGL((k_add_diag<T>), dim3((n + 255) / 256), dim3(256), 0, st, A, n, v);
+    LA_LAUNCH((k_add_diag<T>), dim3((n + 255) / 256), dim3(256), 0, st, A, n, v);
     return launch_check("add_diag");
 }
 
@@ -390,7 +390,7 @@ template <typename T>
 la_status launch_rank1_add(T *C, const T *u, const T *v, int rows, int cols, hipStream_t st)
 {
     const int64_t total = (int64_t)rows * cols;
-    hipLaunchKernelGGL((k_rank1_add<T>), dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, C, u, v, rows, cols);
+    LA_LAUNCH((k_rank1_add<T>), dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, C, u, v, rows, cols);
     return launch_check("rank1_add");
 }
 
@@ -426,7 +426,7 @@ la_status launch_sgp_scalars(int stage, const double *sums, double lam, int n, T
                              hipStream_t st)
 {
     const int blocks = stage == 0 ? 1 : (nk + 255) / 256;
-    hipLaunchKernelGGL((k_sgp_scalars<T>), dim3(blocks > 0 ? blocks : 1), dim3(256), 0, st, stage, sums, lam, n, phi,
+    LA_LAUNCH((k_sgp_scalars<T>), dim3(blocks > 0 ? blocks : 1), dim3(256), 0, st, stage, sums, lam, n, phi,
                        noise_bar, kff_bar, nk);
     return launch_check("sgp_scalars");
 }
@@ -442,7 +442,7 @@ la_status launch_fill_i32(int32_t *p, int64_t count, int32_t v, hipStream_t st)
 {
     if (count <= 0)
         return LA_OK;
-    hipLaunchKernelGGL(k_fill_i32, dim3((unsigned)((count + 255) / 256)), dim3(256), 0, st, p, count, v);
+    LA_LAUNCH(k_fill_i32, dim3((unsigned)((count + 255) / 256)), dim3(256), 0, st, p, count, v);
     return launch_check("fill");
 }
 

@@ -19,8 +19,6 @@
 //    and K a multiple of 16.
 //  * k_gemm: element-wise staged fallback for everything else (ragged / unaligned shapes).
 #include <algorithm>
-#include <mutex>
-#include <vector>
 
 #include "common.hpp"
 
@@ -604,7 +602,7 @@ static la_status launch_gemv(View<const T> A, View<const T> B, View<T> C, int64_
     const int64_t blocks = (int64_t)tiles * batch;
     if (blocks > 0x7fffffffll)
         return LA_ERR_UNSUPPORTED;
-    hipLaunchKernelGGL((k_gemv<T>), dim3((unsigned)blocks), dim3(GEMV_THREADS), 0, st, A, B, C, batch, M, N, K, alpha, beta, triA,
+    LA_LAUNCH((k_gemv<T>), dim3((unsigned)blocks), dim3(GEMV_THREADS), 0, st, A, B, C, batch, M, N, K, alpha, beta, triA,
                        tiles);
     return launch_check("gemv");
 }
@@ -613,33 +611,10 @@ static la_status launch_gemv(View<const T> A, View<const T> B, View<T> C, int64_
 // Split along K for products with few output tiles and a long K (A^T A of a tall A, the syrk of a
 // wide panel): the K range is cut into slices that run as extra batch items into a buffer of
 // partial results, which a second kernel sums in a fixed order (no atomics: results are
-// reproducible) while applying alpha, beta and the output mask.  The buffer belongs to the
-// library, one per device, grown on demand and never freed while work may still use it.
+// reproducible) while applying alpha, beta and the output mask.  The buffer comes out of the
+// calling operator's workspace (at most SPLITK_MAX_BYTES of it).
 // ---------------------------------------------------------------------------------------
-static std::mutex g_splitk_mutex;
-static void *g_splitk_buf[64] = {};
-static size_t g_splitk_bytes[64] = {};
-static std::vector<void *> g_splitk_parked;
 constexpr size_t SPLITK_MAX_BYTES = (size_t)64 << 20;
-
-static la_status splitk_buffer(size_t bytes, void **out)
-{
-    int dev = 0;
-    LA_HIP(hipGetDevice(&dev));
-    if (dev < 0 || dev >= 64)
-        return LA_ERR_UNSUPPORTED;
-    std::lock_guard<std::mutex> lock(g_splitk_mutex);
-    if (g_splitk_bytes[dev] < bytes) {
-        void *np = nullptr;
-        LA_HIP(hipMalloc(&np, bytes));
-        if (g_splitk_buf[dev])
-            g_splitk_parked.push_back(g_splitk_buf[dev]);
-        g_splitk_buf[dev] = np;
-        g_splitk_bytes[dev] = bytes;
-    }
-    *out = g_splitk_buf[dev];
-    return LA_OK;
-}
 
 template <typename T>
 __global__ __launch_bounds__(256) void k_splitk_reduce(const T *partial, View<T> C, int64_t batch, int M, int N,
@@ -694,7 +669,7 @@ static void launch_fast(bool akf, bool bkf, View<const T> A, View<const T> B, Vi
     const int64_t wgs = o.xcd_batch ? 8 * ((batch + 7) / 8) * per : per * batch;
     const dim3 grid((unsigned)wgs), block(256);
 #define LA_GO(AK, BKF_)                                                                                              \
-    hipLaunchKernelGGL((k_gemm_fast<T, BM, BN, BK, NBUF, AK, BKF_>), grid, block, 0, st, A, B, C, batch, M, N, K,    \
+    LA_LAUNCH((k_gemm_fast<T, BM, BN, BK, NBUF, AK, BKF_>), grid, block, 0, st, A, B, C, batch, M, N, K,    \
                        alpha, beta, o, tiles_m, tiles_n)
     if (akf && bkf)
         LA_GO(true, true);
@@ -758,8 +733,9 @@ la_status launch_gemm(View<const T> A, View<const T> B, View<T> C, int64_t batch
             splits = (K + Kc - 1) / Kc;
             const size_t bytes = (size_t)batch * splits * M * N * sizeof(T);
             if (splits >= 2 && bytes <= SPLITK_MAX_BYTES) {
+                ArenaFrame frame;
                 void *buf = nullptr;
-                LA_TRY(splitk_buffer(bytes, &buf));
+                LA_TRY(arena_take(bytes, &buf));
                 const int64_t mn = (int64_t)M * N;
                 View<const T> As = A.level2((int64_t)Kc * A.cs, splits), Bs = B.level2((int64_t)Kc * B.rs, splits);
                 View<T> Ps{(T *)buf, (int64_t)splits * mn, N, 1, mn, splits};
@@ -770,7 +746,7 @@ la_status launch_gemm(View<const T> A, View<const T> B, View<T> C, int64_t batch
                 launch_fast<T, 64, 64, 16, 2>(akf, bkf, As, Bs, Ps, batch * splits, M, N, Kc, T(1), T(0), ps, st);
                 LA_TRY(launch_check("gemm_splitk"));
                 const int64_t total = batch * mn;
-                hipLaunchKernelGGL((k_splitk_reduce<T>), dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st,
+                LA_LAUNCH((k_splitk_reduce<T>), dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st,
                                    (const T *)buf, C, batch, M, N, splits, alpha, beta, o);
                 return launch_check("splitk_reduce");
             }
@@ -828,7 +804,7 @@ la_status launch_gemm(View<const T> A, View<const T> B, View<T> C, int64_t batch
     const int64_t blocks = tile_count(o.order, tiles_m, tiles_n) * batch;
     if (blocks > 0x7fffffffll)
         return LA_ERR_UNSUPPORTED;
-    hipLaunchKernelGGL((k_gemm<T, BM, BN, BK>), dim3((unsigned)blocks), dim3(256), 0, st, A, B, C, batch, M, N, K,
+    LA_LAUNCH((k_gemm<T, BM, BN, BK>), dim3((unsigned)blocks), dim3(256), 0, st, A, B, C, batch, M, N, K,
                        alpha, beta, o, tiles_m, tiles_n);
     return launch_check("gemm");
 }

@@ -367,7 +367,7 @@ static la_status launch_kalman_d(const KfArgs<T> &a, hipStream_t st)
     if (blocks > 0x7fffffffll)
         return LA_ERR_UNSUPPORTED;
     const size_t lds = a.shared ? Lds::BYTES / Lds::GROUPS : Lds::BYTES;
-    hipLaunchKernelGGL((k_kalman<T, D>), dim3((unsigned)blocks), dim3(64), lds, st, a);
+    LA_LAUNCH((k_kalman<T, D>), dim3((unsigned)blocks), dim3(64), lds, st, a);
     return launch_check("kalman");
 }
 

@@ -5,15 +5,16 @@
 // 1710.08717, "potrf", last paragraph, and the R variants of trsm / trmm) is the transposed
 // view of the same memory, so no data is ever transposed or copied for it.
 //
-// potrf / backward of small matrices are single register-resident kernels.  Everything else is
-// split recursively in halves (multiples of 64) down to 64 x 64 diagonal blocks; all the work
-// is GEMMs on the matrix cores: off-diagonal updates, products with (masked) diagonal blocks,
-// and solves as products with the diagonal blocks' inverses, which one kernel launch computes
-// for the whole batch up front.
+// potrf / backward of small matrices are single register-resident kernels, blocks of up to 128
+// rows one-workgroup kernels that keep the block in LDS.  Everything larger is host code over
+// those and GEMMs on the matrix cores: off-diagonal updates, products with (masked) triangular
+// blocks, and solves as products with explicit inverses of diagonal blocks (128 x 128 blocks by
+// one launch for the whole batch, merged level by level where larger ones are wanted).
+// The library owns no device memory: scratch comes out of the workspace the caller passes to the
+// _ws form of an entry point (la_workspace_bytes says how much a call takes).
 #include <cstdio>
 #include <cstring>
 #include <mutex>
-#include <vector>
 
 #include "common.hpp"
 
@@ -27,39 +28,27 @@ void set_error(hipError_t e, const char *where)
 }
 
 // ---------------------------------------------------------------------------------
-// Scratch memory of the blocked paths (n > 64 for potrf / trsm, n > 128 (fp64: 96) for the backward
-// pass): inverses of (diagonal blocks of) the triangular factor, a work matrix and a temporary of
-// the inverse merges, at most 3 * batch * n * n elements.  One buffer per device, grown on demand with hipMalloc and kept
-// until the process ends; a buffer that is outgrown is parked, not freed, because work queued
-// on a stream may still be using it.  Calls that use it must therefore not run concurrently
-// on several streams of one device.
+// Scratch memory (see common.hpp): the arena of the call that is running on this thread.
 // ---------------------------------------------------------------------------------
-struct Scratch {
-    void *p = nullptr;
-    size_t bytes = 0;
-};
-static std::mutex g_ws_mutex;
-static std::vector<Scratch> g_ws(64);
-static std::vector<void *> g_parked;
-
-static la_status scratch_get(size_t bytes, void **out)
+Arena *&current_arena()
 {
-    int dev = 0;
-    LA_HIP(hipGetDevice(&dev));
-    std::lock_guard<std::mutex> lock(g_ws_mutex);
-    if (dev < 0 || dev >= (int)g_ws.size())
-        return LA_ERR_UNSUPPORTED;
-    Scratch &s = g_ws[dev];
-    if (s.bytes < bytes) {
-        size_t want = bytes + bytes / 4;
-        void *np = nullptr;
-        LA_HIP(hipMalloc(&np, want));
-        if (s.p)
-            g_parked.push_back(s.p);
-        s.p = np;
-        s.bytes = want;
+    static thread_local Arena *a = nullptr;
+    return a;
+}
+
+la_status arena_take(size_t bytes, void **out)
+{
+    Arena *a = current_arena();
+    const size_t need = (bytes + 255) & ~(size_t)255;
+    if (!a || (!a->dry && a->used + need > a->cap)) {
+        snprintf(g_err, sizeof(g_err), "workspace too small: %zu more bytes wanted at offset %zu of %zu", need,
+                 a ? a->used : (size_t)0, a ? a->cap : (size_t)0);
+        return LA_ERR_WORKSPACE;
     }
-    *out = s.p;
+    *out = a->base + a->used;
+    a->used += need;
+    if (a->used > a->peak)
+        a->peak = a->used;
     return LA_OK;
 }
 
@@ -69,7 +58,7 @@ static la_status scratch_views(int64_t batch, int n, int count, View<T> *out)
     // `count` row-major n x n matrices per batch item, each batch-contiguous
     const int64_t nn = (int64_t)n * n;
     void *p = nullptr;
-    LA_TRY(scratch_get((size_t)count * batch * nn * sizeof(T), &p));
+    LA_TRY(arena_take((size_t)count * batch * nn * sizeof(T), &p));
     for (int c = 0; c < count; ++c)
         out[c] = View<T>{(T *)p + (int64_t)c * batch * nn, nn, n, 1};
     return LA_OK;
@@ -287,6 +276,7 @@ static la_status backward_impl(View<const T> Lam, View<const T> G, View<T> W, in
         return launch_backward_tiny<T>(Lam, G, W, batch, n, st);
     if (n <= backward_leaf16_max_n<T>())  // one workgroup per matrix, everything in LDS, no scratch
         return launch_backward_leaf16<T>(Lam, G, W, batch, n, st);
+    ArenaFrame frame;
     View<T> sc[2];
     LA_TRY(scratch_views<T>(batch, n, 2, sc));
     View<T> Li = sc[0], X = sc[1];
@@ -399,13 +389,17 @@ static la_status potrf_t(int lower, int64_t batch, int n, const void *A, void *L
         LA_TRY(launch_fill_i32(info, batch, 0, st));
     if (n <= NB)
         return launch_potrf_tiny<T>(Av, Lv, info, 0, batch, n, st);
-    if (n <= 2 * NB) {  // one leaf: it reads A and writes L directly
-        View<T> Inv;
-        LA_TRY(scratch_views<T>(batch, n, 1, &Inv));
-        return launch_potrf_leaf16<T>(Av, Lv, Inv, info, 0, batch, n, true, st);
-    }
-    View<T> sc[3];  // inverses of the diagonal blocks; working copy of the lower triangle of A; merge temporary
-    LA_TRY(scratch_views<T>(batch, n, 3, sc));
+    if (n <= 2 * NB)  // one leaf: it reads A and writes L directly; nobody wants the inverse
+        return launch_potrf_leaf16<T>(Av, Lv, View<T>{nullptr, 0, 0, 0}, info, 0, batch, n, true, st);
+    ArenaFrame frame;
+    // inverses of the diagonal blocks; working copy of the lower triangle of A; temporary of the inverse merges
+    // (not needed where the whole matrix is factored panel by panel without merged inverses)
+    const bool outer_panels = (batch == 1 && n >= 4096) || n >= 8192;
+    const bool merges = outer_panels || !(n <= 2304 && (double)batch * n * n < 24e6);
+    View<T> sc[3];
+    LA_TRY(scratch_views<T>(batch, n, merges ? 3 : 2, sc));
+    if (!merges)
+        sc[2] = sc[1];  // never used
     LA_TRY(launch_tril_split<T>(Av, sc[1], Lv, batch, n, st));  // zeros above the diagonal of L
     // Large matrices: right-looking over panels of 2048 columns -- the panel's diagonal block by the
     // recursion below (which factors it 128 columns at a time and merges its inverse), one product
@@ -414,7 +408,7 @@ static la_status potrf_t(int lower, int64_t batch, int n, const void *A, void *L
     // 19.7 -> 17.3, 6144 4.5 -> 4.1 (fp64; other panel widths from 1024 to 4096 are slower).  Below
     // n = 4096, and for several matrices of that size, the halving is faster (3000: 1.36 against 1.39 ms).
     constexpr int outer = 2048;
-    if ((batch == 1 && n >= 4096) || n >= 8192) {
+    if (outer_panels) {
         View<T> Wk = sc[1], Inv = sc[0];
         for (int o = 0; o < n; o += outer) {
             const int w = n - o < outer ? n - o : outer, r = n - o - w;
@@ -466,6 +460,7 @@ static la_status tri_apply_v(bool solve, bool fwd, T alpha, int64_t batch, int n
     if (solve && n <= 128 && m <= 48)  // small: one workgroup per item does the whole substitution, no scratch
         return launch_trsm_leaf16<T>(Lam, Xin, X, batch, n, m, alpha, fwd, st);
 
+    ArenaFrame frame;
     if (solve && n <= NB) {  // inverse of the single block, then one product in place
         if (!inplace || alpha != T(1))
             LA_TRY(launch_copy<T>(Xin, X, batch, n, m, alpha, 0, st));
@@ -481,7 +476,7 @@ static la_status tri_apply_v(bool solve, bool fwd, T alpha, int64_t batch, int n
     // scratch: [inverse n*n] [merge temporary n*n] (solve only), then a panel shaped like X
     void *sp = nullptr;
     const size_t per_item = (solve ? 2 * (size_t)nn : 0) + (size_t)nm;
-    LA_TRY(scratch_get(per_item * batch * sizeof(T), &sp));
+    LA_TRY(arena_take(per_item * batch * sizeof(T), &sp));
     T *base = (T *)sp;
     View<T> Inv{base, nn, n, 1}, Tmp{base + (solve ? batch * nn : 0), nn, n, 1};
     // a compact panel whose fast index is the one X has
@@ -599,8 +594,8 @@ static la_status tri_outer_t(int lower, int trans, int rightside, T scale, int64
     LA_TRY(launch_zero_strict_upper<T>(lower ? G : G.t(), batch, n, st));  // the other triangle of the result
     GemmOpts o;
     o.maskC = lower ? 1 : 2;
-    if (m == 0)  // empty product: the kept triangle is zero too
-        return launch_copy<T>(cv(G), G, batch, n, n, T(0), 0, st);
+    if (m == 0)  // empty product: the kept triangle is zero too (written without reading what the buffer held)
+        return launch_fill_i32((int32_t *)out, batch * nn * (int64_t)(sizeof(T) / 4), 0, st);
     const T *X1 = trans ? Q : P, *X2 = trans ? P : Q;
     if (!rightside)
         return launch_gemm<T>(View<const T>{X1, nm, m, 1}, View<const T>{X2, nm, 1, m}, G, batch, n, n, m, scale, T(0), o,
@@ -668,6 +663,7 @@ static la_status potri_t(int lower, int64_t batch, int n, const void *L, void *B
     View<const T> Lam = tri_view<const T>((const T *)L, n, lower);
     if (n <= 16)  // both solves on the identity in registers, G lanes per matrix
         return launch_potri_tiny<T>(Lam, View<T>{(T *)B, (int64_t)n * n, n, 1}, batch, n, st);
+    ArenaFrame frame;
     View<T> sc[2];
     LA_TRY(scratch_views<T>(batch, n, 2, sc));
     LA_TRY(inverse_build<T>(Lam, sc[0], sc[1], batch, n, n, st));
@@ -788,34 +784,6 @@ static la_status sgp_t(int U, int n, const void *Kuu_, const void *Kuf_, const v
                             true, st);
 }
 
-static la_status tri_backward(bool solve, la_dtype dt, int lower, int trans, int rightside, double alpha, int64_t batch,
-                              int n, int m, const void *L, const void *X, const void *Bbar, void *Abar, void *Lbar,
-                              void *stream)
-{
-    if (bad_dtype(dt) || batch < 0 || n < 0 || m < 0 || n > MAX_N || m > MAX_N)
-        return LA_ERR_INVALID_ARG;
-    if (batch == 0 || n == 0)
-        return LA_OK;
-    if (!L || !Lbar || (m > 0 && (!X || !Bbar || !Abar)))
-        return LA_ERR_INVALID_ARG;
-    const size_t lb = (size_t)batch * n * n * esize(dt), ab = (size_t)batch * n * m * esize(dt);
-    // Abar may be Bbar itself; Lbar may be L itself for trsm (L is consumed first).  Everything else
-    // must be disjoint.
-    if (m > 0) {
-        if (overlap(Abar, ab, L, lb) || overlap(Abar, ab, X, ab) || (Abar != Bbar && overlap(Abar, ab, Bbar, ab)) ||
-            overlap(Lbar, lb, X, ab) || overlap(Lbar, lb, Bbar, ab) || overlap(Lbar, lb, Abar, ab))
-            return LA_ERR_INVALID_ARG;
-    }
-    if (overlap(Lbar, lb, L, lb) && !(solve && Lbar == L))
-        return LA_ERR_INVALID_ARG;
-    hipStream_t st = (hipStream_t)stream;
-    if (solve)
-        return dt == LA_F32 ? trsm_backward_t<float>(lower, trans, rightside, alpha, batch, n, m, L, X, Bbar, Abar, Lbar, st)
-                            : trsm_backward_t<double>(lower, trans, rightside, alpha, batch, n, m, L, X, Bbar, Abar, Lbar, st);
-    return dt == LA_F32 ? trmm_backward_t<float>(lower, trans, rightside, alpha, batch, n, m, L, X, Bbar, Abar, Lbar, st)
-                        : trmm_backward_t<double>(lower, trans, rightside, alpha, batch, n, m, L, X, Bbar, Abar, Lbar, st);
-}
-
 template <typename T>
 static la_status gp_t(int64_t batch, int n, const void *A, const void *y, void *loss, void *Abar, int32_t *info,
                       void *workspace, hipStream_t st)
@@ -836,10 +804,138 @@ static la_status gp_t(int64_t batch, int n, const void *A, const void *y, void *
                             n, false, st);
 }
 
-extern "C" {
+// ---------------------------------------------------------------------------------
+// Workspace handling of the entry points.  An operator body `op` (host code that enqueues the
+// kernels) runs twice: a sizing pass that launches nothing and records how much scratch the body
+// takes, then, if the caller's workspace holds that much, for real on that workspace.
+// ---------------------------------------------------------------------------------
+template <class F>
+static la_status sizing_pass(F &&op, size_t *peak)
+{
+    Arena a;
+    a.dry = true;
+    a.base = reinterpret_cast<char *>((uintptr_t)1 << 46);  // never dereferenced
+    Arena *prev = current_arena();
+    current_arena() = &a;
+    const la_status s = op();
+    current_arena() = prev;
+    *peak = a.peak;
+    return s;
+}
 
-la_status la_potrf_batched(la_dtype dt, int lower, int64_t batch, int n, const void *A, void *L, int32_t *info,
-                           void *stream)
+template <class F>
+static la_status with_workspace(void *ws, size_t ws_bytes, F &&op)
+{
+    size_t need = 0;
+    LA_TRY(sizing_pass(op, &need));
+    if (need > 0) {
+        if (!ws || need > ws_bytes) {
+            snprintf(g_err, sizeof(g_err), "this call needs a workspace of %zu bytes (la_workspace_bytes), %zu given", need,
+                     ws ? ws_bytes : (size_t)0);
+            return LA_ERR_WORKSPACE;
+        }
+        if ((uintptr_t)ws & 255) {
+            snprintf(g_err, sizeof(g_err), "the workspace must be 256-byte aligned");
+            return LA_ERR_INVALID_ARG;
+        }
+    }
+    Arena a;
+    a.base = (char *)ws;
+    a.cap = need > 0 ? ws_bytes : 0;
+    Arena *prev = current_arena();
+    current_arena() = &a;
+    const la_status s = op();
+    current_arena() = prev;
+    return s;
+}
+
+// does the part of the workspace a call may use overlap an operand?
+static inline bool ws_hits(const void *ws, size_t ws_bytes, const void *p, size_t bytes)
+{
+    return ws && ws_bytes && p && bytes && overlap(ws, ws_bytes, p, bytes);
+}
+
+// ---- operator bodies: validated arguments in, kernels enqueued, scratch from the current arena ----
+static la_status potrf_body(la_dtype dt, int lower, int64_t batch, int n, const void *A, void *L, int32_t *info,
+                            hipStream_t st)
+{
+    return dt == LA_F32 ? potrf_t<float>(lower, batch, n, A, L, info, st)
+                        : potrf_t<double>(lower, batch, n, A, L, info, st);
+}
+
+static la_status backward_body(la_dtype dt, int lower, int64_t batch, int n, const void *L, const void *Lbar, void *Abar,
+                               hipStream_t st)
+{
+    if (dt == LA_F32)
+        return backward_impl<float>(tri_view<const float>((const float *)L, n, lower),
+                                    tri_view<const float>((const float *)Lbar, n, lower),
+                                    tri_view<float>((float *)Abar, n, lower), batch, n, Lbar == Abar, st);
+    return backward_impl<double>(tri_view<const double>((const double *)L, n, lower),
+                                 tri_view<const double>((const double *)Lbar, n, lower),
+                                 tri_view<double>((double *)Abar, n, lower), batch, n, Lbar == Abar, st);
+}
+
+static la_status tri_body(bool solve, la_dtype dt, int lower, int trans, int rightside, double alpha, int64_t batch, int n,
+                          int m, const void *L, const void *A, void *B, hipStream_t st)
+{
+    return dt == LA_F32 ? tri_apply_t<float>(solve, lower, trans, rightside, alpha, batch, n, m, L, A, B, st)
+                        : tri_apply_t<double>(solve, lower, trans, rightside, alpha, batch, n, m, L, A, B, st);
+}
+
+static la_status tri_backward_body(bool solve, la_dtype dt, int lower, int trans, int rightside, double alpha,
+                                   int64_t batch, int n, int m, const void *L, const void *X, const void *Bbar, void *Abar,
+                                   void *Lbar, hipStream_t st)
+{
+    if (solve)
+        return dt == LA_F32 ? trsm_backward_t<float>(lower, trans, rightside, alpha, batch, n, m, L, X, Bbar, Abar, Lbar, st)
+                            : trsm_backward_t<double>(lower, trans, rightside, alpha, batch, n, m, L, X, Bbar, Abar, Lbar, st);
+    return dt == LA_F32 ? trmm_backward_t<float>(lower, trans, rightside, alpha, batch, n, m, L, X, Bbar, Abar, Lbar, st)
+                        : trmm_backward_t<double>(lower, trans, rightside, alpha, batch, n, m, L, X, Bbar, Abar, Lbar, st);
+}
+
+static la_status syrk_body(la_dtype dt, int trans, double alpha, int64_t batch, int n, int k, const void *A, void *B,
+                           hipStream_t st)
+{
+    return dt == LA_F32 ? syrk_t<float>(trans, alpha, batch, n, k, A, B, st)
+                        : syrk_t<double>(trans, alpha, batch, n, k, A, B, st);
+}
+
+static la_status syrk_backward_body(la_dtype dt, int trans, double alpha, int64_t batch, int n, int k, const void *A,
+                                    const void *Bbar, void *Abar, hipStream_t st)
+{
+    return dt == LA_F32 ? syrk_backward_t<float>(trans, alpha, batch, n, k, A, Bbar, Abar, st)
+                        : syrk_backward_t<double>(trans, alpha, batch, n, k, A, Bbar, Abar, st);
+}
+
+static la_status gemm2_body(la_dtype dt, int ta, int tb, double alpha, int64_t batch, int m, int n, int k, const void *A,
+                            const void *B, void *C, hipStream_t st)
+{
+    return dt == LA_F32 ? gemm2_t<float>(ta, tb, alpha, batch, m, n, k, A, B, C, st)
+                        : gemm2_t<double>(ta, tb, alpha, batch, m, n, k, A, B, C, st);
+}
+
+static la_status gemm2_backward_body(la_dtype dt, int ta, int tb, double alpha, int64_t batch, int m, int n, int k,
+                                     const void *A, const void *B, const void *Cbar, void *Abar, void *Bbar, hipStream_t st)
+{
+    return dt == LA_F32 ? gemm2_backward_t<float>(ta, tb, alpha, batch, m, n, k, A, B, Cbar, Abar, Bbar, st)
+                        : gemm2_backward_t<double>(ta, tb, alpha, batch, m, n, k, A, B, Cbar, Abar, Bbar, st);
+}
+
+static la_status potri_body(la_dtype dt, int lower, int64_t batch, int n, const void *L, void *B, hipStream_t st)
+{
+    return dt == LA_F32 ? potri_t<float>(lower, batch, n, L, B, st) : potri_t<double>(lower, batch, n, L, B, st);
+}
+
+static la_status potri_backward_body(la_dtype dt, int lower, int64_t batch, int n, const void *L, const void *B,
+                                     const void *Bbar, void *Lbar, hipStream_t st)
+{
+    return dt == LA_F32 ? potri_backward_t<float>(lower, batch, n, L, B, Bbar, Lbar, st)
+                        : potri_backward_t<double>(lower, batch, n, L, B, Bbar, Lbar, st);
+}
+
+// ---- argument checks + workspace + body, shared by the plain and the _ws entry points ------------
+static la_status potrf_call(la_dtype dt, int lower, int64_t batch, int n, const void *A, void *L, int32_t *info, void *ws,
+                            size_t ws_bytes, void *stream)
 {
     if (bad_dtype(dt) || batch < 0 || n < 0 || n > MAX_N)
         return LA_ERR_INVALID_ARG;
@@ -852,13 +948,14 @@ la_status la_potrf_batched(la_dtype dt, int lower, int64_t batch, int n, const v
         return LA_ERR_INVALID_ARG;
     if (info && (overlap(info, (size_t)batch * 4, L, bytes) || overlap(info, (size_t)batch * 4, A, bytes)))
         return LA_ERR_INVALID_ARG;
+    if (ws_hits(ws, ws_bytes, A, bytes) || ws_hits(ws, ws_bytes, L, bytes) || ws_hits(ws, ws_bytes, info, (size_t)batch * 4))
+        return LA_ERR_INVALID_ARG;
     hipStream_t st = (hipStream_t)stream;
-    return dt == LA_F32 ? potrf_t<float>(lower, batch, n, A, L, info, st)
-                        : potrf_t<double>(lower, batch, n, A, L, info, st);
+    return with_workspace(ws, ws_bytes, [&] { return potrf_body(dt, lower, batch, n, A, L, info, st); });
 }
 
-la_status la_potrf_backward(la_dtype dt, int lower, int64_t batch, int n, const void *L, const void *Lbar, void *Abar,
-                            void *stream)
+static la_status backward_call(la_dtype dt, int lower, int64_t batch, int n, const void *L, const void *Lbar, void *Abar,
+                               void *ws, size_t ws_bytes, void *stream)
 {
     if (bad_dtype(dt) || batch < 0 || n < 0 || n > MAX_N)
         return LA_ERR_INVALID_ARG;
@@ -869,18 +966,14 @@ la_status la_potrf_backward(la_dtype dt, int lower, int64_t batch, int n, const 
     const size_t bytes = (size_t)batch * n * n * esize(dt);
     if (overlap(L, bytes, Abar, bytes) || (Lbar != Abar && overlap(Lbar, bytes, Abar, bytes)))
         return LA_ERR_INVALID_ARG;
+    if (ws_hits(ws, ws_bytes, L, bytes) || ws_hits(ws, ws_bytes, Lbar, bytes) || ws_hits(ws, ws_bytes, Abar, bytes))
+        return LA_ERR_INVALID_ARG;
     hipStream_t st = (hipStream_t)stream;
-    if (dt == LA_F32)
-        return backward_impl<float>(tri_view<const float>((const float *)L, n, lower),
-                                    tri_view<const float>((const float *)Lbar, n, lower),
-                                    tri_view<float>((float *)Abar, n, lower), batch, n, Lbar == Abar, st);
-    return backward_impl<double>(tri_view<const double>((const double *)L, n, lower),
-                                 tri_view<const double>((const double *)Lbar, n, lower),
-                                 tri_view<double>((double *)Abar, n, lower), batch, n, Lbar == Abar, st);
+    return with_workspace(ws, ws_bytes, [&] { return backward_body(dt, lower, batch, n, L, Lbar, Abar, st); });
 }
 
-static la_status tri_apply(bool solve, la_dtype dt, int lower, int trans, int rightside, double alpha, int64_t batch,
-                           int n, int m, const void *L, const void *A, void *B, void *stream)
+static la_status tri_call(bool solve, la_dtype dt, int lower, int trans, int rightside, double alpha, int64_t batch, int n,
+                          int m, const void *L, const void *A, void *B, void *ws, size_t ws_bytes, void *stream)
 {
     if (bad_dtype(dt) || batch < 0 || n < 0 || m < 0 || n > MAX_N || m > MAX_N)
         return LA_ERR_INVALID_ARG;
@@ -891,37 +984,100 @@ static la_status tri_apply(bool solve, la_dtype dt, int lower, int trans, int ri
     const size_t lb = (size_t)batch * n * n * esize(dt), ab = (size_t)batch * n * m * esize(dt);
     if (overlap(L, lb, B, ab) || (A != B && overlap(A, ab, B, ab)))
         return LA_ERR_INVALID_ARG;
+    if (ws_hits(ws, ws_bytes, L, lb) || ws_hits(ws, ws_bytes, A, ab) || ws_hits(ws, ws_bytes, B, ab))
+        return LA_ERR_INVALID_ARG;
     hipStream_t st = (hipStream_t)stream;
-    return dt == LA_F32 ? tri_apply_t<float>(solve, lower, trans, rightside, alpha, batch, n, m, L, A, B, st)
-                        : tri_apply_t<double>(solve, lower, trans, rightside, alpha, batch, n, m, L, A, B, st);
+    return with_workspace(ws, ws_bytes,
+                          [&] { return tri_body(solve, dt, lower, trans, rightside, alpha, batch, n, m, L, A, B, st); });
 }
 
-la_status la_trsm_batched(la_dtype dt, int lower, int trans, int rightside, double alpha, int64_t batch, int n, int m,
-                          const void *L, const void *A, void *B, void *stream)
+static la_status tri_backward_call(bool solve, la_dtype dt, int lower, int trans, int rightside, double alpha,
+                                   int64_t batch, int n, int m, const void *L, const void *X, const void *Bbar, void *Abar,
+                                   void *Lbar, void *ws, size_t ws_bytes, void *stream)
 {
-    return tri_apply(true, dt, lower, trans, rightside, alpha, batch, n, m, L, A, B, stream);
+    if (bad_dtype(dt) || batch < 0 || n < 0 || m < 0 || n > MAX_N || m > MAX_N)
+        return LA_ERR_INVALID_ARG;
+    if (batch == 0 || n == 0)
+        return LA_OK;
+    if (!L || !Lbar || (m > 0 && (!X || !Bbar || !Abar)))
+        return LA_ERR_INVALID_ARG;
+    const size_t lb = (size_t)batch * n * n * esize(dt), ab = (size_t)batch * n * m * esize(dt);
+    // Abar may be Bbar itself; Lbar may be L itself for trsm (L is consumed first).  Everything else
+    // must be disjoint.
+    if (m > 0) {
+        if (overlap(Abar, ab, L, lb) || overlap(Abar, ab, X, ab) || (Abar != Bbar && overlap(Abar, ab, Bbar, ab)) ||
+            overlap(Lbar, lb, X, ab) || overlap(Lbar, lb, Bbar, ab) || overlap(Lbar, lb, Abar, ab))
+            return LA_ERR_INVALID_ARG;
+    }
+    if (overlap(Lbar, lb, L, lb) && !(solve && Lbar == L))
+        return LA_ERR_INVALID_ARG;
+    if (ws_hits(ws, ws_bytes, L, lb) || ws_hits(ws, ws_bytes, Lbar, lb) || ws_hits(ws, ws_bytes, X, ab) ||
+        ws_hits(ws, ws_bytes, Bbar, ab) || ws_hits(ws, ws_bytes, Abar, ab))
+        return LA_ERR_INVALID_ARG;
+    hipStream_t st = (hipStream_t)stream;
+    return with_workspace(ws, ws_bytes, [&] {
+        return tri_backward_body(solve, dt, lower, trans, rightside, alpha, batch, n, m, L, X, Bbar, Abar, Lbar, st);
+    });
 }
 
-la_status la_trmm_batched(la_dtype dt, int lower, int trans, int rightside, double alpha, int64_t batch, int n, int m,
-                          const void *L, const void *A, void *B, void *stream)
+static la_status syrk_call(la_dtype dt, int trans, double alpha, int64_t batch, int n, int k, const void *A, void *B,
+                           void *ws, size_t ws_bytes, void *stream)
 {
-    return tri_apply(false, dt, lower, trans, rightside, alpha, batch, n, m, L, A, B, stream);
+    if (bad_dtype(dt) || batch < 0 || n < 0 || k < 0 || n > MAX_N || k > MAX_N)
+        return LA_ERR_INVALID_ARG;
+    if (batch == 0 || n == 0)
+        return LA_OK;
+    if (!B || (k > 0 && !A))
+        return LA_ERR_INVALID_ARG;
+    const size_t ab = (size_t)batch * n * k * esize(dt), bb = (size_t)batch * n * n * esize(dt);
+    if (k > 0 && overlap(A, ab, B, bb))
+        return LA_ERR_INVALID_ARG;
+    if (ws_hits(ws, ws_bytes, A, ab) || ws_hits(ws, ws_bytes, B, bb))
+        return LA_ERR_INVALID_ARG;
+    hipStream_t st = (hipStream_t)stream;
+    return with_workspace(ws, ws_bytes, [&] { return syrk_body(dt, trans, alpha, batch, n, k, A, B, st); });
 }
 
-la_status la_trsm_backward(la_dtype dt, int lower, int trans, int rightside, double alpha, int64_t batch, int n, int m,
-                           const void *L, const void *B, const void *Bbar, void *Abar, void *Lbar, void *stream)
+static la_status syrk_backward_call(la_dtype dt, int trans, double alpha, int64_t batch, int n, int k, const void *A,
+                                    const void *Bbar, void *Abar, void *ws, size_t ws_bytes, void *stream)
 {
-    return tri_backward(true, dt, lower, trans, rightside, alpha, batch, n, m, L, B, Bbar, Abar, Lbar, stream);
+    if (bad_dtype(dt) || batch < 0 || n < 0 || k < 0 || n > MAX_N || k > MAX_N)
+        return LA_ERR_INVALID_ARG;
+    if (batch == 0 || n == 0 || k == 0)
+        return LA_OK;
+    if (!A || !Bbar || !Abar)
+        return LA_ERR_INVALID_ARG;
+    const size_t ab = (size_t)batch * n * k * esize(dt), bb = (size_t)batch * n * n * esize(dt);
+    if (overlap(Abar, ab, A, ab) || overlap(Abar, ab, Bbar, bb))
+        return LA_ERR_INVALID_ARG;
+    if (ws_hits(ws, ws_bytes, A, ab) || ws_hits(ws, ws_bytes, Bbar, bb) || ws_hits(ws, ws_bytes, Abar, ab))
+        return LA_ERR_INVALID_ARG;
+    hipStream_t st = (hipStream_t)stream;
+    return with_workspace(ws, ws_bytes, [&] { return syrk_backward_body(dt, trans, alpha, batch, n, k, A, Bbar, Abar, st); });
 }
 
-la_status la_trmm_backward(la_dtype dt, int lower, int trans, int rightside, double alpha, int64_t batch, int n, int m,
-                           const void *L, const void *A, const void *Bbar, void *Abar, void *Lbar, void *stream)
+static la_status gemm2_call(la_dtype dt, int ta, int tb, double alpha, int64_t batch, int m, int n, int k, const void *A,
+                            const void *B, void *C, void *ws, size_t ws_bytes, void *stream)
 {
-    return tri_backward(false, dt, lower, trans, rightside, alpha, batch, n, m, L, A, Bbar, Abar, Lbar, stream);
+    if (bad_dtype(dt) || batch < 0 || m < 0 || n < 0 || k < 0 || m > MAX_N || n > MAX_N || k > MAX_N)
+        return LA_ERR_INVALID_ARG;
+    if (batch == 0 || m == 0 || n == 0)
+        return LA_OK;
+    if (!C || (k > 0 && (!A || !B)))
+        return LA_ERR_INVALID_ARG;
+    const size_t ab = (size_t)batch * m * k * esize(dt), bb = (size_t)batch * k * n * esize(dt),
+                 cb = (size_t)batch * m * n * esize(dt);
+    if (k > 0 && (overlap(A, ab, C, cb) || overlap(B, bb, C, cb)))
+        return LA_ERR_INVALID_ARG;
+    if (ws_hits(ws, ws_bytes, A, ab) || ws_hits(ws, ws_bytes, B, bb) || ws_hits(ws, ws_bytes, C, cb))
+        return LA_ERR_INVALID_ARG;
+    hipStream_t st = (hipStream_t)stream;
+    return with_workspace(ws, ws_bytes, [&] { return gemm2_body(dt, ta, tb, alpha, batch, m, n, k, A, B, C, st); });
 }
 
-la_status la_gemm2_backward(la_dtype dt, int ta, int tb, double alpha, int64_t batch, int m, int n, int k,
-                            const void *A, const void *B, const void *Cbar, void *Abar, void *Bbar, void *stream)
+static la_status gemm2_backward_call(la_dtype dt, int ta, int tb, double alpha, int64_t batch, int m, int n, int k,
+                                     const void *A, const void *B, const void *Cbar, void *Abar, void *Bbar, void *ws,
+                                     size_t ws_bytes, void *stream)
 {
     if (bad_dtype(dt) || batch < 0 || m < 0 || n < 0 || k < 0 || m > MAX_N || n > MAX_N || k > MAX_N)
         return LA_ERR_INVALID_ARG;
@@ -934,6 +1090,9 @@ la_status la_gemm2_backward(la_dtype dt, int ta, int tb, double alpha, int64_t b
     if (overlap(Abar, sa, A, sa) || overlap(Abar, sa, B, sb) || overlap(Abar, sa, Cbar, sc) || overlap(Bbar, sb, A, sa) ||
         overlap(Bbar, sb, B, sb) || overlap(Bbar, sb, Cbar, sc) || overlap(Abar, sa, Bbar, sb))
         return LA_ERR_INVALID_ARG;
+    if (ws_hits(ws, ws_bytes, A, sa) || ws_hits(ws, ws_bytes, B, sb) || ws_hits(ws, ws_bytes, Cbar, sc) ||
+        ws_hits(ws, ws_bytes, Abar, sa) || ws_hits(ws, ws_bytes, Bbar, sb))
+        return LA_ERR_INVALID_ARG;
     hipStream_t st = (hipStream_t)stream;
     if (m == 0 || n == 0 || k == 0) {  // empty products: the gradients that exist are zero
         if (sa)
@@ -942,11 +1101,12 @@ la_status la_gemm2_backward(la_dtype dt, int ta, int tb, double alpha, int64_t b
             LA_TRY(launch_fill_i32((int32_t *)Bbar, (int64_t)(sb / 4), 0, st));
         return LA_OK;
     }
-    return dt == LA_F32 ? gemm2_backward_t<float>(ta, tb, alpha, batch, m, n, k, A, B, Cbar, Abar, Bbar, st)
-                        : gemm2_backward_t<double>(ta, tb, alpha, batch, m, n, k, A, B, Cbar, Abar, Bbar, st);
+    return with_workspace(ws, ws_bytes,
+                          [&] { return gemm2_backward_body(dt, ta, tb, alpha, batch, m, n, k, A, B, Cbar, Abar, Bbar, st); });
 }
 
-la_status la_potri(la_dtype dt, int lower, int64_t batch, int n, const void *L, void *B, void *stream)
+static la_status potri_call(la_dtype dt, int lower, int64_t batch, int n, const void *L, void *B, void *ws, size_t ws_bytes,
+                            void *stream)
 {
     if (bad_dtype(dt) || batch < 0 || n < 0 || n > MAX_N)
         return LA_ERR_INVALID_ARG;
@@ -957,12 +1117,14 @@ la_status la_potri(la_dtype dt, int lower, int64_t batch, int n, const void *L, 
     const size_t nb = (size_t)batch * n * n * esize(dt);
     if (L != B && overlap(L, nb, B, nb))
         return LA_ERR_INVALID_ARG;
+    if (ws_hits(ws, ws_bytes, L, nb) || ws_hits(ws, ws_bytes, B, nb))
+        return LA_ERR_INVALID_ARG;
     hipStream_t st = (hipStream_t)stream;
-    return dt == LA_F32 ? potri_t<float>(lower, batch, n, L, B, st) : potri_t<double>(lower, batch, n, L, B, st);
+    return with_workspace(ws, ws_bytes, [&] { return potri_body(dt, lower, batch, n, L, B, st); });
 }
 
-la_status la_potri_backward(la_dtype dt, int lower, int64_t batch, int n, const void *L, const void *B,
-                            const void *Bbar, void *Lbar, void *stream)
+static la_status potri_backward_call(la_dtype dt, int lower, int64_t batch, int n, const void *L, const void *B,
+                                     const void *Bbar, void *Lbar, void *ws, size_t ws_bytes, void *stream)
 {
     if (bad_dtype(dt) || batch < 0 || n < 0 || n > MAX_N)
         return LA_ERR_INVALID_ARG;
@@ -973,17 +1135,250 @@ la_status la_potri_backward(la_dtype dt, int lower, int64_t batch, int n, const 
     const size_t nb = (size_t)batch * n * n * esize(dt);
     if (overlap(Lbar, nb, L, nb) || overlap(Lbar, nb, B, nb) || overlap(Lbar, nb, Bbar, nb))
         return LA_ERR_INVALID_ARG;
+    if (ws_hits(ws, ws_bytes, L, nb) || ws_hits(ws, ws_bytes, B, nb) || ws_hits(ws, ws_bytes, Bbar, nb) ||
+        ws_hits(ws, ws_bytes, Lbar, nb))
+        return LA_ERR_INVALID_ARG;
     hipStream_t st = (hipStream_t)stream;
-    return dt == LA_F32 ? potri_backward_t<float>(lower, batch, n, L, B, Bbar, Lbar, st)
-                        : potri_backward_t<double>(lower, batch, n, L, B, Bbar, Lbar, st);
+    return with_workspace(ws, ws_bytes, [&] { return potri_backward_body(dt, lower, batch, n, L, B, Bbar, Lbar, st); });
+}
+
+// Operand addresses for the sizing passes of la_workspace_bytes: far apart, 256-byte aligned, never dereferenced.
+static inline void *fake_operand(int i) { return reinterpret_cast<void *>(((uintptr_t)1 << 45) + ((uintptr_t)i << 41)); }
+
+static inline size_t align256(size_t b) { return (b + 255) & ~(size_t)255; }
+
+extern "C" {
+
+size_t la_workspace_bytes(la_op op, la_dtype dt, int64_t batch, int n, int m, int k)
+{
+    if (bad_dtype(dt) || batch <= 0 || n < 0 || m < 0 || k < 0 || n > MAX_N || m > MAX_N || k > MAX_N)
+        return 0;
+    void *p0 = fake_operand(0), *p1 = fake_operand(1), *p2 = fake_operand(2), *p3 = fake_operand(3), *p4 = fake_operand(4);
+    size_t most = 0;
+    auto take = [&](auto &&body) {
+        size_t peak = 0;
+        if (sizing_pass(body, &peak) == LA_OK && peak > most)
+            most = peak;
+    };
+    // every flag combination and every permitted aliasing: the answer holds for all of them
+    for (int f = 0; f < 8; ++f) {
+        const int lower = f & 1, trans = (f >> 1) & 1, right = (f >> 2) & 1;
+        switch (op) {
+        case LA_OP_POTRF:
+            if (n > 0 && f < 2) {
+                take([&] { return potrf_body(dt, lower, batch, n, p0, p1, nullptr, nullptr); });
+                take([&] { return potrf_body(dt, lower, batch, n, p0, p0, nullptr, nullptr); });
+            }
+            break;
+        case LA_OP_POTRF_BACKWARD:
+            if (n > 0 && f < 2) {
+                take([&] { return backward_body(dt, lower, batch, n, p0, p1, p2, nullptr); });
+                take([&] { return backward_body(dt, lower, batch, n, p0, p1, p1, nullptr); });
+            }
+            break;
+        case LA_OP_TRSM:
+        case LA_OP_TRMM:
+            if (n > 0 && m > 0) {
+                take([&] { return tri_body(op == LA_OP_TRSM, dt, lower, trans, right, 1.0, batch, n, m, p0, p1, p2, nullptr); });
+                take([&] { return tri_body(op == LA_OP_TRSM, dt, lower, trans, right, 0.5, batch, n, m, p0, p1, p1, nullptr); });
+            }
+            break;
+        case LA_OP_TRSM_BACKWARD:
+        case LA_OP_TRMM_BACKWARD:
+            if (n > 0) {
+                const bool solve = op == LA_OP_TRSM_BACKWARD;
+                take([&] { return tri_backward_body(solve, dt, lower, trans, right, 0.5, batch, n, m, p0, p1, p2, p3, p4, nullptr); });
+                take([&] { return tri_backward_body(solve, dt, lower, trans, right, 1.0, batch, n, m, p0, p1, p2, p2, p4, nullptr); });
+            }
+            break;
+        case LA_OP_SYRK:
+            if (n > 0 && f < 2)
+                take([&] { return syrk_body(dt, f, 1.0, batch, n, k, p0, p1, nullptr); });
+            break;
+        case LA_OP_SYRK_BACKWARD:
+            if (n > 0 && k > 0 && f < 2)
+                take([&] { return syrk_backward_body(dt, f, 1.0, batch, n, k, p0, p1, p2, nullptr); });
+            break;
+        case LA_OP_GEMM2:
+            if (m > 0 && n > 0 && f < 4)
+                take([&] { return gemm2_body(dt, f & 1, f >> 1, 1.0, batch, m, n, k, p0, p1, p2, nullptr); });
+            break;
+        case LA_OP_GEMM2_BACKWARD:
+            if (m > 0 && n > 0 && k > 0 && f < 4)
+                take([&] { return gemm2_backward_body(dt, f & 1, f >> 1, 1.0, batch, m, n, k, p0, p1, p2, p3, p4, nullptr); });
+            break;
+        case LA_OP_POTRI:
+            if (n > 0 && f < 2) {
+                take([&] { return potri_body(dt, lower, batch, n, p0, p1, nullptr); });
+                take([&] { return potri_body(dt, lower, batch, n, p0, p0, nullptr); });
+            }
+            break;
+        case LA_OP_POTRI_BACKWARD:
+            if (n > 0 && f < 2)
+                take([&] { return potri_backward_body(dt, lower, batch, n, p0, p1, p2, p3, nullptr); });
+            break;
+        default:
+            return 0;
+        }
+    }
+    return most;
+}
+
+la_status la_potrf_batched(la_dtype dt, int lower, int64_t batch, int n, const void *A, void *L, int32_t *info,
+                           void *stream)
+{
+    return potrf_call(dt, lower, batch, n, A, L, info, nullptr, 0, stream);
+}
+la_status la_potrf_batched_ws(la_dtype dt, int lower, int64_t batch, int n, const void *A, void *L, int32_t *info,
+                              void *workspace, size_t workspace_bytes, void *stream)
+{
+    return potrf_call(dt, lower, batch, n, A, L, info, workspace, workspace_bytes, stream);
+}
+
+la_status la_potrf_backward(la_dtype dt, int lower, int64_t batch, int n, const void *L, const void *Lbar, void *Abar,
+                            void *stream)
+{
+    return backward_call(dt, lower, batch, n, L, Lbar, Abar, nullptr, 0, stream);
+}
+la_status la_potrf_backward_ws(la_dtype dt, int lower, int64_t batch, int n, const void *L, const void *Lbar, void *Abar,
+                               void *workspace, size_t workspace_bytes, void *stream)
+{
+    return backward_call(dt, lower, batch, n, L, Lbar, Abar, workspace, workspace_bytes, stream);
+}
+
+la_status la_trsm_batched(la_dtype dt, int lower, int trans, int rightside, double alpha, int64_t batch, int n, int m,
+                          const void *L, const void *A, void *B, void *stream)
+{
+    return tri_call(true, dt, lower, trans, rightside, alpha, batch, n, m, L, A, B, nullptr, 0, stream);
+}
+la_status la_trsm_batched_ws(la_dtype dt, int lower, int trans, int rightside, double alpha, int64_t batch, int n, int m,
+                             const void *L, const void *A, void *B, void *workspace, size_t workspace_bytes, void *stream)
+{
+    return tri_call(true, dt, lower, trans, rightside, alpha, batch, n, m, L, A, B, workspace, workspace_bytes, stream);
+}
+
+la_status la_trmm_batched(la_dtype dt, int lower, int trans, int rightside, double alpha, int64_t batch, int n, int m,
+                          const void *L, const void *A, void *B, void *stream)
+{
+    return tri_call(false, dt, lower, trans, rightside, alpha, batch, n, m, L, A, B, nullptr, 0, stream);
+}
+la_status la_trmm_batched_ws(la_dtype dt, int lower, int trans, int rightside, double alpha, int64_t batch, int n, int m,
+                             const void *L, const void *A, void *B, void *workspace, size_t workspace_bytes, void *stream)
+{
+    return tri_call(false, dt, lower, trans, rightside, alpha, batch, n, m, L, A, B, workspace, workspace_bytes, stream);
+}
+
+la_status la_trsm_backward(la_dtype dt, int lower, int trans, int rightside, double alpha, int64_t batch, int n, int m,
+                           const void *L, const void *B, const void *Bbar, void *Abar, void *Lbar, void *stream)
+{
+    return tri_backward_call(true, dt, lower, trans, rightside, alpha, batch, n, m, L, B, Bbar, Abar, Lbar, nullptr, 0, stream);
+}
+la_status la_trsm_backward_ws(la_dtype dt, int lower, int trans, int rightside, double alpha, int64_t batch, int n, int m,
+                              const void *L, const void *B, const void *Bbar, void *Abar, void *Lbar, void *workspace,
+                              size_t workspace_bytes, void *stream)
+{
+    return tri_backward_call(true, dt, lower, trans, rightside, alpha, batch, n, m, L, B, Bbar, Abar, Lbar, workspace,
+                             workspace_bytes, stream);
+}
+
+la_status la_trmm_backward(la_dtype dt, int lower, int trans, int rightside, double alpha, int64_t batch, int n, int m,
+                           const void *L, const void *A, const void *Bbar, void *Abar, void *Lbar, void *stream)
+{
+    return tri_backward_call(false, dt, lower, trans, rightside, alpha, batch, n, m, L, A, Bbar, Abar, Lbar, nullptr, 0, stream);
+}
+la_status la_trmm_backward_ws(la_dtype dt, int lower, int trans, int rightside, double alpha, int64_t batch, int n, int m,
+                              const void *L, const void *A, const void *Bbar, void *Abar, void *Lbar, void *workspace,
+                              size_t workspace_bytes, void *stream)
+{
+    return tri_backward_call(false, dt, lower, trans, rightside, alpha, batch, n, m, L, A, Bbar, Abar, Lbar, workspace,
+                             workspace_bytes, stream);
+}
+
+la_status la_gemm2_backward(la_dtype dt, int ta, int tb, double alpha, int64_t batch, int m, int n, int k,
+                            const void *A, const void *B, const void *Cbar, void *Abar, void *Bbar, void *stream)
+{
+    return gemm2_backward_call(dt, ta, tb, alpha, batch, m, n, k, A, B, Cbar, Abar, Bbar, nullptr, 0, stream);
+}
+la_status la_gemm2_backward_ws(la_dtype dt, int ta, int tb, double alpha, int64_t batch, int m, int n, int k,
+                               const void *A, const void *B, const void *Cbar, void *Abar, void *Bbar, void *workspace,
+                               size_t workspace_bytes, void *stream)
+{
+    return gemm2_backward_call(dt, ta, tb, alpha, batch, m, n, k, A, B, Cbar, Abar, Bbar, workspace, workspace_bytes, stream);
+}
+
+la_status la_potri(la_dtype dt, int lower, int64_t batch, int n, const void *L, void *B, void *stream)
+{
+    return potri_call(dt, lower, batch, n, L, B, nullptr, 0, stream);
+}
+la_status la_potri_ws(la_dtype dt, int lower, int64_t batch, int n, const void *L, void *B, void *workspace,
+                      size_t workspace_bytes, void *stream)
+{
+    return potri_call(dt, lower, batch, n, L, B, workspace, workspace_bytes, stream);
+}
+
+la_status la_potri_backward(la_dtype dt, int lower, int64_t batch, int n, const void *L, const void *B,
+                            const void *Bbar, void *Lbar, void *stream)
+{
+    return potri_backward_call(dt, lower, batch, n, L, B, Bbar, Lbar, nullptr, 0, stream);
+}
+la_status la_potri_backward_ws(la_dtype dt, int lower, int64_t batch, int n, const void *L, const void *B,
+                               const void *Bbar, void *Lbar, void *workspace, size_t workspace_bytes, void *stream)
+{
+    return potri_backward_call(dt, lower, batch, n, L, B, Bbar, Lbar, workspace, workspace_bytes, stream);
+}
+
+la_status la_syrk_backward(la_dtype dt, int trans, double alpha, int64_t batch, int n, int k, const void *A,
+                           const void *Bbar, void *Abar, void *stream)
+{
+    return syrk_backward_call(dt, trans, alpha, batch, n, k, A, Bbar, Abar, nullptr, 0, stream);
+}
+la_status la_syrk_backward_ws(la_dtype dt, int trans, double alpha, int64_t batch, int n, int k, const void *A,
+                              const void *Bbar, void *Abar, void *workspace, size_t workspace_bytes, void *stream)
+{
+    return syrk_backward_call(dt, trans, alpha, batch, n, k, A, Bbar, Abar, workspace, workspace_bytes, stream);
+}
+
+la_status la_syrk_batched(la_dtype dt, int trans, double alpha, int64_t batch, int n, int k, const void *A, void *B,
+                          void *stream)
+{
+    return syrk_call(dt, trans, alpha, batch, n, k, A, B, nullptr, 0, stream);
+}
+la_status la_syrk_batched_ws(la_dtype dt, int trans, double alpha, int64_t batch, int n, int k, const void *A, void *B,
+                             void *workspace, size_t workspace_bytes, void *stream)
+{
+    return syrk_call(dt, trans, alpha, batch, n, k, A, B, workspace, workspace_bytes, stream);
+}
+
+la_status la_gemm2_batched(la_dtype dt, int ta, int tb, double alpha, int64_t batch, int m, int n, int k, const void *A,
+                           const void *B, void *C, void *stream)
+{
+    return gemm2_call(dt, ta, tb, alpha, batch, m, n, k, A, B, C, nullptr, 0, stream);
+}
+la_status la_gemm2_batched_ws(la_dtype dt, int ta, int tb, double alpha, int64_t batch, int m, int n, int k, const void *A,
+                              const void *B, void *C, void *workspace, size_t workspace_bytes, void *stream)
+{
+    return gemm2_call(dt, ta, tb, alpha, batch, m, n, k, A, B, C, workspace, workspace_bytes, stream);
 }
 
 size_t la_sgp_workspace_bytes(la_dtype dt, int U, int n)
 {
-    if (bad_dtype(dt) || U <= 0 || n <= 0)
+    if (bad_dtype(dt) || U <= 0 || n <= 0 || U > MAX_N || n > MAX_N)
         return 0;
     const size_t e = dt == LA_F32 ? sgp_workspace_elems<float>(U, n) : sgp_workspace_elems<double>(U, n);
-    return e * esize(dt) + 8 + 7 * SGP_PARTIALS * sizeof(double);
+    const size_t fixed = align256(e * esize(dt) + 8 + 7 * SGP_PARTIALS * sizeof(double));
+    void *p[10];
+    for (int i = 0; i < 10; ++i)
+        p[i] = fake_operand(i);
+    size_t peak = 0;
+    const la_status s = sizing_pass(
+        [&] {
+            return dt == LA_F32 ? sgp_t<float>(U, n, p[0], p[1], p[2], p[3], 1.0, p[4], p[5], p[6], p[7], p[8], p[9],
+                                               fake_operand(10), nullptr)
+                                : sgp_t<double>(U, n, p[0], p[1], p[2], p[3], 1.0, p[4], p[5], p[6], p[7], p[8], p[9],
+                                                fake_operand(10), nullptr);
+        },
+        &peak);
+    return s == LA_OK ? fixed + peak : 0;
 }
 
 la_status la_sgp_criterion(la_dtype dt, int U, int n, const void *Kuu, const void *Kuf, const void *Kff_diag,
@@ -993,18 +1388,27 @@ la_status la_sgp_criterion(la_dtype dt, int U, int n, const void *Kuu, const voi
     if (bad_dtype(dt) || U <= 0 || n <= 0 || U > MAX_N || n > MAX_N || !(noise_var > 0.0))
         return LA_ERR_INVALID_ARG;
     if (!Kuu || !Kuf || !Kff_diag || !y || !phi || !Kuu_bar || !Kuf_bar || !Kff_diag_bar || !y_bar || !noise_bar ||
-        !workspace || workspace_bytes < la_sgp_workspace_bytes(dt, U, n) || ((uintptr_t)workspace & 15))
+        !workspace || ((uintptr_t)workspace & 255))
         return LA_ERR_INVALID_ARG;
+    const size_t e = dt == LA_F32 ? sgp_workspace_elems<float>(U, n) : sgp_workspace_elems<double>(U, n);
+    const size_t fixed = align256(e * esize(dt) + 8 + 7 * SGP_PARTIALS * sizeof(double));
+    if (workspace_bytes < fixed) {
+        snprintf(g_err, sizeof(g_err), "this call needs a workspace of la_sgp_workspace_bytes bytes, %zu given",
+                 workspace_bytes);
+        return LA_ERR_WORKSPACE;
+    }
     const size_t uu = (size_t)U * U * esize(dt), un = (size_t)U * n * esize(dt);
     if (overlap(Kuu_bar, uu, Kuu, uu) || overlap(Kuf_bar, un, Kuf, un) || overlap(Kuu_bar, uu, Kuf_bar, un) ||
         overlap(workspace, workspace_bytes, Kuu_bar, uu) || overlap(workspace, workspace_bytes, Kuf_bar, un) ||
         overlap(workspace, workspace_bytes, Kuu, uu) || overlap(workspace, workspace_bytes, Kuf, un))
         return LA_ERR_INVALID_ARG;
     hipStream_t st = (hipStream_t)stream;
-    return dt == LA_F32 ? sgp_t<float>(U, n, Kuu, Kuf, Kff_diag, y, noise_var, phi, Kuu_bar, Kuf_bar, Kff_diag_bar, y_bar,
-                                       noise_bar, workspace, st)
-                        : sgp_t<double>(U, n, Kuu, Kuf, Kff_diag, y, noise_var, phi, Kuu_bar, Kuf_bar, Kff_diag_bar, y_bar,
-                                        noise_bar, workspace, st);
+    return with_workspace((char *)workspace + fixed, workspace_bytes - fixed, [&] {
+        return dt == LA_F32 ? sgp_t<float>(U, n, Kuu, Kuf, Kff_diag, y, noise_var, phi, Kuu_bar, Kuf_bar, Kff_diag_bar, y_bar,
+                                           noise_bar, workspace, st)
+                            : sgp_t<double>(U, n, Kuu, Kuf, Kff_diag, y, noise_var, phi, Kuu_bar, Kuf_bar, Kff_diag_bar, y_bar,
+                                            noise_bar, workspace, st);
+    });
 }
 
 la_status la_kalman_filter(la_dtype dt, int64_t batch, int T, int dh, int dv, int shared_params, const void *A,
@@ -1027,58 +1431,6 @@ la_status la_kalman_filter(la_dtype dt, int64_t batch, int T, int dh, int dv, in
     return launch_kalman<double>((const double *)A, (const double *)B, (const double *)Sh, (const double *)Sv,
                                  (const double *)mu0, (const double *)S0, (const double *)v, (double *)f, (double *)F,
                                  (double *)nll, info, batch, T, dh, dv, shared_params != 0, st);
-}
-
-la_status la_syrk_backward(la_dtype dt, int trans, double alpha, int64_t batch, int n, int k, const void *A,
-                           const void *Bbar, void *Abar, void *stream)
-{
-    if (bad_dtype(dt) || batch < 0 || n < 0 || k < 0 || n > MAX_N || k > MAX_N)
-        return LA_ERR_INVALID_ARG;
-    if (batch == 0 || n == 0 || k == 0)
-        return LA_OK;
-    if (!A || !Bbar || !Abar)
-        return LA_ERR_INVALID_ARG;
-    const size_t ab = (size_t)batch * n * k * esize(dt), bb = (size_t)batch * n * n * esize(dt);
-    if (overlap(Abar, ab, A, ab) || overlap(Abar, ab, Bbar, bb))
-        return LA_ERR_INVALID_ARG;
-    hipStream_t st = (hipStream_t)stream;
-    return dt == LA_F32 ? syrk_backward_t<float>(trans, alpha, batch, n, k, A, Bbar, Abar, st)
-                        : syrk_backward_t<double>(trans, alpha, batch, n, k, A, Bbar, Abar, st);
-}
-
-la_status la_syrk_batched(la_dtype dt, int trans, double alpha, int64_t batch, int n, int k, const void *A, void *B,
-                          void *stream)
-{
-    if (bad_dtype(dt) || batch < 0 || n < 0 || k < 0 || n > MAX_N || k > MAX_N)
-        return LA_ERR_INVALID_ARG;
-    if (batch == 0 || n == 0)
-        return LA_OK;
-    if (!B || (k > 0 && !A))
-        return LA_ERR_INVALID_ARG;
-    const size_t ab = (size_t)batch * n * k * esize(dt), bb = (size_t)batch * n * n * esize(dt);
-    if (k > 0 && overlap(A, ab, B, bb))
-        return LA_ERR_INVALID_ARG;
-    hipStream_t st = (hipStream_t)stream;
-    return dt == LA_F32 ? syrk_t<float>(trans, alpha, batch, n, k, A, B, st)
-                        : syrk_t<double>(trans, alpha, batch, n, k, A, B, st);
-}
-
-la_status la_gemm2_batched(la_dtype dt, int ta, int tb, double alpha, int64_t batch, int m, int n, int k, const void *A,
-                           const void *B, void *C, void *stream)
-{
-    if (bad_dtype(dt) || batch < 0 || m < 0 || n < 0 || k < 0 || m > MAX_N || n > MAX_N || k > MAX_N)
-        return LA_ERR_INVALID_ARG;
-    if (batch == 0 || m == 0 || n == 0)
-        return LA_OK;
-    if (!C || (k > 0 && (!A || !B)))
-        return LA_ERR_INVALID_ARG;
-    const size_t ab = (size_t)batch * m * k * esize(dt), bb = (size_t)batch * k * n * esize(dt),
-                 cb = (size_t)batch * m * n * esize(dt);
-    if (k > 0 && (overlap(A, ab, C, cb) || overlap(B, bb, C, cb)))
-        return LA_ERR_INVALID_ARG;
-    hipStream_t st = (hipStream_t)stream;
-    return dt == LA_F32 ? gemm2_t<float>(ta, tb, alpha, batch, m, n, k, A, B, C, st)
-                        : gemm2_t<double>(ta, tb, alpha, batch, m, n, k, A, B, C, st);
 }
 
 la_status la_sumlogdiag(la_dtype dt, int64_t batch, int n, const void *L, void *out, void *stream)
@@ -1113,14 +1465,29 @@ la_status la_gp_glue(la_dtype dt, int64_t batch, int n, const void *L, const voi
                                                  (const double *)alpha, (double *)loss, (double *)Lbar, batch, n, st);
 }
 
+// fixed part of the GP criterion's workspace above the one-launch sizes: L, Lbar, z, alpha
+static size_t gp_fixed_bytes(la_dtype dt, int64_t batch, int n)
+{
+    return align256(((size_t)batch * n * n * 2 + (size_t)batch * n * 2) * esize(dt));
+}
+
 size_t la_gp_workspace_bytes(la_dtype dt, int64_t batch, int n)
 {
-    if (bad_dtype(dt) || batch <= 0 || n <= 0)
+    if (bad_dtype(dt) || batch <= 0 || n <= 0 || n > MAX_N)
         return 0;
     const int fused = dt == LA_F32 ? backward_leaf16_max_n<float>() : backward_leaf16_max_n<double>();
     if (n <= fused)
         return 0;
-    return ((size_t)batch * n * n * 2 + (size_t)batch * n * 2) * esize(dt);
+    size_t peak = 0;
+    const la_status s = sizing_pass(
+        [&] {
+            return dt == LA_F32 ? gp_t<float>(batch, n, fake_operand(0), fake_operand(1), fake_operand(2), fake_operand(3),
+                                              nullptr, fake_operand(4), nullptr)
+                                : gp_t<double>(batch, n, fake_operand(0), fake_operand(1), fake_operand(2), fake_operand(3),
+                                               nullptr, fake_operand(4), nullptr);
+        },
+        &peak);
+    return s == LA_OK ? gp_fixed_bytes(dt, batch, n) + peak : 0;
 }
 
 la_status la_gp_criterion(la_dtype dt, int64_t batch, int n, const void *A, const void *y, void *loss, void *Abar,
@@ -1137,19 +1504,29 @@ la_status la_gp_criterion(la_dtype dt, int64_t batch, int n, const void *A, cons
         return dt == LA_F32 ? launch_gp_glue<float>(nullptr, nullptr, nullptr, nullptr, (float *)loss, nullptr, batch, 0, st)
                             : launch_gp_glue<double>(nullptr, nullptr, nullptr, nullptr, (double *)loss, nullptr, batch, 0,
                                                      st);
-    const size_t need = la_gp_workspace_bytes(dt, batch, n);
+    const int fused = dt == LA_F32 ? backward_leaf16_max_n<float>() : backward_leaf16_max_n<double>();
+    const size_t fixed = n <= fused ? 0 : gp_fixed_bytes(dt, batch, n);
     const size_t bytes = (size_t)batch * n * n * esize(dt);
-    if (need > 0 && (!workspace || workspace_bytes < need || ((uintptr_t)workspace & 15) ||
-                     overlap(workspace, need, A, bytes) || overlap(workspace, need, Abar, bytes)))
-        return LA_ERR_INVALID_ARG;
+    if (fixed > 0) {
+        if (!workspace || workspace_bytes < fixed) {
+            snprintf(g_err, sizeof(g_err), "this call needs a workspace of la_gp_workspace_bytes bytes, %zu given",
+                     workspace ? workspace_bytes : (size_t)0);
+            return LA_ERR_WORKSPACE;
+        }
+        if (((uintptr_t)workspace & 255) || overlap(workspace, workspace_bytes, A, bytes) ||
+            overlap(workspace, workspace_bytes, Abar, bytes))
+            return LA_ERR_INVALID_ARG;
+    }
     if (A != Abar && overlap(A, bytes, Abar, bytes))
         return LA_ERR_INVALID_ARG;
-    return dt == LA_F32 ? gp_t<float>(batch, n, A, y, loss, Abar, info, workspace, st)
-                        : gp_t<double>(batch, n, A, y, loss, Abar, info, workspace, st);
+    return with_workspace(fixed ? (char *)workspace + fixed : nullptr, fixed ? workspace_bytes - fixed : 0, [&] {
+        return dt == LA_F32 ? gp_t<float>(batch, n, A, y, loss, Abar, info, workspace, st)
+                            : gp_t<double>(batch, n, A, y, loss, Abar, info, workspace, st);
+    });
 }
 
 const char *la_last_error(void) { return g_err; }
 
-int la_version(void) { return 100; }
+int la_version(void) { return 200; }
 
 }  // extern "C"

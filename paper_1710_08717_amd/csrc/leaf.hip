@@ -520,7 +520,8 @@ __global__ __launch_bounds__(LEAF16_THREADS) void k_potrf_leaf16(View<const T> A
     // ---- factor and inverse back to memory (lower tiles; zeros above the diagonal inside the
     //      diagonal tiles) -----------------------------------------------------------------------
     leaf_store_lower<T>(m, false, L.p + b * L.bs, L.rs, L.cs, nb, zero_upper != 0, wave, lane);
-    leaf_store_lower<T>(m, true, Inv.p + b * Inv.bs, Inv.rs, Inv.cs, nb, false, wave, lane);
+    if (Inv.p != nullptr)  // a stand-alone factorisation has no use for the inverse
+        leaf_store_lower<T>(m, true, Inv.p + b * Inv.bs, Inv.rs, Inv.cs, nb, false, wave, lane);
     LEAF16_STAMP(30);
     if (info != nullptr && tid == 0 && fail != 0 && fail <= nb) {
         if (info[b] == 0)
@@ -1142,6 +1143,8 @@ la_status launch_potrf_leaf16(View<const T> A, View<T> L, View<T> Inv, int32_t *
     if (nb > LT * LK || batch > 0x7fffffffll)
         return LA_ERR_UNSUPPORTED;
     constexpr size_t lds_bytes = (size_t)Leaf16<T>::TOTAL * sizeof(T);
+    if (dry_run())
+        return LA_OK;
     static bool configured[64] = {};
     int dev = 0;
     LA_HIP(hipGetDevice(&dev));
@@ -1150,7 +1153,7 @@ la_status launch_potrf_leaf16(View<const T> A, View<T> L, View<T> Inv, int32_t *
                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes));
         configured[dev] = true;
     }
-    hipLaunchKernelGGL((k_potrf_leaf16<T>), dim3((unsigned)batch), dim3(LEAF16_THREADS), lds_bytes, st, A, L, Inv, info,
+    LA_LAUNCH((k_potrf_leaf16<T>), dim3((unsigned)batch), dim3(LEAF16_THREADS), lds_bytes, st, A, L, Inv, info,
                        info_off, batch, nb, zero_upper ? 1 : 0);
     return launch_check("potrf_leaf16");
 }
@@ -1169,6 +1172,8 @@ la_status launch_tri_inverse128(View<const T> Lam, View<T> Inv, int64_t batch, i
     if (batch * nblk > 0x7fffffffll)
         return LA_ERR_UNSUPPORTED;
     constexpr size_t lds_bytes = (size_t)Leaf16<T>::TOTAL * sizeof(T);
+    if (dry_run())
+        return LA_OK;
     static bool configured[64] = {};
     int dev = 0;
     LA_HIP(hipGetDevice(&dev));
@@ -1177,7 +1182,7 @@ la_status launch_tri_inverse128(View<const T> Lam, View<T> Inv, int64_t batch, i
                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes));
         configured[dev] = true;
     }
-    hipLaunchKernelGGL((k_tri_inv_leaf16<T>), dim3((unsigned)(batch * nblk)), dim3(LEAF16_THREADS), lds_bytes, st, Lam,
+    LA_LAUNCH((k_tri_inv_leaf16<T>), dim3((unsigned)(batch * nblk)), dim3(LEAF16_THREADS), lds_bytes, st, Lam,
                        Inv, batch, n, nblk);
     return launch_check("tri_inverse128");
 }
@@ -1194,6 +1199,8 @@ la_status launch_trsm_leaf16(View<const T> Lam, View<const T> Xin, View<T> X, in
     if (n > LT * LK || m > LT * TRSM16_MAX_CT || batch > 0x7fffffffll)
         return LA_ERR_UNSUPPORTED;
     constexpr size_t lds_bytes = (size_t)Leaf16<T>::TOTAL * sizeof(T);
+    if (dry_run())
+        return LA_OK;
     static bool configured[64] = {};
     int dev = 0;
     LA_HIP(hipGetDevice(&dev));
@@ -1202,7 +1209,7 @@ la_status launch_trsm_leaf16(View<const T> Lam, View<const T> Xin, View<T> X, in
                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes));
         configured[dev] = true;
     }
-    hipLaunchKernelGGL((k_trsm_leaf16<T>), dim3((unsigned)batch), dim3(LEAF16_THREADS), lds_bytes, st, Lam, Xin, X,
+    LA_LAUNCH((k_trsm_leaf16<T>), dim3((unsigned)batch), dim3(LEAF16_THREADS), lds_bytes, st, Lam, Xin, X,
                        batch, n, m, alpha, fwd ? 1 : 0);
     return launch_check("trsm_leaf16");
 }
@@ -1233,6 +1240,8 @@ la_status launch_backward_leaf16(View<const T> Lam, View<const T> G, View<T> Aba
         return LA_ERR_UNSUPPORTED;
     const int K = (n + LT - 1) / LT;
     const size_t lds_bytes = 3 * (size_t)backward16_area<T>(K) * sizeof(T);
+    if (dry_run())
+        return LA_OK;
     static bool configured[64] = {};
     int dev = 0;
     LA_HIP(hipGetDevice(&dev));
@@ -1241,7 +1250,7 @@ la_status launch_backward_leaf16(View<const T> Lam, View<const T> G, View<T> Aba
                                    hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024));
         configured[dev] = true;
     }
-    hipLaunchKernelGGL((k_backward_leaf16<T>), dim3((unsigned)batch), dim3(LEAF16_THREADS), lds_bytes, st, Lam, G, Abar,
+    LA_LAUNCH((k_backward_leaf16<T>), dim3((unsigned)batch), dim3(LEAF16_THREADS), lds_bytes, st, Lam, G, Abar,
                        batch, n);
     return launch_check("backward_leaf16");
 }
@@ -1261,6 +1270,8 @@ la_status launch_gp_leaf16(View<const T> A, const T *y, T *loss, View<T> Abar, i
         return LA_ERR_UNSUPPORTED;
     const int K = (n + LT - 1) / LT;
     const size_t lds_bytes = (3 * (size_t)backward16_area<T>(K) + 4 * LT * LK) * sizeof(T);
+    if (dry_run())
+        return LA_OK;
     static bool configured[64] = {};
     int dev = 0;
     LA_HIP(hipGetDevice(&dev));
@@ -1270,7 +1281,7 @@ la_status launch_gp_leaf16(View<const T> A, const T *y, T *loss, View<T> Abar, i
                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)most));
         configured[dev] = true;
     }
-    hipLaunchKernelGGL((k_gp_leaf16<T>), dim3((unsigned)batch), dim3(LEAF16_THREADS), lds_bytes, st, A, y, loss, Abar,
+    LA_LAUNCH((k_gp_leaf16<T>), dim3((unsigned)batch), dim3(LEAF16_THREADS), lds_bytes, st, A, y, loss, Abar,
                        info, batch, n);
     return launch_check("gp_leaf16");
 }

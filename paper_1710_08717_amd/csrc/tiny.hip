@@ -417,15 +417,15 @@ la_status launch_potrf_tiny(View<const T> A, View<T> L, int32_t *info, int info_
         return LA_ERR_UNSUPPORTED;
     if (nb <= 4) {
         constexpr int MPW = Stage<T, 4>::MPW;
-        hipLaunchKernelGGL((k_potrf_tiny<T, 4>), dim3((unsigned)((batch + MPW - 1) / MPW)), dim3(WAVE), 0, st, A, L,
+        LA_LAUNCH((k_potrf_tiny<T, 4>), dim3((unsigned)((batch + MPW - 1) / MPW)), dim3(WAVE), 0, st, A, L,
                            info, info_off, batch, nb);
     } else if (nb <= 8) {  // 8 lanes per matrix: half the pivots and twice the matrices per wavefront of the 16-lane form
         constexpr int MPW = Stage<T, 8>::MPW;
-        hipLaunchKernelGGL((k_potrf_tiny<T, 8>), dim3((unsigned)((batch + MPW - 1) / MPW)), dim3(WAVE), 0, st, A, L,
+        LA_LAUNCH((k_potrf_tiny<T, 8>), dim3((unsigned)((batch + MPW - 1) / MPW)), dim3(WAVE), 0, st, A, L,
                            info, info_off, batch, nb);
     } else if (nb <= 16) {
         constexpr int MPW = Stage<T, 16>::MPW;
-        hipLaunchKernelGGL((k_potrf_tiny<T, 16>), dim3((unsigned)((batch + MPW - 1) / MPW)), dim3(WAVE), 0, st, A, L,
+        LA_LAUNCH((k_potrf_tiny<T, 16>), dim3((unsigned)((batch + MPW - 1) / MPW)), dim3(WAVE), 0, st, A, L,
                            info, info_off, batch, nb);
     } else if (nb <= 48) {
         // 16 lanes per matrix, 2 or 3 rows per lane.  (4 rows per lane for n <= 64 need all 256
@@ -435,12 +435,12 @@ la_status launch_potrf_tiny(View<const T> A, View<T> L, int32_t *info, int info_
         const dim3 grid((unsigned)((batch + MPW - 1) / MPW));
         constexpr size_t lds2 = sizeof(T) * Stage<T, 32, MPW>::ELEMS, lds3 = sizeof(T) * Stage<T, 48, MPW>::ELEMS;
         if (nb <= 32) {
-            hipLaunchKernelGGL((k_potrf_tiny_rows<T, 2>), grid, dim3(WAVE), lds2, st, A, L, info, info_off, batch, nb);
+            LA_LAUNCH((k_potrf_tiny_rows<T, 2>), grid, dim3(WAVE), lds2, st, A, L, info, info_off, batch, nb);
         } else {
-            hipLaunchKernelGGL((k_potrf_tiny_rows<T, 3>), grid, dim3(WAVE), lds3, st, A, L, info, info_off, batch, nb);
+            LA_LAUNCH((k_potrf_tiny_rows<T, 3>), grid, dim3(WAVE), lds3, st, A, L, info, info_off, batch, nb);
         }
     } else {
-        hipLaunchKernelGGL((k_potrf_tiny<T, 64>), dim3((unsigned)batch), dim3(WAVE), 0, st, A, L, info, info_off,
+        LA_LAUNCH((k_potrf_tiny<T, 64>), dim3((unsigned)batch), dim3(WAVE), 0, st, A, L, info, info_off,
                            batch, nb);
     }
     return launch_check("potrf_tiny");
@@ -455,21 +455,21 @@ la_status launch_backward_tiny(View<const T> L, View<const T> G, View<T> Abar, i
         return LA_ERR_UNSUPPORTED;
     if (n <= 4) {
         constexpr int MPW = Stage<T, 4>::MPW;
-        hipLaunchKernelGGL((k_backward_tiny<T, 4>), dim3((unsigned)((batch + MPW - 1) / MPW)), dim3(WAVE), 0, st, L,
+        LA_LAUNCH((k_backward_tiny<T, 4>), dim3((unsigned)((batch + MPW - 1) / MPW)), dim3(WAVE), 0, st, L,
                            G, Abar, batch, n);
     } else if (n <= 8) {
         constexpr int MPW = Stage<T, 8>::MPW;
-        hipLaunchKernelGGL((k_backward_tiny<T, 8>), dim3((unsigned)((batch + MPW - 1) / MPW)), dim3(WAVE), 0, st, L,
+        LA_LAUNCH((k_backward_tiny<T, 8>), dim3((unsigned)((batch + MPW - 1) / MPW)), dim3(WAVE), 0, st, L,
                            G, Abar, batch, n);
     } else if (n <= 16) {
         constexpr int MPW = Stage<T, 16>::MPW;
-        hipLaunchKernelGGL((k_backward_tiny<T, 16>), dim3((unsigned)((batch + MPW - 1) / MPW)), dim3(WAVE), 0, st, L,
+        LA_LAUNCH((k_backward_tiny<T, 16>), dim3((unsigned)((batch + MPW - 1) / MPW)), dim3(WAVE), 0, st, L,
                            G, Abar, batch, n);
     } else {
         // 16 lanes per matrix, two rows per lane.  In fp64 the kernel needs 294 registers; the overflow lives in
         // accumulation registers (hence the guarded broadcast multiply-adds), which still beats 32 lanes per
         // matrix with ds_bpermute broadcasts by 2.5 times (16384 matrices of n = 32: 357 -> 140 us).
-        hipLaunchKernelGGL((k_backward_tiny2<T>), dim3((unsigned)((batch + 3) / 4)), dim3(WAVE), 0, st, L, G, Abar,
+        LA_LAUNCH((k_backward_tiny2<T>), dim3((unsigned)((batch + 3) / 4)), dim3(WAVE), 0, st, L, G, Abar,
                            batch, n);
     }
     return launch_check("backward_tiny");

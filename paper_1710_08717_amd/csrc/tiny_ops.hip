@@ -177,10 +177,10 @@ static la_status launch_tri_tiny_g(bool solve, View<const T> Lam, const T *Bin, 
     constexpr int MPW = Stage<T, G>::MPW;
     const dim3 grid((unsigned)((batch + MPW - 1) / MPW));
     if (solve)
-        hipLaunchKernelGGL((k_tri_tiny<T, G, true>), grid, dim3(WAVE), 0, st, Lam, Bin, Bout, batch, n, m, fwd ? 1 : 0,
+        LA_LAUNCH((k_tri_tiny<T, G, true>), grid, dim3(WAVE), 0, st, Lam, Bin, Bout, batch, n, m, fwd ? 1 : 0,
                            img_tr ? 1 : 0, alpha);
     else
-        hipLaunchKernelGGL((k_tri_tiny<T, G, false>), grid, dim3(WAVE), 0, st, Lam, Bin, Bout, batch, n, m, fwd ? 1 : 0,
+        LA_LAUNCH((k_tri_tiny<T, G, false>), grid, dim3(WAVE), 0, st, Lam, Bin, Bout, batch, n, m, fwd ? 1 : 0,
                            img_tr ? 1 : 0, alpha);
     return launch_check("tri_tiny");
 }
@@ -343,10 +343,10 @@ la_status launch_outer_tiny(bool img_tr, int tri, T alpha, int64_t batch, int n,
         constexpr int MPW = Stage<T, GG>::MPW;                                                                            \
         const dim3 grid((unsigned)((batch + MPW - 1) / MPW));                                                             \
         if (images == 2)                                                                                                  \
-            hipLaunchKernelGGL((k_syrk_tiny<T, GG, true>), grid, blk, lds(GG, Stage<T, GG>::ELEMS), st, U, V, C, batch, n, \
+            LA_LAUNCH((k_syrk_tiny<T, GG, true>), grid, blk, lds(GG, Stage<T, GG>::ELEMS), st, U, V, C, batch, n, \
                                k, itr, tri, alpha);                                                                       \
         else                                                                                                              \
-            hipLaunchKernelGGL((k_syrk_tiny<T, GG, false>), grid, blk, lds(GG, Stage<T, GG>::ELEMS), st, U, V, C, batch,   \
+            LA_LAUNCH((k_syrk_tiny<T, GG, false>), grid, blk, lds(GG, Stage<T, GG>::ELEMS), st, U, V, C, batch,   \
                                n, k, itr, tri, alpha);                                                                    \
     } while (0)
     if (n <= 4)
@@ -471,13 +471,13 @@ la_status launch_gemm2_tiny(int ta, int tb, T alpha, int64_t batch, int m, int n
         return LA_ERR_UNSUPPORTED;
     const int d = m > k ? m : k;
     if (d <= 4)
-        hipLaunchKernelGGL((k_gemm2_tiny<T, 4>), dim3((unsigned)((batch + 15) / 16)), dim3(WAVE), 0, st, A, B, C, batch, m, n,
+        LA_LAUNCH((k_gemm2_tiny<T, 4>), dim3((unsigned)((batch + 15) / 16)), dim3(WAVE), 0, st, A, B, C, batch, m, n,
                            k, ta, tb, alpha);
     else if (d <= 8)
-        hipLaunchKernelGGL((k_gemm2_tiny<T, 8>), dim3((unsigned)((batch + 7) / 8)), dim3(WAVE), 0, st, A, B, C, batch, m, n, k,
+        LA_LAUNCH((k_gemm2_tiny<T, 8>), dim3((unsigned)((batch + 7) / 8)), dim3(WAVE), 0, st, A, B, C, batch, m, n, k,
                            ta, tb, alpha);
     else
-        hipLaunchKernelGGL((k_gemm2_tiny<T, 16>), dim3((unsigned)((batch + 3) / 4)), dim3(WAVE), 0, st, A, B, C, batch, m, n,
+        LA_LAUNCH((k_gemm2_tiny<T, 16>), dim3((unsigned)((batch + 3) / 4)), dim3(WAVE), 0, st, A, B, C, batch, m, n,
                            k, ta, tb, alpha);
     return launch_check("gemm2_tiny");
 }
@@ -558,13 +558,13 @@ la_status launch_symm_tiny(bool img_tr, T alpha, int64_t batch, int n, int k, Vi
         return LA_ERR_UNSUPPORTED;
     const int itr = img_tr ? 1 : 0;
     if (n <= 4)
-        hipLaunchKernelGGL((k_symm_tiny<T, 4>), dim3((unsigned)((batch + 15) / 16)), dim3(WAVE), 0, st, Gb, A, Out, batch, n, k,
+        LA_LAUNCH((k_symm_tiny<T, 4>), dim3((unsigned)((batch + 15) / 16)), dim3(WAVE), 0, st, Gb, A, Out, batch, n, k,
                            itr, alpha);
     else if (n <= 8)
-        hipLaunchKernelGGL((k_symm_tiny<T, 8>), dim3((unsigned)((batch + 7) / 8)), dim3(WAVE), 0, st, Gb, A, Out, batch, n, k,
+        LA_LAUNCH((k_symm_tiny<T, 8>), dim3((unsigned)((batch + 7) / 8)), dim3(WAVE), 0, st, Gb, A, Out, batch, n, k,
                            itr, alpha);
     else
-        hipLaunchKernelGGL((k_symm_tiny<T, 16>), dim3((unsigned)((batch + 3) / 4)), dim3(WAVE), 0, st, Gb, A, Out, batch, n, k,
+        LA_LAUNCH((k_symm_tiny<T, 16>), dim3((unsigned)((batch + 3) / 4)), dim3(WAVE), 0, st, Gb, A, Out, batch, n, k,
                            itr, alpha);
     return launch_check("symm_tiny");
 }
@@ -652,13 +652,13 @@ la_status launch_potri_tiny(View<const T> Lam, View<T> B, int64_t batch, int n, 
         return LA_ERR_UNSUPPORTED;
     if (n <= 4) {
         constexpr int MPW = Stage<T, 4>::MPW;
-        hipLaunchKernelGGL((k_potri_tiny<T, 4>), dim3((unsigned)((batch + MPW - 1) / MPW)), dim3(WAVE), 0, st, Lam, B, batch, n);
+        LA_LAUNCH((k_potri_tiny<T, 4>), dim3((unsigned)((batch + MPW - 1) / MPW)), dim3(WAVE), 0, st, Lam, B, batch, n);
     } else if (n <= 8) {
         constexpr int MPW = Stage<T, 8>::MPW;
-        hipLaunchKernelGGL((k_potri_tiny<T, 8>), dim3((unsigned)((batch + MPW - 1) / MPW)), dim3(WAVE), 0, st, Lam, B, batch, n);
+        LA_LAUNCH((k_potri_tiny<T, 8>), dim3((unsigned)((batch + MPW - 1) / MPW)), dim3(WAVE), 0, st, Lam, B, batch, n);
     } else {
         constexpr int MPW = Stage<T, 16>::MPW;
-        hipLaunchKernelGGL((k_potri_tiny<T, 16>), dim3((unsigned)((batch + MPW - 1) / MPW)), dim3(WAVE), 0, st, Lam, B, batch, n);
+        LA_LAUNCH((k_potri_tiny<T, 16>), dim3((unsigned)((batch + MPW - 1) / MPW)), dim3(WAVE), 0, st, Lam, B, batch, n);
     }
     return launch_check("potri_tiny");
 }

@@ -81,3 +81,50 @@ def test_binding_refuses_cpu_tensors():
 
     with pytest.raises(la.LaError):
         la.potrf(torch.eye(4)[None])
+
+
+def test_workspace_sizes_are_host_only_and_cover_the_blocked_paths(lib):
+    lib.la_workspace_bytes.restype = ctypes.c_size_t
+    POTRF, BACKWARD, TRSM, TRMM, SYRK = 0, 1, 2, 3, 4
+    # the register / one-workgroup paths need none
+    for (dt, batch, n) in [(0, 65536, 16), (1, 16, 32), (0, 256, 128), (1, 7, 64)]:
+        assert lib.la_workspace_bytes(POTRF, dt, batch, n, 0, 0) == 0
+    assert lib.la_workspace_bytes(BACKWARD, 0, 256, 128, 0, 0) == 0
+    assert lib.la_workspace_bytes(BACKWARD, 1, 16, 96, 0, 0) == 0
+    assert lib.la_workspace_bytes(TRSM, 1, 16, 128, 48, 0) == 0
+    # the blocked paths: a few matrices' worth, growing with the problem
+    for dt, es in ((0, 4), (1, 8)):
+        prev = 0
+        for n in (256, 512, 1024, 4096, 8192):
+            w = lib.la_workspace_bytes(POTRF, dt, 1, n, 0, 0)
+            assert 2 * n * n * es <= w <= 3 * n * n * es + (64 << 20)
+            assert w > prev and w % 256 == 0
+            prev = w
+        assert lib.la_workspace_bytes(BACKWARD, dt, 32, 512, 0, 0) >= 2 * 32 * 512 * 512 * es
+        assert lib.la_workspace_bytes(TRSM, dt, 32, 512, 64, 0) >= 32 * 512 * 512 * es
+    # bad arguments
+    assert lib.la_workspace_bytes(99, 0, 1, 512, 0, 0) == 0
+    assert lib.la_workspace_bytes(POTRF, 5, 1, 512, 0, 0) == 0
+    assert lib.la_workspace_bytes(POTRF, 0, -1, 512, 0, 0) == 0
+
+
+def test_blocked_call_without_enough_workspace_is_refused_before_any_launch(lib):
+    WORKSPACE, INVALID = 4, 1
+    p = ctypes.c_void_p(1 << 30)
+    q = ctypes.c_void_p(2 << 30)
+    w = ctypes.c_void_p(3 << 30)
+    none = ctypes.c_void_p(0)
+    n = 512
+    lib.la_workspace_bytes.restype = ctypes.c_size_t
+    need = lib.la_workspace_bytes(0, 1, 1, n, 0, 0)
+    assert need > 0
+    # the plain form is the _ws form without a workspace
+    assert lib.la_potrf_batched(1, 1, 1, n, p, q, none, none) == WORKSPACE
+    assert b"workspace" in lib.la_last_error()
+    assert lib.la_potrf_batched_ws(1, 1, 1, n, p, q, none, none, 0, none) == WORKSPACE
+    assert lib.la_potrf_batched_ws(1, 1, 1, n, p, q, none, w, need - 256, none) == WORKSPACE
+    assert lib.la_potrf_backward(1, 1, 1, n, p, q, w, none) == WORKSPACE
+    assert lib.la_trsm_batched(1, 1, 0, 0, 1.0, 1, n, 64, p, q, w, none) == WORKSPACE
+    # misaligned workspace, workspace over an operand
+    assert lib.la_potrf_batched_ws(1, 1, 1, n, p, q, none, ctypes.c_void_p((3 << 30) + 8), need, none) == INVALID
+    assert lib.la_potrf_batched_ws(1, 1, 1, n, p, q, none, ctypes.c_void_p((1 << 30) + 256), need, none) == INVALID

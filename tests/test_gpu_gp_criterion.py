@@ -112,9 +112,9 @@ def test_gp_criterion_reports_a_failing_pivot_and_bad_arguments(la):
     p, z = ctypes.c_void_p(x.data_ptr()), ctypes.c_void_p(0)
     assert lib.la_gp_workspace_bytes(1, 2, 96) == 0 and lib.la_gp_workspace_bytes(0, 2, 128) == 0
     need = lib.la_gp_workspace_bytes(1, 2, 200)
-    assert need == (2 * 200 * 200 * 2 + 2 * 200 * 2) * 8
+    assert need >= (2 * 200 * 200 * 2 + 2 * 200 * 2) * 8  # L, Lbar, z, alpha, plus the scratch of the blocked operators
     q = ctypes.c_void_p(x.data_ptr() + 8 * 200 * 200 * 2)
-    assert lib.la_gp_criterion(1, 2, 200, p, p, p, q, z, z, 0, z) == 1      # workspace missing
+    assert lib.la_gp_criterion(1, 2, 200, p, p, p, q, z, z, 0, z) == 4      # workspace missing (LA_ERR_WORKSPACE)
     assert lib.la_gp_criterion(1, 2, 40, p, p, z, q, z, z, 0, z) == 1       # no loss buffer
     assert lib.la_gp_criterion(5, 2, 40, p, p, p, q, z, z, 0, z) == 1       # bad dtype
     assert lib.la_gp_criterion(1, 0, 40, z, z, z, z, z, z, 0, z) == 0       # empty batch
