@@ -100,6 +100,22 @@ la_status la_potrf_batched_ws(la_dtype dt, int lower, int64_t batch, int n, cons
                            int32_t *info, void *workspace,
         size_t workspace_bytes, void *stream);
 
+/* la_potrf_batched for callers that cannot allocate device memory or pass a workspace: code under
+ * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, results
+ * and errors as la_potrf_batched; the scratch of the blocked path (n > 128) is a static array of
+ * LA_NOALLOC_SCRATCH_BYTES in device memory that every GPU the library is loaded on holds until the
+ * process ends.  No hipMalloc / hipFree, no allocating library call.  A problem whose
+ * la_workspace_bytes(LA_OP_POTRF, ...) exceeds that size is refused with LA_ERR_WORKSPACE (text in
+ * la_last_error()) before anything is launched: in fp64 one matrix up to n = 1672, or any batch with
+ * batch * n * n <= 2.79e6; twice that in fp32 (above 23e6 elements per batch or n >= 4096 the
+ * limit is a third lower).  All calls on one GPU share that array: calls that may run at the same time on
+ * one GPU (different streams or threads) race and must be serialised by the caller; successive
+ * calls on one stream are fine, the array needs no clearing between them.  The first call on a
+ * device looks up the array's address and should therefore be made outside graph capture. */
+#define LA_NOALLOC_SCRATCH_BYTES (64u << 20)
+la_status la_potrf_batched_noalloc(la_dtype dt, int lower, int64_t batch, int n, const void *A, void *L,
+                                   int32_t *info, void *stream);
+
 /* potrf backward (section 4.2, backward of potrf; appendix "potrf"):
  *   Abar = 1/2 L^{-T} copyltu(L^T Lbar) L^{-1}                      (lower != 0)
  *   Abar = 1/2 R^{-1} copyutl(Rbar R^T) R^{-T}                      (lower == 0)

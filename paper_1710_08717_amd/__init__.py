@@ -8,6 +8,7 @@ library is missing, importing the binding raises.
 """
 from .binding import (  # noqa: F401
     LaError,
+    potrf_noalloc,
     workspace_bytes,
     gemm2,
     gemm2_backward,
@@ -31,4 +32,4 @@ from .binding import (  # noqa: F401
 )
 
 __all__ = ["potrf", "potrf_backward", "trsm", "trmm", "syrk", "trsm_backward", "trmm_backward", "syrk_backward", "gemm2_backward", "potri", "potri_backward", "sgp_criterion", "kalman_filter", "gp_criterion", "sumlogdiag",
-           "gp_glue", "gemm2", "load", "lib_path", "LaError", "workspace_bytes"]
+           "gp_glue", "gemm2", "load", "lib_path", "LaError", "workspace_bytes", "potrf_noalloc"]

@@ -22,7 +22,7 @@ SYMBOLS = [
     "la_last_error", "la_version",
     "la_workspace_bytes", "la_potrf_batched_ws", "la_potrf_backward_ws", "la_trsm_batched_ws", "la_trmm_batched_ws",
     "la_syrk_batched_ws", "la_gemm2_batched_ws", "la_trsm_backward_ws", "la_trmm_backward_ws", "la_syrk_backward_ws",
-    "la_gemm2_backward_ws", "la_potri_ws", "la_potri_backward_ws",
+    "la_gemm2_backward_ws", "la_potri_ws", "la_potri_backward_ws", "la_potrf_batched_noalloc",
 ]
 
 # la_op of include/la.h
@@ -82,6 +82,8 @@ def load():
     lib.la_version.restype = i32
     for name in SYMBOLS[:7]:
         getattr(lib, name).restype = i32
+    lib.la_potrf_batched_noalloc.argtypes = lib.la_potrf_batched.argtypes
+    lib.la_potrf_batched_noalloc.restype = i32
     lib.la_workspace_bytes.argtypes = [i32, i32, i64, i32, i32, i32]
     lib.la_workspace_bytes.restype = ctypes.c_size_t
     # the _ws form of an entry point: its arguments with (workspace, workspace_bytes) before the stream
@@ -179,6 +181,23 @@ def potrf(A, lower=True, out=None, info=None, workspace=None):
         _check(load().la_potrf_batched_ws(_dt(A), int(lower), _batch(A), n, _ptr(A), _ptr(L), _ptr(info), wp, wb,
                                           _stream(A)), "la_potrf_batched_ws")
     return L
+
+
+NOALLOC_SCRATCH_BYTES = 64 << 20  # LA_NOALLOC_SCRATCH_BYTES of include/la.h
+
+
+def potrf_noalloc(A, out, lower=True, info=None):
+    """la_potrf_batched_noalloc: potrf on the library's static scratch array; the caller supplies ``out``
+    (which may be ``A``), nothing is allocated here or in the library."""
+    _chk(A, out)
+    n = A.shape[-1]
+    assert A.shape[-2] == n and out.shape == A.shape
+    if info is not None:
+        assert info.dtype == torch.int32 and info.is_cuda and info.numel() == _batch(A)
+    with torch.cuda.device(A.device):
+        _check(load().la_potrf_batched_noalloc(_dt(A), int(lower), _batch(A), n, _ptr(A), _ptr(out), _ptr(info),
+                                               _stream(A)), "la_potrf_batched_noalloc")
+    return out
 
 
 def potrf_backward(L, Lbar, lower=True, out=None, workspace=None):

@@ -1235,6 +1235,52 @@ la_status la_potrf_batched_ws(la_dtype dt, int lower, int64_t batch, int n, cons
     return potrf_call(dt, lower, batch, n, A, L, info, workspace, workspace_bytes, stream);
 }
 
+// ---------------------------------------------------------------------------------
+// potrf for callers that cannot allocate: the scratch of the blocked path is a static array in
+// device memory, one copy per GPU, held from the moment the library is loaded on that GPU.
+// Its device address is looked up once per device (first call on that device) and passed to the
+// kernels like any workspace; the host-side name of the array is not an address and is never
+// handed to a kernel or a copy.
+// ---------------------------------------------------------------------------------
+static __device__ __attribute__((used)) __align__(256) unsigned char scratch[LA_NOALLOC_SCRATCH_BYTES];
+static std::mutex g_scratch_mutex;
+static void *g_scratch_ptr[64] = {};
+
+la_status la_potrf_batched_noalloc(la_dtype dt, int lower, int64_t batch, int n, const void *A, void *L, int32_t *info,
+                                   void *stream)
+{
+    if (bad_dtype(dt) || batch < 0 || n < 0 || n > MAX_N)
+        return LA_ERR_INVALID_ARG;
+    if (batch == 0 || n == 0)
+        return LA_OK;
+    int dev = 0;
+    LA_HIP(hipGetDevice(&dev));
+    if (dev < 0 || dev >= 64)
+        return LA_ERR_UNSUPPORTED;
+    void *ptr = nullptr;
+    {
+        std::lock_guard<std::mutex> lock(g_scratch_mutex);
+        if (!g_scratch_ptr[dev]) {
+            void *p = nullptr;
+            LA_HIP(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+            if (!p) {
+                snprintf(g_err, sizeof(g_err), "hipGetSymbolAddress returned no address for the static scratch array");
+                return LA_ERR_RUNTIME;
+            }
+            g_scratch_ptr[dev] = p;
+        }
+        ptr = g_scratch_ptr[dev];
+    }
+    const la_status s = potrf_call(dt, lower, batch, n, A, L, info, ptr, (size_t)LA_NOALLOC_SCRATCH_BYTES, stream);
+    if (s == LA_ERR_WORKSPACE) {
+        const size_t need = la_workspace_bytes(LA_OP_POTRF, dt, batch, n, 0, 0);
+        snprintf(g_err, sizeof(g_err),
+                 "la_potrf_batched_noalloc: batch %lld of n = %d needs %zu bytes of scratch, the static buffer holds %zu",
+                 (long long)batch, n, need, (size_t)LA_NOALLOC_SCRATCH_BYTES);
+    }
+    return s;
+}
+
 la_status la_potrf_backward(la_dtype dt, int lower, int64_t batch, int n, const void *L, const void *Lbar, void *Abar,
                             void *stream)
 {

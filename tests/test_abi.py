@@ -128,3 +128,6 @@ def test_blocked_call_without_enough_workspace_is_refused_before_any_launch(lib)
     # misaligned workspace, workspace over an operand
     assert lib.la_potrf_batched_ws(1, 1, 1, n, p, q, none, ctypes.c_void_p((3 << 30) + 8), need, none) == INVALID
     assert lib.la_potrf_batched_ws(1, 1, 1, n, p, q, none, ctypes.c_void_p((1 << 30) + 256), need, none) == INVALID
+    # the noalloc form checks its arguments before it looks at the device
+    assert lib.la_potrf_batched_noalloc(7, 1, 1, 4, p, q, none, none) == INVALID
+    assert lib.la_potrf_batched_noalloc(1, 1, 0, 4, none, none, none, none) == 0
