@@ -12,8 +12,11 @@
  *
  * Every result here is exactly defined (the factor with positive diagonal is
  * unique; the rest are closed-form matrix expressions), so each routine is the
- * definition written as loops.  The only liberty taken is the order of the loop
- * nest (so that inner loops walk along rows); there is no tiling, no fusion.
+ * definition written as loops.  The only liberties taken are the order of the loop
+ * nest (so that inner loops walk along rows) and, for one big matrix, handing its
+ * independent vectors (right-hand sides, rows of a product) to the threads in
+ * chunks; every sum keeps its terms and their order.  There is no tiling of the
+ * sums and no fusion of steps.
  *
  * Pins: every function below is pinned by tests/test_oracle_*.py against closed
  * forms, brute-force determinants / inverses, finite differences and the adjoint
@@ -138,6 +141,30 @@ int orc_potrf(int lower, int64_t batch, int n, const double *A, double *L, int32
  *   rightside != 0:  B = alpha * A t(L),   A and B are m x n
  * alpha is not in the paper's statement (alpha = 1 reproduces it); it scales the
  * result the way it does for gemm2 and syrk.  B may be the same memory as A. */
+/* Entries of t(L) laid out with the FIRST index contiguous: Tc[c * n + k] = T(k,c).  The sums of
+ * the right-side operators run over k for a fixed c, i.e. down a column of t(L); reading them
+ * from this copy (made from n = 64 on) keeps those sums on consecutive addresses.  The terms and
+ * their order are those of the plain loop.  NULL if not made. */
+static double *first_index_contiguous(int lower, int trans, int n, const double *L, int parallel)
+{
+    if (n < 64)
+        return NULL;
+    double *Tc = (double *)malloc((size_t)n * n * sizeof(double));
+    if (!Tc)
+        return NULL;
+#pragma omp parallel for schedule(static) if (parallel)
+    for (int c = 0; c < n; ++c)
+        for (int k = 0; k < n; ++k)
+            Tc[(size_t)c * n + k] = tri_at(L, n, lower, trans, k, c);
+    return Tc;
+}
+
+/* The m vectors a triangular operator acts on (columns of A for a left operator, rows for a
+ * right one) are independent.  For one big matrix they are handed to the threads in chunks of
+ * VCHUNK, and a chunk walks through t(L) once for all its vectors; below that size a single
+ * chunk holds all of them.  Every sum keeps its terms and their order. */
+#define VCHUNK 64
+
 static void trmm_one(int lower, int trans, int rightside, double alpha, int n, int m,
                      const double *L, const double *A, double *B, double *tmp)
 {
@@ -145,35 +172,53 @@ static void trmm_one(int lower, int trans, int rightside, double alpha, int n, i
      * entries on the other side of the diagonal are structural zeros and take no
      * part in the sums (so nothing stored there, or paired with it, is touched). */
     int eff_lower = (lower != 0) != (trans != 0);
+    int big = ((double)n * n * m > 5e7);
+    int chunk = big ? VCHUNK : m;
+    int nchunk = (m + chunk - 1) / chunk;
     if (!rightside) {
-        /* row i of the product = sum_k T(i,k) * row k of A */
-        for (int i = 0; i < n; ++i) {
-            double *ti = tmp + (size_t)i * m;
-            for (int c = 0; c < m; ++c)
-                ti[c] = 0.0;
-            int k0 = eff_lower ? 0 : i;
-            int k1 = eff_lower ? i + 1 : n;
-            for (int k = k0; k < k1; ++k) {
-                double t = tri_at(L, n, lower, trans, i, k);
-                const double *ak = A + (size_t)k * m;
-                for (int c = 0; c < m; ++c)
-                    ti[c] += t * ak[c];
+        /* row i of the product = sum_k T(i,k) * row k of A, on the columns of one chunk */
+#pragma omp parallel for schedule(dynamic) if (big)
+        for (int q = 0; q < nchunk; ++q) {
+            int c0 = q * chunk, c1 = c0 + chunk < m ? c0 + chunk : m;
+            for (int i = 0; i < n; ++i) {
+                double *ti = tmp + (size_t)i * m;
+                for (int c = c0; c < c1; ++c)
+                    ti[c] = 0.0;
+                int k0 = eff_lower ? 0 : i;
+                int k1 = eff_lower ? i + 1 : n;
+                for (int k = k0; k < k1; ++k) {
+                    double t = tri_at(L, n, lower, trans, i, k);
+                    const double *ak = A + (size_t)k * m;
+                    for (int c = c0; c < c1; ++c)
+                        ti[c] += t * ak[c];
+                }
             }
         }
     } else {
-        /* entry (r,c) of the product = sum_k a_rk T(k,c) */
-        for (int r = 0; r < m; ++r) {
-            const double *ar = A + (size_t)r * n;
-            double *tr = tmp + (size_t)r * n;
+        /* entry (r,c) of the product = sum_k a_rk T(k,c), for the rows r of one chunk */
+        double *Tc = first_index_contiguous(lower, trans, n, L, big);
+#pragma omp parallel for schedule(dynamic) if (big)
+        for (int q = 0; q < nchunk; ++q) {
+            int r0 = q * chunk, r1 = r0 + chunk < m ? r0 + chunk : m;
             for (int c = 0; c < n; ++c) {
-                double s = 0.0;
                 int k0 = eff_lower ? c : 0;
                 int k1 = eff_lower ? n : c + 1;
-                for (int k = k0; k < k1; ++k)
-                    s += ar[k] * tri_at(L, n, lower, trans, k, c);
-                tr[c] = s;
+                for (int r = r0; r < r1; ++r) {
+                    const double *ar = A + (size_t)r * n;
+                    double s = 0.0;
+                    if (Tc) {
+                        const double *tc = Tc + (size_t)c * n;
+                        for (int k = k0; k < k1; ++k)
+                            s += ar[k] * tc[k];
+                    } else {
+                        for (int k = k0; k < k1; ++k)
+                            s += ar[k] * tri_at(L, n, lower, trans, k, c);
+                    }
+                    tmp[(size_t)r * n + c] = s;
+                }
             }
         }
+        free(Tc);
     }
     for (size_t e = 0; e < (size_t)n * m; ++e)
         B[e] = alpha * tmp[e];
@@ -190,7 +235,7 @@ int orc_trmm(int lower, int trans, int rightside, double alpha, int64_t batch, i
         return ORC_ERR_INVALID_ARG;
     size_t nn = (size_t)n * n, nm = (size_t)n * m;
     int fail = 0;
-#pragma omp parallel for schedule(dynamic)
+#pragma omp parallel for schedule(dynamic) if (batch > 1)
     for (int64_t b = 0; b < batch; ++b) {
         double *tmp = (double *)malloc(nm * sizeof(double));
         if (!tmp) {
@@ -235,31 +280,43 @@ static void trsm_left_cols(int lower, int trans, double alpha, int n, int m, con
     }
 }
 
-static void trsm_right_row(int lower, int trans, double alpha, int n, const double *L,
-                           const double *a, double *x)
+static void trsm_right_rows(int lower, int trans, double alpha, int n, const double *L,
+                            const double *Tc, const double *A, double *B, int r0, int r1)
 {
-    /* x t(L) = alpha a for one row: sum_k x_k T(k,c) = alpha a_c.  Lower T: T(k,c) != 0
-     * for k >= c, so c runs n-1 .. 0; upper T: c runs 0 .. n-1. */
+    /* x t(L) = alpha a for the rows [r0, r1): sum_k x_k T(k,c) = alpha a_c.  Lower T: T(k,c) != 0
+     * for k >= c, so c runs n-1 .. 0; upper T: c runs 0 .. n-1.
+     * Tc, if given, holds T with the summation index contiguous (first_index_contiguous). */
     int eff_lower = (lower != 0) != (trans != 0);
     for (int step = 0; step < n; ++step) {
         int c = eff_lower ? n - 1 - step : step;
-        double s = alpha * a[c];
         int k0 = eff_lower ? c + 1 : 0;
         int k1 = eff_lower ? n : c;
-        for (int k = k0; k < k1; ++k)
-            s -= x[k] * tri_at(L, n, lower, trans, k, c);
-        x[c] = s / tri_at(L, n, lower, trans, c, c);
+        for (int r = r0; r < r1; ++r) {
+            const double *a = A + (size_t)r * n;
+            double *x = B + (size_t)r * n;
+            double s = alpha * a[c];
+            if (Tc) {
+                const double *tc = Tc + (size_t)c * n;
+                for (int k = k0; k < k1; ++k)
+                    s -= x[k] * tc[k];
+                x[c] = s / tc[c];
+            } else {
+                for (int k = k0; k < k1; ++k)
+                    s -= x[k] * tri_at(L, n, lower, trans, k, c);
+                x[c] = s / tri_at(L, n, lower, trans, c, c);
+            }
+        }
     }
 }
 
 /* The right-hand sides (columns for a left solve, rows for a right solve) are
- * independent; for one big matrix they are shared out over threads, nothing else. */
+ * independent; for one big matrix they are shared out over threads in chunks, nothing else. */
 static void trsm_one(int lower, int trans, int rightside, double alpha, int n, int m,
                      const double *L, const double *A, double *B)
 {
     int big = ((double)n * n * m > 5e7);
     if (!rightside) {
-        const int chunk = 64;
+        const int chunk = VCHUNK;
         int nchunk = (m + chunk - 1) / chunk;
 #pragma omp parallel for schedule(dynamic) if (big)
         for (int q = 0; q < nchunk; ++q) {
@@ -267,9 +324,15 @@ static void trsm_one(int lower, int trans, int rightside, double alpha, int n, i
             trsm_left_cols(lower, trans, alpha, n, m, L, A, B, c0, c1);
         }
     } else {
+        double *Tc = first_index_contiguous(lower, trans, n, L, big);
+        int chunk = big ? 8 : m;  /* rows that share one pass over t(L) */
+        int nchunk = (m + chunk - 1) / chunk;
 #pragma omp parallel for schedule(dynamic) if (big)
-        for (int r = 0; r < m; ++r)
-            trsm_right_row(lower, trans, alpha, n, L, A + (size_t)r * n, B + (size_t)r * n);
+        for (int q = 0; q < nchunk; ++q) {
+            int r0 = q * chunk, r1 = r0 + chunk < m ? r0 + chunk : m;
+            trsm_right_rows(lower, trans, alpha, n, L, Tc, A, B, r0, r1);
+        }
+        free(Tc);
     }
 }
 
@@ -283,7 +346,7 @@ int orc_trsm(int lower, int trans, int rightside, double alpha, int64_t batch, i
     if (!L || !A || !B)
         return ORC_ERR_INVALID_ARG;
     size_t nn = (size_t)n * n, nm = (size_t)n * m;
-#pragma omp parallel for schedule(dynamic)
+#pragma omp parallel for schedule(dynamic) if (batch > 1)
     for (int64_t b = 0; b < batch; ++b)
         trsm_one(lower, trans, rightside, alpha, n, m, L + b * nn, A + b * nm, B + b * nm);
     return ORC_OK;
@@ -531,7 +594,7 @@ int orc_potri(int lower, int64_t batch, int n, const double *L, double *B)
         return ORC_ERR_INVALID_ARG;
     size_t nn = (size_t)n * n;
     int fail = 0;
-#pragma omp parallel for schedule(dynamic)
+#pragma omp parallel for schedule(dynamic) if (batch > 1)
     for (int64_t b = 0; b < batch; ++b) {
         double *E = (double *)malloc(nn * sizeof(double));
         if (!E) {
@@ -566,7 +629,7 @@ int orc_potri_backward(int lower, int64_t batch, int n, const double *L, const d
         return ORC_ERR_INVALID_ARG;
     size_t nn = (size_t)n * n;
     int fail = 0;
-#pragma omp parallel for schedule(dynamic)
+#pragma omp parallel for schedule(dynamic) if (batch > 1)
     for (int64_t b = 0; b < batch; ++b) {
         double *M = (double *)malloc(nn * sizeof(double));
         if (!M) {
@@ -674,7 +737,7 @@ int orc_potrf_backward(int lower, int64_t batch, int n, const double *L, const d
         return ORC_ERR_INVALID_ARG;
     size_t nn = (size_t)n * n;
     int fail = 0;
-#pragma omp parallel for schedule(dynamic)
+#pragma omp parallel for schedule(dynamic) if (batch > 1)
     for (int64_t b = 0; b < batch; ++b) {
         double *tmp = (double *)malloc(nn * sizeof(double));
         if (!tmp) {

@@ -294,6 +294,36 @@ def test_trmm_against_dense_product(orc, lower, trans, rightside, n, m):
 
 
 @pytest.mark.parametrize("lower,trans,rightside", FLAGS)
+@pytest.mark.parametrize("n,m,batch", [(96, 40, 2), (380, 400, 1)])
+def test_trsm_trmm_larger_sizes_against_scipy_and_dense_product(orc, lower, trans, rightside, n, m, batch):
+    """From n = 64 on the right-side operators read t(L) from a copy with the summation index
+    contiguous, and one matrix with n * n * m > 5e7 hands its vectors to the threads in chunks:
+    both against scipy's triangular solve and numpy's dense product, NaN in the unread triangle."""
+    from scipy.linalg import solve_triangular
+
+    rng = np.random.default_rng(7000 + n)
+    T = rand_tri(rng, n, lower, batch=batch)
+    T[:, np.arange(n), np.arange(n)] = 1.5 + np.abs(T[:, np.arange(n), np.arange(n)])  # keep the solves tame
+    T[:, np.tril_indices(n, -1)[0], np.tril_indices(n, -1)[1]] *= 0.1
+    T[:, np.triu_indices(n, 1)[0], np.triu_indices(n, 1)[1]] *= 0.1
+    junk = T.copy()
+    mask = np.triu_indices(n, 1) if lower else np.tril_indices(n, -1)
+    junk[:, mask[0], mask[1]] = np.nan
+    A = rng.standard_normal((batch, m, n) if rightside else (batch, n, m))
+    X = orc.trsm(junk, A, lower=lower, trans=trans, rightside=rightside, alpha=0.5)
+    P = orc.trmm(junk, A, lower=lower, trans=trans, rightside=rightside, alpha=0.5)
+    for b in range(batch):
+        if rightside:
+            x = solve_triangular(T[b], 0.5 * A[b].T, lower=lower, trans=0 if trans else 1).T
+            pr = 0.5 * A[b] @ op(T[b], trans)
+        else:
+            x = solve_triangular(T[b], 0.5 * A[b], lower=lower, trans=1 if trans else 0)
+            pr = 0.5 * op(T[b], trans) @ A[b]
+        assert relerr(X[b], x) < 1e-12
+        assert relerr(P[b], pr) < 1e-13
+
+
+@pytest.mark.parametrize("lower,trans,rightside", FLAGS)
 def test_trmm_undoes_trsm(orc, lower, trans, rightside):
     rng = np.random.default_rng(6)
     n, m = 24, 5
