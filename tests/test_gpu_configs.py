@@ -135,7 +135,7 @@ def test_c3_gp_marginal_likelihood(la, orc, lengthscale, jitter):
     # and the textbook gradient 1/2 (A^-1 - alpha alpha^T) as a second opinion on the whole chain
     Ai = np.linalg.inv(w["A"][:4].astype(np.float64))
     a = np.einsum("bij,bj->bi", Ai, w["y"][:4].astype(np.float64))
-    assert relerr(host(Abar)[:4], 0.5 * (Ai - a[:, :, None] * a[:, None, :])) <= 20 * tol
+    assert relerr(host(Abar)[:4], 0.5 * (Ai - a[:, :, None] * a[:, None, :])) <= tol
 
 
 def test_c4_medium_blocked(la, orc):
@@ -201,11 +201,13 @@ def test_c5_large_single(la, orc, dtype):
     L64 = Lh.astype(np.float64)
     scale_a = float(np.max(np.abs(A_h)))
     err_f = max(abs(orc.llt_entry(L64, i, j) - float(A_h[i, j])) for i, j in pts)
-    assert err_f <= 20 * tol * scale_a
+    sys.stderr.write(f"[c5 {dtype}] max |(L L^T - A)_ij| = {err_f:.3e} (scale {scale_a:.3e})\n")
+    assert err_f <= tol * scale_a
     # sampled rows of L X = B (residual of the solve beyond the leading rows)
     rows = [n - 1, n // 2, 5000, 7001]
     resid = L64[rows] @ Xh.astype(np.float64) - R_h[rows]
-    assert np.max(np.abs(resid)) <= 50 * tol * float(np.max(np.abs(R_h)))
+    sys.stderr.write(f"[c5 {dtype}] max |(L X - B)_ij| = {np.max(np.abs(resid)):.3e} (scale {np.max(np.abs(R_h)):.3e})\n")
+    assert np.max(np.abs(resid)) <= tol * float(np.max(np.abs(R_h)))
     # 2 L^T Abar L = copyltu(L^T Lbar) on sampled entries
     Ab64, G64 = Abar_h.astype(np.float64), G_h.astype(np.float64)
     worst, ref_scale = 0.0, 0.0
@@ -214,8 +216,9 @@ def test_c5_large_single(la, orc, dtype):
         rhs = orc.ltlbar_entry(L64, G64, max(i, j), min(i, j))
         worst = max(worst, abs(lhs - rhs))
         ref_scale = max(ref_scale, abs(rhs))
-    assert worst <= 200 * tol * max(ref_scale, 1.0)
+    sys.stderr.write(f"[c5 {dtype}] max |(2 L^T Abar L - copyltu(L^T Lbar))_ij| = {worst:.3e} (scale {ref_scale:.3e})\n")
+    assert worst <= tol * max(ref_scale, 1.0)
     assert np.array_equal(Abar_h, Abar_h.T)
 
     # (c) closed form through every tile
-    assert np.max(np.abs(half_h - 0.5 * np.eye(n))) <= (1e-9 if dtype == "f64" else 5e-3)
+    assert relerr(half_h, 0.5 * np.eye(n)) <= tol

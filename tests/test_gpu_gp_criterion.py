@@ -66,7 +66,7 @@ def test_gp_criterion_parity(la, orc, dtype, batch, n):
     a, info = dev(A), torch.full((batch,), -1, dtype=torch.int32, device="cuda")
     loss, Abar = la.gp_criterion(a, dev(y), info=info)
     torch.cuda.synchronize()
-    tol = 4 * TOL[dtype]
+    tol = TOL[dtype]
     assert np.all(info.cpu().numpy() == 0)
     assert np.array_equal(a.cpu().numpy(), A)
     assert np.max(np.abs(loss.cpu().numpy() - loss_r) / np.maximum(np.abs(loss_r), 1.0)) <= tol
@@ -93,7 +93,7 @@ def test_gp_criterion_c3_and_second_opinion(la, orc):
         assert rel(Abar.cpu().numpy(), Abar_r) <= tol
         Ai = np.linalg.inv(w["A"][:4].astype(np.float64))
         al = np.einsum("bij,bj->bi", Ai, w["y"][:4].astype(np.float64))
-        assert rel(Abar.cpu().numpy()[:4], 0.5 * (Ai - al[:, :, None] * al[:, None, :])) <= 20 * tol
+        assert rel(Abar.cpu().numpy()[:4], 0.5 * (Ai - al[:, :, None] * al[:, None, :])) <= tol
 
 
 def test_gp_criterion_reports_a_failing_pivot_and_bad_arguments(la):

@@ -60,13 +60,13 @@ def test_kalman_parity(la, orc, dtype, shared, batch, T, dh, dv):
     nll, f, F, info = run(la, w)
     tol = TOL[dtype]
     assert np.array_equal(info, ref_info) and np.all(info == 0)
-    assert np.all(np.abs(nll - ref_nll) <= 4 * tol * np.maximum(1.0, np.abs(ref_nll)))
+    assert np.all(np.abs(nll - ref_nll) <= tol * np.maximum(1.0, np.abs(ref_nll)))
     if T > 0:
-        assert rel(f, ref_f) <= 4 * tol
-        assert rel(F, ref_F) <= 4 * tol
+        assert rel(f, ref_f) <= tol
+        assert rel(F, ref_F) <= tol
         # per sequence and step as well, so that one bad item cannot hide in the norm of many
         per = np.linalg.norm((F - ref_F).reshape(batch, T, -1), axis=2) / np.linalg.norm(ref_F.reshape(batch, T, -1), axis=2)
-        assert per.max() <= 20 * tol
+        assert per.max() <= tol
     # likelihood only: same value, no state outputs written
     nll2, f2, F2, _ = run(la, w, want_states=False, with_info=False)
     assert f2 is None and F2 is None
@@ -82,13 +82,13 @@ def test_kalman_many_long_sequences(la, orc, dtype):
     nll, f, F, info = run(la, w)
     tol = TOL[dtype]
     assert np.all(info == 0)
-    assert np.all(np.abs(nll - ref_nll) <= 4 * tol * np.maximum(1.0, np.abs(ref_nll)))
-    assert rel(f, ref_f) <= 4 * tol and rel(F, ref_F) <= 4 * tol
+    assert np.all(np.abs(nll - ref_nll) <= tol * np.maximum(1.0, np.abs(ref_nll)))
+    assert rel(f, ref_f) <= tol and rel(F, ref_F) <= tol
     w = workloads.make_kalman(3, 400, 16, 8, dtype=dtype, shared=False, seed=12)
     ref_nll, ref_f, ref_F, _ = orc.kalman_filter(w["A"], w["B"], w["Sh"], w["Sv"], w["mu0"], w["S0"], w["v"])
     nll, f, F, info = run(la, w)
-    assert np.all(np.abs(nll - ref_nll) <= 4 * tol * np.maximum(1.0, np.abs(ref_nll)))
-    assert rel(f[:, -1], ref_f[:, -1]) <= 4 * tol and rel(F[:, -1], ref_F[:, -1]) <= 4 * tol
+    assert np.all(np.abs(nll - ref_nll) <= tol * np.maximum(1.0, np.abs(ref_nll)))
+    assert rel(f[:, -1], ref_f[:, -1]) <= tol and rel(F[:, -1], ref_F[:, -1]) <= tol
 
 
 @pytest.mark.parametrize("dtype,dh,dv", [("f64", 3, 2), ("f32", 7, 6), ("f32", 12, 9)])  # 4, 8 and 16 lanes per sequence
@@ -100,7 +100,7 @@ def test_kalman_reports_a_failing_pivot(la, orc, dtype, dh, dv):
     assert np.array_equal(info, ref_info) and info[4] == 1 and np.all(np.delete(info, 4) == 0)
     ok = np.delete(np.arange(6), 4)
     ref = orc.kalman_filter(w["A"][ok], w["B"][ok], w["Sh"][ok], w["Sv"][ok], w["mu0"][ok], w["S0"][ok], w["v"][ok])
-    assert np.all(np.abs(nll[ok] - ref[0]) <= 4 * TOL[dtype] * np.maximum(1.0, np.abs(ref[0])))
+    assert np.all(np.abs(nll[ok] - ref[0]) <= TOL[dtype] * np.maximum(1.0, np.abs(ref[0])))
 
 
 def test_kalman_argument_errors(la):

@@ -256,7 +256,7 @@ def test_backward_closed_forms(la, orc):
         idx = np.arange(n)
         D[:, idx, idx] = 1.0 / Lh[:, idx, idx]
         got = host(la.potrf_backward(L, dev(D)))
-        assert relerr(got, 0.5 * np.linalg.inv(A.astype(np.float64))) <= 10 * TOL[dtype]
+        assert relerr(got, 0.5 * np.linalg.inv(A.astype(np.float64))) <= TOL[dtype]
 
 
 # ----------------------------------------------------------------------------

@@ -1,7 +1,6 @@
 """Parity of la_sgp_criterion (sparse-GP criterion of section 3.2 and its gradient, composed of the
 library's operators) against the oracle's plain composition on the same seeded synthetic inputs.
-The criterion is a sum of O(n) terms and the gradients pass through two factorisations, so the
-bounds are the operators' tolerance times a small factor."""
+Every output is held to the operators' own tolerance (relative Frobenius error 1e-10 in fp64, 2e-4 in fp32)."""
 import sys
 
 import numpy as np
@@ -48,7 +47,7 @@ def test_sgp_parity(la, orc, dtype, U, n):
     out = la.sgp_criterion(dev(w["Kuu"]), dev(w["Kuf"]), dev(w["Kff_diag"]), dev(w["y"]), w["noise_var"])
     torch.cuda.synchronize()
     got = {k: v.cpu().numpy() for k, v in out.items()}
-    tol = 20 * TOL[dtype]
+    tol = TOL[dtype]
     assert abs(float(got["phi"][0]) - ref["phi"]) <= tol * max(1.0, abs(ref["phi"]))
     assert abs(float(got["noise_bar"][0]) - ref["noise_bar"]) <= tol * max(1.0, abs(ref["noise_bar"]))
     for key in ("Kuu_bar", "Kuf_bar", "Kff_diag_bar", "y_bar"):
