@@ -314,6 +314,8 @@ def main():
     ap.add_argument("--batch", type=int, default=None)
     ap.add_argument("--n", type=int, default=None)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-secondary", action="store_true",
+                    help="default (C2) run only: skip the blocked configurations C4 and C5-fp64 reported under `secondary`")
     ap.add_argument("--calib-copy", action="store_true",
                     help="also run plain device copies of 256 MiB (reference rows for rocprofv3 --pmc byte counters)")
     args = ap.parse_args()
@@ -338,6 +340,27 @@ def main():
         return bench_kalman(args, la, torch, np, workloads)
     if name == "SMALL":
         return bench_small(args, la, torch, np, workloads)
+    out = run_config(name, args, la, torch, np, workloads)
+    if name == "C2" and not args.no_secondary and args.batch is None and args.n is None and args.dtype is None:
+        # The metric has a second half, "n >= 512 potrf + backward against the fp64 matrix-core peak": the two
+        # blocked configurations run in the same process, same steps and warm-up, and ride along under `secondary`.
+        out["secondary"] = {}
+        for key, cfg, dt in (("C4", "C4", None), ("C5_f64", "C5", "f64")):
+            sub = argparse.Namespace(**vars(args))
+            sub.config, sub.dtype = cfg, dt
+            r = run_config(cfg, sub, la, torch, np, workloads)
+            out["secondary"][key] = {
+                "workload": r["config"]["workload"], "ops": r["config"]["ops"], "dtype": r["dtype"],
+                "steps": r["steps"], "warmup": r["warmup"], "ms_per_step": r["ms_per_step"],
+                "value": r["value"], "unit": r["unit"], "gflops": r["gflops"],
+                "useful_flops_per_step": r["useful_flops_per_step"], "kernel_ms": r["kernel_ms"],
+                "roofline": r["roofline"], "cpu_baseline": r["cpu_baseline"]}
+            torch.cuda.empty_cache()
+    print(json.dumps(out), flush=True)
+
+
+def run_config(name, args, la, torch, np, workloads):
+    """One of the five configurations: returns the JSON record of its run."""
     w = workloads.make(name, batch=args.batch, n=args.n, dtype=args.dtype)
     batch, n, dtype, m = w["batch"], w["n"], w["dtype"], w["m"]
     s = 4 if dtype == "f32" else 8
@@ -374,6 +397,15 @@ def main():
             d["Lb1"] = torch.empty_like(A0)
             d["Lb2"] = torch.empty_like(A0)
         sets.append(d)
+    # one workspace for every call of the step (the calls run one after the other on one stream)
+    from paper_1710_08717_amd import binding as B_
+
+    need = max([la.workspace_bytes(B_.OP_POTRF, A0, batch, n), la.workspace_bytes(B_.OP_POTRF_BACKWARD, A0, batch, n)]
+               + ([la.workspace_bytes(o, A0, batch, n, m) for o in (B_.OP_TRSM, B_.OP_TRMM, B_.OP_TRSM_BACKWARD,
+                                                                    B_.OP_TRMM_BACKWARD)] if m else [])
+               + ([la.workspace_bytes(B_.OP_SYRK_BACKWARD, A0, batch, n, 0, m)] if extra else []))
+    ws = torch.empty(max(need, 256), dtype=torch.uint8, device="cuda")
+    log(f"[bench] workspace for the step's calls: {need / 2 ** 20:.1f} MiB")
     torch.cuda.synchronize()
 
     timers = {}
@@ -394,26 +426,28 @@ def main():
         if fused_gp:  # C3: the whole criterion + gradient is one launch
             call("gp_criterion", lambda: la.gp_criterion(d["A"], d["y"], out=d["Abar"], loss=d["loss"]), timed)
             return
-        call("potrf", lambda: la.potrf(d["A"], out=d["L"]), timed)
+        call("potrf", lambda: la.potrf(d["A"], out=d["L"], workspace=ws), timed)
         if name == "C1":
-            call("trsm", lambda: la.trsm(d["L"], d["rhs"], out=d["X"]), timed)
+            call("trsm", lambda: la.trsm(d["L"], d["rhs"], out=d["X"], workspace=ws), timed)
             call("sumlogdiag", lambda: la.sumlogdiag(d["L"], out=d["sld"]), timed)
         elif name == "C3":
             yv, zv, av = d["y"].view(batch, n, 1), d["z"].view(batch, n, 1), d["alpha"].view(batch, n, 1)
-            call("trsm", lambda: (la.trsm(d["L"], yv, out=zv), la.trsm(d["L"], zv, trans=True, out=av)), timed)
+            call("trsm", lambda: (la.trsm(d["L"], yv, out=zv, workspace=ws), la.trsm(d["L"], zv, trans=True, out=av, workspace=ws)), timed)
             call("gp_glue", lambda: la.gp_glue(d["L"], d["y"], d["z"], d["alpha"], loss=d["loss"], Lbar=d["G"]), timed)
         elif name == "C4":
-            call("trsm", lambda: la.trsm(d["L"], d["rhs"], out=d["X"]), timed)
-            call("trmm", lambda: la.trmm(d["L"], d["X"], out=d["Y"]), timed)
+            call("trsm", lambda: la.trsm(d["L"], d["rhs"], out=d["X"], workspace=ws), timed)
+            call("trmm", lambda: la.trmm(d["L"], d["X"], out=d["Y"], workspace=ws), timed)
             if extra:
-                call("trmm_backward", lambda: la.trmm_backward(d["L"], d["X"], d["Ybar"], out_a=d["Xbar"], out_l=d["Lb1"]),
+                call("trmm_backward", lambda: la.trmm_backward(d["L"], d["X"], d["Ybar"], out_a=d["Xbar"], out_l=d["Lb1"],
+                                                                  workspace=ws),
                      timed)
-                call("trsm_backward", lambda: la.trsm_backward(d["L"], d["X"], d["Xbar"], out_a=d["Rbar"], out_l=d["Lb2"]),
+                call("trsm_backward", lambda: la.trsm_backward(d["L"], d["X"], d["Xbar"], out_a=d["Rbar"], out_l=d["Lb2"],
+                                                                  workspace=ws),
                      timed)
-                call("syrk_backward", lambda: la.syrk_backward(d["rhs"], d["G"], out=d["Sbar"]), timed)
+                call("syrk_backward", lambda: la.syrk_backward(d["rhs"], d["G"], out=d["Sbar"], workspace=ws), timed)
         elif name == "C5":
-            call("trsm", lambda: la.trsm(d["L"], d["rhs"], out=d["X"]), timed)
-        call("backward", lambda: la.potrf_backward(d["L"], d["G"], out=d["Abar"]), timed)
+            call("trsm", lambda: la.trsm(d["L"], d["rhs"], out=d["X"], workspace=ws), timed)
+        call("backward", lambda: la.potrf_backward(d["L"], d["G"], out=d["Abar"], workspace=ws), timed)
 
     for i in range(warmup):
         step(i)
@@ -462,8 +496,12 @@ def main():
         roof = {"bound": "hbm", "kernel": "la_potrf_backward", "achieved": achieved, "peak": HBM_PEAK_GBS,
                 "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": None,
                 "algorithmic_bytes_per_launch": alg_bytes, "avg_launch_ms": kern_ms[dom],
+                "duration_source": "HIP event pair around each launch on the launch stream, averaged over the timed "
+                                   "steps (an event pair adds about 1-2.5 us to a bracketed launch; the rocprofv3 kernel "
+                                   "trace under profiles/ gives the kernel alone)",
                 "potrf_forward": {"achieved": bm["potrf"] * batch / (kern_ms["potrf"] * 1e-3) / 1e9,
-                                  "avg_launch_ms": kern_ms["potrf"]}}
+                                  "avg_launch_ms": kern_ms["potrf"],
+                                  "frac": bm["potrf"] * batch / (kern_ms["potrf"] * 1e-3) / 1e9 / HBM_PEAK_GBS}}
         tf = os.path.join(ROOT, "profiles", f"traffic_{name.lower()}.json")
         if os.path.exists(tf):
             with open(tf) as f:
@@ -479,6 +517,11 @@ def main():
                               + ("" if fl == 2.0 * n ** 3 * batch else "; reverse sweep over the blocked factorisation "
                                  "above the base block (2 n1 n2 n per level, 2 n0^3 per base block), "
                                  f"{fl / (2.0 * n ** 3 * batch):.3f} of the closed expression's count"),
+                "duration_source": "HIP event pair around each library call on the launch stream (a call is many "
+                                   "launches), averaged over the timed steps",
+                "per_call": {k_: {"ms": kern_ms[k_], "tflops": fm[k_] * batch / (kern_ms[k_] * 1e-3) / 1e12,
+                                  "frac": fm[k_] * batch / (kern_ms[k_] * 1e-3) / 1e12 / PEAK_TFLOPS[dtype]}
+                             for k_ in kern_ms if k_ in fm},
                 "whole_step_frac": gflops / 1e3 / PEAK_TFLOPS[dtype]}
 
     # ---- CPU baseline: the oracle, as it stands, on this machine's host cores ------------
@@ -493,9 +536,9 @@ def main():
             sb //= 2
             est /= 2
         if name == "C5":
-            # one matrix of the full size takes the oracle many minutes: time the leading ns x ns problem and
-            # scale by the cubic flop count
-            ns, ms_ = 2048, 128
+            # one matrix of the full size takes the oracle minutes: time the leading ns x ns problem (an SPD matrix
+            # of the same recipe) and scale by the cubic flop count
+            ns, ms_ = 4096, 256
             As = np.ascontiguousarray(w["A"][:, :ns, :ns], dtype=np.float64)
             Gs = np.ascontiguousarray(w["Lbar"][:, :ns, :ns], dtype=np.float64)
             Rs = np.ascontiguousarray(w["rhs"][:, :ns, :ms_], dtype=np.float64)
@@ -558,7 +601,8 @@ def main():
         "roofline": roof,
         "cpu_baseline": cpu,
     }
-    print(json.dumps(out), flush=True)
+    del sets, A0, G0
+    return out
 
 
 if __name__ == "__main__":

@@ -482,7 +482,9 @@ int orc_syrk_backward(int trans, double alpha, int64_t batch, int n, int k, cons
     for (int64_t b = 0; b < batch; ++b) {
         const double *Ab = A + b * nk, *G = Bbar + b * nn;
         double *O = Abar + b * nk;
+        /* every entry of the result is its own sum: rows are shared out over the threads */
         if (!trans) {
+#pragma omp parallel for schedule(dynamic, 4) if ((double)n * n * k > 5e7)
             for (int i = 0; i < n; ++i)
                 for (int p = 0; p < k; ++p) {
                     double s = 0.0;
@@ -491,6 +493,7 @@ int orc_syrk_backward(int trans, double alpha, int64_t batch, int n, int k, cons
                     O[(size_t)i * k + p] = alpha * s;
                 }
         } else {
+#pragma omp parallel for schedule(dynamic, 4) if ((double)n * n * k > 5e7)
             for (int p = 0; p < k; ++p)
                 for (int j = 0; j < n; ++j) {
                     double s = 0.0;
