@@ -440,32 +440,17 @@ __device__ __forceinline__ void leaf_store_lower(const LeafLds<T> &m, bool inver
     }
 }
 
+// The factorisation loop shared by the kernels below: on entry the lower tiles of the block are in
+// the A / L areas of m (and a workgroup barrier has passed), on return they hold the factor and the
+// X areas its inverse.  Returns, in wavefront 0, the 1-based index of the first pivot that is not
+// > 0 (0: none); ends with a workgroup barrier.
 template <typename T>
-__global__ __launch_bounds__(LEAF16_THREADS) void k_potrf_leaf16(View<const T> A, View<T> L, View<T> Inv, int32_t *info,
-                                                                 int info_off, int64_t batch, int nb, int zero_upper)
+__device__ __forceinline__ int leaf_factor(const LeafLds<T> &m, int K, int wave, int lane)
 {
-    using C = Leaf16<T>;
-    extern __shared__ __align__(16) unsigned char leaf16_lds[];
-    T *lds = reinterpret_cast<T *>(leaf16_lds);
-    const LeafLds<T> m{lds + C::OFF_D, lds + C::OFF_XD, lds + C::OFF_A, lds + C::OFF_X};
     constexpr int W = LEAF16_WAVES;
-
-    const int tid = threadIdx.x;
-    const int lane = tid & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int K = (nb + LT - 1) / LT;  // tile columns in use
-    const int64_t b = blockIdx.x;
-    LEAF16_STAMP(31);
-
-    leaf_load_lower<T>(m, A.p + b * A.bs, A.rs, A.cs, nb, wave, lane);
-    __syncthreads();
-    LEAF16_STAMP(0);
-
     int fail = 0;
-    if (wave == 0) {
-        const int f = leaf_diag<T>(m, 0, lane);
-        fail = f;
-    }
+    if (wave == 0)
+        fail = leaf_diag<T>(m, 0, lane);
     __syncthreads();
     LEAF16_STAMP(1);
 
@@ -516,6 +501,30 @@ __global__ __launch_bounds__(LEAF16_THREADS) void k_potrf_leaf16(View<const T> A
         __syncthreads();
         LEAF16_STAMP(3 + 2 * k);
     }
+    return fail;
+}
+
+template <typename T>
+__global__ __launch_bounds__(LEAF16_THREADS) void k_potrf_leaf16(View<const T> A, View<T> L, View<T> Inv, int32_t *info,
+                                                                 int info_off, int64_t batch, int nb, int zero_upper)
+{
+    using C = Leaf16<T>;
+    extern __shared__ __align__(16) unsigned char leaf16_lds[];
+    T *lds = reinterpret_cast<T *>(leaf16_lds);
+    const LeafLds<T> m{lds + C::OFF_D, lds + C::OFF_XD, lds + C::OFF_A, lds + C::OFF_X};
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int K = (nb + LT - 1) / LT;  // tile columns in use
+    const int64_t b = blockIdx.x;
+    LEAF16_STAMP(31);
+
+    leaf_load_lower<T>(m, A.p + b * A.bs, A.rs, A.cs, nb, wave, lane);
+    __syncthreads();
+    LEAF16_STAMP(0);
+
+    const int fail = leaf_factor<T>(m, K, wave, lane);
 
     // ---- factor and inverse back to memory (lower tiles; zeros above the diagonal inside the
     //      diagonal tiles) -----------------------------------------------------------------------
@@ -816,54 +825,8 @@ __global__ __launch_bounds__(LEAF16_THREADS) void k_gp_leaf16(View<const T> A, c
         sy[tid] = tid < n ? y[b * n + tid] : T(0);
     __syncthreads();
 
-    // ---- L and Li: the loop of k_potrf_leaf16 --------------------------------------------------
-    int fail = 0;
-    if (wave == 0)
-        fail = leaf_diag<T>(m, 0, lane);
-    __syncthreads();
-    for (int k = 0; k < K; ++k) {
-        const int rows = K - 1 - k;
-        if (wave == 0) {
-            if (rows > 0)
-                leaf_panel<T>(m, k + 1, k, lane);
-        } else {
-            const int np = rows > 0 ? rows - 1 : 0;
-            for (int it = wave - 1; it < np + k; it += W - 1) {
-                if (it < np)
-                    leaf_panel<T>(m, k + 2 + it, k, lane);
-                else
-                    leaf_xrow<T>(m, k, it - np, lane);
-            }
-        }
-        __syncthreads();
-        if (rows == 0)
-            break;
-        if (wave == 0) {
-            leaf_update_a<T>(m, k + 1, k + 1, k, lane);
-            const int f = leaf_diag<T>(m, k + 1, lane);
-            if (fail == 0 && f != 0)
-                fail = (k + 1) * LT + f;
-        } else {
-            const int nx = rows * (k + 1);
-            const int na = rows * (rows + 1) / 2 - 1;
-            int xi = 0, xj = wave - 1;
-            for (int it = wave - 1; it < nx + na; it += W - 1) {
-                if (it < nx) {
-                    while (xj > k) {
-                        xj -= k + 1;
-                        ++xi;
-                    }
-                    leaf_update_x<T>(m, k + 1 + xi, xj, k, lane);
-                    xj += W - 1;
-                } else {
-                    int ii, jj;
-                    tri_decode(it - nx + 1, ii, jj);
-                    leaf_update_a<T>(m, k + 1 + ii, k + 1 + jj, k, lane);
-                }
-            }
-        }
-        __syncthreads();
-    }
+    // ---- L and Li ------------------------------------------------------------------------------
+    const int fail = leaf_factor<T>(m, K, wave, lane);
     if (info != nullptr && tid == 0 && fail != 0 && fail <= n)
         info[b] = fail;
 
