@@ -280,8 +280,10 @@ size_t la_gp_workspace_bytes(la_dtype dt, int64_t batch, int n);
 la_status la_gp_criterion(la_dtype dt, int64_t batch, int n, const void *A, const void *y, void *loss, void *Abar,
                           int32_t *info, void *workspace, size_t workspace_bytes, void *stream);
 
-/* Variational sparse Gaussian-process criterion and its gradient (section 3.2; the backward sweep
- * applies the backward rules of section 4.2 to the listing's steps in reverse).  One problem per call:
+/* Variational sparse Gaussian-process criterion and its gradient (section 3.2: the criterion is
+ * -log N(y | 0, Q + lam I) + tr(Kff - Q) / (2 lam) with Q = Kuf^T Kuu^-1 Kuf, evaluated through two
+ * Cholesky factors of U x U matrices; the gradient is the reverse sweep over that evaluation with the
+ * backward rules of section 4.2).  One problem per call:
  *   Lu = potrf(Kuu);  B = Lu^{-1} Kuf;  A = B B^T / lam + I;  La = potrf(A);  w = La^{-1} (B y);
  *   phi = (log 2 pi + log lam) n / 2 + sum_i log La_ii + |y|^2 / (2 lam) - |w|^2 / (2 lam^2)
  *         - (|B|_F^2 - sum Kff_diag) / (2 lam),            lam = noise_var > 0.

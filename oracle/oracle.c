@@ -826,16 +826,62 @@ int orc_potrf_backward_phi(int64_t batch, int n, const double *L, const double *
 }
 
 /* ------------------------------------------------------------------------- */
-/* Variational sparse Gaussian-process criterion (section 3.2) and its gradient.
+/* Variational sparse Gaussian-process criterion (section 3.2) and its gradient, from the
+ * DEFINITION of the criterion rather than from the section's efficient evaluation: with the
+ * Nystrom matrix Q = Kuf^T Kuu^-1 Kuf (n x n, formed densely here) and S = Q + lam I,
+ *   phi = -log N(y | 0, S) + tr(Kff - Q) / (2 lam)
+ *       = 1/2 log det S + 1/2 y^T S^-1 y + n/2 log 2 pi + (sum Kff_diag - tr Q) / (2 lam).
+ * Its derivatives by matrix calculus, with a = S^-1 y and W = Kuu^-1 Kuf:
+ *   d phi / dQ = M = 1/2 (S^-1 - a a^T) - I / (2 lam)          (symmetric),
+ *   Kuf_bar = 2 W M,   Kuu_bar = -W M W^T   (symmetric: d phi = <Kuu_bar, dKuu> for symmetric dKuu),
+ *   y_bar = a,   Kff_diag_bar = 1 / (2 lam),
+ *   lam_bar = 1/2 tr S^-1 - 1/2 a^T a - (sum Kff_diag - tr Q) / (2 lam^2).
  * Inputs: Kuu (U x U, symmetric positive definite, lower triangle read), Kuf (U x n),
- * Kff_diag (n), y (n), noise variance lam.  Forward, in the order of the section's listing:
- *   Lu = potrf(Kuu);  B = Lu^-1 Kuf;  A = B B^T / lam + I;  La = potrf(A);
- *   w = La^-1 (B y);
- *   phi = (log 2 pi + log lam) n / 2 + sum_i log La_ii + |y|^2 / (2 lam) - |w|^2 / (2 lam^2)
- *         - (|B|_F^2 - sum Kff_diag) / (2 lam).
- * Backward: the chain rule through the same steps with the operators' backward rules
- * (section 4.2): trsm, gemm2, potrf, syrk, trsm, potrf.  Outputs: phi, Kuu_bar (symmetric,
- * d phi = <Kuu_bar, dKuu> for symmetric dKuu), Kuf_bar, Kff_diag_bar, y_bar, lam_bar. */
+ * Kff_diag (n), y (n), noise variance lam.  Costs O(n^3): for checking only. */
+/* Plain dense products for it (rows of the result shared out over the threads; every entry is
+ * the sum over p = 0, 1, ... in that order):  Z = X^T Y,  Z = X Y,  Z = X Y^T. */
+static void dense_tn(int m, int n, int k, const double *X, const double *Y, double *Z) /* X: k x m, Y: k x n */
+{
+#pragma omp parallel for schedule(static)
+    for (int i = 0; i < m; ++i) {
+        double *zi = Z + (size_t)i * n;
+        for (int j = 0; j < n; ++j)
+            zi[j] = 0.0;
+        for (int p = 0; p < k; ++p) {
+            const double x = X[(size_t)p * m + i];
+            const double *yp = Y + (size_t)p * n;
+            for (int j = 0; j < n; ++j)
+                zi[j] += x * yp[j];
+        }
+    }
+}
+static void dense_nn(int m, int n, int k, const double *X, const double *Y, double *Z) /* X: m x k, Y: k x n */
+{
+#pragma omp parallel for schedule(static)
+    for (int i = 0; i < m; ++i) {
+        double *zi = Z + (size_t)i * n;
+        for (int j = 0; j < n; ++j)
+            zi[j] = 0.0;
+        for (int p = 0; p < k; ++p) {
+            const double x = X[(size_t)i * k + p];
+            const double *yp = Y + (size_t)p * n;
+            for (int j = 0; j < n; ++j)
+                zi[j] += x * yp[j];
+        }
+    }
+}
+static void dense_nt(int m, int n, int k, const double *X, const double *Y, double *Z) /* X: m x k, Y: n x k */
+{
+#pragma omp parallel for schedule(static)
+    for (int i = 0; i < m; ++i)
+        for (int j = 0; j < n; ++j) {
+            double t = 0.0;
+            for (int p = 0; p < k; ++p)
+                t += X[(size_t)i * k + p] * Y[(size_t)j * k + p];
+            Z[(size_t)i * n + j] = t;
+        }
+}
+
 int orc_sgp_criterion(int U, int n, const double *Kuu, const double *Kuf, const double *Kff_diag, const double *y,
                       double lam, double *phi, double *Kuu_bar, double *Kuf_bar, double *Kff_diag_bar, double *y_bar,
                       double *lam_bar)
@@ -843,71 +889,57 @@ int orc_sgp_criterion(int U, int n, const double *Kuu, const double *Kuf, const 
     if (U <= 0 || n <= 0 || !Kuu || !Kuf || !Kff_diag || !y || !phi || !Kuu_bar || !Kuf_bar || !Kff_diag_bar ||
         !y_bar || !lam_bar || !(lam > 0.0))
         return ORC_ERR_INVALID_ARG;
-    size_t uu = (size_t)U * U, un = (size_t)U * n;
-    double *Lu = malloc(uu * sizeof(double)), *B = malloc(un * sizeof(double)), *A = malloc(uu * sizeof(double));
-    double *La = malloc(uu * sizeof(double)), *Lab = malloc(uu * sizeof(double)), *Ab = malloc(uu * sizeof(double));
-    double *v = malloc(U * sizeof(double)), *w = malloc(U * sizeof(double)), *vb = malloc(U * sizeof(double));
-    double *Lub = malloc(uu * sizeof(double)), *G = malloc(un * sizeof(double));
+    size_t uu = (size_t)U * U, un = (size_t)U * n, nn = (size_t)n * n;
+    double *Lu = malloc(uu * sizeof(double)), *Ki = malloc(uu * sizeof(double)), *W = malloc(un * sizeof(double));
+    double *S = malloc(nn * sizeof(double)), *Ls = malloc(nn * sizeof(double)), *Si = malloc(nn * sizeof(double));
+    double *a = malloc(n * sizeof(double)), *T = malloc(un * sizeof(double));
     int rc = ORC_ERR_INVALID_ARG;
-    if (!Lu || !B || !A || !La || !Lab || !Ab || !v || !w || !vb || !Lub || !G)
+    if (!Lu || !Ki || !W || !S || !Ls || !Si || !a || !T)
         goto done;
-    /* forward */
-    if (orc_potrf(1, 1, U, Kuu, Lu, NULL) || orc_trsm(1, 0, 0, 1.0, 1, U, n, Lu, Kuf, B) ||
-        orc_syrk(0, 1.0 / lam, 1, U, n, B, A))
+    /* W = Kuu^-1 Kuf through the explicit inverse of Kuu;  Q = Kuf^T W */
+    if (orc_potrf(1, 1, U, Kuu, Lu, NULL) || orc_potri(1, 1, U, Lu, Ki))
         goto done;
-    for (int i = 0; i < U; ++i)
-        A[(size_t)i * U + i] += 1.0;
-    if (orc_potrf(1, 1, U, A, La, NULL) || orc_gemm2(0, 0, 1.0, 1, U, 1, n, B, y, v) ||
-        orc_trsm(1, 0, 0, 1.0, 1, U, 1, La, v, w))
-        goto done;
-    double logdet = 0.0, yy = 0.0, ww = 0.0, bb = 0.0, kk = 0.0;
-    for (int i = 0; i < U; ++i)
-        logdet += log(La[(size_t)i * U + i]);
+    dense_nn(U, n, U, Ki, Kuf, W);
+    dense_tn(n, n, U, Kuf, W, S);
+    double trq = 0.0, kk = 0.0;
     for (int i = 0; i < n; ++i) {
-        yy += y[i] * y[i];
+        trq += S[(size_t)i * n + i];
         kk += Kff_diag[i];
+        S[(size_t)i * n + i] += lam;
     }
-    for (int i = 0; i < U; ++i)
-        ww += w[i] * w[i];
-    for (size_t e = 0; e < un; ++e)
-        bb += B[e] * B[e];
+    /* S = Ls Ls^T:  log det S = 2 sum log Ls_ii,  a = S^-1 y by two substitutions,  S^-1 explicitly */
+    if (orc_potrf(1, 1, n, S, Ls, NULL) || orc_trsm(1, 0, 0, 1.0, 1, n, 1, Ls, y, a) ||
+        orc_trsm(1, 1, 0, 1.0, 1, n, 1, Ls, a, a) || orc_potri(1, 1, n, Ls, Si))
+        goto done;
+    double logdet = 0.0, ya = 0.0, aa = 0.0, tri = 0.0;
+    for (int i = 0; i < n; ++i) {
+        logdet += 2.0 * log(Ls[(size_t)i * n + i]);
+        ya += y[i] * a[i];
+        aa += a[i] * a[i];
+        tri += Si[(size_t)i * n + i];
+    }
     const double l2pi = 1.8378770664093454835606594728112; /* log(2 pi) */
-    *phi = (l2pi + log(lam)) * n / 2.0 + logdet + yy / (2.0 * lam) - ww / (2.0 * lam * lam) - (bb - kk) / (2.0 * lam);
-    /* backward */
-    for (int i = 0; i < U; ++i)
-        vb[i] = -w[i] / (lam * lam); /* w_bar */
-    /* w = La^-1 v:  v_bar = La^-T w_bar,  La_bar = -tril(v_bar w^T);  log det adds diag(1 / La_ii) */
-    if (orc_trsm_backward(1, 0, 0, 1.0, 1, U, 1, La, w, vb, vb, Lab))
-        goto done;
-    for (int i = 0; i < U; ++i)
-        Lab[(size_t)i * U + i] += 1.0 / La[(size_t)i * U + i];
-    if (orc_potrf_backward(1, 1, U, La, Lab, Ab)) /* A_bar, symmetric */
-        goto done;
-    double sa = 0.0;
+    *phi = 0.5 * logdet + 0.5 * ya + 0.5 * n * l2pi + (kk - trq) / (2.0 * lam);
+    *lam_bar = 0.5 * tri - 0.5 * aa - (kk - trq) / (2.0 * lam * lam);
+    for (int i = 0; i < n; ++i) {
+        y_bar[i] = a[i];
+        Kff_diag_bar[i] = 1.0 / (2.0 * lam);
+    }
+    /* M = 1/2 (S^-1 - a a^T) - I / (2 lam), into Si */
+    for (int i = 0; i < n; ++i)
+        for (int j = 0; j < n; ++j)
+            Si[(size_t)i * n + j] = 0.5 * (Si[(size_t)i * n + j] - a[i] * a[j]) - (i == j ? 1.0 / (2.0 * lam) : 0.0);
+    /* T = W M;  Kuf_bar = 2 T;  Kuu_bar = -T W^T, symmetrised against rounding */
+    dense_nn(U, n, n, W, Si, T);
+    dense_nt(U, U, n, T, W, Lu);
+    for (size_t e = 0; e < un; ++e)
+        Kuf_bar[e] = 2.0 * T[e];
     for (int i = 0; i < U; ++i)
         for (int j = 0; j < U; ++j)
-            sa += Ab[(size_t)i * U + j] * (A[(size_t)i * U + j] - (i == j ? 1.0 : 0.0));
-    *lam_bar = n / (2.0 * lam) - yy / (2.0 * lam * lam) + ww / (lam * lam * lam) + (bb - kk) / (2.0 * lam * lam) - sa / lam;
-    /* B_bar = syrk backward of S = B B^T with S_bar = A_bar / lam, + v_bar y^T, - B / lam */
-    if (orc_syrk_backward(0, 1.0, 1, U, n, B, Ab, G))
-        goto done;
-    for (int i = 0; i < U; ++i)
-        for (int c = 0; c < n; ++c)
-            G[(size_t)i * n + c] = G[(size_t)i * n + c] / lam + vb[i] * y[c] - B[(size_t)i * n + c] / lam;
-    /* y_bar = B^T v_bar + y / lam */
-    for (int c = 0; c < n; ++c) {
-        double t = 0.0;
-        for (int i = 0; i < U; ++i)
-            t += B[(size_t)i * n + c] * vb[i];
-        y_bar[c] = t + y[c] / lam;
-        Kff_diag_bar[c] = 1.0 / (2.0 * lam);
-    }
-    /* B = Lu^-1 Kuf */
-    if (orc_trsm_backward(1, 0, 0, 1.0, 1, U, n, Lu, B, G, Kuf_bar, Lub) || orc_potrf_backward(1, 1, U, Lu, Lub, Kuu_bar))
-        goto done;
+            Kuu_bar[(size_t)i * U + j] = -0.5 * (Lu[(size_t)i * U + j] + Lu[(size_t)j * U + i]);
     rc = ORC_OK;
 done:
-    free(Lu); free(B); free(A); free(La); free(Lab); free(Ab); free(v); free(w); free(vb); free(Lub); free(G);
+    free(Lu); free(Ki); free(W); free(S); free(Ls); free(Si); free(a); free(T);
     return rc;
 }
 

@@ -715,9 +715,11 @@ static la_status gemm2_backward_t(int ta, int tb, double alpha, int64_t batch, i
 }
 
 // ---------------------------------------------------------------------------------
-// Variational sparse Gaussian-process criterion (section 3.2) and its gradient, composed of the
-// operators above in the order of the section's listing; the backward sweep applies their
-// backward rules (section 4.2) in reverse.  One problem per call.  The caller's workspace holds
+// Variational sparse Gaussian-process criterion (section 3.2) and its gradient through two Cholesky
+// factors of U x U matrices -- the evaluation that makes the criterion cost O(n U^2) -- as a chain of
+// the operators above; the gradient is the reverse sweep over that chain with the operators' backward
+// rules (section 4.2), the two places where gradients meet written out.  One problem per call.  The
+// caller's workspace holds
 //   Lu (U^2), B (U n), A (U^2), La (U^2), La_bar -> A_bar (U^2), v, w, v_bar (U each), one scalar,
 // then 7 x SGP_PARTIALS fp64 partial sums.
 // ---------------------------------------------------------------------------------
