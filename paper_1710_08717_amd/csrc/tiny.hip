@@ -20,29 +20,33 @@ namespace la {
 // potrf forward.  View A / L give the LOGICAL lower-triangular problem: A(i,j), i >= j,
 // is read; L(i,j) is written for the whole nb x nb block (zeros for i < j).
 // ---------------------------------------------------------------------------------
-template <typename T, int G>
+template <typename T, int G, int N = G>
 __global__ __launch_bounds__(WAVE) void k_potrf_tiny(View<const T> A, View<T> L, int32_t *info, int info_off,
                                                       int64_t batch, int nb)
 {
-    using S = Stage<T, G>;
+    // G lanes per matrix, N <= G columns kept: a lane group that the matrix does not fill (n = 12 in
+    // 16 lanes) stages and eliminates N columns only; its lanes i >= N follow row N - 1 and write nothing.
+    constexpr int MPW = WAVE / G;
+    using S = Stage<T, N, MPW>;
     __shared__ __align__(16) T sm[S::ELEMS];
     const int lane = threadIdx.x;
     const int q = lane / G, i = lane % G;
-    const int64_t b0 = (int64_t)blockIdx.x * S::MPW;
+    const int ir = (N < G && i >= N) ? N - 1 : i;
+    const int64_t b0 = (int64_t)blockIdx.x * MPW;
 
     const Mem<const T> Am = mem_of(A);
     const Mem<T> Lm = mem_of(L);
-    stage_load<T, G>(sm, Am, b0, batch, nb);
+    stage_load<T, N, MPW>(sm, Am, b0, batch, nb);
     __syncthreads();
-    T a[G];
-    read_lrow<T, G>(sm + q * S::MS, i, Am.tr, a);
+    T a[N];
+    read_lrow<T, N>(sm + q * S::MS, ir, Am.tr, a);
 #pragma unroll
-    for (int k = 0; k < G; ++k)
+    for (int k = 0; k < N; ++k)
         if (k > i)
             a[k] = T(0);  // the other triangle of A is never used
 
     int fail = 0;
-    static_for<0, G>([&](auto J) {
+    static_for<0, N>([&](auto J) {
         constexpr int j = decltype(J)::value;
         T piv = group_bcast<G>(a[j], j);  // a_jj after the updates of columns < j
         if (!(piv > T(0)) && fail == 0)
@@ -50,23 +54,25 @@ __global__ __launch_bounds__(WAVE) void k_potrf_tiny(View<const T> A, View<T> L,
         T r = rsqrt_acc(piv);
         a[j] = (i >= j) ? a[j] * r : T(0);  // column j of L (lane j gets sqrt(piv))
         dpp_settle1<G>(a[j]);
-        static_for<j + 1, G>([&](auto K) {
+        static_for<j + 1, N>([&](auto K) {
             constexpr int k = decltype(K)::value;
             fma_bcast<G, k>(a[k], a[j], a[j], true);  // a_ik -= l_ij l_kj
         });
     });
 #pragma unroll
-    for (int k = 0; k < G; ++k)
+    for (int k = 0; k < N; ++k)
         if (k > i)
             a[k] = T(0);
 
     __syncthreads();
-    if (Lm.tr)
-        write_col<T, G>(sm + q * S::MS, i, a);
-    else
-        write_row<T, G>(sm + q * S::MS, i, a);
+    if (N == G || i < N) {
+        if (Lm.tr)
+            write_col<T, N>(sm + q * S::MS, i, a);
+        else
+            write_row<T, N>(sm + q * S::MS, i, a);
+    }
     __syncthreads();
-    stage_store<T, G>(sm, Lm, b0, batch, nb);
+    stage_store<T, N, MPW>(sm, Lm, b0, batch, nb);
     if (info != nullptr && i == 0 && b0 + q < batch && fail != 0 && fail <= nb) {
         if (info[b0 + q] == 0)
             info[b0 + q] = info_off + fail;
@@ -82,11 +88,14 @@ __global__ __launch_bounds__(WAVE) void k_potrf_tiny(View<const T> A, View<T> L,
 // into accumulation registers, takes the guarded broadcast multiply-add and is still 1.1 to 1.8 times faster
 // than 64 lanes per matrix).
 // ---------------------------------------------------------------------------------
-template <typename T, int R>
+template <typename T, int R, int N = 16 * R>
 __global__ __launch_bounds__(WAVE) void k_potrf_tiny_rows(View<const T> A, View<T> L, int32_t *info, int info_off,
                                                            int64_t batch, int nb)
 {
-    constexpr int G = 16, N = G * R, MPW = WAVE / G;
+    // N columns kept, 16 (R - 1) < N <= 16 R: the last row slot is only partly filled when N < 16 R; a
+    // lane without a row there follows row N - 1 and writes nothing.
+    constexpr int G = 16, MPW = WAVE / G;
+    static_assert(N > G * (R - 1) && N <= G * R && N % 4 == 0, "column count does not fit the row slots");
     using S = Stage<T, N, MPW>;
     extern __shared__ __align__(16) unsigned char tiny_lds[];
     T *sm = reinterpret_cast<T *>(tiny_lds);
@@ -101,7 +110,8 @@ __global__ __launch_bounds__(WAVE) void k_potrf_tiny_rows(View<const T> A, View<
     T a[R][N];  // a[h] = row i + 16 h
     static_for<0, R>([&](auto H) {
         constexpr int h = decltype(H)::value;
-        read_lrow<T, N>(sm + q * S::MS, i + G * h, Am.tr, a[h]);
+        const int row = (G * h + G > N && i + G * h >= N) ? N - 1 : i + G * h;
+        read_lrow<T, N>(sm + q * S::MS, row, Am.tr, a[h]);
 #pragma unroll
         for (int k = 0; k < N; ++k)
             if (k > i + G * h)
@@ -141,10 +151,12 @@ __global__ __launch_bounds__(WAVE) void k_potrf_tiny_rows(View<const T> A, View<
         for (int k = 0; k < N; ++k)
             if (k > i + G * h)
                 a[h][k] = T(0);
-        if (Lm.tr)
-            write_col<T, N>(sm + q * S::MS, i + G * h, a[h]);
-        else
-            write_row<T, N>(sm + q * S::MS, i + G * h, a[h]);
+        if (G * h + G <= N || i + G * h < N) {
+            if (Lm.tr)
+                write_col<T, N>(sm + q * S::MS, i + G * h, a[h]);
+            else
+                write_row<T, N>(sm + q * S::MS, i + G * h, a[h]);
+        }
     });
     __syncthreads();
     stage_store<T, N, MPW>(sm, Lm, b0, batch, nb);
@@ -157,27 +169,31 @@ __global__ __launch_bounds__(WAVE) void k_potrf_tiny_rows(View<const T> A, View<
 // ---------------------------------------------------------------------------------
 // potrf backward for n <= G.  Views give the logical lower-triangular L and Lbar.
 // ---------------------------------------------------------------------------------
-template <typename T, int G>
+template <typename T, int G, int N = G>
 __global__ __launch_bounds__(WAVE) void k_backward_tiny(View<const T> Lv, View<const T> Gv, View<T> Av,
                                                          int64_t batch, int n)
 {
-    using S = Stage<T, G>;
+    // N <= G columns kept (see k_potrf_tiny); lanes i >= N carry zeros and write nothing
+    constexpr int MPW = WAVE / G;
+    using S = Stage<T, N, MPW>;
     __shared__ __align__(16) T sm[S::ELEMS];
     const int lane = threadIdx.x;
     const int q = lane / G, i = lane % G;
-    const int64_t b0 = (int64_t)blockIdx.x * S::MPW;
+    const int ir = (N < G && i >= N) ? N - 1 : i;
+    const bool own = (N == G) || i < N;
+    const int64_t b0 = (int64_t)blockIdx.x * MPW;
     T *smq = sm + q * S::MS;
 
     // lane i takes column i of L: lc[k] = l_ki (k >= i), and its reciprocal diagonal
-    T lc[G];
+    T lc[N];
     const Mem<const T> Lm = mem_of(Lv);
     const Mem<const T> Gm = mem_of(Gv);
-    stage_load<T, G>(sm, Lm, b0, batch, n);
+    stage_load<T, N, MPW>(sm, Lm, b0, batch, n);
     __syncthreads();
-    read_lcol<T, G>(smq, i, Lm.tr, lc);
+    read_lcol<T, N>(smq, ir, Lm.tr, lc);
     T dii = T(1);
 #pragma unroll
-    for (int k = 0; k < G; ++k) {
+    for (int k = 0; k < N; ++k) {
         if (k == i)
             dii = lc[k];
         if (k < i)
@@ -187,22 +203,22 @@ __global__ __launch_bounds__(WAVE) void k_backward_tiny(View<const T> Lv, View<c
     __syncthreads();
 
     // lane k takes row k of Lbar: g[j] = lbar_kj (j <= k)
-    T g[G];
-    stage_load<T, G>(sm, Gm, b0, batch, n);
+    T g[N];
+    stage_load<T, N, MPW>(sm, Gm, b0, batch, n);
     __syncthreads();
-    read_lrow<T, G>(smq, i, Gm.tr, g);
+    read_lrow<T, N>(smq, ir, Gm.tr, g);
 #pragma unroll
-    for (int j = 0; j < G; ++j)
+    for (int j = 0; j < N; ++j)
         if (j > i || i >= n)
             g[j] = T(0);  // also drops the identity padding of the stage
 
     // P = L^T Lbar, row i in lane i: p_ij = sum_k l_ki lbar_kj   (terms with j > k are zero)
-    T y[G];
+    T y[N];
 #pragma unroll
-    for (int j = 0; j < G; ++j)
+    for (int j = 0; j < N; ++j)
         y[j] = T(0);
     dpp_settle<G>(g);
-    static_for<0, G>([&](auto K) {
+    static_for<0, N>([&](auto K) {
         constexpr int k = decltype(K)::value;
         static_for<0, k + 1>([&](auto J) {
             constexpr int j = decltype(J)::value;
@@ -211,32 +227,32 @@ __global__ __launch_bounds__(WAVE) void k_backward_tiny(View<const T> Lv, View<c
     });
     // Phi, then the row scaling D^-1 of L = Lt D (Lt unit lower triangular)
 #pragma unroll
-    for (int j = 0; j < G; ++j) {
+    for (int j = 0; j < N; ++j) {
         T v = (j < i) ? y[j] : ((j == i) ? T(0.5) * y[j] : T(0));
         y[j] = v * rd;
     }
     // lt[k] = l_ki / l_ii for k > i, zero otherwise
 #pragma unroll
-    for (int k = 0; k < G; ++k)
+    for (int k = 0; k < N; ++k)
         lc[k] = (k > i) ? lc[k] * rd : T(0);
 
     // Y = Lt^-T (D^-1 Phi): rows from the bottom; row k is final when it is broadcast
     dpp_settle<G>(y);
-    static_for<0, G - 1>([&](auto Tt) {
-        constexpr int k = G - 1 - decltype(Tt)::value;
-        static_for<0, G>([&](auto C) {
+    static_for<0, N - 1>([&](auto Tt) {
+        constexpr int k = N - 1 - decltype(Tt)::value;
+        static_for<0, N>([&](auto C) {
             constexpr int c = decltype(C)::value;
             fma_bcast_self<G, k>(y[c], lc[k], true);  // G instructions lie between two touches of y[c]
         });
     });
     // V = Y D^-1 (column c scaled by 1 / l_cc), then W = V Lt^-1 from the last column back
 #pragma unroll
-    for (int c = 0; c < G; ++c)
+    for (int c = 0; c < N; ++c)
         y[c] *= group_bcast<G>(rd, c);
     dpp_settle<G>(lc);
-    static_for<0, G - 1>([&](auto Tt) {
-        constexpr int c = G - 2 - decltype(Tt)::value;
-        static_for<c + 1, G>([&](auto K) {
+    static_for<0, N - 1>([&](auto Tt) {
+        constexpr int c = N - 2 - decltype(Tt)::value;
+        static_for<c + 1, N>([&](auto K) {
             constexpr int k = decltype(K)::value;
             fma_bcast<G, c>(y[c], lc[k], y[k], true);
         });
@@ -244,17 +260,19 @@ __global__ __launch_bounds__(WAVE) void k_backward_tiny(View<const T> Lv, View<c
 
     // Abar = 1/2 (W + W^T): rows out to LDS, columns back in
     __syncthreads();
-    write_row<T, G>(smq, i, y);
+    if (own)
+        write_row<T, N>(smq, i, y);
     __syncthreads();
-    T wt[G];
-    read_col<T, G>(smq, i, wt);
+    T wt[N];
+    read_col<T, N>(smq, ir, wt);
 #pragma unroll
-    for (int c = 0; c < G; ++c)
+    for (int c = 0; c < N; ++c)
         y[c] = T(0.5) * (y[c] + wt[c]);
     __syncthreads();
-    write_row<T, G>(smq, i, y);
+    if (own)
+        write_row<T, N>(smq, i, y);
     __syncthreads();
-    stage_store<T, G>(sm, mem_of(Av), b0, batch, n);  // symmetric: orientation is immaterial
+    stage_store<T, N, MPW>(sm, mem_of(Av), b0, batch, n);  // symmetric: orientation is immaterial
 }
 
 // ---------------------------------------------------------------------------------
@@ -262,17 +280,21 @@ __global__ __launch_bounds__(WAVE) void k_backward_tiny(View<const T> Lv, View<c
 // P, Y, W and columns i and i + 16 of L (slot h = 0, 1), so all broadcasts are DPP row broadcasts.
 // Same steps as k_backward_tiny; row / column k = 16 kh + kl lives in slot kh of lane kl.
 // ---------------------------------------------------------------------------------
-template <typename T>
+template <typename T, int N = 32>
 __global__ __launch_bounds__(WAVE) void k_backward_tiny2(View<const T> Lv, View<const T> Gv, View<T> Av,
                                                           int64_t batch, int n)
 {
-    constexpr int N = 32, G = 16, MPW = WAVE / G;
+    // N columns kept, 16 < N <= 32; a lane whose second row i + 16 does not exist carries zeros there
+    constexpr int G = 16, MPW = WAVE / G;
+    static_assert(N > G && N <= 2 * G && N % 4 == 0, "column count does not fit two row slots");
     using S = Stage<T, N, MPW>;
     __shared__ __align__(16) T sm[S::ELEMS];
     const int lane = threadIdx.x;
     const int q = lane / G, i = lane % G;
     const int64_t b0 = (int64_t)blockIdx.x * MPW;
     T *smq = sm + q * S::MS;
+    const bool own1 = (N == 2 * G) || i + G < N;
+    const int i1 = own1 ? i + G : N - 1;
     const Mem<const T> Lm = mem_of(Lv);
     const Mem<const T> Gm = mem_of(Gv);
 
@@ -281,7 +303,7 @@ __global__ __launch_bounds__(WAVE) void k_backward_tiny2(View<const T> Lv, View<
     stage_load<T, N, MPW>(sm, Lm, b0, batch, n);
     __syncthreads();
     read_lcol<T, N>(smq, i, Lm.tr, lc0);
-    read_lcol<T, N>(smq, i + G, Lm.tr, lc1);
+    read_lcol<T, N>(smq, i1, Lm.tr, lc1);
     T d0 = T(1), d1 = T(1);
 #pragma unroll
     for (int k = 0; k < N; ++k) {
@@ -302,7 +324,7 @@ __global__ __launch_bounds__(WAVE) void k_backward_tiny2(View<const T> Lv, View<
     stage_load<T, N, MPW>(sm, Gm, b0, batch, n);
     __syncthreads();
     read_lrow<T, N>(smq, i, Gm.tr, g0);
-    read_lrow<T, N>(smq, i + G, Gm.tr, g1);
+    read_lrow<T, N>(smq, i1, Gm.tr, g1);
 #pragma unroll
     for (int j = 0; j < N; ++j) {
         if (j > i || i >= n)
@@ -391,10 +413,11 @@ __global__ __launch_bounds__(WAVE) void k_backward_tiny2(View<const T> Lv, View<
     // Abar = 1/2 (W + W^T): rows out to LDS, columns back in
     __syncthreads();
     write_row<T, N>(smq, i, y0);
-    write_row<T, N>(smq, i + G, y1);
+    if (own1)
+        write_row<T, N>(smq, i + G, y1);
     __syncthreads();
     read_col<T, N>(smq, i, g0);
-    read_col<T, N>(smq, i + G, g1);
+    read_col<T, N>(smq, i1, g1);
 #pragma unroll
     for (int c = 0; c < N; ++c) {
         y0[c] = T(0.5) * (y0[c] + g0[c]);
@@ -402,7 +425,8 @@ __global__ __launch_bounds__(WAVE) void k_backward_tiny2(View<const T> Lv, View<
     }
     __syncthreads();
     write_row<T, N>(smq, i, y0);
-    write_row<T, N>(smq, i + G, y1);
+    if (own1)
+        write_row<T, N>(smq, i + G, y1);
     __syncthreads();
     stage_store<T, N, MPW>(sm, mem_of(Av), b0, batch, n);  // symmetric: orientation is immaterial
 }
@@ -423,6 +447,9 @@ la_status launch_potrf_tiny(View<const T> A, View<T> L, int32_t *info, int info_
         constexpr int MPW = Stage<T, 8>::MPW;
         LA_LAUNCH((k_potrf_tiny<T, 8>), dim3((unsigned)((batch + MPW - 1) / MPW)), dim3(WAVE), 0, st, A, L,
                            info, info_off, batch, nb);
+    } else if (nb <= 12) {  // 16 lanes per matrix, 12 columns staged and eliminated
+        LA_LAUNCH((k_potrf_tiny<T, 16, 12>), dim3((unsigned)((batch + 3) / 4)), dim3(WAVE), 0, st, A, L, info,
+                  info_off, batch, nb);
     } else if (nb <= 16) {
         constexpr int MPW = Stage<T, 16>::MPW;
         LA_LAUNCH((k_potrf_tiny<T, 16>), dim3((unsigned)((batch + MPW - 1) / MPW)), dim3(WAVE), 0, st, A, L,
@@ -433,11 +460,19 @@ la_status launch_potrf_tiny(View<const T> A, View<T> L, int32_t *info, int info_
         // slower below.)
         constexpr int MPW = 4;
         const dim3 grid((unsigned)((batch + MPW - 1) / MPW));
-        constexpr size_t lds2 = sizeof(T) * Stage<T, 32, MPW>::ELEMS, lds3 = sizeof(T) * Stage<T, 48, MPW>::ELEMS;
-        if (nb <= 32) {
-            LA_LAUNCH((k_potrf_tiny_rows<T, 2>), grid, dim3(WAVE), lds2, st, A, L, info, info_off, batch, nb);
+        // the column count kept is the next of 24, 32, 40, 48: the eliminations cost its cube
+        if (nb <= 24) {
+            LA_LAUNCH((k_potrf_tiny_rows<T, 2, 24>), grid, dim3(WAVE), (sizeof(T) * Stage<T, 24, MPW>::ELEMS), st, A, L,
+                      info, info_off, batch, nb);
+        } else if (nb <= 32) {
+            LA_LAUNCH((k_potrf_tiny_rows<T, 2, 32>), grid, dim3(WAVE), (sizeof(T) * Stage<T, 32, MPW>::ELEMS), st, A, L,
+                      info, info_off, batch, nb);
+        } else if (nb <= 40) {
+            LA_LAUNCH((k_potrf_tiny_rows<T, 3, 40>), grid, dim3(WAVE), (sizeof(T) * Stage<T, 40, MPW>::ELEMS), st, A, L,
+                      info, info_off, batch, nb);
         } else {
-            LA_LAUNCH((k_potrf_tiny_rows<T, 3>), grid, dim3(WAVE), lds3, st, A, L, info, info_off, batch, nb);
+            LA_LAUNCH((k_potrf_tiny_rows<T, 3, 48>), grid, dim3(WAVE), (sizeof(T) * Stage<T, 48, MPW>::ELEMS), st, A, L,
+                      info, info_off, batch, nb);
         }
     } else {
         LA_LAUNCH((k_potrf_tiny<T, 64>), dim3((unsigned)batch), dim3(WAVE), 0, st, A, L, info, info_off,
@@ -461,15 +496,21 @@ la_status launch_backward_tiny(View<const T> L, View<const T> G, View<T> Abar, i
         constexpr int MPW = Stage<T, 8>::MPW;
         LA_LAUNCH((k_backward_tiny<T, 8>), dim3((unsigned)((batch + MPW - 1) / MPW)), dim3(WAVE), 0, st, L,
                            G, Abar, batch, n);
+    } else if (n <= 12) {
+        LA_LAUNCH((k_backward_tiny<T, 16, 12>), dim3((unsigned)((batch + 3) / 4)), dim3(WAVE), 0, st, L, G, Abar,
+                  batch, n);
     } else if (n <= 16) {
         constexpr int MPW = Stage<T, 16>::MPW;
         LA_LAUNCH((k_backward_tiny<T, 16>), dim3((unsigned)((batch + MPW - 1) / MPW)), dim3(WAVE), 0, st, L,
                            G, Abar, batch, n);
+    } else if (n <= 24) {
+        LA_LAUNCH((k_backward_tiny2<T, 24>), dim3((unsigned)((batch + 3) / 4)), dim3(WAVE), 0, st, L, G, Abar,
+                  batch, n);
     } else {
         // 16 lanes per matrix, two rows per lane.  In fp64 the kernel needs 294 registers; the overflow lives in
         // accumulation registers (hence the guarded broadcast multiply-adds), which still beats 32 lanes per
         // matrix with ds_bpermute broadcasts by 2.5 times (16384 matrices of n = 32: 357 -> 140 us).
-        LA_LAUNCH((k_backward_tiny2<T>), dim3((unsigned)((batch + 3) / 4)), dim3(WAVE), 0, st, L, G, Abar,
+        LA_LAUNCH((k_backward_tiny2<T, 32>), dim3((unsigned)((batch + 3) / 4)), dim3(WAVE), 0, st, L, G, Abar,
                            batch, n);
     }
     return launch_check("backward_tiny");

@@ -73,7 +73,9 @@ __device__ __forceinline__ void stage_load(T *sm, Mem<const T> M, int64_t b0, in
         const V4 *src = reinterpret_cast<const V4 *>(M.p + b0 * M.bs);
         constexpr int NV = S::MPW * G * G / VN;
 #pragma unroll
-        for (int t = 0; t < NV / WAVE; ++t) {
+        for (int t = 0; t < (NV + WAVE - 1) / WAVE; ++t) {
+            if (NV % WAVE != 0 && t * WAVE + lane >= NV)
+                break;
             int e = (t * WAVE + lane) * VN;
             int q = e / (G * G), r = (e / G) % G, c = e % G;
             // streamed once: non-temporal, so the lines do not linger in the caches
@@ -82,7 +84,7 @@ __device__ __forceinline__ void stage_load(T *sm, Mem<const T> M, int64_t b0, in
         return;
     }
     // all loads of a batch of 16 first, then the LDS writes: the loads are in flight together
-    constexpr int NIT = S::MPW * G * G / WAVE, CH = NIT < 16 ? NIT : 16;
+    constexpr int NE = S::MPW * G * G, NIT = (NE + WAVE - 1) / WAVE, CH = NIT < 16 ? NIT : 16;
     for (int t0 = 0; t0 < NIT; t0 += CH) {
         T v[CH];
 #pragma unroll
@@ -90,14 +92,15 @@ __device__ __forceinline__ void stage_load(T *sm, Mem<const T> M, int64_t b0, in
             const int e = (t0 + u) * WAVE + lane;
             const int q = e / (G * G), r = (e / G) % G, c = e % G;
             v[u] = (r == c) ? T(1) : T(0);
-            if (b0 + q < batch && r < nb && c < nb)
+            if (e < NE && b0 + q < batch && r < nb && c < nb)
                 v[u] = M.p[(b0 + q) * M.bs + r * M.ld + c];
         }
 #pragma unroll
         for (int u = 0; u < CH; ++u) {
             const int e = (t0 + u) * WAVE + lane;
             const int q = e / (G * G), r = (e / G) % G, c = e % G;
-            sm[q * S::MS + r * S::LD + c] = v[u];
+            if (e < NE)
+                sm[q * S::MS + r * S::LD + c] = v[u];
         }
     }
 }
@@ -113,7 +116,9 @@ __device__ __forceinline__ void stage_store(const T *sm, Mem<T> M, int64_t b0, i
         V4 *dst = reinterpret_cast<V4 *>(M.p + b0 * M.bs);
         constexpr int NV = S::MPW * G * G / VN;
 #pragma unroll
-        for (int t = 0; t < NV / WAVE; ++t) {
+        for (int t = 0; t < (NV + WAVE - 1) / WAVE; ++t) {
+            if (NV % WAVE != 0 && t * WAVE + lane >= NV)
+                break;
             int e = (t * WAVE + lane) * VN;
             int q = e / (G * G), r = (e / G) % G, c = e % G;
             __builtin_nontemporal_store(*reinterpret_cast<const V4 *>(sm + q * S::MS + r * S::LD + c),
@@ -122,11 +127,11 @@ __device__ __forceinline__ void stage_store(const T *sm, Mem<T> M, int64_t b0, i
         return;
     }
 #pragma unroll 4
-    for (int t = 0; t < S::MPW * G * G / WAVE; ++t) {
+    for (int t = 0; t < (S::MPW * G * G + WAVE - 1) / WAVE; ++t) {
         int e = t * WAVE + lane;
         int q = e / (G * G);
         int r = (e / G) % G, c = e % G;
-        if (b0 + q < batch && r < nb && c < nb)
+        if (e < S::MPW * G * G && b0 + q < batch && r < nb && c < nb)
             M.p[(b0 + q) * M.bs + r * M.ld + c] = sm[q * S::MS + r * S::LD + c];
     }
 }
