@@ -449,6 +449,15 @@ template <typename T>
 la_status launch_trsm_leaf16(View<const T> Lam, View<const T> Xin, View<T> X, int64_t batch, int n, int m, T alpha,
                              bool fwd, hipStream_t st);
 
+// The same solve for 128 < n <= 512 as one launch: one workgroup per batch item and slab of 16
+// vectors, the factor streamed from memory.  trsm_stream_takes says for which shapes that is the
+// quicker way.  X may alias Xin.
+template <typename T>
+bool trsm_stream_takes(int64_t batch, int n, int m);
+template <typename T>
+la_status launch_trsm_stream(View<const T> Lam, View<const T> Xin, View<T> X, int64_t batch, int n, int m, T alpha,
+                             bool fwd, hipStream_t st);
+
 // potrf backward with one workgroup per matrix, everything in LDS as 16 x 16 tiles, for
 // n <= backward_leaf16_max_n<T>() (128 in fp32, 96 in fp64).  Abar may alias G.
 template <typename T>

@@ -460,6 +460,12 @@ static la_status tri_apply_v(bool solve, bool fwd, T alpha, int64_t batch, int n
     if (solve && n <= 128 && m <= 48)  // small: one workgroup per item does the whole substitution, no scratch
         return launch_trsm_leaf16<T>(Lam, Xin, X, batch, n, m, alpha, fwd, st);
 
+    if (solve && trsm_stream_takes<T>(batch, n, m)) {  // one launch, no scratch
+        const la_status s = launch_trsm_stream<T>(Lam, Xin, X, batch, n, m, alpha, fwd, st);
+        if (s != LA_ERR_UNSUPPORTED)  // (strides beyond its 32-bit offsets, two-level batches: the blocked path below)
+            return s;
+    }
+
     ArenaFrame frame;
     if (solve && n <= NB) {  // inverse of the single block, then one product in place
         if (!inplace || alpha != T(1))

@@ -16,6 +16,7 @@
 // wavefront 0 walks exactly that chain while the other seven do the rest of (b) and (c) of
 // step k behind it (two workgroup barriers per step).
 #include "common.hpp"
+#include "leaf_dpp.hpp"
 
 #ifndef LEAF16_STAMP
 #define LEAF16_STAMP(i)
@@ -23,7 +24,6 @@
 
 namespace la {
 
-constexpr int LT = 16;              // tile edge
 constexpr int LK = 8;               // tiles per block edge (128 / 16)
 constexpr int LEAF16_THREADS = 1024;
 constexpr int LEAF16_WAVES = LEAF16_THREADS / 64;
@@ -45,69 +45,6 @@ struct Leaf16 {
 };
 
 __device__ __forceinline__ int tri_off(int i, int j) { return i * (i - 1) / 2 + j; }  // i > j
-
-// acc -= (value of src in lane K of the 16-lane row) * other, one instruction.  The hardware
-// needs two wait states between a VALU write of src and this read of it; callers keep that.
-template <int K>
-__device__ __forceinline__ void fnmac_row(float &acc, float src, float other)
-{
-    asm volatile("v_fmac_f32_dpp %0, -%1, %2 row_newbcast:%3 row_mask:0xf bank_mask:0xf"
-                 : "+v"(acc)
-                 : "v"(src), "v"(other), "n"(K));
-}
-template <int K>
-__device__ __forceinline__ void fnmac_row(double &acc, double src, double other)
-{
-    asm volatile("v_fmac_f64_dpp %0, -%1, %2 row_newbcast:%3 row_mask:0xf bank_mask:0xf"
-                 : "+v"(acc)
-                 : "v"(src), "v"(other), "n"(K));
-}
-// acc -= (value of acc in lane K of the row) * other
-template <int K>
-__device__ __forceinline__ void fnmac_row_self(float &acc, float other)
-{
-    asm volatile("v_fmac_f32_dpp %0, -%0, %1 row_newbcast:%2 row_mask:0xf bank_mask:0xf" : "+v"(acc) : "v"(other), "n"(K));
-}
-template <int K>
-__device__ __forceinline__ void fnmac_row_self(double &acc, double other)
-{
-    asm volatile("v_fmac_f64_dpp %0, -%0, %1 row_newbcast:%2 row_mask:0xf bank_mask:0xf" : "+v"(acc) : "v"(other), "n"(K));
-}
-// (value of src in lane K of the row) * other
-template <int K>
-__device__ __forceinline__ float mul_row(float src, float other)
-{
-    float d = 0.0f;
-    asm volatile("v_fmac_f32_dpp %0, %1, %2 row_newbcast:%3 row_mask:0xf bank_mask:0xf"
-                 : "+v"(d)
-                 : "v"(src), "v"(other), "n"(K));
-    return d;
-}
-template <int K>
-__device__ __forceinline__ double mul_row(double src, double other)
-{
-    double d = 0.0;
-    asm volatile("v_fmac_f64_dpp %0, %1, %2 row_newbcast:%3 row_mask:0xf bank_mask:0xf"
-                 : "+v"(d)
-                 : "v"(src), "v"(other), "n"(K));
-    return d;
-}
-// two wait states, with v routed through the statement so that whatever computes it stays before
-template <typename T>
-__device__ __forceinline__ void settle(T &v)
-{
-    asm volatile("s_nop 1" : "+v"(v));
-}
-
-__device__ __forceinline__ float rcp_newton(float x) { return __builtin_amdgcn_rcpf(x); }
-__device__ __forceinline__ double rcp_newton(double x)
-{
-    double r = __builtin_amdgcn_rcp(x);
-    double e = fma(-x, r, 1.0);
-    r = fma(r, e, r);
-    e = fma(-x, r, 1.0);
-    return fma(r, e, r);
-}
 
 // Factor and invert one 16 x 16 tile held one row per lane.  All four 16-lane rows of the
 // wavefront factor copies of the same tile; the inverse is shared out between them: in lane row
@@ -544,32 +481,6 @@ __global__ __launch_bounds__(LEAF16_THREADS) void k_potrf_leaf16(View<const T> A
 // onto the diagonal blocks of Inv.  Same tiles and matrix-core steps as above without the
 // factorisation, so the 16 x 16 diagonal tiles are inverted all at once.
 // ---------------------------------------------------------------------------------------
-
-// x = row r of the inverse of a 16 x 16 lower-triangular tile (a[c] = row r of the tile, dr its
-// diagonal entry), columns shared out over the lane rows as in diag_factor_invert.  With
-// m_rk = l_rk / l_kk the unit-triangular factor M = L diag(l)^-1 is inverted by
-//   y_r. -= m_rk y_k.  (r > k),   k = 0, 1, ...   and   L^-1 = diag(l)^-1 M^-1.
-template <typename T>
-__device__ __forceinline__ void diag_invert(const T (&a)[LT], T dr, T (&x)[4], int r, int g)
-{
-#pragma unroll
-    for (int j = 0; j < 4; ++j)
-        x[j] = (4 * j + g == r) ? T(1) : T(0);
-    T rinv = rcp_newton(dr);
-    settle(rinv);
-    static_for<0, LT - 1>([&](auto kc) {
-        constexpr int k = decltype(kc)::value;
-        const T am = (r > k) ? a[k] : T(0);
-        const T t = mul_row<k>(rinv, am);
-        static_for<0, k / 4 + 1>([&](auto jc) {
-            constexpr int j = decltype(jc)::value;
-            fnmac_row_self<k>(x[j], t);
-        });
-    });
-#pragma unroll
-    for (int j = 0; j < 4; ++j)
-        x[j] *= rinv;
-}
 
 template <typename T>
 __global__ __launch_bounds__(LEAF16_THREADS) void k_tri_inv_leaf16(View<const T> Lam, View<T> Inv, int64_t batch, int n,

@@ -101,7 +101,8 @@ def test_workspace_sizes_are_host_only_and_cover_the_blocked_paths(lib):
             assert w > prev and w % 256 == 0
             prev = w
         assert lib.la_workspace_bytes(BACKWARD, dt, 32, 512, 0, 0) >= 2 * 32 * 512 * 512 * es
-        assert lib.la_workspace_bytes(TRSM, dt, 32, 512, 64, 0) >= 32 * 512 * 512 * es
+        assert lib.la_workspace_bytes(TRSM, dt, 32, 512, 64, 0) == 0  # one launch that streams the factor
+        assert lib.la_workspace_bytes(TRSM, dt, 8, 1024, 64, 0) >= 8 * 1024 * 1024 * es
     # bad arguments
     assert lib.la_workspace_bytes(99, 0, 1, 512, 0, 0) == 0
     assert lib.la_workspace_bytes(POTRF, 5, 1, 512, 0, 0) == 0
@@ -124,7 +125,7 @@ def test_blocked_call_without_enough_workspace_is_refused_before_any_launch(lib)
     assert lib.la_potrf_batched_ws(1, 1, 1, n, p, q, none, none, 0, none) == WORKSPACE
     assert lib.la_potrf_batched_ws(1, 1, 1, n, p, q, none, w, need - 256, none) == WORKSPACE
     assert lib.la_potrf_backward(1, 1, 1, n, p, q, w, none) == WORKSPACE
-    assert lib.la_trsm_batched(1, 1, 0, 0, 1.0, 1, n, 64, p, q, w, none) == WORKSPACE
+    assert lib.la_trsm_batched(1, 1, 0, 0, 1.0, 1, 1024, 64, p, q, w, none) == WORKSPACE  # (n <= 512 needs none)
     # misaligned workspace, workspace over an operand
     assert lib.la_potrf_batched_ws(1, 1, 1, n, p, q, none, ctypes.c_void_p((3 << 30) + 8), need, none) == INVALID
     assert lib.la_potrf_batched_ws(1, 1, 1, n, p, q, none, ctypes.c_void_p((1 << 30) + 256), need, none) == INVALID

@@ -265,7 +265,8 @@ def test_backward_closed_forms(la, orc):
 @pytest.mark.parametrize("dtype", ["f64", "f32"])
 @pytest.mark.parametrize("lower,trans,rightside", FLAGS)
 @pytest.mark.parametrize("n,m", [(1, 1), (5, 3), (17, 17), (32, 8), (64, 64), (65, 7), (100, 33), (100, 130), (113, 20), (128, 1),
-                                 (128, 48), (128, 49), (200, 33), (257, 70)])
+                                 (128, 48), (128, 49), (200, 33), (257, 70), (129, 1), (300, 5), (400, 16),
+                                 (512, 64)])
 def test_trsm_parity(la, orc, dtype, lower, trans, rightside, n, m):
     batch = 3
     T = tri(n + m, batch, n, lower, dtype)
