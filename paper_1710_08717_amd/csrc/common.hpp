@@ -485,7 +485,7 @@ la_status launch_gemm2_tiny(int ta, int tb, T alpha, int64_t batch, int m, int n
 template <typename T>
 la_status launch_symm_tiny(bool img_tr, T alpha, int64_t batch, int n, int k, View<const T> Gb, const T *A, T *Out,
                            hipStream_t st);
-// potri for n <= 16: B = Lam^-T Lam^-1, exactly symmetric
+// potri for n <= 32: B = Lam^-T Lam^-1, exactly symmetric
 template <typename T>
 la_status launch_potri_tiny(View<const T> Lam, View<T> B, int64_t batch, int n, hipStream_t st);
 // Register-resident potrf backward for n <= 32: Abar = sym(L^-T Phi(L^T Lbar) L^-1).

@@ -667,7 +667,7 @@ template <typename T>
 static la_status potri_t(int lower, int64_t batch, int n, const void *L, void *B, hipStream_t st)
 {
     View<const T> Lam = tri_view<const T>((const T *)L, n, lower);
-    if (n <= 16)  // both solves on the identity in registers, G lanes per matrix
+    if (n <= 32)  // both solves on the identity in registers, G lanes per matrix (two rows per lane above 16)
         return launch_potri_tiny<T>(Lam, View<T>{(T *)B, (int64_t)n * n, n, 1}, batch, n, st);
     ArenaFrame frame;
     View<T> sc[2];

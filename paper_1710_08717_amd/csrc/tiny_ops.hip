@@ -643,14 +643,144 @@ __global__ __launch_bounds__(WAVE) void k_potri_tiny(View<const T> Lam, View<T> 
     stage_store<T, G>(sm, mem_of(B), b0, batch, n);  // symmetric: orientation is immaterial
 }
 
+// ---------------------------------------------------------------------------------
+// potri for 16 < n <= 32 in 16 lanes per matrix: lane i owns the rows i and i + 16 (slot h = 0, 1) of the
+// factor and of the result, so every broadcast is a DPP row broadcast; row k = 16 kh + kl lives in slot kh
+// of lane kl.  Same two substitutions as k_potri_tiny, restricted to the columns that can be non-zero
+// (Lam^-1 is lower triangular) or that are kept (the lower triangle of the symmetric result): row k takes
+// part with its columns 0 .. k, in blocks of four.  N: the column count kept (24 or 32).
+// ---------------------------------------------------------------------------------
+template <typename T, int N>
+__global__ __launch_bounds__(WAVE) void k_potri_tiny2(View<const T> Lam, View<T> B, int64_t batch, int n)
+{
+    constexpr int G = 16, MPW = WAVE / G;
+    static_assert(N > G && N <= 2 * G && N % 4 == 0, "column count does not fit two row slots");
+    using S = Stage<T, N, MPW>;
+    __shared__ __align__(16) T sm[S::ELEMS];
+    const int lane = threadIdx.x;
+    const int q = lane / G, i = lane % G;
+    const int64_t b0 = (int64_t)blockIdx.x * MPW;
+    T *smq = sm + q * S::MS;
+    const bool own1 = (N == 2 * G) || i + G < N;  // does row i + 16 exist among the N kept?
+    const int i1 = own1 ? i + G : N - 1;
+    const Mem<const T> Lm = mem_of(Lam);
+    stage_load<T, N, MPW>(sm, Lm, b0, batch, n);  // identity outside n x n
+    __syncthreads();
+
+    // X = Lam^-1, rows r: x_r = (e_r - sum_{k < r} l_rk x_k) / l_rr
+    T m0[N], m1[N];
+    read_lrow<T, N>(smq, i, Lm.tr, m0);
+    read_lrow<T, N>(smq, i1, Lm.tr, m1);
+    T d0 = T(1), d1 = T(1);
+#pragma unroll
+    for (int k = 0; k < N; ++k) {
+        if (k == i)
+            d0 = m0[k];
+        if (own1 && k == i + G)
+            d1 = m1[k];
+    }
+    const T r0 = rcp_acc(d0), r1 = rcp_acc(d1);
+    T x0[N], x1[N];
+#pragma unroll
+    for (int k = 0; k < N; ++k) {
+        m0[k] = (k < i) ? m0[k] * r0 : T(0);
+        m1[k] = (own1 && k < i + G) ? m1[k] * r1 : T(0);
+        x0[k] = (k == i) ? r0 : T(0);
+        x1[k] = (own1 && k == i + G) ? r1 : T(0);
+    }
+    dpp_settle<G>(x0);
+    dpp_settle<G>(x1);
+    static_for<0, N>([&](auto Kk) {
+        constexpr int kk = decltype(Kk)::value;
+        constexpr int kl = kk % G, kh = kk / G;
+        static_for<0, kk / 4 + 1>([&](auto CB) {
+            constexpr int c0 = 4 * decltype(CB)::value;
+            if constexpr (kh == 0) {  // row kk < 16 reaches the later rows of both slots
+                static_for<0, 4>([&](auto J) {
+                    constexpr int c = c0 + decltype(J)::value;
+                    fma_bcast<G, kl>(x1[c], x0[c], m1[kk], true);
+                });
+                static_for<0, 4>([&](auto J) {
+                    constexpr int c = c0 + decltype(J)::value;
+                    fma_bcast<G, kl>(x0[c], x0[c], m0[kk], true);
+                });
+            } else {  // the rows 0 .. 15 have nothing in column kk >= 16
+                static_for<0, 4>([&](auto J) {
+                    constexpr int c = c0 + decltype(J)::value;
+                    fma_bcast<G, kl>(x1[c], x1[c], m1[kk], true);
+                });
+            }
+        });
+    });
+
+    // B = Lam^-T X, rows from the bottom: b_r = (x_r - sum_{k > r} l_kr b_k) / l_rr
+    read_lcol<T, N>(smq, i, Lm.tr, m0);
+    read_lcol<T, N>(smq, i1, Lm.tr, m1);
+#pragma unroll
+    for (int k = 0; k < N; ++k) {
+        m0[k] = (k > i) ? m0[k] * r0 : T(0);
+        m1[k] = (own1 && k > i + G) ? m1[k] * r1 : T(0);
+        x0[k] *= r0;
+        x1[k] *= r1;
+    }
+    dpp_settle<G>(x0);
+    dpp_settle<G>(x1);
+    static_for<0, N>([&](auto Kk) {
+        constexpr int kk = N - 1 - decltype(Kk)::value;
+        constexpr int kl = kk % G, kh = kk / G;
+        static_for<0, kk / 4 + 1>([&](auto CB) {
+            constexpr int c0 = 4 * decltype(CB)::value;
+            if constexpr (kh == 1) {  // row kk >= 16 reaches the earlier rows of both slots
+                static_for<0, 4>([&](auto J) {
+                    constexpr int c = c0 + decltype(J)::value;
+                    fma_bcast<G, kl>(x0[c], x1[c], m0[kk], true);
+                });
+                static_for<0, 4>([&](auto J) {
+                    constexpr int c = c0 + decltype(J)::value;
+                    fma_bcast<G, kl>(x1[c], x1[c], m1[kk], true);
+                });
+            } else {
+                static_for<0, 4>([&](auto J) {
+                    constexpr int c = c0 + decltype(J)::value;
+                    fma_bcast<G, kl>(x0[c], x0[c], m0[kk], true);
+                });
+            }
+        });
+    });
+
+    // the upper triangle from the lower one through the stage (exactly symmetric result)
+    __syncthreads();
+    write_row<T, N>(smq, i, x0);
+    if (own1)
+        write_row<T, N>(smq, i + G, x1);
+    __syncthreads();
+    read_col<T, N>(smq, i, m0);
+    read_col<T, N>(smq, i1, m1);
+#pragma unroll
+    for (int c = 0; c < N; ++c) {
+        x0[c] = (c <= i) ? x0[c] : m0[c];
+        x1[c] = (c <= i + G) ? x1[c] : m1[c];
+    }
+    __syncthreads();
+    write_row<T, N>(smq, i, x0);
+    if (own1)
+        write_row<T, N>(smq, i + G, x1);
+    __syncthreads();
+    stage_store<T, N, MPW>(sm, mem_of(B), b0, batch, n);  // symmetric: orientation is immaterial
+}
+
 template <typename T>
 la_status launch_potri_tiny(View<const T> Lam, View<T> B, int64_t batch, int n, hipStream_t st)
 {
     if (batch <= 0 || n <= 0)
         return LA_OK;
-    if (n > 16 || (batch + 3) / 4 > 0x7fffffffll)
+    if (n > 32 || (batch + 3) / 4 > 0x7fffffffll)
         return LA_ERR_UNSUPPORTED;
-    if (n <= 4) {
+    if (n > 24) {
+        LA_LAUNCH((k_potri_tiny2<T, 32>), dim3((unsigned)((batch + 3) / 4)), dim3(WAVE), 0, st, Lam, B, batch, n);
+    } else if (n > 16) {
+        LA_LAUNCH((k_potri_tiny2<T, 24>), dim3((unsigned)((batch + 3) / 4)), dim3(WAVE), 0, st, Lam, B, batch, n);
+    } else if (n <= 4) {
         constexpr int MPW = Stage<T, 4>::MPW;
         LA_LAUNCH((k_potri_tiny<T, 4>), dim3((unsigned)((batch + MPW - 1) / MPW)), dim3(WAVE), 0, st, Lam, B, batch, n);
     } else if (n <= 8) {

@@ -238,7 +238,7 @@ def spd(seed, batch, n, dtype):
 
 @pytest.mark.parametrize("dtype", ["f64", "f32"])
 @pytest.mark.parametrize("lower", [True, False])
-@pytest.mark.parametrize("n", [1, 5, 16, 33, 64, 100, 128, 200, 384])
+@pytest.mark.parametrize("n", [1, 5, 16, 17, 24, 25, 32, 33, 64, 100, 128, 200, 384])
 def test_potri_parity(la, orc, dtype, lower, n):
     batch = 3
     A = spd(5000 + n, batch, n, dtype)
@@ -257,9 +257,11 @@ def test_potri_parity(la, orc, dtype, lower, n):
 
 @pytest.mark.parametrize("dtype", ["f64", "f32"])
 @pytest.mark.parametrize("lower", [True, False])
-@pytest.mark.parametrize("n,batch", [(16, 4099), (13, 1030), (8, 4101), (6, 259), (4, 4111), (3, 70001), (2, 19), (1, 70)])
+@pytest.mark.parametrize("n,batch", [(16, 4099), (13, 1030), (8, 4101), (6, 259), (4, 4111), (3, 70001), (2, 19), (1, 70),
+                                     (32, 1027), (29, 4098), (24, 515), (20, 130), (17, 5)])
 def test_potri_small_sizes_with_many_matrices(la, orc, dtype, lower, n, batch):
-    """n <= 16: 16, 8 or 4 lanes per matrix, both solves in registers; ragged last wavefronts."""
+    """n <= 16: 16, 8 or 4 lanes per matrix; 16 < n <= 32: 16 lanes per matrix with two rows per lane and 24 or 32
+    columns kept.  Both solves in registers; ragged last wavefronts."""
     A = spd(7000 + n, batch, n, dtype)
     F = orc.potrf(A, lower=lower).astype(npdt(dtype))
     ref = orc.potri(F, lower=lower)

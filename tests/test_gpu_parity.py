@@ -346,6 +346,29 @@ def test_trsm_block_substitution_path(la, orc, dtype, lower, trans, rightside, n
 
 
 @pytest.mark.parametrize("dtype", ["f64", "f32"])
+@pytest.mark.parametrize("lower,trans,rightside", FLAGS)
+@pytest.mark.parametrize("n,m,batch", [(130, 17, 70), (260, 40, 300), (384, 16, 9), (500, 100, 5), (512, 530, 2)])
+def test_trsm_streamed_factor_path(la, orc, dtype, lower, trans, rightside, n, m, batch):
+    """128 < n <= 512: one launch, one workgroup per item and slab of 16 vectors.  Two, three and four tile rows
+    per wavefront, ragged last tiles and slabs, more workgroups than the chip holds at once, both triangles
+    (an upper factor is read through 8-byte loads, a lower one through 16-byte loads), forward and backward
+    substitution, out of place (the other triangle holds NaN) and in place; each item judged on its own."""
+    T = tri(n * 7 + m, batch, n, lower, dtype)
+    other = np.triu_indices(n, 1) if lower else np.tril_indices(n, -1)
+    Tj = T.copy()
+    Tj[:, other[0], other[1]] = np.nan  # never read
+    rng = np.random.default_rng(n * 1000 + m)
+    A = rng.standard_normal((batch, m, n) if rightside else (batch, n, m)).astype(npdt(dtype))
+    ref = orc.trsm(T, A, lower=lower, trans=trans, rightside=rightside, alpha=0.75)
+    out = host(la.trsm(dev(Tj), dev(A), lower=lower, trans=trans, rightside=rightside, alpha=0.75))
+    per = np.linalg.norm((out - ref).reshape(batch, -1), axis=1) / np.linalg.norm(ref.reshape(batch, -1), axis=1)
+    assert per.max() <= TOL[dtype]
+    a = dev(A)
+    out2 = host(la.trsm(dev(Tj), a, lower=lower, trans=trans, rightside=rightside, alpha=0.75, out=a))  # in place
+    assert np.array_equal(out, out2)
+
+
+@pytest.mark.parametrize("dtype", ["f64", "f32"])
 def test_potrf_backward_ragged_large(la, orc, dtype):
     """A size that is no multiple of 64 above every small-matrix shortcut."""
     n, batch = 1100, 1
