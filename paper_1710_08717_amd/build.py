@@ -14,7 +14,7 @@ CSRC = os.path.join(PKG, "csrc")
 BUILD = os.path.join(PKG, "_build")
 LIB = os.path.join(PKG, "libla_mi355x.so")
 
-SOURCES = ["tiny.hip", "tiny_ops.hip", "leaf.hip", "trsm_stream.hip", "gemm.hip", "elem.hip", "kalman.hip", "la_api.hip"]
+SOURCES = ["tiny.hip", "tiny_ops.hip", "tiny_rows.hip", "leaf.hip", "trsm_stream.hip", "gemm.hip", "elem.hip", "kalman.hip", "la_api.hip"]
 FLAGS = [
     "--offload-arch=gfx950",
     "-O3",

@@ -485,6 +485,13 @@ la_status launch_gemm2_tiny(int ta, int tb, T alpha, int64_t batch, int m, int n
 template <typename T>
 la_status launch_symm_tiny(bool img_tr, T alpha, int64_t batch, int n, int k, View<const T> Gb, const T *A, T *Out,
                            hipStream_t st);
+// The same products for 16 < n <= 32 and k <= 32 (16 lanes per matrix, two rows per lane); outer_rows_takes
+// says whether the shape fits (two images of fp64 operands can exceed the LDS of one workgroup).
+template <typename T>
+bool outer_rows_takes(int n, int k, bool two);
+template <typename T>
+la_status launch_outer_rows(bool img_tr, int tri, T alpha, int64_t batch, int n, int k, const T *U, const T *V, View<T> C,
+                            hipStream_t st);
 // potri for n <= 32: B = Lam^-T Lam^-1, exactly symmetric
 template <typename T>
 la_status launch_potri_tiny(View<const T> Lam, View<T> B, int64_t batch, int n, hipStream_t st);

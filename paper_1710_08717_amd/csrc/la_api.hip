@@ -556,6 +556,8 @@ static la_status syrk_t(int trans, double alpha, int64_t batch, int n, int k, co
     View<T> C{(T *)B, nn, n, 1};
     if (n <= 16 && k >= 1 && k <= 32)  // G lanes per matrix, HBM bound
         return launch_syrk_tiny<T>(trans != 0, (T)alpha, batch, n, k, (const T *)A, C, st);
+    if (outer_rows_takes<T>(n, k, false))  // 16 < n <= 32: 16 lanes per matrix, two rows per lane
+        return launch_outer_rows<T>(trans != 0, 0, (T)alpha, batch, n, k, (const T *)A, (const T *)A, C, st);
     GemmOpts o;
     o.maskC = 1;
     LA_TRY(launch_gemm<T>(Ank, Ank.t(), C, batch, n, n, k, (T)alpha, T(0), o, st));
@@ -593,9 +595,11 @@ static la_status tri_outer_t(int lower, int trans, int rightside, T scale, int64
 {
     const int64_t nn = (int64_t)n * n, nm = (int64_t)n * m;
     View<T> G{out, nn, n, 1};
-    if (n <= 16 && m >= 1 && m <= 32) {  // G lanes per matrix: product, mask and zeros in one launch
+    if ((n <= 16 && m >= 1 && m <= 32) || outer_rows_takes<T>(n, m, true)) {  // lane groups: product, mask and zeros in one launch
         const T *U = rightside ? (trans ? P : Q) : (trans ? Q : P), *V = rightside ? (trans ? Q : P) : (trans ? P : Q);
-        return launch_outer_tiny<T>(rightside != 0, lower ? 1 : 2, scale, batch, n, m, U, V, G, st);
+        if (n <= 16)
+            return launch_outer_tiny<T>(rightside != 0, lower ? 1 : 2, scale, batch, n, m, U, V, G, st);
+        return launch_outer_rows<T>(rightside != 0, lower ? 1 : 2, scale, batch, n, m, U, V, G, st);
     }
     LA_TRY(launch_zero_strict_upper<T>(lower ? G : G.t(), batch, n, st));  // the other triangle of the result
     GemmOpts o;

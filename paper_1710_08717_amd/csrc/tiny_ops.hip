@@ -20,7 +20,6 @@ namespace la {
 // ---------------------------------------------------------------------------------
 constexpr int TRI_MC = 16;  // vectors per matrix, at most
 
-__device__ __forceinline__ int img_idx(int e) { return e + (e >> 4); }
 
 template <typename T, int G, bool SOLVE>
 __global__ __launch_bounds__(WAVE) void k_tri_tiny(View<const T> Lam, const T *Bin, T *Bout, int64_t batch, int n, int m,
@@ -220,39 +219,6 @@ template la_status launch_tri_tiny<double>(bool, bool, double, int64_t, int, int
 // ---------------------------------------------------------------------------------
 constexpr int SYRK_KC = 32;
 
-// flat image of cnt items of `per` elements each into LDS (16-byte loads when whole and aligned)
-template <typename T, int IMG, int MPW>
-__device__ __forceinline__ void image_load(T *img, const T *base, int64_t b0, int cnt, int per, int lane)
-{
-    using V4 = typename VecOf<T>::type;
-    constexpr int VN = VecOf<T>::N;
-    const int tot = cnt * per;
-    const T *src = base + b0 * per;
-    if ((cnt == MPW) && ((MPW * per) % VN == 0) && ((reinterpret_cast<uintptr_t>(base) & 15) == 0)) {
-        constexpr int ITV = (IMG / VN + WAVE - 1) / WAVE;
-        const int nvec = tot / VN;
-        V4 v[ITV];
-#pragma unroll
-        for (int t = 0; t < ITV; ++t)
-            if (t * WAVE + lane < nvec)
-                v[t] = __builtin_nontemporal_load(reinterpret_cast<const V4 *>(src) + t * WAVE + lane);
-#pragma unroll
-        for (int t = 0; t < ITV; ++t)
-            if (t * WAVE + lane < nvec) {
-                const int e = (t * WAVE + lane) * VN;
-                img[img_idx(e)] = v[t].x;
-                img[img_idx(e + 1)] = v[t].y;
-                if constexpr (VN == 4) {
-                    img[img_idx(e + 2)] = v[t].z;
-                    img[img_idx(e + 3)] = v[t].w;
-                }
-            }
-    } else {
-        for (int e = lane; e < tot; e += WAVE)
-            img[img_idx(e)] = src[e];
-    }
-}
-
 // C = alpha U V^T for n x k operands U, V (V == U: syrk); tri = 0 writes the whole square, 1 / 2 keep
 // the lower / upper triangle and write zeros to the other one (the gradient of a triangular
 // operand in the trmm / trsm backward rules, section 4.2).
@@ -371,36 +337,6 @@ template la_status launch_outer_tiny<double>(bool, int, double, int64_t, int, in
                                              View<double>, hipStream_t);
 template la_status launch_syrk_tiny<float>(bool, float, int64_t, int, int, const float *, View<float>, hipStream_t);
 template la_status launch_syrk_tiny<double>(bool, double, int64_t, int, int, const double *, View<double>, hipStream_t);
-
-// flat image back to memory (the mirror of image_load)
-template <typename T, int IMG, int MPW>
-__device__ __forceinline__ void image_store(const T *img, T *base, int64_t b0, int cnt, int per, int lane)
-{
-    using V4 = typename VecOf<T>::type;
-    constexpr int VN = VecOf<T>::N;
-    const int tot = cnt * per;
-    T *dst = base + b0 * per;
-    if ((cnt == MPW) && ((MPW * per) % VN == 0) && ((reinterpret_cast<uintptr_t>(base) & 15) == 0)) {
-        constexpr int ITV = (IMG / VN + WAVE - 1) / WAVE;
-        const int nvec = tot / VN;
-#pragma unroll
-        for (int t = 0; t < ITV; ++t)
-            if (t * WAVE + lane < nvec) {
-                const int e = (t * WAVE + lane) * VN;
-                V4 v;
-                v.x = img[img_idx(e)];
-                v.y = img[img_idx(e + 1)];
-                if constexpr (VN == 4) {
-                    v.z = img[img_idx(e + 2)];
-                    v.w = img[img_idx(e + 3)];
-                }
-                __builtin_nontemporal_store(v, reinterpret_cast<V4 *>(dst) + t * WAVE + lane);
-            }
-    } else {
-        for (int e = lane; e < tot; e += WAVE)
-            dst[e] = img[img_idx(e)];
-    }
-}
 
 // ---------------------------------------------------------------------------------
 // gemm2 for m, n, k <= 16 (section 4.2 "gemm2"): C = alpha op(A) op(B), G >= max(m, k) lanes per

@@ -205,4 +205,74 @@ __device__ __forceinline__ void read_lcol(const T *smq, int i, bool tr, T (&a)[G
         read_col<T, G>(smq, i, a);
 }
 
+// ---------------------------------------------------------------------------------
+// Operands that are not square travel as flat memory images of whole items through LDS.  The LDS
+// index of image element e is e + e / 16, so that 16 lanes reading a column of a 16-wide image
+// (stride 16) fall into different banks.
+// ---------------------------------------------------------------------------------
+__device__ __forceinline__ int img_idx(int e) { return e + (e >> 4); }
+
+// flat image of cnt items of `per` elements each into LDS (16-byte loads when whole and aligned)
+template <typename T, int IMG, int MPW>
+__device__ __forceinline__ void image_load(T *img, const T *base, int64_t b0, int cnt, int per, int lane)
+{
+    using V4 = typename VecOf<T>::type;
+    constexpr int VN = VecOf<T>::N;
+    const int tot = cnt * per;
+    const T *src = base + b0 * per;
+    if ((cnt == MPW) && ((MPW * per) % VN == 0) && ((reinterpret_cast<uintptr_t>(base) & 15) == 0)) {
+        constexpr int ITV = (IMG / VN + WAVE - 1) / WAVE;
+        const int nvec = tot / VN;
+        V4 v[ITV];
+#pragma unroll
+        for (int t = 0; t < ITV; ++t)
+            if (t * WAVE + lane < nvec)
+                v[t] = __builtin_nontemporal_load(reinterpret_cast<const V4 *>(src) + t * WAVE + lane);
+#pragma unroll
+        for (int t = 0; t < ITV; ++t)
+            if (t * WAVE + lane < nvec) {
+                const int e = (t * WAVE + lane) * VN;
+                img[img_idx(e)] = v[t].x;
+                img[img_idx(e + 1)] = v[t].y;
+                if constexpr (VN == 4) {
+                    img[img_idx(e + 2)] = v[t].z;
+                    img[img_idx(e + 3)] = v[t].w;
+                }
+            }
+    } else {
+        for (int e = lane; e < tot; e += WAVE)
+            img[img_idx(e)] = src[e];
+    }
+}
+
+// flat image back to memory (the mirror of image_load)
+template <typename T, int IMG, int MPW>
+__device__ __forceinline__ void image_store(const T *img, T *base, int64_t b0, int cnt, int per, int lane)
+{
+    using V4 = typename VecOf<T>::type;
+    constexpr int VN = VecOf<T>::N;
+    const int tot = cnt * per;
+    T *dst = base + b0 * per;
+    if ((cnt == MPW) && ((MPW * per) % VN == 0) && ((reinterpret_cast<uintptr_t>(base) & 15) == 0)) {
+        constexpr int ITV = (IMG / VN + WAVE - 1) / WAVE;
+        const int nvec = tot / VN;
+#pragma unroll
+        for (int t = 0; t < ITV; ++t)
+            if (t * WAVE + lane < nvec) {
+                const int e = (t * WAVE + lane) * VN;
+                V4 v;
+                v.x = img[img_idx(e)];
+                v.y = img[img_idx(e + 1)];
+                if constexpr (VN == 4) {
+                    v.z = img[img_idx(e + 2)];
+                    v.w = img[img_idx(e + 3)];
+                }
+                __builtin_nontemporal_store(v, reinterpret_cast<V4 *>(dst) + t * WAVE + lane);
+            }
+    } else {
+        for (int e = lane; e < tot; e += WAVE)
+            dst[e] = img[img_idx(e)];
+    }
+}
+
 }  // namespace la

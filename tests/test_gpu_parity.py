@@ -427,9 +427,11 @@ def test_syrk_large_lower_triangle_tile_counts(la, orc, dtype, n, k):
 @pytest.mark.parametrize("dtype", ["f64", "f32"])
 @pytest.mark.parametrize("trans", [False, True])
 @pytest.mark.parametrize("n,k,batch", [(16, 32, 4099), (16, 1, 70001), (13, 31, 1030), (8, 16, 4101), (7, 5, 259), (4, 8, 4111),
-                                       (3, 32, 1037), (2, 2, 19), (1, 7, 5), (16, 33, 7)])
+                                       (3, 32, 1037), (2, 2, 19), (1, 7, 5), (16, 33, 7),
+                                       (32, 32, 1027), (29, 9, 4098), (24, 32, 515), (20, 1, 130), (17, 31, 5), (32, 33, 6)])
 def test_small_syrk_with_many_matrices(la, orc, dtype, trans, n, k, batch):
-    """n <= 16 with an inner dimension up to 32 runs in 16, 8 or 4 lanes per matrix (k = 33 does not)."""
+    """n <= 16 with an inner dimension up to 32 runs in 16, 8 or 4 lanes per matrix, 16 < n <= 32 in 16 lanes with
+    two rows per lane (k = 33 does not)."""
     rng = np.random.default_rng(n * 50 + k)
     A = rng.standard_normal((batch, k, n) if trans else (batch, n, k)).astype(npdt(dtype))
     ref = orc.syrk(A, trans=trans, alpha=0.5)

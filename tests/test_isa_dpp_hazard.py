@@ -141,7 +141,7 @@ def _compile_isa(name):
         return open(out).read(), ""
 
 
-_ISA_FILES = ["leaf.hip", "tiny.hip", "tiny_ops.hip", "kalman.hip", "trsm_stream.hip"]
+_ISA_FILES = ["leaf.hip", "tiny.hip", "tiny_ops.hip", "kalman.hip", "trsm_stream.hip", "tiny_rows.hip"]
 _isa_cache = {}
 
 
@@ -150,7 +150,7 @@ def _isa_text(name):
     if not _isa_cache:
         from concurrent.futures import ThreadPoolExecutor
 
-        with ThreadPoolExecutor(max_workers=5) as ex:
+        with ThreadPoolExecutor(max_workers=6) as ex:
             for f, res in zip(_ISA_FILES, ex.map(_compile_isa, _ISA_FILES)):
                 _isa_cache[f] = res
     text, err = _isa_cache[name]
@@ -207,4 +207,11 @@ def test_streamed_solve_kernel_respects_dpp_spacing():
     text = _isa_text("trsm_stream.hip")
     hazards, n_dpp = find_hazards(text)
     assert n_dpp >= 100  # the in-register inverses of the diagonal tiles, per element type and row slot
+    assert hazards == []
+
+
+def test_two_rows_per_lane_operator_kernels_respect_dpp_spacing():
+    text = _isa_text("tiny_rows.hip")
+    hazards, n_dpp = find_hazards(text)
+    assert text.count("v_fmac_f32_dpp") >= 1000 and text.count("v_fmac_f64_dpp") >= 1000
     assert hazards == []
