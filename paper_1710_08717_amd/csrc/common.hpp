@@ -492,6 +492,17 @@ bool outer_rows_takes(int n, int k, bool two);
 template <typename T>
 la_status launch_outer_rows(bool img_tr, int tri, T alpha, int64_t batch, int n, int k, const T *U, const T *V, View<T> C,
                             hipStream_t st);
+// syrk backward and gemm2 in the same form (n, respectively m, n and k, up to 32)
+template <typename T>
+bool symm_rows_takes(int n, int k);
+template <typename T>
+la_status launch_symm_rows(bool img_tr, T alpha, int64_t batch, int n, int k, View<const T> Gb, const T *A, T *Out,
+                           hipStream_t st);
+template <typename T>
+bool gemm2_rows_takes(int m, int n, int k);
+template <typename T>
+la_status launch_gemm2_rows(int ta, int tb, T alpha, int64_t batch, int m, int n, int k, const T *A, const T *B, T *C,
+                            hipStream_t st);
 // potri for n <= 32: B = Lam^-T Lam^-1, exactly symmetric
 template <typename T>
 la_status launch_potri_tiny(View<const T> Lam, View<T> B, int64_t batch, int n, hipStream_t st);

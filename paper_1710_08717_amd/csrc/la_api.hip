@@ -574,6 +574,8 @@ static la_status gemm2_t(int ta, int tb, double alpha, int64_t batch, int m, int
     View<T> Cv{(T *)C, sc, n, 1};
     if (m <= 16 && n <= 16 && k >= 1 && k <= 16)  // lane groups of 4, 8 or 16 per item, HBM bound
         return launch_gemm2_tiny<T>(ta, tb, (T)alpha, batch, m, n, k, (const T *)A, (const T *)B, (T *)C, st);
+    if (gemm2_rows_takes<T>(m, n, k))  // up to 32 each: 16 lanes per item, two rows per lane
+        return launch_gemm2_rows<T>(ta, tb, (T)alpha, batch, m, n, k, (const T *)A, (const T *)B, (T *)C, st);
     GemmOpts o;
     return launch_gemm<T>(Av, Bv, Cv, batch, m, n, k, (T)alpha, T(0), o, st);
 }
@@ -651,6 +653,8 @@ static la_status syrk_backward_t(int trans, double alpha, int64_t batch, int n, 
     View<const T> G{(const T *)Bbar, nn, n, 1};
     if (n <= 16 && k >= 1 && k <= 32)  // lane groups of 4, 8 or 16 per matrix, one launch
         return launch_symm_tiny<T>(trans != 0, (T)alpha, batch, n, k, G, (const T *)A, (T *)Abar, st);
+    if (symm_rows_takes<T>(n, k))  // 16 < n <= 32: 16 lanes per matrix, two rows per lane
+        return launch_symm_rows<T>(trans != 0, (T)alpha, batch, n, k, G, (const T *)A, (T *)Abar, st);
     GemmOpts o;
     if (!trans) {
         View<const T> Av{(const T *)A, nk, k, 1};

@@ -162,4 +162,254 @@ template la_status launch_outer_rows<float>(bool, int, float, int64_t, int, int,
 template la_status launch_outer_rows<double>(bool, int, double, int64_t, int, int, const double *, const double *,
                                              View<double>, hipStream_t);
 
+
+// raise the dynamic LDS limit of a kernel once per device (two images of fp64 operands exceed 64 KB)
+template <class K>
+static la_status rows_lds_limit(K kernel, size_t bytes, bool (&done)[64])
+{
+    int dev = 0;
+    LA_HIP(hipGetDevice(&dev));
+    if (dev >= 0 && dev < 64 && !done[dev]) {
+        LA_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                   (int)bytes));
+        done[dev] = true;
+    }
+    return LA_OK;
+}
+
+// ---------------------------------------------------------------------------------
+// syrk backward for 16 < n <= N and inner dimension <= 32 (section 4.2 "syrk"):
+//   Abar = alpha (Bbar + Bbar^T) A   (A n x k; for the k x n operand of the transposed form the same on
+//   its transposed image).  Lane i holds the rows i, i + 16 of S = Bbar + Bbar^T (row + column of the
+// staged Bbar); abar_rc = alpha sum_j s_rj a_jc with a_jc broadcast from slot jh of lane jl, CH columns c
+// per pass, written back over the image of A.
+// ---------------------------------------------------------------------------------
+template <typename T, int N>
+__global__ __launch_bounds__(WAVE) void k_symm_rows(View<const T> Gb, const T *Ain, T *Out, int64_t batch, int n, int k,
+                                                    int img_tr, T alpha)
+{
+    constexpr int G = ROWS_G, MPW = ROWS_MPW, CH = ROWS_CH;
+    constexpr int IMG = MPW * N * ROWS_KMAX;
+    using S = Stage<T, N, MPW>;
+    extern __shared__ __align__(16) unsigned char tiny_lds[];
+    T *sm = reinterpret_cast<T *>(tiny_lds), *img = sm + (S::ELEMS + 3) / 4 * 4;
+    const int lane = threadIdx.x;
+    const int q = lane / G, i = lane % G;
+    const int64_t b0 = (int64_t)blockIdx.x * MPW;
+    const int cnt = (int)((batch - b0) < MPW ? (batch - b0) : MPW);
+    const int nk = n * k;
+    const bool own1 = (N == 2 * G) || i + G < N;
+    const int i1 = own1 ? i + G : N - 1;
+    image_load<T, IMG, MPW>(img, Ain, b0, cnt, nk, lane);
+    stage_load<T, N, MPW>(sm, mem_of(Gb), b0, batch, n);
+    __syncthreads();
+    T s0[N], s1[N];
+    {
+        T t0[N], t1[N];
+        read_row<T, N>(sm + q * S::MS, i, s0);
+        read_col<T, N>(sm + q * S::MS, i, t0);
+        read_row<T, N>(sm + q * S::MS, i1, s1);
+        read_col<T, N>(sm + q * S::MS, i1, t1);
+#pragma unroll
+        for (int j = 0; j < N; ++j) {
+            s0[j] += t0[j];
+            s1[j] += t1[j];
+        }
+    }
+    const bool live0 = (i < n) && (q < cnt), live1 = (i + G < n) && (q < cnt);
+    const int e0 = q * nk + (img_tr ? i : i * k), e1 = q * nk + (img_tr ? i + G : (i + G) * k), estep = img_tr ? n : 1;
+    static_for<0, ROWS_KMAX / CH>([&](auto CB) {
+        constexpr int c0 = CH * decltype(CB)::value;
+        if (c0 < k) {  // the same for all lanes
+            T a0[CH], a1[CH], o0[CH], o1[CH];
+#pragma unroll
+            for (int u = 0; u < CH; ++u) {
+                a0[u] = (live0 && c0 + u < k) ? img[img_idx(e0 + (c0 + u) * estep)] : T(0);
+                a1[u] = (live1 && c0 + u < k) ? img[img_idx(e1 + (c0 + u) * estep)] : T(0);
+                o0[u] = T(0);
+                o1[u] = T(0);
+            }
+            dpp_settle<G>(a0);
+            dpp_settle<G>(a1);
+            static_for<0, N>([&](auto Jj) {
+                constexpr int j = decltype(Jj)::value;
+                constexpr int jl = j % G, jh = j / G;
+                if (j < n) {
+                    static_for<0, CH>([&](auto U) {
+                        constexpr int u = decltype(U)::value;
+                        if constexpr (jh == 0) {
+                            fma_bcast<G, jl>(o0[u], a0[u], s0[j], false);
+                            fma_bcast<G, jl>(o1[u], a0[u], s1[j], false);
+                        } else {
+                            fma_bcast<G, jl>(o0[u], a1[u], s0[j], false);
+                            fma_bcast<G, jl>(o1[u], a1[u], s1[j], false);
+                        }
+                    });
+                }
+            });
+            // every lane holds its entries of these columns in registers: the image can take the result
+#pragma unroll
+            for (int u = 0; u < CH; ++u) {
+                if (live0 && c0 + u < k)
+                    img[img_idx(e0 + (c0 + u) * estep)] = alpha * o0[u];
+                if (live1 && c0 + u < k)
+                    img[img_idx(e1 + (c0 + u) * estep)] = alpha * o1[u];
+            }
+        }
+    });
+    __syncthreads();
+    image_store<T, IMG, MPW>(img, Out, b0, cnt, nk, lane);
+}
+
+template <typename T>
+bool symm_rows_takes(int n, int k)
+{
+    return n > 16 && n <= 32 && k >= 1 && k <= ROWS_KMAX;
+}
+template bool symm_rows_takes<float>(int, int);
+template bool symm_rows_takes<double>(int, int);
+
+template <typename T>
+la_status launch_symm_rows(bool img_tr, T alpha, int64_t batch, int n, int k, View<const T> Gb, const T *A, T *Out,
+                           hipStream_t st)
+{
+    if (batch <= 0 || n <= 0)
+        return LA_OK;
+    if (!symm_rows_takes<T>(n, k) || (batch + 3) / 4 > 0x7fffffffll)
+        return LA_ERR_UNSUPPORTED;
+    if (dry_run())
+        return LA_OK;
+    const dim3 grid((unsigned)((batch + ROWS_MPW - 1) / ROWS_MPW)), blk(WAVE);
+    const int itr = img_tr ? 1 : 0;
+    auto bytes = [&](int stage_elems) { return ((size_t)(stage_elems + 3) / 4 * 4 + rows_image_elems(n * k)) * sizeof(T); };
+    if (n <= 24) {
+        constexpr int SE = Stage<T, 24, ROWS_MPW>::ELEMS;
+        static bool done[64] = {};
+        LA_TRY(rows_lds_limit(&k_symm_rows<T, 24>, ((size_t)(SE + 3) / 4 * 4 + rows_image_elems(24 * ROWS_KMAX)) * sizeof(T), done));
+        LA_LAUNCH((k_symm_rows<T, 24>), grid, blk, bytes(SE), st, Gb, A, Out, batch, n, k, itr, alpha);
+    } else {
+        constexpr int SE = Stage<T, 32, ROWS_MPW>::ELEMS;
+        static bool done[64] = {};
+        LA_TRY(rows_lds_limit(&k_symm_rows<T, 32>, ((size_t)(SE + 3) / 4 * 4 + rows_image_elems(32 * ROWS_KMAX)) * sizeof(T), done));
+        LA_LAUNCH((k_symm_rows<T, 32>), grid, blk, bytes(SE), st, Gb, A, Out, batch, n, k, itr, alpha);
+    }
+    return launch_check("symm_rows");
+}
+
+template la_status launch_symm_rows<float>(bool, float, int64_t, int, int, View<const float>, const float *, float *,
+                                           hipStream_t);
+template la_status launch_symm_rows<double>(bool, double, int64_t, int, int, View<const double>, const double *, double *,
+                                            hipStream_t);
+
+// ---------------------------------------------------------------------------------
+// gemm2 with m, n, k <= 32 and one of them above 16 (section 4.2 "gemm2"): C = alpha op(A) op(B).  Lane i
+// holds the rows i, i + 16 of op(A) (k registers each); c_rj = sum_c a_rc b_cj with b_cj broadcast from
+// slot ch of lane cl, CH columns j of op(B) and C per pass.  All three operands travel as flat images;
+// the image of C takes the place of that of A, which is in registers by then.
+// ---------------------------------------------------------------------------------
+constexpr int GEMM2R_MAX = 32;
+
+template <typename T>
+__global__ __launch_bounds__(WAVE) void k_gemm2_rows(const T *A, const T *B, T *C, int64_t batch, int m, int n, int k, int ta,
+                                                     int tb, T alpha)
+{
+    constexpr int G = ROWS_G, MPW = ROWS_MPW, CH = ROWS_CH, MX = GEMM2R_MAX;
+    constexpr int IMG = MPW * MX * MX;
+    extern __shared__ __align__(16) unsigned char tiny_lds[];
+    const int mk = m * k, kn = k * n, mn = m * n;
+    T *imga = reinterpret_cast<T *>(tiny_lds), *imgb = imga + rows_image_elems(mk > mn ? mk : mn);
+    const int lane = threadIdx.x;
+    const int q = lane / G, i = lane % G;
+    const int64_t b0 = (int64_t)blockIdx.x * MPW;
+    const int cnt = (int)((batch - b0) < MPW ? (batch - b0) : MPW);
+    image_load<T, IMG, MPW>(imga, A, b0, cnt, mk, lane);
+    image_load<T, IMG, MPW>(imgb, B, b0, cnt, kn, lane);
+    __syncthreads();
+    const bool la0 = (q < cnt) && (i < m), la1 = (q < cnt) && (i + G < m);  // rows of op(A) and of C
+    const bool lb0 = (q < cnt) && (i < k), lb1 = (q < cnt) && (i + G < k);  // rows of op(B)
+    const int sa = ta ? m : 1, sb = tb ? k : 1;
+    const int ea0 = q * mk + (ta ? i : i * k), ea1 = q * mk + (ta ? i + G : (i + G) * k);  // op(A)(r, c)
+    const int eb0 = q * kn + (tb ? i : i * n), eb1 = q * kn + (tb ? i + G : (i + G) * n);  // op(B)(r, j)
+    T a0[MX], a1[MX];
+#pragma unroll
+    for (int c = 0; c < MX; ++c) {
+        a0[c] = (la0 && c < k) ? imga[img_idx(ea0 + c * sa)] : T(0);
+        a1[c] = (la1 && c < k) ? imga[img_idx(ea1 + c * sa)] : T(0);
+    }
+    __syncthreads();  // the image of A is in registers: C may overwrite it
+    const int ec0 = q * mn + i * n, ec1 = q * mn + (i + G) * n;
+    static_for<0, MX / CH>([&](auto JB) {
+        constexpr int j0 = CH * decltype(JB)::value;
+        if (j0 < n) {  // the same for all lanes
+            T r0[CH], r1[CH], o0[CH], o1[CH];
+#pragma unroll
+            for (int u = 0; u < CH; ++u) {
+                r0[u] = (lb0 && j0 + u < n) ? imgb[img_idx(eb0 + (j0 + u) * sb)] : T(0);
+                r1[u] = (lb1 && j0 + u < n) ? imgb[img_idx(eb1 + (j0 + u) * sb)] : T(0);
+                o0[u] = T(0);
+                o1[u] = T(0);
+            }
+            dpp_settle<G>(r0);
+            dpp_settle<G>(r1);
+            static_for<0, MX>([&](auto Cc) {
+                constexpr int c = decltype(Cc)::value;
+                constexpr int cl = c % G, ch = c / G;
+                if (c < k) {
+                    static_for<0, CH>([&](auto U) {
+                        constexpr int u = decltype(U)::value;
+                        if constexpr (ch == 0) {
+                            fma_bcast<G, cl>(o0[u], r0[u], a0[c], false);
+                            fma_bcast<G, cl>(o1[u], r0[u], a1[c], false);
+                        } else {
+                            fma_bcast<G, cl>(o0[u], r1[u], a0[c], false);
+                            fma_bcast<G, cl>(o1[u], r1[u], a1[c], false);
+                        }
+                    });
+                }
+            });
+#pragma unroll
+            for (int u = 0; u < CH; ++u) {
+                if (la0 && j0 + u < n)
+                    imga[img_idx(ec0 + j0 + u)] = alpha * o0[u];
+                if (la1 && j0 + u < n)
+                    imga[img_idx(ec1 + j0 + u)] = alpha * o1[u];
+            }
+        }
+    });
+    __syncthreads();
+    image_store<T, IMG, MPW>(imga, C, b0, cnt, mn, lane);
+}
+
+template <typename T>
+bool gemm2_rows_takes(int m, int n, int k)
+{
+    return m >= 1 && n >= 1 && k >= 1 && m <= GEMM2R_MAX && n <= GEMM2R_MAX && k <= GEMM2R_MAX && (m > 16 || n > 16 || k > 16);
+}
+template bool gemm2_rows_takes<float>(int, int, int);
+template bool gemm2_rows_takes<double>(int, int, int);
+
+template <typename T>
+la_status launch_gemm2_rows(int ta, int tb, T alpha, int64_t batch, int m, int n, int k, const T *A, const T *B, T *C,
+                            hipStream_t st)
+{
+    if (batch <= 0 || m <= 0 || n <= 0)
+        return LA_OK;
+    if (!gemm2_rows_takes<T>(m, n, k) || (batch + 3) / 4 > 0x7fffffffll)
+        return LA_ERR_UNSUPPORTED;
+    if (dry_run())
+        return LA_OK;
+    static bool done[64] = {};
+    LA_TRY(rows_lds_limit(&k_gemm2_rows<T>, 2 * (size_t)rows_image_elems(GEMM2R_MAX * GEMM2R_MAX) * sizeof(T), done));
+    const int mk = m * k, mn = m * n;
+    const size_t lds = ((size_t)rows_image_elems(mk > mn ? mk : mn) + rows_image_elems(k * n)) * sizeof(T);
+    LA_LAUNCH((k_gemm2_rows<T>), dim3((unsigned)((batch + ROWS_MPW - 1) / ROWS_MPW)), dim3(WAVE), lds, st, A, B, C, batch, m, n,
+              k, ta, tb, alpha);
+    return launch_check("gemm2_rows");
+}
+
+template la_status launch_gemm2_rows<float>(int, int, float, int64_t, int, int, int, const float *, const float *, float *,
+                                            hipStream_t);
+template la_status launch_gemm2_rows<double>(int, int, double, int64_t, int, int, int, const double *, const double *,
+                                             double *, hipStream_t);
+
 }  // namespace la

@@ -149,9 +149,11 @@ def test_small_backward_rules_with_many_matrices(la, orc, dtype, lower, trans, r
 @pytest.mark.parametrize("dtype", ["f64", "f32"])
 @pytest.mark.parametrize("trans", [False, True])
 @pytest.mark.parametrize("n,k,batch", [(16, 32, 1031), (16, 1, 70001), (13, 31, 515), (8, 16, 4101), (5, 20, 66), (4, 8, 4111),
-                                       (3, 32, 1037), (1, 1, 5), (16, 33, 9)])
+                                       (3, 32, 1037), (1, 1, 5), (16, 33, 9),
+                                       (32, 32, 1027), (29, 9, 4098), (24, 32, 515), (20, 1, 130), (17, 31, 5), (32, 33, 6)])
 def test_small_syrk_backward_with_many_matrices(la, orc, dtype, trans, n, k, batch):
-    """n <= 16 with an inner dimension up to 32: one lane-group launch (k = 33 takes the tiled path)."""
+    """n <= 32 with an inner dimension up to 32: one lane-group launch, two rows per lane above n = 16 (k = 33 takes
+    the tiled path)."""
     rng = np.random.default_rng(5000 + n + k)
     A = rng.standard_normal((batch, k, n) if trans else (batch, n, k)).astype(npdt(dtype))
     G = (rng.standard_normal((batch, n, n)) / np.sqrt(n)).astype(npdt(dtype))  # not symmetric

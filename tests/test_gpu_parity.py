@@ -480,9 +480,12 @@ def test_gemm2_parity(la, orc, dtype, ta, tb, m, n, k):
 @pytest.mark.parametrize("tb", [False, True])
 @pytest.mark.parametrize("m,n,k,batch", [(16, 16, 16, 4099), (16, 1, 16, 70001), (3, 16, 9, 1030), (8, 8, 8, 4101),
                                          (2, 13, 7, 259), (4, 4, 4, 4111), (4, 16, 3, 1037), (9, 2, 4, 19), (1, 1, 1, 70),
-                                         (16, 16, 17, 5), (16, 17, 16, 5), (17, 16, 16, 5)])
+                                         (16, 16, 17, 5), (16, 17, 16, 5), (17, 16, 16, 5),
+                                         (32, 32, 32, 1027), (24, 16, 32, 4098), (3, 32, 9, 515), (32, 1, 17, 130),
+                                         (20, 27, 5, 66), (1, 1, 32, 7), (33, 32, 32, 3), (32, 32, 33, 3)])
 def test_small_gemm2_with_many_matrices(la, orc, dtype, ta, tb, m, n, k, batch):
-    """m, n, k <= 16 run in lane groups of 4, 8 or 16 per item (the last three shapes do not)."""
+    """m, n, k <= 16 run in lane groups of 4, 8 or 16 per item, up to 32 in 16 lanes with two rows per lane (the
+    last two shapes do not)."""
     rng = np.random.default_rng(m + 3 * n + 7 * k)
     A = rng.standard_normal((batch, k, m) if ta else (batch, m, k)).astype(npdt(dtype))
     B = rng.standard_normal((batch, n, k) if tb else (batch, k, n)).astype(npdt(dtype))
