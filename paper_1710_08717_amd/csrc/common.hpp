@@ -492,6 +492,10 @@ bool outer_rows_takes(int n, int k, bool two);
 template <typename T>
 la_status launch_outer_rows(bool img_tr, int tri, T alpha, int64_t batch, int n, int k, const T *U, const T *V, View<T> C,
                             hipStream_t st);
+// trsm / trmm for 16 < n <= 32 and at most 16 vectors in that form (arguments as launch_tri_tiny)
+template <typename T>
+la_status launch_tri_rows(bool solve, bool fwd, T alpha, int64_t batch, int n, int m, View<const T> Lam, const T *Bin, T *Bout,
+                          bool img_tr, hipStream_t st);
 // syrk backward and gemm2 in the same form (n, respectively m, n and k, up to 32)
 template <typename T>
 bool symm_rows_takes(int n, int k);

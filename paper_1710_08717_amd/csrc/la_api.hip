@@ -453,6 +453,8 @@ static la_status tri_apply_v(bool solve, bool fwd, T alpha, int64_t batch, int n
     if (n <= 64 && m <= 16 && (!solve || n <= 16 || batch > 1024) && X.bs == nm && Xin.bs == nm && Xin.rs == X.rs && Xin.cs == X.cs && X.nb2 == 1 &&
         Xin.nb2 == 1 && Lam.nb2 == 1) {
         const bool rowmajor = (X.rs == m && X.cs == 1), colmajor = (X.rs == 1 && X.cs == n);
+        if ((rowmajor || colmajor) && n > 16 && n <= 32)  // 16 lanes per matrix, two rows per lane
+            return launch_tri_rows<T>(solve, fwd, alpha, batch, n, m, Lam, Xin.p, X.p, !rowmajor, st);
         if (rowmajor || colmajor)
             return launch_tri_tiny<T>(solve, fwd, alpha, batch, n, m, Lam, Xin.p, X.p, !rowmajor, st);
     }

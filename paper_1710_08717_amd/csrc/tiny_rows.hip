@@ -412,4 +412,181 @@ template la_status launch_gemm2_rows<float>(int, int, float, int64_t, int, int, 
 template la_status launch_gemm2_rows<double>(int, int, double, int64_t, int, int, int, const double *, const double *,
                                              double *, hipStream_t);
 
+
+// ---------------------------------------------------------------------------------
+// trsm / trmm for 16 < n <= N and at most 16 vectors (section 4.2 "trsm", "trmm"): lane i holds the rows
+// i, i + 16 of M (M = Lam or Lam^T, whichever the operator applies) and of the n x m operand, which
+// travels as its flat image (n x m or, for the right-side operators, m x n per item).
+//   solve: unit-diagonal form (D^-1 M) x = D^-1 b; in solve order b_r -= (m_rk / m_rr) b_k (r != k), one
+//          broadcast multiply-add per column, row slot and step; row k is final when it is broadcast.
+//   multiply: x_r = sum_k m_rk b_k.
+// Steps that only meet structural zeros of the triangle in a row slot are left out.
+// ---------------------------------------------------------------------------------
+constexpr int TRIR_MC = 16;  // vectors per matrix, at most
+
+template <typename T, int N, bool SOLVE>
+__global__ __launch_bounds__(WAVE) void k_tri_rows(View<const T> Lam, const T *Bin, T *Bout, int64_t batch, int n, int m,
+                                                   int fwd, int img_tr, T alpha)
+{
+    constexpr int G = ROWS_G, MPW = ROWS_MPW;
+    constexpr int IMG = MPW * N * TRIR_MC;
+    using S = Stage<T, N, MPW>;
+    __shared__ __align__(16) T sm[S::ELEMS];
+    __shared__ __align__(16) T img[IMG + IMG / 16 + 4];
+    const int lane = threadIdx.x;
+    const int q = lane / G, i = lane % G;
+    const int64_t b0 = (int64_t)blockIdx.x * MPW;
+    const int cnt = (int)((batch - b0) < MPW ? (batch - b0) : MPW);
+    const int nm = n * m;
+    const bool own1 = (N == 2 * G) || i + G < N;
+    const int i1 = own1 ? i + G : N - 1;
+    image_load<T, IMG, MPW>(img, Bin, b0, cnt, nm, lane);
+    const Mem<const T> Lm = mem_of(Lam);
+    stage_load<T, N, MPW>(sm, Lm, b0, batch, n);  // identity outside n x n
+    __syncthreads();
+
+    T m0[N], m1[N];
+    if (fwd) {  // M = Lam: entries k <= r
+        read_lrow<T, N>(sm + q * S::MS, i, Lm.tr, m0);
+        read_lrow<T, N>(sm + q * S::MS, i1, Lm.tr, m1);
+    } else {  // M = Lam^T: entries k >= r
+        read_lcol<T, N>(sm + q * S::MS, i, Lm.tr, m0);
+        read_lcol<T, N>(sm + q * S::MS, i1, Lm.tr, m1);
+    }
+    T d0 = T(1), d1 = T(1);
+#pragma unroll
+    for (int k = 0; k < N; ++k) {
+        if (k == i)
+            d0 = m0[k];
+        if (own1 && k == i + G)
+            d1 = m1[k];
+        if (fwd ? (k > i) : (k < i))
+            m0[k] = T(0);  // the other triangle is never used
+        if (!own1 || (fwd ? (k > i + G) : (k < i + G)))
+            m1[k] = T(0);
+    }
+    const bool live0 = (i < n) && (q < cnt), live1 = (i + G < n) && (q < cnt);
+    const int e0 = q * nm + (img_tr ? i : i * m), e1 = q * nm + (img_tr ? i + G : (i + G) * m), estep = img_tr ? n : 1;
+    T x0[TRIR_MC], x1[TRIR_MC];
+#pragma unroll
+    for (int c = 0; c < TRIR_MC; ++c) {
+        x0[c] = (live0 && c < m) ? img[img_idx(e0 + c * estep)] : T(0);
+        x1[c] = (live1 && c < m) ? img[img_idx(e1 + c * estep)] : T(0);
+    }
+
+    if constexpr (SOLVE) {
+        const T r0 = rcp_acc(d0), r1 = rcp_acc(d1);
+#pragma unroll
+        for (int k = 0; k < N; ++k) {
+            m0[k] = (k == i) ? T(0) : m0[k] * r0;
+            m1[k] = (k == i + G) ? T(0) : m1[k] * r1;
+        }
+#pragma unroll
+        for (int c = 0; c < TRIR_MC; ++c) {
+            x0[c] *= r0 * alpha;
+            x1[c] *= r1 * alpha;
+        }
+        dpp_settle<G>(x0);
+        dpp_settle<G>(x1);
+        static_for<0, TRIR_MC / 4>([&](auto CB) {
+            constexpr int c0 = 4 * decltype(CB)::value;
+            if (c0 < m) {
+                static_for<0, N>([&](auto Kk) {
+                    constexpr int kf = decltype(Kk)::value, kb = N - 1 - kf;  // forward: 0, 1, ...; backward: N-1, N-2, ...
+                    if (fwd) {
+                        constexpr int kl = kf % G;
+                        if constexpr (kf < G) {  // row kf of slot 0 reaches the later rows of both slots
+                            static_for<0, 4>([&](auto J) { fma_bcast<G, kl>(x1[c0 + decltype(J)::value], x0[c0 + decltype(J)::value], m1[kf], true); });
+                            static_for<0, 4>([&](auto J) { fma_bcast<G, kl>(x0[c0 + decltype(J)::value], x0[c0 + decltype(J)::value], m0[kf], true); });
+                        } else {
+                            static_for<0, 4>([&](auto J) { fma_bcast<G, kl>(x1[c0 + decltype(J)::value], x1[c0 + decltype(J)::value], m1[kf], true); });
+                        }
+                    } else {
+                        constexpr int kl = kb % G;
+                        if constexpr (kb >= G) {  // row kb of slot 1 reaches the earlier rows of both slots
+                            static_for<0, 4>([&](auto J) { fma_bcast<G, kl>(x0[c0 + decltype(J)::value], x1[c0 + decltype(J)::value], m0[kb], true); });
+                            static_for<0, 4>([&](auto J) { fma_bcast<G, kl>(x1[c0 + decltype(J)::value], x1[c0 + decltype(J)::value], m1[kb], true); });
+                        } else {
+                            static_for<0, 4>([&](auto J) { fma_bcast<G, kl>(x0[c0 + decltype(J)::value], x0[c0 + decltype(J)::value], m0[kb], true); });
+                        }
+                    }
+                });
+            }
+        });
+    } else {
+        dpp_settle<G>(x0);
+        dpp_settle<G>(x1);
+        static_for<0, TRIR_MC / 4>([&](auto CB) {
+            constexpr int c0 = 4 * decltype(CB)::value;
+            if (c0 < m) {
+                T y0[4] = {T(0), T(0), T(0), T(0)}, y1[4] = {T(0), T(0), T(0), T(0)};
+                static_for<0, N>([&](auto Kk) {
+                    constexpr int kk = decltype(Kk)::value;
+                    constexpr int kl = kk % G;
+                    // lower M (forward): the rows 0 .. 15 end at column 15; upper M: the rows 16 .. start at column 16
+                    if constexpr (kk < G) {
+                        static_for<0, 4>([&](auto J) { fma_bcast<G, kl>(y0[decltype(J)::value], x0[c0 + decltype(J)::value], m0[kk], false); });
+                        if (fwd)
+                            static_for<0, 4>([&](auto J) { fma_bcast<G, kl>(y1[decltype(J)::value], x0[c0 + decltype(J)::value], m1[kk], false); });
+                    } else {
+                        if (!fwd)
+                            static_for<0, 4>([&](auto J) { fma_bcast<G, kl>(y0[decltype(J)::value], x1[c0 + decltype(J)::value], m0[kk], false); });
+                        static_for<0, 4>([&](auto J) { fma_bcast<G, kl>(y1[decltype(J)::value], x1[c0 + decltype(J)::value], m1[kk], false); });
+                    }
+                });
+                // column c of the operand only feeds column c of the product: the block can be replaced now
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    x0[c0 + j] = alpha * y0[j];
+                    x1[c0 + j] = alpha * y1[j];
+                }
+            }
+        });
+    }
+
+    __syncthreads();
+#pragma unroll
+    for (int c = 0; c < TRIR_MC; ++c) {
+        if (live0 && c < m)
+            img[img_idx(e0 + c * estep)] = x0[c];
+        if (live1 && c < m)
+            img[img_idx(e1 + c * estep)] = x1[c];
+    }
+    __syncthreads();
+    image_store<T, IMG, MPW>(img, Bout, b0, cnt, nm, lane);
+}
+
+// Bin / Bout: items of n * m elements back to back; img_tr says an item is stored m x n (the right-side
+// operators) instead of n x m.
+template <typename T>
+la_status launch_tri_rows(bool solve, bool fwd, T alpha, int64_t batch, int n, int m, View<const T> Lam, const T *Bin, T *Bout,
+                          bool img_tr, hipStream_t st)
+{
+    if (batch <= 0 || n <= 0 || m <= 0)
+        return LA_OK;
+    if (n <= 16 || n > 32 || m > TRIR_MC || (batch + 3) / 4 > 0x7fffffffll)
+        return LA_ERR_UNSUPPORTED;
+    const dim3 grid((unsigned)((batch + ROWS_MPW - 1) / ROWS_MPW)), blk(WAVE);
+    const int f = fwd ? 1 : 0, itr = img_tr ? 1 : 0;
+#define LA_TRI_ROWS(NN, SV) LA_LAUNCH((k_tri_rows<T, NN, SV>), grid, blk, 0, st, Lam, Bin, Bout, batch, n, m, f, itr, alpha)
+    if (n <= 24) {
+        if (solve)
+            LA_TRI_ROWS(24, true);
+        else
+            LA_TRI_ROWS(24, false);
+    } else {
+        if (solve)
+            LA_TRI_ROWS(32, true);
+        else
+            LA_TRI_ROWS(32, false);
+    }
+#undef LA_TRI_ROWS
+    return launch_check("tri_rows");
+}
+
+template la_status launch_tri_rows<float>(bool, bool, float, int64_t, int, int, View<const float>, const float *, float *, bool,
+                                          hipStream_t);
+template la_status launch_tri_rows<double>(bool, bool, double, int64_t, int, int, View<const double>, const double *, double *,
+                                           bool, hipStream_t);
+
 }  // namespace la
