@@ -718,7 +718,7 @@ __global__ __launch_bounds__(LEAF16_THREADS) void k_gp_leaf16(View<const T> A, c
     extern __shared__ __align__(16) unsigned char leaf16_lds[];
     T *lds = reinterpret_cast<T *>(leaf16_lds);
     constexpr int W = LEAF16_WAVES;
-    constexpr int DT = C::DT, OT = C::OT, PS = C::PS;
+    constexpr int DT = C::DT, OT = C::OT;
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
