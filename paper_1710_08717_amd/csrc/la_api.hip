@@ -431,12 +431,15 @@ static la_status potrf_t(int lower, int64_t batch, int n, const void *A, void *L
 // trsm / trmm (section 4.2).  vectors: columns of A/B (left) or rows (right); X(e, v) = element e
 // of vector v, so that every case is "apply Lam, Lam^T or one of their inverses to vectors".
 //   trmm: one GEMM with the triangular operand masked.
+//   trsm / trmm, n <= 64 and at most 16 vectors, many items: lane groups (two rows per lane for 16 < n <= 32).
 //   trsm, n <= 128 and at most 48 vectors: one block-substitution kernel.
-//   trsm, n <= 64: product (in place) with the inverse of the single diagonal block.
-//   trsm, n <= 1024: explicit inverse of Lam (see inverse_build), then one masked GEMM.
-//   trsm, larger n: inverses of the 1024 x 1024 diagonal blocks, then block substitution with two
-//     GEMMs per block (the block's solution goes through a scratch panel because a product
-//     cannot overwrite its own operand across several tiles).
+//   trsm, 128 < n <= 512: one launch per call, one workgroup per item and slab of 16 vectors, the
+//     factor streamed from memory (launch_trsm_stream), unless many vectors meet few items.
+//   trsm, n <= 128 otherwise: product (in place) with the inverse of the single diagonal block.
+//   trsm, otherwise: explicit inverses of the diagonal blocks of 256 to 1024 rows (the more vectors,
+//     the larger; see inverse_build); n within one block: one masked GEMM with the whole inverse,
+//     else block substitution with two GEMMs per block (the block's solution goes through a scratch
+//     panel because a product cannot overwrite its own operand across several tiles).
 template <typename T>
 static la_status tri_apply_v(bool solve, bool fwd, T alpha, int64_t batch, int n, int m, View<const T> Lam,
                              View<const T> Xin, View<T> X, bool inplace, hipStream_t st)

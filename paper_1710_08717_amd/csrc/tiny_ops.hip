@@ -1,7 +1,8 @@
 // Operators on many small matrices in lane groups (G = 4 .. 64 lanes of a wavefront per matrix, as in
 // tiny.hip): trsm / trmm, syrk and the outer products of the trmm / trsm backward rules, gemm2, the syrk
 // backward rule and potri (section 4.2 of arXiv 1710.08717 and its appendix).  Operands that are not
-// square travel as flat memory images of whole items through LDS.
+// square travel as flat memory images of whole items through LDS.  (Their forms with two rows per lane
+// for 16 < n <= 32 are in tiny_rows.hip; potri's is here.)
 #include "tiny_stage.hpp"
 
 namespace la {
