@@ -2,8 +2,8 @@
 // i + 16 (row slot h = 0, 1) of every operand, so that all broadcasts are DPP row broadcasts fused into
 // the multiply-adds (as in the kernels of tiny.hip with two rows per lane); four matrices per
 // wavefront.  Row j = 16 jh + jl lives in slot jh of lane jl.  syrk and the outer products of the
-// trmm / trsm backward rules, the syrk backward rule, gemm2 (section 4.2 of arXiv 1710.08717 and its
-// appendix).  Operands that are not square travel as flat memory images through LDS; the long dimension
+// trmm / trsm backward rules, the syrk backward rule, gemm2, trsm / trmm (section 4.2 of arXiv 1710.08717
+// and its appendix).  Operands that are not square travel as flat memory images through LDS; the long dimension
 // is taken in passes of CH columns to bound the registers.
 #include "tiny_stage.hpp"
 
