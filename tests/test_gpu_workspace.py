@@ -150,3 +150,55 @@ def test_exact_workspace_suffices_for_every_flag_with_a_guard_band(la, orc, dtyp
         ref = orc.potrf_backward(np.ascontiguousarray(Fh), Gh.astype(np.float64), lower=lower)
         assert rel(Bg, ref) <= tol
         assert (buf[need:] == 0xA5).all()
+
+
+@pytest.mark.parametrize("batch,n,m,dtype", [(16, 32, 8, "f64"), (3, 300, 40, "f64"), (2, 700, 24, "f32")])
+def test_calls_with_a_workspace_can_be_captured_in_a_graph(la, batch, n, m, dtype):
+    """With a workspace an entry point allocates nothing and only enqueues kernels on the caller's stream, so a chain
+    of calls can be recorded into a HIP graph.  Every replay -- with eager work of the same library and
+    synchronisations between the replays -- must reproduce the eager results bit for bit."""
+    import torch
+
+    from paper_1710_08717_amd import binding
+
+    dt = torch.float64 if dtype == "f64" else torch.float32
+    gen = torch.Generator(device="cuda").manual_seed(5 + n)
+    X = torch.randn(batch, n, n, dtype=dt, device="cuda", generator=gen)
+    A = (X @ X.transpose(1, 2) / n + torch.eye(n, dtype=dt, device="cuda")).contiguous()
+    rhs = torch.randn(batch, n, m, dtype=dt, device="cuda", generator=gen)
+    G = torch.tril(torch.randn(batch, n, n, dtype=dt, device="cuda", generator=gen))
+    L, Xo, Y, Ab = torch.empty_like(A), torch.empty_like(rhs), torch.empty_like(rhs), torch.empty_like(A)
+    info = torch.zeros(batch, dtype=torch.int32, device="cuda")
+    need = max(la.workspace_bytes(o, A, batch, n, m) for o in (binding.OP_POTRF, binding.OP_POTRF_BACKWARD, binding.OP_TRSM,
+                                                               binding.OP_TRMM))
+    ws = torch.empty(max(need, 256), dtype=torch.uint8, device="cuda")
+
+    def chain():
+        la.potrf(A, out=L, info=info, workspace=ws)
+        la.trsm(L, rhs, out=Xo, workspace=ws)
+        la.trmm(L, Xo, out=Y, trans=True, workspace=ws)
+        la.potrf_backward(L, G, out=Ab, workspace=ws)
+
+    chain()  # eager: also sets the kernels' attributes once, outside the capture
+    torch.cuda.synchronize()
+    ref = [t.clone() for t in (L, Xo, Y, Ab)]
+    s = torch.cuda.Stream()
+    s.wait_stream(torch.cuda.current_stream())
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(s):
+        with torch.cuda.graph(g, stream=s):
+            chain()
+    torch.cuda.synchronize()
+    for rep in range(3):
+        for t in (L, Xo, Y, Ab):
+            t.fill_(float("nan"))
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        for got, want in zip((L, Xo, Y, Ab), ref):
+            assert torch.equal(got, want), rep
+        assert int(info.abs().sum()) == 0
+        # eager work of the library between the replays (other sizes, its own scratch use)
+        other = la.potrf(A[:, : n // 2, : n // 2].contiguous())
+        torch.cuda.synchronize()
+        assert torch.isfinite(other).all()
