@@ -85,7 +85,7 @@ def tri(seed, batch, n, lower, dtype):
     return T.astype(npdt(dtype))
 
 
-SIZES = [1, 2, 3, 4, 5, 7, 8, 9, 15, 16, 17, 31, 32, 33, 48, 64, 65, 80, 97, 100, 112, 113, 127, 128, 129, 192, 200, 256, 321, 384]
+SIZES = [1, 2, 3, 4, 5, 7, 8, 9, 10, 12, 13, 15, 16, 17, 20, 24, 25, 31, 32, 33, 36, 40, 41, 48, 64, 65, 80, 97, 100, 112, 113, 127, 128, 129, 192, 200, 256, 321, 384]
 
 
 # ----------------------------------------------------------------------------
@@ -127,7 +127,8 @@ def test_potrf_in_place_and_other_triangle_ignored(la, orc, dtype, n, lower):
 
 @pytest.mark.parametrize("dtype", ["f64", "f32"])
 @pytest.mark.parametrize("n,bad", [(1, 0), (3, 1), (4, 3), (6, 3), (8, 0), (8, 7), (16, 15), (32, 0), (32, 20), (24, 23), (48, 17), (48, 40), (40, 39),
-                                   (64, 40), (100, 0), (100, 70), (128, 127), (200, 130)])
+                                   (64, 40), (100, 0), (100, 70), (128, 127), (200, 130), (12, 11), (10, 3), (9, 0), (20, 17),
+                                   (36, 33)])
 def test_potrf_info_first_bad_pivot(la, orc, dtype, n, bad):
     import torch
 
