@@ -758,11 +758,14 @@ la_status launch_gemm(View<const T> A, View<const T> B, View<T> C, int64_t batch
             // rounds of tiles, so take the largest tile that still gives 1024 workgroups.
             e = wg128 >= 1024 ? 128 : ((wg64 >= 1024 || !k64 || o.min_tile64) ? 64 : 32);
         } else {
-            // Equal tiles: big tiles once they fill most of the chip, quarter tiles when 64 x 64
-            // tiles would leave most compute units idle.
+            // Equal tiles: big tiles once they fill most of the chip, quarter tiles while 64 x 64 tiles
+            // would fill the 512 workgroup slots less than twice -- with so few rounds the last one runs
+            // part empty (32 x 384 x 384 lower triangle, K = 128: 672 tiles of 64, 38 -> 30 us; potrf of
+            // 32 x 512 x 512 0.245 -> 0.231 ms, of 4 x 2048 x 2048 1.14 -> 1.10, 8192 x 8192 with 512
+            // vectors trsm 1.19 -> 1.12 ms).
             const int64_t t128 = o.maskC ? wg128 : (int64_t)((M + 127) / 128) * ((N + 127) / 128) * batch;
             const bool big = o.maskC ? (M >= 2048 && N >= 2048) : (M >= 128 && N >= 128);
-            e = (t128 >= 192 && big) ? 128 : ((wg64 <= 256 && k64 && !o.min_tile64) ? 32 : 64);
+            e = (t128 >= 192 && big) ? 128 : ((wg64 < 1024 && k64 && !o.min_tile64) ? 32 : 64);
         }
         if (e >= 64 && o.maskC == 1 && !o.triA && !o.triB && !o.halfDiag && !o.shells && !o.min_tile64 && M == N &&
             M % e == 0 && A.nb2 == 1 && B.nb2 == 1 && C.nb2 == 1) {
