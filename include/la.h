@@ -31,8 +31,9 @@
  *    calls; it is re-entrant, and calls on different streams may overlap as long as
  *    their workspaces differ.  Small problems (potrf with n <= 128, backward with
  *    n <= 128 in fp32 and <= 96 in fp64, trsm with n <= 128 and at most 48 right-hand
- *    sides, every operator with n <= 16, sumlogdiag, gp_glue, gp_criterion up to the same
- *    n as backward, kalman_filter) need no scratch memory.  The blocked paths for larger
+ *    sides and with n <= 512 and at most 512 of them, every operator with n <= 32 on operands of at
+ *    most 16 vectors / an inner dimension of at most 32, sumlogdiag, gp_glue, gp_criterion up to the
+ *    same n as backward, kalman_filter) need no scratch memory; la_workspace_bytes() is the authority.  The blocked paths for larger
  *    n do (explicit inverses of the factor or of its diagonal blocks, a working copy of
  *    the triangle being factored or one work panel, partial results of products split
  *    along a long inner dimension): la_workspace_bytes() says how many bytes a call
