@@ -529,6 +529,10 @@ struct GemmOpts {
     int ktotal = 0;
     int xcd_batch = 0;   // set by the launcher: batched launch, items dealt to the XCDs, tile-major inside
     int min_tile64 = 0;  // 1: no workgroup tiles smaller than 64 x 64 (a caller that updates C in place over <= 64 rows)
+    int symsum = 0;      // 1: C = alpha (A B + (A B)^T) on a square C, both triangles written, exactly symmetric.  The
+                         // tiles on and below the diagonal accumulate A B and then B^T A^T -- B^T must have A's strides and
+                         // A^T B's, so the second pass only swaps the two base pointers -- and store every entry with its
+                         // mirror image.  beta and maskC are not used.
 };
 template <typename T>
 la_status launch_gemm(View<const T> A, View<const T> B, View<T> C, int64_t batch, int M, int N, int K, T alpha,

@@ -182,6 +182,15 @@ template <typename T>
 __device__ __forceinline__ void store_c(T *Cp, int64_t rs, int64_t cs, int i, int j, int M, int N, T acc, T alpha,
                                         T beta, const GemmOpts &o)
 {
+    if (o.symsum) {  // the lower triangle's values go to both triangles
+        if (i < M && j <= i) {
+            const T upd = alpha * acc;
+            Cp[(int64_t)i * rs + (int64_t)j * cs] = upd;
+            if (j < i)
+                Cp[(int64_t)j * rs + (int64_t)i * cs] = upd;
+        }
+        return;
+    }
     if (i < M && j < N && !(o.maskC == 1 && i < j) && !(o.maskC == 2 && i > j)) {
         T upd = alpha * acc;
         if (o.halfDiag && i == j)
@@ -241,6 +250,12 @@ __global__ __launch_bounds__(256) void k_gemm(View<const T> A, View<const T> B, 
     const int b_sj = b_kfast ? (BK + 1) : 1, b_sk = b_kfast ? 1 : (BN + PAD);
     const int triB_o = o.triB == 1 ? 2 : (o.triB == 2 ? 1 : 0);  // in (j, k) order
 
+    for (int pass = 0; pass <= o.symsum; ++pass) {
+    if (pass == 1) {  // second half of A B + B^T A^T: same strides, the base pointers change places
+        const T *t = Ap;
+        Ap = Bp;
+        Bp = t;
+    }
     for (int k0 = kbeg; k0 < kend; k0 += BK) {
         stage_slab<T, BM, BK, PAD>(sA, Ap, A.rs, A.cs, i0, M, k0, kend, o.triA, a_kfast);
         stage_slab<T, BN, BK, PAD>(sB, Bp, B.cs, B.rs, j0, N, k0, kend, triB_o, b_kfast);
@@ -261,6 +276,7 @@ __global__ __launch_bounds__(256) void k_gemm(View<const T> A, View<const T> B, 
                     acc[x][y] = MF::run(af[x], bf[y], acc[x][y]);
         }
         __syncthreads();
+    }
     }
 
 #pragma unroll
@@ -365,7 +381,7 @@ __device__ __forceinline__ void slab_commit(T *s, RV &r, int o0, int k0, int tri
     }
 }
 
-template <typename T, int BM, int BN, int BK, int NBUF, bool AKF, bool BKF>
+template <typename T, int BM, int BN, int BK, int NBUF, bool AKF, bool BKF, bool SYM = false>
 __global__ __launch_bounds__(256, 2) void k_gemm_fast(View<const T> A, View<const T> B, View<T> C, int64_t batch, int M,
                                                    int N, int K, T alpha, T beta, GemmOpts o, int tiles_m, int tiles_n)
 {
@@ -415,8 +431,6 @@ __global__ __launch_bounds__(256, 2) void k_gemm_fast(View<const T> A, View<cons
     kbeg = (kbeg / BK) * BK;
     kend = ((kend + BK - 1) / BK) * BK;  // K is a multiple of BK, so this stays <= K
 
-    const T *Ap = A.item(b);
-    const T *Bp = B.item(b);
     T *Cp = C.item(b);
     const int triB_o = o.triB == 1 ? 2 : (o.triB == 2 ? 1 : 0);
 
@@ -439,6 +453,8 @@ __global__ __launch_bounds__(256, 2) void k_gemm_fast(View<const T> A, View<cons
     // One LDS buffer: slab s+1 is fetched into registers while slab s is multiplied, and written
     // once everybody is done reading (two barriers per slab).
     V ra[SA::NCH], rb[SB::NCH];
+    const T *Ap = A.item(b);
+    const T *Bp = B.item(b);
     auto multiply = [&](const T *a_s, const T *b_s) {
 #pragma unroll
         for (int kk = 0; kk < BK; kk += 4) {
@@ -456,6 +472,13 @@ __global__ __launch_bounds__(256, 2) void k_gemm_fast(View<const T> A, View<cons
                     acc[x][y] = MF::run(af[x], bf[y], acc[x][y]);
         }
     };
+    // SYM (GemmOpts::symsum): a second pass adds B^T A^T -- same strides, the base pointers change places
+    for (int pass = 0; pass < (SYM ? 2 : 1); ++pass) {
+    if (SYM && pass == 1) {
+        const T *t = Ap;
+        Ap = Bp;
+        Bp = t;
+    }
     if constexpr (NBUF == 2) {
         if (kbeg < kend) {
             slab_fetch<T, BM, BK, AKF>(ra, Ap, A.rs, A.cs, i0, M, kbeg);
@@ -498,6 +521,7 @@ __global__ __launch_bounds__(256, 2) void k_gemm_fast(View<const T> A, View<cons
             multiply(sA[0], sB[0]);
             __syncthreads();
         }
+    }
     }
 
 #pragma unroll
@@ -647,6 +671,8 @@ static inline int pick_order(const GemmOpts &o, int tiles_m, int tiles_n)
 {
     if (o.maskC == 0 && o.triA == 0 && o.triB != 0)
         return 4;  // work depends on the column only
+    if (o.symsum)
+        return 1;
     if (tiles_m != tiles_n)
         return 0;
     if (o.maskC == 1 && o.triA == 1 && o.triB == 1 && tiles_m >= 16)
@@ -671,6 +697,17 @@ static void launch_fast(bool akf, bool bkf, View<const T> A, View<const T> B, Vi
 #define LA_GO(AK, BKF_)                                                                                              \
     LA_LAUNCH((k_gemm_fast<T, BM, BN, BK, NBUF, AK, BKF_>), grid, block, 0, st, A, B, C, batch, M, N, K,    \
                        alpha, beta, o, tiles_m, tiles_n)
+    if constexpr (BM <= 64) {  // the symmetric sum exists for the small tiles only (launch_gemm picks them)
+        if (o.symsum) {         // and its operands have mirrored strides, so akf == bkf
+            if (akf)
+                LA_LAUNCH((k_gemm_fast<T, BM, BN, BK, NBUF, true, true, true>), grid, block, 0, st, A, B, C, batch, M, N,
+                          K, alpha, beta, o, tiles_m, tiles_n);
+            else
+                LA_LAUNCH((k_gemm_fast<T, BM, BN, BK, NBUF, false, false, true>), grid, block, 0, st, A, B, C, batch, M,
+                          N, K, alpha, beta, o, tiles_m, tiles_n);
+            return;
+        }
+    }
     if (akf && bkf)
         LA_GO(true, true);
     else if (akf && !bkf)
@@ -690,8 +727,16 @@ la_status launch_gemm(View<const T> A, View<const T> B, View<T> C, int64_t batch
 {
     if (batch <= 0 || M <= 0 || N <= 0)
         return LA_OK;
+    if (o.symsum) {
+        if (M != N || A.rs != B.cs || A.cs != B.rs || A.bs != B.bs || A.nb2 != 1 || B.nb2 != 1 || C.nb2 != 1)
+            return LA_ERR_UNSUPPORTED;
+        o.maskC = 0;
+        o.halfDiag = 0;
+        if (C.cs != 1 && C.rs == 1)  // the result is symmetric: its transpose is the same matrix
+            C = C.t();
+    }
     // a few vectors on either side: one pass over the big operand
-    if (!o.maskC && !o.halfDiag && !o.min_tile64 && K > 0) {
+    if (!o.maskC && !o.halfDiag && !o.min_tile64 && !o.symsum && K > 0) {
         if (N <= GEMV_N && o.triB == 0)
             return launch_gemv<T>(A, B, C, batch, M, N, K, alpha, beta, o.triA, st);
         if (M <= GEMV_N && o.triA == 0)  // C^T = B^T A^T
@@ -699,7 +744,7 @@ la_status launch_gemm(View<const T> A, View<const T> B, View<T> C, int64_t batch
     }
     // Keep the stores of C along its contiguous direction: if C is stored with i contiguous,
     // compute C^T = B^T A^T instead (a pure re-labelling of the views).
-    if (C.cs != 1 && C.rs == 1) {
+    if (C.cs != 1 && C.rs == 1 && !o.symsum) {
         GemmOpts t;
         t.triA = flip_tri(o.triB);
         t.triB = flip_tri(o.triA);
@@ -757,6 +802,8 @@ la_status launch_gemm(View<const T> A, View<const T> B, View<T> C, int64_t batch
             // list (heaviest first): the 512 workgroup slots only fill evenly if there are several
             // rounds of tiles, so take the largest tile that still gives 1024 workgroups.
             e = wg128 >= 1024 ? 128 : ((wg64 >= 1024 || !k64 || o.min_tile64) ? 64 : 32);
+            if (o.symsum && e == 128)
+                e = 64;
         } else {
             // Equal tiles: big tiles once they fill most of the chip, quarter tiles while 64 x 64 tiles
             // would fill the 512 workgroup slots less than twice -- with so few rounds the last one runs

@@ -244,8 +244,7 @@ static la_status potrf_rec(View<T> Wk, View<T> L, int32_t *info, int off, int64_
 // K ranges skip every structural zero (5 n^3 / 3 flops in all, inverse included):
 //   P = Phi(tril(Lam^T Lbar))      lower x lower, lower part kept, diagonal halved
 //   Z = P Li                       lower x lower = lower
-//   W = Li^T Z                     upper x lower = full
-//   Abar = 1/2 (W + W^T)
+//   Abar = 1/2 (W + W^T), W = Li^T Z (upper x lower = full): the lower tiles of Li^T Z + Z^T Li, mirrored
 template <typename T>
 static la_status backward_blocked(View<const T> Lam, View<const T> G, View<T> W, int64_t batch, int n, bool aliased,
                                   hipStream_t st);
@@ -298,12 +297,13 @@ static la_status backward_impl(View<const T> Lam, View<const T> G, View<T> W, in
     oz.maskC = 1;
     oz.reverse = 1;  // K range of tile (i, j) grows with i - j: bottom rows first
     LA_TRY(launch_gemm<T>(cv(W), cv(Li), X, batch, n, n, n, T(1), T(0), oz, st));
+    // Abar = 1/2 (Li^T Z + Z^T Li) in one launch: the tiles on and below the diagonal accumulate both
+    // products (K range from the tile's first row on) and write every entry with its mirror image
     GemmOpts ow;
     ow.triA = 2;
     ow.triB = 1;
-    ow.shells = 1;  // K range of tile (i, j) starts at max(i, j)
-    LA_TRY(launch_gemm<T>(cv(Li).t(), cv(X), W, batch, n, n, n, T(1), T(0), ow, st));
-    return launch_symmetrize<T>(W, batch, n, T(0.5), st);
+    ow.symsum = 1;
+    return launch_gemm<T>(cv(Li).t(), cv(X), W, batch, n, n, n, T(0.5), T(0), ow, st);
 }
 
 template <typename T>
