@@ -284,6 +284,80 @@ __device__ __forceinline__ void tri_decode(int t, int &ti, int &tj)
     tj = t;
 }
 
+// Whole 16-byte pieces can move between a block at p and the tiles: rows contiguous and 16-byte
+// aligned, no ragged last tile.
+template <typename T>
+__device__ __forceinline__ bool leaf_vec_ok(const T *p, int64_t rs, int64_t cs, int nb)
+{
+    constexpr int VW = Mfma<T>::VW;
+    return cs == 1 && (rs % VW) == 0 && (reinterpret_cast<uintptr_t>(p) & 15) == 0 && (nb % LT) == 0;
+}
+// tri_decode for t < LK (LK + 1) / 2 without a loop
+__device__ __forceinline__ void tri_decode8(int t, int &ti, int &tj)
+{
+    static_assert(LK == 8, "row starts below are those of eight tile rows");
+    ti = (t >= 1) + (t >= 3) + (t >= 6) + (t >= 10) + (t >= 15) + (t >= 21) + (t >= 28);
+    tj = t - ti * (ti + 1) / 2;
+}
+// Lane -> 16-byte piece of a 16 x 16 tile: row `row0 + pass * RPP`, elements col .. col + VW - 1.
+template <typename T>
+struct TileVec {
+    using V = typename Mfma<T>::vec_t;
+    static constexpr int VW = Mfma<T>::VW;
+    static constexpr int CPR = LT / VW;   // pieces per tile row
+    static constexpr int RPP = 64 / CPR;  // tile rows a wavefront covers at once
+    static constexpr int NP = LT / RPP;   // passes per tile
+};
+
+// leaf_load_lower for blocks that satisfy leaf_vec_ok: no predicates, half (a quarter of) the
+// memory instructions, the 64-bit address arithmetic once per tile.  The pieces of a diagonal tile
+// that reach above the diagonal are cleared element by element.
+template <typename T>
+__device__ __forceinline__ void leaf_load_lower_vec(const LeafLds<T> &m, const T *p, int64_t rs, int K, int wave,
+                                                    int lane, bool into_x)
+{
+    using TV = TileVec<T>;
+    using V = typename TV::V;
+    constexpr int W = LEAF16_WAVES;
+    constexpr int TPW = (LK * (LK + 1) / 2 + W - 1) / W;
+    const int ntl = K * (K + 1) / 2;
+    const int row0 = lane / TV::CPR, col = (lane % TV::CPR) * TV::VW;
+    V val[TPW][TV::NP];
+#pragma unroll
+    for (int q = 0; q < TPW; ++q) {
+        const int t = wave + q * W;
+        if (t < ntl) {
+            int ti, tj;
+            tri_decode8(t, ti, tj);
+            const T *tp = p + (int64_t)(ti * LT + row0) * rs + (tj * LT + col);
+#pragma unroll
+            for (int ps = 0; ps < TV::NP; ++ps)
+                val[q][ps] = *reinterpret_cast<const V *>(tp + (int64_t)(ps * TV::RPP) * rs);
+        }
+    }
+#pragma unroll
+    for (int q = 0; q < TPW; ++q) {
+        const int t = wave + q * W;
+        if (t < ntl) {
+            int ti, tj;
+            tri_decode8(t, ti, tj);
+            const TileRef<T> tr = into_x ? m.x(ti, tj) : m.a(ti, tj);
+#pragma unroll
+            for (int ps = 0; ps < TV::NP; ++ps) {
+                const int row = row0 + ps * TV::RPP;
+                V v = val[q][ps];
+                if (ti == tj) {
+                    T *e = reinterpret_cast<T *>(&v);
+#pragma unroll
+                    for (int u = 0; u < TV::VW; ++u)
+                        e[u] = (col + u <= row) ? e[u] : T(0);
+                }
+                *reinterpret_cast<V *>(tr.p + tr.at(row, col)) = v;
+            }
+        }
+    }
+}
+
 // Lower triangle of an nb x nb block at p (element strides rs, cs) into the tiles of A (or of the
 // inverse's area with into_x); outside nb x nb the tiles get pad_diag on the diagonal and zero
 // elsewhere.  Per tile a lane moves four elements, 16 lanes along the contiguous direction of the
@@ -292,6 +366,10 @@ template <typename T>
 __device__ __forceinline__ void leaf_load_lower(const LeafLds<T> &m, const T *p, int64_t rs, int64_t cs, int nb,
                                                 int wave, int lane, bool into_x = false, T pad_diag = T(1))
 {
+    if (leaf_vec_ok<T>(p, rs, cs, nb)) {
+        leaf_load_lower_vec<T>(m, p, rs, nb / LT, wave, lane, into_x);
+        return;
+    }
     constexpr int W = LEAF16_WAVES;
     constexpr int TPW = (LK * (LK + 1) / 2 + W - 1) / W;  // lower tiles per wavefront, at most
     const int K = (nb + LT - 1) / LT;
@@ -336,10 +414,61 @@ __device__ __forceinline__ void leaf_load_lower(const LeafLds<T> &m, const T *p,
 
 // The lower tiles of A / L (inverse == false) or of the inverse back to an nb x nb block at p;
 // zero_upper also writes zeros to the tiles above the diagonal.
+// leaf_store_lower for blocks that satisfy leaf_vec_ok
+template <typename T>
+__device__ __forceinline__ void leaf_store_lower_vec(const LeafLds<T> &m, bool inverse, T *p, int64_t rs, int K,
+                                                     bool zero_upper, int wave, int lane)
+{
+    using TV = TileVec<T>;
+    using V = typename TV::V;
+    constexpr int W = LEAF16_WAVES;
+    constexpr int TPW = (LK * (LK + 1) / 2 + W - 1) / W;
+    const int ntl = K * (K + 1) / 2;
+    const int row0 = lane / TV::CPR, col = (lane % TV::CPR) * TV::VW;
+#pragma unroll
+    for (int q = 0; q < TPW; ++q) {
+        const int t = wave + q * W;
+        if (t < ntl) {
+            int ti, tj;
+            tri_decode8(t, ti, tj);
+            const TileRef<T> tr = inverse ? m.x(ti, tj) : m.a(ti, tj);
+            T *tp = p + (int64_t)(ti * LT + row0) * rs + (tj * LT + col);
+            V v0 = *reinterpret_cast<const V *>(tr.p + tr.at(row0, col));
+            if constexpr (TV::NP == 2) {
+                V v1 = *reinterpret_cast<const V *>(tr.p + tr.at(row0 + TV::RPP, col));
+                *reinterpret_cast<V *>(tp) = v0;
+                *reinterpret_cast<V *>(tp + (int64_t)TV::RPP * rs) = v1;
+            } else {
+                static_assert(TV::NP == 1 || TV::NP == 2, "one or two passes per tile");
+                *reinterpret_cast<V *>(tp) = v0;
+            }
+        }
+    }
+    if (zero_upper) {
+        V z;
+        T *e = reinterpret_cast<T *>(&z);
+#pragma unroll
+        for (int u = 0; u < TV::VW; ++u)
+            e[u] = T(0);
+        for (int t = wave; t < ntl - K; t += W) {
+            int tj, ti;
+            tri_decode8(t, tj, ti);  // strictly lower (tj + 1, ti), mirrored
+            T *tp = p + (int64_t)(ti * LT + row0) * rs + ((tj + 1) * LT + col);
+#pragma unroll
+            for (int ps = 0; ps < TV::NP; ++ps)
+                *reinterpret_cast<V *>(tp + (int64_t)(ps * TV::RPP) * rs) = z;
+        }
+    }
+}
+
 template <typename T>
 __device__ __forceinline__ void leaf_store_lower(const LeafLds<T> &m, bool inverse, T *p, int64_t rs, int64_t cs,
                                                  int nb, bool zero_upper, int wave, int lane)
 {
+    if (leaf_vec_ok<T>(p, rs, cs, nb)) {
+        leaf_store_lower_vec<T>(m, inverse, p, rs, nb / LT, zero_upper, wave, lane);
+        return;
+    }
     constexpr int W = LEAF16_WAVES;
     const int K = (nb + LT - 1) / LT;
     const int ntl = K * (K + 1) / 2;
