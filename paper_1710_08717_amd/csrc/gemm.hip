@@ -178,19 +178,22 @@ __device__ __forceinline__ void k_range(const GemmOpts &o, int i0, int j0, int B
         kend = min(kend, j0 + BN);
 }
 
+// GemmOpts::symsum: the lower triangle's values go to both triangles
+template <typename T>
+__device__ __forceinline__ void store_c_sym(T *Cp, int64_t rs, int64_t cs, int i, int j, int M, T acc, T alpha)
+{
+    if (i < M && j <= i) {
+        const T upd = alpha * acc;
+        Cp[(int64_t)i * rs + (int64_t)j * cs] = upd;
+        if (j < i)
+            Cp[(int64_t)j * rs + (int64_t)i * cs] = upd;
+    }
+}
+
 template <typename T>
 __device__ __forceinline__ void store_c(T *Cp, int64_t rs, int64_t cs, int i, int j, int M, int N, T acc, T alpha,
                                         T beta, const GemmOpts &o)
 {
-    if (o.symsum) {  // the lower triangle's values go to both triangles
-        if (i < M && j <= i) {
-            const T upd = alpha * acc;
-            Cp[(int64_t)i * rs + (int64_t)j * cs] = upd;
-            if (j < i)
-                Cp[(int64_t)j * rs + (int64_t)i * cs] = upd;
-        }
-        return;
-    }
     if (i < M && j < N && !(o.maskC == 1 && i < j) && !(o.maskC == 2 && i > j)) {
         T upd = alpha * acc;
         if (o.halfDiag && i == j)
@@ -284,9 +287,13 @@ __global__ __launch_bounds__(256) void k_gemm(View<const T> A, View<const T> B, 
 #pragma unroll
         for (int y = 0; y < TN; ++y)
 #pragma unroll
-            for (int v = 0; v < 4; ++v)
-                store_c<T>(Cp, C.rs, C.cs, i0 + wm + x * 16 + MF::row(lane, v), j0 + wn + y * 16 + l16, M, N,
-                           acc[x][y][v], alpha, beta, o);
+            for (int v = 0; v < 4; ++v) {
+                const int i = i0 + wm + x * 16 + MF::row(lane, v), j = j0 + wn + y * 16 + l16;
+                if (o.symsum)
+                    store_c_sym<T>(Cp, C.rs, C.cs, i, j, M, acc[x][y][v], alpha);
+                else
+                    store_c<T>(Cp, C.rs, C.cs, i, j, M, N, acc[x][y][v], alpha, beta, o);
+            }
 }
 
 // ---------------------------------------------------------------------------------------
@@ -431,6 +438,8 @@ __global__ __launch_bounds__(256, 2) void k_gemm_fast(View<const T> A, View<cons
     kbeg = (kbeg / BK) * BK;
     kend = ((kend + BK - 1) / BK) * BK;  // K is a multiple of BK, so this stays <= K
 
+    const T *Ap = A.item(b);
+    const T *Bp = B.item(b);
     T *Cp = C.item(b);
     const int triB_o = o.triB == 1 ? 2 : (o.triB == 2 ? 1 : 0);
 
@@ -453,8 +462,6 @@ __global__ __launch_bounds__(256, 2) void k_gemm_fast(View<const T> A, View<cons
     // One LDS buffer: slab s+1 is fetched into registers while slab s is multiplied, and written
     // once everybody is done reading (two barriers per slab).
     V ra[SA::NCH], rb[SB::NCH];
-    const T *Ap = A.item(b);
-    const T *Bp = B.item(b);
     auto multiply = [&](const T *a_s, const T *b_s) {
 #pragma unroll
         for (int kk = 0; kk < BK; kk += 4) {
@@ -529,9 +536,13 @@ __global__ __launch_bounds__(256, 2) void k_gemm_fast(View<const T> A, View<cons
 #pragma unroll
         for (int y = 0; y < TN; ++y)
 #pragma unroll
-            for (int v = 0; v < 4; ++v)
-                store_c<T>(Cp, C.rs, C.cs, i0 + wm + x * 16 + MF::row(lane, v), j0 + wn + y * 16 + l16, M, N,
-                           acc[x][y][v], alpha, beta, o);
+            for (int v = 0; v < 4; ++v) {
+                const int i = i0 + wm + x * 16 + MF::row(lane, v), j = j0 + wn + y * 16 + l16;
+                if constexpr (SYM)
+                    store_c_sym<T>(Cp, C.rs, C.cs, i, j, M, acc[x][y][v], alpha);
+                else
+                    store_c<T>(Cp, C.rs, C.cs, i, j, M, N, acc[x][y][v], alpha, beta, o);
+            }
 }
 
 // ---------------------------------------------------------------------------------------
