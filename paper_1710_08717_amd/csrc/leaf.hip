@@ -273,15 +273,12 @@ __device__ __forceinline__ void leaf_update_x(const LeafLds<T> &m, int i, int j,
     acc_store<T>(m.x(i, j), lane, acc);
 }
 
-// tile (ti, tj) number t of the lower triangle counted row by row
+// tile (ti, tj) number t < LK (LK + 1) / 2 of the lower triangle counted row by row
 __device__ __forceinline__ void tri_decode(int t, int &ti, int &tj)
 {
-    ti = 0;
-    while (t > ti) {
-        t -= ti + 1;
-        ++ti;
-    }
-    tj = t;
+    static_assert(LK == 8, "the row starts below are those of eight tile rows");
+    ti = (t >= 1) + (t >= 3) + (t >= 6) + (t >= 10) + (t >= 15) + (t >= 21) + (t >= 28);
+    tj = t - ti * (ti + 1) / 2;
 }
 
 // Whole 16-byte pieces can move between a block at p and the tiles: rows contiguous and 16-byte
@@ -291,13 +288,6 @@ __device__ __forceinline__ bool leaf_vec_ok(const T *p, int64_t rs, int64_t cs, 
 {
     constexpr int VW = Mfma<T>::VW;
     return cs == 1 && (rs % VW) == 0 && (reinterpret_cast<uintptr_t>(p) & 15) == 0 && (nb % LT) == 0;
-}
-// tri_decode for t < LK (LK + 1) / 2 without a loop
-__device__ __forceinline__ void tri_decode8(int t, int &ti, int &tj)
-{
-    static_assert(LK == 8, "row starts below are those of eight tile rows");
-    ti = (t >= 1) + (t >= 3) + (t >= 6) + (t >= 10) + (t >= 15) + (t >= 21) + (t >= 28);
-    tj = t - ti * (ti + 1) / 2;
 }
 // Lane -> 16-byte piece of a 16 x 16 tile: row `row0 + pass * RPP`, elements col .. col + VW - 1.
 template <typename T>
@@ -328,7 +318,7 @@ __device__ __forceinline__ void leaf_load_lower_vec(const LeafLds<T> &m, const T
         const int t = wave + q * W;
         if (t < ntl) {
             int ti, tj;
-            tri_decode8(t, ti, tj);
+            tri_decode(t, ti, tj);
             const T *tp = p + (int64_t)(ti * LT + row0) * rs + (tj * LT + col);
 #pragma unroll
             for (int ps = 0; ps < TV::NP; ++ps)
@@ -340,7 +330,7 @@ __device__ __forceinline__ void leaf_load_lower_vec(const LeafLds<T> &m, const T
         const int t = wave + q * W;
         if (t < ntl) {
             int ti, tj;
-            tri_decode8(t, ti, tj);
+            tri_decode(t, ti, tj);
             const TileRef<T> tr = into_x ? m.x(ti, tj) : m.a(ti, tj);
 #pragma unroll
             for (int ps = 0; ps < TV::NP; ++ps) {
@@ -430,7 +420,7 @@ __device__ __forceinline__ void leaf_store_lower_vec(const LeafLds<T> &m, bool i
         const int t = wave + q * W;
         if (t < ntl) {
             int ti, tj;
-            tri_decode8(t, ti, tj);
+            tri_decode(t, ti, tj);
             const TileRef<T> tr = inverse ? m.x(ti, tj) : m.a(ti, tj);
             T *tp = p + (int64_t)(ti * LT + row0) * rs + (tj * LT + col);
             V v0 = *reinterpret_cast<const V *>(tr.p + tr.at(row0, col));
@@ -452,7 +442,7 @@ __device__ __forceinline__ void leaf_store_lower_vec(const LeafLds<T> &m, bool i
             e[u] = T(0);
         for (int t = wave; t < ntl - K; t += W) {
             int tj, ti;
-            tri_decode8(t, tj, ti);  // strictly lower (tj + 1, ti), mirrored
+            tri_decode(t, tj, ti);  // strictly lower (tj + 1, ti), mirrored
             T *tp = p + (int64_t)(ti * LT + row0) * rs + ((tj + 1) * LT + col);
 #pragma unroll
             for (int ps = 0; ps < TV::NP; ++ps)
