@@ -20,6 +20,28 @@ __global__ __launch_bounds__(256) void k_copy(View<const T> src, View<T> dst, in
     const bool colfast = (dst.cs == 1) || (dst.rs != 1);
     const T *sp = src.p + b * src.bs;
     T *dp = dst.p + b * dst.bs;
+    const bool src_colfast = (src.cs == 1) || (src.rs != 1);
+    if (src_colfast != colfast && (src.cs == 1 || src.rs == 1)) {
+        // A transposing copy: the tile is read along the source's contiguous direction, turned in LDS
+        // and written along the destination's (an element-wise copy would read with a stride).
+        __shared__ T turn[ET][ET + 1];
+        for (int t = threadIdx.x; t < ET * ET; t += 256) {
+            const int u = t / ET, w = t % ET;  // w runs along the source's contiguous direction
+            const int r = r0 + (src_colfast ? u : w), c = c0 + (src_colfast ? w : u);
+            T v = T(0);
+            if (r < rows && c < cols && !(keep == 1 && r < c))
+                v = alpha * sp[(int64_t)r * src.rs + (int64_t)c * src.cs];
+            turn[u][w] = v;
+        }
+        __syncthreads();
+        for (int t = threadIdx.x; t < ET * ET; t += 256) {
+            const int u = t / ET, w = t % ET;  // w runs along the destination's contiguous direction
+            const int r = r0 + (colfast ? u : w), c = c0 + (colfast ? w : u);
+            if (r < rows && c < cols)
+                dp[(int64_t)r * dst.rs + (int64_t)c * dst.cs] = turn[w][u];
+        }
+        return;
+    }
     for (int t = threadIdx.x; t < ET * ET; t += 256) {
         const int u = t / ET, w = t % ET;
         const int r = r0 + (colfast ? u : w), c = c0 + (colfast ? w : u);

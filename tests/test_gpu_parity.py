@@ -224,7 +224,7 @@ def test_backward_parity_large_batch_register_kernel(la, orc, dtype, n, lower):
 
 
 @pytest.mark.parametrize("dtype", ["f64", "f32"])
-@pytest.mark.parametrize("n", [7, 16, 32, 40, 130])
+@pytest.mark.parametrize("n", [7, 16, 32, 40, 130, 256])
 @pytest.mark.parametrize("lower", [True, False])
 def test_backward_aliasing_and_junk_triangles(la, orc, dtype, n, lower):
     batch = 5
