@@ -540,7 +540,8 @@ la_status launch_gemm(View<const T> A, View<const T> B, View<T> C, int64_t batch
 
 
 // Element-wise helpers.
-// dst(i,j) = alpha * src(i,j) on rows x cols; keep: 0 all, 1 only i >= j (rest written as 0).
+// dst(i,j) = alpha * src(i,j) on rows x cols; keep: 0 all, 1 only i >= j (rest written as 0), 2 only i >= j
+// (rest not written).
 template <typename T>
 la_status launch_copy(View<const T> src, View<T> dst, int64_t batch, int rows, int cols, T alpha, int keep,
                       hipStream_t st);

@@ -29,7 +29,7 @@ __global__ __launch_bounds__(256) void k_copy(View<const T> src, View<T> dst, in
             const int u = t / ET, w = t % ET;  // w runs along the source's contiguous direction
             const int r = r0 + (src_colfast ? u : w), c = c0 + (src_colfast ? w : u);
             T v = T(0);
-            if (r < rows && c < cols && !(keep == 1 && r < c))
+            if (r < rows && c < cols && !(keep != 0 && r < c))
                 v = alpha * sp[(int64_t)r * src.rs + (int64_t)c * src.cs];
             turn[u][w] = v;
         }
@@ -37,7 +37,7 @@ __global__ __launch_bounds__(256) void k_copy(View<const T> src, View<T> dst, in
         for (int t = threadIdx.x; t < ET * ET; t += 256) {
             const int u = t / ET, w = t % ET;  // w runs along the destination's contiguous direction
             const int r = r0 + (colfast ? u : w), c = c0 + (colfast ? w : u);
-            if (r < rows && c < cols)
+            if (r < rows && c < cols && !(keep == 2 && r < c))
                 dp[(int64_t)r * dst.rs + (int64_t)c * dst.cs] = turn[w][u];
         }
         return;
@@ -45,7 +45,7 @@ __global__ __launch_bounds__(256) void k_copy(View<const T> src, View<T> dst, in
     for (int t = threadIdx.x; t < ET * ET; t += 256) {
         const int u = t / ET, w = t % ET;
         const int r = r0 + (colfast ? u : w), c = c0 + (colfast ? w : u);
-        if (r < rows && c < cols) {
+        if (r < rows && c < cols && !(keep == 2 && r < c)) {
             T v = T(0);
             if (!(keep == 1 && r < c))
                 v = alpha * sp[(int64_t)r * src.rs + (int64_t)c * src.cs];

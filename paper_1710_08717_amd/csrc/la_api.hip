@@ -356,8 +356,9 @@ template <typename T>
 static la_status backward_blocked(View<const T> Lam, View<const T> G, View<T> W, int64_t batch, int n, bool aliased,
                                   hipStream_t st)
 {
-    if (!aliased)  // lower triangle of Lbar into the output, which is then updated in place
-        LA_TRY(launch_copy<T>(G, W, batch, n, n, T(1), 1, st));
+    if (!aliased)  // lower triangle of Lbar into the output, which is then updated in place; what lies above the
+                   // diagonal is never read and is all written by the sweep (base blocks and mirror copies)
+        LA_TRY(launch_copy<T>(G, W, batch, n, n, T(1), 2, st));
     return backward_rec<T>(Lam, W, batch, n, st);
 }
 

@@ -402,7 +402,8 @@ def test_potrf_backward_blocked_sweep(la, orc, dtype, lower, batch, n):
     F, G = np.ascontiguousarray(F).astype(npdt(dtype)), np.ascontiguousarray(G).astype(npdt(dtype))
     ref = orc.potrf_backward(F, G, lower=lower)
     f, g = dev(F), dev(G)
-    out = host(la.potrf_backward(f, g, lower=lower))
+    o = dev(np.full(G.shape, np.nan, dtype=npdt(dtype)))  # every entry of the output has to be written
+    out = host(la.potrf_backward(f, g, lower=lower, out=o))
     assert np.array_equal(host(g), G)  # the input is left alone
     assert np.array_equal(out, out.transpose(0, 2, 1))
     assert relerr(out, ref) <= TOL[dtype]
