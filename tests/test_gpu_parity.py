@@ -186,6 +186,38 @@ def test_argument_errors(la):
         la.potrf(A.cpu())
 
 
+@pytest.mark.parametrize("dtype", ["f64", "f32"])
+@pytest.mark.parametrize("n", [96, 128, 256])
+def test_potrf_and_backward_on_pointers_off_the_16_byte_grid(la, orc, dtype, n):
+    """Operands that start one element into their allocation: the block kernels and the products have
+    to leave their 16-byte paths."""
+    import torch
+
+    batch = 3
+    A = spd(n + 11, batch, n, dtype)
+    rng = np.random.default_rng(n)
+    G = np.tril(rng.standard_normal((batch, n, n))).astype(npdt(dtype))
+
+    def shifted(a):
+        buf = torch.empty(a.size + 1, dtype=torch.from_numpy(a).dtype, device="cuda")
+        v = buf[1:].view(a.shape)
+        v.copy_(torch.from_numpy(a))
+        assert v.data_ptr() % 16 != 0
+        return v
+
+    a, g = shifted(A), shifted(G)
+    l = shifted(np.zeros_like(A))
+    la.potrf(a, out=l)
+    ref = orc.potrf(A)
+    assert relerr(host(l), ref) <= TOL[dtype]
+    Lf = ref.astype(npdt(dtype))
+    out = shifted(np.zeros_like(A))
+    la.potrf_backward(shifted(Lf), g, out=out)
+    o = host(out)
+    assert np.array_equal(o, o.transpose(0, 2, 1))
+    assert relerr(o, orc.potrf_backward(Lf, G)) <= TOL[dtype]
+
+
 # ----------------------------------------------------------------------------
 # potrf backward
 # ----------------------------------------------------------------------------
