@@ -302,14 +302,13 @@ struct TileVec {
 // leaf_load_lower for blocks that satisfy leaf_vec_ok: no predicates, half (a quarter of) the
 // memory instructions, the 64-bit address arithmetic once per tile.  The pieces of a diagonal tile
 // that reach above the diagonal are cleared element by element.
-template <typename T>
+template <typename T, int W, int MAXK>
 __device__ __forceinline__ void leaf_load_lower_vec(const LeafLds<T> &m, const T *p, int64_t rs, int K, int wave,
                                                     int lane, bool into_x)
 {
     using TV = TileVec<T>;
     using V = typename TV::V;
-    constexpr int W = LEAF16_WAVES;
-    constexpr int TPW = (LK * (LK + 1) / 2 + W - 1) / W;
+    constexpr int TPW = (MAXK * (MAXK + 1) / 2 + W - 1) / W;
     const int ntl = K * (K + 1) / 2;
     const int row0 = lane / TV::CPR, col = (lane % TV::CPR) * TV::VW;
     V val[TPW][TV::NP];
@@ -352,16 +351,16 @@ __device__ __forceinline__ void leaf_load_lower_vec(const LeafLds<T> &m, const T
 // inverse's area with into_x); outside nb x nb the tiles get pad_diag on the diagonal and zero
 // elsewhere.  Per tile a lane moves four elements, 16 lanes along the contiguous direction of the
 // operand; all loads of a wavefront are in flight together.
-template <typename T>
+// W wavefronts share the work; the block has at most MAXK tile rows.
+template <typename T, int W = LEAF16_WAVES, int MAXK = LK>
 __device__ __forceinline__ void leaf_load_lower(const LeafLds<T> &m, const T *p, int64_t rs, int64_t cs, int nb,
                                                 int wave, int lane, bool into_x = false, T pad_diag = T(1))
 {
     if (leaf_vec_ok<T>(p, rs, cs, nb)) {
-        leaf_load_lower_vec<T>(m, p, rs, nb / LT, wave, lane, into_x);
+        leaf_load_lower_vec<T, W, MAXK>(m, p, rs, nb / LT, wave, lane, into_x);
         return;
     }
-    constexpr int W = LEAF16_WAVES;
-    constexpr int TPW = (LK * (LK + 1) / 2 + W - 1) / W;  // lower tiles per wavefront, at most
+    constexpr int TPW = (MAXK * (MAXK + 1) / 2 + W - 1) / W;  // lower tiles per wavefront, at most
     const int K = (nb + LT - 1) / LT;
     const int ntl = K * (K + 1) / 2;
     const bool colfast = (cs == 1) || (rs != 1);
@@ -674,15 +673,17 @@ __host__ __device__ constexpr int backward16_area(int K)  // elements of one til
     return K * Leaf16<T>::DT + K * (K - 1) / 2 * Leaf16<T>::OT;
 }
 
-template <typename T>
-__global__ __launch_bounds__(LEAF16_THREADS) void k_backward_leaf16(View<const T> Lam, View<const T> G, View<T> Abar,
-                                                                    int64_t batch, int n)
+// NW wavefronts per matrix: 16, or 4 for at most MAXK = 4 tile rows when there are many matrices (ten tiles
+// keep four wavefronts busy, and seven or eight such workgroups fit a compute unit instead of two).
+template <typename T, int NW, int MAXK>
+__global__ __launch_bounds__(NW * 64) void k_backward_leaf16(View<const T> Lam, View<const T> G, View<T> Abar,
+                                                             int64_t batch, int n)
 {
     using C = Leaf16<T>;
     using MF = Mfma<T>;
     extern __shared__ __align__(16) unsigned char leaf16_lds[];
     T *lds = reinterpret_cast<T *>(leaf16_lds);
-    constexpr int W = LEAF16_WAVES;
+    constexpr int W = NW;
     constexpr int PS = C::PS, DT = C::DT, OT = C::OT;
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -696,8 +697,8 @@ __global__ __launch_bounds__(LEAF16_THREADS) void k_backward_leaf16(View<const T
     T *pD = lds + 2 * area, *pO = pD + K * DT;
     auto ptile = [&](int i, int j) { return i == j ? TileRef<T>{pD + i * DT, true} : TileRef<T>{pO + tri_off(i, j) * OT, false}; };
 
-    leaf_load_lower<T>(m, Lam.p + b * Lam.bs, Lam.rs, Lam.cs, n, wave, lane, false, T(1));
-    leaf_load_lower<T>(m, G.p + b * G.bs, G.rs, G.cs, n, wave, lane, true, T(0));
+    leaf_load_lower<T, NW, MAXK>(m, Lam.p + b * Lam.bs, Lam.rs, Lam.cs, n, wave, lane, false, T(1));
+    leaf_load_lower<T, NW, MAXK>(m, G.p + b * G.bs, G.rs, G.cs, n, wave, lane, true, T(0));
     __syncthreads();
 
     // ---- P_ij = sum_{k >= i} L_ki^T Lbar_kj, i >= j; Phi on the diagonal tiles ------------------
@@ -1239,12 +1240,19 @@ la_status launch_backward_leaf16(View<const T> Lam, View<const T> G, View<T> Aba
     int dev = 0;
     LA_HIP(hipGetDevice(&dev));
     if (dev >= 0 && dev < 64 && !configured[dev]) {
-        LA_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&k_backward_leaf16<T>),
+        LA_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&k_backward_leaf16<T, LEAF16_WAVES, LK>),
+                                   hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024));
+        LA_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&k_backward_leaf16<T, 4, 4>),
                                    hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024));
         configured[dev] = true;
     }
-    LA_LAUNCH((k_backward_leaf16<T>), dim3((unsigned)batch), dim3(LEAF16_THREADS), lds_bytes, st, Lam, G, Abar,
-                       batch, n);
+    // more matrices than two rounds of the 512 places that 16-wavefront workgroups have on the chip, and small
+    // enough for four workgroups per compute unit (fp64 with four tile rows needs 65 KB: no gain there)
+    if (K <= 4 && batch > 1024 && lds_bytes <= 40 * 1024)
+        LA_LAUNCH((k_backward_leaf16<T, 4, 4>), dim3((unsigned)batch), dim3(4 * 64), lds_bytes, st, Lam, G, Abar, batch, n);
+    else
+        LA_LAUNCH((k_backward_leaf16<T, LEAF16_WAVES, LK>), dim3((unsigned)batch), dim3(LEAF16_THREADS), lds_bytes, st, Lam,
+                  G, Abar, batch, n);
     return launch_check("backward_leaf16");
 }
 

@@ -256,6 +256,23 @@ def test_backward_parity_large_batch_register_kernel(la, orc, dtype, n, lower):
 
 
 @pytest.mark.parametrize("dtype", ["f64", "f32"])
+@pytest.mark.parametrize("n", [33, 40, 48, 57, 64])
+@pytest.mark.parametrize("lower", [True, False])
+def test_backward_parity_many_matrices_of_up_to_four_tile_rows(la, orc, dtype, n, lower):
+    """Above 1024 matrices the one-workgroup kernel runs with four wavefronts per matrix for n <= 64."""
+    batch = 1030
+    A = spd(n * 3 + lower, batch, n, dtype)
+    Lf = orc.potrf(A, lower=lower).astype(npdt(dtype))
+    rng = np.random.default_rng(n + 9)
+    G = rng.standard_normal((batch, n, n))
+    G = (np.tril(G) if lower else np.triu(G)).astype(npdt(dtype))
+    ref = orc.potrf_backward(Lf, G, lower=lower)
+    out = host(la.potrf_backward(dev(Lf), dev(G), lower=lower))
+    assert np.array_equal(out, out.transpose(0, 2, 1))
+    assert relerr(out, ref) <= TOL[dtype]
+
+
+@pytest.mark.parametrize("dtype", ["f64", "f32"])
 @pytest.mark.parametrize("n", [7, 16, 32, 40, 130, 256])
 @pytest.mark.parametrize("lower", [True, False])
 def test_backward_aliasing_and_junk_triangles(la, orc, dtype, n, lower):
