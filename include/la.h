@@ -29,7 +29,7 @@
  *    LA_ERR_WORKSPACE: the call needs more scratch memory than it was given.
  *  - The library allocates nothing and keeps no device memory or other state between
  *    calls; it is re-entrant, and calls on different streams may overlap as long as
- *    their workspaces differ.  Small problems (potrf with n <= 128, backward with
+ *    their workspaces differ.  Small problems (potrf and potri with n <= 128, backward with
  *    n <= 128 in fp32 and <= 96 in fp64, trsm with n <= 128 and at most 48 right-hand
  *    sides and with n <= 512 and at most 512 of them, every operator with n <= 32 on operands of at
  *    most 16 vectors / an inner dimension of at most 32, sumlogdiag, gp_glue, gp_criterion up to the

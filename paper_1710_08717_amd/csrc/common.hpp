@@ -464,6 +464,10 @@ template <typename T>
 int backward_leaf16_max_n();
 template <typename T>
 la_status launch_backward_leaf16(View<const T> Lam, View<const T> G, View<T> Abar, int64_t batch, int n, hipStream_t st);
+// potri of matrices of edge n <= 128, one workgroup per matrix, no scratch: B = A^-1 (both triangles, exactly
+// symmetric) from the lower factor Lam of A.  B may alias Lam.
+template <typename T>
+la_status launch_potri_leaf16(View<const T> Lam, View<T> B, int64_t batch, int n, hipStream_t st);
 
 // trsm / trmm for n <= 64 with at most 16 vectors, any batch: the operand as flat items of n * m
 // elements (stored m x n when img_tr), M = Lam (fwd) or Lam^T

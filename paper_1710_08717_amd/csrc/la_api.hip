@@ -683,6 +683,8 @@ static la_status potri_t(int lower, int64_t batch, int n, const void *L, void *B
     View<const T> Lam = tri_view<const T>((const T *)L, n, lower);
     if (n <= 32)  // both solves on the identity in registers, G lanes per matrix (two rows per lane above 16)
         return launch_potri_tiny<T>(Lam, View<T>{(T *)B, (int64_t)n * n, n, 1}, batch, n, st);
+    if (n <= 2 * NB)  // one workgroup per matrix, everything in LDS, no scratch
+        return launch_potri_leaf16<T>(Lam, View<T>{(T *)B, (int64_t)n * n, n, 1}, batch, n, st);
     ArenaFrame frame;
     View<T> sc[2];
     LA_TRY(scratch_views<T>(batch, n, 2, sc));

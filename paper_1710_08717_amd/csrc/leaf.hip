@@ -819,6 +819,101 @@ __global__ __launch_bounds__(NW * 64) void k_backward_leaf16(View<const T> Lam, 
 }
 
 // ---------------------------------------------------------------------------------------
+// potri (section 4.2 "potri": B = A^-1 from the factor of A = L L^T) for one matrix per workgroup,
+// everything in LDS:  Li = L^-1 as in k_tri_inv_leaf16, then  B_ij = sum_{k >= i} Li_ki^T Li_kj  for
+// tiles i >= j, stored with the mirror image.  Two tile areas: [L, later staging of B], [Li].
+// NW and MAXK as in k_backward_leaf16.
+// ---------------------------------------------------------------------------------------
+template <typename T, int NW, int MAXK>
+__global__ __launch_bounds__(NW * 64) void k_potri_leaf16(View<const T> Lam, View<T> B, int64_t batch, int n)
+{
+    using C = Leaf16<T>;
+    using MF = Mfma<T>;
+    extern __shared__ __align__(16) unsigned char leaf16_lds[];
+    T *lds = reinterpret_cast<T *>(leaf16_lds);
+    constexpr int W = NW;
+    constexpr int PS = C::PS, DT = C::DT;
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int64_t b = blockIdx.x;
+    const int K = (n + LT - 1) / LT;
+    const int ntl = K * (K + 1) / 2;
+    const int area = backward16_area<T>(K);
+    const LeafLds<T> m{lds, lds + area, lds + K * DT, lds + area + K * DT};
+
+    leaf_load_lower<T, NW, MAXK>(m, Lam.p + b * Lam.bs, Lam.rs, Lam.cs, n, wave, lane, false, T(1));
+    __syncthreads();
+
+    if (wave < K) {  // all diagonal tiles at once
+        const int r = lane & 15, g = lane >> 4;
+        const T *dk = m.sD + wave * DT + r * PS;
+        T *xk = m.sXD + wave * DT + r * PS;
+        T a[LT], x[4];
+#pragma unroll
+        for (int c = 0; c < LT; ++c)
+            a[c] = dk[c];
+        diag_invert<T>(a, dk[r], x, r, g);
+#pragma unroll
+        for (int jj = 0; jj < 4; ++jj)
+            xk[4 * jj + g] = (4 * jj + g <= r) ? x[jj] : T(0);
+    }
+    __syncthreads();
+    for (int k = 0; k < K; ++k) {
+        if (k > 0) {  // X_kj <- Li_kk X_kj, j < k
+            for (int j = wave; j < k; j += W)
+                leaf_xrow<T>(m, k, j, lane);
+            __syncthreads();
+        }
+        const int rows = K - 1 - k;
+        if (rows > 0) {  // X_ij -= L_ik X_kj, i > k, j <= k
+            int xi = 0, xj = wave;
+            for (int it = wave; it < rows * (k + 1); it += W) {
+                while (xj > k) {
+                    xj -= k + 1;
+                    ++xi;
+                }
+                leaf_update_x<T>(m, k + 1 + xi, xj, k, lane);
+                xj += W;
+            }
+            __syncthreads();
+        }
+    }
+
+    // ---- B_ij = sum_{k >= i} Li_ki^T Li_kj, i >= j, through the tile's slot of the (finished) L area ----
+    T *op = B.p + b * B.bs;
+    const bool colfast = (B.cs == 1) || (B.rs != 1);
+    const int f = lane & 15, s0 = lane >> 4;
+    for (int t = wave; t < ntl; t += W) {
+        int i, j;
+        tri_decode(t, i, j);
+        typename MF::acc_t acc = {0, 0, 0, 0};
+        for (int k = i; k < K; ++k) {
+            T av[4], bv[4];
+            op_nat<T>(m.x(k, i), lane, av);
+            op_nat<T>(m.x(k, j), lane, bv);
+            acc = mma4<T>(av, bv, acc, false);
+        }
+        const TileRef<T> st = m.a(i, j);
+        acc_store<T>(st, lane, acc);
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+            const int u = colfast ? s0 + 4 * v : f, w = colfast ? f : s0 + 4 * v;
+            const T direct = st.p[st.at(u, w)], mirror = st.p[st.at(w, u)];
+            const int r = i * LT + u, c = j * LT + w;
+            if (r < n && c < n)
+                op[(int64_t)r * B.rs + (int64_t)c * B.cs] = (i == j && u < w) ? mirror : direct;
+            const int r2 = j * LT + u, c2 = i * LT + w;
+            if (i != j && r2 < n && c2 < n)
+                op[(int64_t)r2 * B.rs + (int64_t)c2 * B.cs] = mirror;
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------------
 // Gaussian-process criterion and its gradient in one launch (section 3.1: potrf, two trsm,
 // sumlogdiag; backward of trsm (first case) and of potrf from section 4.2), one workgroup per
 // matrix, everything in LDS.  For A = K + noise, targets y:
@@ -1260,6 +1355,37 @@ template la_status launch_backward_leaf16<float>(View<const float>, View<const f
                                                  hipStream_t);
 template la_status launch_backward_leaf16<double>(View<const double>, View<const double>, View<double>, int64_t, int,
                                                   hipStream_t);
+
+template <typename T>
+la_status launch_potri_leaf16(View<const T> Lam, View<T> B, int64_t batch, int n, hipStream_t st)
+{
+    if (batch <= 0 || n <= 0)
+        return LA_OK;
+    if (n > LT * LK || batch > 0x7fffffffll)
+        return LA_ERR_UNSUPPORTED;
+    const int K = (n + LT - 1) / LT;
+    const size_t lds_bytes = 2 * (size_t)backward16_area<T>(K) * sizeof(T);
+    if (dry_run())
+        return LA_OK;
+    static bool configured[64] = {};
+    int dev = 0;
+    LA_HIP(hipGetDevice(&dev));
+    if (dev >= 0 && dev < 64 && !configured[dev]) {
+        LA_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&k_potri_leaf16<T, LEAF16_WAVES, LK>),
+                                   hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024));
+        LA_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&k_potri_leaf16<T, 4, 4>),
+                                   hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024));
+        configured[dev] = true;
+    }
+    if (K <= 4 && batch > 1024 && lds_bytes <= 40 * 1024)  // as for the backward kernel
+        LA_LAUNCH((k_potri_leaf16<T, 4, 4>), dim3((unsigned)batch), dim3(4 * 64), lds_bytes, st, Lam, B, batch, n);
+    else
+        LA_LAUNCH((k_potri_leaf16<T, LEAF16_WAVES, LK>), dim3((unsigned)batch), dim3(LEAF16_THREADS), lds_bytes, st, Lam, B,
+                  batch, n);
+    return launch_check("potri_leaf16");
+}
+template la_status launch_potri_leaf16<float>(View<const float>, View<float>, int64_t, int, hipStream_t);
+template la_status launch_potri_leaf16<double>(View<const double>, View<double>, int64_t, int, hipStream_t);
 
 template <typename T>
 la_status launch_gp_leaf16(View<const T> A, const T *y, T *loss, View<T> Abar, int32_t *info, int64_t batch, int n,

@@ -263,10 +263,12 @@ def test_potri_parity(la, orc, dtype, lower, n):
 @pytest.mark.parametrize("dtype", ["f64", "f32"])
 @pytest.mark.parametrize("lower", [True, False])
 @pytest.mark.parametrize("n,batch", [(16, 4099), (13, 1030), (8, 4101), (6, 259), (4, 4111), (3, 70001), (2, 19), (1, 70),
-                                     (32, 1027), (29, 4098), (24, 515), (20, 130), (17, 5)])
+                                     (32, 1027), (29, 4098), (24, 515), (20, 130), (17, 5), (40, 1030), (48, 1100), (64, 1025),
+                                     (57, 40)])
 def test_potri_small_sizes_with_many_matrices(la, orc, dtype, lower, n, batch):
     """n <= 16: 16, 8 or 4 lanes per matrix; 16 < n <= 32: 16 lanes per matrix with two rows per lane and 24 or 32
-    columns kept.  Both solves in registers; ragged last wavefronts."""
+    columns kept.  Both solves in registers; ragged last wavefronts.  33 <= n <= 128: one workgroup per matrix,
+    with four wavefronts instead of sixteen for many matrices of at most four tile rows."""
     A = spd(7000 + n, batch, n, dtype)
     F = orc.potrf(A, lower=lower).astype(npdt(dtype))
     ref = orc.potri(F, lower=lower)
