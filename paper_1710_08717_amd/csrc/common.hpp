@@ -464,6 +464,14 @@ template <typename T>
 int backward_leaf16_max_n();
 template <typename T>
 la_status launch_backward_leaf16(View<const T> Lam, View<const T> G, View<T> Abar, int64_t batch, int n, hipStream_t st);
+// C = alpha U V^T for many items of 16 < n <= 128 (U, V: n x k views; C n x n), one workgroup per item, operands in
+// LDS.  tri 0: V is U and C is written with both triangles, exactly symmetric; tri 1 / 2: the lower / upper triangle of
+// the product is kept and the other one written as zeros.  outer_leaf_takes says whether the shape fits.
+template <typename T>
+bool outer_leaf_takes(int64_t batch, int n, int k, bool two);
+template <typename T>
+la_status launch_outer_leaf(int tri, T alpha, int64_t batch, int n, int k, View<const T> U, View<const T> V, View<T> C,
+                            hipStream_t st);
 // potri of matrices of edge n <= 128, one workgroup per matrix, no scratch: B = A^-1 (both triangles, exactly
 // symmetric) from the lower factor Lam of A.  B may alias Lam.
 template <typename T>

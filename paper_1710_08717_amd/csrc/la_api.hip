@@ -564,6 +564,8 @@ static la_status syrk_t(int trans, double alpha, int64_t batch, int n, int k, co
         return launch_syrk_tiny<T>(trans != 0, (T)alpha, batch, n, k, (const T *)A, C, st);
     if (outer_rows_takes<T>(n, k, false))  // 16 < n <= 32: 16 lanes per matrix, two rows per lane
         return launch_outer_rows<T>(trans != 0, 0, (T)alpha, batch, n, k, (const T *)A, (const T *)A, C, st);
+    if (outer_leaf_takes<T>(batch, n, k, false))  // one workgroup per matrix, operands in LDS
+        return launch_outer_leaf<T>(0, (T)alpha, batch, n, k, Ank, Ank, C, st);
     GemmOpts o;
     o.maskC = 1;
     LA_TRY(launch_gemm<T>(Ank, Ank.t(), C, batch, n, n, k, (T)alpha, T(0), o, st));
@@ -608,6 +610,14 @@ static la_status tri_outer_t(int lower, int trans, int rightside, T scale, int64
         if (n <= 16)
             return launch_outer_tiny<T>(rightside != 0, lower ? 1 : 2, scale, batch, n, m, U, V, G, st);
         return launch_outer_rows<T>(rightside != 0, lower ? 1 : 2, scale, batch, n, m, U, V, G, st);
+    }
+    if (outer_leaf_takes<T>(batch, n, m, true)) {  // one workgroup per matrix: product, mask and zeros in one launch
+        const T *X1 = trans ? Q : P, *X2 = trans ? P : Q;
+        if (!rightside)
+            return launch_outer_leaf<T>(lower ? 1 : 2, scale, batch, n, m, View<const T>{X1, nm, m, 1},
+                                        View<const T>{X2, nm, m, 1}, G, st);
+        return launch_outer_leaf<T>(lower ? 1 : 2, scale, batch, n, m, View<const T>{X2, nm, 1, n},
+                                    View<const T>{X1, nm, 1, n}, G, st);
     }
     LA_TRY(launch_zero_strict_upper<T>(lower ? G : G.t(), batch, n, st));  // the other triangle of the result
     GemmOpts o;

@@ -914,6 +914,109 @@ __global__ __launch_bounds__(NW * 64) void k_potri_leaf16(View<const T> Lam, Vie
 }
 
 // ---------------------------------------------------------------------------------------
+// Outer products of small matrices, one workgroup per item, operands in LDS as 16 x 16 tiles:
+//   C = alpha U V^T,  U and V n x k (any strides), C n x n.
+// tri 0: U and V are the same matrix (syrk, section 4.2): the tiles on and below the diagonal are
+//        computed and stored with their mirror image, so C is exactly symmetric;
+// tri 1 / 2: only the lower / upper triangle of the product is kept, the other one is written as
+//        zeros (the triangular operand's gradient in the trmm and trsm backward rules).
+// ---------------------------------------------------------------------------------------
+template <typename T>
+__device__ __forceinline__ void rect_load(T *tiles, int Kc, const T *p, int64_t rs, int64_t cs, int rows, int cols,
+                                          int Kr, int wave, int lane, int W)
+{
+    const bool colfast = (cs == 1) || (rs != 1);
+    const int f = lane & 15, s0 = lane >> 4;
+    for (int t = wave; t < Kr * Kc; t += W) {
+        const int ti = t / Kc, tk = t % Kc;
+        const TileRef<T> tr{tiles + t * Leaf16<T>::OT, false};
+        T val[4];
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+            const int u = colfast ? s0 + 4 * v : f, w = colfast ? f : s0 + 4 * v;
+            const int r = ti * LT + u, c = tk * LT + w;
+            val[v] = (r < rows && c < cols) ? p[(int64_t)r * rs + (int64_t)c * cs] : T(0);
+        }
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+            const int u = colfast ? s0 + 4 * v : f, w = colfast ? f : s0 + 4 * v;
+            tr.p[tr.at(u, w)] = val[v];
+        }
+    }
+}
+
+template <typename T, int NW>
+__global__ __launch_bounds__(NW * 64) void k_outer_leaf16(View<const T> U, View<const T> V, View<T> Cv, int64_t batch,
+                                                          int n, int k, T alpha, int tri)
+{
+    using C = Leaf16<T>;
+    using MF = Mfma<T>;
+    extern __shared__ __align__(16) unsigned char leaf16_lds[];
+    T *lds = reinterpret_cast<T *>(leaf16_lds);
+    constexpr int OT = C::OT;
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int64_t b = blockIdx.x;
+    const int Kn = (n + LT - 1) / LT, Kk = (k + LT - 1) / LT;
+    T *tu = lds, *tv = tri == 0 ? lds : lds + Kn * Kk * OT;
+    T *stage = lds + (tri == 0 ? 1 : 2) * Kn * Kk * OT + wave * OT;  // one tile per wavefront
+
+    rect_load<T>(tu, Kk, U.p + b * U.bs, U.rs, U.cs, n, k, Kn, wave, lane, NW);
+    if (tri != 0)
+        rect_load<T>(tv, Kk, V.p + b * V.bs, V.rs, V.cs, n, k, Kn, wave, lane, NW);
+    __syncthreads();
+
+    T *op = Cv.p + b * Cv.bs;
+    const bool colfast = (Cv.cs == 1) || (Cv.rs != 1);
+    const int f = lane & 15, s0 = lane >> 4;
+    for (int t = wave; t < Kn * Kn; t += NW) {
+        const int i = t / Kn, j = t % Kn;
+        const bool kept = tri == 2 ? (i <= j) : (i >= j);
+        if (tri == 0 && !kept)
+            continue;  // written as the mirror image of tile (j, i)
+        typename MF::acc_t acc = {0, 0, 0, 0};
+        if (kept) {
+            for (int kk = 0; kk < Kk; ++kk) {
+                T av[4], bv[4];
+                op_rows<T>(TileRef<T>{tu + (i * Kk + kk) * OT, false}, lane, av);
+                op_rows<T>(TileRef<T>{tv + (j * Kk + kk) * OT, false}, lane, bv);
+                acc = mma4<T>(av, bv, acc, false);
+            }
+        }
+        const TileRef<T> st{stage, false};
+#pragma unroll
+        for (int v = 0; v < 4; ++v)
+            acc[v] *= alpha;
+        acc_store<T>(st, lane, acc);
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+            const int u = colfast ? s0 + 4 * v : f, w = colfast ? f : s0 + 4 * v;
+            const T direct = st.p[st.at(u, w)], mirror = st.p[st.at(w, u)];
+            const int r = i * LT + u, c = j * LT + w;
+            T val = direct;
+            if (i == j) {
+                if (tri == 0)
+                    val = u < w ? mirror : direct;
+                else if (tri == 1 ? (u < w) : (u > w))
+                    val = T(0);
+            }
+            if (r < n && c < n)
+                op[(int64_t)r * Cv.rs + (int64_t)c * Cv.cs] = val;
+            const int r2 = j * LT + u, c2 = i * LT + w;
+            if (tri == 0 && i != j && r2 < n && c2 < n)
+                op[(int64_t)r2 * Cv.rs + (int64_t)c2 * Cv.cs] = mirror;
+        }
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();  // the staging tile is free again
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    }
+}
+
+// ---------------------------------------------------------------------------------------
 // Gaussian-process criterion and its gradient in one launch (section 3.1: potrf, two trsm,
 // sumlogdiag; backward of trsm (first case) and of potrf from section 4.2), one workgroup per
 // matrix, everything in LDS.  For A = K + noise, targets y:
@@ -1386,6 +1489,64 @@ la_status launch_potri_leaf16(View<const T> Lam, View<T> B, int64_t batch, int n
 }
 template la_status launch_potri_leaf16<float>(View<const float>, View<float>, int64_t, int, hipStream_t);
 template la_status launch_potri_leaf16<double>(View<const double>, View<double>, int64_t, int, hipStream_t);
+
+// LDS of k_outer_leaf16 with NW wavefronts: the operand tiles and a staging tile per wavefront
+template <typename T>
+static size_t outer_leaf_lds(int n, int k, bool two, int nw)
+{
+    const int Kn = (n + LT - 1) / LT, Kk = (k + LT - 1) / LT;
+    return ((size_t)(two ? 2 : 1) * Kn * Kk + nw) * Leaf16<T>::OT * sizeof(T);
+}
+template <typename T>
+bool outer_leaf_takes(int64_t batch, int n, int k, bool two)
+{
+    // worth it while a matrix is too small for the tiles of the general product to fill the chip, and as
+    // long as a few workgroups fit a compute unit
+    // (measured against the general product, 4096 items of 64 x 64 with k = 64 in fp32: one operand 80 -> 40 us,
+    // two operands 157 -> 181 us for the whole trmm backward rule, hence the tile limit on two operands)
+    const int Kn = (n + LT - 1) / LT, Kk = (k + LT - 1) / LT;
+    if (two && Kn * Kk > 8)
+        return false;
+    return n > 16 && n <= 128 && k >= 1 && k <= 128 && batch >= 64 && outer_leaf_lds<T>(n, k, two, LEAF16_WAVES) <= 64 * 1024;
+}
+template bool outer_leaf_takes<float>(int64_t, int, int, bool);
+template bool outer_leaf_takes<double>(int64_t, int, int, bool);
+
+template <typename T>
+la_status launch_outer_leaf(int tri, T alpha, int64_t batch, int n, int k, View<const T> U, View<const T> V, View<T> C,
+                            hipStream_t st)
+{
+    if (batch <= 0 || n <= 0)
+        return LA_OK;
+    if (!outer_leaf_takes<T>(batch, n, k, tri != 0) || batch > 0x7fffffffll)
+        return LA_ERR_UNSUPPORTED;
+    if (dry_run())
+        return LA_OK;
+    static bool configured[64] = {};
+    int dev = 0;
+    LA_HIP(hipGetDevice(&dev));
+    if (dev >= 0 && dev < 64 && !configured[dev]) {
+        LA_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&k_outer_leaf16<T, LEAF16_WAVES>),
+                                   hipFuncAttributeMaxDynamicSharedMemorySize, 64 * 1024));
+        LA_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&k_outer_leaf16<T, 4>),
+                                   hipFuncAttributeMaxDynamicSharedMemorySize, 64 * 1024));
+        configured[dev] = true;
+    }
+    const int Kn = (n + LT - 1) / LT;
+    const int tiles = tri == 0 ? Kn * (Kn + 1) / 2 : Kn * Kn;
+    if (tiles <= 16 && batch > 1024) {  // many small items: four wavefronts each
+        LA_LAUNCH((k_outer_leaf16<T, 4>), dim3((unsigned)batch), dim3(4 * 64), outer_leaf_lds<T>(n, k, tri != 0, 4), st, U, V,
+                  C, batch, n, k, alpha, tri);
+    } else {
+        LA_LAUNCH((k_outer_leaf16<T, LEAF16_WAVES>), dim3((unsigned)batch), dim3(LEAF16_THREADS),
+                  outer_leaf_lds<T>(n, k, tri != 0, LEAF16_WAVES), st, U, V, C, batch, n, k, alpha, tri);
+    }
+    return launch_check("outer_leaf16");
+}
+template la_status launch_outer_leaf<float>(int, float, int64_t, int, int, View<const float>, View<const float>, View<float>,
+                                            hipStream_t);
+template la_status launch_outer_leaf<double>(int, double, int64_t, int, int, View<const double>, View<const double>,
+                                             View<double>, hipStream_t);
 
 template <typename T>
 la_status launch_gp_leaf16(View<const T> A, const T *y, T *loss, View<T> Abar, int32_t *info, int64_t batch, int n,

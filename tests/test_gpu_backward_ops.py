@@ -125,12 +125,14 @@ def test_trsm_backward_parity(la, orc, dtype, lower, trans, rightside, n, m):
 @pytest.mark.parametrize("op", ["trsm", "trmm"])
 @pytest.mark.parametrize("n,m,batch", [(16, 16, 1031), (16, 32, 70), (13, 7, 515), (8, 8, 4101), (5, 20, 66), (4, 4, 4111),
                                        (3, 1, 1037), (1, 1, 5), (16, 33, 9),
-                                       (32, 16, 1027), (32, 32, 9), (24, 16, 515), (19, 5, 130), (27, 32, 7)])
+                                       (32, 16, 1027), (32, 32, 9), (24, 16, 515), (19, 5, 130), (27, 32, 7),
+                                       (40, 16, 70), (48, 32, 1030), (64, 20, 66), (100, 9, 64), (33, 40, 65), (128, 16, 64)])
 def test_small_backward_rules_with_many_matrices(la, orc, dtype, lower, trans, rightside, op, n, m, batch):
     """n <= 16: the solve / multiply and the triangular operand's gradient (outer product over up to 32 vectors, masked)
     run in lane groups of 16, 8 or 4 per matrix; 16 < n <= 32: the outer product in 16 lanes with two rows per lane
     (two fp64 images of 32 x 32 do not fit one workgroup's LDS and take the tiled path, as does m = 33); ragged last
-    wavefronts."""
+    wavefronts.  From 64 matrices of 32 < n <= 128 on, the outer product of operands of at most eight tiles is one
+    workgroup per matrix (with four wavefronts above 1024 matrices)."""
     T, Tj, A, G, other = case(4000 + n + m, n, m, lower, rightside, dtype, batch=batch)
     alpha = 0.5
     if op == "trsm":

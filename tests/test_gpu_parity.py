@@ -479,6 +479,26 @@ def test_syrk_large_lower_triangle_tile_counts(la, orc, dtype, n, k):
 
 @pytest.mark.parametrize("dtype", ["f64", "f32"])
 @pytest.mark.parametrize("trans", [False, True])
+@pytest.mark.parametrize("n,k,batch", [(33, 8, 70), (48, 32, 1030), (40, 50, 64), (64, 64, 65), (100, 17, 64), (128, 48, 64),
+                                       (128, 128, 64), (57, 1, 1100)])
+def test_syrk_one_workgroup_per_matrix(la, orc, dtype, trans, n, k, batch):
+    """From 64 matrices of 32 < n <= 128 on, syrk keeps its operand in LDS, one workgroup per matrix (four wavefronts
+    above 1024 matrices of at most four tile rows), and writes every tile with its mirror image; 128 x 128 operands
+    in fp64 do not fit and take the tiled product."""
+    import torch
+
+    rng = np.random.default_rng(n * k + batch)
+    A = rng.standard_normal((batch, k, n) if trans else (batch, n, k)).astype(npdt(dtype))
+    ref = orc.syrk(A, trans=trans, alpha=-0.75)
+    out = torch.full((batch, n, n), float("nan"), dtype=dev(A).dtype, device="cuda")
+    la.syrk(dev(A), trans=trans, alpha=-0.75, out=out)
+    o = host(out)
+    assert np.array_equal(o, o.transpose(0, 2, 1))
+    assert relerr(o, ref) <= TOL[dtype]
+
+
+@pytest.mark.parametrize("dtype", ["f64", "f32"])
+@pytest.mark.parametrize("trans", [False, True])
 @pytest.mark.parametrize("n,k,batch", [(16, 32, 4099), (16, 1, 70001), (13, 31, 1030), (8, 16, 4101), (7, 5, 259), (4, 8, 4111),
                                        (3, 32, 1037), (2, 2, 19), (1, 7, 5), (16, 33, 7),
                                        (32, 32, 1027), (29, 9, 4098), (24, 32, 515), (20, 1, 130), (17, 31, 5), (32, 33, 6)])
