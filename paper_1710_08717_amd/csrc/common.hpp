@@ -472,6 +472,12 @@ bool outer_leaf_takes(int64_t batch, int n, int k, bool two);
 template <typename T>
 la_status launch_outer_leaf(int tri, T alpha, int64_t batch, int n, int k, View<const T> U, View<const T> V, View<T> C,
                             hipStream_t st);
+// syrk backward in the same form: Out = alpha (G + G^T) A with G n x n, A and Out n x k views
+template <typename T>
+bool symm_leaf_takes(int64_t batch, int n, int k);
+template <typename T>
+la_status launch_symm_leaf(T alpha, int64_t batch, int n, int k, View<const T> G, View<const T> A, View<T> Out,
+                           hipStream_t st);
 // potri of matrices of edge n <= 128, one workgroup per matrix, no scratch: B = A^-1 (both triangles, exactly
 // symmetric) from the lower factor Lam of A.  B may alias Lam.
 template <typename T>

@@ -671,6 +671,13 @@ static la_status syrk_backward_t(int trans, double alpha, int64_t batch, int n, 
         return launch_symm_tiny<T>(trans != 0, (T)alpha, batch, n, k, G, (const T *)A, (T *)Abar, st);
     if (symm_rows_takes<T>(n, k))  // 16 < n <= 32: 16 lanes per matrix, two rows per lane
         return launch_symm_rows<T>(trans != 0, (T)alpha, batch, n, k, G, (const T *)A, (T *)Abar, st);
+    if (symm_leaf_takes<T>(batch, n, k)) {  // one workgroup per matrix, operands in LDS; A and Abar as n x k views
+        if (!trans)
+            return launch_symm_leaf<T>((T)alpha, batch, n, k, G, View<const T>{(const T *)A, nk, k, 1},
+                                       View<T>{(T *)Abar, nk, k, 1}, st);
+        return launch_symm_leaf<T>((T)alpha, batch, n, k, G, View<const T>{(const T *)A, nk, 1, n},
+                                   View<T>{(T *)Abar, nk, 1, n}, st);
+    }
     GemmOpts o;
     if (!trans) {
         View<const T> Av{(const T *)A, nk, k, 1};

@@ -1017,6 +1017,70 @@ __global__ __launch_bounds__(NW * 64) void k_outer_leaf16(View<const T> U, View<
 }
 
 // ---------------------------------------------------------------------------------------
+// syrk backward (section 4.2 "syrk", backward) for small matrices, one workgroup per item:
+//   Out = alpha (G + G^T) A,   G n x n (need not be symmetric), A and Out n x k (any strides).
+// G and A sit in LDS as tiles; the left operand of each 16 x 16 x 16 product is G_ij + G_ji^T, added
+// in the operand registers.
+// ---------------------------------------------------------------------------------------
+template <typename T, int NW>
+__global__ __launch_bounds__(NW * 64) void k_symm_leaf16(View<const T> G, View<const T> A, View<T> Out, int64_t batch, int n,
+                                                         int k, T alpha)
+{
+    using C = Leaf16<T>;
+    using MF = Mfma<T>;
+    extern __shared__ __align__(16) unsigned char leaf16_lds[];
+    T *lds = reinterpret_cast<T *>(leaf16_lds);
+    constexpr int OT = C::OT;
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int64_t b = blockIdx.x;
+    const int Kn = (n + LT - 1) / LT, Kk = (k + LT - 1) / LT;
+    T *tg = lds, *ta = lds + Kn * Kn * OT;
+    T *stage = ta + Kn * Kk * OT + wave * OT;  // one tile per wavefront
+
+    rect_load<T>(tg, Kn, G.p + b * G.bs, G.rs, G.cs, n, n, Kn, wave, lane, NW);
+    rect_load<T>(ta, Kk, A.p + b * A.bs, A.rs, A.cs, n, k, Kn, wave, lane, NW);
+    __syncthreads();
+
+    T *op = Out.p + b * Out.bs;
+    const bool colfast = (Out.cs == 1) || (Out.rs != 1);
+    const int f = lane & 15, s0 = lane >> 4;
+    for (int t = wave; t < Kn * Kk; t += NW) {
+        const int i = t / Kk, c = t % Kk;
+        typename MF::acc_t acc = {0, 0, 0, 0};
+        for (int j = 0; j < Kn; ++j) {
+            T av[4], at[4], bv[4];
+            op_rows<T>(TileRef<T>{tg + (i * Kn + j) * OT, false}, lane, av);
+            op_nat<T>(TileRef<T>{tg + (j * Kn + i) * OT, false}, lane, at);  // as a left operand: the transpose
+            op_nat<T>(TileRef<T>{ta + (j * Kk + c) * OT, false}, lane, bv);
+#pragma unroll
+            for (int s = 0; s < 4; ++s)
+                av[s] += at[s];
+            acc = mma4<T>(av, bv, acc, false);
+        }
+        const TileRef<T> st{stage, false};
+#pragma unroll
+        for (int v = 0; v < 4; ++v)
+            acc[v] *= alpha;
+        acc_store<T>(st, lane, acc);
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+            const int u = colfast ? s0 + 4 * v : f, w = colfast ? f : s0 + 4 * v;
+            const int r = i * LT + u, cc = c * LT + w;
+            if (r < n && cc < k)
+                op[(int64_t)r * Out.rs + (int64_t)cc * Out.cs] = st.p[st.at(u, w)];
+        }
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();  // the staging tile is free again
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    }
+}
+
+// ---------------------------------------------------------------------------------------
 // Gaussian-process criterion and its gradient in one launch (section 3.1: potrf, two trsm,
 // sumlogdiag; backward of trsm (first case) and of potrf from section 4.2), one workgroup per
 // matrix, everything in LDS.  For A = K + noise, targets y:
@@ -1547,6 +1611,45 @@ template la_status launch_outer_leaf<float>(int, float, int64_t, int, int, View<
                                             hipStream_t);
 template la_status launch_outer_leaf<double>(int, double, int64_t, int, int, View<const double>, View<const double>,
                                              View<double>, hipStream_t);
+
+template <typename T>
+static size_t symm_leaf_lds(int n, int k, int nw)
+{
+    const int Kn = (n + LT - 1) / LT, Kk = (k + LT - 1) / LT;
+    return ((size_t)Kn * Kn + (size_t)Kn * Kk + nw) * Leaf16<T>::OT * sizeof(T);
+}
+template <typename T>
+bool symm_leaf_takes(int64_t batch, int n, int k)
+{
+    return n > 16 && n <= 128 && k >= 1 && k <= 128 && batch >= 64 && symm_leaf_lds<T>(n, k, LEAF16_WAVES) <= 64 * 1024;
+}
+template bool symm_leaf_takes<float>(int64_t, int, int);
+template bool symm_leaf_takes<double>(int64_t, int, int);
+
+template <typename T>
+la_status launch_symm_leaf(T alpha, int64_t batch, int n, int k, View<const T> G, View<const T> A, View<T> Out,
+                           hipStream_t st)
+{
+    if (batch <= 0 || n <= 0)
+        return LA_OK;
+    if (!symm_leaf_takes<T>(batch, n, k) || batch > 0x7fffffffll)
+        return LA_ERR_UNSUPPORTED;
+    if (dry_run())
+        return LA_OK;
+    const int Kn = (n + LT - 1) / LT, Kk = (k + LT - 1) / LT;
+    if (Kn * Kk <= 16 && batch > 1024) {  // many small items: four wavefronts each
+        LA_LAUNCH((k_symm_leaf16<T, 4>), dim3((unsigned)batch), dim3(4 * 64), symm_leaf_lds<T>(n, k, 4), st, G, A, Out, batch,
+                  n, k, alpha);
+    } else {
+        LA_LAUNCH((k_symm_leaf16<T, LEAF16_WAVES>), dim3((unsigned)batch), dim3(LEAF16_THREADS),
+                  symm_leaf_lds<T>(n, k, LEAF16_WAVES), st, G, A, Out, batch, n, k, alpha);
+    }
+    return launch_check("symm_leaf16");
+}
+template la_status launch_symm_leaf<float>(float, int64_t, int, int, View<const float>, View<const float>, View<float>,
+                                           hipStream_t);
+template la_status launch_symm_leaf<double>(double, int64_t, int, int, View<const double>, View<const double>, View<double>,
+                                            hipStream_t);
 
 template <typename T>
 la_status launch_gp_leaf16(View<const T> A, const T *y, T *loss, View<T> Abar, int32_t *info, int64_t batch, int n,

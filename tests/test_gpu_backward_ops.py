@@ -179,6 +179,21 @@ def test_syrk_backward_parity(la, orc, dtype, trans, n, k):
     assert relerr(out, ref) <= TOL[dtype]
 
 
+@pytest.mark.parametrize("dtype", ["f64", "f32"])
+@pytest.mark.parametrize("trans", [False, True])
+@pytest.mark.parametrize("n,k,batch", [(33, 8, 70), (48, 32, 1030), (40, 50, 64), (64, 64, 65), (100, 17, 64), (57, 1, 1100),
+                                       (128, 16, 64)])
+def test_syrk_backward_one_workgroup_per_matrix(la, orc, dtype, trans, n, k, batch):
+    """From 64 matrices of 32 < n <= 128 on, the rule keeps Bbar and A in LDS, one workgroup per matrix (where both fit
+    64 KB; four wavefronts above 1024 matrices of at most 16 output tiles)."""
+    rng = np.random.default_rng(n * k + batch + 1)
+    A = rng.standard_normal((batch, k, n) if trans else (batch, n, k)).astype(npdt(dtype))
+    G = (rng.standard_normal((batch, n, n)) / np.sqrt(n)).astype(npdt(dtype))  # not symmetric
+    ref = orc.syrk_backward(A, G, trans=trans, alpha=-0.6)
+    out = host(la.syrk_backward(dev(A), dev(G), trans=trans, alpha=-0.6))
+    assert relerr(out, ref) <= TOL[dtype]
+
+
 def test_backward_ops_gp_chain(la, orc):
     """The chain the GP criterion of section 3.1 differentiates through: z = L^-1 y, then the trsm
     rule gives ybar and Lbar; checked against the oracle with one right-hand side per matrix."""
