@@ -478,6 +478,13 @@ bool symm_leaf_takes(int64_t batch, int n, int k);
 template <typename T>
 la_status launch_symm_leaf(T alpha, int64_t batch, int n, int k, View<const T> G, View<const T> A, View<T> Out,
                            hipStream_t st);
+// trmm in the same form: X = alpha M Xin with M = Lam (fwd) or Lam^T, Lam lower triangular, Xin and X n x m views
+// (X may be Xin); no scratch
+template <typename T>
+bool trmm_leaf_takes(int64_t batch, int n, int m);
+template <typename T>
+la_status launch_trmm_leaf(View<const T> Lam, View<const T> Xin, View<T> X, int64_t batch, int n, int m, T alpha, bool fwd,
+                           hipStream_t st);
 // potri of matrices of edge n <= 128, one workgroup per matrix, no scratch: B = A^-1 (both triangles, exactly
 // symmetric) from the lower factor Lam of A.  B may alias Lam.
 template <typename T>

@@ -454,6 +454,13 @@ static la_status tri_apply_v(bool solve, bool fwd, T alpha, int64_t batch, int n
     // with 16 < n over a small batch is quicker in the one-workgroup kernel below: 16 matrices of n = 32,
     // fp64: 6.5 against 10.9 us; the lane-group kernel wins once there are more matrices than workgroup
     // slots.)
+    // A multiply on many small items: one workgroup per item, Lam's lower tiles and the vectors in LDS, no scratch.
+    // Up to n = 32 with at most 16 vectors the lane-group kernels below are faster; above that this one is
+    // (7281 x 48 x 48 times 16 vectors, fp32 / fp64: 64 lanes per matrix 91 / 183 us).
+    const bool leaf_mul = !solve && trmm_leaf_takes<T>(batch, n, m) && Lam.nb2 == 1 && Xin.nb2 == 1 && X.nb2 == 1;
+    if (leaf_mul && (n > 32 || m > 16))
+        return launch_trmm_leaf<T>(Lam, Xin, X, batch, n, m, alpha, fwd, st);
+
     if (n <= 64 && m <= 16 && (!solve || n <= 16 || batch > 1024) && X.bs == nm && Xin.bs == nm && Xin.rs == X.rs && Xin.cs == X.cs && X.nb2 == 1 &&
         Xin.nb2 == 1 && Lam.nb2 == 1) {
         const bool rowmajor = (X.rs == m && X.cs == 1), colmajor = (X.rs == 1 && X.cs == n);
@@ -462,6 +469,9 @@ static la_status tri_apply_v(bool solve, bool fwd, T alpha, int64_t batch, int n
         if (rowmajor || colmajor)
             return launch_tri_tiny<T>(solve, fwd, alpha, batch, n, m, Lam, Xin.p, X.p, !rowmajor, st);
     }
+
+    if (leaf_mul)  // (operands the lane-group kernels do not take: other strides)
+        return launch_trmm_leaf<T>(Lam, Xin, X, batch, n, m, alpha, fwd, st);
 
     if (solve && n <= 128 && m <= 48)  // small: one workgroup per item does the whole substitution, no scratch
         return launch_trsm_leaf16<T>(Lam, Xin, X, batch, n, m, alpha, fwd, st);

@@ -1081,6 +1081,71 @@ __global__ __launch_bounds__(NW * 64) void k_symm_leaf16(View<const T> G, View<c
 }
 
 // ---------------------------------------------------------------------------------------
+// trmm (section 4.2 "trmm") for small matrices, one workgroup per item:  X = alpha M Xin with M = Lam
+// (fwd) or Lam^T, Lam lower triangular n x n, Xin and X n x m (any strides; X may be Xin).  The lower
+// tiles of Lam and the tiles of Xin sit in LDS; what lies above Lam's diagonal is never read.
+// ---------------------------------------------------------------------------------------
+template <typename T, int NW, int MAXK>
+__global__ __launch_bounds__(NW * 64) void k_trmm_leaf16(View<const T> Lam, View<const T> Xin, View<T> X, int64_t batch, int n,
+                                                         int m, T alpha, int fwd)
+{
+    using C = Leaf16<T>;
+    using MF = Mfma<T>;
+    extern __shared__ __align__(16) unsigned char leaf16_lds[];
+    T *lds = reinterpret_cast<T *>(leaf16_lds);
+    constexpr int OT = C::OT, DT = C::DT;
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int64_t b = blockIdx.x;
+    const int Kn = (n + LT - 1) / LT, Km = (m + LT - 1) / LT;
+    const int area = backward16_area<T>(Kn);
+    const LeafLds<T> ml{lds, lds, lds + Kn * DT, lds + Kn * DT};  // only the A / L areas are used
+    T *tx = lds + area;
+    T *stage = tx + Kn * Km * OT + wave * OT;  // one tile per wavefront
+
+    leaf_load_lower<T, NW, MAXK>(ml, Lam.p + b * Lam.bs, Lam.rs, Lam.cs, n, wave, lane, false, T(0));
+    rect_load<T>(tx, Km, Xin.p + b * Xin.bs, Xin.rs, Xin.cs, n, m, Kn, wave, lane, NW);
+    __syncthreads();
+
+    T *op = X.p + b * X.bs;
+    const bool colfast = (X.cs == 1) || (X.rs != 1);
+    const int f = lane & 15, s0 = lane >> 4;
+    for (int t = wave; t < Kn * Km; t += NW) {
+        const int i = t / Km, c = t % Km;
+        typename MF::acc_t acc = {0, 0, 0, 0};
+        const int j0 = fwd ? 0 : i, j1 = fwd ? i : Kn - 1;
+        for (int j = j0; j <= j1; ++j) {
+            T av[4], bv[4];
+            if (fwd)
+                op_rows<T>(ml.a(i, j), lane, av);
+            else
+                op_nat<T>(ml.a(j, i), lane, av);  // as a left operand: the transpose
+            op_nat<T>(TileRef<T>{tx + (j * Km + c) * OT, false}, lane, bv);
+            acc = mma4<T>(av, bv, acc, false);
+        }
+        const TileRef<T> st{stage, false};
+#pragma unroll
+        for (int v = 0; v < 4; ++v)
+            acc[v] *= alpha;
+        acc_store<T>(st, lane, acc);
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+            const int u = colfast ? s0 + 4 * v : f, w = colfast ? f : s0 + 4 * v;
+            const int r = i * LT + u, cc = c * LT + w;
+            if (r < n && cc < m)
+                op[(int64_t)r * X.rs + (int64_t)cc * X.cs] = st.p[st.at(u, w)];
+        }
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();  // the staging tile is free again
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    }
+}
+
+// ---------------------------------------------------------------------------------------
 // Gaussian-process criterion and its gradient in one launch (section 3.1: potrf, two trsm,
 // sumlogdiag; backward of trsm (first case) and of potrf from section 4.2), one workgroup per
 // matrix, everything in LDS.  For A = K + noise, targets y:
@@ -1650,6 +1715,45 @@ template la_status launch_symm_leaf<float>(float, int64_t, int, int, View<const 
                                            hipStream_t);
 template la_status launch_symm_leaf<double>(double, int64_t, int, int, View<const double>, View<const double>, View<double>,
                                             hipStream_t);
+
+template <typename T>
+static size_t trmm_leaf_lds(int n, int m, int nw)
+{
+    const int Kn = (n + LT - 1) / LT, Km = (m + LT - 1) / LT;
+    return ((size_t)backward16_area<T>(Kn) + ((size_t)Kn * Km + nw) * Leaf16<T>::OT) * sizeof(T);
+}
+template <typename T>
+bool trmm_leaf_takes(int64_t batch, int n, int m)
+{
+    return n >= 1 && n <= 128 && m >= 1 && m <= 128 && batch >= 64 && trmm_leaf_lds<T>(n, m, LEAF16_WAVES) <= 64 * 1024;
+}
+template bool trmm_leaf_takes<float>(int64_t, int, int);
+template bool trmm_leaf_takes<double>(int64_t, int, int);
+
+template <typename T>
+la_status launch_trmm_leaf(View<const T> Lam, View<const T> Xin, View<T> X, int64_t batch, int n, int m, T alpha, bool fwd,
+                           hipStream_t st)
+{
+    if (batch <= 0 || n <= 0 || m <= 0)
+        return LA_OK;
+    if (!trmm_leaf_takes<T>(batch, n, m) || batch > 0x7fffffffll)
+        return LA_ERR_UNSUPPORTED;
+    if (dry_run())
+        return LA_OK;
+    const int Kn = (n + LT - 1) / LT, Km = (m + LT - 1) / LT;
+    if (Kn <= 4 && Kn * Km <= 16 && batch > 1024) {  // many small items: four wavefronts each
+        LA_LAUNCH((k_trmm_leaf16<T, 4, 4>), dim3((unsigned)batch), dim3(4 * 64), trmm_leaf_lds<T>(n, m, 4), st, Lam, Xin, X,
+                  batch, n, m, alpha, fwd ? 1 : 0);
+    } else {
+        LA_LAUNCH((k_trmm_leaf16<T, LEAF16_WAVES, LK>), dim3((unsigned)batch), dim3(LEAF16_THREADS),
+                  trmm_leaf_lds<T>(n, m, LEAF16_WAVES), st, Lam, Xin, X, batch, n, m, alpha, fwd ? 1 : 0);
+    }
+    return launch_check("trmm_leaf16");
+}
+template la_status launch_trmm_leaf<float>(View<const float>, View<const float>, View<float>, int64_t, int, int, float, bool,
+                                           hipStream_t);
+template la_status launch_trmm_leaf<double>(View<const double>, View<const double>, View<double>, int64_t, int, int, double,
+                                            bool, hipStream_t);
 
 template <typename T>
 la_status launch_gp_leaf16(View<const T> A, const T *y, T *loss, View<T> Abar, int32_t *info, int64_t batch, int n,

@@ -340,12 +340,14 @@ def test_trsm_parity(la, orc, dtype, lower, trans, rightside, n, m):
 @pytest.mark.parametrize("n,m,batch", [(16, 16, 4099), (16, 1, 70001), (13, 7, 1030), (8, 8, 4101), (7, 16, 259), (5, 3, 66),
                                        (4, 4, 4111), (3, 16, 1037), (2, 5, 19), (1, 1, 5), (32, 8, 1031), (24, 16, 130),
                                        (17, 2, 3), (64, 8, 1300), (40, 3, 2100), (33, 1, 1029), (64, 16, 5),
-                                       (32, 16, 4098), (24, 16, 1030), (29, 5, 2051), (20, 1, 1500)])
+                                       (32, 16, 4098), (24, 16, 1030), (29, 5, 2051), (20, 1, 1500),
+                                       (48, 32, 1030), (100, 9, 64), (128, 16, 64), (16, 40, 70), (96, 33, 65)])
 def test_small_triangular_operators_with_many_matrices(la, orc, dtype, lower, trans, rightside, op, n, m, batch):
     """n <= 64 with at most 16 vectors: 4 .. 64 lanes per matrix (16 < n <= 32: 16 lanes with two rows per lane),
     operands moved as flat images; batches that
     leave the last wavefront ragged, more items than one grid dimension holds, in place and out of place.  (Solves
-    with n > 16 take this kernel above 1024 matrices only, multiplies always.)"""
+    with n > 16 take this kernel above 1024 matrices only.)  Multiplies of 64 items or more with n > 32 or more than
+    16 vectors, n and m up to 128: one workgroup per item with the factor's lower tiles and the vectors in LDS."""
     T = tri(n * 3 + m, batch, n, lower, dtype)
     other = np.triu_indices(n, 1) if lower else np.tril_indices(n, -1)
     Tj = T.copy()
