@@ -452,8 +452,9 @@ static la_status tri_apply_v(bool solve, bool fwd, T alpha, int64_t batch, int n
 
     // n <= 64 with at most 16 vectors stored as whole items back to back: G lanes per matrix.  (A solve
     // with 16 < n over a small batch is quicker in the one-workgroup kernel below: 16 matrices of n = 32,
-    // fp64: 6.5 against 10.9 us; the lane-group kernel wins once there are more matrices than workgroup
-    // slots.)
+    // fp64: 6.5 against 10.9 us; up to n = 32 the lane-group kernel wins once there are more matrices than
+    // workgroup slots, above that the one-workgroup kernel with four wavefronts per item does: 7281
+    // solves of 48 x 48 with 16 vectors 136 -> 35 us in fp32, 285 -> 46 in fp64.)
     // A multiply on many small items: one workgroup per item, Lam's lower tiles and the vectors in LDS, no scratch.
     // Up to n = 32 with at most 16 vectors the lane-group kernels below are faster; above that this one is
     // (7281 x 48 x 48 times 16 vectors, fp32 / fp64: 64 lanes per matrix 91 / 183 us).
@@ -461,7 +462,7 @@ static la_status tri_apply_v(bool solve, bool fwd, T alpha, int64_t batch, int n
     if (leaf_mul && (n > 32 || m > 16))
         return launch_trmm_leaf<T>(Lam, Xin, X, batch, n, m, alpha, fwd, st);
 
-    if (n <= 64 && m <= 16 && (!solve || n <= 16 || batch > 1024) && X.bs == nm && Xin.bs == nm && Xin.rs == X.rs && Xin.cs == X.cs && X.nb2 == 1 &&
+    if (n <= 64 && m <= 16 && (!solve || n <= 16 || (batch > 1024 && n <= 32)) && X.bs == nm && Xin.bs == nm && Xin.rs == X.rs && Xin.cs == X.cs && X.nb2 == 1 &&
         Xin.nb2 == 1 && Lam.nb2 == 1) {
         const bool rowmajor = (X.rs == m && X.cs == 1), colmajor = (X.rs == 1 && X.cs == n);
         if ((rowmajor || colmajor) && n > 16 && n <= 32)  // 16 lanes per matrix, two rows per lane

@@ -1336,24 +1336,32 @@ __global__ __launch_bounds__(LEAF16_THREADS) void k_gp_leaf16(View<const T> A, c
 // ---------------------------------------------------------------------------------------
 constexpr int TRSM16_MAX_CT = 3;  // column tiles of right-hand sides (they live in the inverse's tile area)
 
+// LDS of k_trsm_leaf16 (elements): diagonal tiles of Lam and of their inverses, the tiles below the diagonal, the
+// right-hand sides
 template <typename T>
-__global__ __launch_bounds__(LEAF16_THREADS) void k_trsm_leaf16(View<const T> Lam, View<const T> Xin, View<T> X,
-                                                                int64_t batch, int n, int m, T alpha, int fwd)
+__host__ __device__ constexpr int trsm16_lds_elems(int K, int MT)
+{
+    return 2 * K * Leaf16<T>::DT + (K * (K - 1) / 2 + K * MT) * Leaf16<T>::OT;
+}
+
+// W wavefronts per item: 16, or 4 for at most MAXK = 4 tile rows when there are many items.
+template <typename T, int W, int MAXK>
+__global__ __launch_bounds__(W * 64) void k_trsm_leaf16(View<const T> Lam, View<const T> Xin, View<T> X,
+                                                        int64_t batch, int n, int m, T alpha, int fwd)
 {
     using C = Leaf16<T>;
     extern __shared__ __align__(16) unsigned char leaf16_lds[];
     T *lds = reinterpret_cast<T *>(leaf16_lds);
-    const LeafLds<T> mm{lds + C::OFF_D, lds + C::OFF_XD, lds + C::OFF_A, lds + C::OFF_X};
-    constexpr int W = LEAF16_WAVES;
     constexpr int PS = C::PS, OT = C::OT;
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int64_t b = blockIdx.x;
     const int K = (n + LT - 1) / LT, MT = (m + LT - 1) / LT;
+    const LeafLds<T> mm{lds, lds + K * C::DT, lds + 2 * K * C::DT, lds + 2 * K * C::DT + K * (K - 1) / 2 * OT};
     auto btile = [&](int k, int ct) { return TileRef<T>{mm.sX + (k * MT + ct) * OT, false}; };
 
-    leaf_load_lower<T>(mm, Lam.p + b * Lam.bs, Lam.rs, Lam.cs, n, wave, lane);
+    leaf_load_lower<T, W, MAXK>(mm, Lam.p + b * Lam.bs, Lam.rs, Lam.cs, n, wave, lane);
     {  // right-hand sides, scaled by alpha, zero outside n x m
         const T *xp = Xin.p + b * Xin.bs;
         const bool colfast = (Xin.cs == 1) || (Xin.rs != 1);
@@ -1519,19 +1527,28 @@ la_status launch_trsm_leaf16(View<const T> Lam, View<const T> Xin, View<T> X, in
         return LA_OK;
     if (n > LT * LK || m > LT * TRSM16_MAX_CT || batch > 0x7fffffffll)
         return LA_ERR_UNSUPPORTED;
-    constexpr size_t lds_bytes = (size_t)Leaf16<T>::TOTAL * sizeof(T);
+    const int K = (n + LT - 1) / LT, MT = (m + LT - 1) / LT;
+    const size_t lds_bytes = (size_t)trsm16_lds_elems<T>(K, MT) * sizeof(T);
     if (dry_run())
         return LA_OK;
     static bool configured[64] = {};
     int dev = 0;
     LA_HIP(hipGetDevice(&dev));
     if (dev >= 0 && dev < 64 && !configured[dev]) {
-        LA_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&k_trsm_leaf16<T>),
-                                   hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes));
+        LA_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&k_trsm_leaf16<T, LEAF16_WAVES, LK>),
+                                   hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024));
+        LA_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&k_trsm_leaf16<T, 4, 4>),
+                                   hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024));
         configured[dev] = true;
     }
-    LA_LAUNCH((k_trsm_leaf16<T>), dim3((unsigned)batch), dim3(LEAF16_THREADS), lds_bytes, st, Lam, Xin, X,
-                       batch, n, m, alpha, fwd ? 1 : 0);
+    // many items of at most four tile rows: four wavefronts each (one per tile of right-hand sides walks the
+    // chain, which leaves at least one for the far updates), several workgroups per compute unit
+    if (K <= 4 && batch > 1024 && lds_bytes <= 40 * 1024)
+        LA_LAUNCH((k_trsm_leaf16<T, 4, 4>), dim3((unsigned)batch), dim3(4 * 64), lds_bytes, st, Lam, Xin, X, batch, n, m, alpha,
+                  fwd ? 1 : 0);
+    else
+        LA_LAUNCH((k_trsm_leaf16<T, LEAF16_WAVES, LK>), dim3((unsigned)batch), dim3(LEAF16_THREADS), lds_bytes, st, Lam, Xin, X,
+                  batch, n, m, alpha, fwd ? 1 : 0);
     return launch_check("trsm_leaf16");
 }
 

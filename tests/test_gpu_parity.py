@@ -346,7 +346,8 @@ def test_small_triangular_operators_with_many_matrices(la, orc, dtype, lower, tr
     """n <= 64 with at most 16 vectors: 4 .. 64 lanes per matrix (16 < n <= 32: 16 lanes with two rows per lane),
     operands moved as flat images; batches that
     leave the last wavefront ragged, more items than one grid dimension holds, in place and out of place.  (Solves
-    with n > 16 take this kernel above 1024 matrices only.)  Multiplies of 64 items or more with n > 32 or more than
+    with 16 < n <= 32 take this kernel above 1024 matrices only; solves with n > 32 the one-workgroup substitution
+    kernel, with four wavefronts per item above 1024 items of n <= 64.)  Multiplies of 64 items or more with n > 32 or more than
     16 vectors, n and m up to 128: one workgroup per item with the factor's lower tiles and the vectors in LDS."""
     T = tri(n * 3 + m, batch, n, lower, dtype)
     other = np.triu_indices(n, 1) if lower else np.tril_indices(n, -1)
