@@ -428,6 +428,10 @@ template <typename T>
 la_status launch_potrf_tiny(View<const T> A, View<T> L, int32_t *info, int info_off, int64_t batch, int nb,
                             hipStream_t st);
 
+// potrf of many matrices of 32 < n <= 64: four wavefronts per matrix, tiles in LDS, no inverse.  Writes the factor
+// and zeros above the diagonal; A may alias L.  info as above (offset 0).
+template <typename T>
+la_status launch_potrf_small16(View<const T> A, View<T> L, int32_t *info, int64_t batch, int n, hipStream_t st);
 // potrf of blocks of edge nb <= 128 together with the inverse of the factor, one workgroup per
 // block: writes the factor's lower triangle (zeros above the diagonal inside the 16 x 16
 // diagonal tiles; nothing else above it is written unless zero_upper, which zeroes all of L

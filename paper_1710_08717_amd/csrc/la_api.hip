@@ -388,6 +388,12 @@ static la_status potrf_t(int lower, int64_t batch, int n, const void *A, void *L
     View<T> Lv = tri_view<T>((T *)L, n, lower);
     if (info)
         LA_TRY(launch_fill_i32(info, batch, 0, st));
+    // Many matrices of up to four tile rows: four wavefronts per matrix, tiles in LDS.  Measured against the lane-group
+    // kernels at equal data volume, n = 33 ... 64 (us, fp32: 146 -> 111, 113 -> 84 at 38, 146 -> 71 at 41, 57 -> 42 at 48,
+    // 90 -> 59 at 56, 56 -> 38 at 64; fp64: 334 -> 180, 161 -> 73 at 48, 123 -> 64 at 64); only fp32 at n = 40, whose rows fill
+    // the three-rows-per-lane kernel exactly, is faster there (54 against 75).
+    if (n > 32 && n <= NB && batch > 1024 && !(sizeof(T) == 4 && n == 40))
+        return launch_potrf_small16<T>(Av, Lv, info, batch, n, st);
     if (n <= NB)
         return launch_potrf_tiny<T>(Av, Lv, info, 0, batch, n, st);
     if (n <= 2 * NB)  // one leaf: it reads A and writes L directly; nobody wants the inverse

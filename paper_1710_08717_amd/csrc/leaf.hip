@@ -404,14 +404,13 @@ __device__ __forceinline__ void leaf_load_lower(const LeafLds<T> &m, const T *p,
 // The lower tiles of A / L (inverse == false) or of the inverse back to an nb x nb block at p;
 // zero_upper also writes zeros to the tiles above the diagonal.
 // leaf_store_lower for blocks that satisfy leaf_vec_ok
-template <typename T>
+template <typename T, int W, int MAXK>
 __device__ __forceinline__ void leaf_store_lower_vec(const LeafLds<T> &m, bool inverse, T *p, int64_t rs, int K,
                                                      bool zero_upper, int wave, int lane)
 {
     using TV = TileVec<T>;
     using V = typename TV::V;
-    constexpr int W = LEAF16_WAVES;
-    constexpr int TPW = (LK * (LK + 1) / 2 + W - 1) / W;
+    constexpr int TPW = (MAXK * (MAXK + 1) / 2 + W - 1) / W;
     const int ntl = K * (K + 1) / 2;
     const int row0 = lane / TV::CPR, col = (lane % TV::CPR) * TV::VW;
 #pragma unroll
@@ -450,15 +449,14 @@ __device__ __forceinline__ void leaf_store_lower_vec(const LeafLds<T> &m, bool i
     }
 }
 
-template <typename T>
+template <typename T, int W = LEAF16_WAVES, int MAXK = LK>
 __device__ __forceinline__ void leaf_store_lower(const LeafLds<T> &m, bool inverse, T *p, int64_t rs, int64_t cs,
                                                  int nb, bool zero_upper, int wave, int lane)
 {
     if (leaf_vec_ok<T>(p, rs, cs, nb)) {
-        leaf_store_lower_vec<T>(m, inverse, p, rs, nb / LT, zero_upper, wave, lane);
+        leaf_store_lower_vec<T, W, MAXK>(m, inverse, p, rs, nb / LT, zero_upper, wave, lane);
         return;
     }
-    constexpr int W = LEAF16_WAVES;
     const int K = (nb + LT - 1) / LT;
     const int ntl = K * (K + 1) / 2;
     const bool colfast = (cs == 1) || (rs != 1);
@@ -590,6 +588,65 @@ __global__ __launch_bounds__(LEAF16_THREADS) void k_potrf_leaf16(View<const T> A
     if (info != nullptr && tid == 0 && fail != 0 && fail <= nb) {
         if (info[b] == 0)
             info[b] = info_off + fail;
+    }
+}
+
+// ---------------------------------------------------------------------------------------
+// potrf of many matrices of at most four tile rows (32 < n <= 64), four wavefronts per matrix and LDS for
+// the tiles in use only, so that several workgroups share a compute unit.  Nobody wants the inverse of
+// the factor here: per tile column one wavefront factors the diagonal tile (and inverts it in registers,
+// for the panel), then the panel tiles L_ik = A_ik Li_kk^T and the trailing updates are dealt over the four.
+// ---------------------------------------------------------------------------------------
+constexpr int SMALL16_WAVES = 4, SMALL16_MAXK = 4;
+template <typename T>
+__host__ __device__ constexpr int small16_lds_elems(int K)
+{
+    return 2 * K * Leaf16<T>::DT + K * (K - 1) / 2 * Leaf16<T>::OT;
+}
+
+template <typename T>
+__global__ __launch_bounds__(SMALL16_WAVES * 64) void k_potrf_small16(View<const T> A, View<T> L, int32_t *info,
+                                                                      int64_t batch, int n)
+{
+    using C = Leaf16<T>;
+    extern __shared__ __align__(16) unsigned char leaf16_lds[];
+    T *lds = reinterpret_cast<T *>(leaf16_lds);
+    constexpr int W = SMALL16_WAVES;
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int64_t b = blockIdx.x;
+    const int K = (n + LT - 1) / LT;
+    // diagonal tiles of A / L, diagonal tiles of the inverse, tiles below the diagonal (no other tiles of the inverse)
+    const LeafLds<T> m{lds, lds + K * C::DT, lds + 2 * K * C::DT, lds + 2 * K * C::DT};
+
+    leaf_load_lower<T, W, SMALL16_MAXK>(m, A.p + b * A.bs, A.rs, A.cs, n, wave, lane);
+    __syncthreads();
+    int fail = 0;
+    for (int k = 0; k < K; ++k) {
+        if (wave == 0) {
+            const int f = leaf_diag<T>(m, k, lane);
+            if (fail == 0 && f != 0)
+                fail = k * LT + f;
+        }
+        __syncthreads();
+        const int rows = K - 1 - k;
+        if (rows == 0)
+            break;
+        for (int i = k + 1 + wave; i < K; i += W)
+            leaf_panel<T>(m, i, k, lane);
+        __syncthreads();
+        for (int t = wave; t < rows * (rows + 1) / 2; t += W) {
+            int ii, jj;
+            tri_decode(t, ii, jj);
+            leaf_update_a<T>(m, k + 1 + ii, k + 1 + jj, k, lane);
+        }
+        __syncthreads();
+    }
+    leaf_store_lower<T, W, SMALL16_MAXK>(m, false, L.p + b * L.bs, L.rs, L.cs, n, true, wave, lane);
+    if (info != nullptr && tid == 0 && fail != 0 && fail <= n) {
+        if (info[b] == 0)
+            info[b] = fail;
     }
 }
 
@@ -1491,6 +1548,23 @@ template la_status launch_potrf_leaf16<float>(View<const float>, View<float>, Vi
                                               bool, hipStream_t);
 template la_status launch_potrf_leaf16<double>(View<const double>, View<double>, View<double>, int32_t *, int, int64_t,
                                                int, bool, hipStream_t);
+
+template <typename T>
+la_status launch_potrf_small16(View<const T> A, View<T> L, int32_t *info, int64_t batch, int n, hipStream_t st)
+{
+    if (batch <= 0 || n <= 0)
+        return LA_OK;
+    if (n > LT * SMALL16_MAXK || batch > 0x7fffffffll)
+        return LA_ERR_UNSUPPORTED;
+    const int K = (n + LT - 1) / LT;
+    if (dry_run())
+        return LA_OK;
+    LA_LAUNCH((k_potrf_small16<T>), dim3((unsigned)batch), dim3(SMALL16_WAVES * 64), (size_t)small16_lds_elems<T>(K) * sizeof(T),
+              st, A, L, info, batch, n);
+    return launch_check("potrf_small16");
+}
+template la_status launch_potrf_small16<float>(View<const float>, View<float>, int32_t *, int64_t, int, hipStream_t);
+template la_status launch_potrf_small16<double>(View<const double>, View<double>, int32_t *, int64_t, int, hipStream_t);
 
 template <typename T>
 la_status launch_tri_inverse128(View<const T> Lam, View<T> Inv, int64_t batch, int n, hipStream_t st)

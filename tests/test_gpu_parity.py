@@ -142,6 +142,30 @@ def test_potrf_info_first_bad_pivot(la, orc, dtype, n, bad):
     assert relerr(L[ok], orc.potrf(A[ok])) <= TOL[dtype]
 
 
+@pytest.mark.parametrize("dtype", ["f64", "f32"])
+@pytest.mark.parametrize("lower", [True, False])
+@pytest.mark.parametrize("n,bad", [(33, 32), (40, 17), (48, 0), (57, 40), (64, 63)])
+def test_potrf_many_matrices_of_up_to_four_tile_rows(la, orc, dtype, lower, n, bad):
+    """Above 1024 matrices, 32 < n <= 64 is factored with four wavefronts per matrix and the tiles in LDS; one matrix
+    of the batch is not positive definite; the unread triangle holds NaN; in place."""
+    import torch
+
+    batch = 1030
+    A = spd(n + 1, batch, n, dtype)
+    A[7, bad, bad] = -1.0
+    ref, ref_info = orc.potrf(A, lower=lower, return_info=True)
+    other = np.triu_indices(n, 1) if lower else np.tril_indices(n, -1)
+    Aj = A.copy()
+    Aj[:, other[0], other[1]] = np.nan
+    info = torch.zeros(batch, dtype=torch.int32, device="cuda")
+    a = dev(Aj)
+    L = host(la.potrf(a, lower=lower, info=info, out=a))
+    assert np.array_equal(host(info), ref_info) and ref_info[7] == bad + 1 and ref_info.sum() == bad + 1
+    ok = np.arange(batch) != 7
+    assert np.all(L[:, other[0], other[1]][ok] == 0.0)
+    assert relerr(L[ok], ref[ok]) <= TOL[dtype]
+
+
 def test_potrf_ragged_batch_and_large_batch(la, orc):
     # batches that do not fill the last wavefront, and more items than one grid dimension holds
     for n, batch, dtype in [(16, 5, "f32"), (16, 70001, "f32"), (9, 3, "f64"), (32, 3, "f64"), (20, 4097, "f32"),
