@@ -1777,7 +1777,9 @@ static size_t symm_leaf_lds(int n, int k, int nw)
 template <typename T>
 bool symm_leaf_takes(int64_t batch, int n, int k)
 {
-    return n > 16 && n <= 128 && k >= 1 && k <= 128 && batch >= 64 && symm_leaf_lds<T>(n, k, LEAF16_WAVES) <= 64 * 1024;
+    const int Kn = (n + LT - 1) / LT, Kk = (k + LT - 1) / LT;
+    const int nw = (Kn * Kk <= 16 && batch > 1024) ? 4 : LEAF16_WAVES;  // as launch_symm_leaf chooses
+    return n > 16 && n <= 128 && k >= 1 && k <= 128 && batch >= 64 && symm_leaf_lds<T>(n, k, nw) <= 64 * 1024;
 }
 template bool symm_leaf_takes<float>(int64_t, int, int);
 template bool symm_leaf_takes<double>(int64_t, int, int);
